@@ -1,0 +1,162 @@
+/*
+ * prism.h - C-ABI of the MI355X (gfx950) PRISM library.
+ *
+ * PRISM accelerates Newton-Schulz-like matrix iterations by fitting, at every
+ * iteration, the highest coefficient alpha_k of the update polynomial
+ * g_d(R_k; alpha) to the spectrum of the current residual R_k through a
+ * sketched least-squares problem (paper Sections 3-4, eq. (2)-(4)).
+ * Three iterations of Table 1 are provided:
+ *
+ *   prism_polar      polar factor U V^T          R_k = I - X_k^T X_k
+ *   prism_sqrt       A^{1/2} and A^{-1/2}        R_k = I - Y_k X_k   (Theorem 3)
+ *   prism_inv_root   A^{-1/p}                    R_k = I - M_k       (App. A.3)
+ *
+ * Conventions common to all entry points
+ *   - Every matrix pointer is a DEVICE pointer to row-major, contiguous,
+ *     batch-strided data: x[batch][m][n].  The caller owns all of it.
+ *   - `dt` is the storage type of the caller's matrices.  PRISM_F32 computes
+ *     with fp32 matrix instructions (the inverse-root recurrence for M_k in
+ *     fp64); PRISM_BF16 computes with bf16 matrix instructions accumulating in
+ *     fp32 and is available for prism_polar only.
+ *   - `degree` is the degree of the update in X: 3 (d = 1) or 5 (d = 2).
+ *   - `sketch_dim` = p_s, the number of rows of the Gaussian sketch S_k
+ *     (1..64).  0 disables the fit: alpha_k stays at the Taylor value, which is
+ *     the classical iteration.
+ *   - `seed` selects the sketch stream; S_k depends only on (seed, k, function)
+ *     and is shared by all matrices of the call.
+ *   - `tol` > 0: iterate until ||R_k||_F / sqrt(n_R) <= tol (n_R = order of
+ *     R_k), at most `max_iters` updates.  `tol` <= 0: exactly `max_iters`
+ *     updates.  max_iters <= PRISM_MAX_ITERS.
+ *   - `stream` is a hipStream_t (NULL = the default stream).  Calls only
+ *     enqueue work on it and return; nothing synchronises with the host and
+ *     there is no host round trip per iteration.
+ *   - The return value reports errors the host can detect (prism_status).
+ *     Numerical outcomes are reported per matrix in prism_info.status.
+ *   - Unless a workspace is passed through prism_options, the library keeps
+ *     one grow-only device workspace per (device, stream); calls that share
+ *     it must be ordered on that stream.
+ *   - A matrix whose info.status is PRISM_INFO_NONFINITE or PRISM_INFO_ZERO is
+ *     left untouched.
+ */
+#ifndef PRISM_H
+#define PRISM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define PRISM_MAX_ITERS 64
+#define PRISM_MAX_SKETCH 64
+#define PRISM_MAX_ROOT 8
+
+typedef enum { PRISM_F32 = 0, PRISM_BF16 = 1 } prism_dtype;
+
+typedef enum {
+  PRISM_OK = 0,
+  PRISM_EINVAL = 1,       /* null pointer, bad size, degree, root order, budget ... */
+  PRISM_EUNSUPPORTED = 2, /* combination not implemented (e.g. bf16 square root) */
+  PRISM_ENOMEM = 3,       /* workspace allocation failed or passed workspace too small */
+  PRISM_EHIP = 4          /* a HIP runtime call failed */
+} prism_status;
+
+/* function ids; also the function tag of the sketch counter */
+typedef enum { PRISM_FN_POLAR = 1, PRISM_FN_SQRT = 2, PRISM_FN_INV_ROOT = 3 } prism_fn;
+
+enum {
+  PRISM_INFO_CONVERGED = 0, /* residual <= tol after `iters` updates */
+  PRISM_INFO_BUDGET = 1,    /* max_iters updates done (the normal outcome when tol <= 0) */
+  PRISM_INFO_NONFINITE = 2, /* input holds inf or nan */
+  PRISM_INFO_ZERO = 3,      /* input is all zero */
+  PRISM_INFO_DIVERGED = 4   /* residual non-finite, or rising twice in a row above its start */
+};
+
+/* Per-matrix report, written on the device.  residual[k] = ||R_k||_F / sqrt(n_R)
+ * for k = 0..iters (residual[max_iters] is not evaluated when tol <= 0 and is
+ * set to -1); alpha[k] is the coefficient used by update k. */
+typedef struct {
+  int32_t iters;
+  int32_t status;
+  float residual[PRISM_MAX_ITERS + 1];
+  float alpha[PRISM_MAX_ITERS];
+} prism_info;
+
+enum {
+  /* bf16 polar only: keep the iterate X_k in plain bf16 between iterations (one
+   * matrix-core pass per update).  By default X_k is carried as a pair of bf16
+   * matrices (high + low part, two passes per update), which is what an
+   * ill-conditioned input needs to reach its own polar factor. */
+  PRISM_FLAG_BF16_PLAIN_ITERATE = 1u
+};
+
+typedef struct {
+  uint32_t flags;         /* PRISM_FLAG_* */
+  int32_t warm_iters;     /* the first warm_iters updates use alpha = u without a fit (App. C) */
+  void* workspace;        /* device memory, 256-byte aligned, or NULL for the cached one */
+  size_t workspace_bytes; /* size of `workspace` */
+  prism_info* info;       /* device array of `batch` entries, or NULL */
+} prism_options;
+
+/* Device bytes a call with these arguments needs (host-only computation). */
+int prism_workspace_bytes(int fn, int batch, int m, int n, prism_dtype dt, int degree,
+                          int sketch_dim, int root_p, size_t* out_bytes);
+
+/* Polar factor (Table 1, "Newton-Schulz, U V^T"; App. A.1).  x[batch][m][n] is
+ * replaced in place by U V^T.  m < n is handled on the transpose. */
+int prism_polar(void* x, int batch, int m, int n, prism_dtype dt, int degree, int max_iters,
+                int sketch_dim, uint64_t seed, double tol, void* stream);
+int prism_polar_ex(void* x, int batch, int m, int n, prism_dtype dt, int degree, int max_iters,
+                   int sketch_dim, uint64_t seed, double tol, void* stream,
+                   const prism_options* opt);
+
+/* Coupled square root (Table 1, "A^{1/2}, A^{-1/2}"; Theorem 3).  a[batch][n][n]
+ * symmetric positive definite is replaced by A^{1/2}; inv_out[batch][n][n]
+ * receives A^{-1/2}.  m must equal n. */
+int prism_sqrt(void* a, void* inv_out, int batch, int m, int n, prism_dtype dt, int degree,
+               int max_iters, int sketch_dim, uint64_t seed, double tol, void* stream);
+int prism_sqrt_ex(void* a, void* inv_out, int batch, int m, int n, prism_dtype dt, int degree,
+                  int max_iters, int sketch_dim, uint64_t seed, double tol, void* stream,
+                  const prism_options* opt);
+
+/* Coupled inverse Newton (Table 1, "Coupled Inverse Newton"; App. A.3).
+ * a[batch][n][n] symmetric positive definite is replaced by A^{-1/root_p},
+ * 1 <= root_p <= PRISM_MAX_ROOT.  The update is linear in R_k: degree must be 3. */
+int prism_inv_root(void* a, int root_p, int batch, int m, int n, prism_dtype dt, int degree,
+                   int max_iters, int sketch_dim, uint64_t seed, double tol, void* stream);
+int prism_inv_root_ex(void* a, int root_p, int batch, int m, int n, prism_dtype dt, int degree,
+                      int max_iters, int sketch_dim, uint64_t seed, double tol, void* stream,
+                      const prism_options* opt);
+
+/* ---- single steps of the path, exposed for unit tests and profiling ---- */
+
+/* S_k^T (Section 4.2: Gaussian sketch): out[n][sketch_dim] fp32 on the device,
+ * unit-variance entries; entry (j, r) depends only on (seed, k, fn, r, j). */
+int prism_sketch(float* out, int n, int sketch_dim, uint64_t seed, int k, int fn, void* stream);
+
+/* The two Box-Muller factors for `count` consecutive 24-bit arguments starting
+ * at `first`: radius[i] = sqrt(-2 ln((first+i+1) 2^-24)), (cosv, sinv)[i] =
+ * (cos, sin)(2 pi (first+i) 2^-24).  Device arrays of doubles. */
+int prism_gauss_parts(uint32_t first, uint32_t count, double* radius, double* cosv, double* sinv,
+                      void* stream);
+
+/* C[batch][M][N] = A * B on the matrix cores, no epilogue.  Device pointers.
+ *   prism_gemm_f32 : fp32 in/out; a_km != 0 means A is stored [K][M].  B is [K][N].
+ *   prism_gemm_f64a: A fp32 (promoted), B and C fp64, A stored [M][K].
+ *   prism_gemm_bf16_nt: A [M][K], B [N][K] bf16 bit patterns, C fp32 = A B^T.
+ * M, N must be multiples of 128 (bf16: `tile`, 128 or 256) and K of 64. */
+int prism_gemm_f32(const float* A, const float* B, float* C, int batch, int M, int N, int K,
+                   int a_km, void* stream);
+int prism_gemm_f64a(const float* A, const double* B, double* C, int batch, int M, int N, int K,
+                    void* stream);
+int prism_gemm_bf16_nt(const uint16_t* A, const uint16_t* B, float* C, int batch, int M, int N,
+                       int K, int tile, void* stream);
+
+/* Last HIP error string seen by the library on this thread ("" if none). */
+const char* prism_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PRISM_H */

@@ -1,0 +1,141 @@
+// Internal declarations shared by the translation units of libprism (not part of the C-ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "prism.h"
+
+namespace prism {
+
+// Per-matrix control block, device resident.  Written by the prepare and solve
+// kernels, read by every kernel of the iteration (done != 0 => the matrix is skipped).
+struct Ctrl {
+  int done;      // 0 while iterating
+  int iters;     // updates performed
+  int status;    // PRISM_INFO_*
+  int pad0;
+  float alpha;   // coefficient of the update being applied
+  float res0;    // residual at k = 0
+  float res1;    // residual at k - 1
+  float res2;    // residual at k - 2
+  double norm;   // ||A||_F of the input
+  double scale;  // factor applied to the input when it is copied in
+};
+
+// ---- gemm_f32.hip : fp32 / fp64 matrix-core GEMMs with fused epilogues ----
+enum EpiKind {
+  EPI_STORE = 0,     // C = acc
+  EPI_RESIDUAL = 1,  // R = I - acc (masked to n x n), rho partial
+  EPI_POLYQ = 2,     // Q = c1 * Rin + alpha * acc
+  EPI_AXPY = 3,      // C = Cin + coef * acc          (coef = 1 or alpha)
+  EPI_MNEXT = 4      // fp64: M' = acc, R32' = I - acc (masked), rho partial
+};
+
+struct GemmDesc {
+  const void* A; long long strideA; int lda;
+  const void* B; long long strideB; int ldb;
+  int M, N, K;          // padded sizes: multiples of the tile sizes
+  int a_km;             // A stored [K][M] instead of [M][K]
+  int batch;
+  // epilogue operands
+  int epi;
+  int n_true;           // unpadded order for masks
+  void* C; long long strideC; int ldc;           // main output (float, or double for EPI_MNEXT / f64 store)
+  const void* Cin; long long strideCin; int ldcin;  // extra input (R for POLYQ, X for AXPY)
+  float* R32out; long long strideR; int ldr;     // EPI_MNEXT: fp32 residual out
+  float c1;             // POLYQ: coefficient of Rin
+  int coef_is_alpha;    // AXPY: multiply acc by ctrl.alpha
+  float* rho_part;      // [batch][tiles] partial sums of R^2 (RESIDUAL / MNEXT)
+  const Ctrl* ctrl;     // may be null (test entry points)
+};
+
+// tile: 64 or 128 (square tiles), or skinny N (16/32/64) with tile_m 64/128 for the sketch chain
+int launch_gemm_f32(const GemmDesc& g, int tile_m, int tile_n, hipStream_t s);
+int launch_gemm_f64a(const GemmDesc& g, int tile_m, int tile_n, hipStream_t s);  // A float, B/C double
+
+// ---- gemm_bf16.hip : bf16 matrix-core NT GEMMs (both operands K-contiguous) ----
+enum Bf16Epi {
+  BEPI_STORE = 0,   // C(fp32) = acc
+  BEPI_GRAM = 1,    // R = I - acc: R32 (fp32) and Rb (bf16), rho partial
+  BEPI_POLYQ = 2,   // Q(bf16) = c1 * R32 + alpha * acc
+  BEPI_APPLY = 3    // X' = Xhi + Xlo + acc -> Xa_hi', Xa_lo' ([L][S]) and Xg_hi' ([S][L])
+};
+
+struct Bf16Desc {
+  const uint16_t* A; long long strideA; int lda;    // [M][K]
+  const uint16_t* A2;                                // optional second A (low part), same layout
+  const uint16_t* B; long long strideB; int ldb;    // [N][K]
+  int M, N, K, batch;
+  int epi;
+  int n_true;                                        // GRAM mask
+  float* C32; long long strideC32; int ldc32;        // STORE / GRAM fp32 out; POLYQ fp32 in
+  uint16_t* Cb; long long strideCb; int ldcb;        // GRAM: Rb out; POLYQ: Q out; APPLY: Xa_hi' out
+  uint16_t* Cb2;                                     // APPLY: Xa_lo' out (null in plain mode)
+  uint16_t* Ct; long long strideCt; int ldct;        // APPLY: Xg_hi' out, transposed [N][M]
+  const uint16_t* Xhi; const uint16_t* Xlo;          // APPLY: current iterate (same layout as Cb)
+  float c1;
+  int coef_is_alpha;                                 // APPLY: multiply acc by ctrl.alpha (d = 1)
+  float* rho_part;
+  const Ctrl* ctrl;
+};
+int launch_gemm_bf16(const Bf16Desc& g, int tile, hipStream_t s);
+
+// ---- sketch.hip ----
+void launch_sketch(float* v0, int rows_total, int n, int ld, int p_s, uint64_t seed, int k, int fn,
+                   hipStream_t s);
+void launch_gauss_parts(uint32_t first, uint32_t count, double* r, double* c, double* sn,
+                        hipStream_t s);
+
+// ---- fit.hip ----
+struct SolveArgs {
+  int fn;            // PRISM_FN_*
+  int k;             // iteration index
+  int d;             // NS order (1, 2); unused for inverse root
+  int p;             // root order (inverse root)
+  int n;             // unpadded order of R
+  int rows;          // padded rows of V
+  int ld;            // leading dimension (padded sketch columns) of V
+  const float* V;    // V_1 .. V_nv: [nv][batch][rows][ld]; V_j at V + (j-1)*vstride
+  long long vstride; // elements between V_j and V_{j+1}
+  long long bstride; // elements between matrices inside one V_j
+  const float* rho_part; int nparts;
+  Ctrl* ctrl;
+  prism_info* info;
+  double tol;
+  int max_iters;
+  int mode;          // 0 fit, 1 alpha = l (no sketch), 2 alpha = u (warm start)
+  int last;          // this is the residual-only evaluation at k = max_iters
+};
+void launch_solve(const SolveArgs& a, int batch, hipStream_t s);
+
+// ---- misc.hip ----
+struct PrepArgs {
+  int fn; int dt; int batch; int m, n;     // caller's shape
+  int S, L, Sp, Lp;                         // short / long side and padded sizes
+  int transpose;                            // polar with m < n: internal iterate is the transpose
+  int root_p;
+  const void* src;
+  double* sumsq_part; int nsum;             // [batch][nsum]
+  Ctrl* ctrl; prism_info* info;
+  // outputs (which are used depends on fn/dt)
+  float* X32; float* Y32; double* M64; float* R32;   // fp32 paths
+  uint16_t* Xa_hi; uint16_t* Xa_lo; uint16_t* Xg;    // bf16 polar
+  float* rho_part; int tile;                // inverse root: residual of M_0
+};
+void launch_sumsq(const PrepArgs& a, hipStream_t s);
+void launch_prepare(const PrepArgs& a, hipStream_t s);
+
+struct FinalArgs {
+  int fn; int dt; int batch; int m, n; int S, L, Sp, Lp; int transpose;
+  void* dst; void* dst2;                    // caller's arrays (dst2 = inverse square root)
+  const Ctrl* ctrl;
+  const float* X32[2]; const float* Y32[2];
+  const uint16_t* Xa_hi[2]; const uint16_t* Xa_lo[2];
+};
+void launch_finalize(const FinalArgs& a, hipStream_t s);
+// T = I + alpha R (identity masked to n), one matrix per blockIdx.y; skipped when done
+void launch_make_t(float* T, const float* R, const Ctrl* ctrl, int batch, int np, int n, hipStream_t s);
+
+void set_last_error(const char* msg);
+
+}  // namespace prism

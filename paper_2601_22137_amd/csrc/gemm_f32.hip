@@ -1,0 +1,245 @@
+// fp32 / fp64 GEMMs on the CDNA4 matrix cores (v_mfma_f32_16x16x4_f32, v_mfma_f64_16x16x4_f64)
+// with the epilogues of the PRISM iterations fused in (Table 1 of the paper: residual
+// R = I - G, polynomial Q = R/2 + alpha R^2, update X + X Q, inverse-Newton factors).
+//
+// One workgroup = 256 threads = 4 wavefronts computes one TM x TN tile of C for one matrix of
+// the batch.  K is consumed in slabs of BK = 16 staged through LDS in K-major order
+// (As[k][m], Bs[k][n]) and double buffered: the global loads of slab t+1 are in flight while
+// the MFMAs of slab t run.  All operand sizes are padded to tile multiples by the caller, so
+// the main loop has no bounds checks; masks are applied in the epilogue only.
+#include "common.h"
+
+namespace prism {
+namespace {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef double f64x4 __attribute__((ext_vector_type(4)));
+typedef double f64x2 __attribute__((ext_vector_type(2)));
+
+constexpr int BK = 16;
+constexpr int NT = 256;
+
+__host__ __device__ constexpr int lds_ld(int t) { return ((t + 31) / 32) * 32 + 16; }
+
+template <typename T> struct Vec16;
+template <> struct Vec16<float> { typedef f32x4 type; static constexpr int N = 4; };
+template <> struct Vec16<double> { typedef f64x2 type; static constexpr int N = 2; };
+
+__device__ inline f32x4 mfma(float a, float b, f32x4 c) {
+  return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
+}
+__device__ inline f64x4 mfma(double a, double b, f64x4 c) {
+  return __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, c, 0, 0, 0);
+}
+template <typename T> struct Acc;
+template <> struct Acc<float> { typedef f32x4 type; };
+template <> struct Acc<double> { typedef f64x4 type; };
+
+// Row of the 16x16 result held in register r of lane l (column is l % 16).
+template <typename TC> __device__ inline int acc_row(int lane, int r);
+template <> __device__ inline int acc_row<float>(int lane, int r) { return 4 * (lane >> 4) + r; }
+template <> __device__ inline int acc_row<double>(int lane, int r) { return 4 * r + (lane >> 4); }
+
+template <typename TC>
+__device__ inline TC epilogue(const GemmDesc& g, int b, int i, int j, TC acc, float alpha) {
+  const long long oc = (long long)b * g.strideC + (long long)i * g.ldc + j;
+  switch (g.epi) {
+    case EPI_STORE:
+      ((TC*)g.C)[oc] = acc;
+      return 0;
+    case EPI_RESIDUAL: {
+      TC r = (i < g.n_true && j < g.n_true) ? ((i == j ? (TC)1 : (TC)0) - acc) : (TC)0;
+      ((TC*)g.C)[oc] = r;
+      return r * r;
+    }
+    case EPI_POLYQ: {
+      const float rin = ((const float*)g.Cin)[(long long)b * g.strideCin + (long long)i * g.ldcin + j];
+      ((float*)g.C)[oc] = g.c1 * rin + alpha * (float)acc;
+      return 0;
+    }
+    case EPI_AXPY: {
+      const float cin = ((const float*)g.Cin)[(long long)b * g.strideCin + (long long)i * g.ldcin + j];
+      const float coef = g.coef_is_alpha ? alpha : 1.0f;
+      ((float*)g.C)[oc] = cin + coef * (float)acc;
+      return 0;
+    }
+    case EPI_MNEXT: {
+      const bool in = (i < g.n_true && j < g.n_true);
+      const TC mval = in ? acc : (TC)0;
+      ((TC*)g.C)[oc] = mval;
+      const TC r = in ? ((i == j ? (TC)1 : (TC)0) - acc) : (TC)0;
+      g.R32out[(long long)b * g.strideR + (long long)i * g.ldr + j] = (float)r;
+      return r * r;
+    }
+  }
+  return 0;
+}
+
+template <typename TC, typename TB, int TM, int TN, int WGM, int WGN, bool A_KM>
+__global__ __launch_bounds__(NT) void gemm_kernel(GemmDesc g) {
+  constexpr int LDA = lds_ld(TM), LDB = lds_ld(TN);
+  constexpr int WTM = TM / WGM, WTN = TN / WGN;  // wave tile
+  constexpr int BM = WTM / 16, BN = WTN / 16;    // 16x16 blocks per wave
+  static_assert(WGM * WGN == 4 && BM >= 1 && BN >= 1, "bad tiling");
+  __shared__ TC As[2][BK][LDA];
+  __shared__ TC Bs[2][BK][LDB];
+  __shared__ TC red[4];
+
+  const int tiles_m = g.M / TM, tiles_n = g.N / TN;
+  const int per_mat = tiles_m * tiles_n;
+  const int total = per_mat * g.batch;
+  int wg = blockIdx.x;
+  if ((total & 7) == 0) wg = (wg & 7) * (total >> 3) + (wg >> 3);  // one XCD = one contiguous tile range
+  const int b = wg / per_mat;
+  const int rem = wg - b * per_mat;
+  const int tm = rem / tiles_n, tn = rem - tm * tiles_n;
+  if (g.ctrl && g.ctrl[b].done) return;
+  const float alpha = g.ctrl ? g.ctrl[b].alpha : 1.0f;
+
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  const int wm0 = (wave / WGN) * WTM, wn0 = (wave % WGN) * WTN;
+  const int m0 = tm * TM, n0 = tn * TN;
+  const float* Ab = (const float*)g.A + (long long)b * g.strideA;
+  const TB* Bb = (const TB*)g.B + (long long)b * g.strideB;
+
+  // staging registers
+  constexpr int A_LOADS = TM * BK / 4;                       // float4 loads per slab
+  constexpr int A_IT = (A_LOADS + NT - 1) / NT;
+  constexpr int BV = Vec16<TB>::N;
+  constexpr int B_LOADS = TN * BK / BV;
+  constexpr int B_IT = (B_LOADS + NT - 1) / NT;
+  f32x4 ra[A_IT];
+  typename Vec16<TB>::type rb[B_IT];
+
+  auto load_slab = [&](int k0) {
+#pragma unroll
+    for (int it = 0; it < A_IT; ++it) {
+      const int idx = t + it * NT;
+      if (A_LOADS % NT == 0 || idx < A_LOADS) {
+        if (A_KM) {
+          const int kr = idx / (TM / 4), c4 = idx % (TM / 4);
+          ra[it] = *(const f32x4*)(Ab + (long long)(k0 + kr) * g.lda + m0 + c4 * 4);
+        } else {
+          const int row = idx / (BK / 4), c4 = idx % (BK / 4);
+          ra[it] = *(const f32x4*)(Ab + (long long)(m0 + row) * g.lda + k0 + c4 * 4);
+        }
+      }
+    }
+#pragma unroll
+    for (int it = 0; it < B_IT; ++it) {
+      const int idx = t + it * NT;
+      if (B_LOADS % NT == 0 || idx < B_LOADS) {
+        const int kr = idx / (TN / BV), c = idx % (TN / BV);
+        rb[it] = *(const typename Vec16<TB>::type*)(Bb + (long long)(k0 + kr) * g.ldb + n0 + c * BV);
+      }
+    }
+  };
+  auto store_slab = [&](int buf) {
+#pragma unroll
+    for (int it = 0; it < A_IT; ++it) {
+      const int idx = t + it * NT;
+      if (A_LOADS % NT == 0 || idx < A_LOADS) {
+        if (A_KM) {
+          const int kr = idx / (TM / 4), c4 = idx % (TM / 4);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) As[buf][kr][c4 * 4 + e] = (TC)ra[it][e];
+        } else {
+          const int row = idx / (BK / 4), c4 = idx % (BK / 4);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) As[buf][c4 * 4 + e][row] = (TC)ra[it][e];
+        }
+      }
+    }
+#pragma unroll
+    for (int it = 0; it < B_IT; ++it) {
+      const int idx = t + it * NT;
+      if (B_LOADS % NT == 0 || idx < B_LOADS) {
+        const int kr = idx / (TN / BV), c = idx % (TN / BV);
+#pragma unroll
+        for (int e = 0; e < BV; ++e) Bs[buf][kr][c * BV + e] = (TC)rb[it][e];
+      }
+    }
+  };
+
+  typename Acc<TC>::type acc[BM][BN];
+#pragma unroll
+  for (int i = 0; i < BM; ++i)
+#pragma unroll
+    for (int j = 0; j < BN; ++j) acc[i][j] = (typename Acc<TC>::type){0, 0, 0, 0};
+
+  const int KT = g.K / BK;
+  load_slab(0);
+  store_slab(0);
+  __syncthreads();
+  const int lr = lane & 15, lk = lane >> 4;
+  for (int kt = 0; kt < KT; ++kt) {
+    const int cur = kt & 1;
+    if (kt + 1 < KT) load_slab((kt + 1) * BK);
+#pragma unroll
+    for (int kk = 0; kk < BK / 4; ++kk) {
+      TC a[BM], bb[BN];
+#pragma unroll
+      for (int i = 0; i < BM; ++i) a[i] = As[cur][kk * 4 + lk][wm0 + i * 16 + lr];
+#pragma unroll
+      for (int j = 0; j < BN; ++j) bb[j] = Bs[cur][kk * 4 + lk][wn0 + j * 16 + lr];
+#pragma unroll
+      for (int i = 0; i < BM; ++i)
+#pragma unroll
+        for (int j = 0; j < BN; ++j) acc[i][j] = mfma(a[i], bb[j], acc[i][j]);
+    }
+    if (kt + 1 < KT) store_slab(cur ^ 1);
+    __syncthreads();
+  }
+
+  TC part = 0;
+#pragma unroll
+  for (int i = 0; i < BM; ++i)
+#pragma unroll
+    for (int j = 0; j < BN; ++j)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int gi = m0 + wm0 + i * 16 + acc_row<TC>(lane, r);
+        const int gj = n0 + wn0 + j * 16 + lr;
+        part += epilogue<TC>(g, b, gi, gj, acc[i][j][r], alpha);
+      }
+  if (g.epi == EPI_RESIDUAL || g.epi == EPI_MNEXT) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) part += __shfl_down(part, off, 64);
+    if (lane == 0) red[wave] = part;
+    __syncthreads();
+    if (t == 0) g.rho_part[(long long)b * per_mat + rem] = (float)(red[0] + red[1] + red[2] + red[3]);
+  }
+}
+
+template <typename TC, typename TB, int TM, int TN, int WGM, int WGN>
+int launch_cfg(const GemmDesc& g, hipStream_t s) {
+  if (g.M % TM || g.N % TN || g.K % BK || g.lda % 4 || g.ldb % 4) return PRISM_EINVAL;
+  const int total = (g.M / TM) * (g.N / TN) * g.batch;
+  if (total <= 0) return PRISM_EINVAL;
+  if (g.a_km)
+    hipLaunchKernelGGL((gemm_kernel<TC, TB, TM, TN, WGM, WGN, true>), dim3(total), dim3(NT), 0, s, g);
+  else
+    hipLaunchKernelGGL((gemm_kernel<TC, TB, TM, TN, WGM, WGN, false>), dim3(total), dim3(NT), 0, s, g);
+  return hipGetLastError() == hipSuccess ? PRISM_OK : PRISM_EHIP;
+}
+
+}  // namespace
+
+int launch_gemm_f32(const GemmDesc& g, int tile_m, int tile_n, hipStream_t s) {
+  if (tile_m == 128 && tile_n == 128) return launch_cfg<float, float, 128, 128, 2, 2>(g, s);
+  if (tile_m == 64 && tile_n == 64) return launch_cfg<float, float, 64, 64, 2, 2>(g, s);
+  if (tile_m == 128 && tile_n == 64) return launch_cfg<float, float, 128, 64, 4, 1>(g, s);
+  if (tile_m == 128 && tile_n == 32) return launch_cfg<float, float, 128, 32, 4, 1>(g, s);
+  if (tile_m == 128 && tile_n == 16) return launch_cfg<float, float, 128, 16, 4, 1>(g, s);
+  if (tile_m == 64 && tile_n == 32) return launch_cfg<float, float, 64, 32, 4, 1>(g, s);
+  if (tile_m == 64 && tile_n == 16) return launch_cfg<float, float, 64, 16, 4, 1>(g, s);
+  return PRISM_EINVAL;
+}
+
+int launch_gemm_f64a(const GemmDesc& g, int tile_m, int tile_n, hipStream_t s) {
+  if (g.a_km) return PRISM_EINVAL;
+  if (tile_m == 64 && tile_n == 64) return launch_cfg<double, double, 64, 64, 2, 2>(g, s);
+  return PRISM_EINVAL;
+}
+
+}  // namespace prism

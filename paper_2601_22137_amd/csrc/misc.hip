@@ -1,0 +1,197 @@
+// Entry and exit of the PRISM iterations: Frobenius norm of the input, initial iterates
+// (paper Section 3: X_0 = A / ||A||_F; App. A.3: X_0 = I / c, M_0 = A / c^p with
+// c = (2 ||A||_F / (p+1))^(1/p)), copy into the padded internal layouts, and the final
+// un-scaling / copy-out (A^{1/2} = sqrt(s) X, A^{-1/2} = Y / sqrt(s)).
+#include "common.h"
+
+namespace prism {
+namespace {
+
+constexpr int NT = 256;
+
+__device__ inline unsigned short f2bf(float x) {
+  unsigned int u = __float_as_uint(x);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return (unsigned short)(u >> 16);
+}
+__device__ inline float bf2f(unsigned short h) { return __uint_as_float(((unsigned int)h) << 16); }
+
+__device__ inline double load_src(const void* src, int dt, long long idx) {
+  return dt == PRISM_BF16 ? (double)bf2f(((const unsigned short*)src)[idx]) : (double)((const float*)src)[idx];
+}
+
+// sumsq_part[b][blockIdx.x] = sum of squares of a strided share of matrix b (fp64).
+// An inf or nan entry makes its partial non-finite, which the prepare step reports.
+__global__ __launch_bounds__(NT) void sumsq_kernel(PrepArgs a) {
+  const int b = blockIdx.y;
+  const long long total = (long long)a.m * a.n;
+  const long long base = (long long)b * total;
+  double acc = 0.0;
+  for (long long i = (long long)blockIdx.x * NT + threadIdx.x; i < total; i += (long long)gridDim.x * NT) {
+    const double v = load_src(a.src, a.dt, base + i);
+    acc += v * v;
+  }
+  __shared__ double red[4];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) acc += __shfl_down(acc, off, 64);
+  if (lane == 0) red[wave] = acc;
+  __syncthreads();
+  if (threadIdx.x == 0) a.sumsq_part[(long long)b * a.nsum + blockIdx.x] = red[0] + red[1] + red[2] + red[3];
+}
+
+// One workgroup per 64 x 64 tile of the padded internal iterate [Lp][Sp].
+__global__ __launch_bounds__(NT) void prepare_kernel(PrepArgs a) {
+  const int b = blockIdx.y;
+  const int tiles_c = a.Sp / 64;
+  const int tr = blockIdx.x / tiles_c, tc = blockIdx.x % tiles_c;
+  double ss = 0.0;
+  for (int i = 0; i < a.nsum; ++i) ss += a.sumsq_part[(long long)b * a.nsum + i];
+  const bool finite = (ss == ss) && ss < 1.0e300;
+  const bool zero = finite && ss == 0.0;
+  const double norm = sqrt(ss);
+  double scale = 0.0, cinv = 0.0;
+  if (finite && !zero) {
+    if (a.fn == PRISM_FN_INV_ROOT) {
+      const double cp = 2.0 * norm / (double)(a.root_p + 1);   // c^p
+      scale = 1.0 / cp;
+      cinv = pow(cp, -1.0 / (double)a.root_p);                 // 1 / c
+    } else {
+      scale = 1.0 / norm;
+    }
+  }
+  if (blockIdx.x == 0 && threadIdx.x == 0) {
+    Ctrl c;
+    c.done = (finite && !zero) ? 0 : 1;
+    c.iters = 0;
+    c.status = !finite ? PRISM_INFO_NONFINITE : (zero ? PRISM_INFO_ZERO : PRISM_INFO_BUDGET);
+    c.pad0 = 0;
+    c.alpha = 0.0f; c.res0 = 0.0f; c.res1 = 0.0f; c.res2 = 0.0f;
+    c.norm = norm; c.scale = scale;
+    a.ctrl[b] = c;
+    a.info[b].iters = 0;
+    a.info[b].status = c.status;
+  }
+  if (blockIdx.x == 0) {
+    for (int i = threadIdx.x; i <= PRISM_MAX_ITERS; i += NT) a.info[b].residual[i] = -1.0f;
+    for (int i = threadIdx.x; i < PRISM_MAX_ITERS; i += NT) a.info[b].alpha[i] = 0.0f;
+  }
+
+  __shared__ float tile_t[64][65];
+  float rho = 0.0f;
+  const long long mat = (long long)a.m * a.n;
+  for (int e = threadIdx.x; e < 64 * 64; e += NT) {
+    const int lr = e >> 6, lc = e & 63;
+    const int r = tr * 64 + lr, c = tc * 64 + lc;   // position in the internal [Lp][Sp] iterate
+    double v = 0.0;
+    if (r < a.L && c < a.S) {
+      const long long si = a.transpose ? ((long long)c * a.n + r) : ((long long)r * a.n + c);
+      v = load_src(a.src, a.dt, (long long)b * mat + si) * scale;
+    }
+    const long long o = (long long)b * a.Lp * a.Sp + (long long)r * a.Sp + c;
+    if (a.fn == PRISM_FN_POLAR) {
+      if (a.dt == PRISM_BF16) {
+        const unsigned short hi = f2bf((float)v);
+        a.Xa_hi[o] = hi;
+        if (a.Xa_lo) a.Xa_lo[o] = f2bf((float)v - bf2f(hi));
+        tile_t[lc][lr] = bf2f(hi);
+      } else {
+        a.X32[o] = (float)v;
+      }
+    } else if (a.fn == PRISM_FN_SQRT) {
+      a.X32[o] = (float)v;
+      a.Y32[o] = (r == c && r < a.S) ? 1.0f : 0.0f;
+    } else {  // inverse root: v = M_0 entry
+      const bool in = (r < a.S && c < a.S);
+      const double eye = (r == c && in) ? 1.0 : 0.0;
+      a.M64[o] = v;
+      a.X32[o] = (float)(eye * cinv);
+      const double res = in ? (eye - v) : 0.0;
+      a.R32[o] = (float)res;
+      rho += (float)(res * res);
+    }
+  }
+  if (a.fn == PRISM_FN_POLAR && a.dt == PRISM_BF16) {
+    __syncthreads();
+    // transposed copy Xg[Sp][Lp] (high part), written with the long side contiguous
+    for (int e = threadIdx.x; e < 64 * 64; e += NT) {
+      const int lc = e >> 6, lr = e & 63;
+      const int r = tr * 64 + lr, c = tc * 64 + lc;
+      a.Xg[(long long)b * a.Lp * a.Sp + (long long)c * a.Lp + r] = f2bf(tile_t[lc][lr]);
+    }
+  }
+  if (a.fn == PRISM_FN_INV_ROOT) {
+    __shared__ float red[4];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) rho += __shfl_down(rho, off, 64);
+    if (lane == 0) red[wave] = rho;
+    __syncthreads();
+    if (threadIdx.x == 0)
+      a.rho_part[(long long)b * gridDim.x + blockIdx.x] = red[0] + red[1] + red[2] + red[3];
+  }
+}
+
+// One thread per element of the caller's array.
+__global__ __launch_bounds__(NT) void finalize_kernel(FinalArgs a) {
+  const int b = blockIdx.y;
+  const Ctrl c = a.ctrl[b];
+  if (c.status == PRISM_INFO_NONFINITE || c.status == PRISM_INFO_ZERO) return;
+  const int par = c.iters & 1;
+  const long long mat = (long long)a.m * a.n;
+  const long long i = (long long)blockIdx.x * NT + threadIdx.x;
+  if (i >= mat) return;
+  const int r = (int)(i / a.n), col = (int)(i % a.n);
+  const long long o = (long long)b * a.Lp * a.Sp +
+                      (a.transpose ? ((long long)col * a.Sp + r) : ((long long)r * a.Sp + col));
+  if (a.fn == PRISM_FN_POLAR) {
+    if (a.dt == PRISM_BF16) {
+      float x = bf2f(a.Xa_hi[par][o]);
+      if (a.Xa_lo[par]) x += bf2f(a.Xa_lo[par][o]);
+      ((unsigned short*)a.dst)[(long long)b * mat + i] = f2bf(x);
+    } else {
+      ((float*)a.dst)[(long long)b * mat + i] = a.X32[par][o];
+    }
+  } else if (a.fn == PRISM_FN_SQRT) {
+    const double rs = sqrt(c.norm);
+    ((float*)a.dst)[(long long)b * mat + i] = (float)((double)a.X32[par][o] * rs);
+    ((float*)a.dst2)[(long long)b * mat + i] = (float)((double)a.Y32[par][o] / rs);
+  } else {
+    ((float*)a.dst)[(long long)b * mat + i] = a.X32[par][o];
+  }
+}
+
+__global__ __launch_bounds__(NT) void make_t_kernel(float* T, const float* R, const Ctrl* ctrl, int np, int n) {
+  const int b = blockIdx.y;
+  if (ctrl[b].done) return;
+  const float alpha = ctrl[b].alpha;
+  const long long total = (long long)np * np;
+  const long long i = (long long)blockIdx.x * NT + threadIdx.x;
+  if (i >= total) return;
+  const int r = (int)(i / np), c = (int)(i % np);
+  const float eye = (r == c && r < n) ? 1.0f : 0.0f;
+  T[(long long)b * total + i] = eye + alpha * R[(long long)b * total + i];
+}
+
+}  // namespace
+
+void launch_make_t(float* T, const float* R, const Ctrl* ctrl, int batch, int np, int n, hipStream_t s) {
+  const long long total = (long long)np * np;
+  hipLaunchKernelGGL(make_t_kernel, dim3((unsigned)((total + NT - 1) / NT), batch), dim3(NT), 0, s, T, R, ctrl, np, n);
+}
+
+void launch_sumsq(const PrepArgs& a, hipStream_t s) {
+  hipLaunchKernelGGL(sumsq_kernel, dim3(a.nsum, a.batch), dim3(NT), 0, s, a);
+}
+
+void launch_prepare(const PrepArgs& a, hipStream_t s) {
+  const int tiles = (a.Lp / 64) * (a.Sp / 64);
+  hipLaunchKernelGGL(prepare_kernel, dim3(tiles, a.batch), dim3(NT), 0, s, a);
+}
+
+void launch_finalize(const FinalArgs& a, hipStream_t s) {
+  const long long mat = (long long)a.m * a.n;
+  hipLaunchKernelGGL(finalize_kernel, dim3((unsigned)((mat + NT - 1) / NT), a.batch), dim3(NT), 0, s, a);
+}
+
+}  // namespace prism

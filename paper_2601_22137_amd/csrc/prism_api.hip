@@ -1,0 +1,520 @@
+// Host side of libprism: argument checks, workspace layout and the launch sequences of the
+// three PRISM iterations (paper Table 1; App. A.1, A.3).  Every call only enqueues kernels on
+// the caller's stream: the whole budget of iterations is enqueued up front and each kernel
+// skips matrices whose `done` flag the on-device solve step has set, so there is no host
+// round trip per iteration.
+#include <map>
+#include <mutex>
+#include <string>
+#include <utility>
+
+#include "common.h"
+
+namespace prism {
+
+static thread_local std::string g_last_error;
+void set_last_error(const char* msg) { g_last_error = msg ? msg : ""; }
+
+namespace {
+
+inline int round_up(int x, int m) { return (x + m - 1) / m * m; }
+inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+struct Plan {
+  int fn, dt, batch, m, n;
+  int S, L, Sp, Lp, transpose;
+  int d, p, p_s, ld, nv;
+  int tile;        // GEMM tile of the main products
+  bool split;      // bf16: iterate carried as high + low part
+  int nsum;        // partial sums of the Frobenius norm per matrix
+  int max_parts;   // residual partials per matrix
+  // byte offsets into the workspace
+  size_t o_ctrl, o_info, o_sumsq, o_rho, o_v0, o_v;
+  size_t o_x[2], o_y[2], o_r, o_q, o_t[3];        // fp32 paths (o_y doubles as M64 for inverse root)
+  size_t o_xhi[2], o_xlo[2], o_xg[2], o_rb, o_qb; // bf16 polar
+  size_t total;
+};
+
+int make_plan(Plan& P, int fn, int batch, int m, int n, int dt, int degree, int sketch_dim, int root_p,
+              unsigned flags) {
+  if (batch <= 0 || m <= 0 || n <= 0) return PRISM_EINVAL;
+  if (degree != 3 && degree != 5) return PRISM_EINVAL;
+  if (sketch_dim < 0 || sketch_dim > PRISM_MAX_SKETCH) return PRISM_EINVAL;
+  if (dt != PRISM_F32 && dt != PRISM_BF16) return PRISM_EINVAL;
+  if (fn != PRISM_FN_POLAR && fn != PRISM_FN_SQRT && fn != PRISM_FN_INV_ROOT) return PRISM_EINVAL;
+  if (fn != PRISM_FN_POLAR && m != n) return PRISM_EINVAL;
+  if (fn == PRISM_FN_INV_ROOT && (root_p < 1 || root_p > PRISM_MAX_ROOT || degree != 3)) return PRISM_EINVAL;
+  if (fn != PRISM_FN_POLAR && dt == PRISM_BF16) return PRISM_EUNSUPPORTED;
+  if ((long long)m * n > (1ll << 31) - 1) return PRISM_EUNSUPPORTED;
+  P = Plan();
+  P.fn = fn; P.dt = dt; P.batch = batch; P.m = m; P.n = n;
+  P.transpose = (fn == PRISM_FN_POLAR && m < n) ? 1 : 0;
+  P.S = m < n ? m : n;
+  P.L = m < n ? n : m;
+  P.d = degree == 3 ? 1 : 2;
+  P.p = fn == PRISM_FN_INV_ROOT ? root_p : 0;
+  P.p_s = sketch_dim;
+  P.ld = sketch_dim <= 16 ? 16 : (sketch_dim <= 32 ? 32 : 64);
+  P.nv = fn == PRISM_FN_INV_ROOT ? root_p + 1 : 2 * P.d + 1;
+  P.split = (dt == PRISM_BF16) && !(flags & PRISM_FLAG_BF16_PLAIN_ITERATE);
+  if (dt == PRISM_BF16) {
+    const int s256 = round_up(P.S, 256);
+    P.tile = ((long long)batch * (s256 / 256) * (s256 / 256) >= 512) ? 256 : 128;
+  } else {
+    P.tile = P.S <= 256 ? 64 : 128;
+  }
+  P.Sp = round_up(P.S, P.tile);
+  P.Lp = round_up(P.L, P.tile);
+  P.nsum = 64;
+  const int t0 = (P.Sp / 64) * (P.Lp / 64);   // prepare-step tiles (inverse root residual of M_0)
+  P.max_parts = t0;
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t o = off; off = align256(off + bytes); return o; };
+  const size_t SS = (size_t)P.Sp * P.Sp, LS = (size_t)P.Lp * P.Sp, B = (size_t)batch;
+  P.o_ctrl = take(B * sizeof(Ctrl));
+  P.o_info = take(B * sizeof(prism_info));
+  P.o_sumsq = take(B * P.nsum * sizeof(double));
+  P.o_rho = take(B * P.max_parts * sizeof(float));
+  P.o_v0 = take((size_t)P.Sp * P.ld * sizeof(float));
+  P.o_v = take((size_t)P.nv * B * P.Sp * P.ld * sizeof(float));
+  if (dt == PRISM_BF16) {
+    for (int i = 0; i < 2; ++i) {
+      P.o_xhi[i] = take(B * LS * 2);
+      P.o_xlo[i] = P.split ? take(B * LS * 2) : 0;
+      P.o_xg[i] = take(B * LS * 2);
+    }
+    P.o_r = take(B * SS * 4);
+    P.o_rb = take(B * SS * 2);
+    P.o_qb = P.d == 2 ? take(B * SS * 2) : 0;
+  } else if (fn == PRISM_FN_POLAR) {
+    for (int i = 0; i < 2; ++i) P.o_x[i] = take(B * LS * 4);
+    P.o_r = take(B * SS * 4);
+    P.o_q = P.d == 2 ? take(B * SS * 4) : 0;
+  } else if (fn == PRISM_FN_SQRT) {
+    for (int i = 0; i < 2; ++i) { P.o_x[i] = take(B * SS * 4); P.o_y[i] = take(B * SS * 4); }
+    P.o_r = take(B * SS * 4);
+    P.o_q = P.d == 2 ? take(B * SS * 4) : 0;
+  } else {
+    for (int i = 0; i < 2; ++i) { P.o_x[i] = take(B * SS * 4); P.o_y[i] = take(B * SS * 8); }
+    P.o_r = take(B * SS * 4);
+    for (int i = 0; i < 3; ++i) P.o_t[i] = take(B * SS * 4);
+  }
+  P.total = off;
+  return PRISM_OK;
+}
+
+// grow-only workspace per (device, stream)
+struct Cached { void* ptr = nullptr; size_t bytes = 0; };
+std::mutex g_mu;
+std::map<std::pair<int, void*>, Cached> g_cache;
+
+int get_workspace(size_t bytes, hipStream_t stream, const prism_options* opt, char** out) {
+  if (opt && opt->workspace) {
+    if (opt->workspace_bytes < bytes || ((uintptr_t)opt->workspace & 255)) return PRISM_ENOMEM;
+    *out = (char*)opt->workspace;
+    return PRISM_OK;
+  }
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) { set_last_error("hipGetDevice failed"); return PRISM_EHIP; }
+  std::lock_guard<std::mutex> lock(g_mu);
+  Cached& c = g_cache[std::make_pair(dev, (void*)stream)];
+  if (c.bytes < bytes) {
+    if (c.ptr) { (void)hipFree(c.ptr); c.ptr = nullptr; c.bytes = 0; }
+    if (hipMalloc(&c.ptr, bytes) != hipSuccess) {
+      (void)hipGetLastError();
+      set_last_error("hipMalloc of the workspace failed");
+      c.ptr = nullptr;
+      return PRISM_ENOMEM;
+    }
+    c.bytes = bytes;
+  }
+  *out = (char*)c.ptr;
+  return PRISM_OK;
+}
+
+#define CHECK_LAUNCH(expr)                         \
+  do {                                             \
+    int rc_ = (expr);                              \
+    if (rc_ != PRISM_OK) return rc_;               \
+  } while (0)
+
+int check_hip() {
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) { set_last_error(hipGetErrorString(e)); return PRISM_EHIP; }
+  return PRISM_OK;
+}
+
+struct Run {
+  Plan P;
+  char* ws;
+  hipStream_t s;
+  Ctrl* ctrl;
+  prism_info* info;
+  float* rho;
+  float* v0;
+  float* v;
+  int max_iters, warm;
+  double tol;
+  uint64_t seed;
+
+  template <typename T> T* at(size_t off) const { return (T*)(ws + off); }
+
+  // sketch + chain V_j = R V_{j-1} (fp32 matrix cores, skinny N = padded sketch width)
+  int chain(const float* R, int k) {
+    const int Sp = P.Sp, ld = P.ld;
+    launch_sketch(v0, Sp, P.S, ld, P.p_s, seed, k, P.fn, s);
+    const long long vs = (long long)P.batch * Sp * ld;
+    const int tm = (Sp % 128 == 0) ? 128 : 64;
+    for (int j = 1; j <= P.nv; ++j) {
+      GemmDesc g = {};
+      g.A = R; g.strideA = (long long)Sp * Sp; g.lda = Sp;
+      if (j == 1) { g.B = v0; g.strideB = 0; } else { g.B = v + (j - 2) * vs; g.strideB = (long long)Sp * ld; }
+      g.ldb = ld;
+      g.M = Sp; g.N = ld; g.K = Sp; g.a_km = 0; g.batch = P.batch;
+      g.epi = EPI_STORE;
+      g.C = v + (j - 1) * vs; g.strideC = (long long)Sp * ld; g.ldc = ld;
+      g.ctrl = ctrl;
+      CHECK_LAUNCH(launch_gemm_f32(g, tm, ld, s));
+    }
+    return PRISM_OK;
+  }
+
+  int solve(int k, int nparts) {
+    SolveArgs a = {};
+    a.fn = P.fn; a.k = k; a.d = P.d; a.p = P.p; a.n = P.S; a.rows = P.Sp; a.ld = P.ld;
+    a.V = v; a.vstride = (long long)P.batch * P.Sp * P.ld; a.bstride = (long long)P.Sp * P.ld;
+    a.rho_part = rho; a.nparts = nparts;
+    a.ctrl = ctrl; a.info = info; a.tol = tol; a.max_iters = max_iters;
+    a.mode = P.p_s == 0 ? 1 : (k < warm ? 2 : 0);
+    a.last = (k == max_iters);
+    launch_solve(a, P.batch, s);
+    return check_hip();
+  }
+  bool fit_needed(int k) const { return P.p_s > 0 && k >= warm && k < max_iters; }
+};
+
+GemmDesc f32_desc(const Run& r, const float* A, int lda, long long sa, const float* B, int ldb, long long sb,
+                  int M, int N, int K, int a_km) {
+  GemmDesc g = {};
+  g.A = A; g.strideA = sa; g.lda = lda; g.B = B; g.strideB = sb; g.ldb = ldb;
+  g.M = M; g.N = N; g.K = K; g.a_km = a_km; g.batch = r.P.batch; g.n_true = r.P.S; g.ctrl = r.ctrl;
+  return g;
+}
+
+int run_polar_f32(Run& r) {
+  const Plan& P = r.P;
+  const int Sp = P.Sp, Lp = P.Lp, T = P.tile;
+  const long long SS = (long long)Sp * Sp, LS = (long long)Lp * Sp;
+  float* X[2] = {r.at<float>(P.o_x[0]), r.at<float>(P.o_x[1])};
+  float* R = r.at<float>(P.o_r);
+  float* Q = P.d == 2 ? r.at<float>(P.o_q) : nullptr;
+  const int nparts = (Sp / T) * (Sp / T);
+  int cur = 0;
+  for (int k = 0; k <= r.max_iters; ++k) {
+    if (k == r.max_iters && r.tol <= 0.0) break;
+    GemmDesc g = f32_desc(r, X[cur], Sp, LS, X[cur], Sp, LS, Sp, Sp, Lp, 1);   // G = X^T X
+    g.epi = EPI_RESIDUAL; g.C = R; g.strideC = SS; g.ldc = Sp; g.rho_part = r.rho;
+    CHECK_LAUNCH(launch_gemm_f32(g, T, T, r.s));
+    if (r.fit_needed(k)) CHECK_LAUNCH(r.chain(R, k));
+    CHECK_LAUNCH(r.solve(k, nparts));
+    if (k == r.max_iters) break;
+    const float* Bop = R;
+    if (P.d == 2) {
+      GemmDesc q = f32_desc(r, R, Sp, SS, R, Sp, SS, Sp, Sp, Sp, 1);           // R symmetric: R^2 = R^T R
+      q.epi = EPI_POLYQ; q.C = Q; q.strideC = SS; q.ldc = Sp; q.Cin = R; q.strideCin = SS; q.ldcin = Sp; q.c1 = 0.5f;
+      CHECK_LAUNCH(launch_gemm_f32(q, T, T, r.s));
+      Bop = Q;
+    }
+    GemmDesc a = f32_desc(r, X[cur], Sp, LS, Bop, Sp, SS, Lp, Sp, Sp, 0);      // X + X Q
+    a.epi = EPI_AXPY; a.C = X[cur ^ 1]; a.strideC = LS; a.ldc = Sp; a.Cin = X[cur]; a.strideCin = LS; a.ldcin = Sp;
+    a.coef_is_alpha = P.d == 1;
+    CHECK_LAUNCH(launch_gemm_f32(a, T, T, r.s));
+    cur ^= 1;
+  }
+  return PRISM_OK;
+}
+
+int run_polar_bf16(Run& r) {
+  const Plan& P = r.P;
+  const int Sp = P.Sp, Lp = P.Lp, T = P.tile;
+  const long long SS = (long long)Sp * Sp, LS = (long long)Lp * Sp;
+  uint16_t* Xhi[2] = {r.at<uint16_t>(P.o_xhi[0]), r.at<uint16_t>(P.o_xhi[1])};
+  uint16_t* Xlo[2] = {P.split ? r.at<uint16_t>(P.o_xlo[0]) : nullptr, P.split ? r.at<uint16_t>(P.o_xlo[1]) : nullptr};
+  uint16_t* Xg[2] = {r.at<uint16_t>(P.o_xg[0]), r.at<uint16_t>(P.o_xg[1])};
+  float* R = r.at<float>(P.o_r);
+  uint16_t* Rb = r.at<uint16_t>(P.o_rb);
+  uint16_t* Qb = P.d == 2 ? r.at<uint16_t>(P.o_qb) : nullptr;
+  const int nparts = (Sp / T) * (Sp / T);
+  int cur = 0;
+  for (int k = 0; k <= r.max_iters; ++k) {
+    if (k == r.max_iters && r.tol <= 0.0) break;
+    Bf16Desc g = {};
+    g.A = Xg[cur]; g.strideA = LS; g.lda = Lp; g.B = Xg[cur]; g.strideB = LS; g.ldb = Lp;
+    g.M = Sp; g.N = Sp; g.K = Lp; g.batch = P.batch; g.epi = BEPI_GRAM; g.n_true = P.S;
+    g.C32 = R; g.strideC32 = SS; g.ldc32 = Sp; g.Cb = Rb; g.strideCb = SS; g.ldcb = Sp;
+    g.rho_part = r.rho; g.ctrl = r.ctrl;
+    CHECK_LAUNCH(launch_gemm_bf16(g, T, r.s));
+    if (r.fit_needed(k)) CHECK_LAUNCH(r.chain(R, k));
+    CHECK_LAUNCH(r.solve(k, nparts));
+    if (k == r.max_iters) break;
+    const uint16_t* Bop = Rb;
+    if (P.d == 2) {
+      Bf16Desc q = {};
+      q.A = Rb; q.strideA = SS; q.lda = Sp; q.B = Rb; q.strideB = SS; q.ldb = Sp;
+      q.M = Sp; q.N = Sp; q.K = Sp; q.batch = P.batch; q.epi = BEPI_POLYQ;
+      q.C32 = R; q.strideC32 = SS; q.ldc32 = Sp; q.Cb = Qb; q.strideCb = SS; q.ldcb = Sp; q.c1 = 0.5f;
+      q.ctrl = r.ctrl;
+      CHECK_LAUNCH(launch_gemm_bf16(q, T, r.s));
+      Bop = Qb;
+    }
+    Bf16Desc a = {};
+    a.A = Xhi[cur]; a.A2 = Xlo[cur]; a.strideA = LS; a.lda = Sp; a.B = Bop; a.strideB = SS; a.ldb = Sp;
+    a.M = Lp; a.N = Sp; a.K = Sp; a.batch = P.batch; a.epi = BEPI_APPLY;
+    a.Cb = Xhi[cur ^ 1]; a.Cb2 = Xlo[cur ^ 1]; a.strideCb = LS; a.ldcb = Sp;
+    a.Ct = Xg[cur ^ 1]; a.strideCt = LS; a.ldct = Lp;
+    a.Xhi = Xhi[cur]; a.Xlo = Xlo[cur]; a.coef_is_alpha = P.d == 1; a.ctrl = r.ctrl;
+    CHECK_LAUNCH(launch_gemm_bf16(a, T, r.s));
+    cur ^= 1;
+  }
+  return PRISM_OK;
+}
+
+int run_sqrt_f32(Run& r) {
+  const Plan& P = r.P;
+  const int Sp = P.Sp, T = P.tile;
+  const long long SS = (long long)Sp * Sp;
+  float* X[2] = {r.at<float>(P.o_x[0]), r.at<float>(P.o_x[1])};
+  float* Y[2] = {r.at<float>(P.o_y[0]), r.at<float>(P.o_y[1])};
+  float* R = r.at<float>(P.o_r);
+  float* Q = P.d == 2 ? r.at<float>(P.o_q) : nullptr;
+  const int nparts = (Sp / T) * (Sp / T);
+  int cur = 0;
+  for (int k = 0; k <= r.max_iters; ++k) {
+    if (k == r.max_iters && r.tol <= 0.0) break;
+    GemmDesc g = f32_desc(r, Y[cur], Sp, SS, X[cur], Sp, SS, Sp, Sp, Sp, 0);    // G = Y X
+    g.epi = EPI_RESIDUAL; g.C = R; g.strideC = SS; g.ldc = Sp; g.rho_part = r.rho;
+    CHECK_LAUNCH(launch_gemm_f32(g, T, T, r.s));
+    if (r.fit_needed(k)) CHECK_LAUNCH(r.chain(R, k));
+    CHECK_LAUNCH(r.solve(k, nparts));
+    if (k == r.max_iters) break;
+    const float* Pm = R;
+    if (P.d == 2) {
+      GemmDesc q = f32_desc(r, R, Sp, SS, R, Sp, SS, Sp, Sp, Sp, 0);
+      q.epi = EPI_POLYQ; q.C = Q; q.strideC = SS; q.ldc = Sp; q.Cin = R; q.strideCin = SS; q.ldcin = Sp; q.c1 = 0.5f;
+      CHECK_LAUNCH(launch_gemm_f32(q, T, T, r.s));
+      Pm = Q;
+    }
+    GemmDesc ax = f32_desc(r, X[cur], Sp, SS, Pm, Sp, SS, Sp, Sp, Sp, 0);        // X + X Q
+    ax.epi = EPI_AXPY; ax.C = X[cur ^ 1]; ax.strideC = SS; ax.ldc = Sp; ax.Cin = X[cur]; ax.strideCin = SS; ax.ldcin = Sp;
+    ax.coef_is_alpha = P.d == 1;
+    CHECK_LAUNCH(launch_gemm_f32(ax, T, T, r.s));
+    GemmDesc ay = f32_desc(r, Pm, Sp, SS, Y[cur], Sp, SS, Sp, Sp, Sp, 0);        // Y + Q Y
+    ay.epi = EPI_AXPY; ay.C = Y[cur ^ 1]; ay.strideC = SS; ay.ldc = Sp; ay.Cin = Y[cur]; ay.strideCin = SS; ay.ldcin = Sp;
+    ay.coef_is_alpha = P.d == 1;
+    CHECK_LAUNCH(launch_gemm_f32(ay, T, T, r.s));
+    cur ^= 1;
+  }
+  return PRISM_OK;
+}
+
+int run_inv_root_f32(Run& r) {
+  const Plan& P = r.P;
+  const int Sp = P.Sp, T = P.tile, p = P.p;
+  const long long SS = (long long)Sp * Sp;
+  float* X[2] = {r.at<float>(P.o_x[0]), r.at<float>(P.o_x[1])};
+  double* M[2] = {r.at<double>(P.o_y[0]), r.at<double>(P.o_y[1])};
+  float* R = r.at<float>(P.o_r);
+  float* Tm[3] = {r.at<float>(P.o_t[0]), r.at<float>(P.o_t[1]), r.at<float>(P.o_t[2])};
+  const int nparts0 = (Sp / 64) * (Sp / 64);  // residual of M_0 comes from the prepare step (64 x 64 tiles)
+  const int nparts = (Sp / 64) * (Sp / 64);   // later ones from the fp64 product (64 x 64 tiles)
+  int cur = 0;
+  for (int k = 0; k <= r.max_iters; ++k) {
+    if (k == r.max_iters && r.tol <= 0.0) break;
+    if (r.fit_needed(k)) CHECK_LAUNCH(r.chain(R, k));
+    CHECK_LAUNCH(r.solve(k, k == 0 ? nparts0 : nparts));
+    if (k == r.max_iters) break;
+    GemmDesc ax = f32_desc(r, X[cur], Sp, SS, R, Sp, SS, Sp, Sp, Sp, 0);         // X (I + alpha R)
+    ax.epi = EPI_AXPY; ax.C = X[cur ^ 1]; ax.strideC = SS; ax.ldc = Sp; ax.Cin = X[cur]; ax.strideCin = SS; ax.ldcin = Sp;
+    ax.coef_is_alpha = 1;
+    CHECK_LAUNCH(launch_gemm_f32(ax, T, T, r.s));
+    launch_make_t(Tm[0], R, r.ctrl, P.batch, Sp, P.S, r.s);                       // T = I + alpha R
+    CHECK_LAUNCH(check_hip());
+    // U = T^p by left-to-right binary powering (fp32 products)
+    const float* U = Tm[0];
+    int hb = 0;
+    while ((p >> (hb + 1)) != 0) ++hb;
+    int pp = 1;
+    for (int bit = hb - 1; bit >= 0; --bit) {
+      float* dst = (U == Tm[1]) ? Tm[2] : Tm[1];
+      GemmDesc sq = f32_desc(r, U, Sp, SS, U, Sp, SS, Sp, Sp, Sp, 0);
+      sq.epi = EPI_STORE; sq.C = dst; sq.strideC = SS; sq.ldc = Sp;
+      CHECK_LAUNCH(launch_gemm_f32(sq, T, T, r.s));
+      U = dst;
+      if ((p >> bit) & 1) {
+        float* dst2 = (U == Tm[1]) ? Tm[2] : Tm[1];
+        GemmDesc mu = f32_desc(r, U, Sp, SS, Tm[0], Sp, SS, Sp, Sp, Sp, 0);
+        mu.epi = EPI_STORE; mu.C = dst2; mu.strideC = SS; mu.ldc = Sp;
+        CHECK_LAUNCH(launch_gemm_f32(mu, T, T, r.s));
+        U = dst2;
+      }
+    }
+    (void)pp;
+    GemmDesc mn = {};                                                             // M' = T^p M in fp64
+    mn.A = U; mn.strideA = SS; mn.lda = Sp; mn.B = M[cur]; mn.strideB = SS; mn.ldb = Sp;
+    mn.M = Sp; mn.N = Sp; mn.K = Sp; mn.batch = P.batch; mn.n_true = P.S; mn.ctrl = r.ctrl;
+    mn.epi = EPI_MNEXT; mn.C = M[cur ^ 1]; mn.strideC = SS; mn.ldc = Sp;
+    mn.R32out = R; mn.strideR = SS; mn.ldr = Sp; mn.rho_part = r.rho;
+    CHECK_LAUNCH(launch_gemm_f64a(mn, 64, 64, r.s));
+    cur ^= 1;
+  }
+  return PRISM_OK;
+}
+
+int run(int fn, void* a, void* inv_out, int root_p, int batch, int m, int n, int dt, int degree, int max_iters,
+        int sketch_dim, uint64_t seed, double tol, void* stream, const prism_options* opt) {
+  set_last_error("");
+  if (!a) return PRISM_EINVAL;
+  if (fn == PRISM_FN_SQRT && !inv_out) return PRISM_EINVAL;
+  if (max_iters < 0 || max_iters > PRISM_MAX_ITERS) return PRISM_EINVAL;
+  if (!(tol == tol)) return PRISM_EINVAL;
+  if (opt && opt->warm_iters < 0) return PRISM_EINVAL;
+  Run r;
+  int rc = make_plan(r.P, fn, batch, m, n, dt, degree, sketch_dim, root_p, opt ? opt->flags : 0u);
+  if (rc != PRISM_OK) return rc;
+  r.s = (hipStream_t)stream;
+  rc = get_workspace(r.P.total, r.s, opt, &r.ws);
+  if (rc != PRISM_OK) return rc;
+  const Plan& P = r.P;
+  r.ctrl = r.at<Ctrl>(P.o_ctrl);
+  r.info = (opt && opt->info) ? opt->info : r.at<prism_info>(P.o_info);
+  r.rho = r.at<float>(P.o_rho);
+  r.v0 = r.at<float>(P.o_v0);
+  r.v = r.at<float>(P.o_v);
+  r.max_iters = max_iters; r.tol = tol; r.seed = seed; r.warm = opt ? opt->warm_iters : 0;
+
+  PrepArgs pa = {};
+  pa.fn = fn; pa.dt = dt; pa.batch = batch; pa.m = m; pa.n = n; pa.S = P.S; pa.L = P.L; pa.Sp = P.Sp; pa.Lp = P.Lp;
+  pa.transpose = P.transpose; pa.root_p = root_p; pa.src = a;
+  pa.sumsq_part = r.at<double>(P.o_sumsq); pa.nsum = P.nsum; pa.ctrl = r.ctrl; pa.info = r.info;
+  pa.rho_part = r.rho; pa.tile = P.tile;
+  FinalArgs fa = {};
+  fa.fn = fn; fa.dt = dt; fa.batch = batch; fa.m = m; fa.n = n; fa.S = P.S; fa.L = P.L; fa.Sp = P.Sp; fa.Lp = P.Lp;
+  fa.transpose = P.transpose; fa.dst = a; fa.dst2 = inv_out; fa.ctrl = r.ctrl;
+  if (dt == PRISM_BF16) {
+    pa.Xa_hi = r.at<uint16_t>(P.o_xhi[0]); pa.Xa_lo = P.split ? r.at<uint16_t>(P.o_xlo[0]) : nullptr;
+    pa.Xg = r.at<uint16_t>(P.o_xg[0]);
+    for (int i = 0; i < 2; ++i) {
+      fa.Xa_hi[i] = r.at<uint16_t>(P.o_xhi[i]);
+      fa.Xa_lo[i] = P.split ? r.at<uint16_t>(P.o_xlo[i]) : nullptr;
+    }
+  } else {
+    pa.X32 = r.at<float>(P.o_x[0]);
+    if (fn == PRISM_FN_SQRT) pa.Y32 = r.at<float>(P.o_y[0]);
+    if (fn == PRISM_FN_INV_ROOT) { pa.M64 = r.at<double>(P.o_y[0]); pa.R32 = r.at<float>(P.o_r); }
+    for (int i = 0; i < 2; ++i) {
+      fa.X32[i] = r.at<float>(P.o_x[i]);
+      fa.Y32[i] = fn == PRISM_FN_SQRT ? r.at<float>(P.o_y[i]) : nullptr;
+    }
+  }
+  launch_sumsq(pa, r.s);
+  launch_prepare(pa, r.s);
+  rc = check_hip();
+  if (rc != PRISM_OK) return rc;
+  if (dt == PRISM_BF16) rc = run_polar_bf16(r);
+  else if (fn == PRISM_FN_POLAR) rc = run_polar_f32(r);
+  else if (fn == PRISM_FN_SQRT) rc = run_sqrt_f32(r);
+  else rc = run_inv_root_f32(r);
+  if (rc != PRISM_OK) return rc;
+  launch_finalize(fa, r.s);
+  return check_hip();
+}
+
+}  // namespace
+}  // namespace prism
+
+using namespace prism;
+
+extern "C" {
+
+const char* prism_last_error(void) { return g_last_error.c_str(); }
+
+int prism_workspace_bytes(int fn, int batch, int m, int n, prism_dtype dt, int degree, int sketch_dim,
+                          int root_p, size_t* out_bytes) {
+  if (!out_bytes) return PRISM_EINVAL;
+  Plan P;
+  int rc = make_plan(P, fn, batch, m, n, (int)dt, degree, sketch_dim, root_p, 0u);
+  if (rc != PRISM_OK) return rc;
+  *out_bytes = P.total;
+  return PRISM_OK;
+}
+
+int prism_polar(void* x, int batch, int m, int n, prism_dtype dt, int degree, int max_iters, int sketch_dim,
+                uint64_t seed, double tol, void* stream) {
+  return run(PRISM_FN_POLAR, x, nullptr, 0, batch, m, n, (int)dt, degree, max_iters, sketch_dim, seed, tol, stream, nullptr);
+}
+int prism_polar_ex(void* x, int batch, int m, int n, prism_dtype dt, int degree, int max_iters, int sketch_dim,
+                   uint64_t seed, double tol, void* stream, const prism_options* opt) {
+  return run(PRISM_FN_POLAR, x, nullptr, 0, batch, m, n, (int)dt, degree, max_iters, sketch_dim, seed, tol, stream, opt);
+}
+int prism_sqrt(void* a, void* inv_out, int batch, int m, int n, prism_dtype dt, int degree, int max_iters,
+               int sketch_dim, uint64_t seed, double tol, void* stream) {
+  return run(PRISM_FN_SQRT, a, inv_out, 0, batch, m, n, (int)dt, degree, max_iters, sketch_dim, seed, tol, stream, nullptr);
+}
+int prism_sqrt_ex(void* a, void* inv_out, int batch, int m, int n, prism_dtype dt, int degree, int max_iters,
+                  int sketch_dim, uint64_t seed, double tol, void* stream, const prism_options* opt) {
+  return run(PRISM_FN_SQRT, a, inv_out, 0, batch, m, n, (int)dt, degree, max_iters, sketch_dim, seed, tol, stream, opt);
+}
+int prism_inv_root(void* a, int root_p, int batch, int m, int n, prism_dtype dt, int degree, int max_iters,
+                   int sketch_dim, uint64_t seed, double tol, void* stream) {
+  return run(PRISM_FN_INV_ROOT, a, nullptr, root_p, batch, m, n, (int)dt, degree, max_iters, sketch_dim, seed, tol, stream, nullptr);
+}
+int prism_inv_root_ex(void* a, int root_p, int batch, int m, int n, prism_dtype dt, int degree, int max_iters,
+                      int sketch_dim, uint64_t seed, double tol, void* stream, const prism_options* opt) {
+  return run(PRISM_FN_INV_ROOT, a, nullptr, root_p, batch, m, n, (int)dt, degree, max_iters, sketch_dim, seed, tol, stream, opt);
+}
+
+int prism_sketch(float* out, int n, int sketch_dim, uint64_t seed, int k, int fn, void* stream) {
+  if (!out || n <= 0 || sketch_dim <= 0 || sketch_dim > PRISM_MAX_SKETCH || k < 0) return PRISM_EINVAL;
+  launch_sketch(out, n, n, sketch_dim, sketch_dim, seed, k, fn, (hipStream_t)stream);
+  return check_hip();
+}
+
+int prism_gauss_parts(uint32_t first, uint32_t count, double* radius, double* cosv, double* sinv, void* stream) {
+  if (!radius || !cosv || !sinv || count == 0 || (uint64_t)first + count > (1ull << 24)) return PRISM_EINVAL;
+  launch_gauss_parts(first, count, radius, cosv, sinv, (hipStream_t)stream);
+  return check_hip();
+}
+
+int prism_gemm_f32(const float* A, const float* B, float* C, int batch, int M, int N, int K, int a_km, void* stream) {
+  if (!A || !B || !C || batch <= 0 || M <= 0 || N <= 0 || K <= 0) return PRISM_EINVAL;
+  GemmDesc g = {};
+  g.A = A; g.strideA = (long long)M * K; g.lda = a_km ? M : K;
+  g.B = B; g.strideB = (long long)K * N; g.ldb = N;
+  g.M = M; g.N = N; g.K = K; g.a_km = a_km; g.batch = batch; g.epi = EPI_STORE;
+  g.C = C; g.strideC = (long long)M * N; g.ldc = N;
+  const int tn = (N == 16 || N == 32 || N == 64) ? N : 128;
+  return launch_gemm_f32(g, (tn == 64 && M % 128) ? 64 : 128, tn, (hipStream_t)stream);
+}
+
+int prism_gemm_f64a(const float* A, const double* B, double* C, int batch, int M, int N, int K, void* stream) {
+  if (!A || !B || !C || batch <= 0 || M <= 0 || N <= 0 || K <= 0) return PRISM_EINVAL;
+  GemmDesc g = {};
+  g.A = A; g.strideA = (long long)M * K; g.lda = K;
+  g.B = B; g.strideB = (long long)K * N; g.ldb = N;
+  g.M = M; g.N = N; g.K = K; g.a_km = 0; g.batch = batch; g.epi = EPI_STORE;
+  g.C = C; g.strideC = (long long)M * N; g.ldc = N;
+  return launch_gemm_f64a(g, 64, 64, (hipStream_t)stream);
+}
+
+int prism_gemm_bf16_nt(const uint16_t* A, const uint16_t* B, float* C, int batch, int M, int N, int K, int tile,
+                       void* stream) {
+  if (!A || !B || !C || batch <= 0 || M <= 0 || N <= 0 || K <= 0) return PRISM_EINVAL;
+  Bf16Desc g = {};
+  g.A = A; g.strideA = (long long)M * K; g.lda = K;
+  g.B = B; g.strideB = (long long)N * K; g.ldb = K;
+  g.M = M; g.N = N; g.K = K; g.batch = batch; g.epi = BEPI_STORE;
+  g.C32 = C; g.strideC32 = (long long)M * N; g.ldc32 = N;
+  return launch_gemm_bf16(g, tile, (hipStream_t)stream);
+}
+
+}  // extern "C"

@@ -1,0 +1,184 @@
+"""ctypes binding of libprism.so (see include/prism.h).  Argument marshalling only: every
+step of the path runs in the HIP kernels.  PyTorch supplies device memory and the stream.
+
+The library must have been built (python -m paper_2601_22137_amd.build); there is no fallback.
+"""
+import ctypes
+import os
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libprism.so")
+
+F32, BF16 = 0, 1
+FN_POLAR, FN_SQRT, FN_INV_ROOT = 1, 2, 3
+MAX_ITERS = 64
+FLAG_BF16_PLAIN_ITERATE = 1
+OK, EINVAL, EUNSUPPORTED, ENOMEM, EHIP = 0, 1, 2, 3, 4
+INFO_CONVERGED, INFO_BUDGET, INFO_NONFINITE, INFO_ZERO, INFO_DIVERGED = 0, 1, 2, 3, 4
+
+INFO_DTYPE = np.dtype([("iters", np.int32), ("status", np.int32),
+                       ("residual", np.float32, (MAX_ITERS + 1,)), ("alpha", np.float32, (MAX_ITERS,))])
+
+EXPORTS = ("prism_workspace_bytes", "prism_polar", "prism_polar_ex", "prism_sqrt", "prism_sqrt_ex",
+           "prism_inv_root", "prism_inv_root_ex", "prism_sketch", "prism_gauss_parts", "prism_gemm_f32",
+           "prism_gemm_f64a", "prism_gemm_bf16_nt", "prism_last_error")
+
+
+class Options(ctypes.Structure):
+    _fields_ = [("flags", ctypes.c_uint32), ("warm_iters", ctypes.c_int32), ("workspace", ctypes.c_void_p),
+                ("workspace_bytes", ctypes.c_size_t), ("info", ctypes.c_void_p)]
+
+
+class PrismError(RuntimeError):
+    pass
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise PrismError("libprism.so is not built: run `python -m paper_2601_22137_amd.build`")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i, u64, dbl = ctypes.c_void_p, ctypes.c_int, ctypes.c_uint64, ctypes.c_double
+        L.prism_last_error.restype = ctypes.c_char_p
+        L.prism_workspace_bytes.argtypes = [i, i, i, i, i, i, i, i, ctypes.POINTER(ctypes.c_size_t)]
+        L.prism_polar.argtypes = [vp, i, i, i, i, i, i, i, u64, dbl, vp]
+        L.prism_polar_ex.argtypes = L.prism_polar.argtypes + [ctypes.POINTER(Options)]
+        L.prism_sqrt.argtypes = [vp, vp, i, i, i, i, i, i, i, u64, dbl, vp]
+        L.prism_sqrt_ex.argtypes = L.prism_sqrt.argtypes + [ctypes.POINTER(Options)]
+        L.prism_inv_root.argtypes = [vp, i, i, i, i, i, i, i, i, u64, dbl, vp]
+        L.prism_inv_root_ex.argtypes = L.prism_inv_root.argtypes + [ctypes.POINTER(Options)]
+        L.prism_sketch.argtypes = [vp, i, i, u64, i, i, vp]
+        L.prism_gauss_parts.argtypes = [ctypes.c_uint32, ctypes.c_uint32, vp, vp, vp, vp]
+        L.prism_gemm_f32.argtypes = [vp, vp, vp, i, i, i, i, i, vp]
+        L.prism_gemm_f64a.argtypes = [vp, vp, vp, i, i, i, i, vp]
+        L.prism_gemm_bf16_nt.argtypes = [vp, vp, vp, i, i, i, i, i, vp]
+        _lib = L
+    return _lib
+
+
+def _check(rc):
+    if rc != OK:
+        names = {EINVAL: "PRISM_EINVAL", EUNSUPPORTED: "PRISM_EUNSUPPORTED", ENOMEM: "PRISM_ENOMEM", EHIP: "PRISM_EHIP"}
+        raise PrismError("%s (%s)" % (names.get(rc, rc), lib().prism_last_error().decode()))
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _dtype_code(t):
+    if t.dtype == torch.float32:
+        return F32
+    if t.dtype == torch.bfloat16:
+        return BF16
+    raise PrismError("unsupported dtype %s" % t.dtype)
+
+
+def _batched(t):
+    if not (t.is_cuda and t.is_contiguous() and t.dim() == 3):
+        raise PrismError("expected a contiguous CUDA tensor [batch, m, n]")
+    return t.shape
+
+
+class _Info:
+    def __init__(self, batch, device):
+        self.buf = torch.empty(batch * INFO_DTYPE.itemsize, dtype=torch.uint8, device=device)
+
+    def read(self):
+        """Synchronises and returns a numpy structured array (one record per matrix)."""
+        return self.buf.cpu().numpy().view(INFO_DTYPE).copy()
+
+
+def _options(info, flags, warm_iters, workspace):
+    o = Options()
+    o.flags = flags
+    o.warm_iters = warm_iters
+    o.workspace = workspace.data_ptr() if workspace is not None else None
+    o.workspace_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    o.info = info.buf.data_ptr()
+    return o
+
+
+def workspace_bytes(fn, batch, m, n, dtype_code, degree, sketch_dim, root_p=0):
+    out = ctypes.c_size_t(0)
+    _check(lib().prism_workspace_bytes(fn, batch, m, n, dtype_code, degree, sketch_dim, root_p, ctypes.byref(out)))
+    return out.value
+
+
+def polar(x, degree=5, max_iters=30, sketch_dim=8, seed=22137, tol=1e-6, flags=0, warm_iters=0, workspace=None):
+    """In place: x[batch, m, n] <- polar factor.  Returns an info handle (.read() synchronises)."""
+    b, m, n = _batched(x)
+    info = _Info(b, x.device)
+    o = _options(info, flags, warm_iters, workspace)
+    _check(lib().prism_polar_ex(x.data_ptr(), b, m, n, _dtype_code(x), degree, max_iters, sketch_dim, seed, tol,
+                                _stream(), ctypes.byref(o)))
+    return info
+
+
+def sqrt(a, degree=5, max_iters=30, sketch_dim=8, seed=22137, tol=1e-6, warm_iters=0, workspace=None):
+    """In place: a <- A^(1/2); returns (A^(-1/2), info handle)."""
+    b, m, n = _batched(a)
+    inv = torch.empty_like(a)
+    info = _Info(b, a.device)
+    o = _options(info, 0, warm_iters, workspace)
+    _check(lib().prism_sqrt_ex(a.data_ptr(), inv.data_ptr(), b, m, n, _dtype_code(a), degree, max_iters, sketch_dim,
+                               seed, tol, _stream(), ctypes.byref(o)))
+    return inv, info
+
+
+def inv_root(a, root_p, max_iters=30, sketch_dim=8, seed=22137, tol=1e-6, warm_iters=0, workspace=None):
+    """In place: a <- A^(-1/root_p).  Returns an info handle."""
+    b, m, n = _batched(a)
+    info = _Info(b, a.device)
+    o = _options(info, 0, warm_iters, workspace)
+    _check(lib().prism_inv_root_ex(a.data_ptr(), root_p, b, m, n, _dtype_code(a), 3, max_iters, sketch_dim, seed,
+                                   tol, _stream(), ctypes.byref(o)))
+    return info
+
+
+# ---- single steps (unit tests, profiling) ----
+
+def sketch(n, sketch_dim, seed, k, fn, device="cuda"):
+    out = torch.empty((n, sketch_dim), dtype=torch.float32, device=device)
+    _check(lib().prism_sketch(out.data_ptr(), n, sketch_dim, seed, k, fn, _stream()))
+    return out
+
+
+def gauss_parts(first, count, device="cuda"):
+    r = torch.empty(count, dtype=torch.float64, device=device)
+    c = torch.empty_like(r)
+    s = torch.empty_like(r)
+    _check(lib().prism_gauss_parts(first, count, r.data_ptr(), c.data_ptr(), s.data_ptr(), _stream()))
+    return r, c, s
+
+
+def gemm_f32(A, B, a_km=False):
+    batch = A.shape[0]
+    M, K = (A.shape[2], A.shape[1]) if a_km else (A.shape[1], A.shape[2])
+    N = B.shape[2]
+    C = torch.empty((batch, M, N), dtype=torch.float32, device=A.device)
+    _check(lib().prism_gemm_f32(A.data_ptr(), B.data_ptr(), C.data_ptr(), batch, M, N, K, int(a_km), _stream()))
+    return C
+
+
+def gemm_f64a(A, B):
+    batch, M, K = A.shape
+    N = B.shape[2]
+    C = torch.empty((batch, M, N), dtype=torch.float64, device=A.device)
+    _check(lib().prism_gemm_f64a(A.data_ptr(), B.data_ptr(), C.data_ptr(), batch, M, N, K, _stream()))
+    return C
+
+
+def gemm_bf16_nt(A, B, tile):
+    batch, M, K = A.shape
+    N = B.shape[1]
+    C = torch.empty((batch, M, N), dtype=torch.float32, device=A.device)
+    _check(lib().prism_gemm_bf16_nt(A.data_ptr(), B.data_ptr(), C.data_ptr(), batch, M, N, K, tile, _stream()))
+    return C

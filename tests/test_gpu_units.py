@@ -1,0 +1,75 @@
+"""Unit parity of single kernels against numpy / the oracle (GPU)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import gauss_sketch as gs
+from paper_2601_22137_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def prism():
+    from paper_2601_22137_amd import prism as P
+    P.lib()
+    return P
+
+
+def _dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+@pytest.mark.parametrize("a_km", [False, True])
+@pytest.mark.parametrize("shape", [(128, 128, 64), (256, 128, 80), (128, 16, 128), (128, 32, 256), (256, 64, 128), (64, 64, 48)])
+def test_gemm_f32(prism, a_km, shape):
+    M, N, K = shape
+    rng = np.random.default_rng(M + N + K)
+    A = rng.standard_normal((3, M, K)).astype(np.float32)
+    B = rng.standard_normal((3, K, N)).astype(np.float32)
+    Ain = np.ascontiguousarray(A.transpose(0, 2, 1)) if a_km else A
+    C = prism.gemm_f32(_dev(Ain), _dev(B), a_km=a_km).cpu().numpy()
+    ref = A.astype(np.float64) @ B.astype(np.float64)
+    assert np.linalg.norm(C - ref) / np.linalg.norm(ref) < 1e-6
+
+
+def test_gemm_f64a(prism):
+    rng = np.random.default_rng(7)
+    A = rng.standard_normal((2, 128, 96)).astype(np.float32)
+    B = rng.standard_normal((2, 96, 192))
+    C = prism.gemm_f64a(_dev(A), _dev(B)).cpu().numpy()
+    ref = A.astype(np.float64) @ B
+    assert np.linalg.norm(C - ref) / np.linalg.norm(ref) < 1e-14
+
+
+@pytest.mark.parametrize("tile,shape", [(128, (128, 256, 192)), (256, (512, 256, 128)), (128, (384, 128, 64))])
+def test_gemm_bf16_nt(prism, tile, shape):
+    M, N, K = shape
+    rng = np.random.default_rng(M * 3 + N)
+    A = W.to_bf16_bits(rng.standard_normal((2, M, K)))
+    B = W.to_bf16_bits(rng.standard_normal((2, N, K)))
+    C = prism.gemm_bf16_nt(_dev(A.view(np.int16)), _dev(B.view(np.int16)), tile).cpu().numpy()
+    ref = W.from_bf16_bits(A).astype(np.float64) @ W.from_bf16_bits(B).astype(np.float64).transpose(0, 2, 1)
+    assert np.linalg.norm(C - ref) / np.linalg.norm(ref) < 1e-6
+
+
+@pytest.mark.parametrize("n,p_s,k,fn,seed", [(300, 8, 0, 1, 22137), (1000, 16, 3, 2, 5), (257, 6, 7, 3, 2 ** 40 + 17),
+                                             (4096, 32, 11, 1, 22137), (512, 64, 1, 2, 2 ** 63 + 5)])
+def test_sketch_bit_exact(prism, n, p_s, k, fn, seed):
+    got = prism.sketch(n, p_s, seed, k, fn).cpu().numpy()
+    want = gs.sketch(seed, k, fn, p_s, n).T
+    assert got.dtype == np.float32
+    assert np.array_equal(got.view(np.uint32), np.ascontiguousarray(want).view(np.uint32))
+
+
+def test_box_muller_factors_exhaustive_bit_exact(prism):
+    """All 2^24 radii and all 2^24 angles: the device arithmetic equals the oracle's bit for bit."""
+    step = 1 << 22
+    for first in range(0, 1 << 24, step):
+        r, c, s = prism.gauss_parts(first, step)
+        v = np.arange(first, first + step, dtype=np.int64)
+        wr = gs.radius(v + 1)
+        wc, ws = gs.cos_sin(v)
+        assert np.array_equal(r.cpu().numpy().view(np.uint64), wr.view(np.uint64)), first
+        assert np.array_equal(c.cpu().numpy().view(np.uint64), np.ascontiguousarray(wc).view(np.uint64)), first
+        assert np.array_equal(s.cpu().numpy().view(np.uint64), np.ascontiguousarray(ws).view(np.uint64)), first
