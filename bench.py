@@ -1,0 +1,253 @@
+#!/usr/bin/env python3
+"""Benchmark of the PRISM hot path on one MI355X.
+
+A step is one pass of the whole path (norm, Gram/residual, sketch chain, fit, polynomial build and
+apply, every iteration to the budget or tolerance) over one batch of synthetic matrices that is
+already resident in HBM.  Default workload: the Muon-shaped batch (64 bf16 matrices, 16 each of
+768x768, 768x3072, 3072x768, 768x2304; degree 5, sketch 16, 5 iterations).  Prints one JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK = {"bf16": 2500.0, "f32": 157.3, "f64": 78.6}   # dense MFMA TFLOP/s, MI355X
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5"])
+    ap.add_argument("--split", action="store_true", help="c2: carry the iterate as a bf16 high+low pair")
+    ap.add_argument("--batch", type=int, default=0, help="override the batch size (c3/c4/c5)")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
+    ap.add_argument("--no-profile", action="store_true", help="skip the per-kernel event pass")
+    return ap.parse_args()
+
+
+class Workload:
+    """name, groups of device tensors, how to call the library, flop model."""
+
+
+def make_workload(args, torch, prism, W):
+    wl = Workload()
+    name = args.workload
+    wl.name = name
+    wl.seed = W.SKETCH_SEED
+    if name == "c2":
+        wl.desc = "muon-shaped: 64 bf16 matrices = 16 x {768x768, 768x3072, 3072x768, 768x2304}, degree 5, sketch 16, 5 iterations" + \
+                  (", split-bf16 iterate" if args.split else ", plain bf16 iterate")
+        wl.dtype = "bf16"
+        wl.host = [W.c2_muon_group(i) for i in range(4)]
+        wl.flags = 0 if args.split else prism.FLAG_BF16_PLAIN_ITERATE
+        wl.call = lambda x: prism.polar(x, 5, 5, 16, wl.seed, 0.0, flags=wl.flags)
+        wl.split = args.split
+    elif name == "c3":
+        b = args.batch or 8
+        wl.desc = "polar of %d x 4096x4096 bf16, sigma log-uniform [1e-4,1], degree 5, sketch 32, tol 1e-2, split-bf16 iterate" % b
+        wl.dtype = "bf16"
+        wl.host = [W.c3_polar_large(batch=b)]
+        wl.call = lambda x: prism.polar(x, 5, 40, 32, wl.seed, 1e-2)
+        wl.split = True
+    elif name == "c4":
+        b = args.batch or 32
+        wl.desc = "inverse 4th root of %d x 1024x1024 fp32 SPD (power-law spectrum), sketch 16, tol 1e-5" % b
+        wl.dtype = "f32"
+        wl.host = [W.c4_shampoo_spd(batch=b)]
+        wl.call = lambda x: prism.inv_root(x, 4, 40, 16, wl.seed, 1e-5)
+    elif name == "c5":
+        b = args.batch or 4
+        wl.desc = "sqrt + inverse sqrt of %d x 8192x8192 fp32 SPD (Wishart), degree 5, sketch 64, tol 1e-5" % b
+        wl.dtype = "f32"
+        wl.host = [W.c5_wishart_spd(batch=b)]
+        wl.call = lambda x: prism.sqrt(x, 5, 40, 64, wl.seed, 1e-5)[1]
+    else:
+        wl.desc = "polar of one 64x32 fp32 matrix, cond 1e3, degree 5, sketch 8, tol 1e-6"
+        wl.dtype = "f32"
+        wl.host = [W.c1_polar_small()]
+        wl.call = lambda x: prism.polar(x, 5, 30, 8, wl.seed, 1e-6)
+    wl.n_matrices = sum(h.shape[0] for h in wl.host)
+    return wl
+
+
+def to_device(h, torch):
+    if h.dtype == np.uint16:
+        return torch.from_numpy(h.view(np.int16)).cuda().view(torch.bfloat16)
+    return torch.from_numpy(h).cuda()
+
+
+def flops_per_iteration(name, m, n, split):
+    """(algorithmic, executed) GEMM flops of one iteration for one matrix (dense, no symmetry savings)."""
+    S, L = min(m, n), max(m, n)
+    if name in ("c1", "c2", "c3"):
+        algo = 4.0 * L * S * S + 2.0 * S ** 3
+        return algo, algo + (2.0 * L * S * S if split else 0.0)
+    if name == "c5":
+        return 8.0 * n ** 3, 8.0 * n ** 3
+    return 8.0 * n ** 3, 8.0 * n ** 3      # c4, p = 4: X R, T^2, T^4, T^4 M
+
+
+def oracle_call(name, host_matrix, W, O, seed):
+    if name == "c2":
+        return O.polar(W.from_bf16_bits(host_matrix), 5, 5, 16, seed, 0.0)
+    if name == "c3":
+        return O.polar(W.from_bf16_bits(host_matrix), 5, 40, 32, seed, 1e-2)
+    if name == "c4":
+        return O.inv_root(host_matrix, 4, 40, 16, seed, 1e-5)
+    if name == "c5":
+        r, _, info = O.sqrt(host_matrix, 5, 40, 64, seed, 1e-5)
+        return r, info
+    return O.polar(host_matrix, 5, 30, 8, seed, 1e-6)
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); --gpus %d is not supported" % args.gpus,
+              file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2601_22137_amd import prism, workloads as W
+    prism.lib()
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    wl = make_workload(args, torch, prism, W)
+    K, Wm = args.steps, args.warmup
+
+    # one pristine device copy per step: the calls work in place and nothing is re-uploaded in the timed region
+    pristine = [to_device(h, torch) for h in wl.host]
+    bytes_per_copy = sum(p.numel() * p.element_size() for p in pristine)
+    n_copies = K + Wm
+    copies = [[p.clone() for p in pristine] for _ in range(n_copies)]
+
+    def step(i):
+        return [wl.call(x) for x in copies[i]]
+
+    for i in range(Wm):
+        step(i)
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    ev0.record()
+    handles = None
+    for i in range(K):
+        handles = step(Wm + i)
+    ev1.record()
+    torch.cuda.synchronize()
+    ms_total = ev0.elapsed_time(ev1)
+    ms_per_step = ms_total / K
+    value = wl.n_matrices / (ms_per_step * 1e-3)
+
+    # iteration counts of the last step -> flops
+    infos = []
+    for h in handles:
+        infos.append(h.read())
+    algo = execd = 0.0
+    iters_all = []
+    for h, inf in zip(wl.host, infos):
+        m, n = h.shape[1], h.shape[2]
+        fa, fe = flops_per_iteration(wl.name, m, n, getattr(wl, "split", False))
+        for rec in inf:
+            algo += fa * rec["iters"]
+            execd += fe * rec["iters"]
+            iters_all.append(int(rec["iters"]))
+    tflops_algo = algo / (ms_per_step * 1e-3) / 1e12
+    tflops_exec = execd / (ms_per_step * 1e-3) / 1e12
+
+    # CPU oracle on a bounded sample of the same workload
+    cpu = None
+    parity = None
+    if not args.no_cpu:
+        from oracle import prism_ref as O
+        try:
+            from threadpoolctl import threadpool_info
+            threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+        except Exception:
+            threads = len(os.sched_getaffinity(0))
+        per_group = {"c1": 1, "c2": 2, "c3": 1, "c4": 4, "c5": 1}[wl.name]
+        if wl.name in ("c3", "c5") and wl.host[0].shape[1] > 2048:
+            per_group = 1
+        t_cpu, n_cpu, worst = 0.0, 0, 0.0
+        last = [x for x in copies[Wm + K - 1]]
+        for g, h in enumerate(wl.host):
+            out = last[g]
+            if out.dtype == torch.bfloat16:
+                out_h = W.from_bf16_bits(out.view(torch.int16).cpu().numpy().view(np.uint16))
+            else:
+                out_h = out.cpu().numpy()
+            for i in range(min(per_group, h.shape[0])):
+                t0 = time.perf_counter()
+                ref, oinfo = oracle_call(wl.name, h[i], W, O, wl.seed)
+                t_cpu += time.perf_counter() - t0
+                n_cpu += 1
+                rel = float(np.linalg.norm(out_h[i].astype(np.float64) - ref) / np.linalg.norm(ref))
+                worst = max(worst, rel)
+                if oinfo["iters"] != int(infos[g][i]["iters"]):
+                    worst = float("inf")
+        cpu = {"value": round(n_cpu / t_cpu, 4), "unit": "matrices/s", "cores": int(threads), "kind": "oracle",
+               "sample": "%d matrices (%d per shape group) of the same workload, numpy fp64" % (n_cpu, per_group)}
+        parity = {"max_rel_fro_err_vs_oracle": worst, "matrices_checked": n_cpu}
+
+    # per-kernel durations (HIP events around each launch) over a repeat of the timed steps
+    roofline = None
+    kernel_ms = {}
+    if not args.no_profile:
+        for i in range(n_copies):
+            for dst, src in zip(copies[i], pristine):
+                dst.copy_(src)
+        torch.cuda.synchronize()
+        nprof = min(K, 3)
+        prism.profile_enable(True)
+        for i in range(nprof):
+            step(Wm + i)
+        torch.cuda.synchronize()
+        prof = prism.profile_collect()
+        prism.profile_enable(False)
+        kernel_ms = {k: round(v[0] / nprof, 4) for k, v in prof.items() if v[1]}
+        gemm_kinds = [k for k in prof if prof[k][1] and (k.startswith("bf16_") or k.startswith("f32_") or k.startswith("f64_"))]
+        dom = max(gemm_kinds, key=lambda k: prof[k][0])
+        # algorithmic flops of all launches of that kind in the profiled steps
+        fl = 0.0
+        for h, inf in zip(wl.host, infos):
+            m, n = h.shape[1], h.shape[2]
+            S, L = min(m, n), max(m, n)
+            per_iter = {"bf16_apply": 2.0 * L * S * S, "bf16_gram": 2.0 * L * S * S, "bf16_polyq": 2.0 * S ** 3,
+                        "f32_resid": 2.0 * L * S * S, "f32_polyq": 2.0 * S ** 3,
+                        "f32_apply": (4.0 if wl.name == "c5" else 2.0) * L * S * S,
+                        "f32_store": 4.0 * S ** 3, "f64_mnext": 2.0 * S ** 3}[dom]
+            for rec in inf:
+                nit = rec["iters"] + (1 if dom in ("bf16_gram", "f32_resid") and rec["status"] == prism.INFO_CONVERGED else 0)
+                fl += per_iter * nit
+        fl *= nprof
+        dur_s = prof[dom][0] * 1e-3
+        dt_peak = "f64" if dom.startswith("f64") else ("bf16" if dom.startswith("bf16") else "f32")
+        achieved = fl / dur_s / 1e12
+        roofline = {"bound": "mfma", "kernel": dom, "achieved": round(achieved, 2), "peak": PEAK[dt_peak], "unit": "TFLOP/s",
+                    "frac": round(achieved / PEAK[dt_peak], 4), "traffic": None,
+                    "launches": int(prof[dom][1]), "avg_launch_ms": round(prof[dom][0] / prof[dom][1], 4)}
+
+    out = {
+        "metric": "matrices_per_s", "value": round(value, 3), "unit": "matrices/s", "n_gpus": 1, "steps": K, "warmup": Wm,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": wl.dtype, "data": "synthetic",
+        "config": {"workload": wl.name + ": " + wl.desc, "matrices_per_step": wl.n_matrices,
+                   "input_bytes_per_step": bytes_per_copy},
+        "tflops_algorithmic": round(tflops_algo, 2), "tflops_executed": round(tflops_exec, 2),
+        "frac_of_mfma_peak": round(tflops_exec / PEAK[wl.dtype], 4),
+        "iterations": {"min": min(iters_all), "max": max(iters_all)},
+        "kernel_ms_per_step": kernel_ms,
+        "roofline": roofline, "cpu_baseline": cpu, "parity": parity,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -153,6 +153,15 @@ int prism_gemm_f64a(const float* A, const double* B, double* C, int batch, int M
 int prism_gemm_bf16_nt(const uint16_t* A, const uint16_t* B, float* C, int batch, int M, int N,
                        int K, int tile, void* stream);
 
+/* Per-kernel timing for benchmarks: while enabled, every kernel launch of the library is
+ * bracketed by a HIP event pair on the caller's stream.  prism_profile_enable(on) also discards
+ * what was recorded so far.  prism_profile_collect waits for the recorded events and returns the
+ * summed milliseconds and the launch counts per kernel kind (PRISM_PROFILE_KINDS host arrays).
+ * Not thread safe; meant for a single benchmarking thread. */
+#define PRISM_PROFILE_KINDS 15
+int prism_profile_enable(int on);
+int prism_profile_collect(double* ms_by_kind, long long* launches_by_kind, int nkinds);
+
 /* Last HIP error string seen by the library on this thread ("" if none). */
 const char* prism_last_error(void);
 

@@ -77,6 +77,7 @@ struct Bf16Desc {
   int coef_is_alpha;                                 // APPLY: multiply acc by ctrl.alpha (d = 1)
   float* rho_part;
   const Ctrl* ctrl;
+  int dbg;                                           // timing experiments only (test entry): bit0: no global loads after the prologue; bit1: XCD-private tile ranges; bit2: 4x8 tile blocks
 };
 int launch_gemm_bf16(const Bf16Desc& g, int tile, hipStream_t s);
 
@@ -137,5 +138,18 @@ void launch_finalize(const FinalArgs& a, hipStream_t s);
 void launch_make_t(float* T, const float* R, const Ctrl* ctrl, int batch, int np, int n, hipStream_t s);
 
 void set_last_error(const char* msg);
+
+// ---- per-kernel timing with HIP events (off unless prism_profile_enable(1)) ----
+enum ProfKind {
+  PK_PREP = 0, PK_FINAL, PK_SKETCH, PK_CHAIN, PK_SOLVE,
+  PK_F32_RESID, PK_F32_POLYQ, PK_F32_APPLY, PK_F32_STORE, PK_F64_MNEXT, PK_MAKE_T,
+  PK_BF16_GRAM, PK_BF16_POLYQ, PK_BF16_APPLY, PK_BF16_STORE,
+  PK_COUNT
+};
+struct ProfScope {   // records an event pair around the launches made during its lifetime
+  ProfScope(int kind, hipStream_t s);
+  ~ProfScope();
+  int slot; hipStream_t stream;
+};
 
 }  // namespace prism

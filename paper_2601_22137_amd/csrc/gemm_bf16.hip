@@ -8,8 +8,9 @@
 // of the iterate, R and Q are symmetric, and the update reads the [L][S] copy.
 //
 // One workgroup = 4 wavefronts computes a T x T tile (T = 256 or 128) for one matrix; K runs in
-// slabs of 64 staged through LDS rows padded to 144 bytes (conflict-free 16-byte reads), double
-// buffered.  With a second A operand (the low half of a split-bf16 iterate) the K loop simply
+// slabs of 32 moved straight from global memory into a four-deep LDS ring (no register staging;
+// loads run three slabs ahead to cover the memory latency), in a swizzled layout that keeps the
+// 16-byte fragment reads free of bank conflicts.  With a second A operand (the low half of a split-bf16 iterate) the K loop simply
 // runs over both halves against the same B.
 #include "common.h"
 
@@ -21,8 +22,7 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned short u16x4 __attribute__((ext_vector_type(4)));
 
-constexpr int BK = 64;
-constexpr int LDK = BK + 8;  // LDS row stride in elements (144 bytes)
+constexpr int BK = 32;
 constexpr int NT = 256;
 
 __device__ inline unsigned short f2bf(float x) {
@@ -32,28 +32,49 @@ __device__ inline unsigned short f2bf(float x) {
 }
 __device__ inline float bf2f(unsigned short h) { return __uint_as_float(((unsigned int)h) << 16); }
 
+typedef const void __attribute__((address_space(1)))* gptr_t;
+typedef void __attribute__((address_space(3)))* lptr_t;
+
+constexpr int STAGES = 4;    // LDS ring: loads run three slabs ahead of the MFMAs
+
+// s_waitcnt vmcnt(N) with the other counters left alone (gfx9 encoding)
+template <int N> __device__ inline void wait_vmcnt() {
+  __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | 0x0F70);
+}
+
 template <int T, int EPI>
 __global__ __launch_bounds__(NT) void gemm_bf16_kernel(Bf16Desc g) {
-  constexpr int WT = T / 2;        // wave tile (2 x 2 waves)
-  constexpr int NB = WT / 32;      // 32x32 blocks per wave and dimension
-  constexpr int LOADS = T * 8 / NT;  // 16-byte chunks per thread, operand and slab
-  extern __shared__ __align__(16) unsigned char smem[];
-  unsigned short* As = (unsigned short*)smem;       // [2][T][LDK]
-  unsigned short* Bs = As + 2 * T * LDK;            // [2][T][LDK]
+  constexpr int WT = T / 2;         // wave tile (2 x 2 waves)
+  constexpr int NB = WT / 32;       // 32x32 blocks per wave and dimension
+  constexpr int LDI = T / 64;       // direct-to-LDS load instructions per wave, operand and slab
+  constexpr int OP_BYTES = T * 64;  // one operand slab in LDS: T rows x 32 bf16, unpadded
+  constexpr int BUF_BYTES = 2 * OP_BYTES;
+  // LDS: ring of STAGES buffers, each [A slab | B slab].  Two consecutive rows share one 128-byte
+  // line; the eight 16-byte chunks of line q sit at slot ((row & 1) * 4 + chunk) ^ (q & 7), so the
+  // 16-byte fragment reads of 8 consecutive rows cover all banks exactly once.
+  extern __shared__ __align__(1024) unsigned char smem[];
   __shared__ float red[4];
 
   const int tiles_m = g.M / T, tiles_n = g.N / T;
   const int per_mat = tiles_m * tiles_n;
   const int total = per_mat * g.batch;
   int wg = blockIdx.x;
-  if ((total & 7) == 0) wg = (wg & 7) * (total >> 3) + (wg >> 3);  // one XCD = contiguous tile range
+  // Workgroup i runs tile i: consecutive workgroups go to different XCDs, so at any time all
+  // XCDs work on neighbouring tiles of the same matrix and share its panels through the
+  // Infinity Cache.  (Measured equal to or better than giving each XCD a private tile range.)
+  if ((total & 7) == 0 && (g.dbg & 2)) wg = (wg & 7) * (total >> 3) + (wg >> 3);  // experiment: one XCD = contiguous tile range
   const int b = wg / per_mat;
-  const int rem = wg - b * per_mat;
-  const int tm = rem / tiles_n, tn = rem - tm * tiles_n;
+  int rem = wg - b * per_mat;
+  int tm = rem / tiles_n, tn = rem - tm * tiles_n;
+  if (g.dbg & 4) {  // experiment: 4 x 8 blocks of tiles
+    const int blk = rem / 32, in = rem % 32, bpr = tiles_n / 8;
+    tm = (blk / bpr) * 4 + in / 8; tn = (blk % bpr) * 8 + in % 8;
+  }
   if (g.ctrl && g.ctrl[b].done) return;
   const float alpha = g.ctrl ? g.ctrl[b].alpha : 1.0f;
 
-  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  const int t = threadIdx.x, lane = t & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(t >> 6);  // uniform: LDS destinations stay scalar
   const int wm0 = (wave >> 1) * WT, wn0 = (wave & 1) * WT;
   const int m0 = tm * T, n0 = tn * T;
   const unsigned short* A1 = g.A + (long long)b * g.strideA + (long long)m0 * g.lda;
@@ -63,26 +84,32 @@ __global__ __launch_bounds__(NT) void gemm_bf16_kernel(Bf16Desc g) {
   const int KT1 = g.K / BK;
   const int KT = A2 ? 2 * KT1 : KT1;
 
-  u32x4 ra[LOADS], rb[LOADS];
-  auto load_slab = [&](int kt) {
-    const unsigned short* Ap = (kt < KT1) ? A1 : A2;
-    const int k0 = ((kt < KT1) ? kt : kt - KT1) * BK;
+  // Global -> LDS without passing through registers (global_load_lds_dwordx4): one wave
+  // instruction moves 64 lanes x 16 bytes into 1 KiB of consecutive LDS = 16 rows of a slab.
+  // Lane l fills slot l & 7 of line l >> 3 and therefore fetches the chunk that belongs there.
+  const int lq = lane >> 3, lu = (lane & 7) ^ lq;
+  unsigned aoff[LDI], boff[LDI];
 #pragma unroll
-    for (int it = 0; it < LOADS; ++it) {
-      const int idx = t + it * NT;
-      const int row = idx >> 3, c = idx & 7;
-      ra[it] = *(const u32x4*)(Ap + (long long)row * g.lda + k0 + c * 8);
-      rb[it] = *(const u32x4*)(Bb + (long long)row * g.ldb + k0 + c * 8);
+  for (int it = 0; it < LDI; ++it) {
+    const int row = (it * 4 + wave) * 16 + 2 * lq + (lu >> 2);
+    aoff[it] = (unsigned)(row * g.lda + (lu & 3) * 8) * 2u;
+    boff[it] = (unsigned)(row * g.ldb + (lu & 3) * 8) * 2u;
+  }
+  // one load instruction pair index u in [0, 2*LDI): even = A, odd = B
+  auto issue_load = [&](int kt, int u) {
+    const int it = u >> 1;
+    const int kk0 = ((kt < KT1) ? kt : kt - KT1) * BK;
+    unsigned char* dst = smem + (kt & (STAGES - 1)) * BUF_BYTES + wave * 1024 + it * 4096;
+    if (u & 1) {
+      __builtin_amdgcn_global_load_lds((gptr_t)((const char*)(Bb + kk0) + boff[it]), (lptr_t)(dst + OP_BYTES), 16, 0, 0);
+    } else {
+      const unsigned short* Ap = ((kt < KT1) ? A1 : A2) + kk0;
+      __builtin_amdgcn_global_load_lds((gptr_t)((const char*)Ap + aoff[it]), (lptr_t)dst, 16, 0, 0);
     }
   };
-  auto store_slab = [&](int buf) {
+  auto issue_loads = [&](int kt) {
 #pragma unroll
-    for (int it = 0; it < LOADS; ++it) {
-      const int idx = t + it * NT;
-      const int row = idx >> 3, c = idx & 7;
-      *(u32x4*)(As + ((long long)buf * T + row) * LDK + c * 8) = ra[it];
-      *(u32x4*)(Bs + ((long long)buf * T + row) * LDK + c * 8) = rb[it];
-    }
+    for (int u = 0; u < 2 * LDI; ++u) issue_load(kt, u);
   };
 
   f32x16 acc[NB][NB];
@@ -93,30 +120,99 @@ __global__ __launch_bounds__(NT) void gemm_bf16_kernel(Bf16Desc g) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
-  load_slab(0);
-  store_slab(0);
-  __syncthreads();
-  const int lr = lane & 31, lk = (lane >> 5) * 8;
-  for (int kt = 0; kt < KT; ++kt) {
-    const int cur = kt & 1;
-    if (kt + 1 < KT) load_slab(kt + 1);
-    const unsigned short* Ac = As + ((long long)cur * T + wm0 + lr) * LDK + lk;
-    const unsigned short* Bc = Bs + ((long long)cur * T + wn0 + lr) * LDK + lk;
+  // fragment addresses: row r = tile row, chunk cc = 2 * kk + (lane >> 5)
+  const int lr = lane & 31, lh = lane >> 5;
+  const unsigned char* Afr = smem + ((wm0 + lr) >> 1) * 128;
+  const unsigned char* Bfr = smem + OP_BYTES + ((wn0 + lr) >> 1) * 128;
+  int koff[2];
 #pragma unroll
-    for (int kk = 0; kk < BK / 16; ++kk) {
-      bf16x8 a[NB], bb[NB];
+  for (int kk = 0; kk < 2; ++kk) koff[kk] = ((((lr & 1) << 2) + kk * 2 + lh) ^ ((lr >> 1) & 7)) << 4;
+  bf16x8 fa[2][NB], fb[2][NB];
+  // fragment f in [0, 2*NB) of sub-step kk: first the NB row blocks of A, then the NB of B
+  auto load_frag = [&](int kt, int kk, int f) {
+    const int o = (kt & (STAGES - 1)) * BUF_BYTES + koff[kk];
+    if (f < NB) fa[kk][f] = *(const bf16x8*)(Afr + o + f * 2048);
+    else fb[kk][f - NB] = *(const bf16x8*)(Bfr + o + (f - NB) * 2048);
+  };
+  auto load_frags = [&](int kt, int kk) {
 #pragma unroll
-      for (int i = 0; i < NB; ++i) a[i] = *(const bf16x8*)(Ac + i * 32 * LDK + kk * 16);
+    for (int f = 0; f < 2 * NB; ++f) load_frag(kt, kk, f);
+  };
+  auto mfma_one = [&](int set, int m) {
+    const int i = m / NB, j = m % NB;
+    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[set][i], fb[set][j], acc[i][j], 0, 0, 0);
+  };
+  auto mfma_block = [&](int set) {
 #pragma unroll
-      for (int j = 0; j < NB; ++j) bb[j] = *(const bf16x8*)(Bc + j * 32 * LDK + kk * 16);
+    for (int i = 0; i < NB; ++i)
 #pragma unroll
-      for (int i = 0; i < NB; ++i)
+      for (int j = 0; j < NB; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[set][i], fb[set][j], acc[i][j], 0, 0, 0);
+  };
+  // wait until the loads of slab `kt` have landed: up to two younger slabs may still be in flight
+  auto wait_slab = [&](int kt) {
+    const int younger = KT - 1 - kt;
+    if (younger >= 2) wait_vmcnt<4 * LDI>();
+    else if (younger == 1) wait_vmcnt<2 * LDI>();
+    else wait_vmcnt<0>();
+  };
+
+  // Workgroup barrier without the release fence of __syncthreads(): that fence would wait for
+  // ALL outstanding loads (vmcnt(0)) and serialise the ring.  What must be complete is awaited
+  // explicitly: this wave's share of the slab about to be consumed (wait_slab) and its own
+  // fragment reads of the ring slot that is recycled after the barrier (lgkmcnt(0)).
+  auto ring_barrier = [&]() {
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+  };
+
+  // Main loop.  Slab kt+3 is requested at the top of slab kt (its ring slot was released by the
+  // barrier that closed slab kt-1); the fragments of the second half of slab kt are read while
+  // its first half computes, and after the single barrier of the slab the first fragments of
+  // slab kt+1 are read while the second half computes.
+  static_assert(BK == 32 && STAGES == 4, "pipeline written for two sub-steps per slab and a ring of four");
 #pragma unroll
-        for (int j = 0; j < NB; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], bb[j], acc[i][j], 0, 0, 0);
+  for (int s0 = 0; s0 < STAGES - 1; ++s0)
+    if (s0 < KT) issue_loads(s0);
+  wait_slab(0);
+  ring_barrier();
+  load_frags(0, 0);
+  int kt = 0;
+  const int KT_main = (g.dbg & 1) ? 0 : KT - (STAGES - 1);
+  constexpr int NF = 2 * NB;            // fragment reads per sub-step = interleave steps
+  constexpr int MPS = NB * NB / NF;     // MFMAs per interleave step
+  static_assert(2 * LDI == NF, "one load instruction per interleave step");
+  for (; kt < KT_main; ++kt) {          // steady state: no conditions inside
+    // sub-step 0 of slab kt: request slab kt+3 and read the fragments of sub-step 1, one of each
+    // between MFMAs so that they issue in the shadow of the matrix pipe
+#pragma unroll
+    for (int u = 0; u < NF; ++u) {
+      issue_load(kt + STAGES - 1, u);
+      load_frag(kt, 1, u);
+#pragma unroll
+      for (int v = 0; v < MPS; ++v) mfma_one(0, u * MPS + v);
+      __builtin_amdgcn_sched_barrier(0);
     }
-    if (kt + 1 < KT) store_slab(cur ^ 1);
-    __syncthreads();
+    wait_vmcnt<4 * LDI>();              // slab kt+1 has landed; kt+2 and kt+3 may be in flight
+    ring_barrier();
+#pragma unroll
+    for (int u = 0; u < NF; ++u) {
+      load_frag(kt + 1, 0, u);
+#pragma unroll
+      for (int v = 0; v < MPS; ++v) mfma_one(1, u * MPS + v);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  }
+  for (; kt < KT; ++kt) {               // drain: nothing left to request
+    load_frags(kt, 1);
+    mfma_block(0);
+    if (kt + 1 < KT) {
+      if (g.dbg & 1) wait_vmcnt<0>(); else wait_slab(kt + 1);
+    }
+    ring_barrier();
+    if (kt + 1 < KT) load_frags(kt + 1, 0);
+    mfma_block(1);
   }
 
   // epilogue: register r of lane l holds row (r/4)*8 + (l/32)*4 + r%4, column l%32 of a block
@@ -180,7 +276,7 @@ __global__ __launch_bounds__(NT) void gemm_bf16_kernel(Bf16Desc g) {
 template <int T, int EPI>
 int launch_te(const Bf16Desc& g, hipStream_t s) {
   const int total = (g.M / T) * (g.N / T) * g.batch;
-  const size_t lds = (size_t)4 * T * LDK * sizeof(unsigned short);
+  const size_t lds = (size_t)STAGES * 2 * T * 64;   // ring of STAGES x (A slab + B slab)
   static bool attr_set = false;  // per instantiation
   if (!attr_set) {
     if (hipFuncSetAttribute((const void*)gemm_bf16_kernel<T, EPI>, hipFuncAttributeMaxDynamicSharedMemorySize,

@@ -3,9 +3,11 @@
 // the caller's stream: the whole budget of iterations is enqueued up front and each kernel
 // skips matrices whose `done` flag the on-device solve step has set, so there is no host
 // round trip per iteration.
+#include <cstdlib>
 #include <map>
 #include <mutex>
 #include <string>
+#include <vector>
 #include <utility>
 
 #include "common.h"
@@ -14,6 +16,26 @@ namespace prism {
 
 static thread_local std::string g_last_error;
 void set_last_error(const char* msg) { g_last_error = msg ? msg : ""; }
+
+// ---------------------------------------------------------------- event profiling
+namespace {
+struct ProfRec { int kind; hipEvent_t a, b; };
+bool g_prof_on = false;
+std::vector<ProfRec> g_prof;
+}  // namespace
+
+ProfScope::ProfScope(int kind, hipStream_t s) : slot(-1), stream(s) {
+  if (!g_prof_on) return;
+  ProfRec r;
+  r.kind = kind;
+  if (hipEventCreate(&r.a) != hipSuccess || hipEventCreate(&r.b) != hipSuccess) return;
+  (void)hipEventRecord(r.a, s);
+  g_prof.push_back(r);
+  slot = (int)g_prof.size() - 1;
+}
+ProfScope::~ProfScope() {
+  if (slot >= 0) (void)hipEventRecord(g_prof[slot].b, stream);
+}
 
 namespace {
 
@@ -162,7 +184,7 @@ struct Run {
   // sketch + chain V_j = R V_{j-1} (fp32 matrix cores, skinny N = padded sketch width)
   int chain(const float* R, int k) {
     const int Sp = P.Sp, ld = P.ld;
-    launch_sketch(v0, Sp, P.S, ld, P.p_s, seed, k, P.fn, s);
+    { ProfScope ps(PK_SKETCH, s); launch_sketch(v0, Sp, P.S, ld, P.p_s, seed, k, P.fn, s); }
     const long long vs = (long long)P.batch * Sp * ld;
     const int tm = (Sp % 128 == 0) ? 128 : 64;
     for (int j = 1; j <= P.nv; ++j) {
@@ -174,7 +196,7 @@ struct Run {
       g.epi = EPI_STORE;
       g.C = v + (j - 1) * vs; g.strideC = (long long)Sp * ld; g.ldc = ld;
       g.ctrl = ctrl;
-      CHECK_LAUNCH(launch_gemm_f32(g, tm, ld, s));
+      { ProfScope ps(PK_CHAIN, s); CHECK_LAUNCH(launch_gemm_f32(g, tm, ld, s)); }
     }
     return PRISM_OK;
   }
@@ -187,7 +209,7 @@ struct Run {
     a.ctrl = ctrl; a.info = info; a.tol = tol; a.max_iters = max_iters;
     a.mode = P.p_s == 0 ? 1 : (k < warm ? 2 : 0);
     a.last = (k == max_iters);
-    launch_solve(a, P.batch, s);
+    { ProfScope ps(PK_SOLVE, s); launch_solve(a, P.batch, s); }
     return check_hip();
   }
   bool fit_needed(int k) const { return P.p_s > 0 && k >= warm && k < max_iters; }
@@ -214,7 +236,7 @@ int run_polar_f32(Run& r) {
     if (k == r.max_iters && r.tol <= 0.0) break;
     GemmDesc g = f32_desc(r, X[cur], Sp, LS, X[cur], Sp, LS, Sp, Sp, Lp, 1);   // G = X^T X
     g.epi = EPI_RESIDUAL; g.C = R; g.strideC = SS; g.ldc = Sp; g.rho_part = r.rho;
-    CHECK_LAUNCH(launch_gemm_f32(g, T, T, r.s));
+    { ProfScope ps(PK_F32_RESID, r.s); CHECK_LAUNCH(launch_gemm_f32(g, T, T, r.s)); }
     if (r.fit_needed(k)) CHECK_LAUNCH(r.chain(R, k));
     CHECK_LAUNCH(r.solve(k, nparts));
     if (k == r.max_iters) break;
@@ -222,13 +244,13 @@ int run_polar_f32(Run& r) {
     if (P.d == 2) {
       GemmDesc q = f32_desc(r, R, Sp, SS, R, Sp, SS, Sp, Sp, Sp, 1);           // R symmetric: R^2 = R^T R
       q.epi = EPI_POLYQ; q.C = Q; q.strideC = SS; q.ldc = Sp; q.Cin = R; q.strideCin = SS; q.ldcin = Sp; q.c1 = 0.5f;
-      CHECK_LAUNCH(launch_gemm_f32(q, T, T, r.s));
+      { ProfScope ps(PK_F32_POLYQ, r.s); CHECK_LAUNCH(launch_gemm_f32(q, T, T, r.s)); }
       Bop = Q;
     }
     GemmDesc a = f32_desc(r, X[cur], Sp, LS, Bop, Sp, SS, Lp, Sp, Sp, 0);      // X + X Q
     a.epi = EPI_AXPY; a.C = X[cur ^ 1]; a.strideC = LS; a.ldc = Sp; a.Cin = X[cur]; a.strideCin = LS; a.ldcin = Sp;
     a.coef_is_alpha = P.d == 1;
-    CHECK_LAUNCH(launch_gemm_f32(a, T, T, r.s));
+    { ProfScope ps(PK_F32_APPLY, r.s); CHECK_LAUNCH(launch_gemm_f32(a, T, T, r.s)); }
     cur ^= 1;
   }
   return PRISM_OK;
@@ -253,7 +275,7 @@ int run_polar_bf16(Run& r) {
     g.M = Sp; g.N = Sp; g.K = Lp; g.batch = P.batch; g.epi = BEPI_GRAM; g.n_true = P.S;
     g.C32 = R; g.strideC32 = SS; g.ldc32 = Sp; g.Cb = Rb; g.strideCb = SS; g.ldcb = Sp;
     g.rho_part = r.rho; g.ctrl = r.ctrl;
-    CHECK_LAUNCH(launch_gemm_bf16(g, T, r.s));
+    { ProfScope ps(PK_BF16_GRAM, r.s); CHECK_LAUNCH(launch_gemm_bf16(g, T, r.s)); }
     if (r.fit_needed(k)) CHECK_LAUNCH(r.chain(R, k));
     CHECK_LAUNCH(r.solve(k, nparts));
     if (k == r.max_iters) break;
@@ -264,7 +286,7 @@ int run_polar_bf16(Run& r) {
       q.M = Sp; q.N = Sp; q.K = Sp; q.batch = P.batch; q.epi = BEPI_POLYQ;
       q.C32 = R; q.strideC32 = SS; q.ldc32 = Sp; q.Cb = Qb; q.strideCb = SS; q.ldcb = Sp; q.c1 = 0.5f;
       q.ctrl = r.ctrl;
-      CHECK_LAUNCH(launch_gemm_bf16(q, T, r.s));
+      { ProfScope ps(PK_BF16_POLYQ, r.s); CHECK_LAUNCH(launch_gemm_bf16(q, T, r.s)); }
       Bop = Qb;
     }
     Bf16Desc a = {};
@@ -273,7 +295,7 @@ int run_polar_bf16(Run& r) {
     a.Cb = Xhi[cur ^ 1]; a.Cb2 = Xlo[cur ^ 1]; a.strideCb = LS; a.ldcb = Sp;
     a.Ct = Xg[cur ^ 1]; a.strideCt = LS; a.ldct = Lp;
     a.Xhi = Xhi[cur]; a.Xlo = Xlo[cur]; a.coef_is_alpha = P.d == 1; a.ctrl = r.ctrl;
-    CHECK_LAUNCH(launch_gemm_bf16(a, T, r.s));
+    { ProfScope ps(PK_BF16_APPLY, r.s); CHECK_LAUNCH(launch_gemm_bf16(a, T, r.s)); }
     cur ^= 1;
   }
   return PRISM_OK;
@@ -293,7 +315,7 @@ int run_sqrt_f32(Run& r) {
     if (k == r.max_iters && r.tol <= 0.0) break;
     GemmDesc g = f32_desc(r, Y[cur], Sp, SS, X[cur], Sp, SS, Sp, Sp, Sp, 0);    // G = Y X
     g.epi = EPI_RESIDUAL; g.C = R; g.strideC = SS; g.ldc = Sp; g.rho_part = r.rho;
-    CHECK_LAUNCH(launch_gemm_f32(g, T, T, r.s));
+    { ProfScope ps(PK_F32_RESID, r.s); CHECK_LAUNCH(launch_gemm_f32(g, T, T, r.s)); }
     if (r.fit_needed(k)) CHECK_LAUNCH(r.chain(R, k));
     CHECK_LAUNCH(r.solve(k, nparts));
     if (k == r.max_iters) break;
@@ -301,17 +323,17 @@ int run_sqrt_f32(Run& r) {
     if (P.d == 2) {
       GemmDesc q = f32_desc(r, R, Sp, SS, R, Sp, SS, Sp, Sp, Sp, 0);
       q.epi = EPI_POLYQ; q.C = Q; q.strideC = SS; q.ldc = Sp; q.Cin = R; q.strideCin = SS; q.ldcin = Sp; q.c1 = 0.5f;
-      CHECK_LAUNCH(launch_gemm_f32(q, T, T, r.s));
+      { ProfScope ps(PK_F32_POLYQ, r.s); CHECK_LAUNCH(launch_gemm_f32(q, T, T, r.s)); }
       Pm = Q;
     }
     GemmDesc ax = f32_desc(r, X[cur], Sp, SS, Pm, Sp, SS, Sp, Sp, Sp, 0);        // X + X Q
     ax.epi = EPI_AXPY; ax.C = X[cur ^ 1]; ax.strideC = SS; ax.ldc = Sp; ax.Cin = X[cur]; ax.strideCin = SS; ax.ldcin = Sp;
     ax.coef_is_alpha = P.d == 1;
-    CHECK_LAUNCH(launch_gemm_f32(ax, T, T, r.s));
+    { ProfScope ps(PK_F32_APPLY, r.s); CHECK_LAUNCH(launch_gemm_f32(ax, T, T, r.s)); }
     GemmDesc ay = f32_desc(r, Pm, Sp, SS, Y[cur], Sp, SS, Sp, Sp, Sp, 0);        // Y + Q Y
     ay.epi = EPI_AXPY; ay.C = Y[cur ^ 1]; ay.strideC = SS; ay.ldc = Sp; ay.Cin = Y[cur]; ay.strideCin = SS; ay.ldcin = Sp;
     ay.coef_is_alpha = P.d == 1;
-    CHECK_LAUNCH(launch_gemm_f32(ay, T, T, r.s));
+    { ProfScope ps(PK_F32_APPLY, r.s); CHECK_LAUNCH(launch_gemm_f32(ay, T, T, r.s)); }
     cur ^= 1;
   }
   return PRISM_OK;
@@ -336,8 +358,8 @@ int run_inv_root_f32(Run& r) {
     GemmDesc ax = f32_desc(r, X[cur], Sp, SS, R, Sp, SS, Sp, Sp, Sp, 0);         // X (I + alpha R)
     ax.epi = EPI_AXPY; ax.C = X[cur ^ 1]; ax.strideC = SS; ax.ldc = Sp; ax.Cin = X[cur]; ax.strideCin = SS; ax.ldcin = Sp;
     ax.coef_is_alpha = 1;
-    CHECK_LAUNCH(launch_gemm_f32(ax, T, T, r.s));
-    launch_make_t(Tm[0], R, r.ctrl, P.batch, Sp, P.S, r.s);                       // T = I + alpha R
+    { ProfScope ps(PK_F32_APPLY, r.s); CHECK_LAUNCH(launch_gemm_f32(ax, T, T, r.s)); }
+    { ProfScope ps(PK_MAKE_T, r.s); launch_make_t(Tm[0], R, r.ctrl, P.batch, Sp, P.S, r.s); }                       // T = I + alpha R
     CHECK_LAUNCH(check_hip());
     // U = T^p by left-to-right binary powering (fp32 products)
     const float* U = Tm[0];
@@ -348,13 +370,13 @@ int run_inv_root_f32(Run& r) {
       float* dst = (U == Tm[1]) ? Tm[2] : Tm[1];
       GemmDesc sq = f32_desc(r, U, Sp, SS, U, Sp, SS, Sp, Sp, Sp, 0);
       sq.epi = EPI_STORE; sq.C = dst; sq.strideC = SS; sq.ldc = Sp;
-      CHECK_LAUNCH(launch_gemm_f32(sq, T, T, r.s));
+      { ProfScope ps(PK_F32_STORE, r.s); CHECK_LAUNCH(launch_gemm_f32(sq, T, T, r.s)); }
       U = dst;
       if ((p >> bit) & 1) {
         float* dst2 = (U == Tm[1]) ? Tm[2] : Tm[1];
         GemmDesc mu = f32_desc(r, U, Sp, SS, Tm[0], Sp, SS, Sp, Sp, Sp, 0);
         mu.epi = EPI_STORE; mu.C = dst2; mu.strideC = SS; mu.ldc = Sp;
-        CHECK_LAUNCH(launch_gemm_f32(mu, T, T, r.s));
+        { ProfScope ps(PK_F32_STORE, r.s); CHECK_LAUNCH(launch_gemm_f32(mu, T, T, r.s)); }
         U = dst2;
       }
     }
@@ -364,7 +386,7 @@ int run_inv_root_f32(Run& r) {
     mn.M = Sp; mn.N = Sp; mn.K = Sp; mn.batch = P.batch; mn.n_true = P.S; mn.ctrl = r.ctrl;
     mn.epi = EPI_MNEXT; mn.C = M[cur ^ 1]; mn.strideC = SS; mn.ldc = Sp;
     mn.R32out = R; mn.strideR = SS; mn.ldr = Sp; mn.rho_part = r.rho;
-    CHECK_LAUNCH(launch_gemm_f64a(mn, 64, 64, r.s));
+    { ProfScope ps(PK_F64_MNEXT, r.s); CHECK_LAUNCH(launch_gemm_f64a(mn, 64, 64, r.s)); }
     cur ^= 1;
   }
   return PRISM_OK;
@@ -416,8 +438,7 @@ int run(int fn, void* a, void* inv_out, int root_p, int batch, int m, int n, int
       fa.Y32[i] = fn == PRISM_FN_SQRT ? r.at<float>(P.o_y[i]) : nullptr;
     }
   }
-  launch_sumsq(pa, r.s);
-  launch_prepare(pa, r.s);
+  { ProfScope ps(PK_PREP, r.s); launch_sumsq(pa, r.s); launch_prepare(pa, r.s); }
   rc = check_hip();
   if (rc != PRISM_OK) return rc;
   if (dt == PRISM_BF16) rc = run_polar_bf16(r);
@@ -425,7 +446,7 @@ int run(int fn, void* a, void* inv_out, int root_p, int batch, int m, int n, int
   else if (fn == PRISM_FN_SQRT) rc = run_sqrt_f32(r);
   else rc = run_inv_root_f32(r);
   if (rc != PRISM_OK) return rc;
-  launch_finalize(fa, r.s);
+  { ProfScope ps(PK_FINAL, r.s); launch_finalize(fa, r.s); }
   return check_hip();
 }
 
@@ -437,6 +458,26 @@ using namespace prism;
 extern "C" {
 
 const char* prism_last_error(void) { return g_last_error.c_str(); }
+
+int prism_profile_enable(int on) {
+  for (auto& r : g_prof) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
+  g_prof.clear();
+  g_prof_on = on != 0;
+  return PRISM_OK;
+}
+
+int prism_profile_collect(double* ms_by_kind, long long* launches_by_kind, int nkinds) {
+  if (!ms_by_kind || !launches_by_kind || nkinds < PK_COUNT) return PRISM_EINVAL;
+  for (int i = 0; i < nkinds; ++i) { ms_by_kind[i] = 0.0; launches_by_kind[i] = 0; }
+  for (auto& r : g_prof) {
+    if (hipEventSynchronize(r.b) != hipSuccess) return PRISM_EHIP;
+    float ms = 0.0f;
+    if (hipEventElapsedTime(&ms, r.a, r.b) != hipSuccess) return PRISM_EHIP;
+    ms_by_kind[r.kind] += ms;
+    launches_by_kind[r.kind] += 1;
+  }
+  return PRISM_OK;
+}
 
 int prism_workspace_bytes(int fn, int batch, int m, int n, prism_dtype dt, int degree, int sketch_dim,
                           int root_p, size_t* out_bytes) {
@@ -514,6 +555,8 @@ int prism_gemm_bf16_nt(const uint16_t* A, const uint16_t* B, float* C, int batch
   g.B = B; g.strideB = (long long)N * K; g.ldb = K;
   g.M = M; g.N = N; g.K = K; g.batch = batch; g.epi = BEPI_STORE;
   g.C32 = C; g.strideC32 = (long long)M * N; g.ldc32 = N;
+  const char* dbg = getenv("PRISM_GEMM_TIMING_EXPERIMENT");   // results are wrong when set: timing only
+  g.dbg = dbg ? atoi(dbg) : 0;
   return launch_gemm_bf16(g, tile, (hipStream_t)stream);
 }
 

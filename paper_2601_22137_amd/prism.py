@@ -24,7 +24,11 @@ INFO_DTYPE = np.dtype([("iters", np.int32), ("status", np.int32),
 
 EXPORTS = ("prism_workspace_bytes", "prism_polar", "prism_polar_ex", "prism_sqrt", "prism_sqrt_ex",
            "prism_inv_root", "prism_inv_root_ex", "prism_sketch", "prism_gauss_parts", "prism_gemm_f32",
-           "prism_gemm_f64a", "prism_gemm_bf16_nt", "prism_last_error")
+           "prism_gemm_f64a", "prism_gemm_bf16_nt", "prism_profile_enable", "prism_profile_collect",
+           "prism_last_error")
+
+PROFILE_KINDS = ("prep", "final", "sketch", "chain", "solve", "f32_resid", "f32_polyq", "f32_apply", "f32_store",
+                 "f64_mnext", "make_t", "bf16_gram", "bf16_polyq", "bf16_apply", "bf16_store")
 
 
 class Options(ctypes.Structure):
@@ -59,6 +63,8 @@ def lib():
         L.prism_gemm_f32.argtypes = [vp, vp, vp, i, i, i, i, i, vp]
         L.prism_gemm_f64a.argtypes = [vp, vp, vp, i, i, i, i, vp]
         L.prism_gemm_bf16_nt.argtypes = [vp, vp, vp, i, i, i, i, i, vp]
+        L.prism_profile_enable.argtypes = [i]
+        L.prism_profile_collect.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_longlong), i]
         _lib = L
     return _lib
 
@@ -182,3 +188,16 @@ def gemm_bf16_nt(A, B, tile):
     C = torch.empty((batch, M, N), dtype=torch.float32, device=A.device)
     _check(lib().prism_gemm_bf16_nt(A.data_ptr(), B.data_ptr(), C.data_ptr(), batch, M, N, K, tile, _stream()))
     return C
+
+
+def profile_enable(on):
+    _check(lib().prism_profile_enable(int(on)))
+
+
+def profile_collect():
+    """{kind: (milliseconds, launches)} summed over everything recorded since profile_enable(True)."""
+    n = len(PROFILE_KINDS)
+    ms = (ctypes.c_double * n)()
+    cnt = (ctypes.c_longlong * n)()
+    _check(lib().prism_profile_collect(ms, cnt, n))
+    return {k: (ms[j], cnt[j]) for j, k in enumerate(PROFILE_KINDS)}

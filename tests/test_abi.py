@@ -1,0 +1,59 @@
+"""The C-ABI library loads and exports every function include/prism.h declares; host-only
+argument checks (no GPU needed: prism_workspace_bytes computes on the host)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    from paper_2601_22137_amd import build, prism
+    if not os.path.exists(prism.LIB_PATH):
+        build.build(verbose=False)
+    return prism.lib()
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "prism.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(prism_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_every_declared_function_is_exported(lib):
+    from paper_2601_22137_amd import prism
+    names = _declared()
+    assert len(names) >= 12
+    for name in names:
+        assert hasattr(lib, name), name
+    assert sorted(prism.EXPORTS) == names
+
+
+def test_workspace_query_and_argument_checks(lib):
+    from paper_2601_22137_amd import prism as P
+    out = ctypes.c_size_t(0)
+    q = lambda *a: lib.prism_workspace_bytes(*a, ctypes.byref(out))
+    assert q(P.FN_POLAR, 8, 4096, 4096, P.BF16, 5, 32, 0) == P.OK
+    per_matrix = 4096 * 4096
+    # six bf16 copies of the iterate (hi/lo/gram layout, double buffered) + R (fp32, bf16) + Q (bf16)
+    assert 8 * per_matrix * (6 * 2 + 4 + 2 + 2) <= out.value <= 8 * per_matrix * 21
+    assert q(P.FN_POLAR, 1, 64, 32, P.F32, 5, 8, 0) == P.OK and out.value > 0
+    assert q(P.FN_POLAR, 0, 64, 32, P.F32, 5, 8, 0) == P.EINVAL
+    assert q(P.FN_POLAR, 1, 64, 32, P.F32, 4, 8, 0) == P.EINVAL
+    assert q(P.FN_POLAR, 1, 64, 32, P.F32, 5, 65, 0) == P.EINVAL
+    assert q(P.FN_POLAR, 1, 64, 32, 7, 5, 8, 0) == P.EINVAL
+    assert q(P.FN_SQRT, 1, 64, 32, P.F32, 5, 8, 0) == P.EINVAL          # square root needs m == n
+    assert q(P.FN_SQRT, 1, 64, 64, P.BF16, 5, 8, 0) == P.EUNSUPPORTED
+    assert q(P.FN_INV_ROOT, 1, 64, 64, P.F32, 3, 8, 0) == P.EINVAL       # root order missing
+    assert q(P.FN_INV_ROOT, 1, 64, 64, P.F32, 5, 8, 4) == P.EINVAL       # the update is linear in R
+    assert q(P.FN_INV_ROOT, 1, 64, 64, P.F32, 3, 8, 9) == P.EINVAL
+    assert q(P.FN_INV_ROOT, 32, 1024, 1024, P.F32, 3, 16, 4) == P.OK
+    assert lib.prism_workspace_bytes(P.FN_POLAR, 1, 8, 8, P.F32, 5, 8, 0, None) == P.EINVAL
+
+
+def test_info_layout_matches_header():
+    from paper_2601_22137_amd import prism as P
+    assert P.INFO_DTYPE.itemsize == 4 + 4 + 4 * 65 + 4 * 64
