@@ -141,11 +141,17 @@ int prism_sketch(float* out, int n, int sketch_dim, uint64_t seed, int k, int fn
 int prism_gauss_parts(uint32_t first, uint32_t count, double* radius, double* cosv, double* sinv,
                       void* stream);
 
+/* One product of the sketch chain (Section 4.2, App. A.1): out[batch][n][ld] = R[batch][n][n] *
+ * V[batch][n][ld], fp32 device arrays, n a multiple of 64, ld = 16, 32 or 64. */
+int prism_chain_product(const float* R, const float* V, float* out, int batch, int n, int ld,
+                        void* stream);
+
 /* C[batch][M][N] = A * B on the matrix cores, no epilogue.  Device pointers.
  *   prism_gemm_f32 : fp32 in/out; a_km != 0 means A is stored [K][M].  B is [K][N].
  *   prism_gemm_f64a: A fp32 (promoted), B and C fp64, A stored [M][K].
  *   prism_gemm_bf16_nt: A [M][K], B [N][K] bf16 bit patterns, C fp32 = A B^T.
- * M, N must be multiples of 128 (bf16: `tile`, 128 or 256) and K of 64. */
+ * M, N must be multiples of 128 (bf16: of `tile`, 128 or 256; fp32 skinny N = 16, 32, 64 also allowed)
+ * and K of 64. */
 int prism_gemm_f32(const float* A, const float* B, float* C, int batch, int M, int N, int K,
                    int a_km, void* stream);
 int prism_gemm_f64a(const float* A, const double* B, double* C, int batch, int M, int N, int K,

@@ -1,0 +1,126 @@
+// Sketch chain V_out = R * V_in (paper Section 4.2 and App. A.1: the products R(R(...(R S^T)))
+// that make the fit cost O(n^2 p_s) instead of O(n^3)).  R is n x n fp32, V is n x p_s with the
+// sketch width padded to ld = 16, 32 or 64 columns.  The product reads R exactly once and is bound
+// by HBM bandwidth, so R never goes through LDS: every lane fetches 16 bytes of its row straight
+// into registers and feeds v_mfma_f32_16x16x4_f32; only the small V is staged in LDS and shared by
+// the four wavefronts of a workgroup.
+//
+//   workgroup = 4 wavefronts = 64 rows of R for one matrix, wave w owns rows 16w..16w+15
+//   K runs in chunks of 64: lane (i = l % 16, q = l / 16) holds R[row i][k0 + 16 s + 4 q + e],
+//   s = 0..3, e = 0..3; MFMA (s, e) pairs it with V[k0 + 16 s + 4 q + e][col] (the order of the
+//   four k of one instruction is free as long as both operands agree).
+//   V chunk in LDS: Vs[64][LD + 4]; with that stride the four lane groups of a fragment read
+//   (rows 4 apart) fall on disjoint bank halves.
+//   The loads of R run two chunks ahead of the MFMAs.
+#include "common.h"
+
+namespace prism {
+namespace {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+constexpr int NT = 256;
+constexpr int KC = 64;     // k per chunk
+constexpr int ROWS = 64;   // rows of R per workgroup
+
+template <int LD>
+__global__ __launch_bounds__(NT) void chain_kernel(const float* __restrict__ R, long long strideR, int ldr,
+                                                   const float* __restrict__ Vin, long long strideVin,
+                                                   float* __restrict__ Vout, long long strideVout, int n,
+                                                   const Ctrl* __restrict__ ctrl) {
+  constexpr int NBLK = LD / 16;
+  constexpr int VS = LD + 4;
+  __shared__ float Vs[2][KC][VS];
+  const int b = blockIdx.y;
+  if (ctrl && ctrl[b].done) return;
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  const int li = lane & 15, lq = lane >> 4;
+  const int row0 = blockIdx.x * ROWS + wave * 16;
+  const float* Rrow = R + (long long)b * strideR + (long long)(row0 + li) * ldr + 4 * lq;
+  const float* Vb = Vin + (long long)b * strideVin;
+
+  // V chunk loader: KC x LD floats = KC * LD / 4 float4, spread over the workgroup
+  constexpr int V_LOADS = KC * LD / 4;
+  constexpr int V_IT = (V_LOADS + NT - 1) / NT;
+  f32x4 vreg[V_IT];
+  auto load_v = [&](int k0) {
+#pragma unroll
+    for (int it = 0; it < V_IT; ++it) {
+      const int idx = t + it * NT;
+      if (V_LOADS % NT == 0 || idx < V_LOADS) {
+        const int kr = idx / (LD / 4), c4 = idx % (LD / 4);
+        vreg[it] = *(const f32x4*)(Vb + (long long)(k0 + kr) * LD + c4 * 4);
+      }
+    }
+  };
+  auto store_v = [&](int buf) {
+#pragma unroll
+    for (int it = 0; it < V_IT; ++it) {
+      const int idx = t + it * NT;
+      if (V_LOADS % NT == 0 || idx < V_LOADS) {
+        const int kr = idx / (LD / 4), c4 = idx % (LD / 4);
+        *(f32x4*)&Vs[buf][kr][c4 * 4] = vreg[it];
+      }
+    }
+  };
+  f32x4 ra[3][4];   // ring of three chunks of this lane's row of R
+  auto load_r = [&](int slot, int k0) {
+#pragma unroll
+    for (int s = 0; s < 4; ++s) ra[slot][s] = *(const f32x4*)(Rrow + k0 + 16 * s);
+  };
+
+  f32x4 acc[NBLK];
+#pragma unroll
+  for (int j = 0; j < NBLK; ++j) acc[j] = (f32x4){0.f, 0.f, 0.f, 0.f};
+
+  const int nchunks = n / KC;
+  load_r(0, 0);
+  if (nchunks > 1) load_r(1, KC);
+  load_v(0);
+  store_v(0);
+  __syncthreads();
+  for (int c = 0; c < nchunks; ++c) {
+    const int cur = c & 1;
+    if (c + 2 < nchunks) {
+      // ring slot (c + 2) % 3, written with compile-time indices
+      if ((c + 2) % 3 == 0) load_r(0, (c + 2) * KC);
+      else if ((c + 2) % 3 == 1) load_r(1, (c + 2) * KC);
+      else load_r(2, (c + 2) * KC);
+    }
+    if (c + 1 < nchunks) load_v((c + 1) * KC);
+    auto compute = [&](const f32x4 (&a)[4]) {
+#pragma unroll
+      for (int s = 0; s < 4; ++s)
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+#pragma unroll
+          for (int j = 0; j < NBLK; ++j)
+            acc[j] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[s][e], Vs[cur][16 * s + 4 * lq + e][j * 16 + li], acc[j], 0, 0, 0);
+    };
+    if (c % 3 == 0) compute(ra[0]);
+    else if (c % 3 == 1) compute(ra[1]);
+    else compute(ra[2]);
+    if (c + 1 < nchunks) store_v(cur ^ 1);
+    __syncthreads();
+  }
+#pragma unroll
+  for (int j = 0; j < NBLK; ++j)
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+      Vout[(long long)b * strideVout + (long long)(row0 + 4 * lq + r) * LD + j * 16 + li] = acc[j][r];
+}
+
+}  // namespace
+
+// R: [batch][n][ldr] fp32 (n a multiple of 64), Vin/Vout: [n][ld] per matrix (strideVin may be 0)
+int launch_chain(const float* R, long long strideR, int ldr, const float* Vin, long long strideVin, float* Vout,
+                 long long strideVout, int n, int ld, int batch, const Ctrl* ctrl, hipStream_t s) {
+  if (n % KC || n % ROWS || ldr % 4 || batch <= 0) return PRISM_EINVAL;
+  const dim3 grid(n / ROWS, batch), block(NT);
+  if (ld == 16) hipLaunchKernelGGL(chain_kernel<16>, grid, block, 0, s, R, strideR, ldr, Vin, strideVin, Vout, strideVout, n, ctrl);
+  else if (ld == 32) hipLaunchKernelGGL(chain_kernel<32>, grid, block, 0, s, R, strideR, ldr, Vin, strideVin, Vout, strideVout, n, ctrl);
+  else if (ld == 64) hipLaunchKernelGGL(chain_kernel<64>, grid, block, 0, s, R, strideR, ldr, Vin, strideVin, Vout, strideVout, n, ctrl);
+  else return PRISM_EINVAL;
+  return hipGetLastError() == hipSuccess ? PRISM_OK : PRISM_EHIP;
+}
+
+}  // namespace prism

@@ -27,8 +27,8 @@ enum EpiKind {
   EPI_STORE = 0,     // C = acc
   EPI_RESIDUAL = 1,  // R = I - acc (masked to n x n), rho partial
   EPI_POLYQ = 2,     // Q = c1 * Rin + alpha * acc
-  EPI_AXPY = 3,      // C = Cin + coef * acc          (coef = 1 or alpha)
-  EPI_MNEXT = 4      // fp64: M' = acc, R32' = I - acc (masked), rho partial
+  EPI_AXPY = 3,      // C = c_in * Cin + Cin2 + coef * acc   (coef = 1 or alpha; Cin2 optional)
+  EPI_MNEXT = 4      // fp64: M' = Cin + acc, R32' = I - M' (masked), rho partial
 };
 
 struct GemmDesc {
@@ -44,6 +44,8 @@ struct GemmDesc {
   const void* Cin; long long strideCin; int ldcin;  // extra input (R for POLYQ, X for AXPY)
   float* R32out; long long strideR; int ldr;     // EPI_MNEXT: fp32 residual out
   float c1;             // POLYQ: coefficient of Rin
+  float c_in;           // AXPY: coefficient of Cin
+  const float* Cin2;    // AXPY: optional second addend, same layout as Cin
   int coef_is_alpha;    // AXPY: multiply acc by ctrl.alpha
   float* rho_part;      // [batch][tiles] partial sums of R^2 (RESIDUAL / MNEXT)
   const Ctrl* ctrl;     // may be null (test entry points)
@@ -86,6 +88,10 @@ void launch_sketch(float* v0, int rows_total, int n, int ld, int p_s, uint64_t s
                    hipStream_t s);
 void launch_gauss_parts(uint32_t first, uint32_t count, double* r, double* c, double* sn,
                         hipStream_t s);
+
+// ---- chain.hip : V_out = R V_in for the sketch chain (HBM bound; R read once, straight into registers) ----
+int launch_chain(const float* R, long long strideR, int ldr, const float* Vin, long long strideVin, float* Vout,
+                 long long strideVout, int n, int ld, int batch, const Ctrl* ctrl, hipStream_t s);
 
 // ---- fit.hip ----
 struct SolveArgs {
@@ -134,8 +140,8 @@ struct FinalArgs {
   const uint16_t* Xa_hi[2]; const uint16_t* Xa_lo[2];
 };
 void launch_finalize(const FinalArgs& a, hipStream_t s);
-// T = I + alpha R (identity masked to n), one matrix per blockIdx.y; skipped when done
-void launch_make_t(float* T, const float* R, const Ctrl* ctrl, int batch, int np, int n, hipStream_t s);
+// E = alpha R, one matrix per blockIdx.y; skipped when done
+void launch_make_e(float* E, const float* R, const Ctrl* ctrl, int batch, int np, hipStream_t s);
 
 void set_last_error(const char* msg);
 

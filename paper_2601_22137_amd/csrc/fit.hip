@@ -100,9 +100,18 @@ __global__ __launch_bounds__(NT) void solve_kernel(SolveArgs a) {
   __shared__ double s_roots[2][MAXC + 2];
   __shared__ int s_nroots[2];
 
+  // residual: sum of the per-tile partials, every thread a strided share, then a fixed tree
+  __shared__ double s_rho[4];
+  {
+    double part = 0.0;
+    for (int i = t; i < a.nparts; i += NT) part += (double)a.rho_part[(long long)b * a.nparts + i];
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) part += __shfl_down(part, off, 64);
+    if ((t & 63) == 0) s_rho[t >> 6] = part;
+    __syncthreads();
+  }
   if (t == 0) {
-    double rho = 0.0;
-    for (int i = 0; i < a.nparts; ++i) rho += (double)a.rho_part[(long long)b * a.nparts + i];
+    const double rho = (s_rho[0] + s_rho[1]) + (s_rho[2] + s_rho[3]);
     const double res = sqrt(rho / (double)a.n);
     info->residual[a.k] = (float)res;
     int status = -1;

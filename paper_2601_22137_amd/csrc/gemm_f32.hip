@@ -60,11 +60,14 @@ __device__ inline TC epilogue(const GemmDesc& g, int b, int i, int j, TC acc, fl
     case EPI_AXPY: {
       const float cin = ((const float*)g.Cin)[(long long)b * g.strideCin + (long long)i * g.ldcin + j];
       const float coef = g.coef_is_alpha ? alpha : 1.0f;
-      ((float*)g.C)[oc] = cin + coef * (float)acc;
+      float v = g.c_in * cin + coef * (float)acc;
+      if (g.Cin2) v += g.Cin2[(long long)b * g.strideCin + (long long)i * g.ldcin + j];
+      ((float*)g.C)[oc] = v;
       return 0;
     }
     case EPI_MNEXT: {
       const bool in = (i < g.n_true && j < g.n_true);
+      if (g.Cin) acc += ((const TC*)g.Cin)[(long long)b * g.strideCin + (long long)i * g.ldcin + j];
       const TC mval = in ? acc : (TC)0;
       ((TC*)g.C)[oc] = mval;
       const TC r = in ? ((i == j ? (TC)1 : (TC)0) - acc) : (TC)0;
@@ -167,6 +170,17 @@ __global__ __launch_bounds__(NT) void gemm_kernel(GemmDesc g) {
 #pragma unroll
     for (int j = 0; j < BN; ++j) acc[i][j] = (typename Acc<TC>::type){0, 0, 0, 0};
 
+  // Long fp32 sums are accumulated in two levels (partial sums of 256 terms inside the matrix
+  // core accumulator, then added up in registers): the rounding error then grows like the square
+  // root of the chunk length instead of that of K, which the 1e-5 parity bar needs at K = 8192.
+  constexpr bool FLUSH = sizeof(TC) == 4 && BM * BN <= 16;
+  typename Acc<TC>::type ksum[FLUSH ? BM : 1][FLUSH ? BN : 1];
+  if (FLUSH) {
+#pragma unroll
+    for (int i = 0; i < BM; ++i)
+#pragma unroll
+      for (int j = 0; j < BN; ++j) ksum[i][j] = (typename Acc<TC>::type){0, 0, 0, 0};
+  }
   const int KT = g.K / BK;
   load_slab(0);
   store_slab(0);
@@ -189,6 +203,21 @@ __global__ __launch_bounds__(NT) void gemm_kernel(GemmDesc g) {
     }
     if (kt + 1 < KT) store_slab(cur ^ 1);
     __syncthreads();
+    if (FLUSH && (kt & 15) == 15) {   // fp32: close a partial sum every 256 k
+#pragma unroll
+      for (int i = 0; i < BM; ++i)
+#pragma unroll
+        for (int j = 0; j < BN; ++j) {
+          ksum[i][j] += acc[i][j];
+          acc[i][j] = (typename Acc<TC>::type){0, 0, 0, 0};
+        }
+    }
+  }
+  if (FLUSH) {
+#pragma unroll
+    for (int i = 0; i < BM; ++i)
+#pragma unroll
+      for (int j = 0; j < BN; ++j) acc[i][j] += ksum[i][j];
   }
 
   TC part = 0;

@@ -161,23 +161,21 @@ __global__ __launch_bounds__(NT) void finalize_kernel(FinalArgs a) {
   }
 }
 
-__global__ __launch_bounds__(NT) void make_t_kernel(float* T, const float* R, const Ctrl* ctrl, int np, int n) {
+__global__ __launch_bounds__(NT) void make_e_kernel(float* E, const float* R, const Ctrl* ctrl, int np) {
   const int b = blockIdx.y;
   if (ctrl[b].done) return;
   const float alpha = ctrl[b].alpha;
   const long long total = (long long)np * np;
   const long long i = (long long)blockIdx.x * NT + threadIdx.x;
   if (i >= total) return;
-  const int r = (int)(i / np), c = (int)(i % np);
-  const float eye = (r == c && r < n) ? 1.0f : 0.0f;
-  T[(long long)b * total + i] = eye + alpha * R[(long long)b * total + i];
+  E[(long long)b * total + i] = alpha * R[(long long)b * total + i];
 }
 
 }  // namespace
 
-void launch_make_t(float* T, const float* R, const Ctrl* ctrl, int batch, int np, int n, hipStream_t s) {
+void launch_make_e(float* E, const float* R, const Ctrl* ctrl, int batch, int np, hipStream_t s) {
   const long long total = (long long)np * np;
-  hipLaunchKernelGGL(make_t_kernel, dim3((unsigned)((total + NT - 1) / NT), batch), dim3(NT), 0, s, T, R, ctrl, np, n);
+  hipLaunchKernelGGL(make_e_kernel, dim3((unsigned)((total + NT - 1) / NT), batch), dim3(NT), 0, s, E, R, ctrl, np);
 }
 
 void launch_sumsq(const PrepArgs& a, hipStream_t s) {

@@ -186,17 +186,12 @@ struct Run {
     const int Sp = P.Sp, ld = P.ld;
     { ProfScope ps(PK_SKETCH, s); launch_sketch(v0, Sp, P.S, ld, P.p_s, seed, k, P.fn, s); }
     const long long vs = (long long)P.batch * Sp * ld;
-    const int tm = (Sp % 128 == 0) ? 128 : 64;
     for (int j = 1; j <= P.nv; ++j) {
-      GemmDesc g = {};
-      g.A = R; g.strideA = (long long)Sp * Sp; g.lda = Sp;
-      if (j == 1) { g.B = v0; g.strideB = 0; } else { g.B = v + (j - 2) * vs; g.strideB = (long long)Sp * ld; }
-      g.ldb = ld;
-      g.M = Sp; g.N = ld; g.K = Sp; g.a_km = 0; g.batch = P.batch;
-      g.epi = EPI_STORE;
-      g.C = v + (j - 1) * vs; g.strideC = (long long)Sp * ld; g.ldc = ld;
-      g.ctrl = ctrl;
-      { ProfScope ps(PK_CHAIN, s); CHECK_LAUNCH(launch_gemm_f32(g, tm, ld, s)); }
+      const float* vin = (j == 1) ? v0 : v + (j - 2) * vs;
+      const long long sin = (j == 1) ? 0 : (long long)Sp * ld;
+      ProfScope ps(PK_CHAIN, s);
+      CHECK_LAUNCH(launch_chain(R, (long long)Sp * Sp, Sp, vin, sin, v + (j - 1) * vs, (long long)Sp * ld, Sp, ld,
+                                P.batch, ctrl, s));
     }
     return PRISM_OK;
   }
@@ -220,6 +215,7 @@ GemmDesc f32_desc(const Run& r, const float* A, int lda, long long sa, const flo
   GemmDesc g = {};
   g.A = A; g.strideA = sa; g.lda = lda; g.B = B; g.strideB = sb; g.ldb = ldb;
   g.M = M; g.N = N; g.K = K; g.a_km = a_km; g.batch = r.P.batch; g.n_true = r.P.S; g.ctrl = r.ctrl;
+  g.c_in = 1.0f;
   return g;
 }
 
@@ -359,32 +355,33 @@ int run_inv_root_f32(Run& r) {
     ax.epi = EPI_AXPY; ax.C = X[cur ^ 1]; ax.strideC = SS; ax.ldc = Sp; ax.Cin = X[cur]; ax.strideCin = SS; ax.ldcin = Sp;
     ax.coef_is_alpha = 1;
     { ProfScope ps(PK_F32_APPLY, r.s); CHECK_LAUNCH(launch_gemm_f32(ax, T, T, r.s)); }
-    { ProfScope ps(PK_MAKE_T, r.s); launch_make_t(Tm[0], R, r.ctrl, P.batch, Sp, P.S, r.s); }                       // T = I + alpha R
+    // (I + alpha R)^p = I + E_p, built on the part beyond the identity so that fp32 rounding acts
+    // on the small quantity only: E_1 = alpha R, squaring E <- 2E + E E, times T: E <- E + E_1 + E E_1
+    { ProfScope ps(PK_MAKE_T, r.s); launch_make_e(Tm[0], R, r.ctrl, P.batch, Sp, r.s); }
     CHECK_LAUNCH(check_hip());
-    // U = T^p by left-to-right binary powering (fp32 products)
     const float* U = Tm[0];
     int hb = 0;
     while ((p >> (hb + 1)) != 0) ++hb;
-    int pp = 1;
     for (int bit = hb - 1; bit >= 0; --bit) {
       float* dst = (U == Tm[1]) ? Tm[2] : Tm[1];
       GemmDesc sq = f32_desc(r, U, Sp, SS, U, Sp, SS, Sp, Sp, Sp, 0);
-      sq.epi = EPI_STORE; sq.C = dst; sq.strideC = SS; sq.ldc = Sp;
+      sq.epi = EPI_AXPY; sq.C = dst; sq.strideC = SS; sq.ldc = Sp; sq.Cin = U; sq.strideCin = SS; sq.ldcin = Sp; sq.c_in = 2.0f;
       { ProfScope ps(PK_F32_STORE, r.s); CHECK_LAUNCH(launch_gemm_f32(sq, T, T, r.s)); }
       U = dst;
       if ((p >> bit) & 1) {
         float* dst2 = (U == Tm[1]) ? Tm[2] : Tm[1];
         GemmDesc mu = f32_desc(r, U, Sp, SS, Tm[0], Sp, SS, Sp, Sp, Sp, 0);
-        mu.epi = EPI_STORE; mu.C = dst2; mu.strideC = SS; mu.ldc = Sp;
+        mu.epi = EPI_AXPY; mu.C = dst2; mu.strideC = SS; mu.ldc = Sp; mu.Cin = U; mu.strideCin = SS; mu.ldcin = Sp; mu.c_in = 1.0f;
+        mu.Cin2 = Tm[0];
         { ProfScope ps(PK_F32_STORE, r.s); CHECK_LAUNCH(launch_gemm_f32(mu, T, T, r.s)); }
         U = dst2;
       }
     }
-    (void)pp;
-    GemmDesc mn = {};                                                             // M' = T^p M in fp64
+    GemmDesc mn = {};                                                             // M' = M + E_p M in fp64
     mn.A = U; mn.strideA = SS; mn.lda = Sp; mn.B = M[cur]; mn.strideB = SS; mn.ldb = Sp;
     mn.M = Sp; mn.N = Sp; mn.K = Sp; mn.batch = P.batch; mn.n_true = P.S; mn.ctrl = r.ctrl;
     mn.epi = EPI_MNEXT; mn.C = M[cur ^ 1]; mn.strideC = SS; mn.ldc = Sp;
+    mn.Cin = M[cur]; mn.strideCin = SS; mn.ldcin = Sp;
     mn.R32out = R; mn.strideR = SS; mn.ldr = Sp; mn.rho_part = r.rho;
     { ProfScope ps(PK_F64_MNEXT, r.s); CHECK_LAUNCH(launch_gemm_f64a(mn, 64, 64, r.s)); }
     cur ^= 1;
@@ -524,6 +521,12 @@ int prism_gauss_parts(uint32_t first, uint32_t count, double* radius, double* co
   if (!radius || !cosv || !sinv || count == 0 || (uint64_t)first + count > (1ull << 24)) return PRISM_EINVAL;
   launch_gauss_parts(first, count, radius, cosv, sinv, (hipStream_t)stream);
   return check_hip();
+}
+
+int prism_chain_product(const float* R, const float* V, float* out, int batch, int n, int ld, void* stream) {
+  if (!R || !V || !out || batch <= 0 || n <= 0) return PRISM_EINVAL;
+  return launch_chain(R, (long long)n * n, n, V, (long long)n * ld, out, (long long)n * ld, n, ld, batch, nullptr,
+                      (hipStream_t)stream);
 }
 
 int prism_gemm_f32(const float* A, const float* B, float* C, int batch, int M, int N, int K, int a_km, void* stream) {

@@ -23,7 +23,7 @@ INFO_DTYPE = np.dtype([("iters", np.int32), ("status", np.int32),
                        ("residual", np.float32, (MAX_ITERS + 1,)), ("alpha", np.float32, (MAX_ITERS,))])
 
 EXPORTS = ("prism_workspace_bytes", "prism_polar", "prism_polar_ex", "prism_sqrt", "prism_sqrt_ex",
-           "prism_inv_root", "prism_inv_root_ex", "prism_sketch", "prism_gauss_parts", "prism_gemm_f32",
+           "prism_inv_root", "prism_inv_root_ex", "prism_sketch", "prism_gauss_parts", "prism_chain_product", "prism_gemm_f32",
            "prism_gemm_f64a", "prism_gemm_bf16_nt", "prism_profile_enable", "prism_profile_collect",
            "prism_last_error")
 
@@ -60,6 +60,7 @@ def lib():
         L.prism_inv_root_ex.argtypes = L.prism_inv_root.argtypes + [ctypes.POINTER(Options)]
         L.prism_sketch.argtypes = [vp, i, i, u64, i, i, vp]
         L.prism_gauss_parts.argtypes = [ctypes.c_uint32, ctypes.c_uint32, vp, vp, vp, vp]
+        L.prism_chain_product.argtypes = [vp, vp, vp, i, i, i, vp]
         L.prism_gemm_f32.argtypes = [vp, vp, vp, i, i, i, i, i, vp]
         L.prism_gemm_f64a.argtypes = [vp, vp, vp, i, i, i, i, vp]
         L.prism_gemm_bf16_nt.argtypes = [vp, vp, vp, i, i, i, i, i, vp]
@@ -163,6 +164,13 @@ def gauss_parts(first, count, device="cuda"):
     s = torch.empty_like(r)
     _check(lib().prism_gauss_parts(first, count, r.data_ptr(), c.data_ptr(), s.data_ptr(), _stream()))
     return r, c, s
+
+
+def chain_product(R, V):
+    batch, n, ld = V.shape
+    out = torch.empty_like(V)
+    _check(lib().prism_chain_product(R.data_ptr(), V.data_ptr(), out.data_ptr(), batch, n, ld, _stream()))
+    return out
 
 
 def gemm_f32(A, B, a_km=False):

@@ -2,7 +2,7 @@
 
 Calls ONLY the CPU oracle (oracle/) and the seeded input generators; nothing here touches the
 HIP path.  For matrix 0 of the batch it stores the oracle's iteration count, residual and alpha
-histories, the Frobenius norm of the result and the result at 4096 seeded sample positions.
+histories, the Frobenius norm of the result and the result at seeded sample positions.
 
     python tests/golden/make_full_size_golden.py c3     (about 3 minutes on 8 cores)
     python tests/golden/make_full_size_golden.py c5     (about 15 minutes on 8 cores)
@@ -20,11 +20,16 @@ from oracle import prism_ref as O                      # noqa: E402
 from paper_2601_22137_amd import workloads as W        # noqa: E402
 
 N_SAMPLES = 4096
+N_DIAG = 512
 
 
 def sample_positions(n_rows, n_cols, seed=7):
+    """4096 random positions followed by 512 evenly spaced diagonal positions (the square roots of
+    SPD matrices are diagonally dominant, so the diagonal is sampled separately)."""
     rng = np.random.Generator(np.random.PCG64(seed))
-    return rng.integers(0, n_rows, N_SAMPLES), rng.integers(0, n_cols, N_SAMPLES)
+    r, c = rng.integers(0, n_rows, N_SAMPLES), rng.integers(0, n_cols, N_SAMPLES)
+    d = (np.arange(N_DIAG) * (min(n_rows, n_cols) // N_DIAG)).astype(np.int64)
+    return np.concatenate([r, d]), np.concatenate([c, d])
 
 
 def write(path, header, info, outputs):

@@ -33,6 +33,17 @@ def test_gemm_f32(prism, a_km, shape):
     assert np.linalg.norm(C - ref) / np.linalg.norm(ref) < 1e-6
 
 
+@pytest.mark.parametrize("n,ld", [(64, 16), (192, 32), (768, 16), (1024, 64), (4096, 32)])
+def test_chain_product(prism, n, ld):
+    rng = np.random.default_rng(n + ld)
+    R = (rng.standard_normal((2, n, n)) / np.sqrt(n)).astype(np.float32)
+    V = rng.standard_normal((2, n, ld)).astype(np.float32)
+    out = prism.chain_product(_dev(R), _dev(V)).cpu().numpy()
+    ref = R.astype(np.float64) @ V.astype(np.float64)
+    err = np.linalg.norm(out - ref) / np.linalg.norm(ref)
+    assert err < 2e-7 * np.sqrt(n), err       # fp32 accumulation over n terms
+
+
 def test_gemm_f64a(prism):
     rng = np.random.default_rng(7)
     A = rng.standard_normal((2, 128, 96)).astype(np.float32)
