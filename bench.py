@@ -31,6 +31,8 @@ def parse():
     ap.add_argument("--batch", type=int, default=0, help="override the batch size (c3/c4/c5)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
     ap.add_argument("--no-profile", action="store_true", help="skip the per-kernel event pass")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="only copy 1 GiB device to device three times (calibrates the FETCH_SIZE / WRITE_SIZE counters)")
     return ap.parse_args()
 
 
@@ -116,6 +118,14 @@ def main():
               file=sys.stderr)
         sys.exit(2)
     import torch
+    if args.copy_probe:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")     # 1 GiB
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_probe_bytes": src.numel() * 4, "copies": 3}))
+        return
     from paper_2601_22137_amd import prism, workloads as W
     prism.lib()
     assert torch.cuda.is_available(), "bench.py needs a GPU"

@@ -11,7 +11,7 @@
 //   four k of one instruction is free as long as both operands agree).
 //   V chunk in LDS: Vs[64][LD + 4]; with that stride the four lane groups of a fragment read
 //   (rows 4 apart) fall on disjoint bank halves.
-//   The loads of R run two chunks ahead of the MFMAs.
+//   The loads of R run five chunks ahead of the MFMAs (the kernel is latency bound otherwise).
 #include "common.h"
 
 namespace prism {
@@ -62,45 +62,54 @@ __global__ __launch_bounds__(NT) void chain_kernel(const float* __restrict__ R, 
       }
     }
   };
-  f32x4 ra[3][4];   // ring of three chunks of this lane's row of R
-  auto load_r = [&](int slot, int k0) {
+  constexpr int DEPTH = 6;   // ring of chunks of this lane's row of R: loads run DEPTH-1 chunks ahead
+  f32x4 ra[DEPTH][4];
+  const int nchunks = n / KC;
+  auto load_r = [&](int slot, int c) {   // slot is a compile-time constant at every call site
+    if (c < nchunks) {
 #pragma unroll
-    for (int s = 0; s < 4; ++s) ra[slot][s] = *(const f32x4*)(Rrow + k0 + 16 * s);
+      for (int s = 0; s < 4; ++s) ra[slot][s] = *(const f32x4*)(Rrow + c * KC + 16 * s);
+    }
   };
 
   f32x4 acc[NBLK];
 #pragma unroll
   for (int j = 0; j < NBLK; ++j) acc[j] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
-  const int nchunks = n / KC;
-  load_r(0, 0);
-  if (nchunks > 1) load_r(1, KC);
+  // Workgroup barrier without the release fence of __syncthreads(): that fence waits for every
+  // outstanding load and would expose the memory latency of the prefetched rows of R at every
+  // chunk.  LDS traffic of this wave is complete (lgkmcnt(0)); loads into registers stay in flight.
+  auto lds_barrier = [&]() {
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+  };
   load_v(0);
+#pragma unroll
+  for (int d = 0; d < DEPTH - 1; ++d) load_r(d, d);
   store_v(0);
-  __syncthreads();
-  for (int c = 0; c < nchunks; ++c) {
-    const int cur = c & 1;
-    if (c + 2 < nchunks) {
-      // ring slot (c + 2) % 3, written with compile-time indices
-      if ((c + 2) % 3 == 0) load_r(0, (c + 2) * KC);
-      else if ((c + 2) % 3 == 1) load_r(1, (c + 2) * KC);
-      else load_r(2, (c + 2) * KC);
+  lds_barrier();
+  for (int c0 = 0; c0 < nchunks; c0 += DEPTH) {
+#pragma unroll
+    for (int d = 0; d < DEPTH; ++d) {
+      const int c = c0 + d;
+      if (c < nchunks) {          // uniform
+        const int cur = c & 1;
+        // the small V chunk is requested before the rows of R further ahead, so that waiting for
+        // it (to stage it in LDS) leaves those rows in flight
+        if (c + 1 < nchunks) load_v((c + 1) * KC);
+        load_r((d + DEPTH - 1) % DEPTH, c + DEPTH - 1);
+#pragma unroll
+        for (int s = 0; s < 4; ++s)
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+#pragma unroll
+            for (int j = 0; j < NBLK; ++j)
+              acc[j] = __builtin_amdgcn_mfma_f32_16x16x4f32(ra[d][s][e], Vs[cur][16 * s + 4 * lq + e][j * 16 + li], acc[j], 0, 0, 0);
+        if (c + 1 < nchunks) store_v(cur ^ 1);
+        lds_barrier();
+      }
     }
-    if (c + 1 < nchunks) load_v((c + 1) * KC);
-    auto compute = [&](const f32x4 (&a)[4]) {
-#pragma unroll
-      for (int s = 0; s < 4; ++s)
-#pragma unroll
-        for (int e = 0; e < 4; ++e)
-#pragma unroll
-          for (int j = 0; j < NBLK; ++j)
-            acc[j] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[s][e], Vs[cur][16 * s + 4 * lq + e][j * 16 + li], acc[j], 0, 0, 0);
-    };
-    if (c % 3 == 0) compute(ra[0]);
-    else if (c % 3 == 1) compute(ra[1]);
-    else compute(ra[2]);
-    if (c + 1 < nchunks) store_v(cur ^ 1);
-    __syncthreads();
   }
 #pragma unroll
   for (int j = 0; j < NBLK; ++j)

@@ -112,7 +112,10 @@ struct SolveArgs {
   int max_iters;
   int mode;          // 0 fit, 1 alpha = l (no sketch), 2 alpha = u (warm start)
   int last;          // this is the residual-only evaluation at k = max_iters
+  double* cpart;     // [batch][ngroups][17] partial coefficient sums (moments -> solve)
+  int ngroups;
 };
+void launch_moments(const SolveArgs& a, int batch, hipStream_t s);
 void launch_solve(const SolveArgs& a, int batch, hipStream_t s);
 
 // ---- misc.hip ----

@@ -1,10 +1,12 @@
 // The per-iteration coefficient fit of PRISM (paper Section 4.2, eq. (4); App. A.1 and A.3)
-// after the sketch chain V_j = R V_{j-1} has been formed: one workgroup per matrix
-//   1. sums the residual partials, applies the stop rule and records the residual;
-//   2. forms the blocks W_i = u_i(R) S^T from the chain (the factor (1 - xi) = G = I - R is
-//      applied as V_j - V_{j+1}) and accumulates the coefficients
+// after the sketch chain V_j = R V_{j-1} has been formed:
+//   moments_kernel (a few workgroups per matrix) forms the blocks W_i = u_i(R) S^T from the chain
+//      (the factor (1 - xi) = G = I - R is applied as V_j - V_{j+1}) and accumulates
 //         c_s = sum_{i+l=s} <W_i, W_l>,  m(alpha) = || sum_i alpha^i W_i ||_F^2,
-//      in fp64, reduced in a fixed order (results are run-to-run identical);
+//      in fp64 with a fixed reduction order (results are run-to-run identical);
+//   solve_kernel (one workgroup per matrix)
+//   1. sums the residual partials, applies the stop rule and records the residual;
+//   2. adds up the coefficient partials;
 //   3. minimises m over [l, u]: all real roots of m' in the interval are bracketed between the
 //      roots of m'' (recursively down to the linear derivative) and found by bisection, then m
 //      is compared at the end points and those roots; the smallest alpha wins ties.
@@ -55,14 +57,14 @@ template <int P> struct BlocksInv {
 };
 
 template <class BL>
-__device__ void accumulate_coefficients(const SolveArgs& a, int b, double* c_out /* shared, MAXC */) {
+__device__ void accumulate_coefficients(const SolveArgs& a, int b, int grp, int ngrp, double* c_out /* global, MAXC */) {
   constexpr int NV = BL::NV, NW = BL::NW, NC = 2 * NW - 1;
   double c[NC];
 #pragma unroll
   for (int s = 0; s < NC; ++s) c[s] = 0.0;
   const long long total = (long long)a.rows * a.ld;
   const float* base = a.V + (long long)b * a.bstride;
-  for (long long idx = threadIdx.x; idx < total; idx += NT) {
+  for (long long idx = (long long)grp * NT + threadIdx.x; idx < total; idx += (long long)ngrp * NT) {
     double v[NV], w[NW];
 #pragma unroll
     for (int j = 0; j < NV; ++j) v[j] = (double)base[(long long)j * a.vstride + idx];
@@ -86,7 +88,29 @@ __device__ void accumulate_coefficients(const SolveArgs& a, int b, double* c_out
     const int s = threadIdx.x;
     c_out[s] = (s < NC) ? (red[0][s] + red[1][s] + red[2][s] + red[3][s]) : 0.0;
   }
-  __syncthreads();
+}
+
+// grid (groups, batch): partial coefficient sums of one matrix, groups interleaved over the elements
+__global__ __launch_bounds__(NT) void moments_kernel(SolveArgs a) {
+  const int b = blockIdx.y, grp = blockIdx.x, ngrp = gridDim.x;
+  if (a.ctrl[b].done) return;
+  double* out = a.cpart + ((long long)b * ngrp + grp) * MAXC;
+  if (a.fn == PRISM_FN_INV_ROOT) {
+    switch (a.p) {
+      case 1: accumulate_coefficients<BlocksInv<1>>(a, b, grp, ngrp, out); break;
+      case 2: accumulate_coefficients<BlocksInv<2>>(a, b, grp, ngrp, out); break;
+      case 3: accumulate_coefficients<BlocksInv<3>>(a, b, grp, ngrp, out); break;
+      case 4: accumulate_coefficients<BlocksInv<4>>(a, b, grp, ngrp, out); break;
+      case 5: accumulate_coefficients<BlocksInv<5>>(a, b, grp, ngrp, out); break;
+      case 6: accumulate_coefficients<BlocksInv<6>>(a, b, grp, ngrp, out); break;
+      case 7: accumulate_coefficients<BlocksInv<7>>(a, b, grp, ngrp, out); break;
+      default: accumulate_coefficients<BlocksInv<8>>(a, b, grp, ngrp, out); break;
+    }
+  } else if (a.d == 1) {
+    accumulate_coefficients<Blocks<1>>(a, b, grp, ngrp, out);
+  } else {
+    accumulate_coefficients<Blocks<2>>(a, b, grp, ngrp, out);
+  }
 }
 
 __global__ __launch_bounds__(NT) void solve_kernel(SolveArgs a) {
@@ -153,24 +177,13 @@ __global__ __launch_bounds__(NT) void solve_kernel(SolveArgs a) {
     return;
   }
 
-  int nc = 5;
-  if (a.fn == PRISM_FN_INV_ROOT) {
-    nc = 2 * a.p + 1;
-    switch (a.p) {
-      case 1: accumulate_coefficients<BlocksInv<1>>(a, b, s_c); break;
-      case 2: accumulate_coefficients<BlocksInv<2>>(a, b, s_c); break;
-      case 3: accumulate_coefficients<BlocksInv<3>>(a, b, s_c); break;
-      case 4: accumulate_coefficients<BlocksInv<4>>(a, b, s_c); break;
-      case 5: accumulate_coefficients<BlocksInv<5>>(a, b, s_c); break;
-      case 6: accumulate_coefficients<BlocksInv<6>>(a, b, s_c); break;
-      case 7: accumulate_coefficients<BlocksInv<7>>(a, b, s_c); break;
-      default: accumulate_coefficients<BlocksInv<8>>(a, b, s_c); break;
-    }
-  } else if (a.d == 1) {
-    accumulate_coefficients<Blocks<1>>(a, b, s_c);
-  } else {
-    accumulate_coefficients<Blocks<2>>(a, b, s_c);
+  const int nc = (a.fn == PRISM_FN_INV_ROOT) ? 2 * a.p + 1 : 5;
+  if (t < MAXC) {   // coefficient s = sum of the group partials, in group order
+    double v = 0.0;
+    for (int gidx = 0; gidx < a.ngroups; ++gidx) v += a.cpart[((long long)b * a.ngroups + gidx) * MAXC + t];
+    s_c[t] = v;
   }
+  __syncthreads();
 
   // ---- minimise m(alpha) = sum_s c_s alpha^s on [lo, hi] ----
   const int deg = nc - 1;   // degree of m
@@ -260,6 +273,10 @@ __global__ __launch_bounds__(NT) void solve_kernel(SolveArgs a) {
 }
 
 }  // namespace
+
+void launch_moments(const SolveArgs& a, int batch, hipStream_t s) {
+  hipLaunchKernelGGL(moments_kernel, dim3(a.ngroups, batch), dim3(NT), 0, s, a);
+}
 
 void launch_solve(const SolveArgs& a, int batch, hipStream_t s) {
   hipLaunchKernelGGL(solve_kernel, dim3(batch), dim3(NT), 0, s, a);

@@ -51,7 +51,8 @@ struct Plan {
   int nsum;        // partial sums of the Frobenius norm per matrix
   int max_parts;   // residual partials per matrix
   // byte offsets into the workspace
-  size_t o_ctrl, o_info, o_sumsq, o_rho, o_v0, o_v;
+  size_t o_ctrl, o_info, o_sumsq, o_rho, o_v0, o_v, o_cpart;
+  int ngroups;     // workgroups per matrix of the moments kernel
   size_t o_x[2], o_y[2], o_r, o_q, o_t[3];        // fp32 paths (o_y doubles as M64 for inverse root)
   size_t o_xhi[2], o_xlo[2], o_xg[2], o_rb, o_qb; // bf16 polar
   size_t total;
@@ -80,8 +81,7 @@ int make_plan(Plan& P, int fn, int batch, int m, int n, int dt, int degree, int 
   P.nv = fn == PRISM_FN_INV_ROOT ? root_p + 1 : 2 * P.d + 1;
   P.split = (dt == PRISM_BF16) && !(flags & PRISM_FLAG_BF16_PLAIN_ITERATE);
   if (dt == PRISM_BF16) {
-    const int s256 = round_up(P.S, 256);
-    P.tile = ((long long)batch * (s256 / 256) * (s256 / 256) >= 512) ? 256 : 128;
+    P.tile = P.S >= 512 ? 256 : 128;   // padding granularity; the tile is chosen per launch
   } else {
     P.tile = P.S <= 256 ? 64 : 128;
   }
@@ -99,6 +99,11 @@ int make_plan(Plan& P, int fn, int batch, int m, int n, int dt, int degree, int 
   P.o_rho = take(B * P.max_parts * sizeof(float));
   P.o_v0 = take((size_t)P.Sp * P.ld * sizeof(float));
   P.o_v = take((size_t)P.nv * B * P.Sp * P.ld * sizeof(float));
+  {
+    const long long el = (long long)P.Sp * P.ld;
+    P.ngroups = (int)(el / (256 * 16) < 1 ? 1 : (el / (256 * 16) > 64 ? 64 : el / (256 * 16)));
+  }
+  P.o_cpart = take(B * P.ngroups * 17 * sizeof(double));
   if (dt == PRISM_BF16) {
     for (int i = 0; i < 2; ++i) {
       P.o_xhi[i] = take(B * LS * 2);
@@ -204,7 +209,8 @@ struct Run {
     a.ctrl = ctrl; a.info = info; a.tol = tol; a.max_iters = max_iters;
     a.mode = P.p_s == 0 ? 1 : (k < warm ? 2 : 0);
     a.last = (k == max_iters);
-    { ProfScope ps(PK_SOLVE, s); launch_solve(a, P.batch, s); }
+    a.cpart = at<double>(P.o_cpart); a.ngroups = P.ngroups;
+    { ProfScope ps(PK_SOLVE, s); if (a.mode == 0 && !a.last) launch_moments(a, P.batch, s); launch_solve(a, P.batch, s); }
     return check_hip();
   }
   bool fit_needed(int k) const { return P.p_s > 0 && k >= warm && k < max_iters; }
@@ -252,9 +258,18 @@ int run_polar_f32(Run& r) {
   return PRISM_OK;
 }
 
+// 256 x 256 tiles when they still give every CU work, else 128 x 128
+int bf16_tile(const Plan& P, int M, int N) {
+  static const int forced = getenv("PRISM_BF16_TILE") ? atoi(getenv("PRISM_BF16_TILE")) : 0;
+  if (P.tile != 256) return 128;
+  if (forced == 128 || forced == 256) return forced;
+  return ((long long)(M / 256) * (N / 256) * P.batch >= 192) ? 256 : 128;
+}
+
 int run_polar_bf16(Run& r) {
   const Plan& P = r.P;
-  const int Sp = P.Sp, Lp = P.Lp, T = P.tile;
+  const int Sp = P.Sp, Lp = P.Lp;
+  const int Tg = bf16_tile(P, Sp, Sp), Ta = bf16_tile(P, Lp, Sp);
   const long long SS = (long long)Sp * Sp, LS = (long long)Lp * Sp;
   uint16_t* Xhi[2] = {r.at<uint16_t>(P.o_xhi[0]), r.at<uint16_t>(P.o_xhi[1])};
   uint16_t* Xlo[2] = {P.split ? r.at<uint16_t>(P.o_xlo[0]) : nullptr, P.split ? r.at<uint16_t>(P.o_xlo[1]) : nullptr};
@@ -262,7 +277,7 @@ int run_polar_bf16(Run& r) {
   float* R = r.at<float>(P.o_r);
   uint16_t* Rb = r.at<uint16_t>(P.o_rb);
   uint16_t* Qb = P.d == 2 ? r.at<uint16_t>(P.o_qb) : nullptr;
-  const int nparts = (Sp / T) * (Sp / T);
+  const int nparts = (Sp / Tg) * (Sp / Tg);
   int cur = 0;
   for (int k = 0; k <= r.max_iters; ++k) {
     if (k == r.max_iters && r.tol <= 0.0) break;
@@ -271,7 +286,7 @@ int run_polar_bf16(Run& r) {
     g.M = Sp; g.N = Sp; g.K = Lp; g.batch = P.batch; g.epi = BEPI_GRAM; g.n_true = P.S;
     g.C32 = R; g.strideC32 = SS; g.ldc32 = Sp; g.Cb = Rb; g.strideCb = SS; g.ldcb = Sp;
     g.rho_part = r.rho; g.ctrl = r.ctrl;
-    { ProfScope ps(PK_BF16_GRAM, r.s); CHECK_LAUNCH(launch_gemm_bf16(g, T, r.s)); }
+    { ProfScope ps(PK_BF16_GRAM, r.s); CHECK_LAUNCH(launch_gemm_bf16(g, Tg, r.s)); }
     if (r.fit_needed(k)) CHECK_LAUNCH(r.chain(R, k));
     CHECK_LAUNCH(r.solve(k, nparts));
     if (k == r.max_iters) break;
@@ -282,7 +297,7 @@ int run_polar_bf16(Run& r) {
       q.M = Sp; q.N = Sp; q.K = Sp; q.batch = P.batch; q.epi = BEPI_POLYQ;
       q.C32 = R; q.strideC32 = SS; q.ldc32 = Sp; q.Cb = Qb; q.strideCb = SS; q.ldcb = Sp; q.c1 = 0.5f;
       q.ctrl = r.ctrl;
-      { ProfScope ps(PK_BF16_POLYQ, r.s); CHECK_LAUNCH(launch_gemm_bf16(q, T, r.s)); }
+      { ProfScope ps(PK_BF16_POLYQ, r.s); CHECK_LAUNCH(launch_gemm_bf16(q, Tg, r.s)); }
       Bop = Qb;
     }
     Bf16Desc a = {};
@@ -291,7 +306,7 @@ int run_polar_bf16(Run& r) {
     a.Cb = Xhi[cur ^ 1]; a.Cb2 = Xlo[cur ^ 1]; a.strideCb = LS; a.ldcb = Sp;
     a.Ct = Xg[cur ^ 1]; a.strideCt = LS; a.ldct = Lp;
     a.Xhi = Xhi[cur]; a.Xlo = Xlo[cur]; a.coef_is_alpha = P.d == 1; a.ctrl = r.ctrl;
-    { ProfScope ps(PK_BF16_APPLY, r.s); CHECK_LAUNCH(launch_gemm_bf16(a, T, r.s)); }
+    { ProfScope ps(PK_BF16_APPLY, r.s); CHECK_LAUNCH(launch_gemm_bf16(a, Ta, r.s)); }
     cur ^= 1;
   }
   return PRISM_OK;
