@@ -69,6 +69,7 @@ struct Bf16Desc {
   const uint16_t* B; long long strideB; int ldb;    // [N][K]
   int M, N, K, batch;
   int epi;
+  int sym;                                           // GRAM / POLYQ with A == B: compute the upper triangle of tiles only
   int n_true;                                        // GRAM mask
   float* C32; long long strideC32; int ldc32;        // STORE / GRAM fp32 out; POLYQ fp32 in
   uint16_t* Cb; long long strideCb; int ldcb;        // GRAM: Rb out; POLYQ: Q out; APPLY: Xa_hi' out

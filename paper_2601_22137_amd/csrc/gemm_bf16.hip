@@ -43,7 +43,7 @@ template <int N> __device__ inline void wait_vmcnt() {
   __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | 0x0F70);
 }
 
-template <int T, int EPI>
+template <int T, int EPI, bool SYM>
 __global__ __launch_bounds__(NT) void gemm_bf16_kernel(Bf16Desc g) {
   constexpr int WT = T / 2;         // wave tile (2 x 2 waves)
   constexpr int NB = WT / 32;       // 32x32 blocks per wave and dimension
@@ -56,8 +56,10 @@ __global__ __launch_bounds__(NT) void gemm_bf16_kernel(Bf16Desc g) {
   extern __shared__ __align__(1024) unsigned char smem[];
   __shared__ float red[4];
 
+  // SYM: A == B and the result is symmetric (Gram matrix, R^2): only the tiles on and above the
+  // diagonal are computed, each off-diagonal tile is also written mirrored.
   const int tiles_m = g.M / T, tiles_n = g.N / T;
-  const int per_mat = tiles_m * tiles_n;
+  const int per_mat = SYM ? tiles_m * (tiles_m + 1) / 2 : tiles_m * tiles_n;
   const int total = per_mat * g.batch;
   int wg = blockIdx.x;
   // Workgroup -> tile.  The hardware deals consecutive workgroups round-robin to the 8 XCDs, each
@@ -71,10 +73,15 @@ __global__ __launch_bounds__(NT) void gemm_bf16_kernel(Bf16Desc g) {
   if ((total & 7) == 0 && xcd_private) wg = (wg & 7) * (total >> 3) + (wg >> 3);
   const int b = wg / per_mat;
   int rem = wg - b * per_mat;
-  int tm = rem / tiles_n, tn = rem - tm * tiles_n;
-  if (g.dbg & 4) {  // experiment: 4 x 8 blocks of tiles
-    const int blk = rem / 32, in = rem % 32, bpr = tiles_n / 8;
-    tm = (blk / bpr) * 4 + in / 8; tn = (blk % bpr) * 8 + in % 8;
+  int tm, tn;
+  if (SYM) {       // row tm of the upper triangle holds tiles_m - tm tiles
+    int left = rem;
+    tm = 0;
+    while (left >= tiles_m - tm) { left -= tiles_m - tm; ++tm; }
+    tn = tm + left;
+  } else {
+    tm = rem / tiles_n;
+    tn = rem - tm * tiles_n;
   }
   if (g.ctrl && g.ctrl[b].done) return;
   const float alpha = g.ctrl ? g.ctrl[b].alpha : 1.0f;
@@ -225,7 +232,86 @@ __global__ __launch_bounds__(NT) void gemm_bf16_kernel(Bf16Desc g) {
   float part = 0.0f;
   const float coef = g.coef_is_alpha ? alpha : 1.0f;
   const int rbase = (lane >> 5) * 4;
-  if constexpr (EPI == BEPI_APPLY) {
+  if constexpr (SYM && (EPI == BEPI_GRAM || EPI == BEPI_POLYQ)) {
+    // Each wave passes its tile through its own LDS strip of 32 rows (the ring is free after the
+    // last barrier): row-wise for the tile itself, column-wise for its mirror image, so that both
+    // are written with 16- and 32-byte vectors on contiguous runs.
+    constexpr int SW = WT + 4;
+    float* strip = (float*)smem + wave * 32 * SW;
+    constexpr int LPR = WT / 8, RPI = 64 / LPR;
+    const int rr = lane / LPR, cc = (lane % LPR) * 8;
+    const int cq = lane >> 2, rq = lane & 3;
+    const bool mirror = tm != tn;
+    const long long b32 = (long long)b * g.strideC32, bb = (long long)b * g.strideCb;
+#pragma unroll
+    for (int i = 0; i < NB; ++i) {
+#pragma unroll
+      for (int j = 0; j < NB; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+          strip[((r >> 2) * 8 + rbase + (r & 3)) * SW + j * 32 + lr] = acc[i][j][r];
+#pragma unroll
+      for (int it = 0; it < 32 / RPI; ++it) {
+        const int row = it * RPI + rr;
+        float* sp = strip + row * SW + cc;
+        f32x4 v0 = *(const f32x4*)sp, v1 = *(const f32x4*)(sp + 4);
+        const int m = m0 + wm0 + i * 32 + row, n = n0 + wn0 + cc;
+        const long long o32 = b32 + (long long)m * g.ldc32 + n;
+        if (EPI == BEPI_GRAM) {
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            v0[e] = (m < g.n_true && n + e < g.n_true) ? ((m == n + e ? 1.0f : 0.0f) - v0[e]) : 0.0f;
+            v1[e] = (m < g.n_true && n + 4 + e < g.n_true) ? ((m == n + 4 + e ? 1.0f : 0.0f) - v1[e]) : 0.0f;
+            part += v0[e] * v0[e] + v1[e] * v1[e];
+          }
+          *(f32x4*)(g.C32 + o32) = v0;
+          *(f32x4*)(g.C32 + o32 + 4) = v1;
+        } else {
+          const f32x4 r0 = *(const f32x4*)(g.C32 + o32), r1 = *(const f32x4*)(g.C32 + o32 + 4);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            v0[e] = g.c1 * r0[e] + alpha * v0[e];
+            v1[e] = g.c1 * r1[e] + alpha * v1[e];
+          }
+        }
+        u32x4 pk;
+        pk[0] = (unsigned)f2bf(v0[0]) | ((unsigned)f2bf(v0[1]) << 16);
+        pk[1] = (unsigned)f2bf(v0[2]) | ((unsigned)f2bf(v0[3]) << 16);
+        pk[2] = (unsigned)f2bf(v1[0]) | ((unsigned)f2bf(v1[1]) << 16);
+        pk[3] = (unsigned)f2bf(v1[2]) | ((unsigned)f2bf(v1[3]) << 16);
+        *(u32x4*)(g.Cb + bb + (long long)m * g.ldcb + n) = pk;
+        if (mirror) {
+          *(f32x4*)sp = v0;
+          *(f32x4*)(sp + 4) = v1;
+        }
+      }
+      if (mirror) {
+        // column-wise: 8 consecutive rows of one column = 8 consecutive entries of a mirrored row
+#pragma unroll
+        for (int it = 0; it < WT / 16; ++it) {
+          const int col = it * 16 + cq;
+          f32x4 t0, t1;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            t0[e] = strip[(rq * 8 + e) * SW + col];
+            t1[e] = strip[(rq * 8 + 4 + e) * SW + col];
+          }
+          const int mr = n0 + wn0 + col, nr = m0 + wm0 + i * 32 + rq * 8;   // mirrored position
+          if (EPI == BEPI_GRAM) {
+            *(f32x4*)(g.C32 + b32 + (long long)mr * g.ldc32 + nr) = t0;
+            *(f32x4*)(g.C32 + b32 + (long long)mr * g.ldc32 + nr + 4) = t1;
+          }
+          u32x4 pk;
+          pk[0] = (unsigned)f2bf(t0[0]) | ((unsigned)f2bf(t0[1]) << 16);
+          pk[1] = (unsigned)f2bf(t0[2]) | ((unsigned)f2bf(t0[3]) << 16);
+          pk[2] = (unsigned)f2bf(t1[0]) | ((unsigned)f2bf(t1[1]) << 16);
+          pk[3] = (unsigned)f2bf(t1[2]) | ((unsigned)f2bf(t1[3]) << 16);
+          *(u32x4*)(g.Cb + bb + (long long)mr * g.ldcb + nr) = pk;
+        }
+      }
+    }
+    if (mirror) part *= 2.0f;
+  } else if constexpr (EPI == BEPI_APPLY) {
     // The new iterate goes out in two layouts ([L][S] for the next update, [S][L] for the next
     // Gram product).  Each wave passes its tile through its own LDS strip of 32 rows so that
     // every global access is a 16-byte vector on a contiguous run: row-wise for X (read) and
@@ -328,20 +414,21 @@ __global__ __launch_bounds__(NT) void gemm_bf16_kernel(Bf16Desc g) {
   }
 }
 
-template <int T, int EPI>
+template <int T, int EPI, bool SYM>
 int launch_te(const Bf16Desc& g, hipStream_t s) {
-  const int total = (g.M / T) * (g.N / T) * g.batch;
+  const int tm = g.M / T, tn = g.N / T;
+  const int total = (SYM ? tm * (tm + 1) / 2 : tm * tn) * g.batch;
   const size_t lds = (size_t)STAGES * 2 * T * 64;   // ring of STAGES x (A slab + B slab)
   static bool attr_set = false;  // per instantiation
   if (!attr_set) {
-    if (hipFuncSetAttribute((const void*)gemm_bf16_kernel<T, EPI>, hipFuncAttributeMaxDynamicSharedMemorySize,
+    if (hipFuncSetAttribute((const void*)gemm_bf16_kernel<T, EPI, SYM>, hipFuncAttributeMaxDynamicSharedMemorySize,
                             (int)lds) != hipSuccess) {
       set_last_error("hipFuncSetAttribute(MaxDynamicSharedMemorySize) failed");
       return PRISM_EHIP;
     }
     attr_set = true;
   }
-  hipLaunchKernelGGL((gemm_bf16_kernel<T, EPI>), dim3(total), dim3(NT), lds, s, g);
+  hipLaunchKernelGGL((gemm_bf16_kernel<T, EPI, SYM>), dim3(total), dim3(NT), lds, s, g);
   return hipGetLastError() == hipSuccess ? PRISM_OK : PRISM_EHIP;
 }
 
@@ -349,11 +436,12 @@ template <int T>
 int launch_t(const Bf16Desc& g, hipStream_t s) {
   if (g.M % T || g.N % T || g.K % BK || g.lda % 8 || g.ldb % 8) return PRISM_EINVAL;
   if ((g.M / T) * (g.N / T) * g.batch <= 0) return PRISM_EINVAL;
+  if (g.sym && (g.M != g.N || g.A != g.B || g.A2)) return PRISM_EINVAL;
   switch (g.epi) {
-    case BEPI_STORE: return launch_te<T, BEPI_STORE>(g, s);
-    case BEPI_GRAM: return launch_te<T, BEPI_GRAM>(g, s);
-    case BEPI_POLYQ: return launch_te<T, BEPI_POLYQ>(g, s);
-    case BEPI_APPLY: return launch_te<T, BEPI_APPLY>(g, s);
+    case BEPI_STORE: return launch_te<T, BEPI_STORE, false>(g, s);
+    case BEPI_GRAM: return g.sym ? launch_te<T, BEPI_GRAM, true>(g, s) : launch_te<T, BEPI_GRAM, false>(g, s);
+    case BEPI_POLYQ: return g.sym ? launch_te<T, BEPI_POLYQ, true>(g, s) : launch_te<T, BEPI_POLYQ, false>(g, s);
+    case BEPI_APPLY: return launch_te<T, BEPI_APPLY, false>(g, s);
   }
   return PRISM_EINVAL;
 }

@@ -277,11 +277,15 @@ int run_polar_bf16(Run& r) {
   float* R = r.at<float>(P.o_r);
   uint16_t* Rb = r.at<uint16_t>(P.o_rb);
   uint16_t* Qb = P.d == 2 ? r.at<uint16_t>(P.o_qb) : nullptr;
-  const int nparts = (Sp / Tg) * (Sp / Tg);
+  static const int no_sym = getenv("PRISM_BF16_NO_SYM") ? atoi(getenv("PRISM_BF16_NO_SYM")) : 0;
+  const int sym = no_sym ? 0 : 1;
+  const int ntg = Sp / Tg;
+  const int nparts = sym ? ntg * (ntg + 1) / 2 : ntg * ntg;
   int cur = 0;
   for (int k = 0; k <= r.max_iters; ++k) {
     if (k == r.max_iters && r.tol <= 0.0) break;
     Bf16Desc g = {};
+    g.sym = sym;
     g.A = Xg[cur]; g.strideA = LS; g.lda = Lp; g.B = Xg[cur]; g.strideB = LS; g.ldb = Lp;
     g.M = Sp; g.N = Sp; g.K = Lp; g.batch = P.batch; g.epi = BEPI_GRAM; g.n_true = P.S;
     g.C32 = R; g.strideC32 = SS; g.ldc32 = Sp; g.Cb = Rb; g.strideCb = SS; g.ldcb = Sp;
@@ -294,7 +298,7 @@ int run_polar_bf16(Run& r) {
     if (P.d == 2) {
       Bf16Desc q = {};
       q.A = Rb; q.strideA = SS; q.lda = Sp; q.B = Rb; q.strideB = SS; q.ldb = Sp;
-      q.M = Sp; q.N = Sp; q.K = Sp; q.batch = P.batch; q.epi = BEPI_POLYQ;
+      q.M = Sp; q.N = Sp; q.K = Sp; q.batch = P.batch; q.epi = BEPI_POLYQ; q.sym = sym;
       q.C32 = R; q.strideC32 = SS; q.ldc32 = Sp; q.Cb = Qb; q.strideCb = SS; q.ldcb = Sp; q.c1 = 0.5f;
       q.ctrl = r.ctrl;
       { ProfScope ps(PK_BF16_POLYQ, r.s); CHECK_LAUNCH(launch_gemm_bf16(q, Tg, r.s)); }
