@@ -111,6 +111,31 @@ def oracle_call(name, host_matrix, W, O, seed):
     return O.polar(host_matrix, 5, 30, 8, seed, 1e-6)
 
 
+KERNEL_OF_KIND = {"bf16_gram": r"gemm_bf16_kernel<\d+, 1,", "bf16_polyq": r"gemm_bf16_kernel<\d+, 2,",
+                  "bf16_apply": r"gemm_bf16_kernel<\d+, 3,"}
+
+
+def recorded_traffic(workload, kind):
+    """HBM bytes per launch (fetch + write) of the dominant kernel, from the rocprofv3 --pmc summary
+    committed under profiles/ for this workload (counters scaled by a copy of known size); None
+    when no such summary exists.  It is a recorded measurement, not taken during this run."""
+    import re
+    path = os.path.join(ROOT, "profiles", "%s_hbm_traffic.md" % workload)
+    pat = KERNEL_OF_KIND.get(kind)
+    if pat is None or not os.path.exists(path):
+        return None
+    tot, n = {"FETCH_SIZE": 0.0, "WRITE_SIZE": 0.0}, {"FETCH_SIZE": 0, "WRITE_SIZE": 0}
+    for line in open(path):
+        cells = [c.strip() for c in line.split("|")]
+        if len(cells) >= 6 and re.search(pat, cells[1]) and cells[2] in tot and cells[5]:
+            d = int(cells[3])
+            tot[cells[2]] += float(cells[5]) * d
+            n[cells[2]] += d
+    if not n["FETCH_SIZE"] or not n["WRITE_SIZE"]:
+        return None
+    return round(tot["FETCH_SIZE"] / n["FETCH_SIZE"] + tot["WRITE_SIZE"] / n["WRITE_SIZE"])
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -241,7 +266,7 @@ def main():
         dt_peak = "f64" if dom.startswith("f64") else ("bf16" if dom.startswith("bf16") else "f32")
         achieved = fl / dur_s / 1e12
         roofline = {"bound": "mfma", "kernel": dom, "achieved": round(achieved, 2), "peak": PEAK[dt_peak], "unit": "TFLOP/s",
-                    "frac": round(achieved / PEAK[dt_peak], 4), "traffic": None,
+                    "frac": round(achieved / PEAK[dt_peak], 4), "traffic": recorded_traffic(wl.name, dom),
                     "launches": int(prof[dom][1]), "avg_launch_ms": round(prof[dom][0] / prof[dom][1], 4)}
 
     out = {

@@ -141,7 +141,7 @@ struct FinalArgs {
   void* dst; void* dst2;                    // caller's arrays (dst2 = inverse square root)
   const Ctrl* ctrl;
   const float* X32[2]; const float* Y32[2];
-  const uint16_t* Xa_hi[2]; const uint16_t* Xa_lo[2];
+  const uint16_t* Xa_hi[2]; const uint16_t* Xa_lo[2]; const uint16_t* Xg[2];
 };
 void launch_finalize(const FinalArgs& a, hipStream_t s);
 // E = alpha R, one matrix per blockIdx.y; skipped when done

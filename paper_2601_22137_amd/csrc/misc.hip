@@ -8,6 +8,8 @@ namespace prism {
 namespace {
 
 constexpr int NT = 256;
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 __device__ inline unsigned short f2bf(float x) {
   unsigned int u = __float_as_uint(x);
@@ -27,9 +29,29 @@ __global__ __launch_bounds__(NT) void sumsq_kernel(PrepArgs a) {
   const long long total = (long long)a.m * a.n;
   const long long base = (long long)b * total;
   double acc = 0.0;
-  for (long long i = (long long)blockIdx.x * NT + threadIdx.x; i < total; i += (long long)gridDim.x * NT) {
-    const double v = load_src(a.src, a.dt, base + i);
-    acc += v * v;
+  const long long first = (long long)blockIdx.x * NT + threadIdx.x, step = (long long)gridDim.x * NT;
+  if (a.dt == PRISM_BF16 && (total & 7) == 0) {          // 16-byte loads: 8 bf16 at a time
+    const u32x4* v = (const u32x4*)((const unsigned short*)a.src + base);
+    for (long long i = first; i < total / 8; i += step) {
+      const u32x4 w = v[i];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const double x0 = (double)__uint_as_float(w[e] << 16), x1 = (double)__uint_as_float(w[e] & 0xFFFF0000u);
+        acc += x0 * x0 + x1 * x1;
+      }
+    }
+  } else if (a.dt == PRISM_F32 && (total & 3) == 0) {
+    const f32x4* v = (const f32x4*)((const float*)a.src + base);
+    for (long long i = first; i < total / 4; i += step) {
+      const f32x4 w = v[i];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) acc += (double)w[e] * (double)w[e];
+    }
+  } else {
+    for (long long i = first; i < total; i += step) {
+      const double v = load_src(a.src, a.dt, base + i);
+      acc += v * v;
+    }
   }
   __shared__ double red[4];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -132,6 +154,113 @@ __global__ __launch_bounds__(NT) void prepare_kernel(PrepArgs a) {
   }
 }
 
+// bf16 polar, both sides multiples of 8: one workgroup per 64 x 64 tile of the CALLER's matrix.
+// The tile is read with 16-byte loads along the caller's rows, scaled, split into high and low
+// halves and written to the internal array of the same orientation directly and to the other one
+// through an LDS transpose, everything as 16-byte vectors.
+__global__ __launch_bounds__(NT) void prepare_bf16_kernel(PrepArgs a) {
+  const int b = blockIdx.y;
+  const int tiles_c = (a.transpose ? a.Lp : a.Sp) / 64;             // tiles over the padded, caller-oriented matrix
+  const int tr = blockIdx.x / tiles_c, tc = blockIdx.x % tiles_c;
+  double ss = 0.0;
+  for (int i = 0; i < a.nsum; ++i) ss += a.sumsq_part[(long long)b * a.nsum + i];
+  const bool finite = (ss == ss) && ss < 1.0e300;
+  const bool zero = finite && ss == 0.0;
+  const double norm = sqrt(ss);
+  const float scale = (finite && !zero) ? (float)(1.0 / norm) : 0.0f;
+  if (blockIdx.x == 0 && threadIdx.x == 0) {
+    Ctrl c;
+    c.done = (finite && !zero) ? 0 : 1;
+    c.iters = 0;
+    c.status = !finite ? PRISM_INFO_NONFINITE : (zero ? PRISM_INFO_ZERO : PRISM_INFO_BUDGET);
+    c.pad0 = 0;
+    c.alpha = 0.0f; c.res0 = 0.0f; c.res1 = 0.0f; c.res2 = 0.0f;
+    c.norm = norm; c.scale = scale;
+    a.ctrl[b] = c;
+    a.info[b].iters = 0;
+    a.info[b].status = c.status;
+  }
+  if (blockIdx.x == 0) {
+    for (int i = threadIdx.x; i <= PRISM_MAX_ITERS; i += NT) a.info[b].residual[i] = -1.0f;
+    for (int i = threadIdx.x; i < PRISM_MAX_ITERS; i += NT) a.info[b].alpha[i] = 0.0f;
+  }
+  // "same" = internal array with the caller's orientation, "other" = its transpose
+  //   m >= n: same = Xa [Lp][Sp] (hi, lo), other = Xg [Sp][Lp] (hi)
+  //   m <  n: same = Xg [Sp][Lp] (hi),     other = Xa [Lp][Sp] (hi, lo)
+  const int ld_same = a.transpose ? a.Lp : a.Sp, ld_other = a.transpose ? a.Sp : a.Lp;
+  const long long mat_int = (long long)a.Lp * a.Sp;
+  __shared__ float tile_hi[64][65], tile_lo[64][65];
+  const unsigned short* src = (const unsigned short*)a.src + (long long)b * a.m * a.n;
+#pragma unroll
+  for (int it = 0; it < 2; ++it) {
+    const int v = threadIdx.x + it * NT;          // 512 vectors of 8 per tile
+    const int lr = v >> 3, lc = (v & 7) * 8;
+    const int r = tr * 64 + lr, c = tc * 64 + lc;
+    u32x4 w = {0u, 0u, 0u, 0u};
+    if (r < a.m && c < a.n) w = *(const u32x4*)(src + (long long)r * a.n + c);
+    u32x4 hi, lo;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const float x0 = __uint_as_float(w[e] << 16) * scale, x1 = __uint_as_float(w[e] & 0xFFFF0000u) * scale;
+      const unsigned short h0 = f2bf(x0), h1 = f2bf(x1);
+      const unsigned short l0 = f2bf(x0 - bf2f(h0)), l1 = f2bf(x1 - bf2f(h1));
+      hi[e] = (unsigned)h0 | ((unsigned)h1 << 16);
+      lo[e] = (unsigned)l0 | ((unsigned)l1 << 16);
+      tile_hi[lc + 2 * e][lr] = bf2f(h0); tile_hi[lc + 2 * e + 1][lr] = bf2f(h1);
+      tile_lo[lc + 2 * e][lr] = bf2f(l0); tile_lo[lc + 2 * e + 1][lr] = bf2f(l1);
+    }
+    {  // rows / columns beyond the caller's matrix but inside the padded arrays are written as zeros
+      const long long o = (long long)b * mat_int + (long long)r * ld_same + c;
+      if (a.transpose) {
+        *(u32x4*)(a.Xg + o) = hi;
+      } else {
+        *(u32x4*)(a.Xa_hi + o) = hi;
+        if (a.Xa_lo) *(u32x4*)(a.Xa_lo + o) = lo;
+      }
+    }
+  }
+  __syncthreads();
+#pragma unroll
+  for (int it = 0; it < 2; ++it) {
+    const int v = threadIdx.x + it * NT;
+    const int lc = v >> 3, lr = (v & 7) * 8;      // row lc of the transposed tile, 8 consecutive source rows
+    const int r = tr * 64 + lr, c = tc * 64 + lc;
+    u32x4 hi, lo;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      hi[e] = (unsigned)f2bf(tile_hi[lc][lr + 2 * e]) | ((unsigned)f2bf(tile_hi[lc][lr + 2 * e + 1]) << 16);
+      lo[e] = (unsigned)f2bf(tile_lo[lc][lr + 2 * e]) | ((unsigned)f2bf(tile_lo[lc][lr + 2 * e + 1]) << 16);
+    }
+    {
+      const long long o = (long long)b * mat_int + (long long)c * ld_other + r;
+      if (a.transpose) {
+        *(u32x4*)(a.Xa_hi + o) = hi;
+        if (a.Xa_lo) *(u32x4*)(a.Xa_lo + o) = lo;
+      } else {
+        *(u32x4*)(a.Xg + o) = hi;
+      }
+    }
+  }
+}
+
+// bf16 polar, both sides multiples of 8: the result is the high half of the iterate, copied with
+// 16-byte vectors from the internal array that has the caller's orientation.
+__global__ __launch_bounds__(NT) void finalize_bf16_kernel(FinalArgs a) {
+  const int b = blockIdx.y;
+  const Ctrl c = a.ctrl[b];
+  if (c.status == PRISM_INFO_NONFINITE || c.status == PRISM_INFO_ZERO) return;
+  const int par = c.iters & 1;
+  const int vec_per_row = a.n / 8;
+  const long long nvec = (long long)a.m * vec_per_row;
+  const long long i = (long long)blockIdx.x * NT + threadIdx.x;
+  if (i >= nvec) return;
+  const int r = (int)(i / vec_per_row), col = (int)(i % vec_per_row) * 8;
+  const unsigned short* srcm = a.transpose ? a.Xg[par] : a.Xa_hi[par];
+  const int ld = a.transpose ? a.Lp : a.Sp;
+  const u32x4 v = *(const u32x4*)(srcm + (long long)b * a.Lp * a.Sp + (long long)r * ld + col);
+  *(u32x4*)((unsigned short*)a.dst + (long long)b * a.m * a.n + (long long)r * a.n + col) = v;
+}
+
 // One thread per element of the caller's array.
 __global__ __launch_bounds__(NT) void finalize_kernel(FinalArgs a) {
   const int b = blockIdx.y;
@@ -182,12 +311,27 @@ void launch_sumsq(const PrepArgs& a, hipStream_t s) {
   hipLaunchKernelGGL(sumsq_kernel, dim3(a.nsum, a.batch), dim3(NT), 0, s, a);
 }
 
+static bool bf16_vector_path(int fn, int dt, int m, int n) {
+  return fn == PRISM_FN_POLAR && dt == PRISM_BF16 && m % 8 == 0 && n % 8 == 0;
+}
+
 void launch_prepare(const PrepArgs& a, hipStream_t s) {
+  if (bf16_vector_path(a.fn, a.dt, a.m, a.n)) {
+    // tiles over the padded caller-oriented matrix, so that the padding is written too
+    const int tiles = (a.Lp / 64) * (a.Sp / 64);
+    hipLaunchKernelGGL(prepare_bf16_kernel, dim3(tiles, a.batch), dim3(NT), 0, s, a);
+    return;
+  }
   const int tiles = (a.Lp / 64) * (a.Sp / 64);
   hipLaunchKernelGGL(prepare_kernel, dim3(tiles, a.batch), dim3(NT), 0, s, a);
 }
 
 void launch_finalize(const FinalArgs& a, hipStream_t s) {
+  if (bf16_vector_path(a.fn, a.dt, a.m, a.n)) {
+    const long long nvec = (long long)a.m * (a.n / 8);
+    hipLaunchKernelGGL(finalize_bf16_kernel, dim3((unsigned)((nvec + NT - 1) / NT), a.batch), dim3(NT), 0, s, a);
+    return;
+  }
   const long long mat = (long long)a.m * a.n;
   hipLaunchKernelGGL(finalize_kernel, dim3((unsigned)((mat + NT - 1) / NT), a.batch), dim3(NT), 0, s, a);
 }

@@ -444,6 +444,7 @@ int run(int fn, void* a, void* inv_out, int root_p, int batch, int m, int n, int
     for (int i = 0; i < 2; ++i) {
       fa.Xa_hi[i] = r.at<uint16_t>(P.o_xhi[i]);
       fa.Xa_lo[i] = P.split ? r.at<uint16_t>(P.o_xlo[i]) : nullptr;
+      fa.Xg[i] = r.at<uint16_t>(P.o_xg[i]);
     }
   } else {
     pa.X32 = r.at<float>(P.o_x[0]);
