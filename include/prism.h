@@ -147,7 +147,9 @@ int prism_chain_product(const float* R, const float* V, float* out, int batch, i
                         void* stream);
 
 /* C[batch][M][N] = A * B on the matrix cores, no epilogue.  Device pointers.
- *   prism_gemm_f32 : fp32 in/out; a_km != 0 means A is stored [K][M].  B is [K][N].
+ *   prism_gemm_f32 : fp32 in/out; bit 0 of a_km: A is stored [K][M].  B is [K][N].  Bit 1: the
+ *                    caller asserts A B is symmetric (M = N, tile-sized); only the tiles on and
+ *                    above the diagonal are computed and the rest is their mirror image.
  *   prism_gemm_f64a: A fp32 (promoted), B and C fp64, A stored [M][K].
  *   prism_gemm_bf16_nt: A [M][K], B [N][K] bf16 bit patterns, C fp32 = A B^T.
  * M, N must be multiples of 128 (bf16: of `tile`, 128 or 256; fp32 skinny N = 16, 32, 64 also allowed)

@@ -118,12 +118,102 @@ __global__ __launch_bounds__(NT) void chain_kernel(const float* __restrict__ R, 
       Vout[(long long)b * strideVout + (long long)(row0 + 4 * lq + r) * LD + j * 16 + li] = acc[j][r];
 }
 
+// Variant for small matrices (n <= 2048), where the kernel above is latency bound for lack of
+// workgroups: a workgroup owns only 16 rows of R and its four wavefronts split K between them
+// (wave w takes the chunks c = w, w+4, ...), each staging its own chunks of V in a private LDS
+// area (no workgroup barrier inside the loop); the four partial sums are added through LDS in a
+// fixed order at the end.
+template <int LD>
+__global__ __launch_bounds__(NT) void chain_small_kernel(const float* __restrict__ R, long long strideR, int ldr,
+                                                         const float* __restrict__ Vin, long long strideVin,
+                                                         float* __restrict__ Vout, long long strideVout, int n,
+                                                         const Ctrl* __restrict__ ctrl) {
+  constexpr int NBLK = LD / 16;
+  constexpr int VS = LD + 4;
+  constexpr int VL = KC * LD / 4 / 64;          // float4 loads per lane for one chunk of V
+  __shared__ float Vs[4][2][KC][VS];             // [wave][double buffer]
+  __shared__ float red[4][NBLK][4][64];
+  const int b = blockIdx.y;
+  if (ctrl && ctrl[b].done) return;
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  const int li = lane & 15, lq = lane >> 4;
+  const int row0 = blockIdx.x * 16;
+  const float* Rrow = R + (long long)b * strideR + (long long)(row0 + li) * ldr + 4 * lq;
+  const float* Vb = Vin + (long long)b * strideVin;
+  const int nchunks = n / KC;
+  const int mine = (nchunks - wave + 3) / 4;     // chunks of this wave
+
+  constexpr int DEPTH = 3;
+  f32x4 ra[DEPTH][4], va[DEPTH][VL];
+  auto load = [&](int slot, int i) {             // i-th chunk of this wave; slot is compile time
+    if (i < mine) {
+      const int c = wave + 4 * i;
+#pragma unroll
+      for (int s = 0; s < 4; ++s) ra[slot][s] = *(const f32x4*)(Rrow + c * KC + 16 * s);
+#pragma unroll
+      for (int v = 0; v < VL; ++v) {
+        const int idx = lane + 64 * v;
+        va[slot][v] = *(const f32x4*)(Vb + (long long)(c * KC + idx / (LD / 4)) * LD + (idx % (LD / 4)) * 4);
+      }
+    }
+  };
+  f32x4 acc[NBLK];
+#pragma unroll
+  for (int j = 0; j < NBLK; ++j) acc[j] = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int d = 0; d < DEPTH - 1; ++d) load(d, d);
+  for (int i0 = 0; i0 < mine; i0 += DEPTH) {
+#pragma unroll
+    for (int d = 0; d < DEPTH; ++d) {
+      const int i = i0 + d;
+      if (i < mine) {                             // uniform within the wave
+        load((d + DEPTH - 1) % DEPTH, i + DEPTH - 1);
+        const int buf = i & 1;
+#pragma unroll
+        for (int v = 0; v < VL; ++v) {
+          const int idx = lane + 64 * v;
+          *(f32x4*)&Vs[wave][buf][idx / (LD / 4)][(idx % (LD / 4)) * 4] = va[d][v];
+        }
+        // wave-private LDS area: LDS operations of one wave complete in order, no barrier needed
+#pragma unroll
+        for (int s = 0; s < 4; ++s)
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+#pragma unroll
+            for (int j = 0; j < NBLK; ++j)
+              acc[j] = __builtin_amdgcn_mfma_f32_16x16x4f32(ra[d][s][e], Vs[wave][buf][16 * s + 4 * lq + e][j * 16 + li], acc[j], 0, 0, 0);
+      }
+    }
+  }
+#pragma unroll
+  for (int j = 0; j < NBLK; ++j)
+#pragma unroll
+    for (int r = 0; r < 4; ++r) red[wave][j][r][lane] = acc[j][r];
+  __syncthreads();
+  if (wave == 0) {
+#pragma unroll
+    for (int j = 0; j < NBLK; ++j)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const float v = (red[0][j][r][lane] + red[1][j][r][lane]) + (red[2][j][r][lane] + red[3][j][r][lane]);
+        Vout[(long long)b * strideVout + (long long)(row0 + 4 * lq + r) * LD + j * 16 + li] = v;
+      }
+  }
+}
+
 }  // namespace
 
 // R: [batch][n][ldr] fp32 (n a multiple of 64), Vin/Vout: [n][ld] per matrix (strideVin may be 0)
 int launch_chain(const float* R, long long strideR, int ldr, const float* Vin, long long strideVin, float* Vout,
                  long long strideVout, int n, int ld, int batch, const Ctrl* ctrl, hipStream_t s) {
   if (n % KC || n % ROWS || ldr % 4 || batch <= 0) return PRISM_EINVAL;
+  // 64-row workgroups leave most CUs idle on small batches of small matrices: 16-row ones there
+  if (ld <= 32 && (long long)(n / ROWS) * batch < 256) {
+    const dim3 grid(n / 16, batch), block(NT);
+    if (ld == 16) hipLaunchKernelGGL(chain_small_kernel<16>, grid, block, 0, s, R, strideR, ldr, Vin, strideVin, Vout, strideVout, n, ctrl);
+    else hipLaunchKernelGGL(chain_small_kernel<32>, grid, block, 0, s, R, strideR, ldr, Vin, strideVin, Vout, strideVout, n, ctrl);
+    return hipGetLastError() == hipSuccess ? PRISM_OK : PRISM_EHIP;
+  }
   const dim3 grid(n / ROWS, batch), block(NT);
   if (ld == 16) hipLaunchKernelGGL(chain_kernel<16>, grid, block, 0, s, R, strideR, ldr, Vin, strideVin, Vout, strideVout, n, ctrl);
   else if (ld == 32) hipLaunchKernelGGL(chain_kernel<32>, grid, block, 0, s, R, strideR, ldr, Vin, strideVin, Vout, strideVout, n, ctrl);

@@ -36,6 +36,7 @@ struct GemmDesc {
   const void* B; long long strideB; int ldb;
   int M, N, K;          // padded sizes: multiples of the tile sizes
   int a_km;             // A stored [K][M] instead of [M][K]
+  int sym;              // the exact result is symmetric: compute the upper triangle of tiles, mirror the rest
   int batch;
   // epilogue operands
   int epi;
@@ -85,7 +86,8 @@ struct Bf16Desc {
 int launch_gemm_bf16(const Bf16Desc& g, int tile, hipStream_t s);
 
 // ---- sketch.hip ----
-void launch_sketch(float* v0, int rows_total, int n, int ld, int p_s, uint64_t seed, int k, int fn,
+// v0[k - k_first][rows_total][ld] for k = k_first .. k_first + k_count - 1
+void launch_sketch(float* v0, int rows_total, int n, int ld, int p_s, uint64_t seed, int k_first, int k_count, int fn,
                    hipStream_t s);
 void launch_gauss_parts(uint32_t first, uint32_t count, double* r, double* c, double* sn,
                         hipStream_t s);

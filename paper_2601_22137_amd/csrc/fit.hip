@@ -178,6 +178,27 @@ __global__ __launch_bounds__(NT) void solve_kernel(SolveArgs a) {
   }
 
   const int nc = (a.fn == PRISM_FN_INV_ROOT) ? 2 * a.p + 1 : 5;
+  if (a.ngroups == 1) {   // small matrices: the moments are accumulated right here
+    double* out = a.cpart + (long long)b * MAXC;
+    if (a.fn == PRISM_FN_INV_ROOT) {
+      switch (a.p) {
+        case 1: accumulate_coefficients<BlocksInv<1>>(a, b, 0, 1, out); break;
+        case 2: accumulate_coefficients<BlocksInv<2>>(a, b, 0, 1, out); break;
+        case 3: accumulate_coefficients<BlocksInv<3>>(a, b, 0, 1, out); break;
+        case 4: accumulate_coefficients<BlocksInv<4>>(a, b, 0, 1, out); break;
+        case 5: accumulate_coefficients<BlocksInv<5>>(a, b, 0, 1, out); break;
+        case 6: accumulate_coefficients<BlocksInv<6>>(a, b, 0, 1, out); break;
+        case 7: accumulate_coefficients<BlocksInv<7>>(a, b, 0, 1, out); break;
+        default: accumulate_coefficients<BlocksInv<8>>(a, b, 0, 1, out); break;
+      }
+    } else if (a.d == 1) {
+      accumulate_coefficients<Blocks<1>>(a, b, 0, 1, out);
+    } else {
+      accumulate_coefficients<Blocks<2>>(a, b, 0, 1, out);
+    }
+    __threadfence_block();
+    __syncthreads();
+  }
   if (t < MAXC) {   // coefficient s = sum of the group partials, in group order
     double v = 0.0;
     for (int gidx = 0; gidx < a.ngroups; ++gidx) v += a.cpart[((long long)b * a.ngroups + gidx) * MAXC + t];

@@ -40,21 +40,27 @@ template <typename TC> __device__ inline int acc_row(int lane, int r);
 template <> __device__ inline int acc_row<float>(int lane, int r) { return 4 * (lane >> 4) + r; }
 template <> __device__ inline int acc_row<double>(int lane, int r) { return 4 * r + (lane >> 4); }
 
+// Applies the fused epilogue to one element, stores it, returns its contribution to the residual
+// sum; `out` receives the stored value (for the mirrored store of the symmetric variants).
 template <typename TC>
-__device__ inline TC epilogue(const GemmDesc& g, int b, int i, int j, TC acc, float alpha) {
+__device__ inline TC epilogue(const GemmDesc& g, int b, int i, int j, TC acc, float alpha, TC& out) {
   const long long oc = (long long)b * g.strideC + (long long)i * g.ldc + j;
   switch (g.epi) {
     case EPI_STORE:
       ((TC*)g.C)[oc] = acc;
+      out = acc;
       return 0;
     case EPI_RESIDUAL: {
       TC r = (i < g.n_true && j < g.n_true) ? ((i == j ? (TC)1 : (TC)0) - acc) : (TC)0;
       ((TC*)g.C)[oc] = r;
+      out = r;
       return r * r;
     }
     case EPI_POLYQ: {
       const float rin = ((const float*)g.Cin)[(long long)b * g.strideCin + (long long)i * g.ldcin + j];
-      ((float*)g.C)[oc] = g.c1 * rin + alpha * (float)acc;
+      const float q = g.c1 * rin + alpha * (float)acc;
+      ((float*)g.C)[oc] = q;
+      out = (TC)q;
       return 0;
     }
     case EPI_AXPY: {
@@ -63,6 +69,7 @@ __device__ inline TC epilogue(const GemmDesc& g, int b, int i, int j, TC acc, fl
       float v = g.c_in * cin + coef * (float)acc;
       if (g.Cin2) v += g.Cin2[(long long)b * g.strideCin + (long long)i * g.ldcin + j];
       ((float*)g.C)[oc] = v;
+      out = (TC)v;
       return 0;
     }
     case EPI_MNEXT: {
@@ -72,13 +79,15 @@ __device__ inline TC epilogue(const GemmDesc& g, int b, int i, int j, TC acc, fl
       ((TC*)g.C)[oc] = mval;
       const TC r = in ? ((i == j ? (TC)1 : (TC)0) - acc) : (TC)0;
       g.R32out[(long long)b * g.strideR + (long long)i * g.ldr + j] = (float)r;
+      out = mval;
       return r * r;
     }
   }
+  out = 0;
   return 0;
 }
 
-template <typename TC, typename TB, int TM, int TN, int WGM, int WGN, bool A_KM>
+template <typename TC, typename TB, int TM, int TN, int WGM, int WGN, bool A_KM, bool SYM>
 __global__ __launch_bounds__(NT) void gemm_kernel(GemmDesc g) {
   constexpr int LDA = lds_ld(TM), LDB = lds_ld(TN);
   constexpr int WTM = TM / WGM, WTN = TN / WGN;  // wave tile
@@ -88,14 +97,25 @@ __global__ __launch_bounds__(NT) void gemm_kernel(GemmDesc g) {
   __shared__ TC Bs[2][BK][LDB];
   __shared__ TC red[4];
 
+  // SYM (square fp32 products whose exact result is symmetric): only the tiles on and above the
+  // diagonal are computed; every off-diagonal tile is also stored mirrored.
   const int tiles_m = g.M / TM, tiles_n = g.N / TN;
-  const int per_mat = tiles_m * tiles_n;
+  const int per_mat = SYM ? tiles_m * (tiles_m + 1) / 2 : tiles_m * tiles_n;
   const int total = per_mat * g.batch;
   int wg = blockIdx.x;
   if ((total & 7) == 0) wg = (wg & 7) * (total >> 3) + (wg >> 3);  // one XCD = one contiguous tile range
   const int b = wg / per_mat;
   const int rem = wg - b * per_mat;
-  const int tm = rem / tiles_n, tn = rem - tm * tiles_n;
+  int tm, tn;
+  if (SYM) {
+    int left = rem;
+    tm = 0;
+    while (left >= tiles_m - tm) { left -= tiles_m - tm; ++tm; }
+    tn = tm + left;
+  } else {
+    tm = rem / tiles_n;
+    tn = rem - tm * tiles_n;
+  }
   if (g.ctrl && g.ctrl[b].done) return;
   const float alpha = g.ctrl ? g.ctrl[b].alpha : 1.0f;
 
@@ -224,13 +244,23 @@ __global__ __launch_bounds__(NT) void gemm_kernel(GemmDesc g) {
 #pragma unroll
   for (int i = 0; i < BM; ++i)
 #pragma unroll
-    for (int j = 0; j < BN; ++j)
+    for (int j = 0; j < BN; ++j) {
+      const int gj = n0 + wn0 + j * 16 + lr;
+      typename Acc<TC>::type outv;
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
         const int gi = m0 + wm0 + i * 16 + acc_row<TC>(lane, r);
-        const int gj = n0 + wn0 + j * 16 + lr;
-        part += epilogue<TC>(g, b, gi, gj, acc[i][j][r], alpha);
+        TC o;
+        part += epilogue<TC>(g, b, gi, gj, acc[i][j][r], alpha, o);
+        outv[r] = o;
       }
+      if (SYM && tm != tn) {
+        // the lane holds four consecutive rows of one column: one 16-byte store in the mirror image
+        const int gi0 = m0 + wm0 + i * 16 + 4 * (lane >> 4);
+        *(typename Acc<TC>::type*)((TC*)g.C + (long long)b * g.strideC + (long long)gj * g.ldc + gi0) = outv;
+      }
+    }
+  if (SYM && tm != tn) part *= (TC)2;
   if (g.epi == EPI_RESIDUAL || g.epi == EPI_MNEXT) {
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) part += __shfl_down(part, off, 64);
@@ -243,12 +273,25 @@ __global__ __launch_bounds__(NT) void gemm_kernel(GemmDesc g) {
 template <typename TC, typename TB, int TM, int TN, int WGM, int WGN>
 int launch_cfg(const GemmDesc& g, hipStream_t s) {
   if (g.M % TM || g.N % TN || g.K % BK || g.lda % 4 || g.ldb % 4) return PRISM_EINVAL;
-  const int total = (g.M / TM) * (g.N / TN) * g.batch;
+  const int tm = g.M / TM, tn = g.N / TN;
+  int total = tm * tn * g.batch;
   if (total <= 0) return PRISM_EINVAL;
+  if constexpr (sizeof(TC) == 4 && TM == TN) {
+    if (g.sym) {
+      if (g.M != g.N || g.epi == EPI_MNEXT || g.ldc % 4) return PRISM_EINVAL;
+      total = tm * (tm + 1) / 2 * g.batch;
+      if (g.a_km)
+        hipLaunchKernelGGL((gemm_kernel<TC, TB, TM, TN, WGM, WGN, true, true>), dim3(total), dim3(NT), 0, s, g);
+      else
+        hipLaunchKernelGGL((gemm_kernel<TC, TB, TM, TN, WGM, WGN, false, true>), dim3(total), dim3(NT), 0, s, g);
+      return hipGetLastError() == hipSuccess ? PRISM_OK : PRISM_EHIP;
+    }
+  }
+  if (g.sym) return PRISM_EINVAL;
   if (g.a_km)
-    hipLaunchKernelGGL((gemm_kernel<TC, TB, TM, TN, WGM, WGN, true>), dim3(total), dim3(NT), 0, s, g);
+    hipLaunchKernelGGL((gemm_kernel<TC, TB, TM, TN, WGM, WGN, true, false>), dim3(total), dim3(NT), 0, s, g);
   else
-    hipLaunchKernelGGL((gemm_kernel<TC, TB, TM, TN, WGM, WGN, false>), dim3(total), dim3(NT), 0, s, g);
+    hipLaunchKernelGGL((gemm_kernel<TC, TB, TM, TN, WGM, WGN, false, false>), dim3(total), dim3(NT), 0, s, g);
   return hipGetLastError() == hipSuccess ? PRISM_OK : PRISM_EHIP;
 }
 

@@ -97,11 +97,11 @@ int make_plan(Plan& P, int fn, int batch, int m, int n, int dt, int degree, int 
   P.o_info = take(B * sizeof(prism_info));
   P.o_sumsq = take(B * P.nsum * sizeof(double));
   P.o_rho = take(B * P.max_parts * sizeof(float));
-  P.o_v0 = take((size_t)P.Sp * P.ld * sizeof(float));
+  P.o_v0 = take((size_t)PRISM_MAX_ITERS * P.Sp * P.ld * sizeof(float));   // S_k^T for every k, generated once per call
   P.o_v = take((size_t)P.nv * B * P.Sp * P.ld * sizeof(float));
   {
     const long long el = (long long)P.Sp * P.ld;
-    P.ngroups = (int)(el / (256 * 16) < 1 ? 1 : (el / (256 * 16) > 64 ? 64 : el / (256 * 16)));
+    P.ngroups = el <= 4096 ? 1 : (int)(el / 4096 > 64 ? 64 : el / 4096);   // 1: done inside the solve kernel
   }
   P.o_cpart = take(B * P.ngroups * 17 * sizeof(double));
   if (dt == PRISM_BF16) {
@@ -189,10 +189,9 @@ struct Run {
   // sketch + chain V_j = R V_{j-1} (fp32 matrix cores, skinny N = padded sketch width)
   int chain(const float* R, int k) {
     const int Sp = P.Sp, ld = P.ld;
-    { ProfScope ps(PK_SKETCH, s); launch_sketch(v0, Sp, P.S, ld, P.p_s, seed, k, P.fn, s); }
     const long long vs = (long long)P.batch * Sp * ld;
     for (int j = 1; j <= P.nv; ++j) {
-      const float* vin = (j == 1) ? v0 : v + (j - 2) * vs;
+      const float* vin = (j == 1) ? v0 + (long long)(k - warm) * Sp * ld : v + (j - 2) * vs;
       const long long sin = (j == 1) ? 0 : (long long)Sp * ld;
       ProfScope ps(PK_CHAIN, s);
       CHECK_LAUNCH(launch_chain(R, (long long)Sp * Sp, Sp, vin, sin, v + (j - 1) * vs, (long long)Sp * ld, Sp, ld,
@@ -210,7 +209,7 @@ struct Run {
     a.mode = P.p_s == 0 ? 1 : (k < warm ? 2 : 0);
     a.last = (k == max_iters);
     a.cpart = at<double>(P.o_cpart); a.ngroups = P.ngroups;
-    { ProfScope ps(PK_SOLVE, s); if (a.mode == 0 && !a.last) launch_moments(a, P.batch, s); launch_solve(a, P.batch, s); }
+    { ProfScope ps(PK_SOLVE, s); if (a.mode == 0 && !a.last && a.ngroups > 1) launch_moments(a, P.batch, s); launch_solve(a, P.batch, s); }
     return check_hip();
   }
   bool fit_needed(int k) const { return P.p_s > 0 && k >= warm && k < max_iters; }
@@ -225,6 +224,13 @@ GemmDesc f32_desc(const Run& r, const float* A, int lda, long long sa, const flo
   return g;
 }
 
+// Products whose exact result is symmetric are computed on the upper triangle of tiles only.
+int f32_sym() {
+  static const int off = getenv("PRISM_F32_NO_SYM") ? atoi(getenv("PRISM_F32_NO_SYM")) : 0;
+  return off ? 0 : 1;
+}
+int sym_parts(int nt, int sym) { return sym ? nt * (nt + 1) / 2 : nt * nt; }
+
 int run_polar_f32(Run& r) {
   const Plan& P = r.P;
   const int Sp = P.Sp, Lp = P.Lp, T = P.tile;
@@ -232,11 +238,13 @@ int run_polar_f32(Run& r) {
   float* X[2] = {r.at<float>(P.o_x[0]), r.at<float>(P.o_x[1])};
   float* R = r.at<float>(P.o_r);
   float* Q = P.d == 2 ? r.at<float>(P.o_q) : nullptr;
-  const int nparts = (Sp / T) * (Sp / T);
+  const int sym = f32_sym();
+  const int nparts = sym_parts(Sp / T, sym);
   int cur = 0;
   for (int k = 0; k <= r.max_iters; ++k) {
     if (k == r.max_iters && r.tol <= 0.0) break;
     GemmDesc g = f32_desc(r, X[cur], Sp, LS, X[cur], Sp, LS, Sp, Sp, Lp, 1);   // G = X^T X
+    g.sym = sym;
     g.epi = EPI_RESIDUAL; g.C = R; g.strideC = SS; g.ldc = Sp; g.rho_part = r.rho;
     { ProfScope ps(PK_F32_RESID, r.s); CHECK_LAUNCH(launch_gemm_f32(g, T, T, r.s)); }
     if (r.fit_needed(k)) CHECK_LAUNCH(r.chain(R, k));
@@ -245,6 +253,7 @@ int run_polar_f32(Run& r) {
     const float* Bop = R;
     if (P.d == 2) {
       GemmDesc q = f32_desc(r, R, Sp, SS, R, Sp, SS, Sp, Sp, Sp, 1);           // R symmetric: R^2 = R^T R
+      q.sym = sym;
       q.epi = EPI_POLYQ; q.C = Q; q.strideC = SS; q.ldc = Sp; q.Cin = R; q.strideCin = SS; q.ldcin = Sp; q.c1 = 0.5f;
       { ProfScope ps(PK_F32_POLYQ, r.s); CHECK_LAUNCH(launch_gemm_f32(q, T, T, r.s)); }
       Bop = Q;
@@ -258,18 +267,19 @@ int run_polar_f32(Run& r) {
   return PRISM_OK;
 }
 
-// 256 x 256 tiles when they still give every CU work, else 128 x 128
-int bf16_tile(const Plan& P, int M, int N) {
+// 256 x 256 tiles when they still give every CU work and K is long enough to amortise their
+// epilogue (one workgroup per CU, nothing overlaps it), else 128 x 128 (two workgroups per CU)
+int bf16_tile(const Plan& P, int M, int N, int K) {
   static const int forced = getenv("PRISM_BF16_TILE") ? atoi(getenv("PRISM_BF16_TILE")) : 0;
   if (P.tile != 256) return 128;
   if (forced == 128 || forced == 256) return forced;
-  return ((long long)(M / 256) * (N / 256) * P.batch >= 192) ? 256 : 128;
+  return ((long long)(M / 256) * (N / 256) * P.batch >= 192 && K >= 2048) ? 256 : 128;
 }
 
 int run_polar_bf16(Run& r) {
   const Plan& P = r.P;
   const int Sp = P.Sp, Lp = P.Lp;
-  const int Tg = bf16_tile(P, Sp, Sp), Ta = bf16_tile(P, Lp, Sp);
+  const int Tg = bf16_tile(P, Sp, Sp, Sp), Ta = bf16_tile(P, Lp, Sp, Sp);
   const long long SS = (long long)Sp * Sp, LS = (long long)Lp * Sp;
   uint16_t* Xhi[2] = {r.at<uint16_t>(P.o_xhi[0]), r.at<uint16_t>(P.o_xhi[1])};
   uint16_t* Xlo[2] = {P.split ? r.at<uint16_t>(P.o_xlo[0]) : nullptr, P.split ? r.at<uint16_t>(P.o_xlo[1]) : nullptr};
@@ -324,11 +334,14 @@ int run_sqrt_f32(Run& r) {
   float* Y[2] = {r.at<float>(P.o_y[0]), r.at<float>(P.o_y[1])};
   float* R = r.at<float>(P.o_r);
   float* Q = P.d == 2 ? r.at<float>(P.o_q) : nullptr;
-  const int nparts = (Sp / T) * (Sp / T);
+  // X_k, Y_k, R_k and Q_k are polynomials in A: they commute and every product here is symmetric
+  const int sym = f32_sym();
+  const int nparts = sym_parts(Sp / T, sym);
   int cur = 0;
   for (int k = 0; k <= r.max_iters; ++k) {
     if (k == r.max_iters && r.tol <= 0.0) break;
     GemmDesc g = f32_desc(r, Y[cur], Sp, SS, X[cur], Sp, SS, Sp, Sp, Sp, 0);    // G = Y X
+    g.sym = sym;
     g.epi = EPI_RESIDUAL; g.C = R; g.strideC = SS; g.ldc = Sp; g.rho_part = r.rho;
     { ProfScope ps(PK_F32_RESID, r.s); CHECK_LAUNCH(launch_gemm_f32(g, T, T, r.s)); }
     if (r.fit_needed(k)) CHECK_LAUNCH(r.chain(R, k));
@@ -337,17 +350,18 @@ int run_sqrt_f32(Run& r) {
     const float* Pm = R;
     if (P.d == 2) {
       GemmDesc q = f32_desc(r, R, Sp, SS, R, Sp, SS, Sp, Sp, Sp, 0);
+      q.sym = sym;
       q.epi = EPI_POLYQ; q.C = Q; q.strideC = SS; q.ldc = Sp; q.Cin = R; q.strideCin = SS; q.ldcin = Sp; q.c1 = 0.5f;
       { ProfScope ps(PK_F32_POLYQ, r.s); CHECK_LAUNCH(launch_gemm_f32(q, T, T, r.s)); }
       Pm = Q;
     }
     GemmDesc ax = f32_desc(r, X[cur], Sp, SS, Pm, Sp, SS, Sp, Sp, Sp, 0);        // X + X Q
     ax.epi = EPI_AXPY; ax.C = X[cur ^ 1]; ax.strideC = SS; ax.ldc = Sp; ax.Cin = X[cur]; ax.strideCin = SS; ax.ldcin = Sp;
-    ax.coef_is_alpha = P.d == 1;
+    ax.coef_is_alpha = P.d == 1; ax.sym = sym;
     { ProfScope ps(PK_F32_APPLY, r.s); CHECK_LAUNCH(launch_gemm_f32(ax, T, T, r.s)); }
     GemmDesc ay = f32_desc(r, Pm, Sp, SS, Y[cur], Sp, SS, Sp, Sp, Sp, 0);        // Y + Q Y
     ay.epi = EPI_AXPY; ay.C = Y[cur ^ 1]; ay.strideC = SS; ay.ldc = Sp; ay.Cin = Y[cur]; ay.strideCin = SS; ay.ldcin = Sp;
-    ay.coef_is_alpha = P.d == 1;
+    ay.coef_is_alpha = P.d == 1; ay.sym = sym;
     { ProfScope ps(PK_F32_APPLY, r.s); CHECK_LAUNCH(launch_gemm_f32(ay, T, T, r.s)); }
     cur ^= 1;
   }
@@ -372,7 +386,7 @@ int run_inv_root_f32(Run& r) {
     if (k == r.max_iters) break;
     GemmDesc ax = f32_desc(r, X[cur], Sp, SS, R, Sp, SS, Sp, Sp, Sp, 0);         // X (I + alpha R)
     ax.epi = EPI_AXPY; ax.C = X[cur ^ 1]; ax.strideC = SS; ax.ldc = Sp; ax.Cin = X[cur]; ax.strideCin = SS; ax.ldcin = Sp;
-    ax.coef_is_alpha = 1;
+    ax.coef_is_alpha = 1; ax.sym = f32_sym();   // X_k and R_k commute; the power chain below keeps all tiles
     { ProfScope ps(PK_F32_APPLY, r.s); CHECK_LAUNCH(launch_gemm_f32(ax, T, T, r.s)); }
     // (I + alpha R)^p = I + E_p, built on the part beyond the identity so that fp32 rounding acts
     // on the small quantity only: E_1 = alpha R, squaring E <- 2E + E E, times T: E <- E + E_1 + E E_1
@@ -456,6 +470,10 @@ int run(int fn, void* a, void* inv_out, int root_p, int batch, int m, int n, int
     }
   }
   { ProfScope ps(PK_PREP, r.s); launch_sumsq(pa, r.s); launch_prepare(pa, r.s); }
+  if (P.p_s > 0 && max_iters > r.warm) {
+    ProfScope ps(PK_SKETCH, r.s);
+    launch_sketch(r.v0, P.Sp, P.S, P.ld, P.p_s, seed, r.warm, max_iters - r.warm, P.fn, r.s);
+  }
   rc = check_hip();
   if (rc != PRISM_OK) return rc;
   if (dt == PRISM_BF16) rc = run_polar_bf16(r);
@@ -533,7 +551,7 @@ int prism_inv_root_ex(void* a, int root_p, int batch, int m, int n, prism_dtype 
 
 int prism_sketch(float* out, int n, int sketch_dim, uint64_t seed, int k, int fn, void* stream) {
   if (!out || n <= 0 || sketch_dim <= 0 || sketch_dim > PRISM_MAX_SKETCH || k < 0) return PRISM_EINVAL;
-  launch_sketch(out, n, n, sketch_dim, sketch_dim, seed, k, fn, (hipStream_t)stream);
+  launch_sketch(out, n, n, sketch_dim, sketch_dim, seed, k, 1, fn, (hipStream_t)stream);
   return check_hip();
 }
 
@@ -552,9 +570,9 @@ int prism_chain_product(const float* R, const float* V, float* out, int batch, i
 int prism_gemm_f32(const float* A, const float* B, float* C, int batch, int M, int N, int K, int a_km, void* stream) {
   if (!A || !B || !C || batch <= 0 || M <= 0 || N <= 0 || K <= 0) return PRISM_EINVAL;
   GemmDesc g = {};
-  g.A = A; g.strideA = (long long)M * K; g.lda = a_km ? M : K;
+  g.A = A; g.strideA = (long long)M * K; g.lda = (a_km & 1) ? M : K;
   g.B = B; g.strideB = (long long)K * N; g.ldb = N;
-  g.M = M; g.N = N; g.K = K; g.a_km = a_km; g.batch = batch; g.epi = EPI_STORE;
+  g.M = M; g.N = N; g.K = K; g.a_km = a_km & 1; g.sym = (a_km >> 1) & 1; g.batch = batch; g.epi = EPI_STORE;
   g.C = C; g.strideC = (long long)M * N; g.ldc = N;
   const int tn = (N == 16 || N == 32 || N == 64) ? N : 128;
   return launch_gemm_f32(g, (tn == 64 && M % 128) ? 64 : 128, tn, (hipStream_t)stream);

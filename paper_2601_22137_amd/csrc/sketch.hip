@@ -107,6 +107,8 @@ __global__ void sketch_kernel(float* v0, int rows_total, int n, int ld, int p_s,
   const int groups = (ld + 3) / 4;
   const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
   if (idx >= (long long)rows_total * groups) return;
+  iter += blockIdx.y;                                   // one sketch per blockIdx.y
+  v0 += (long long)blockIdx.y * rows_total * ld;
   const int j = (int)(idx / groups), q = (int)(idx % groups);
   float z[4] = {0.0f, 0.0f, 0.0f, 0.0f};
   if (j < n && 4 * q < p_s) {
@@ -136,12 +138,12 @@ __global__ void gauss_parts_kernel(unsigned int first, unsigned int count, doubl
 
 }  // namespace
 
-void launch_sketch(float* v0, int rows_total, int n, int ld, int p_s, uint64_t seed, int k, int fn,
+void launch_sketch(float* v0, int rows_total, int n, int ld, int p_s, uint64_t seed, int k_first, int k_count, int fn,
                    hipStream_t s) {
   const long long total = (long long)rows_total * ((ld + 3) / 4);
   const int nb = (int)((total + 255) / 256);
-  hipLaunchKernelGGL(sketch_kernel, dim3(nb), dim3(256), 0, s, v0, rows_total, n, ld, p_s,
-                     (unsigned int)(seed & 0xFFFFFFFFull), (unsigned int)(seed >> 32), (unsigned int)k,
+  hipLaunchKernelGGL(sketch_kernel, dim3(nb, k_count), dim3(256), 0, s, v0, rows_total, n, ld, p_s,
+                     (unsigned int)(seed & 0xFFFFFFFFull), (unsigned int)(seed >> 32), (unsigned int)k_first,
                      (unsigned int)fn);
 }
 

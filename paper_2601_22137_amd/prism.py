@@ -173,12 +173,12 @@ def chain_product(R, V):
     return out
 
 
-def gemm_f32(A, B, a_km=False):
+def gemm_f32(A, B, a_km=False, sym=False):
     batch = A.shape[0]
     M, K = (A.shape[2], A.shape[1]) if a_km else (A.shape[1], A.shape[2])
     N = B.shape[2]
     C = torch.empty((batch, M, N), dtype=torch.float32, device=A.device)
-    _check(lib().prism_gemm_f32(A.data_ptr(), B.data_ptr(), C.data_ptr(), batch, M, N, K, int(a_km), _stream()))
+    _check(lib().prism_gemm_f32(A.data_ptr(), B.data_ptr(), C.data_ptr(), batch, M, N, K, int(a_km) | (2 if sym else 0), _stream()))
     return C
 
 

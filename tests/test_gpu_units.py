@@ -33,6 +33,22 @@ def test_gemm_f32(prism, a_km, shape):
     assert np.linalg.norm(C - ref) / np.linalg.norm(ref) < 1e-6
 
 
+@pytest.mark.parametrize("a_km", [False, True])
+@pytest.mark.parametrize("n,K", [(128, 64), (384, 208), (64, 48)])
+def test_gemm_f32_symmetric(prism, a_km, n, K):
+    """A A^T (or A^T A) through the variant that computes the upper triangle of tiles only."""
+    rng = np.random.default_rng(n + K)
+    A = rng.standard_normal((3, n, K)).astype(np.float32)
+    At = np.ascontiguousarray(A.transpose(0, 2, 1))
+    C = prism.gemm_f32(_dev(At if a_km else A), _dev(At), a_km=a_km, sym=True).cpu().numpy()
+    ref = A.astype(np.float64) @ At.astype(np.float64)
+    assert np.linalg.norm(C - ref) / np.linalg.norm(ref) < 1e-6
+    full = prism.gemm_f32(_dev(At if a_km else A), _dev(At), a_km=a_km).cpu().numpy()
+    iu = np.triu_indices(n)
+    assert np.array_equal(C[:, iu[0], iu[1]], full[:, iu[0], iu[1]])      # the computed half is unchanged
+    assert np.array_equal(C, C.transpose(0, 2, 1))
+
+
 @pytest.mark.parametrize("n,ld", [(64, 16), (192, 32), (768, 16), (1024, 64), (4096, 32)])
 def test_chain_product(prism, n, ld):
     rng = np.random.default_rng(n + ld)
