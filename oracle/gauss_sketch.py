@@ -138,7 +138,7 @@ def box_muller(xa, xb):
     return (r * c).astype(np.float32), (r * s).astype(np.float32)
 
 
-TAG_POLAR, TAG_SQRT, TAG_INV_ROOT = 1, 2, 3
+TAG_POLAR, TAG_SQRT, TAG_INV_ROOT, TAG_SIGN, TAG_INVERSE = 1, 2, 3, 4, 5
 
 
 def sketch(seed, k, tag, p_s, n):

@@ -38,7 +38,13 @@ Readings of the paper taken here (the paper is silent or garbled):
     {l, u} U {roots in [l, u]} is taken, ties to the smallest alpha
     (PARITY UNPINNED by the paper);
   * m < n for the polar factor: run on the transpose (the paper assumes m >= n);
-  * the same S_k serves all matrices of a call.
+  * the same S_k serves all matrices of a call;
+  * Chebyshev inverse (App. A.4): the input is normalised by its Frobenius norm as the
+    text says, A_s = A / ||A||_F, X_0 = A_s^T, and the result is un-scaled at the end;
+    without a fit alpha_k is the Taylor value 1 (the classical iteration), which
+    is not the lower end of the printed interval [1/2, 2]; the objective is taken
+    with R_k symmetric (it is, for X_0 = A_s^T: R_k is a polynomial in A A^T), so
+    ||S h(R)||_F = ||h(R) S^T||_F and the chain again multiplies from the left.
 """
 from math import comb
 
@@ -154,6 +160,24 @@ def fit_coefficients_inv(R, M, St, p):
 def fit_alpha_inv(R, M, St, p):
     lo, hi = inv_root_interval(p)
     return minimize_poly_on_interval(fit_coefficients_inv(R, M, St, p), lo, hi)
+
+
+def fit_coefficients_cheb(R, G, St):
+    """Coefficients c_0, c_1, c_2 of the quadratic (App. A.4)
+        m(alpha) = || (R^2 - alpha (R^2 - R^3)) S^T ||_F^2,
+    R symmetric, G = I - R = A X:  W_0 = R^2 S^T,  W_1 = -(R^2 - R^3) S^T = -G R^2 S^T."""
+    V1 = R @ St
+    V2 = R @ V1
+    W0 = V2
+    W1 = -(G @ V2)
+    return np.array([np.sum(W0 * W0), 2.0 * np.sum(W0 * W1), np.sum(W1 * W1)])
+
+
+CHEB_INTERVAL = (0.5, 2.0)      # App. A.4
+
+
+def fit_alpha_cheb(R, G, St):
+    return minimize_poly_on_interval(fit_coefficients_cheb(R, G, St), *CHEB_INTERVAL)
 
 
 def _sketch_T(seed, k, tag, p_s, n, exact_fit):
@@ -322,3 +346,71 @@ def inv_root(A, p, max_iters=30, sketch_dim=8, seed=22137, tol=1e-6,
         M = np.linalg.matrix_power(T, p) @ M
         k += 1
     return X, loop.info()
+
+
+def sign(A, degree=5, max_iters=30, sketch_dim=8, seed=22137, tol=1e-6,
+         exact_fit=False, alpha_schedule=None):
+    """sign(A) = A (A^2)^{-1/2} of a square A with A^2 symmetric, by the PRISM
+    Newton-Schulz iteration of Section 4, eq. (2)-(4):
+        X_0 = A / ||A||_F,  R_k = I - X_k^2,  X_{k+1} = X_k g_d(R_k; alpha_k).
+    Returns (X, info)."""
+    A = np.asarray(A, dtype=np.float64)
+    bad = _precheck(A)
+    if bad is not None:
+        return A.copy(), _early(A, bad)
+    d = {3: 1, 5: 2}[degree]
+    n = A.shape[0]
+    X = A / np.linalg.norm(A, 'fro')
+    loop = _Loop(n, max_iters, tol)
+    k = 0
+    while True:
+        G = X @ X
+        R = np.eye(n) - G
+        if loop.stop(R, k):
+            break
+        if alpha_schedule is not None and k < len(alpha_schedule):
+            alpha = float(alpha_schedule[k])
+        elif sketch_dim == 0 and not exact_fit:
+            alpha = clamp_interval(d)[0]
+        else:
+            St = _sketch_T(seed, k, gauss_sketch.TAG_SIGN, sketch_dim, n, exact_fit)
+            alpha = fit_alpha_ns(R, G, St, d)
+        loop.alpha.append(alpha)
+        X = X @ g_poly(R, d, alpha)
+        k += 1
+    return X, loop.info()
+
+
+def inverse(A, max_iters=30, sketch_dim=8, seed=22137, tol=1e-6,
+            exact_fit=False, alpha_schedule=None):
+    """A^{-1} of a full-rank square A by the PRISM Chebyshev iteration
+    (Table 1, row "Chebyshev"; App. A.4):  A_s = A / s (s = ||A||_F),
+        X_0 = A_s^T,  R_k = I - A_s X_k,  X_{k+1} = X_k (I + R_k + alpha_k R_k^2),
+    and A^{-1} = X / s.  Returns (X / s, info)."""
+    A = np.asarray(A, dtype=np.float64)
+    bad = _precheck(A)
+    if bad is not None:
+        return A.copy(), _early(A, bad)
+    n = A.shape[0]
+    s = np.linalg.norm(A, 'fro')
+    As = A / s
+    X = As.T.copy()
+    loop = _Loop(n, max_iters, tol)
+    k = 0
+    while True:
+        G = As @ X
+        R = np.eye(n) - G
+        if loop.stop(R, k):
+            break
+        if alpha_schedule is not None and k < len(alpha_schedule):
+            alpha = float(alpha_schedule[k])
+        elif sketch_dim == 0 and not exact_fit:
+            alpha = 1.0
+        else:
+            St = _sketch_T(seed, k, gauss_sketch.TAG_INVERSE, sketch_dim, n, exact_fit)
+            alpha = fit_alpha_cheb(R, G, St)
+        loop.alpha.append(alpha)
+        R2 = R @ R
+        X = X @ (np.eye(n) + R + alpha * R2)
+        k += 1
+    return X / s, loop.info()
