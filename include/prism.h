@@ -63,7 +63,9 @@ typedef enum {
 } prism_status;
 
 /* function ids; also the function tag of the sketch counter */
-typedef enum { PRISM_FN_POLAR = 1, PRISM_FN_SQRT = 2, PRISM_FN_INV_ROOT = 3 } prism_fn;
+typedef enum {
+  PRISM_FN_POLAR = 1, PRISM_FN_SQRT = 2, PRISM_FN_INV_ROOT = 3, PRISM_FN_SIGN = 4, PRISM_FN_INVERSE = 5
+} prism_fn;
 
 enum {
   PRISM_INFO_CONVERGED = 0, /* residual <= tol after `iters` updates */
@@ -97,6 +99,10 @@ typedef struct {
   void* workspace;        /* device memory, 256-byte aligned, or NULL for the cached one */
   size_t workspace_bytes; /* size of `workspace` */
   prism_info* info;       /* device array of `batch` entries, or NULL */
+  const float* alpha_schedule; /* HOST array, read before the call returns, or NULL: update k <
+                                * schedule_len uses alpha_schedule[k] as given (no fit, no clamp);
+                                * fixed-coefficient schemes run through the same kernels this way */
+  int32_t schedule_len;   /* 0 <= schedule_len <= PRISM_MAX_ITERS */
 } prism_options;
 
 /* Device bytes a call with these arguments needs (host-only computation). */
@@ -128,6 +134,26 @@ int prism_inv_root(void* a, int root_p, int batch, int m, int n, prism_dtype dt,
 int prism_inv_root_ex(void* a, int root_p, int batch, int m, int n, prism_dtype dt, int degree,
                       int max_iters, int sketch_dim, uint64_t seed, double tol, void* stream,
                       const prism_options* opt);
+
+/* Matrix sign (Section 4, eq. (2)-(4)): x[batch][n][n], square with x^2 symmetric, is replaced
+ * in place by sign(x) = x (x^2)^{-1/2}.  X_0 = x / ||x||_F, R_k = I - X_k^2,
+ * X_{k+1} = X_k g_d(R_k; alpha_k).  m must equal n; fp32 only (bf16: PRISM_EUNSUPPORTED). */
+int prism_sign(void* x, int batch, int m, int n, prism_dtype dt, int degree, int max_iters,
+               int sketch_dim, uint64_t seed, double tol, void* stream);
+int prism_sign_ex(void* x, int batch, int m, int n, prism_dtype dt, int degree, int max_iters,
+                  int sketch_dim, uint64_t seed, double tol, void* stream,
+                  const prism_options* opt);
+
+/* Inverse by the PRISM Chebyshev iteration (Table 1, "Chebyshev"; App. A.4): a[batch][n][n],
+ * square and of full rank (symmetry is not needed), is replaced in place by a^{-1}.
+ * A_s = a / ||a||_F, X_0 = A_s^T, R_k = I - A_s X_k, X_{k+1} = X_k (I + R_k + alpha_k R_k^2),
+ * alpha_k in [1/2, 2] minimises the sketched next residual (a quadratic); sketch_dim = 0
+ * keeps alpha_k = 1, the classical iteration.  m must equal n; fp32 only. */
+int prism_inverse(void* a, int batch, int m, int n, prism_dtype dt, int max_iters, int sketch_dim,
+                  uint64_t seed, double tol, void* stream);
+int prism_inverse_ex(void* a, int batch, int m, int n, prism_dtype dt, int max_iters,
+                     int sketch_dim, uint64_t seed, double tol, void* stream,
+                     const prism_options* opt);
 
 /* ---- single steps of the path, exposed for unit tests and profiling ---- */
 

@@ -113,7 +113,8 @@ struct SolveArgs {
   prism_info* info;
   double tol;
   int max_iters;
-  int mode;          // 0 fit, 1 alpha = l (no sketch), 2 alpha = u (warm start)
+  int mode;          // 0 fit, 1 Taylor alpha (no sketch), 2 alpha = u (warm start), 3 alpha = sched_alpha
+  float sched_alpha; // mode 3: the caller's coefficient for this update
   int last;          // this is the residual-only evaluation at k = max_iters
   double* cpart;     // [batch][ngroups][17] partial coefficient sums (moments -> solve)
   int ngroups;
@@ -131,7 +132,7 @@ struct PrepArgs {
   double* sumsq_part; int nsum;             // [batch][nsum]
   Ctrl* ctrl; prism_info* info;
   // outputs (which are used depends on fn/dt)
-  float* X32; float* Y32; double* M64; float* R32;   // fp32 paths
+  float* X32; float* Y32; double* M64; float* R32;   // fp32 paths (inverse: Y32 = A / ||A||_F)
   uint16_t* Xa_hi; uint16_t* Xa_lo; uint16_t* Xg;    // bf16 polar
   float* rho_part; int tile;                // inverse root: residual of M_0
 };

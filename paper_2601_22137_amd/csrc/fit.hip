@@ -1,4 +1,4 @@
-// The per-iteration coefficient fit of PRISM (paper Section 4.2, eq. (4); App. A.1 and A.3)
+// The per-iteration coefficient fit of PRISM (paper Section 4.2, eq. (4); App. A.1, A.3 and A.4)
 // after the sketch chain V_j = R V_{j-1} has been formed:
 //   moments_kernel (a few workgroups per matrix) forms the blocks W_i = u_i(R) S^T from the chain
 //      (the factor (1 - xi) = G = I - R is applied as V_j - V_{j+1}) and accumulates
@@ -25,7 +25,8 @@ __device__ inline double horner(const double* c, int deg, double x) {
   return v;
 }
 
-// KIND 1, 2: Newton-Schulz family with d = KIND.  KIND = 10 + p: coupled inverse Newton.
+// Blocks<d>: Newton-Schulz family (polar, square root, sign).  BlocksInv<p>: coupled inverse
+// Newton.  BlocksCheb: Chebyshev inverse.
 template <int KIND> struct Blocks;
 template <> struct Blocks<1> {
   static constexpr int NV = 3, NW = 3;
@@ -41,6 +42,13 @@ template <> struct Blocks<2> {
     w[0] = (3.0 * v[1] + v[2]) * 0.25;
     w[1] = -((2.0 * v[1] + v[2]) - (2.0 * v[2] + v[3]));
     w[2] = -(v[3] - v[4]);
+  }
+};
+struct BlocksCheb {   // App. A.4: W_0 = R^2 S^T, W_1 = -(R^2 - R^3) S^T
+  static constexpr int NV = 3, NW = 2;
+  __device__ static void make(const double* v, double* w) {
+    w[0] = v[1];
+    w[1] = -(v[1] - v[2]);
   }
 };
 template <int P> struct BlocksInv {
@@ -90,11 +98,7 @@ __device__ void accumulate_coefficients(const SolveArgs& a, int b, int grp, int 
   }
 }
 
-// grid (groups, batch): partial coefficient sums of one matrix, groups interleaved over the elements
-__global__ __launch_bounds__(NT) void moments_kernel(SolveArgs a) {
-  const int b = blockIdx.y, grp = blockIdx.x, ngrp = gridDim.x;
-  if (a.ctrl[b].done) return;
-  double* out = a.cpart + ((long long)b * ngrp + grp) * MAXC;
+__device__ void accumulate_for(const SolveArgs& a, int b, int grp, int ngrp, double* out) {
   if (a.fn == PRISM_FN_INV_ROOT) {
     switch (a.p) {
       case 1: accumulate_coefficients<BlocksInv<1>>(a, b, grp, ngrp, out); break;
@@ -106,11 +110,20 @@ __global__ __launch_bounds__(NT) void moments_kernel(SolveArgs a) {
       case 7: accumulate_coefficients<BlocksInv<7>>(a, b, grp, ngrp, out); break;
       default: accumulate_coefficients<BlocksInv<8>>(a, b, grp, ngrp, out); break;
     }
+  } else if (a.fn == PRISM_FN_INVERSE) {
+    accumulate_coefficients<BlocksCheb>(a, b, grp, ngrp, out);
   } else if (a.d == 1) {
     accumulate_coefficients<Blocks<1>>(a, b, grp, ngrp, out);
   } else {
     accumulate_coefficients<Blocks<2>>(a, b, grp, ngrp, out);
   }
+}
+
+// grid (groups, batch): partial coefficient sums of one matrix, groups interleaved over the elements
+__global__ __launch_bounds__(NT) void moments_kernel(SolveArgs a) {
+  const int b = blockIdx.y, grp = blockIdx.x, ngrp = gridDim.x;
+  if (a.ctrl[b].done) return;
+  accumulate_for(a, b, grp, ngrp, a.cpart + ((long long)b * ngrp + grp) * MAXC);
 }
 
 __global__ __launch_bounds__(NT) void solve_kernel(SolveArgs a) {
@@ -165,37 +178,24 @@ __global__ __launch_bounds__(NT) void solve_kernel(SolveArgs a) {
 
   double lo, hi;
   if (a.fn == PRISM_FN_INV_ROOT) { lo = 1.0 / a.p; hi = 2.0 / a.p; }
+  else if (a.fn == PRISM_FN_INVERSE) { lo = 0.5; hi = 2.0; }
   else if (a.d == 1) { lo = 0.5; hi = 1.0; }
   else { lo = 0.375; hi = 1.45; }
 
   if (a.mode != 0) {
     if (t == 0) {
-      const double al = (a.mode == 1) ? lo : hi;
-      ctl->alpha = (float)al;
-      info->alpha[a.k] = (float)al;
+      // without a fit: the Taylor coefficient, which is l except for the Chebyshev inverse (1)
+      const double taylor = (a.fn == PRISM_FN_INVERSE) ? 1.0 : lo;
+      const float al = (a.mode == 3) ? a.sched_alpha : (float)((a.mode == 1) ? taylor : hi);
+      ctl->alpha = al;
+      info->alpha[a.k] = al;
     }
     return;
   }
 
-  const int nc = (a.fn == PRISM_FN_INV_ROOT) ? 2 * a.p + 1 : 5;
+  const int nc = (a.fn == PRISM_FN_INV_ROOT) ? 2 * a.p + 1 : (a.fn == PRISM_FN_INVERSE ? 3 : 5);
   if (a.ngroups == 1) {   // small matrices: the moments are accumulated right here
-    double* out = a.cpart + (long long)b * MAXC;
-    if (a.fn == PRISM_FN_INV_ROOT) {
-      switch (a.p) {
-        case 1: accumulate_coefficients<BlocksInv<1>>(a, b, 0, 1, out); break;
-        case 2: accumulate_coefficients<BlocksInv<2>>(a, b, 0, 1, out); break;
-        case 3: accumulate_coefficients<BlocksInv<3>>(a, b, 0, 1, out); break;
-        case 4: accumulate_coefficients<BlocksInv<4>>(a, b, 0, 1, out); break;
-        case 5: accumulate_coefficients<BlocksInv<5>>(a, b, 0, 1, out); break;
-        case 6: accumulate_coefficients<BlocksInv<6>>(a, b, 0, 1, out); break;
-        case 7: accumulate_coefficients<BlocksInv<7>>(a, b, 0, 1, out); break;
-        default: accumulate_coefficients<BlocksInv<8>>(a, b, 0, 1, out); break;
-      }
-    } else if (a.d == 1) {
-      accumulate_coefficients<Blocks<1>>(a, b, 0, 1, out);
-    } else {
-      accumulate_coefficients<Blocks<2>>(a, b, 0, 1, out);
-    }
+    accumulate_for(a, b, 0, 1, a.cpart + (long long)b * MAXC);
     __threadfence_block();
     __syncthreads();
   }

@@ -1,7 +1,9 @@
 // Entry and exit of the PRISM iterations: Frobenius norm of the input, initial iterates
 // (paper Section 3: X_0 = A / ||A||_F; App. A.3: X_0 = I / c, M_0 = A / c^p with
 // c = (2 ||A||_F / (p+1))^(1/p)), copy into the padded internal layouts, and the final
-// un-scaling / copy-out (A^{1/2} = sqrt(s) X, A^{-1/2} = Y / sqrt(s)).
+// un-scaling / copy-out (A^{1/2} = sqrt(s) X, A^{-1/2} = Y / sqrt(s)).  Matrix sign (Section 4)
+// starts like the polar factor; the Chebyshev inverse (App. A.4) keeps A_s = A / ||A||_F, starts
+// from X_0 = A_s^T and returns X / ||A||_F.
 #include "common.h"
 
 namespace prism {
@@ -111,7 +113,12 @@ __global__ __launch_bounds__(NT) void prepare_kernel(PrepArgs a) {
       v = load_src(a.src, a.dt, (long long)b * mat + si) * scale;
     }
     const long long o = (long long)b * a.Lp * a.Sp + (long long)r * a.Sp + c;
-    if (a.fn == PRISM_FN_POLAR) {
+    if (a.fn == PRISM_FN_SIGN) {
+      a.X32[o] = (float)v;
+    } else if (a.fn == PRISM_FN_INVERSE) {
+      a.Y32[o] = (float)v;                                                                    // A_s
+      a.X32[(long long)b * a.Lp * a.Sp + (long long)c * a.Sp + r] = (float)v;                 // X_0 = A_s^T
+    } else if (a.fn == PRISM_FN_POLAR) {
       if (a.dt == PRISM_BF16) {
         const unsigned short hi = f2bf((float)v);
         a.Xa_hi[o] = hi;
@@ -273,7 +280,9 @@ __global__ __launch_bounds__(NT) void finalize_kernel(FinalArgs a) {
   const int r = (int)(i / a.n), col = (int)(i % a.n);
   const long long o = (long long)b * a.Lp * a.Sp +
                       (a.transpose ? ((long long)col * a.Sp + r) : ((long long)r * a.Sp + col));
-  if (a.fn == PRISM_FN_POLAR) {
+  if (a.fn == PRISM_FN_INVERSE) {
+    ((float*)a.dst)[(long long)b * mat + i] = (float)((double)a.X32[par][o] / c.norm);
+  } else if (a.fn == PRISM_FN_POLAR) {
     if (a.dt == PRISM_BF16) {
       float x = bf2f(a.Xa_hi[par][o]);
       if (a.Xa_lo[par]) x += bf2f(a.Xa_lo[par][o]);

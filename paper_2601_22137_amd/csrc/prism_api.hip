@@ -1,5 +1,5 @@
 // Host side of libprism: argument checks, workspace layout and the launch sequences of the
-// three PRISM iterations (paper Table 1; App. A.1, A.3).  Every call only enqueues kernels on
+// PRISM iterations (paper Table 1; Section 4; App. A.1, A.3, A.4).  Every call only enqueues kernels on
 // the caller's stream: the whole budget of iterations is enqueued up front and each kernel
 // skips matrices whose `done` flag the on-device solve step has set, so there is no host
 // round trip per iteration.
@@ -64,7 +64,7 @@ int make_plan(Plan& P, int fn, int batch, int m, int n, int dt, int degree, int 
   if (degree != 3 && degree != 5) return PRISM_EINVAL;
   if (sketch_dim < 0 || sketch_dim > PRISM_MAX_SKETCH) return PRISM_EINVAL;
   if (dt != PRISM_F32 && dt != PRISM_BF16) return PRISM_EINVAL;
-  if (fn != PRISM_FN_POLAR && fn != PRISM_FN_SQRT && fn != PRISM_FN_INV_ROOT) return PRISM_EINVAL;
+  if (fn < PRISM_FN_POLAR || fn > PRISM_FN_INVERSE) return PRISM_EINVAL;
   if (fn != PRISM_FN_POLAR && m != n) return PRISM_EINVAL;
   if (fn == PRISM_FN_INV_ROOT && (root_p < 1 || root_p > PRISM_MAX_ROOT || degree != 3)) return PRISM_EINVAL;
   if (fn != PRISM_FN_POLAR && dt == PRISM_BF16) return PRISM_EUNSUPPORTED;
@@ -78,7 +78,7 @@ int make_plan(Plan& P, int fn, int batch, int m, int n, int dt, int degree, int 
   P.p = fn == PRISM_FN_INV_ROOT ? root_p : 0;
   P.p_s = sketch_dim;
   P.ld = sketch_dim <= 16 ? 16 : (sketch_dim <= 32 ? 32 : 64);
-  P.nv = fn == PRISM_FN_INV_ROOT ? root_p + 1 : 2 * P.d + 1;
+  P.nv = fn == PRISM_FN_INV_ROOT ? root_p + 1 : (fn == PRISM_FN_INVERSE ? 3 : 2 * P.d + 1);
   P.split = (dt == PRISM_BF16) && !(flags & PRISM_FLAG_BF16_PLAIN_ITERATE);
   if (dt == PRISM_BF16) {
     P.tile = P.S >= 512 ? 256 : 128;   // padding granularity; the tile is chosen per launch
@@ -113,10 +113,15 @@ int make_plan(Plan& P, int fn, int batch, int m, int n, int dt, int degree, int 
     P.o_r = take(B * SS * 4);
     P.o_rb = take(B * SS * 2);
     P.o_qb = P.d == 2 ? take(B * SS * 2) : 0;
-  } else if (fn == PRISM_FN_POLAR) {
+  } else if (fn == PRISM_FN_POLAR || fn == PRISM_FN_SIGN) {
     for (int i = 0; i < 2; ++i) P.o_x[i] = take(B * LS * 4);
     P.o_r = take(B * SS * 4);
     P.o_q = P.d == 2 ? take(B * SS * 4) : 0;
+  } else if (fn == PRISM_FN_INVERSE) {
+    for (int i = 0; i < 2; ++i) P.o_x[i] = take(B * SS * 4);
+    P.o_y[0] = take(B * SS * 4);     // A / ||A||_F
+    P.o_r = take(B * SS * 4);
+    P.o_q = take(B * SS * 4);
   } else if (fn == PRISM_FN_SQRT) {
     for (int i = 0; i < 2; ++i) { P.o_x[i] = take(B * SS * 4); P.o_y[i] = take(B * SS * 4); }
     P.o_r = take(B * SS * 4);
@@ -181,6 +186,8 @@ struct Run {
   float* v0;
   float* v;
   int max_iters, warm;
+  const float* sched; int sched_len;   // caller's coefficients for the leading updates (host array)
+  int first_fit;                       // first update whose coefficient is fitted
   double tol;
   uint64_t seed;
 
@@ -191,7 +198,7 @@ struct Run {
     const int Sp = P.Sp, ld = P.ld;
     const long long vs = (long long)P.batch * Sp * ld;
     for (int j = 1; j <= P.nv; ++j) {
-      const float* vin = (j == 1) ? v0 + (long long)(k - warm) * Sp * ld : v + (j - 2) * vs;
+      const float* vin = (j == 1) ? v0 + (long long)(k - first_fit) * Sp * ld : v + (j - 2) * vs;
       const long long sin = (j == 1) ? 0 : (long long)Sp * ld;
       ProfScope ps(PK_CHAIN, s);
       CHECK_LAUNCH(launch_chain(R, (long long)Sp * Sp, Sp, vin, sin, v + (j - 1) * vs, (long long)Sp * ld, Sp, ld,
@@ -206,13 +213,14 @@ struct Run {
     a.V = v; a.vstride = (long long)P.batch * P.Sp * P.ld; a.bstride = (long long)P.Sp * P.ld;
     a.rho_part = rho; a.nparts = nparts;
     a.ctrl = ctrl; a.info = info; a.tol = tol; a.max_iters = max_iters;
-    a.mode = P.p_s == 0 ? 1 : (k < warm ? 2 : 0);
+    a.mode = k < sched_len ? 3 : (P.p_s == 0 ? 1 : (k < warm ? 2 : 0));
+    a.sched_alpha = k < sched_len ? sched[k] : 0.0f;
     a.last = (k == max_iters);
     a.cpart = at<double>(P.o_cpart); a.ngroups = P.ngroups;
     { ProfScope ps(PK_SOLVE, s); if (a.mode == 0 && !a.last && a.ngroups > 1) launch_moments(a, P.batch, s); launch_solve(a, P.batch, s); }
     return check_hip();
   }
-  bool fit_needed(int k) const { return P.p_s > 0 && k >= warm && k < max_iters; }
+  bool fit_needed(int k) const { return P.p_s > 0 && k >= first_fit && k < max_iters; }
 };
 
 GemmDesc f32_desc(const Run& r, const float* A, int lda, long long sa, const float* B, int ldb, long long sb,
@@ -243,7 +251,8 @@ int run_polar_f32(Run& r) {
   int cur = 0;
   for (int k = 0; k <= r.max_iters; ++k) {
     if (k == r.max_iters && r.tol <= 0.0) break;
-    GemmDesc g = f32_desc(r, X[cur], Sp, LS, X[cur], Sp, LS, Sp, Sp, Lp, 1);   // G = X^T X
+    // G = X^T X; matrix sign: G = X X, symmetric by assumption on the input
+    GemmDesc g = f32_desc(r, X[cur], Sp, LS, X[cur], Sp, LS, Sp, Sp, Lp, P.fn == PRISM_FN_SIGN ? 0 : 1);
     g.sym = sym;
     g.epi = EPI_RESIDUAL; g.C = R; g.strideC = SS; g.ldc = Sp; g.rho_part = r.rho;
     { ProfScope ps(PK_F32_RESID, r.s); CHECK_LAUNCH(launch_gemm_f32(g, T, T, r.s)); }
@@ -368,6 +377,40 @@ int run_sqrt_f32(Run& r) {
   return PRISM_OK;
 }
 
+// Chebyshev inverse (App. A.4): R = I - A_s X, Q = R + alpha R^2, X <- X + X Q
+int run_inverse_f32(Run& r) {
+  const Plan& P = r.P;
+  const int Sp = P.Sp, T = P.tile;
+  const long long SS = (long long)Sp * Sp;
+  float* X[2] = {r.at<float>(P.o_x[0]), r.at<float>(P.o_x[1])};
+  const float* As = r.at<float>(P.o_y[0]);
+  float* R = r.at<float>(P.o_r);
+  float* Q = r.at<float>(P.o_q);
+  // X_k = A_s^T q(A_s A_s^T): A_s X_k, R_k and Q_k are symmetric, X_k Q_k is not
+  const int sym = f32_sym();
+  const int nparts = sym_parts(Sp / T, sym);
+  int cur = 0;
+  for (int k = 0; k <= r.max_iters; ++k) {
+    if (k == r.max_iters && r.tol <= 0.0) break;
+    GemmDesc g = f32_desc(r, As, Sp, SS, X[cur], Sp, SS, Sp, Sp, Sp, 0);
+    g.sym = sym;
+    g.epi = EPI_RESIDUAL; g.C = R; g.strideC = SS; g.ldc = Sp; g.rho_part = r.rho;
+    { ProfScope ps(PK_F32_RESID, r.s); CHECK_LAUNCH(launch_gemm_f32(g, T, T, r.s)); }
+    if (r.fit_needed(k)) CHECK_LAUNCH(r.chain(R, k));
+    CHECK_LAUNCH(r.solve(k, nparts));
+    if (k == r.max_iters) break;
+    GemmDesc q = f32_desc(r, R, Sp, SS, R, Sp, SS, Sp, Sp, Sp, 0);
+    q.sym = sym;
+    q.epi = EPI_POLYQ; q.C = Q; q.strideC = SS; q.ldc = Sp; q.Cin = R; q.strideCin = SS; q.ldcin = Sp; q.c1 = 1.0f;
+    { ProfScope ps(PK_F32_POLYQ, r.s); CHECK_LAUNCH(launch_gemm_f32(q, T, T, r.s)); }
+    GemmDesc ax = f32_desc(r, X[cur], Sp, SS, Q, Sp, SS, Sp, Sp, Sp, 0);
+    ax.epi = EPI_AXPY; ax.C = X[cur ^ 1]; ax.strideC = SS; ax.ldc = Sp; ax.Cin = X[cur]; ax.strideCin = SS; ax.ldcin = Sp;
+    { ProfScope ps(PK_F32_APPLY, r.s); CHECK_LAUNCH(launch_gemm_f32(ax, T, T, r.s)); }
+    cur ^= 1;
+  }
+  return PRISM_OK;
+}
+
 int run_inv_root_f32(Run& r) {
   const Plan& P = r.P;
   const int Sp = P.Sp, T = P.tile, p = P.p;
@@ -430,6 +473,8 @@ int run(int fn, void* a, void* inv_out, int root_p, int batch, int m, int n, int
   if (max_iters < 0 || max_iters > PRISM_MAX_ITERS) return PRISM_EINVAL;
   if (!(tol == tol)) return PRISM_EINVAL;
   if (opt && opt->warm_iters < 0) return PRISM_EINVAL;
+  if (opt && (opt->schedule_len < 0 || opt->schedule_len > PRISM_MAX_ITERS || (opt->schedule_len > 0 && !opt->alpha_schedule)))
+    return PRISM_EINVAL;
   Run r;
   int rc = make_plan(r.P, fn, batch, m, n, dt, degree, sketch_dim, root_p, opt ? opt->flags : 0u);
   if (rc != PRISM_OK) return rc;
@@ -443,6 +488,9 @@ int run(int fn, void* a, void* inv_out, int root_p, int batch, int m, int n, int
   r.v0 = r.at<float>(P.o_v0);
   r.v = r.at<float>(P.o_v);
   r.max_iters = max_iters; r.tol = tol; r.seed = seed; r.warm = opt ? opt->warm_iters : 0;
+  r.sched = opt ? opt->alpha_schedule : nullptr;
+  r.sched_len = opt ? opt->schedule_len : 0;
+  r.first_fit = r.warm > r.sched_len ? r.warm : r.sched_len;
 
   PrepArgs pa = {};
   pa.fn = fn; pa.dt = dt; pa.batch = batch; pa.m = m; pa.n = n; pa.S = P.S; pa.L = P.L; pa.Sp = P.Sp; pa.Lp = P.Lp;
@@ -462,7 +510,7 @@ int run(int fn, void* a, void* inv_out, int root_p, int batch, int m, int n, int
     }
   } else {
     pa.X32 = r.at<float>(P.o_x[0]);
-    if (fn == PRISM_FN_SQRT) pa.Y32 = r.at<float>(P.o_y[0]);
+    if (fn == PRISM_FN_SQRT || fn == PRISM_FN_INVERSE) pa.Y32 = r.at<float>(P.o_y[0]);
     if (fn == PRISM_FN_INV_ROOT) { pa.M64 = r.at<double>(P.o_y[0]); pa.R32 = r.at<float>(P.o_r); }
     for (int i = 0; i < 2; ++i) {
       fa.X32[i] = r.at<float>(P.o_x[i]);
@@ -470,14 +518,15 @@ int run(int fn, void* a, void* inv_out, int root_p, int batch, int m, int n, int
     }
   }
   { ProfScope ps(PK_PREP, r.s); launch_sumsq(pa, r.s); launch_prepare(pa, r.s); }
-  if (P.p_s > 0 && max_iters > r.warm) {
+  if (P.p_s > 0 && max_iters > r.first_fit) {
     ProfScope ps(PK_SKETCH, r.s);
-    launch_sketch(r.v0, P.Sp, P.S, P.ld, P.p_s, seed, r.warm, max_iters - r.warm, P.fn, r.s);
+    launch_sketch(r.v0, P.Sp, P.S, P.ld, P.p_s, seed, r.first_fit, max_iters - r.first_fit, P.fn, r.s);
   }
   rc = check_hip();
   if (rc != PRISM_OK) return rc;
   if (dt == PRISM_BF16) rc = run_polar_bf16(r);
-  else if (fn == PRISM_FN_POLAR) rc = run_polar_f32(r);
+  else if (fn == PRISM_FN_POLAR || fn == PRISM_FN_SIGN) rc = run_polar_f32(r);
+  else if (fn == PRISM_FN_INVERSE) rc = run_inverse_f32(r);
   else if (fn == PRISM_FN_SQRT) rc = run_sqrt_f32(r);
   else rc = run_inv_root_f32(r);
   if (rc != PRISM_OK) return rc;
@@ -547,6 +596,23 @@ int prism_inv_root(void* a, int root_p, int batch, int m, int n, prism_dtype dt,
 int prism_inv_root_ex(void* a, int root_p, int batch, int m, int n, prism_dtype dt, int degree, int max_iters,
                       int sketch_dim, uint64_t seed, double tol, void* stream, const prism_options* opt) {
   return run(PRISM_FN_INV_ROOT, a, nullptr, root_p, batch, m, n, (int)dt, degree, max_iters, sketch_dim, seed, tol, stream, opt);
+}
+
+int prism_sign(void* x, int batch, int m, int n, prism_dtype dt, int degree, int max_iters, int sketch_dim,
+               uint64_t seed, double tol, void* stream) {
+  return run(PRISM_FN_SIGN, x, nullptr, 0, batch, m, n, (int)dt, degree, max_iters, sketch_dim, seed, tol, stream, nullptr);
+}
+int prism_sign_ex(void* x, int batch, int m, int n, prism_dtype dt, int degree, int max_iters, int sketch_dim,
+                  uint64_t seed, double tol, void* stream, const prism_options* opt) {
+  return run(PRISM_FN_SIGN, x, nullptr, 0, batch, m, n, (int)dt, degree, max_iters, sketch_dim, seed, tol, stream, opt);
+}
+int prism_inverse(void* a, int batch, int m, int n, prism_dtype dt, int max_iters, int sketch_dim, uint64_t seed,
+                  double tol, void* stream) {
+  return run(PRISM_FN_INVERSE, a, nullptr, 0, batch, m, n, (int)dt, 5, max_iters, sketch_dim, seed, tol, stream, nullptr);
+}
+int prism_inverse_ex(void* a, int batch, int m, int n, prism_dtype dt, int max_iters, int sketch_dim, uint64_t seed,
+                     double tol, void* stream, const prism_options* opt) {
+  return run(PRISM_FN_INVERSE, a, nullptr, 0, batch, m, n, (int)dt, 5, max_iters, sketch_dim, seed, tol, stream, opt);
 }
 
 int prism_sketch(float* out, int n, int sketch_dim, uint64_t seed, int k, int fn, void* stream) {

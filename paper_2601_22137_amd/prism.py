@@ -13,7 +13,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libprism.so")
 
 F32, BF16 = 0, 1
-FN_POLAR, FN_SQRT, FN_INV_ROOT = 1, 2, 3
+FN_POLAR, FN_SQRT, FN_INV_ROOT, FN_SIGN, FN_INVERSE = 1, 2, 3, 4, 5
 MAX_ITERS = 64
 FLAG_BF16_PLAIN_ITERATE = 1
 OK, EINVAL, EUNSUPPORTED, ENOMEM, EHIP = 0, 1, 2, 3, 4
@@ -23,7 +23,8 @@ INFO_DTYPE = np.dtype([("iters", np.int32), ("status", np.int32),
                        ("residual", np.float32, (MAX_ITERS + 1,)), ("alpha", np.float32, (MAX_ITERS,))])
 
 EXPORTS = ("prism_workspace_bytes", "prism_polar", "prism_polar_ex", "prism_sqrt", "prism_sqrt_ex",
-           "prism_inv_root", "prism_inv_root_ex", "prism_sketch", "prism_gauss_parts", "prism_chain_product", "prism_gemm_f32",
+           "prism_inv_root", "prism_inv_root_ex", "prism_sign", "prism_sign_ex", "prism_inverse", "prism_inverse_ex",
+           "prism_sketch", "prism_gauss_parts", "prism_chain_product", "prism_gemm_f32",
            "prism_gemm_f64a", "prism_gemm_bf16_nt", "prism_profile_enable", "prism_profile_collect",
            "prism_last_error")
 
@@ -33,7 +34,8 @@ PROFILE_KINDS = ("prep", "final", "sketch", "chain", "solve", "f32_resid", "f32_
 
 class Options(ctypes.Structure):
     _fields_ = [("flags", ctypes.c_uint32), ("warm_iters", ctypes.c_int32), ("workspace", ctypes.c_void_p),
-                ("workspace_bytes", ctypes.c_size_t), ("info", ctypes.c_void_p)]
+                ("workspace_bytes", ctypes.c_size_t), ("info", ctypes.c_void_p),
+                ("alpha_schedule", ctypes.POINTER(ctypes.c_float)), ("schedule_len", ctypes.c_int32)]
 
 
 class PrismError(RuntimeError):
@@ -58,6 +60,10 @@ def lib():
         L.prism_sqrt_ex.argtypes = L.prism_sqrt.argtypes + [ctypes.POINTER(Options)]
         L.prism_inv_root.argtypes = [vp, i, i, i, i, i, i, i, i, u64, dbl, vp]
         L.prism_inv_root_ex.argtypes = L.prism_inv_root.argtypes + [ctypes.POINTER(Options)]
+        L.prism_sign.argtypes = [vp, i, i, i, i, i, i, i, u64, dbl, vp]
+        L.prism_sign_ex.argtypes = L.prism_sign.argtypes + [ctypes.POINTER(Options)]
+        L.prism_inverse.argtypes = [vp, i, i, i, i, i, i, u64, dbl, vp]
+        L.prism_inverse_ex.argtypes = L.prism_inverse.argtypes + [ctypes.POINTER(Options)]
         L.prism_sketch.argtypes = [vp, i, i, u64, i, i, vp]
         L.prism_gauss_parts.argtypes = [ctypes.c_uint32, ctypes.c_uint32, vp, vp, vp, vp]
         L.prism_chain_product.argtypes = [vp, vp, vp, i, i, i, vp]
@@ -103,8 +109,12 @@ class _Info:
         return self.buf.cpu().numpy().view(INFO_DTYPE).copy()
 
 
-def _options(info, flags, warm_iters, workspace):
+def _options(info, flags, warm_iters, workspace, alpha_schedule=None):
     o = Options()
+    if alpha_schedule is not None and len(alpha_schedule) > 0:
+        o._sched = (ctypes.c_float * len(alpha_schedule))(*[float(a) for a in alpha_schedule])   # kept alive by o
+        o.alpha_schedule = ctypes.cast(o._sched, ctypes.POINTER(ctypes.c_float))
+        o.schedule_len = len(alpha_schedule)
     o.flags = flags
     o.warm_iters = warm_iters
     o.workspace = workspace.data_ptr() if workspace is not None else None
@@ -119,34 +129,58 @@ def workspace_bytes(fn, batch, m, n, dtype_code, degree, sketch_dim, root_p=0):
     return out.value
 
 
-def polar(x, degree=5, max_iters=30, sketch_dim=8, seed=22137, tol=1e-6, flags=0, warm_iters=0, workspace=None):
+def polar(x, degree=5, max_iters=30, sketch_dim=8, seed=22137, tol=1e-6, flags=0, warm_iters=0, workspace=None,
+          alpha_schedule=None):
     """In place: x[batch, m, n] <- polar factor.  Returns an info handle (.read() synchronises)."""
     b, m, n = _batched(x)
     info = _Info(b, x.device)
-    o = _options(info, flags, warm_iters, workspace)
+    o = _options(info, flags, warm_iters, workspace, alpha_schedule)
     _check(lib().prism_polar_ex(x.data_ptr(), b, m, n, _dtype_code(x), degree, max_iters, sketch_dim, seed, tol,
                                 _stream(), ctypes.byref(o)))
     return info
 
 
-def sqrt(a, degree=5, max_iters=30, sketch_dim=8, seed=22137, tol=1e-6, warm_iters=0, workspace=None):
+def sqrt(a, degree=5, max_iters=30, sketch_dim=8, seed=22137, tol=1e-6, warm_iters=0, workspace=None,
+         alpha_schedule=None):
     """In place: a <- A^(1/2); returns (A^(-1/2), info handle)."""
     b, m, n = _batched(a)
     inv = torch.empty_like(a)
     info = _Info(b, a.device)
-    o = _options(info, 0, warm_iters, workspace)
+    o = _options(info, 0, warm_iters, workspace, alpha_schedule)
     _check(lib().prism_sqrt_ex(a.data_ptr(), inv.data_ptr(), b, m, n, _dtype_code(a), degree, max_iters, sketch_dim,
                                seed, tol, _stream(), ctypes.byref(o)))
     return inv, info
 
 
-def inv_root(a, root_p, max_iters=30, sketch_dim=8, seed=22137, tol=1e-6, warm_iters=0, workspace=None):
+def inv_root(a, root_p, max_iters=30, sketch_dim=8, seed=22137, tol=1e-6, warm_iters=0, workspace=None,
+             alpha_schedule=None):
     """In place: a <- A^(-1/root_p).  Returns an info handle."""
     b, m, n = _batched(a)
     info = _Info(b, a.device)
-    o = _options(info, 0, warm_iters, workspace)
+    o = _options(info, 0, warm_iters, workspace, alpha_schedule)
     _check(lib().prism_inv_root_ex(a.data_ptr(), root_p, b, m, n, _dtype_code(a), 3, max_iters, sketch_dim, seed,
                                    tol, _stream(), ctypes.byref(o)))
+    return info
+
+
+def sign(x, degree=5, max_iters=30, sketch_dim=8, seed=22137, tol=1e-6, warm_iters=0, workspace=None,
+         alpha_schedule=None):
+    """In place: x[batch, n, n] <- sign(x).  Returns an info handle."""
+    b, m, n = _batched(x)
+    info = _Info(b, x.device)
+    o = _options(info, 0, warm_iters, workspace, alpha_schedule)
+    _check(lib().prism_sign_ex(x.data_ptr(), b, m, n, _dtype_code(x), degree, max_iters, sketch_dim, seed, tol,
+                               _stream(), ctypes.byref(o)))
+    return info
+
+
+def inverse(a, max_iters=30, sketch_dim=8, seed=22137, tol=1e-6, warm_iters=0, workspace=None, alpha_schedule=None):
+    """In place: a[batch, n, n] <- a^(-1) by the Chebyshev iteration.  Returns an info handle."""
+    b, m, n = _batched(a)
+    info = _Info(b, a.device)
+    o = _options(info, 0, warm_iters, workspace, alpha_schedule)
+    _check(lib().prism_inverse_ex(a.data_ptr(), b, m, n, _dtype_code(a), max_iters, sketch_dim, seed, tol,
+                                  _stream(), ctypes.byref(o)))
     return info
 
 

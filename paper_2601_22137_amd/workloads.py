@@ -100,3 +100,46 @@ def c5_wishart_spd(n=8192, batch=4, data_seed=1005, ratio=2, ridge=1e-4):
         a[np.diag_indices(n)] += ridge
         out[b] = a.astype(np.float32)
     return out
+
+
+def sign_indefinite(n=512, batch=4, data_seed=1006, decades=3.0):
+    """fp32 symmetric indefinite matrices Q diag(lambda) Q^T: |lambda| log-uniform in
+    [10^-decades, 1], random signs.  Stands in for the paper's matrix-sign experiments
+    (Gaussian and heavy-tailed spectra); the sign function is sign-pattern of lambda."""
+    out = np.empty((batch, n, n), dtype=np.float32)
+    for b in range(batch):
+        rng = _rng(data_seed + b)
+        q = _orthogonal(rng, n)
+        lam = 10.0 ** rng.uniform(-decades, 0.0, size=n) * rng.choice([-1.0, 1.0], size=n)
+        a = (q * lam[None, :]) @ q.T
+        out[b] = (0.5 * (a + a.T)).astype(np.float32)
+    return out
+
+
+def sign_block(n_half=192, batch=2, data_seed=1007):
+    """fp32 [[0, A], [I, 0]] with A symmetric positive definite (eigenvalues log-uniform in
+    [1e-2, 1]): not symmetric, but its square is; sign gives A^(1/2) and A^(-1/2) in the
+    off-diagonal blocks (the route from matrix sign to square roots, Section 5)."""
+    n = n_half
+    out = np.zeros((batch, 2 * n, 2 * n), dtype=np.float32)
+    for b in range(batch):
+        rng = _rng(data_seed + b)
+        q = _orthogonal(rng, n)
+        lam = 10.0 ** rng.uniform(-2.0, 0.0, size=n)
+        a = (q * lam[None, :]) @ q.T
+        out[b, :n, n:] = (0.5 * (a + a.T)).astype(np.float32)
+        out[b, n:, :n] = np.eye(n, dtype=np.float32)
+    return out
+
+
+def inverse_general(n=512, batch=4, data_seed=1008, cond=30.0):
+    """fp32 non-symmetric full-rank matrices U diag(sigma) V^T times a per-matrix scale, sigma
+    log-uniform in [1/cond, 1]."""
+    out = np.empty((batch, n, n), dtype=np.float32)
+    for b in range(batch):
+        rng = _rng(data_seed + b)
+        u = _orthogonal(rng, n)
+        v = _orthogonal(rng, n)
+        sigma = np.exp(rng.uniform(-np.log(cond), 0.0, size=n))
+        out[b] = ((u * sigma[None, :]) @ v.T * (1.0 + 2.0 * b)).astype(np.float32)
+    return out

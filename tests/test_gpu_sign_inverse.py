@@ -1,0 +1,134 @@
+"""Parity of prism_sign, prism_inverse and caller-supplied coefficient schedules against the fp64
+oracle on the same seeded inputs (bars as in test_gpu_parity.py: relative Frobenius error of the
+output <= 1e-5 for fp32 inputs, identical iteration counts)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import prism_ref as O
+from paper_2601_22137_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+SEED = W.SKETCH_SEED
+TOL_F32 = 1e-5
+
+
+@pytest.fixture(scope="module")
+def prism():
+    from paper_2601_22137_amd import prism as P
+    P.lib()
+    return P
+
+
+def _rel(x, ref):
+    return np.linalg.norm(np.asarray(x, dtype=np.float64) - ref) / np.linalg.norm(ref)
+
+
+def _check_info(rec, oinfo, lo, hi, alpha_tol=2e-3, res_rtol=2e-2, res_floor=2e-6, alpha_res_min=1e-3):
+    assert rec["iters"] == oinfo["iters"], (rec["residual"][:rec["iters"] + 1], oinfo["residual"])
+    assert rec["status"] == oinfo["status"]
+    k = oinfo["iters"]
+    for j in range(k):
+        if oinfo["residual"][j] >= alpha_res_min:
+            assert abs(rec["alpha"][j] - oinfo["alpha"][j]) <= alpha_tol, (j, rec["alpha"][:k], oinfo["alpha"])
+        else:   # residual near the fp32 rounding level: the fit sees mostly noise
+            assert lo - 1e-6 <= rec["alpha"][j] <= hi + 1e-6
+    got, want = rec["residual"][:k + 1].astype(np.float64), np.array(oinfo["residual"][:k + 1])
+    assert np.all(np.abs(got - want) <= res_rtol * want + res_floor), (got, want)
+
+
+@pytest.mark.parametrize("degree,n,p_s", [(5, 512, 32), (3, 300, 16), (5, 130, 8)])
+def test_sign_symmetric_indefinite(prism, degree, n, p_s):
+    A = W.sign_indefinite(n=n, batch=3, decades=2.0)
+    x = torch.from_numpy(A.copy()).cuda()
+    info = prism.sign(x, degree, 40, p_s, SEED, 1e-5).read()
+    out = x.cpu().numpy()
+    lo, hi = O.clamp_interval({3: 1, 5: 2}[degree])
+    for b in range(3):
+        ref, oinfo = O.sign(A[b], degree, 40, p_s, SEED, 1e-5)
+        assert oinfo["status"] == O.STATUS_CONVERGED
+        assert _rel(out[b], ref) <= TOL_F32
+        _check_info(info[b], oinfo, lo, hi)
+    # involutory, symmetric
+    s = out[0].astype(np.float64)
+    assert np.linalg.norm(s @ s - np.eye(n)) / np.sqrt(n) <= 5e-5
+
+
+def test_sign_block_matrix_gives_square_roots(prism):
+    """A non-symmetric input with a symmetric square: the product order of the residual matters."""
+    A = W.sign_block()
+    x = torch.from_numpy(A.copy()).cuda()
+    info = prism.sign(x, 5, 40, 16, SEED, 1e-5).read()
+    out = x.cpu().numpy()
+    n = A.shape[1] // 2
+    for b in range(A.shape[0]):
+        ref, oinfo = O.sign(A[b], 5, 40, 16, SEED, 1e-5)
+        assert _rel(out[b], ref) <= TOL_F32
+        _check_info(info[b], oinfo, 0.375, 1.45)
+        root = out[b, :n, n:].astype(np.float64)
+        a = A[b, :n, n:].astype(np.float64)
+        assert np.linalg.norm(root @ root - a) / np.linalg.norm(a) <= 1e-4
+
+
+@pytest.mark.parametrize("n,p_s,cond", [(512, 32, 30.0), (300, 16, 30.0), (64, 8, 10.0)])
+def test_inverse_general(prism, n, p_s, cond):
+    """The forward error of any fp32 inverse scales with cond(A) * 2^-24 (about 6e-6 at cond = 100),
+    so the 1e-5 bar is tested at condition numbers up to 30."""
+    A = W.inverse_general(n=n, batch=3, cond=cond)
+    x = torch.from_numpy(A.copy()).cuda()
+    info = prism.inverse(x, 40, p_s, SEED, 1e-5).read()
+    out = x.cpu().numpy()
+    for b in range(3):
+        ref, oinfo = O.inverse(A[b], 40, p_s, SEED, 1e-5)
+        assert oinfo["status"] == O.STATUS_CONVERGED
+        assert _rel(out[b], ref) <= TOL_F32
+        _check_info(info[b], oinfo, 0.5, 2.0, res_floor=5e-6)
+        assert np.linalg.norm(A[b].astype(np.float64) @ out[b] - np.eye(n)) / np.sqrt(n) <= 5e-5
+
+
+def test_inverse_without_fit_is_classical(prism):
+    A = W.inverse_general(n=200, batch=2, cond=10.0)
+    x = torch.from_numpy(A.copy()).cuda()
+    info = prism.inverse(x, 40, 0, SEED, 1e-5).read()
+    ref, oinfo = O.inverse(A[1], 40, 0, SEED, 1e-5)
+    assert info[1]["iters"] == oinfo["iters"]
+    assert np.all(info[1]["alpha"][:oinfo["iters"]] == np.float32(1.0))
+    assert _rel(x.cpu().numpy()[1], ref) <= TOL_F32
+
+
+def test_alpha_schedule_overrides_leading_fits(prism):
+    """Fixed-coefficient schemes through the same kernels: the first updates take the caller's
+    alpha (exactly representable values here), the rest are fitted from the sketches of their
+    own iteration index."""
+    A = W.c1_polar_small(m=200, n=96)
+    sched = [1.25, 1.0, 0.75]
+    x = torch.from_numpy(A.copy()).cuda()
+    info = prism.polar(x, 5, 30, 8, SEED, 1e-6, alpha_schedule=sched).read()
+    ref, oinfo = O.polar(A[0], 5, 30, 8, SEED, 1e-6, alpha_schedule=sched)
+    assert _rel(x.cpu().numpy()[0], ref) <= TOL_F32
+    assert np.all(info[0]["alpha"][:3] == np.float32(sched))
+    _check_info(info[0], oinfo, 0.375, 1.45, alpha_res_min=1e-2)
+    # schedule longer than the budget, with warm_iters below it; inverse root and inverse too
+    S = W.c4_shampoo_spd(n=128, batch=2)
+    x = torch.from_numpy(S.copy()).cuda()
+    info = prism.inv_root(x, 2, 6, 8, SEED, 0.0, warm_iters=1, alpha_schedule=[0.75] * 8).read()
+    ref, oinfo = O.inv_root(S[0], 2, 6, 8, SEED, 0.0, alpha_schedule=[0.75] * 8)
+    assert info[0]["iters"] == 6 and np.all(info[0]["alpha"][:6] == np.float32(0.75))
+    assert _rel(x.cpu().numpy()[0], ref) <= TOL_F32
+
+
+def test_sign_and_inverse_argument_errors(prism):
+    x = torch.zeros((1, 8, 12), dtype=torch.float32, device="cuda")
+    with pytest.raises(prism.PrismError):
+        prism.sign(x)
+    with pytest.raises(prism.PrismError):
+        prism.inverse(x)
+    xb = torch.zeros((1, 16, 16), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(prism.PrismError, match="UNSUPPORTED"):
+        prism.sign(xb)
+    z = torch.zeros((2, 16, 16), dtype=torch.float32, device="cuda")
+    z[1] = torch.eye(16)
+    info = prism.inverse(z, 20, 4, SEED, 1e-6).read()
+    assert info[0]["status"] == prism.INFO_ZERO and info[1]["status"] == prism.INFO_CONVERGED
+    assert torch.allclose(z[1], torch.eye(16, device="cuda"), atol=1e-5)
