@@ -29,6 +29,8 @@ def parse():
     ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5"])
     ap.add_argument("--split", action="store_true", help="c2: carry the iterate as a bf16 high+low pair")
     ap.add_argument("--batch", type=int, default=0, help="override the batch size (c3/c4/c5)")
+    ap.add_argument("--streams", type=int, default=0,
+                    help="HIP streams the calls of one step are spread over (default: one per shape group, i.e. 4 for c2)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
     ap.add_argument("--no-profile", action="store_true", help="skip the per-kernel event pass")
     ap.add_argument("--copy-probe", action="store_true",
@@ -164,8 +166,20 @@ def main():
     n_copies = K + Wm
     copies = [[p.clone() for p in pristine] for _ in range(n_copies)]
 
-    def step(i):
-        return [wl.call(x) for x in copies[i]]
+    # The calls of one step (one per shape group) are independent: each goes to a stream of its own
+    # (default priority), so that the small latency-bound kernels of one call run beside the GEMMs
+    # of another.  Consecutive steps queue up behind each other on the same streams.
+    nstreams = args.streams or len(wl.host)
+    side = [torch.cuda.Stream() for _ in range(nstreams)] if nstreams > 1 else None
+
+    def step(i, use_streams=True):
+        if side is None or not use_streams:
+            return [wl.call(x) for x in copies[i]]
+        hs = []
+        for g, x in enumerate(copies[i]):
+            with torch.cuda.stream(side[g % nstreams]):
+                hs.append(wl.call(x))
+        return hs
 
     for i in range(Wm):
         step(i)
@@ -175,6 +189,9 @@ def main():
     handles = None
     for i in range(K):
         handles = step(Wm + i)
+    if side is not None:
+        for st in side:
+            torch.cuda.current_stream().wait_stream(st)
     ev1.record()
     torch.cuda.synchronize()
     ms_total = ev0.elapsed_time(ev1)
@@ -242,7 +259,7 @@ def main():
         nprof = min(K, 3)
         prism.profile_enable(True)
         for i in range(nprof):
-            step(Wm + i)
+            step(Wm + i, use_streams=False)     # one stream: every kernel is timed running alone
         torch.cuda.synchronize()
         prof = prism.profile_collect()
         prism.profile_enable(False)
@@ -274,7 +291,7 @@ def main():
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": wl.dtype, "data": "synthetic",
         "config": {"workload": wl.name + ": " + wl.desc, "matrices_per_step": wl.n_matrices,
-                   "input_bytes_per_step": bytes_per_copy},
+                   "input_bytes_per_step": bytes_per_copy, "streams": nstreams},
         "tflops_algorithmic": round(tflops_algo, 2), "tflops_executed": round(tflops_exec, 2),
         "frac_of_mfma_peak": round(tflops_exec / PEAK[wl.dtype], 4),
         "iterations": {"min": min(iters_all), "max": max(iters_all)},

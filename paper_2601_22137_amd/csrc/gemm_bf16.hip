@@ -50,9 +50,12 @@ __global__ __launch_bounds__(NT) void gemm_bf16_kernel(Bf16Desc g) {
   constexpr int LDI = T / 64;       // direct-to-LDS load instructions per wave, operand and slab
   constexpr int OP_BYTES = T * 64;  // one operand slab in LDS: T rows x 32 bf16, unpadded
   constexpr int BUF_BYTES = 2 * OP_BYTES;
-  // LDS: ring of STAGES buffers, each [A slab | B slab].  Two consecutive rows share one 128-byte
-  // line; the eight 16-byte chunks of line q sit at slot ((row & 1) * 4 + chunk) ^ (q & 7), so the
-  // 16-byte fragment reads of 8 consecutive rows cover all banks exactly once.
+  // LDS: ring of STAGES buffers, each [A slab | B slab].  The LDS has 64 banks of 4 bytes and
+  // serves a 16-byte read per lane in groups of 16 lanes, so 16 consecutive lanes must cover one
+  // 256-byte bank line exactly once.  Four consecutive rows (64 bytes each) share a line; the
+  // sixteen 16-byte chunks of line q sit at slot ((row & 3) * 4 + chunk) ^ (q & 15): the fragment
+  // reads (16 consecutive rows, same chunk) then hit 16 different slots (measured: 116 B/clk/CU
+  // against 82 for a swizzle over 128-byte lines and 63 unswizzled).
   extern __shared__ __align__(1024) unsigned char smem[];
   __shared__ float red[4];
 
@@ -99,12 +102,13 @@ __global__ __launch_bounds__(NT) void gemm_bf16_kernel(Bf16Desc g) {
 
   // Global -> LDS without passing through registers (global_load_lds_dwordx4): one wave
   // instruction moves 64 lanes x 16 bytes into 1 KiB of consecutive LDS = 16 rows of a slab.
-  // Lane l fills slot l & 7 of line l >> 3 and therefore fetches the chunk that belongs there.
-  const int lq = lane >> 3, lu = (lane & 7) ^ lq;
+  // Lane l fills slot l & 15 of line l >> 4 of those 16 rows and fetches the chunk that belongs
+  // there (the line index within the slab is (it * 4 + wave) * 4 + (l >> 4)).
+  const int lq = lane >> 4, lu = (lane & 15) ^ ((wave * 4 + lq) & 15);
   unsigned aoff[LDI], boff[LDI];
 #pragma unroll
   for (int it = 0; it < LDI; ++it) {
-    const int row = (it * 4 + wave) * 16 + 2 * lq + (lu >> 2);
+    const int row = (it * 4 + wave) * 16 + 4 * lq + (lu >> 2);
     aoff[it] = (unsigned)(row * g.lda + (lu & 3) * 8) * 2u;
     boff[it] = (unsigned)(row * g.ldb + (lu & 3) * 8) * 2u;
   }
@@ -135,17 +139,21 @@ __global__ __launch_bounds__(NT) void gemm_bf16_kernel(Bf16Desc g) {
 
   // fragment addresses: row r = tile row, chunk cc = 2 * kk + (lane >> 5)
   const int lr = lane & 31, lh = lane >> 5;
-  const unsigned char* Afr = smem + ((wm0 + lr) >> 1) * 128;
-  const unsigned char* Bfr = smem + OP_BYTES + ((wn0 + lr) >> 1) * 128;
-  int koff[2];
+  // (row block f starts 32 rows = 8 lines further on, which flips bit 3 of the line index)
+  const unsigned char* Afr = smem + wm0 * 64 + (lr >> 2) * 256;
+  const unsigned char* Bfr = smem + OP_BYTES + wn0 * 64 + (lr >> 2) * 256;
+  int koff[2][2];
 #pragma unroll
-  for (int kk = 0; kk < 2; ++kk) koff[kk] = ((((lr & 1) << 2) + kk * 2 + lh) ^ ((lr >> 1) & 7)) << 4;
+  for (int kk = 0; kk < 2; ++kk)
+#pragma unroll
+    for (int par = 0; par < 2; ++par)
+      koff[kk][par] = ((((lr & 3) << 2) + kk * 2 + lh) ^ ((lr >> 2) + 8 * par)) << 4;
   bf16x8 fa[2][NB], fb[2][NB];
   // fragment f in [0, 2*NB) of sub-step kk: first the NB row blocks of A, then the NB of B
   auto load_frag = [&](int kt, int kk, int f) {
-    const int o = (kt & (STAGES - 1)) * BUF_BYTES + koff[kk];
-    if (f < NB) fa[kk][f] = *(const bf16x8*)(Afr + o + f * 2048);
-    else fb[kk][f - NB] = *(const bf16x8*)(Bfr + o + (f - NB) * 2048);
+    const int o = (kt & (STAGES - 1)) * BUF_BYTES;
+    if (f < NB) fa[kk][f] = *(const bf16x8*)(Afr + o + koff[kk][f & 1] + f * 2048);
+    else fb[kk][f - NB] = *(const bf16x8*)(Bfr + o + koff[kk][(f - NB) & 1] + (f - NB) * 2048);
   };
   auto load_frags = [&](int kt, int kk) {
 #pragma unroll

@@ -66,11 +66,22 @@ def _sampled_rel_err(x, samples, fro, n=4096):
 
 
 def test_c2_muon_full(prism):
-    """64 bf16 matrices in four calls of 16, plain bf16 iterate, 5 fixed iterations (the bench workload)."""
+    """64 bf16 matrices in four calls of 16, plain bf16 iterate, 5 fixed iterations, each call on a
+    stream of its own (the bench launch configuration)."""
+    streams = [torch.cuda.Stream() for _ in range(4)]
+    xs, handles, allbits = [], [], []
     for shape_idx in range(4):
         bits = W.c2_muon_group(shape_idx)
-        x = _bf16_tensor(bits.copy())
-        info = prism.polar(x, 5, 5, 16, SEED, 0.0, flags=prism.FLAG_BF16_PLAIN_ITERATE).read()
+        allbits.append(bits)
+        xs.append(_bf16_tensor(bits.copy()))
+    torch.cuda.synchronize()
+    for shape_idx in range(4):
+        with torch.cuda.stream(streams[shape_idx]):
+            handles.append(prism.polar(xs[shape_idx], 5, 5, 16, SEED, 0.0, flags=prism.FLAG_BF16_PLAIN_ITERATE))
+    torch.cuda.synchronize()
+    for shape_idx in range(4):
+        bits, x = allbits[shape_idx], xs[shape_idx]
+        info = handles[shape_idx].read()
         out = W.from_bf16_bits(x.view(torch.int16).cpu().numpy().view(np.uint16))
         assert np.all(info["iters"] == 5) and np.all(info["status"] == prism.INFO_BUDGET)
         assert np.all(np.isfinite(out))
