@@ -12,6 +12,8 @@
 // loads run three slabs ahead to cover the memory latency), in a swizzled layout that keeps the
 // 16-byte fragment reads free of bank conflicts.  With a second A operand (the low half of a split-bf16 iterate) the K loop simply
 // runs over both halves against the same B.
+#include <type_traits>
+
 #include "common.h"
 
 namespace prism {
@@ -43,7 +45,9 @@ template <int N> __device__ inline void wait_vmcnt() {
   __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | 0x0F70);
 }
 
-template <int T, int EPI, bool SYM>
+// DUAL (update GEMM with a split iterate): every K slab holds the high and the low half of A next
+// to the one slab of B they both multiply, so B passes through the LDS once instead of twice.
+template <int T, int EPI, bool SYM, bool DUAL>
 __global__ __launch_bounds__(NT) void gemm_bf16_kernel(Bf16Desc g) {
   constexpr int WT = T / 2;         // wave tile (2 x 2 waves)
   constexpr int NB = WT / 32;       // 32x32 blocks per wave and dimension
@@ -93,12 +97,15 @@ __global__ __launch_bounds__(NT) void gemm_bf16_kernel(Bf16Desc g) {
   const int wave = __builtin_amdgcn_readfirstlane(t >> 6);  // uniform: LDS destinations stay scalar
   const int wm0 = (wave >> 1) * WT, wn0 = (wave & 1) * WT;
   const int m0 = tm * T, n0 = tn * T;
-  const unsigned short* A1 = g.A + (long long)b * g.strideA + (long long)m0 * g.lda;
+  const unsigned short* A1_ = g.A + (long long)b * g.strideA + (long long)m0 * g.lda;
   const unsigned short* A2 = g.A2 ? g.A2 + (long long)b * g.strideA + (long long)m0 * g.lda : nullptr;
-  const unsigned short* Bb = g.B + (long long)b * g.strideB + (long long)n0 * g.ldb;
+  const unsigned short* Bb_ = g.B + (long long)b * g.strideB + (long long)n0 * g.ldb;
+  // timing experiment (test entry only): every workgroup reads the operands of tile 0
+  const unsigned short* A1 = (g.dbg & 16) ? g.A : A1_;
+  const unsigned short* Bb = (g.dbg & 16) ? g.B : Bb_;
 
   const int KT1 = g.K / BK;
-  const int KT = A2 ? 2 * KT1 : KT1;
+  const int KT = (A2 && !DUAL) ? 2 * KT1 : KT1;
 
   // Global -> LDS without passing through registers (global_load_lds_dwordx4): one wave
   // instruction moves 64 lanes x 16 bytes into 1 KiB of consecutive LDS = 16 rows of a slab.
@@ -188,6 +195,98 @@ __global__ __launch_bounds__(NT) void gemm_bf16_kernel(Bf16Desc g) {
     asm volatile("" ::: "memory");
   };
 
+  if constexpr (DUAL) {
+    // Ring of three buffers [A_hi slab | A_lo slab | B slab].  One slab = four sub-steps:
+    //   0: hi(k 0..15) x B(k 0..15)   1: lo(k 0..15) x B(k 0..15)
+    //   2: hi(k 16..31) x B(16..31)   3: lo(k 16..31) x B(16..31)
+    // The fragments of a sub-step are read during the one before it; the single barrier of the
+    // slab sits after sub-step 2 (all its fragments are in registers then), and sub-step 3
+    // requests slab kt+3 into the buffer the barrier has just released.
+    constexpr int DBUF = 3 * OP_BYTES;
+    constexpr int NL = 3 * LDI;                 // load instructions per wave and slab
+    constexpr int NM = NB * NB;                 // MFMAs per sub-step
+    auto d_issue = [&](int kt_, int slot, int u) {
+      const int op = u % 3, it = u / 3;
+      const int kk0 = kt_ * BK;
+      unsigned char* dst = smem + slot * DBUF + op * OP_BYTES + wave * 1024 + it * 4096;
+      if (op == 2) __builtin_amdgcn_global_load_lds((gptr_t)((const char*)(Bb + kk0) + boff[it]), (lptr_t)dst, 16, 0, 0);
+      else __builtin_amdgcn_global_load_lds((gptr_t)((const char*)((op ? A2 : A1) + kk0) + aoff[it]), (lptr_t)dst, 16, 0, 0);
+    };
+    const unsigned char* Ahi = smem + wm0 * 64 + (lr >> 2) * 256;
+    const unsigned char* Alo = Ahi + OP_BYTES;
+    const unsigned char* Bf = smem + 2 * OP_BYTES + wn0 * 64 + (lr >> 2) * 256;
+    bf16x8 fA[NB], fB[NB], fb2[2][NB];          // fA: high half, fB: low half, fb2[kk]: B
+    auto rd_hi = [&](int slot, int kk, int f) { fA[f] = *(const bf16x8*)(Ahi + slot * DBUF + koff[kk][f & 1] + f * 2048); };
+    auto rd_lo = [&](int slot, int kk, int f) { fB[f] = *(const bf16x8*)(Alo + slot * DBUF + koff[kk][f & 1] + f * 2048); };
+    auto rd_b = [&](int slot, int kk, int f) { fb2[kk][f] = *(const bf16x8*)(Bf + slot * DBUF + koff[kk][f & 1] + f * 2048); };
+    auto mm_hi = [&](int kk, int m) { acc[m / NB][m % NB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fA[m / NB], fb2[kk][m % NB], acc[m / NB][m % NB], 0, 0, 0); };
+    auto mm_lo = [&](int kk, int m) { acc[m / NB][m % NB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fB[m / NB], fb2[kk][m % NB], acc[m / NB][m % NB], 0, 0, 0); };
+    // prologue: slabs 0, 1, 2
+#pragma unroll
+    for (int s0 = 0; s0 < 3; ++s0) {
+#pragma unroll
+      for (int u = 0; u < NL; ++u) d_issue(s0, s0, u);
+    }
+    wait_vmcnt<2 * NL>();
+    ring_barrier();
+#pragma unroll
+    for (int f = 0; f < NB; ++f) { rd_hi(0, 0, f); rd_b(0, 0, f); }
+    // MORE: slab kt+3 exists and is requested; NEXT: slab kt+1 exists; AHEAD: slab kt+2 exists
+    // (its loads may still be in flight at the barrier)
+    auto slab = [&](int kt, int slot, int nslot, auto more_c, auto next_c, auto ahead_c) {
+      constexpr bool MORE = decltype(more_c)::value, NEXT = decltype(next_c)::value, AHEAD = decltype(ahead_c)::value;
+      // sub-step 0: hi x B (first half of the slab); read lo (first half)
+#pragma unroll
+      for (int m = 0; m < NM; ++m) {
+        if (m < NB) rd_lo(slot, 0, m);
+        mm_hi(0, m);
+        if ((m & 1) == 1) __builtin_amdgcn_sched_barrier(0);
+      }
+      // sub-step 1: lo x B (first half); read hi and B (second half)
+#pragma unroll
+      for (int m = 0; m < NM; ++m) {
+        if (m < 2 * NB) { if (m & 1) rd_b(slot, 1, m >> 1); else rd_hi(slot, 1, m >> 1); }
+        mm_lo(0, m);
+        if ((m & 1) == 1) __builtin_amdgcn_sched_barrier(0);
+      }
+      // sub-step 2: hi x B (second half); read lo (second half)
+#pragma unroll
+      for (int m = 0; m < NM; ++m) {
+        if (m < NB) rd_lo(slot, 1, m);
+        mm_hi(1, m);
+        if ((m & 1) == 1) __builtin_amdgcn_sched_barrier(0);
+      }
+      // slab kt+1 must have landed; slab kt+2 (requested one slab ago) may still be in flight
+      if (AHEAD) wait_vmcnt<NL>(); else wait_vmcnt<0>();
+      ring_barrier();
+      // sub-step 3: lo x B (second half); request slab kt+3; read hi and B of slab kt+1
+#pragma unroll
+      for (int m = 0; m < NM; ++m) {
+        if (NEXT && m < 2 * NB) { if (m & 1) rd_b(nslot, 0, m >> 1); else rd_hi(nslot, 0, m >> 1); }
+        if (MORE && m < NL) d_issue(kt + 3, slot, m);
+        mm_lo(1, m);
+        if ((m & 1) == 1) __builtin_amdgcn_sched_barrier(0);
+      }
+      if (MORE && NL > NM) {
+#pragma unroll
+        for (int u = NM; u < NL; ++u) d_issue(kt + 3, slot, u);
+      }
+    };
+    typedef std::integral_constant<bool, true> yes;
+    typedef std::integral_constant<bool, false> no;
+    int slot = 0, kt = 0;
+    for (; kt + 3 < KT; ++kt) {
+      const int nslot = slot == 2 ? 0 : slot + 1;
+      slab(kt, slot, nslot, yes(), yes(), yes());
+      slot = nslot;
+    }
+    {  // the last three slabs (the launcher guarantees KT >= 3): nothing left to request
+      const int s1 = slot == 2 ? 0 : slot + 1, s2 = s1 == 2 ? 0 : s1 + 1;
+      slab(kt, slot, s1, no(), yes(), yes());
+      slab(kt + 1, s1, s2, no(), yes(), no());
+      slab(kt + 2, s2, slot, no(), no(), no());
+    }
+  } else {
   // Main loop.  Slab kt+3 is requested at the top of slab kt (its ring slot was released by the
   // barrier that closed slab kt-1); the fragments of the second half of slab kt are read while
   // its first half computes, and after the single barrier of the slab the first fragments of
@@ -234,6 +333,8 @@ __global__ __launch_bounds__(NT) void gemm_bf16_kernel(Bf16Desc g) {
     ring_barrier();
     if (kt + 1 < KT) load_frags(kt + 1, 0);
     mfma_block(1);
+  }
+
   }
 
   // epilogue: register r of lane l holds row (r/4)*8 + (l/32)*4 + r%4, column l%32 of a block
@@ -422,21 +523,22 @@ __global__ __launch_bounds__(NT) void gemm_bf16_kernel(Bf16Desc g) {
   }
 }
 
-template <int T, int EPI, bool SYM>
+template <int T, int EPI, bool SYM, bool DUAL = false>
 int launch_te(const Bf16Desc& g, hipStream_t s) {
   const int tm = g.M / T, tn = g.N / T;
   const int total = (SYM ? tm * (tm + 1) / 2 : tm * tn) * g.batch;
-  const size_t lds = (size_t)STAGES * 2 * T * 64;   // ring of STAGES x (A slab + B slab)
+  // ring of STAGES x (A slab + B slab), or of 3 x (A_hi + A_lo + B)
+  const size_t lds = DUAL ? (size_t)3 * 3 * T * 64 : (size_t)STAGES * 2 * T * 64;
   static bool attr_set = false;  // per instantiation
   if (!attr_set) {
-    if (hipFuncSetAttribute((const void*)gemm_bf16_kernel<T, EPI, SYM>, hipFuncAttributeMaxDynamicSharedMemorySize,
+    if (hipFuncSetAttribute((const void*)gemm_bf16_kernel<T, EPI, SYM, DUAL>, hipFuncAttributeMaxDynamicSharedMemorySize,
                             (int)lds) != hipSuccess) {
       set_last_error("hipFuncSetAttribute(MaxDynamicSharedMemorySize) failed");
       return PRISM_EHIP;
     }
     attr_set = true;
   }
-  hipLaunchKernelGGL((gemm_bf16_kernel<T, EPI, SYM>), dim3(total), dim3(NT), lds, s, g);
+  hipLaunchKernelGGL((gemm_bf16_kernel<T, EPI, SYM, DUAL>), dim3(total), dim3(NT), lds, s, g);
   return hipGetLastError() == hipSuccess ? PRISM_OK : PRISM_EHIP;
 }
 
@@ -449,7 +551,8 @@ int launch_t(const Bf16Desc& g, hipStream_t s) {
     case BEPI_STORE: return launch_te<T, BEPI_STORE, false>(g, s);
     case BEPI_GRAM: return g.sym ? launch_te<T, BEPI_GRAM, true>(g, s) : launch_te<T, BEPI_GRAM, false>(g, s);
     case BEPI_POLYQ: return g.sym ? launch_te<T, BEPI_POLYQ, true>(g, s) : launch_te<T, BEPI_POLYQ, false>(g, s);
-    case BEPI_APPLY: return launch_te<T, BEPI_APPLY, false>(g, s);
+    case BEPI_APPLY:
+      return (g.A2 && g.K >= 3 * BK && !(g.dbg & 8)) ? launch_te<T, BEPI_APPLY, false, true>(g, s) : launch_te<T, BEPI_APPLY, false>(g, s);
   }
   return PRISM_EINVAL;
 }

@@ -297,6 +297,7 @@ int run_polar_bf16(Run& r) {
   uint16_t* Rb = r.at<uint16_t>(P.o_rb);
   uint16_t* Qb = P.d == 2 ? r.at<uint16_t>(P.o_qb) : nullptr;
   static const int no_sym = getenv("PRISM_BF16_NO_SYM") ? atoi(getenv("PRISM_BF16_NO_SYM")) : 0;
+  static const int no_dual = getenv("PRISM_BF16_NO_DUAL") ? atoi(getenv("PRISM_BF16_NO_DUAL")) : 0;
   const int sym = no_sym ? 0 : 1;
   const int ntg = Sp / Tg;
   const int nparts = sym ? ntg * (ntg + 1) / 2 : ntg * ntg;
@@ -329,6 +330,7 @@ int run_polar_bf16(Run& r) {
     a.Cb = Xhi[cur ^ 1]; a.Cb2 = Xlo[cur ^ 1]; a.strideCb = LS; a.ldcb = Sp;
     a.Ct = Xg[cur ^ 1]; a.strideCt = LS; a.ldct = Lp;
     a.Xhi = Xhi[cur]; a.Xlo = Xlo[cur]; a.coef_is_alpha = P.d == 1; a.ctrl = r.ctrl;
+    a.dbg = no_dual ? 8 : 0;
     { ProfScope ps(PK_BF16_APPLY, r.s); CHECK_LAUNCH(launch_gemm_bf16(a, Ta, r.s)); }
     cur ^= 1;
   }
