@@ -31,6 +31,8 @@ def parse():
     ap.add_argument("--batch", type=int, default=0, help="override the batch size (c3/c4/c5)")
     ap.add_argument("--streams", type=int, default=0,
                     help="HIP streams the calls of one step are spread over (default: one per shape group, i.e. 4 for c2)")
+    ap.add_argument("--sub-batches", type=int, default=1,
+                    help="split every group's batch into this many calls (spread over the streams)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
     ap.add_argument("--no-profile", action="store_true", help="skip the per-kernel event pass")
     ap.add_argument("--copy-probe", action="store_true",
@@ -169,16 +171,35 @@ def main():
     # The calls of one step (one per shape group) are independent: each goes to a stream of its own
     # (default priority), so that the small latency-bound kernels of one call run beside the GEMMs
     # of another.  Consecutive steps queue up behind each other on the same streams.
-    nstreams = args.streams or len(wl.host)
+    nsub = max(1, args.sub_batches)
+    nstreams = args.streams or len(wl.host) * nsub
     side = [torch.cuda.Stream() for _ in range(nstreams)] if nstreams > 1 else None
 
+    def parts(x):
+        if nsub == 1:
+            return [x]
+        per = (x.shape[0] + nsub - 1) // nsub
+        return [x[j:j + per] for j in range(0, x.shape[0], per)]
+
+    class Joined:      # the info records of the sub-batch calls of one group, in matrix order
+        def __init__(self, hs):
+            self.hs = hs
+
+        def read(self):
+            return np.concatenate([h.read() for h in self.hs])
+
     def step(i, use_streams=True):
-        if side is None or not use_streams:
-            return [wl.call(x) for x in copies[i]]
-        hs = []
-        for g, x in enumerate(copies[i]):
-            with torch.cuda.stream(side[g % nstreams]):
-                hs.append(wl.call(x))
+        hs, slot = [], 0
+        for x in copies[i]:
+            sub = []
+            for xp in parts(x):
+                if side is None or not use_streams:
+                    sub.append(wl.call(xp))
+                else:
+                    with torch.cuda.stream(side[slot % nstreams]):
+                        sub.append(wl.call(xp))
+                slot += 1
+            hs.append(Joined(sub))
         return hs
 
     for i in range(Wm):
@@ -291,7 +312,8 @@ def main():
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": wl.dtype, "data": "synthetic",
         "config": {"workload": wl.name + ": " + wl.desc, "matrices_per_step": wl.n_matrices,
-                   "input_bytes_per_step": bytes_per_copy, "streams": nstreams},
+                   "input_bytes_per_step": bytes_per_copy, "streams": nstreams,
+                   "calls_per_step": len(wl.host) * nsub},
         "tflops_algorithmic": round(tflops_algo, 2), "tflops_executed": round(tflops_exec, 2),
         "frac_of_mfma_peak": round(tflops_exec / PEAK[wl.dtype], 4),
         "iterations": {"min": min(iters_all), "max": max(iters_all)},

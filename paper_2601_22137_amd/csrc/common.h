@@ -27,7 +27,7 @@ enum EpiKind {
   EPI_STORE = 0,     // C = acc
   EPI_RESIDUAL = 1,  // R = I - acc (masked to n x n), rho partial
   EPI_POLYQ = 2,     // Q = c1 * Rin + alpha * acc
-  EPI_AXPY = 3,      // C = c_in * Cin + Cin2 + coef * acc   (coef = 1 or alpha; Cin2 optional)
+  EPI_AXPY = 3,      // C = c_in alpha^a * Cin + alpha^b * Cin2 + alpha^c * acc   (a, b, c in 0..2; Cin2 optional)
   EPI_MNEXT = 4      // fp64: M' = Cin + acc, R32' = I - M' (masked), rho partial
 };
 
@@ -47,7 +47,9 @@ struct GemmDesc {
   float c1;             // POLYQ: coefficient of Rin
   float c_in;           // AXPY: coefficient of Cin
   const float* Cin2;    // AXPY: optional second addend, same layout as Cin
-  int coef_is_alpha;    // AXPY: multiply acc by ctrl.alpha
+  int coef_is_alpha;    // AXPY: power of ctrl.alpha (0, 1, 2) that multiplies acc
+  int cin_alpha_pow;    // AXPY: power of ctrl.alpha that multiplies Cin (besides c_in)
+  int cin2_alpha_pow;   // AXPY: power of ctrl.alpha that multiplies Cin2
   float* rho_part;      // [batch][tiles] partial sums of R^2 (RESIDUAL / MNEXT)
   const Ctrl* ctrl;     // may be null (test entry points)
 };

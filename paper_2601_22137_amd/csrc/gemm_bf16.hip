@@ -38,7 +38,7 @@ __device__ inline float bf2f(unsigned short h) { return __uint_as_float(((unsign
 typedef const void __attribute__((address_space(1)))* gptr_t;
 typedef void __attribute__((address_space(3)))* lptr_t;
 
-constexpr int STAGES = 4;    // LDS ring: loads run three slabs ahead of the MFMAs
+constexpr int STAGES = 4;    // LDS ring: loads run three slabs ahead of the MFMAs (a ring of five measured no faster)
 
 // s_waitcnt vmcnt(N) with the other counters left alone (gfx9 encoding)
 template <int N> __device__ inline void wait_vmcnt() {
@@ -61,7 +61,6 @@ __global__ __launch_bounds__(NT) void gemm_bf16_kernel(Bf16Desc g) {
   // reads (16 consecutive rows, same chunk) then hit 16 different slots (measured: 116 B/clk/CU
   // against 82 for a swizzle over 128-byte lines and 63 unswizzled).
   extern __shared__ __align__(1024) unsigned char smem[];
-  __shared__ float red[4];
 
   // SYM: A == B and the result is symmetric (Gram matrix, R^2): only the tiles on and above the
   // diagonal are computed, each off-diagonal tile is also written mirrored.
@@ -120,10 +119,10 @@ __global__ __launch_bounds__(NT) void gemm_bf16_kernel(Bf16Desc g) {
     boff[it] = (unsigned)(row * g.ldb + (lu & 3) * 8) * 2u;
   }
   // one load instruction pair index u in [0, 2*LDI): even = A, odd = B
-  auto issue_load = [&](int kt, int u) {
+  auto issue_load = [&](int kt, int slot, int u) {
     const int it = u >> 1;
     const int kk0 = ((kt < KT1) ? kt : kt - KT1) * BK;
-    unsigned char* dst = smem + (kt & (STAGES - 1)) * BUF_BYTES + wave * 1024 + it * 4096;
+    unsigned char* dst = smem + slot * BUF_BYTES + wave * 1024 + it * 4096;
     if (u & 1) {
       __builtin_amdgcn_global_load_lds((gptr_t)((const char*)(Bb + kk0) + boff[it]), (lptr_t)(dst + OP_BYTES), 16, 0, 0);
     } else {
@@ -131,9 +130,9 @@ __global__ __launch_bounds__(NT) void gemm_bf16_kernel(Bf16Desc g) {
       __builtin_amdgcn_global_load_lds((gptr_t)((const char*)Ap + aoff[it]), (lptr_t)dst, 16, 0, 0);
     }
   };
-  auto issue_loads = [&](int kt) {
+  auto issue_loads = [&](int kt, int slot) {
 #pragma unroll
-    for (int u = 0; u < 2 * LDI; ++u) issue_load(kt, u);
+    for (int u = 0; u < 2 * LDI; ++u) issue_load(kt, slot, u);
   };
 
   f32x16 acc[NB][NB];
@@ -157,14 +156,14 @@ __global__ __launch_bounds__(NT) void gemm_bf16_kernel(Bf16Desc g) {
       koff[kk][par] = ((((lr & 3) << 2) + kk * 2 + lh) ^ ((lr >> 2) + 8 * par)) << 4;
   bf16x8 fa[2][NB], fb[2][NB];
   // fragment f in [0, 2*NB) of sub-step kk: first the NB row blocks of A, then the NB of B
-  auto load_frag = [&](int kt, int kk, int f) {
-    const int o = (kt & (STAGES - 1)) * BUF_BYTES;
+  auto load_frag = [&](int slot, int kk, int f) {
+    const int o = slot * BUF_BYTES;
     if (f < NB) fa[kk][f] = *(const bf16x8*)(Afr + o + koff[kk][f & 1] + f * 2048);
     else fb[kk][f - NB] = *(const bf16x8*)(Bfr + o + koff[kk][(f - NB) & 1] + (f - NB) * 2048);
   };
-  auto load_frags = [&](int kt, int kk) {
+  auto load_frags = [&](int slot, int kk) {
 #pragma unroll
-    for (int f = 0; f < 2 * NB; ++f) load_frag(kt, kk, f);
+    for (int f = 0; f < 2 * NB; ++f) load_frag(slot, kk, f);
   };
   auto mfma_one = [&](int set, int m) {
     const int i = m / NB, j = m % NB;
@@ -177,10 +176,11 @@ __global__ __launch_bounds__(NT) void gemm_bf16_kernel(Bf16Desc g) {
       for (int j = 0; j < NB; ++j)
         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[set][i], fb[set][j], acc[i][j], 0, 0, 0);
   };
-  // wait until the loads of slab `kt` have landed: up to two younger slabs may still be in flight
+  // wait until the loads of slab `kt` have landed: up to STAGES - 2 younger slabs may still be in flight
   auto wait_slab = [&](int kt) {
     const int younger = KT - 1 - kt;
-    if (younger >= 2) wait_vmcnt<4 * LDI>();
+    if (younger >= 3 && STAGES >= 5) wait_vmcnt<6 * LDI>();
+    else if (younger >= 2) wait_vmcnt<4 * LDI>();
     else if (younger == 1) wait_vmcnt<2 * LDI>();
     else wait_vmcnt<0>();
   };
@@ -287,52 +287,57 @@ __global__ __launch_bounds__(NT) void gemm_bf16_kernel(Bf16Desc g) {
       slab(kt + 2, s2, slot, no(), no(), no());
     }
   } else {
-  // Main loop.  Slab kt+3 is requested at the top of slab kt (its ring slot was released by the
-  // barrier that closed slab kt-1); the fragments of the second half of slab kt are read while
-  // its first half computes, and after the single barrier of the slab the first fragments of
-  // slab kt+1 are read while the second half computes.
-  static_assert(BK == 32 && STAGES == 4, "pipeline written for two sub-steps per slab and a ring of four");
+  // Main loop.  Slab kt+STAGES-1 is requested at the top of slab kt (its ring slot was released
+  // by the barrier that closed slab kt-1); the fragments of the second half of slab kt are read
+  // while its first half computes, and after the single barrier of the slab the first fragments
+  // of slab kt+1 are read while the second half computes.
+  static_assert(BK == 32 && (STAGES == 4 || STAGES == 5), "pipeline written for two sub-steps per slab");
 #pragma unroll
   for (int s0 = 0; s0 < STAGES - 1; ++s0)
-    if (s0 < KT) issue_loads(s0);
+    if (s0 < KT) issue_loads(s0, s0);
   wait_slab(0);
   ring_barrier();
   load_frags(0, 0);
-  int kt = 0;
+  int kt = 0, slot = 0;                 // slot = kt mod STAGES
   const int KT_main = (g.dbg & 1) ? 0 : KT - (STAGES - 1);
   constexpr int NF = 2 * NB;            // fragment reads per sub-step = interleave steps
   constexpr int MPS = NB * NB / NF;     // MFMAs per interleave step
   static_assert(2 * LDI == NF, "one load instruction per interleave step");
   for (; kt < KT_main; ++kt) {          // steady state: no conditions inside
-    // sub-step 0 of slab kt: request slab kt+3 and read the fragments of sub-step 1, one of each
-    // between MFMAs so that they issue in the shadow of the matrix pipe
+    const int nslot = slot == STAGES - 1 ? 0 : slot + 1;
+    const int lslot = slot == 0 ? STAGES - 1 : slot - 1;   // slot of slab kt-1 = slot of slab kt+STAGES-1
+    // sub-step 0 of slab kt: request slab kt+STAGES-1 and read the fragments of sub-step 1, one of
+    // each between MFMAs so that they issue in the shadow of the matrix pipe
 #pragma unroll
     for (int u = 0; u < NF; ++u) {
-      issue_load(kt + STAGES - 1, u);
-      load_frag(kt, 1, u);
+      issue_load(kt + STAGES - 1, lslot, u);
+      load_frag(slot, 1, u);
 #pragma unroll
       for (int v = 0; v < MPS; ++v) mfma_one(0, u * MPS + v);
       __builtin_amdgcn_sched_barrier(0);
     }
-    wait_vmcnt<4 * LDI>();              // slab kt+1 has landed; kt+2 and kt+3 may be in flight
+    wait_vmcnt<2 * (STAGES - 2) * LDI>();   // slab kt+1 has landed; the younger ones may be in flight
     ring_barrier();
 #pragma unroll
     for (int u = 0; u < NF; ++u) {
-      load_frag(kt + 1, 0, u);
+      load_frag(nslot, 0, u);
 #pragma unroll
       for (int v = 0; v < MPS; ++v) mfma_one(1, u * MPS + v);
       __builtin_amdgcn_sched_barrier(0);
     }
+    slot = nslot;
   }
   for (; kt < KT; ++kt) {               // drain: nothing left to request
-    load_frags(kt, 1);
+    const int nslot = slot == STAGES - 1 ? 0 : slot + 1;
+    load_frags(slot, 1);
     mfma_block(0);
     if (kt + 1 < KT) {
       if (g.dbg & 1) wait_vmcnt<0>(); else wait_slab(kt + 1);
     }
     ring_barrier();
-    if (kt + 1 < KT) load_frags(kt + 1, 0);
+    if (kt + 1 < KT) load_frags(nslot, 0);
     mfma_block(1);
+    slot = nslot;
   }
 
   }
@@ -517,6 +522,8 @@ __global__ __launch_bounds__(NT) void gemm_bf16_kernel(Bf16Desc g) {
   if (EPI == BEPI_GRAM) {
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) part += __shfl_down(part, off, 64);
+    float* red = (float*)smem;          // the epilogue strips are dead once every wave is here
+    __syncthreads();
     if (lane == 0) red[wave] = part;
     __syncthreads();
     if (t == 0) g.rho_part[(long long)b * per_mat + rem] = red[0] + red[1] + red[2] + red[3];

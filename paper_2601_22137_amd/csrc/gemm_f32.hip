@@ -40,6 +40,8 @@ template <typename TC> __device__ inline int acc_row(int lane, int r);
 template <> __device__ inline int acc_row<float>(int lane, int r) { return 4 * (lane >> 4) + r; }
 template <> __device__ inline int acc_row<double>(int lane, int r) { return 4 * r + (lane >> 4); }
 
+__device__ inline float apow(float alpha, int p) { return p == 0 ? 1.0f : (p == 1 ? alpha : alpha * alpha); }
+
 // Applies the fused epilogue to one element, stores it, returns its contribution to the residual
 // sum; `out` receives the stored value (for the mirrored store of the symmetric variants).
 template <typename TC>
@@ -65,9 +67,8 @@ __device__ inline TC epilogue(const GemmDesc& g, int b, int i, int j, TC acc, fl
     }
     case EPI_AXPY: {
       const float cin = ((const float*)g.Cin)[(long long)b * g.strideCin + (long long)i * g.ldcin + j];
-      const float coef = g.coef_is_alpha ? alpha : 1.0f;
-      float v = g.c_in * cin + coef * (float)acc;
-      if (g.Cin2) v += g.Cin2[(long long)b * g.strideCin + (long long)i * g.ldcin + j];
+      float v = g.c_in * apow(alpha, g.cin_alpha_pow) * cin + apow(alpha, g.coef_is_alpha) * (float)acc;
+      if (g.Cin2) v += apow(alpha, g.cin2_alpha_pow) * g.Cin2[(long long)b * g.strideCin + (long long)i * g.ldcin + j];
       ((float*)g.C)[oc] = v;
       out = (TC)v;
       return 0;

@@ -434,26 +434,33 @@ int run_inv_root_f32(Run& r) {
     ax.coef_is_alpha = 1; ax.sym = f32_sym();   // X_k and R_k commute; the power chain below keeps all tiles
     { ProfScope ps(PK_F32_APPLY, r.s); CHECK_LAUNCH(launch_gemm_f32(ax, T, T, r.s)); }
     // (I + alpha R)^p = I + E_p, built on the part beyond the identity so that fp32 rounding acts
-    // on the small quantity only: E_1 = alpha R, squaring E <- 2E + E E, times T: E <- E + E_1 + E E_1
-    { ProfScope ps(PK_MAKE_T, r.s); launch_make_e(Tm[0], R, r.ctrl, P.batch, Sp, r.s); }
-    CHECK_LAUNCH(check_hip());
-    const float* U = Tm[0];
+    // on the small quantity only: E_1 = alpha R, squaring E <- 2E + E E, times T: E <- E + E_1 + E E_1.
+    // E_1 itself is never stored: wherever it is an operand R stands in and the epilogue supplies
+    // the powers of alpha.
+    const float* U = nullptr;   // null: E = E_1 = alpha R
     int hb = 0;
     while ((p >> (hb + 1)) != 0) ++hb;
     for (int bit = hb - 1; bit >= 0; --bit) {
       float* dst = (U == Tm[1]) ? Tm[2] : Tm[1];
-      GemmDesc sq = f32_desc(r, U, Sp, SS, U, Sp, SS, Sp, Sp, Sp, 0);
-      sq.epi = EPI_AXPY; sq.C = dst; sq.strideC = SS; sq.ldc = Sp; sq.Cin = U; sq.strideCin = SS; sq.ldcin = Sp; sq.c_in = 2.0f;
+      const float* E = U ? U : R;
+      GemmDesc sq = f32_desc(r, E, Sp, SS, E, Sp, SS, Sp, Sp, Sp, 0);
+      sq.epi = EPI_AXPY; sq.C = dst; sq.strideC = SS; sq.ldc = Sp; sq.Cin = E; sq.strideCin = SS; sq.ldcin = Sp; sq.c_in = 2.0f;
+      if (!U) { sq.cin_alpha_pow = 1; sq.coef_is_alpha = 2; }
       { ProfScope ps(PK_F32_STORE, r.s); CHECK_LAUNCH(launch_gemm_f32(sq, T, T, r.s)); }
       U = dst;
       if ((p >> bit) & 1) {
         float* dst2 = (U == Tm[1]) ? Tm[2] : Tm[1];
-        GemmDesc mu = f32_desc(r, U, Sp, SS, Tm[0], Sp, SS, Sp, Sp, Sp, 0);
+        GemmDesc mu = f32_desc(r, U, Sp, SS, R, Sp, SS, Sp, Sp, Sp, 0);          // E + alpha R + alpha E R
         mu.epi = EPI_AXPY; mu.C = dst2; mu.strideC = SS; mu.ldc = Sp; mu.Cin = U; mu.strideCin = SS; mu.ldcin = Sp; mu.c_in = 1.0f;
-        mu.Cin2 = Tm[0];
+        mu.Cin2 = R; mu.cin2_alpha_pow = 1; mu.coef_is_alpha = 1;
         { ProfScope ps(PK_F32_STORE, r.s); CHECK_LAUNCH(launch_gemm_f32(mu, T, T, r.s)); }
         U = dst2;
       }
+    }
+    if (!U) {   // p = 1: E_p = alpha R.  The product below overwrites R, so it cannot read R as an operand
+      { ProfScope ps(PK_MAKE_T, r.s); launch_make_e(Tm[0], R, r.ctrl, P.batch, Sp, r.s); }
+      CHECK_LAUNCH(check_hip());
+      U = Tm[0];
     }
     GemmDesc mn = {};                                                             // M' = M + E_p M in fp64
     mn.A = U; mn.strideA = SS; mn.lda = Sp; mn.B = M[cur]; mn.strideB = SS; mn.ldb = Sp;
