@@ -276,19 +276,24 @@ int run_polar_f32(Run& r) {
   return PRISM_OK;
 }
 
-// 256 x 256 tiles when they still give every CU work and K is long enough to amortise their
-// epilogue (one workgroup per CU, nothing overlaps it), else 128 x 128 (two workgroups per CU)
-int bf16_tile(const Plan& P, int M, int N, int K) {
+// 256 x 256 tiles (one workgroup per CU) move half the bytes per flop of 128 x 128 ones (two per
+// CU) but nothing overlaps their epilogue: they are taken when they still give every CU work and
+// K is long enough to amortise it.  (At K = 768 the bare product is faster with large tiles from
+// 144 tiles on, the update GEMM with its three-output epilogue is not.)
+int bf16_tile(const Plan& P, int M, int N, int K, bool symmetric) {
   static const int forced = getenv("PRISM_BF16_TILE") ? atoi(getenv("PRISM_BF16_TILE")) : 0;
   if (P.tile != 256) return 128;
   if (forced == 128 || forced == 256) return forced;
-  return ((long long)(M / 256) * (N / 256) * P.batch >= 192 && K >= 2048) ? 256 : 128;
+  const long long per_mat = symmetric ? (long long)(M / 256) * (M / 256 + 1) / 2 : (long long)(M / 256) * (N / 256);
+  return (per_mat * P.batch >= 192 && K >= 2048) ? 256 : 128;
 }
 
 int run_polar_bf16(Run& r) {
   const Plan& P = r.P;
   const int Sp = P.Sp, Lp = P.Lp;
-  const int Tg = bf16_tile(P, Sp, Sp, Sp), Ta = bf16_tile(P, Lp, Sp, Sp);
+  static const int no_sym = getenv("PRISM_BF16_NO_SYM") ? atoi(getenv("PRISM_BF16_NO_SYM")) : 0;
+  const int sym = no_sym ? 0 : 1;
+  const int Tg = bf16_tile(P, Sp, Sp, Lp, sym != 0), Ta = bf16_tile(P, Lp, Sp, Sp, false);
   const long long SS = (long long)Sp * Sp, LS = (long long)Lp * Sp;
   uint16_t* Xhi[2] = {r.at<uint16_t>(P.o_xhi[0]), r.at<uint16_t>(P.o_xhi[1])};
   uint16_t* Xlo[2] = {P.split ? r.at<uint16_t>(P.o_xlo[0]) : nullptr, P.split ? r.at<uint16_t>(P.o_xlo[1]) : nullptr};
@@ -296,9 +301,7 @@ int run_polar_bf16(Run& r) {
   float* R = r.at<float>(P.o_r);
   uint16_t* Rb = r.at<uint16_t>(P.o_rb);
   uint16_t* Qb = P.d == 2 ? r.at<uint16_t>(P.o_qb) : nullptr;
-  static const int no_sym = getenv("PRISM_BF16_NO_SYM") ? atoi(getenv("PRISM_BF16_NO_SYM")) : 0;
   static const int no_dual = getenv("PRISM_BF16_NO_DUAL") ? atoi(getenv("PRISM_BF16_NO_DUAL")) : 0;
-  const int sym = no_sym ? 0 : 1;
   const int ntg = Sp / Tg;
   const int nparts = sym ? ntg * (ntg + 1) / 2 : ntg * ntg;
   int cur = 0;
