@@ -83,6 +83,7 @@ struct Bf16Desc {
   int coef_is_alpha;                                 // APPLY: multiply acc by ctrl.alpha (d = 1)
   float* rho_part;
   const Ctrl* ctrl;
+  int xcd_private;                                   // set by launch_gemm_bf16: contiguous tile ranges per XCD
   int dbg;                                           // timing experiments only (test entry): bit0: no global loads after the prologue; bit1: XCD-private tile ranges; bit2: 4x8 tile blocks
 };
 int launch_gemm_bf16(const Bf16Desc& g, int tile, hipStream_t s);

@@ -38,7 +38,10 @@ __device__ inline float bf2f(unsigned short h) { return __uint_as_float(((unsign
 typedef const void __attribute__((address_space(1)))* gptr_t;
 typedef void __attribute__((address_space(3)))* lptr_t;
 
-constexpr int STAGES = 4;    // LDS ring: loads run three slabs ahead of the MFMAs (a ring of five measured no faster)
+// LDS ring depth: loads run STAGES - 1 slabs ahead of the MFMAs.  T = 256: four (one workgroup per
+// CU; a ring of five measured no faster).  T = 128: three, so that three workgroups fit a CU and
+// overlap each other's prologue and epilogue (the 768-sized products are short: 24 slabs).
+constexpr int stages_of(int T) { return T == 128 ? 3 : 4; }
 
 // s_waitcnt vmcnt(N) with the other counters left alone (gfx9 encoding)
 template <int N> __device__ inline void wait_vmcnt() {
@@ -48,7 +51,8 @@ template <int N> __device__ inline void wait_vmcnt() {
 // DUAL (update GEMM with a split iterate): every K slab holds the high and the low half of A next
 // to the one slab of B they both multiply, so B passes through the LDS once instead of twice.
 template <int T, int EPI, bool SYM, bool DUAL>
-__global__ __launch_bounds__(NT) void gemm_bf16_kernel(Bf16Desc g) {
+__global__ __launch_bounds__(NT, T == 128 ? 3 : 1) void gemm_bf16_kernel(Bf16Desc g) {
+  constexpr int STAGES = stages_of(T);
   constexpr int WT = T / 2;         // wave tile (2 x 2 waves)
   constexpr int NB = WT / 32;       // 32x32 blocks per wave and dimension
   constexpr int LDI = T / 64;       // direct-to-LDS load instructions per wave, operand and slab
@@ -69,13 +73,13 @@ __global__ __launch_bounds__(NT) void gemm_bf16_kernel(Bf16Desc g) {
   const int total = per_mat * g.batch;
   int wg = blockIdx.x;
   // Workgroup -> tile.  The hardware deals consecutive workgroups round-robin to the 8 XCDs, each
-  // with its own L2.  Small matrices (all tiles of one matrix fit on one XCD at once): give every
-  // XCD a contiguous range of tiles, i.e. whole matrices, so that the tiles sharing a panel share
-  // an L2 (without this the 768-sized Gram fetched 7x its algorithmic bytes).  Large matrices:
-  // workgroup i runs tile i, all XCDs sweep the same matrix and share its panels through the
-  // Infinity Cache (private ranges measured 20 % slower at 8 x 4096^2: eight matrices at once
-  // overflow that cache).
-  const bool xcd_private = (per_mat <= 64) != ((g.dbg & 2) != 0);
+  // with its own L2.  g.xcd_private (set by the launcher for small matrices, or when all operands
+  // of the launch fit the Infinity Cache together): every XCD gets a contiguous range of tiles, i.e. whole matrices, so
+  // that the tiles sharing a panel share an L2 (without this the 768-sized Gram fetched 7x its
+  // algorithmic bytes).  Otherwise workgroup i runs tile i: all XCDs sweep the same matrix and
+  // share its panels through the Infinity Cache (private ranges measured 20 % slower at
+  // 8 x 4096^2, where eight matrices at once overflow that cache).
+  const bool xcd_private = (g.xcd_private != 0) != ((g.dbg & 2) != 0);
   if ((total & 7) == 0 && xcd_private) wg = (wg & 7) * (total >> 3) + (wg >> 3);
   const int b = wg / per_mat;
   int rem = wg - b * per_mat;
@@ -180,8 +184,8 @@ __global__ __launch_bounds__(NT) void gemm_bf16_kernel(Bf16Desc g) {
   auto wait_slab = [&](int kt) {
     const int younger = KT - 1 - kt;
     if (younger >= 3 && STAGES >= 5) wait_vmcnt<6 * LDI>();
-    else if (younger >= 2) wait_vmcnt<4 * LDI>();
-    else if (younger == 1) wait_vmcnt<2 * LDI>();
+    else if (younger >= 2 && STAGES >= 4) wait_vmcnt<4 * LDI>();
+    else if (younger >= 1) wait_vmcnt<2 * LDI>();
     else wait_vmcnt<0>();
   };
 
@@ -291,7 +295,7 @@ __global__ __launch_bounds__(NT) void gemm_bf16_kernel(Bf16Desc g) {
   // by the barrier that closed slab kt-1); the fragments of the second half of slab kt are read
   // while its first half computes, and after the single barrier of the slab the first fragments
   // of slab kt+1 are read while the second half computes.
-  static_assert(BK == 32 && (STAGES == 4 || STAGES == 5), "pipeline written for two sub-steps per slab");
+  static_assert(BK == 32 && STAGES >= 3 && STAGES <= 5, "pipeline written for two sub-steps per slab");
 #pragma unroll
   for (int s0 = 0; s0 < STAGES - 1; ++s0)
     if (s0 < KT) issue_loads(s0, s0);
@@ -535,7 +539,7 @@ int launch_te(const Bf16Desc& g, hipStream_t s) {
   const int tm = g.M / T, tn = g.N / T;
   const int total = (SYM ? tm * (tm + 1) / 2 : tm * tn) * g.batch;
   // ring of STAGES x (A slab + B slab), or of 3 x (A_hi + A_lo + B)
-  const size_t lds = DUAL ? (size_t)3 * 3 * T * 64 : (size_t)STAGES * 2 * T * 64;
+  const size_t lds = DUAL ? (size_t)3 * 3 * T * 64 : (size_t)stages_of(T) * 2 * T * 64;
   static bool attr_set = false;  // per instantiation
   if (!attr_set) {
     if (hipFuncSetAttribute((const void*)gemm_bf16_kernel<T, EPI, SYM, DUAL>, hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -566,7 +570,13 @@ int launch_t(const Bf16Desc& g, hipStream_t s) {
 
 }  // namespace
 
-int launch_gemm_bf16(const Bf16Desc& g, int tile, hipStream_t s) {
+int launch_gemm_bf16(const Bf16Desc& g0, int tile, hipStream_t s) {
+  Bf16Desc g = g0;
+  // bytes of all operands of the launch against half the 256 MiB Infinity Cache
+  const double operand_bytes = 2.0 * g.batch * ((double)g.M * g.K * (g.A2 ? 2 : 1) + (g.A == g.B ? 0.0 : (double)g.N * g.K));
+  const long long tm = g.M / tile, tn = g.N / tile;
+  const long long per_mat = g.sym ? tm * (tm + 1) / 2 : tm * tn;
+  g.xcd_private = per_mat <= 64 || operand_bytes <= 128.0 * 1024 * 1024;
   if (tile == 256) return launch_t<256>(g, s);
   if (tile == 128) return launch_t<128>(g, s);
   return PRISM_EINVAL;
