@@ -26,13 +26,16 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5"])
+    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5", "sign", "inverse"])
     ap.add_argument("--split", action="store_true", help="c2: carry the iterate as a bf16 high+low pair")
     ap.add_argument("--batch", type=int, default=0, help="override the batch size (c3/c4/c5)")
     ap.add_argument("--streams", type=int, default=0,
                     help="HIP streams the calls of one step are spread over (default: one per shape group, i.e. 4 for c2)")
     ap.add_argument("--sub-batches", type=int, default=1,
                     help="split every group's batch into this many calls (spread over the streams)")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture every step's calls in a HIP graph beforehand and time the replays (one stream)")
+    ap.add_argument("--only-group", type=int, default=-1, help="c2: run a single shape group (profiling aid)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
     ap.add_argument("--no-profile", action="store_true", help="skip the per-kernel event pass")
     ap.add_argument("--copy-probe", action="store_true",
@@ -53,7 +56,7 @@ def make_workload(args, torch, prism, W):
         wl.desc = "muon-shaped: 64 bf16 matrices = 16 x {768x768, 768x3072, 3072x768, 768x2304}, degree 5, sketch 16, 5 iterations" + \
                   (", split-bf16 iterate" if args.split else ", plain bf16 iterate")
         wl.dtype = "bf16"
-        wl.host = [W.c2_muon_group(i) for i in range(4)]
+        wl.host = [W.c2_muon_group(i) for i in range(4) if args.only_group < 0 or i == args.only_group]
         wl.flags = 0 if args.split else prism.FLAG_BF16_PLAIN_ITERATE
         wl.call = lambda x: prism.polar(x, 5, 5, 16, wl.seed, 0.0, flags=wl.flags)
         wl.split = args.split
@@ -76,6 +79,18 @@ def make_workload(args, torch, prism, W):
         wl.dtype = "f32"
         wl.host = [W.c5_wishart_spd(batch=b)]
         wl.call = lambda x: prism.sqrt(x, 5, 40, 64, wl.seed, 1e-5)[1]
+    elif name == "sign":
+        b = args.batch or 8
+        wl.desc = "matrix sign of %d x 2048x2048 fp32 symmetric indefinite (|lambda| over 2 decades), degree 5, sketch 32, tol 1e-5" % b
+        wl.dtype = "f32"
+        wl.host = [W.sign_indefinite(n=2048, batch=b, decades=2.0)]
+        wl.call = lambda x: prism.sign(x, 5, 40, 32, wl.seed, 1e-5)
+    elif name == "inverse":
+        b = args.batch or 8
+        wl.desc = "Chebyshev inverse of %d x 2048x2048 fp32 non-symmetric (cond 30), sketch 32, tol 1e-5" % b
+        wl.dtype = "f32"
+        wl.host = [W.inverse_general(n=2048, batch=b, cond=30.0)]
+        wl.call = lambda x: prism.inverse(x, 40, 32, wl.seed, 1e-5)
     else:
         wl.desc = "polar of one 64x32 fp32 matrix, cond 1e3, degree 5, sketch 8, tol 1e-6"
         wl.dtype = "f32"
@@ -99,6 +114,8 @@ def flops_per_iteration(name, m, n, split):
         return algo, algo + (2.0 * L * S * S if split else 0.0)
     if name == "c5":
         return 8.0 * n ** 3, 8.0 * n ** 3
+    if name in ("sign", "inverse"):      # residual product, R^2, update
+        return 6.0 * n ** 3, 6.0 * n ** 3
     return 8.0 * n ** 3, 8.0 * n ** 3      # c4, p = 4: X R, T^2, T^4, T^4 M
 
 
@@ -112,6 +129,10 @@ def oracle_call(name, host_matrix, W, O, seed):
     if name == "c5":
         r, _, info = O.sqrt(host_matrix, 5, 40, 64, seed, 1e-5)
         return r, info
+    if name == "sign":
+        return O.sign(host_matrix, 5, 40, 32, seed, 1e-5)
+    if name == "inverse":
+        return O.inverse(host_matrix, 40, 32, seed, 1e-5)
     return O.polar(host_matrix, 5, 30, 8, seed, 1e-6)
 
 
@@ -202,14 +223,39 @@ def main():
             hs.append(Joined(sub))
         return hs
 
+    graphs = None
+    if args.graph:
+        # the calls allocate nothing once their workspace exists, so a step can be captured as is;
+        # a graph holds fixed pointers, hence one graph per resident copy
+        side = None
+        cap = torch.cuda.Stream()
+        with torch.cuda.stream(cap):
+            step(0)                      # creates the workspace of this stream
+            cap.synchronize()
+            for dst, src in zip(copies[0], pristine):
+                dst.copy_(src)
+            graphs = []
+            for i in range(n_copies):
+                gr = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(gr, stream=cap):
+                    hs = step(i)
+                graphs.append((gr, hs))
+        torch.cuda.synchronize()
+
+        def run_step(i):
+            graphs[i][0].replay()
+            return graphs[i][1]
+    else:
+        run_step = step
+
     for i in range(Wm):
-        step(i)
+        run_step(i)
     torch.cuda.synchronize()
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     ev0.record()
     handles = None
     for i in range(K):
-        handles = step(Wm + i)
+        handles = run_step(Wm + i)
     if side is not None:
         for st in side:
             torch.cuda.current_stream().wait_stream(st)
@@ -245,7 +291,7 @@ def main():
             threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
         except Exception:
             threads = len(os.sched_getaffinity(0))
-        per_group = {"c1": 1, "c2": 2, "c3": 1, "c4": 4, "c5": 1}[wl.name]
+        per_group = {"c1": 1, "c2": 2, "c3": 1, "c4": 4, "c5": 1, "sign": 1, "inverse": 1}[wl.name]
         if wl.name in ("c3", "c5") and wl.host[0].shape[1] > 2048:
             per_group = 1
         t_cpu, n_cpu, worst = 0.0, 0, 0.0
@@ -313,7 +359,7 @@ def main():
         "dtype": wl.dtype, "data": "synthetic",
         "config": {"workload": wl.name + ": " + wl.desc, "matrices_per_step": wl.n_matrices,
                    "input_bytes_per_step": bytes_per_copy, "streams": nstreams,
-                   "calls_per_step": len(wl.host) * nsub},
+                   "calls_per_step": len(wl.host) * nsub, "hip_graph": bool(args.graph)},
         "tflops_algorithmic": round(tflops_algo, 2), "tflops_executed": round(tflops_exec, 2),
         "frac_of_mfma_peak": round(tflops_exec / PEAK[wl.dtype], 4),
         "iterations": {"min": min(iters_all), "max": max(iters_all)},

@@ -209,3 +209,37 @@ def test_invalid_arguments(prism):
         prism.inv_root(x, 9, 5, 8, SEED, 1e-6)
     with pytest.raises(prism.PrismError):
         prism.sqrt(x.to(torch.bfloat16), 5, 5, 8, SEED, 1e-6)
+
+
+def test_call_replays_from_a_hip_graph(prism):
+    """A call only enqueues kernels (no allocation with a caller workspace, no memset, no host
+    read), so it can be captured once and replayed: every replay must reproduce the eager result
+    bit for bit, with eager work and synchronisations between the replays."""
+    A = W.c1_polar_small(m=200, n=96)
+    src = torch.from_numpy(A.copy()).cuda()
+    nbytes = prism.workspace_bytes(prism.FN_POLAR, 1, 200, 96, prism.F32, 5, 8)
+    ws = torch.empty(nbytes + 256, dtype=torch.uint8, device="cuda")
+    ws = ws[(-ws.data_ptr()) % 256:][:nbytes]
+    x = src.clone()
+    info_eager = prism.polar(x, 5, 30, 8, SEED, 1e-6, workspace=ws).read()
+    eager = x.clone()
+    ref, oinfo = O.polar(A[0], 5, 30, 8, SEED, 1e-6)
+    assert _rel(eager.cpu().numpy()[0], ref) <= TOL_F32
+
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        x.copy_(src)
+        prism.polar(x, 5, 30, 8, SEED, 1e-6, workspace=ws)      # warm-up on the capture stream
+        side.synchronize()
+        x.copy_(src)
+        with torch.cuda.graph(graph, stream=side):
+            handle = prism.polar(x, 5, 30, 8, SEED, 1e-6, workspace=ws)
+        for _ in range(3):
+            x.copy_(src)                                         # eager work between the replays
+            graph.replay()
+            side.synchronize()
+            assert torch.equal(x, eager)
+            info = handle.read()
+            assert info[0]["iters"] == info_eager[0]["iters"] and info[0]["status"] == info_eager[0]["status"]
+            assert np.array_equal(info[0]["alpha"], info_eager[0]["alpha"])
