@@ -44,7 +44,17 @@ Readings of the paper taken here (the paper is silent or garbled):
     without a fit alpha_k is the Taylor value 1 (the classical iteration), which
     is not the lower end of the printed interval [1/2, 2]; the objective is taken
     with R_k symmetric (it is, for X_0 = A_s^T: R_k is a polynomial in A A^T), so
-    ||S h(R)||_F = ||h(R) S^T||_F and the chain again multiplies from the left.
+    ||S h(R)||_F = ||h(R) S^T||_F and the chain again multiplies from the left;
+  * DB Newton (App. A.2, product form): X_0 = M_0 = A and Y_0 = I as printed (no
+    normalisation); the residual of the stop rule is I - M_k (Table 1: I - X_k Y_k);
+    alpha_k minimises the printed quartic over [0, 1].  The paper imposes no interval;
+    every eigenvalue mu of M_k contributes a term whose two zeros are
+    sqrt(mu)/(sqrt(mu)+1), inside (0, 1), and sqrt(mu)/(sqrt(mu)-1), outside [0, 1],
+    where (1-alpha) + alpha/mu < 0 and X_{k+1} loses definiteness; the zeros outside
+    scatter over the real line, those inside cluster, so the unconstrained global
+    minimiser lies in (0, 1) whenever the spectrum has more than one point (pinned
+    on random spectra) and the interval only breaks the exact tie of a one-point
+    spectrum; without a fit alpha_k = 1/2, the classical iteration.
 """
 from math import comb
 
@@ -414,3 +424,57 @@ def inverse(A, max_iters=30, sketch_dim=8, seed=22137, tol=1e-6,
         X = X @ (np.eye(n) + R + alpha * R2)
         k += 1
     return X / s, loop.info()
+
+
+def db_newton_coefficients(M, N):
+    """Coefficients c_0..c_4 of m(alpha) = ||I - M_{k+1}(alpha)||_F^2 for the product form of
+    DB Newton (App. A.2), M_{k+1} = 2 alpha (1 - alpha) I + (1 - alpha)^2 M + alpha^2 N, N = M^{-1}:
+        M_{k+1} - I = (1 - 2 alpha) D_0 + alpha^2 D_2,   D_0 = M - I,   D_2 = M + N - 2 I,
+    so c_0 = <D_0,D_0>, c_1 = -4 <D_0,D_0>, c_2 = 4 <D_0,D_0> + 2 <D_0,D_2>, c_3 = -4 <D_0,D_2>,
+    c_4 = <D_2,D_2> (Frobenius inner products: O(n^2), no matrix product).  Expanding the inner
+    products gives the printed combinations of n, tr M, tr M^2, tr M^-1, tr M^-2 (pinned in the
+    tests); those subtract nearly equal numbers once M is close to I and stall the iteration at
+    a residual of about sqrt(machine epsilon), this form does not."""
+    n = M.shape[0]
+    D0 = M - np.eye(n)
+    D2 = M + N - 2.0 * np.eye(n)
+    g00, g02, g22 = np.sum(D0 * D0), np.sum(D0 * D2), np.sum(D2 * D2)
+    return np.array([g00, -4.0 * g00, 4.0 * g00 + 2.0 * g02, -4.0 * g02, g22])
+
+
+DB_NEWTON_INTERVAL = (0.0, 1.0)     # reading, see the module docstring
+
+
+def sqrt_db_newton(A, max_iters=30, tol=1e-6, fit=True, alpha_schedule=None):
+    """A^{1/2} and A^{-1/2} of a symmetric positive definite A by the PRISM-accelerated DB Newton
+    iteration in product form (Table 1, row "DB Newton"; App. A.2):
+        M_0 = X_0 = A, Y_0 = I, N_k = M_k^{-1},
+        M_{k+1} = 2 a (1 - a) I + (1 - a)^2 M_k + a^2 N_k,
+        X_{k+1} = (1 - a) X_k + a X_k N_k,   Y_{k+1} = (1 - a) Y_k + a Y_k N_k,   a = alpha_k,
+    alpha_k = argmin ||I - M_{k+1}||_F^2 (exact traces, no sketch).  fit = False keeps
+    alpha_k = 1/2.  Returns (X, Y, info)."""
+    A = np.asarray(A, dtype=np.float64)
+    bad = _precheck(A)
+    if bad is not None:
+        return A.copy(), np.zeros_like(A), _early(A, bad)
+    n = A.shape[0]
+    I = np.eye(n)
+    X, Y, M = A.copy(), I.copy(), A.copy()
+    loop = _Loop(n, max_iters, tol)
+    k = 0
+    while True:
+        if loop.stop(I - M, k):
+            break
+        N = np.linalg.inv(M)
+        if alpha_schedule is not None and k < len(alpha_schedule):
+            a = float(alpha_schedule[k])
+        elif not fit:
+            a = 0.5
+        else:
+            a = minimize_poly_on_interval(db_newton_coefficients(M, N), *DB_NEWTON_INTERVAL)
+        loop.alpha.append(a)
+        X = (1.0 - a) * X + a * (X @ N)
+        Y = (1.0 - a) * Y + a * (Y @ N)
+        M = 2.0 * a * (1.0 - a) * I + (1.0 - a) ** 2 * M + a * a * N
+        k += 1
+    return X, Y, loop.info()
