@@ -26,7 +26,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5", "sign", "inverse"])
+    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5", "sign", "inverse", "sqrt-newton"])
     ap.add_argument("--split", action="store_true", help="c2: carry the iterate as a bf16 high+low pair")
     ap.add_argument("--batch", type=int, default=0, help="override the batch size (c3/c4/c5)")
     ap.add_argument("--streams", type=int, default=0,
@@ -79,6 +79,12 @@ def make_workload(args, torch, prism, W):
         wl.dtype = "f32"
         wl.host = [W.c5_wishart_spd(batch=b)]
         wl.call = lambda x: prism.sqrt(x, 5, 40, 64, wl.seed, 1e-5)[1]
+    elif name == "sqrt-newton":
+        b = args.batch or 4
+        wl.desc = "sqrt + inverse sqrt of %d x 8192x8192 fp32 SPD (Wishart, the config-5 inputs) by PRISM DB Newton, tol 1e-5, at most 12 iterations" % b
+        wl.dtype = "f32"
+        wl.host = [W.c5_wishart_spd(batch=b)]
+        wl.call = lambda x: prism.sqrt_newton(x, 12, 1e-5)[1]
     elif name == "sign":
         b = args.batch or 8
         wl.desc = "matrix sign of %d x 2048x2048 fp32 symmetric indefinite (|lambda| over 2 decades), degree 5, sketch 32, tol 1e-5" % b
@@ -114,6 +120,8 @@ def flops_per_iteration(name, m, n, split):
         return algo, algo + (2.0 * L * S * S if split else 0.0)
     if name == "c5":
         return 8.0 * n ** 3, 8.0 * n ** 3
+    if name == "sqrt-newton":           # block Gauss-Jordan inverse (2 n^3) and the two updates
+        return 6.0 * n ** 3, 6.0 * n ** 3
     if name in ("sign", "inverse"):      # residual product, R^2, update
         return 6.0 * n ** 3, 6.0 * n ** 3
     return 8.0 * n ** 3, 8.0 * n ** 3      # c4, p = 4: X R, T^2, T^4, T^4 M
@@ -128,6 +136,9 @@ def oracle_call(name, host_matrix, W, O, seed):
         return O.inv_root(host_matrix, 4, 40, 16, seed, 1e-5)
     if name == "c5":
         r, _, info = O.sqrt(host_matrix, 5, 40, 64, seed, 1e-5)
+        return r, info
+    if name == "sqrt-newton":
+        r, _, info = O.sqrt_db_newton(host_matrix, 12, 1e-5)
         return r, info
     if name == "sign":
         return O.sign(host_matrix, 5, 40, 32, seed, 1e-5)
@@ -291,7 +302,7 @@ def main():
             threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
         except Exception:
             threads = len(os.sched_getaffinity(0))
-        per_group = {"c1": 1, "c2": 2, "c3": 1, "c4": 4, "c5": 1, "sign": 1, "inverse": 1}[wl.name]
+        per_group = {"c1": 1, "c2": 2, "c3": 1, "c4": 4, "c5": 1, "sign": 1, "inverse": 1, "sqrt-newton": 1}[wl.name]
         if wl.name in ("c3", "c5") and wl.host[0].shape[1] > 2048:
             per_group = 1
         t_cpu, n_cpu, worst = 0.0, 0, 0.0
@@ -331,7 +342,8 @@ def main():
         prof = prism.profile_collect()
         prism.profile_enable(False)
         kernel_ms = {k: round(v[0] / nprof, 4) for k, v in prof.items() if v[1]}
-        gemm_kinds = [k for k in prof if prof[k][1] and (k.startswith("bf16_") or k.startswith("f32_") or k.startswith("f64_"))]
+        gemm_kinds = [k for k in prof if prof[k][1] and (k.startswith("bf16_") or k.startswith("f32_") or k.startswith("f64_")
+                                                          or k == "spd_inverse")]
         dom = max(gemm_kinds, key=lambda k: prof[k][0])
         # algorithmic flops of all launches of that kind in the profiled steps
         fl = 0.0
@@ -340,8 +352,8 @@ def main():
             S, L = min(m, n), max(m, n)
             per_iter = {"bf16_apply": 2.0 * L * S * S, "bf16_gram": 2.0 * L * S * S, "bf16_polyq": 2.0 * S ** 3,
                         "f32_resid": 2.0 * L * S * S, "f32_polyq": 2.0 * S ** 3,
-                        "f32_apply": (4.0 if wl.name == "c5" else 2.0) * L * S * S,
-                        "f32_store": 4.0 * S ** 3, "f64_mnext": 2.0 * S ** 3}[dom]
+                        "f32_apply": (4.0 if wl.name in ("c5", "sqrt-newton") else 2.0) * L * S * S,
+                        "f32_store": 4.0 * S ** 3, "f64_mnext": 2.0 * S ** 3, "spd_inverse": 2.0 * S ** 3}[dom]
             for rec in inf:
                 nit = rec["iters"] + (1 if dom in ("bf16_gram", "f32_resid") and rec["status"] == prism.INFO_CONVERGED else 0)
                 fl += per_iter * nit

@@ -64,7 +64,8 @@ typedef enum {
 
 /* function ids; also the function tag of the sketch counter */
 typedef enum {
-  PRISM_FN_POLAR = 1, PRISM_FN_SQRT = 2, PRISM_FN_INV_ROOT = 3, PRISM_FN_SIGN = 4, PRISM_FN_INVERSE = 5
+  PRISM_FN_POLAR = 1, PRISM_FN_SQRT = 2, PRISM_FN_INV_ROOT = 3, PRISM_FN_SIGN = 4, PRISM_FN_INVERSE = 5,
+  PRISM_FN_SQRT_NEWTON = 6
 } prism_fn;
 
 enum {
@@ -155,6 +156,18 @@ int prism_inverse_ex(void* a, int batch, int m, int n, prism_dtype dt, int max_i
                      int sketch_dim, uint64_t seed, double tol, void* stream,
                      const prism_options* opt);
 
+/* Square root and inverse square root by the PRISM DB Newton iteration in product form (Table 1,
+ * "DB Newton"; App. A.2): a[batch][n][n] symmetric positive definite is replaced by A^{1/2},
+ * inv_out[batch][n][n] receives A^{-1/2}.  M_0 = X_0 = A, Y_0 = I, N_k = M_k^{-1} (block
+ * Gauss-Jordan on the device), alpha_k minimises ||I - M_{k+1}||_F^2 over [0, 1] from exact O(n^2)
+ * inner products (no sketch); fit = 0 keeps alpha_k = 1/2, the classical iteration.  The stop rule
+ * tests ||I - M_k||_F / sqrt(n).  m must equal n; fp32 only; options.warm_iters is ignored. */
+int prism_sqrt_newton(void* a, void* inv_out, int batch, int m, int n, prism_dtype dt, int max_iters,
+                      int fit, double tol, void* stream);
+int prism_sqrt_newton_ex(void* a, void* inv_out, int batch, int m, int n, prism_dtype dt,
+                         int max_iters, int fit, double tol, void* stream,
+                         const prism_options* opt);
+
 /* ---- single steps of the path, exposed for unit tests and profiling ---- */
 
 /* S_k^T (Section 4.2: Gaussian sketch): out[n][sketch_dim] fp32 on the device,
@@ -171,6 +184,11 @@ int prism_gauss_parts(uint32_t first, uint32_t count, double* radius, double* co
  * V[batch][n][ld], fp32 device arrays, n a multiple of 64, ld = 16, 32 or 64. */
 int prism_chain_product(const float* R, const float* V, float* out, int batch, int n, int ld,
                         void* stream);
+
+/* Inverse of symmetric positive definite matrices by block Gauss-Jordan elimination without
+ * pivoting (the N_k = M_k^{-1} step of DB Newton, App. A.2): out[batch][n][n] = a^{-1}, fp32
+ * device arrays, n a multiple of 64, a is left unchanged. */
+int prism_spd_inverse(const float* a, float* out, int batch, int n, void* stream);
 
 /* C[batch][M][N] = A * B on the matrix cores, no epilogue.  Device pointers.
  *   prism_gemm_f32 : fp32 in/out; bit 0 of a_km: A is stored [K][M].  B is [K][N].  Bit 1: the
@@ -192,7 +210,7 @@ int prism_gemm_bf16_nt(const uint16_t* A, const uint16_t* B, float* C, int batch
  * what was recorded so far.  prism_profile_collect waits for the recorded events and returns the
  * summed milliseconds and the launch counts per kernel kind (PRISM_PROFILE_KINDS host arrays).
  * Not thread safe; meant for a single benchmarking thread. */
-#define PRISM_PROFILE_KINDS 15
+#define PRISM_PROFILE_KINDS 18
 int prism_profile_enable(int on);
 int prism_profile_collect(double* ms_by_kind, long long* launches_by_kind, int nkinds);
 

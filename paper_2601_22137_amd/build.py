@@ -9,7 +9,7 @@ CSRC = os.path.join(HERE, "csrc")
 OUT = os.path.join(HERE, "libprism.so")
 BUILD_DIR = os.path.join(HERE, "_build")
 
-SOURCES = ["prism_api.hip", "gemm_f32.hip", "gemm_bf16.hip", "chain.hip", "fit.hip", "misc.hip", "sketch.hip"]
+SOURCES = ["prism_api.hip", "gemm_f32.hip", "gemm_bf16.hip", "chain.hip", "dbnewton.hip", "fit.hip", "misc.hip", "sketch.hip"]
 COMMON = ["--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17", "-I" + os.path.join(ROOT, "include"),
           "-I" + CSRC, "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument"]
 # the sketch generator is specified as unfused IEEE operations

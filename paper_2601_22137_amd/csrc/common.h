@@ -24,7 +24,7 @@ struct Ctrl {
 
 // ---- gemm_f32.hip : fp32 / fp64 matrix-core GEMMs with fused epilogues ----
 enum EpiKind {
-  EPI_STORE = 0,     // C = acc
+  EPI_STORE = 0,     // C = +-acc
   EPI_RESIDUAL = 1,  // R = I - acc (masked to n x n), rho partial
   EPI_POLYQ = 2,     // Q = c1 * Rin + alpha * acc
   EPI_AXPY = 3,      // C = c_in alpha^a * Cin + alpha^b * Cin2 + alpha^c * acc   (a, b, c in 0..2; Cin2 optional)
@@ -50,6 +50,10 @@ struct GemmDesc {
   int coef_is_alpha;    // AXPY: power of ctrl.alpha (0, 1, 2) that multiplies acc
   int cin_alpha_pow;    // AXPY: power of ctrl.alpha that multiplies Cin (besides c_in)
   int cin2_alpha_pow;   // AXPY: power of ctrl.alpha that multiplies Cin2
+  int cin_one_minus_alpha;  // AXPY: Cin is weighted by (1 - ctrl.alpha) (DB Newton updates)
+  int acc_neg;          // STORE, AXPY: acc enters with a minus sign
+  int skip_m0, skip_m1; // output tiles starting in rows [skip_m0, skip_m1) are left untouched (0, 0: none)
+  int skip_n0, skip_n1; // likewise for columns
   float* rho_part;      // [batch][tiles] partial sums of R^2 (RESIDUAL / MNEXT)
   const Ctrl* ctrl;     // may be null (test entry points)
 };
@@ -119,6 +123,8 @@ struct SolveArgs {
   int mode;          // 0 fit, 1 Taylor alpha (no sketch), 2 alpha = u (warm start), 3 alpha = sched_alpha
   float sched_alpha; // mode 3: the caller's coefficient for this update
   int last;          // this is the residual-only evaluation at k = max_iters
+  int phase;         // 0: stop test and coefficient; 1: stop test only; 2: coefficient only (DB Newton: the
+                     //    inverse that the coefficient needs is computed between the two)
   double* cpart;     // [batch][ngroups][17] partial coefficient sums (moments -> solve)
   int ngroups;
 };
@@ -153,6 +159,18 @@ void launch_finalize(const FinalArgs& a, hipStream_t s);
 // E = alpha R, one matrix per blockIdx.y; skipped when done
 void launch_make_e(float* E, const float* R, const Ctrl* ctrl, int batch, int np, hipStream_t s);
 
+// ---- dbnewton.hip : pieces of the DB Newton iteration (App. A.2) ----
+// N = M (copy), then the in-place inverse of the SPD matrices N[batch][np][np] by block Gauss-Jordan.
+// panels: scratch of spd_inverse_scratch_floats(np, batch) floats (may be null when that is 0).
+long long spd_inverse_scratch_floats(int np, int batch);
+int launch_spd_inverse(const float* M, float* N, int np, int batch, const Ctrl* ctrl, float* panels, hipStream_t s);
+// partial sums of <D0,D0>, <D0,D2>, <D2,D2> (D0 = M - I, D2 = M + N - 2I) -> the five coefficient partials
+void launch_db_moments(const float* M, const float* N, int np, int n_true, int batch, const Ctrl* ctrl, double* cpart,
+                       int ngroups, hipStream_t s);
+// M <- 2a(1-a) I + (1-a)^2 M + a^2 N (a = ctrl.alpha) on the true n x n part, partial sums of ||I - M'||_F^2
+void launch_db_update_m(float* M, const float* N, int np, int n_true, int batch, const Ctrl* ctrl, float* rho_part,
+                        int nparts, hipStream_t s);
+
 void set_last_error(const char* msg);
 
 // ---- per-kernel timing with HIP events (off unless prism_profile_enable(1)) ----
@@ -160,6 +178,7 @@ enum ProfKind {
   PK_PREP = 0, PK_FINAL, PK_SKETCH, PK_CHAIN, PK_SOLVE,
   PK_F32_RESID, PK_F32_POLYQ, PK_F32_APPLY, PK_F32_STORE, PK_F64_MNEXT, PK_MAKE_T,
   PK_BF16_GRAM, PK_BF16_POLYQ, PK_BF16_APPLY, PK_BF16_STORE,
+  PK_SPD_INVERSE, PK_DB_MOMENTS, PK_DB_UPDATE_M,
   PK_COUNT
 };
 struct ProfScope {   // records an event pair around the launches made during its lifetime

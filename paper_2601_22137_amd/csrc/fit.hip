@@ -147,7 +147,9 @@ __global__ __launch_bounds__(NT) void solve_kernel(SolveArgs a) {
     if ((t & 63) == 0) s_rho[t >> 6] = part;
     __syncthreads();
   }
-  if (t == 0) {
+  if (a.phase == 2) {
+    if (t == 0) s_stop = 0;          // coefficient only: the stop test of this k has been taken
+  } else if (t == 0) {
     const double rho = (s_rho[0] + s_rho[1]) + (s_rho[2] + s_rho[3]);
     const double res = sqrt(rho / (double)a.n);
     info->residual[a.k] = (float)res;
@@ -174,18 +176,20 @@ __global__ __launch_bounds__(NT) void solve_kernel(SolveArgs a) {
     }
   }
   __syncthreads();
-  if (s_stop) return;
+  if (s_stop || a.phase == 1) return;
 
   double lo, hi;
   if (a.fn == PRISM_FN_INV_ROOT) { lo = 1.0 / a.p; hi = 2.0 / a.p; }
   else if (a.fn == PRISM_FN_INVERSE) { lo = 0.5; hi = 2.0; }
+  else if (a.fn == PRISM_FN_SQRT_NEWTON) { lo = 0.0; hi = 1.0; }
   else if (a.d == 1) { lo = 0.5; hi = 1.0; }
   else { lo = 0.375; hi = 1.45; }
 
   if (a.mode != 0) {
     if (t == 0) {
       // without a fit: the Taylor coefficient, which is l except for the Chebyshev inverse (1)
-      const double taylor = (a.fn == PRISM_FN_INVERSE) ? 1.0 : lo;
+      // (and the DB Newton iteration, whose classical coefficient is 1/2)
+      const double taylor = (a.fn == PRISM_FN_INVERSE) ? 1.0 : (a.fn == PRISM_FN_SQRT_NEWTON ? 0.5 : lo);
       const float al = (a.mode == 3) ? a.sched_alpha : (float)((a.mode == 1) ? taylor : hi);
       ctl->alpha = al;
       info->alpha[a.k] = al;
@@ -194,7 +198,7 @@ __global__ __launch_bounds__(NT) void solve_kernel(SolveArgs a) {
   }
 
   const int nc = (a.fn == PRISM_FN_INV_ROOT) ? 2 * a.p + 1 : (a.fn == PRISM_FN_INVERSE ? 3 : 5);
-  if (a.ngroups == 1) {   // small matrices: the moments are accumulated right here
+  if (a.ngroups == 1 && a.fn != PRISM_FN_SQRT_NEWTON) {   // small matrices: the moments are accumulated right here
     accumulate_for(a, b, 0, 1, a.cpart + (long long)b * MAXC);
     __threadfence_block();
     __syncthreads();

@@ -49,6 +49,7 @@ __device__ inline TC epilogue(const GemmDesc& g, int b, int i, int j, TC acc, fl
   const long long oc = (long long)b * g.strideC + (long long)i * g.ldc + j;
   switch (g.epi) {
     case EPI_STORE:
+      if (g.acc_neg) acc = -acc;
       ((TC*)g.C)[oc] = acc;
       out = acc;
       return 0;
@@ -67,7 +68,9 @@ __device__ inline TC epilogue(const GemmDesc& g, int b, int i, int j, TC acc, fl
     }
     case EPI_AXPY: {
       const float cin = ((const float*)g.Cin)[(long long)b * g.strideCin + (long long)i * g.ldcin + j];
-      float v = g.c_in * apow(alpha, g.cin_alpha_pow) * cin + apow(alpha, g.coef_is_alpha) * (float)acc;
+      const float wc = g.cin_one_minus_alpha ? (1.0f - alpha) : g.c_in * apow(alpha, g.cin_alpha_pow);
+      const float wa = g.acc_neg ? -apow(alpha, g.coef_is_alpha) : apow(alpha, g.coef_is_alpha);
+      float v = wc * cin + wa * (float)acc;
       if (g.Cin2) v += apow(alpha, g.cin2_alpha_pow) * g.Cin2[(long long)b * g.strideCin + (long long)i * g.ldcin + j];
       ((float*)g.C)[oc] = v;
       out = (TC)v;
@@ -118,6 +121,8 @@ __global__ __launch_bounds__(NT) void gemm_kernel(GemmDesc g) {
     tn = rem - tm * tiles_n;
   }
   if (g.ctrl && g.ctrl[b].done) return;
+  // block Gauss-Jordan: the pivot row / column block has launches of its own
+  if ((tm * TM >= g.skip_m0 && tm * TM < g.skip_m1) || (tn * TN >= g.skip_n0 && tn * TN < g.skip_n1)) return;
   const float alpha = g.ctrl ? g.ctrl[b].alpha : 1.0f;
 
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;

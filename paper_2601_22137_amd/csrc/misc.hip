@@ -76,7 +76,9 @@ __global__ __launch_bounds__(NT) void prepare_kernel(PrepArgs a) {
   const double norm = sqrt(ss);
   double scale = 0.0, cinv = 0.0;
   if (finite && !zero) {
-    if (a.fn == PRISM_FN_INV_ROOT) {
+    if (a.fn == PRISM_FN_SQRT_NEWTON) {
+      scale = 1.0;                                             // App. A.2 starts from A itself
+    } else if (a.fn == PRISM_FN_INV_ROOT) {
       const double cp = 2.0 * norm / (double)(a.root_p + 1);   // c^p
       scale = 1.0 / cp;
       cinv = pow(cp, -1.0 / (double)a.root_p);                 // 1 / c
@@ -115,6 +117,14 @@ __global__ __launch_bounds__(NT) void prepare_kernel(PrepArgs a) {
     const long long o = (long long)b * a.Lp * a.Sp + (long long)r * a.Sp + c;
     if (a.fn == PRISM_FN_SIGN) {
       a.X32[o] = (float)v;
+    } else if (a.fn == PRISM_FN_SQRT_NEWTON) {   // X_0 = M_0 = A, Y_0 = I; the padding of M is the identity
+      const bool in = (r < a.S && c < a.S);
+      const float eye = (r == c) ? 1.0f : 0.0f;
+      a.X32[o] = (float)v;
+      a.Y32[o] = in ? eye : 0.0f;
+      a.R32[o] = in ? (float)v : eye;
+      const double res = in ? ((double)eye - v) : 0.0;
+      rho += (float)(res * res);
     } else if (a.fn == PRISM_FN_INVERSE) {
       a.Y32[o] = (float)v;                                                                    // A_s
       a.X32[(long long)b * a.Lp * a.Sp + (long long)c * a.Sp + r] = (float)v;                 // X_0 = A_s^T
@@ -149,7 +159,7 @@ __global__ __launch_bounds__(NT) void prepare_kernel(PrepArgs a) {
       a.Xg[(long long)b * a.Lp * a.Sp + (long long)c * a.Lp + r] = f2bf(tile_t[lc][lr]);
     }
   }
-  if (a.fn == PRISM_FN_INV_ROOT) {
+  if (a.fn == PRISM_FN_INV_ROOT || a.fn == PRISM_FN_SQRT_NEWTON) {
     __shared__ float red[4];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
 #pragma unroll
@@ -290,6 +300,9 @@ __global__ __launch_bounds__(NT) void finalize_kernel(FinalArgs a) {
     } else {
       ((float*)a.dst)[(long long)b * mat + i] = a.X32[par][o];
     }
+  } else if (a.fn == PRISM_FN_SQRT_NEWTON) {
+    ((float*)a.dst)[(long long)b * mat + i] = a.X32[par][o];
+    ((float*)a.dst2)[(long long)b * mat + i] = a.Y32[par][o];
   } else if (a.fn == PRISM_FN_SQRT) {
     const double rs = sqrt(c.norm);
     ((float*)a.dst)[(long long)b * mat + i] = (float)((double)a.X32[par][o] * rs);

@@ -64,7 +64,7 @@ int make_plan(Plan& P, int fn, int batch, int m, int n, int dt, int degree, int 
   if (degree != 3 && degree != 5) return PRISM_EINVAL;
   if (sketch_dim < 0 || sketch_dim > PRISM_MAX_SKETCH) return PRISM_EINVAL;
   if (dt != PRISM_F32 && dt != PRISM_BF16) return PRISM_EINVAL;
-  if (fn < PRISM_FN_POLAR || fn > PRISM_FN_INVERSE) return PRISM_EINVAL;
+  if (fn < PRISM_FN_POLAR || fn > PRISM_FN_SQRT_NEWTON) return PRISM_EINVAL;
   if (fn != PRISM_FN_POLAR && m != n) return PRISM_EINVAL;
   if (fn == PRISM_FN_INV_ROOT && (root_p < 1 || root_p > PRISM_MAX_ROOT || degree != 3)) return PRISM_EINVAL;
   if (fn != PRISM_FN_POLAR && dt == PRISM_BF16) return PRISM_EUNSUPPORTED;
@@ -102,6 +102,10 @@ int make_plan(Plan& P, int fn, int batch, int m, int n, int dt, int degree, int 
   {
     const long long el = (long long)P.Sp * P.ld;
     P.ngroups = el <= 4096 ? 1 : (int)(el / 4096 > 64 ? 64 : el / 4096);   // 1: done inside the solve kernel
+    if (fn == PRISM_FN_SQRT_NEWTON) {   // the moments run over the n x n matrices themselves
+      const long long mm = (long long)P.Sp * P.Sp / 65536;
+      P.ngroups = mm < 1 ? 1 : (mm > 64 ? 64 : (int)mm);
+    }
   }
   P.o_cpart = take(B * P.ngroups * 17 * sizeof(double));
   if (dt == PRISM_BF16) {
@@ -117,6 +121,11 @@ int make_plan(Plan& P, int fn, int batch, int m, int n, int dt, int degree, int 
     for (int i = 0; i < 2; ++i) P.o_x[i] = take(B * LS * 4);
     P.o_r = take(B * SS * 4);
     P.o_q = P.d == 2 ? take(B * SS * 4) : 0;
+  } else if (fn == PRISM_FN_SQRT_NEWTON) {
+    for (int i = 0; i < 2; ++i) { P.o_x[i] = take(B * SS * 4); P.o_y[i] = take(B * SS * 4); }
+    P.o_r = take(B * SS * 4);        // M_k
+    P.o_q = take(B * SS * 4);        // N_k = M_k^{-1}
+    P.o_t[0] = take((size_t)spd_inverse_scratch_floats(P.Sp, batch) * 4 + 256);   // pivot panels of the inverse
   } else if (fn == PRISM_FN_INVERSE) {
     for (int i = 0; i < 2; ++i) P.o_x[i] = take(B * SS * 4);
     P.o_y[0] = take(B * SS * 4);     // A / ||A||_F
@@ -207,8 +216,9 @@ struct Run {
     return PRISM_OK;
   }
 
-  int solve(int k, int nparts) {
+  int solve(int k, int nparts, int phase = 0) {
     SolveArgs a = {};
+    a.phase = phase;
     a.fn = P.fn; a.k = k; a.d = P.d; a.p = P.p; a.n = P.S; a.rows = P.Sp; a.ld = P.ld;
     a.V = v; a.vstride = (long long)P.batch * P.Sp * P.ld; a.bstride = (long long)P.Sp * P.ld;
     a.rho_part = rho; a.nparts = nparts;
@@ -217,7 +227,11 @@ struct Run {
     a.sched_alpha = k < sched_len ? sched[k] : 0.0f;
     a.last = (k == max_iters);
     a.cpart = at<double>(P.o_cpart); a.ngroups = P.ngroups;
-    { ProfScope ps(PK_SOLVE, s); if (a.mode == 0 && !a.last && a.ngroups > 1) launch_moments(a, P.batch, s); launch_solve(a, P.batch, s); }
+    {
+      ProfScope ps(PK_SOLVE, s);
+      if (a.mode == 0 && !a.last && a.ngroups > 1 && P.fn != PRISM_FN_SQRT_NEWTON) launch_moments(a, P.batch, s);
+      launch_solve(a, P.batch, s);
+    }
     return check_hip();
   }
   bool fit_needed(int k) const { return P.p_s > 0 && k >= first_fit && k < max_iters; }
@@ -416,6 +430,45 @@ int run_inverse_f32(Run& r) {
   return PRISM_OK;
 }
 
+// DB Newton in product form (App. A.2): N = M^{-1}, X <- (1-a) X + a X N, Y likewise,
+// M <- 2a(1-a) I + (1-a)^2 M + a^2 N.  The stop test of iteration k runs before the inverse.
+int run_sqrt_newton_f32(Run& r) {
+  const Plan& P = r.P;
+  const int Sp = P.Sp, T = P.tile;
+  const long long SS = (long long)Sp * Sp;
+  float* X[2] = {r.at<float>(P.o_x[0]), r.at<float>(P.o_x[1])};
+  float* Y[2] = {r.at<float>(P.o_y[0]), r.at<float>(P.o_y[1])};
+  float* M = r.at<float>(P.o_r);
+  float* N = r.at<float>(P.o_q);
+  const int nparts0 = (Sp / 64) * (Sp / 64);               // prepare step: one partial per 64 x 64 tile
+  const int nparts = nparts0 < 512 ? nparts0 : 512;        // later: the M update
+  const int sym = f32_sym();                               // X_k, Y_k, N_k are functions of A and commute
+  int cur = 0;
+  for (int k = 0; k <= r.max_iters; ++k) {
+    if (k == r.max_iters && r.tol <= 0.0) break;
+    CHECK_LAUNCH(r.solve(k, k == 0 ? nparts0 : nparts, 1));
+    if (k == r.max_iters) break;
+    { ProfScope ps(PK_SPD_INVERSE, r.s); CHECK_LAUNCH(launch_spd_inverse(M, N, Sp, P.batch, r.ctrl, r.at<float>(P.o_t[0]), r.s)); }
+    if (P.p_s > 0 && k >= r.sched_len) {
+      ProfScope ps(PK_DB_MOMENTS, r.s);
+      launch_db_moments(M, N, Sp, P.S, P.batch, r.ctrl, r.at<double>(P.o_cpart), P.ngroups, r.s);
+    }
+    CHECK_LAUNCH(r.solve(k, 0, 2));
+    GemmDesc ax = f32_desc(r, X[cur], Sp, SS, N, Sp, SS, Sp, Sp, Sp, 0);
+    ax.epi = EPI_AXPY; ax.C = X[cur ^ 1]; ax.strideC = SS; ax.ldc = Sp; ax.Cin = X[cur]; ax.strideCin = SS; ax.ldcin = Sp;
+    ax.cin_one_minus_alpha = 1; ax.coef_is_alpha = 1; ax.sym = sym;
+    { ProfScope ps(PK_F32_APPLY, r.s); CHECK_LAUNCH(launch_gemm_f32(ax, T, T, r.s)); }
+    GemmDesc ay = f32_desc(r, Y[cur], Sp, SS, N, Sp, SS, Sp, Sp, Sp, 0);
+    ay.epi = EPI_AXPY; ay.C = Y[cur ^ 1]; ay.strideC = SS; ay.ldc = Sp; ay.Cin = Y[cur]; ay.strideCin = SS; ay.ldcin = Sp;
+    ay.cin_one_minus_alpha = 1; ay.coef_is_alpha = 1; ay.sym = sym;
+    { ProfScope ps(PK_F32_APPLY, r.s); CHECK_LAUNCH(launch_gemm_f32(ay, T, T, r.s)); }
+    { ProfScope ps(PK_DB_UPDATE_M, r.s); launch_db_update_m(M, N, Sp, P.S, P.batch, r.ctrl, r.rho, nparts, r.s); }
+    CHECK_LAUNCH(check_hip());
+    cur ^= 1;
+  }
+  return PRISM_OK;
+}
+
 int run_inv_root_f32(Run& r) {
   const Plan& P = r.P;
   const int Sp = P.Sp, T = P.tile, p = P.p;
@@ -481,7 +534,7 @@ int run(int fn, void* a, void* inv_out, int root_p, int batch, int m, int n, int
         int sketch_dim, uint64_t seed, double tol, void* stream, const prism_options* opt) {
   set_last_error("");
   if (!a) return PRISM_EINVAL;
-  if (fn == PRISM_FN_SQRT && !inv_out) return PRISM_EINVAL;
+  if ((fn == PRISM_FN_SQRT || fn == PRISM_FN_SQRT_NEWTON) && !inv_out) return PRISM_EINVAL;
   if (max_iters < 0 || max_iters > PRISM_MAX_ITERS) return PRISM_EINVAL;
   if (!(tol == tol)) return PRISM_EINVAL;
   if (opt && opt->warm_iters < 0) return PRISM_EINVAL;
@@ -502,6 +555,7 @@ int run(int fn, void* a, void* inv_out, int root_p, int batch, int m, int n, int
   r.max_iters = max_iters; r.tol = tol; r.seed = seed; r.warm = opt ? opt->warm_iters : 0;
   r.sched = opt ? opt->alpha_schedule : nullptr;
   r.sched_len = opt ? opt->schedule_len : 0;
+  if (fn == PRISM_FN_SQRT_NEWTON) r.warm = 0;   // no upper end to start from: the coefficient is not clamped to a fit interval
   r.first_fit = r.warm > r.sched_len ? r.warm : r.sched_len;
 
   PrepArgs pa = {};
@@ -522,15 +576,16 @@ int run(int fn, void* a, void* inv_out, int root_p, int batch, int m, int n, int
     }
   } else {
     pa.X32 = r.at<float>(P.o_x[0]);
-    if (fn == PRISM_FN_SQRT || fn == PRISM_FN_INVERSE) pa.Y32 = r.at<float>(P.o_y[0]);
+    if (fn == PRISM_FN_SQRT || fn == PRISM_FN_INVERSE || fn == PRISM_FN_SQRT_NEWTON) pa.Y32 = r.at<float>(P.o_y[0]);
+    if (fn == PRISM_FN_SQRT_NEWTON) pa.R32 = r.at<float>(P.o_r);
     if (fn == PRISM_FN_INV_ROOT) { pa.M64 = r.at<double>(P.o_y[0]); pa.R32 = r.at<float>(P.o_r); }
     for (int i = 0; i < 2; ++i) {
       fa.X32[i] = r.at<float>(P.o_x[i]);
-      fa.Y32[i] = fn == PRISM_FN_SQRT ? r.at<float>(P.o_y[i]) : nullptr;
+      fa.Y32[i] = (fn == PRISM_FN_SQRT || fn == PRISM_FN_SQRT_NEWTON) ? r.at<float>(P.o_y[i]) : nullptr;
     }
   }
   { ProfScope ps(PK_PREP, r.s); launch_sumsq(pa, r.s); launch_prepare(pa, r.s); }
-  if (P.p_s > 0 && max_iters > r.first_fit) {
+  if (P.p_s > 0 && max_iters > r.first_fit && fn != PRISM_FN_SQRT_NEWTON) {
     ProfScope ps(PK_SKETCH, r.s);
     launch_sketch(r.v0, P.Sp, P.S, P.ld, P.p_s, seed, r.first_fit, max_iters - r.first_fit, P.fn, r.s);
   }
@@ -539,6 +594,7 @@ int run(int fn, void* a, void* inv_out, int root_p, int batch, int m, int n, int
   if (dt == PRISM_BF16) rc = run_polar_bf16(r);
   else if (fn == PRISM_FN_POLAR || fn == PRISM_FN_SIGN) rc = run_polar_f32(r);
   else if (fn == PRISM_FN_INVERSE) rc = run_inverse_f32(r);
+  else if (fn == PRISM_FN_SQRT_NEWTON) rc = run_sqrt_newton_f32(r);
   else if (fn == PRISM_FN_SQRT) rc = run_sqrt_f32(r);
   else rc = run_inv_root_f32(r);
   if (rc != PRISM_OK) return rc;
@@ -625,6 +681,26 @@ int prism_inverse(void* a, int batch, int m, int n, prism_dtype dt, int max_iter
 int prism_inverse_ex(void* a, int batch, int m, int n, prism_dtype dt, int max_iters, int sketch_dim, uint64_t seed,
                      double tol, void* stream, const prism_options* opt) {
   return run(PRISM_FN_INVERSE, a, nullptr, 0, batch, m, n, (int)dt, 5, max_iters, sketch_dim, seed, tol, stream, opt);
+}
+
+int prism_sqrt_newton(void* a, void* inv_out, int batch, int m, int n, prism_dtype dt, int max_iters, int fit, double tol,
+                      void* stream) {
+  return run(PRISM_FN_SQRT_NEWTON, a, inv_out, 0, batch, m, n, (int)dt, 3, max_iters, fit ? 1 : 0, 0, tol, stream, nullptr);
+}
+int prism_sqrt_newton_ex(void* a, void* inv_out, int batch, int m, int n, prism_dtype dt, int max_iters, int fit, double tol,
+                         void* stream, const prism_options* opt) {
+  return run(PRISM_FN_SQRT_NEWTON, a, inv_out, 0, batch, m, n, (int)dt, 3, max_iters, fit ? 1 : 0, 0, tol, stream, opt);
+}
+
+int prism_spd_inverse(const float* a, float* out, int batch, int n, void* stream) {
+  if (!a || !out || batch <= 0 || n <= 0 || n % 64) return PRISM_EINVAL;
+  char* ws = nullptr;
+  const size_t bytes = (size_t)spd_inverse_scratch_floats(n, batch) * 4;
+  if (bytes) {
+    const int rc = get_workspace(bytes, (hipStream_t)stream, nullptr, &ws);
+    if (rc != PRISM_OK) return rc;
+  }
+  return launch_spd_inverse(a, out, n, batch, nullptr, (float*)ws, (hipStream_t)stream);
 }
 
 int prism_sketch(float* out, int n, int sketch_dim, uint64_t seed, int k, int fn, void* stream) {

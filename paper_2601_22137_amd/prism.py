@@ -13,7 +13,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libprism.so")
 
 F32, BF16 = 0, 1
-FN_POLAR, FN_SQRT, FN_INV_ROOT, FN_SIGN, FN_INVERSE = 1, 2, 3, 4, 5
+FN_POLAR, FN_SQRT, FN_INV_ROOT, FN_SIGN, FN_INVERSE, FN_SQRT_NEWTON = 1, 2, 3, 4, 5, 6
 MAX_ITERS = 64
 FLAG_BF16_PLAIN_ITERATE = 1
 OK, EINVAL, EUNSUPPORTED, ENOMEM, EHIP = 0, 1, 2, 3, 4
@@ -23,13 +23,14 @@ INFO_DTYPE = np.dtype([("iters", np.int32), ("status", np.int32),
                        ("residual", np.float32, (MAX_ITERS + 1,)), ("alpha", np.float32, (MAX_ITERS,))])
 
 EXPORTS = ("prism_workspace_bytes", "prism_polar", "prism_polar_ex", "prism_sqrt", "prism_sqrt_ex",
-           "prism_inv_root", "prism_inv_root_ex", "prism_sign", "prism_sign_ex", "prism_inverse", "prism_inverse_ex",
+           "prism_inv_root", "prism_inv_root_ex", "prism_sign", "prism_sign_ex", "prism_inverse", "prism_inverse_ex", "prism_sqrt_newton", "prism_sqrt_newton_ex", "prism_spd_inverse",
            "prism_sketch", "prism_gauss_parts", "prism_chain_product", "prism_gemm_f32",
            "prism_gemm_f64a", "prism_gemm_bf16_nt", "prism_profile_enable", "prism_profile_collect",
            "prism_last_error")
 
 PROFILE_KINDS = ("prep", "final", "sketch", "chain", "solve", "f32_resid", "f32_polyq", "f32_apply", "f32_store",
-                 "f64_mnext", "make_t", "bf16_gram", "bf16_polyq", "bf16_apply", "bf16_store")
+                 "f64_mnext", "make_t", "bf16_gram", "bf16_polyq", "bf16_apply", "bf16_store", "spd_inverse", "db_moments",
+                 "db_update_m")
 
 
 class Options(ctypes.Structure):
@@ -64,6 +65,9 @@ def lib():
         L.prism_sign_ex.argtypes = L.prism_sign.argtypes + [ctypes.POINTER(Options)]
         L.prism_inverse.argtypes = [vp, i, i, i, i, i, i, u64, dbl, vp]
         L.prism_inverse_ex.argtypes = L.prism_inverse.argtypes + [ctypes.POINTER(Options)]
+        L.prism_sqrt_newton.argtypes = [vp, vp, i, i, i, i, i, i, dbl, vp]
+        L.prism_sqrt_newton_ex.argtypes = L.prism_sqrt_newton.argtypes + [ctypes.POINTER(Options)]
+        L.prism_spd_inverse.argtypes = [vp, vp, i, i, vp]
         L.prism_sketch.argtypes = [vp, i, i, u64, i, i, vp]
         L.prism_gauss_parts.argtypes = [ctypes.c_uint32, ctypes.c_uint32, vp, vp, vp, vp]
         L.prism_chain_product.argtypes = [vp, vp, vp, i, i, i, vp]
@@ -184,7 +188,25 @@ def inverse(a, max_iters=30, sketch_dim=8, seed=22137, tol=1e-6, warm_iters=0, w
     return info
 
 
+def sqrt_newton(a, max_iters=30, tol=1e-6, fit=True, workspace=None, alpha_schedule=None):
+    """In place: a <- A^(1/2) by the DB Newton iteration; returns (A^(-1/2), info handle)."""
+    b, m, n = _batched(a)
+    inv = torch.empty_like(a)
+    info = _Info(b, a.device)
+    o = _options(info, 0, 0, workspace, alpha_schedule)
+    _check(lib().prism_sqrt_newton_ex(a.data_ptr(), inv.data_ptr(), b, m, n, _dtype_code(a), max_iters, int(bool(fit)), tol,
+                                      _stream(), ctypes.byref(o)))
+    return inv, info
+
+
 # ---- single steps (unit tests, profiling) ----
+
+def spd_inverse(a):
+    batch, n, _ = a.shape
+    out = torch.empty_like(a)
+    _check(lib().prism_spd_inverse(a.data_ptr(), out.data_ptr(), batch, n, _stream()))
+    return out
+
 
 def sketch(n, sketch_dim, seed, k, fn, device="cuda"):
     out = torch.empty((n, sketch_dim), dtype=torch.float32, device=device)

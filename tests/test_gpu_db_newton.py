@@ -1,0 +1,113 @@
+"""Parity of prism_sqrt_newton (PRISM DB Newton, product form) and of its SPD inverse step against
+the fp64 oracle / numpy on the same seeded inputs (relative Frobenius error <= 1e-5, identical
+iteration counts)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import prism_ref as O
+from paper_2601_22137_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+TOL_F32 = 1e-5
+
+
+@pytest.fixture(scope="module")
+def prism():
+    from paper_2601_22137_amd import prism as P
+    P.lib()
+    return P
+
+
+def _rel(x, ref):
+    return np.linalg.norm(np.asarray(x, dtype=np.float64) - ref) / np.linalg.norm(ref)
+
+
+def _spd(n, batch, cond, seed):
+    out = np.empty((batch, n, n), dtype=np.float32)
+    for b in range(batch):
+        rng = np.random.default_rng(seed + b)
+        q, _ = np.linalg.qr(rng.standard_normal((n, n)))
+        lam = np.exp(rng.uniform(-np.log(cond), 0.0, n)) * (1.0 + b)
+        a = (q * lam) @ q.T
+        out[b] = (0.5 * (a + a.T)).astype(np.float32)
+    return out
+
+
+@pytest.mark.parametrize("n,batch,cond", [(64, 3, 20.0), (128, 2, 50.0), (320, 2, 30.0), (256, 2, 30.0), (1024, 2, 30.0), (2048, 1, 20.0)])
+def test_spd_inverse(prism, n, batch, cond):
+    """Block Gauss-Jordan against numpy's inverse: one to sixteen elimination blocks.  The forward
+    error of an fp32 inverse scales with cond * 2^-24."""
+    A = _spd(n, batch, cond, 40 + n)
+    out = prism.spd_inverse(torch.from_numpy(A).cuda()).cpu().numpy()
+    for b in range(batch):
+        ref = np.linalg.inv(A[b].astype(np.float64))
+        assert _rel(out[b], ref) <= 20 * cond * 2.0 ** -24, (b, _rel(out[b], ref))
+        assert np.linalg.norm(A[b].astype(np.float64) @ out[b] - np.eye(n)) / np.sqrt(n) <= 1e-4
+
+
+def _check_info(rec, oinfo, res_floor=3e-6, alpha_tol=2e-3, alpha_res_min=1e-3):
+    assert rec["iters"] == oinfo["iters"], (rec["residual"][:rec["iters"] + 1], oinfo["residual"])
+    assert rec["status"] == oinfo["status"]
+    k = oinfo["iters"]
+    for j in range(k):
+        if oinfo["residual"][j] >= alpha_res_min:
+            assert abs(rec["alpha"][j] - oinfo["alpha"][j]) <= alpha_tol, (j, rec["alpha"][:k], oinfo["alpha"])
+        else:
+            assert -1e-6 <= rec["alpha"][j] <= 1.0 + 1e-6
+    got, want = rec["residual"][:k + 1].astype(np.float64), np.array(oinfo["residual"][:k + 1])
+    assert np.all(np.abs(got - want) <= 2e-2 * want + res_floor), (got, want)
+
+
+@pytest.mark.parametrize("n,batch", [(512, 2), (300, 3), (96, 2)])
+def test_sqrt_newton_wishart(prism, n, batch):
+    A = W.c5_wishart_spd(n=n, batch=batch)
+    x = torch.from_numpy(A.copy()).cuda()
+    inv, h = prism.sqrt_newton(x, 30, 1e-5)
+    info = h.read()
+    root, iroot = x.cpu().numpy(), inv.cpu().numpy()
+    for b in range(batch):
+        rx, ry, oinfo = O.sqrt_db_newton(A[b], 30, 1e-5)
+        assert oinfo["status"] == O.STATUS_CONVERGED
+        assert _rel(root[b], rx) <= TOL_F32
+        assert _rel(iroot[b], ry) <= TOL_F32
+        _check_info(info[b], oinfo)
+    s = root[0].astype(np.float64)
+    assert np.linalg.norm(s @ s - A[0]) / np.linalg.norm(A[0]) <= 1e-5
+
+
+def test_sqrt_newton_classical_and_schedule(prism):
+    A = _spd(192, 2, 40.0, 7)
+    x = torch.from_numpy(A.copy()).cuda()
+    inv, h = prism.sqrt_newton(x, 30, 1e-5, fit=False)
+    info = h.read()
+    rx, ry, oinfo = O.sqrt_db_newton(A[1], 30, 1e-5, fit=False)
+    assert info[1]["iters"] == oinfo["iters"]
+    assert np.all(info[1]["alpha"][:oinfo["iters"]] == np.float32(0.5))
+    assert _rel(x.cpu().numpy()[1], rx) <= TOL_F32 and _rel(inv.cpu().numpy()[1], ry) <= TOL_F32
+    # the fitted iteration needs fewer updates than the classical one on the same input
+    x2 = torch.from_numpy(A.copy()).cuda()
+    _, h2 = prism.sqrt_newton(x2, 30, 1e-5)
+    assert h2.read()[1]["iters"] < oinfo["iters"]
+    # a schedule overrides the leading coefficients
+    x3 = torch.from_numpy(A.copy()).cuda()
+    inv3, h3 = prism.sqrt_newton(x3, 30, 1e-5, alpha_schedule=[0.25, 0.75])
+    info3 = h3.read()
+    rx, ry, oinfo = O.sqrt_db_newton(A[0], 30, 1e-5, alpha_schedule=[0.25, 0.75])
+    assert np.all(info3[0]["alpha"][:2] == np.float32([0.25, 0.75]))
+    assert _rel(x3.cpu().numpy()[0], rx) <= TOL_F32
+    _check_info(info3[0], oinfo)
+
+
+def test_sqrt_newton_degenerate_and_errors(prism):
+    z = torch.zeros((2, 64, 64), dtype=torch.float32, device="cuda")
+    z[1] = 4.0 * torch.eye(64)
+    inv, h = prism.sqrt_newton(z, 10, 1e-6)
+    info = h.read()
+    assert info[0]["status"] == prism.INFO_ZERO and info[1]["status"] == prism.INFO_CONVERGED
+    assert info[1]["iters"] == 1                       # one-point spectrum: one fitted step
+    assert torch.allclose(z[1], 2.0 * torch.eye(64, device="cuda"), atol=1e-5)
+    assert torch.allclose(inv[1], 0.5 * torch.eye(64, device="cuda"), atol=1e-5)
+    with pytest.raises(prism.PrismError):
+        prism.sqrt_newton(torch.zeros((1, 8, 12), dtype=torch.float32, device="cuda"))
