@@ -33,6 +33,9 @@ def parse():
                     help="HIP streams the calls of one step are spread over (default: one per shape group, i.e. 4 for c2)")
     ap.add_argument("--sub-batches", type=int, default=1,
                     help="split every group's batch into this many calls (spread over the streams)")
+    ap.add_argument("--no-grouped", dest="grouped", action="store_false",
+                    help="c2: four calls on --streams streams per step instead of one prism_run_grouped call (the default, in "
+                         "which the library forks to its internal streams)")
     ap.add_argument("--graph", action="store_true",
                     help="capture every step's calls in a HIP graph beforehand and time the replays (one stream)")
     ap.add_argument("--only-group", type=int, default=-1, help="c2: run a single shape group (profiling aid)")
@@ -204,7 +207,9 @@ def main():
     # (default priority), so that the small latency-bound kernels of one call run beside the GEMMs
     # of another.  Consecutive steps queue up behind each other on the same streams.
     nsub = max(1, args.sub_batches)
-    nstreams = args.streams or len(wl.host) * nsub
+    if args.streams or args.sub_batches > 1 or wl.name != "c2":
+        args.grouped = False
+    nstreams = 1 if args.grouped else (args.streams or len(wl.host) * nsub)
     side = [torch.cuda.Stream() for _ in range(nstreams)] if nstreams > 1 else None
 
     def parts(x):
@@ -221,6 +226,8 @@ def main():
             return np.concatenate([h.read() for h in self.hs])
 
     def step(i, use_streams=True):
+        if args.grouped and use_streams and wl.name == "c2":
+            return prism.run_grouped(prism.FN_POLAR, copies[i], 5, 5, 16, wl.seed, 0.0, flags=wl.flags)[1]
         hs, slot = [], 0
         for x in copies[i]:
             sub = []
@@ -371,7 +378,7 @@ def main():
         "dtype": wl.dtype, "data": "synthetic",
         "config": {"workload": wl.name + ": " + wl.desc, "matrices_per_step": wl.n_matrices,
                    "input_bytes_per_step": bytes_per_copy, "streams": nstreams,
-                   "calls_per_step": len(wl.host) * nsub, "hip_graph": bool(args.graph)},
+                   "calls_per_step": 1 if args.grouped else len(wl.host) * nsub, "hip_graph": bool(args.graph), "grouped_call": bool(args.grouped)},
         "tflops_algorithmic": round(tflops_algo, 2), "tflops_executed": round(tflops_exec, 2),
         "frac_of_mfma_peak": round(tflops_exec / PEAK[wl.dtype], 4),
         "iterations": {"min": min(iters_all), "max": max(iters_all)},

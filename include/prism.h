@@ -168,6 +168,30 @@ int prism_sqrt_newton_ex(void* a, void* inv_out, int batch, int m, int n, prism_
                          int max_iters, int fit, double tol, void* stream,
                          const prism_options* opt);
 
+/* ---- one call over groups of different shapes (an optimizer step over all parameters) ----
+ *
+ * Callers: a Muon-style step orthogonalises the gradient of every weight matrix, a Shampoo-style
+ * step takes the inverse root of every preconditioner; the matrices come in a few shapes, each a
+ * batch.  The groups are independent, so the library enqueues them on internal streams of
+ * default priority that fork from and join back into `stream` (event record / wait only: the call
+ * stays asynchronous and capturable), and the latency-bound kernels of one group run beside the
+ * GEMMs of another.  Every group is computed exactly as by its own single-group call. */
+typedef struct {
+  void* x;          /* device: [batch][m][n], replaced in place as by the single-group call */
+  void* inv_out;    /* device: second output of prism_sqrt / prism_sqrt_newton, else NULL */
+  prism_info* info; /* device array of `batch` entries, or NULL */
+  int32_t batch, m, n;
+} prism_group;
+
+/* fn selects the iteration (PRISM_FN_*); root_p is used by PRISM_FN_INV_ROOT only, degree by the
+ * Newton-Schulz family, sketch_dim by all but PRISM_FN_SQRT_NEWTON (where non-zero means "fit").
+ * opt may be NULL; its workspace and info fields must be NULL (each internal stream keeps its own
+ * cached workspace).  Returns the first error of any group; nothing is enqueued for the groups
+ * after it. */
+int prism_run_grouped(prism_fn fn, const prism_group* groups, int ngroups, int root_p, prism_dtype dt,
+                      int degree, int max_iters, int sketch_dim, uint64_t seed, double tol,
+                      void* stream, const prism_options* opt);
+
 /* ---- single steps of the path, exposed for unit tests and profiling ---- */
 
 /* S_k^T (Section 4.2: Gaussian sketch): out[n][sketch_dim] fp32 on the device,

@@ -602,6 +602,71 @@ int run(int fn, void* a, void* inv_out, int root_p, int batch, int m, int n, int
   return check_hip();
 }
 
+// Internal streams of the grouped call, per device, created on first use (default priority).
+constexpr int GROUP_STREAMS = 4;
+struct Fork {
+  hipStream_t streams[GROUP_STREAMS] = {};
+  hipEvent_t forked = nullptr, joined[GROUP_STREAMS] = {};
+  bool ready = false;
+};
+std::mutex g_fork_mu;
+std::map<int, Fork> g_forks;
+
+int get_fork(Fork** out) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) { set_last_error("hipGetDevice failed"); return PRISM_EHIP; }
+  std::lock_guard<std::mutex> lock(g_fork_mu);
+  Fork& f = g_forks[dev];
+  if (!f.ready) {
+    if (hipEventCreateWithFlags(&f.forked, hipEventDisableTiming) != hipSuccess) return PRISM_EHIP;
+    for (int i = 0; i < GROUP_STREAMS; ++i) {
+      if (hipStreamCreateWithFlags(&f.streams[i], hipStreamNonBlocking) != hipSuccess) return PRISM_EHIP;
+      if (hipEventCreateWithFlags(&f.joined[i], hipEventDisableTiming) != hipSuccess) return PRISM_EHIP;
+    }
+    f.ready = true;
+  }
+  *out = &f;
+  return PRISM_OK;
+}
+
+int run_grouped(int fn, const prism_group* groups, int ngroups, int root_p, int dt, int degree, int max_iters,
+                int sketch_dim, uint64_t seed, double tol, void* stream, const prism_options* opt) {
+  set_last_error("");
+  if (!groups || ngroups <= 0) return PRISM_EINVAL;
+  if (opt && (opt->workspace || opt->info)) return PRISM_EINVAL;
+  if (fn == PRISM_FN_INVERSE) degree = 5;                     // fixed polynomial
+  if (fn == PRISM_FN_SQRT_NEWTON) { degree = 3; sketch_dim = sketch_dim ? 1 : 0; seed = 0; }
+  static std::mutex enqueue_mu;      // the internal streams and events are shared by all callers on a device
+  std::lock_guard<std::mutex> enqueue_lock(enqueue_mu);
+  if (ngroups == 1) {
+    prism_options o = opt ? *opt : prism_options{};
+    o.info = groups[0].info;
+    return run(fn, groups[0].x, groups[0].inv_out, root_p, groups[0].batch, groups[0].m, groups[0].n, dt, degree,
+               max_iters, sketch_dim, seed, tol, stream, &o);
+  }
+  Fork* f = nullptr;
+  int rc = get_fork(&f);
+  if (rc != PRISM_OK) return rc;
+  hipStream_t user = (hipStream_t)stream;
+  const int used = ngroups < GROUP_STREAMS ? ngroups : GROUP_STREAMS;
+  if (hipEventRecord(f->forked, user) != hipSuccess) return PRISM_EHIP;
+  for (int i = 0; i < used; ++i)
+    if (hipStreamWaitEvent(f->streams[i], f->forked, 0) != hipSuccess) return PRISM_EHIP;
+  int first_error = PRISM_OK;
+  for (int gi = 0; gi < ngroups && first_error == PRISM_OK; ++gi) {
+    prism_options o = opt ? *opt : prism_options{};
+    o.info = groups[gi].info;
+    first_error = run(fn, groups[gi].x, groups[gi].inv_out, root_p, groups[gi].batch, groups[gi].m, groups[gi].n, dt,
+                      degree, max_iters, sketch_dim, seed, tol, f->streams[gi % GROUP_STREAMS], &o);
+  }
+  // join whatever has been enqueued, also after an error
+  for (int i = 0; i < used; ++i) {
+    if (hipEventRecord(f->joined[i], f->streams[i]) != hipSuccess) return PRISM_EHIP;
+    if (hipStreamWaitEvent(user, f->joined[i], 0) != hipSuccess) return PRISM_EHIP;
+  }
+  return first_error;
+}
+
 }  // namespace
 }  // namespace prism
 
@@ -701,6 +766,11 @@ int prism_spd_inverse(const float* a, float* out, int batch, int n, void* stream
     if (rc != PRISM_OK) return rc;
   }
   return launch_spd_inverse(a, out, n, batch, nullptr, (float*)ws, (hipStream_t)stream);
+}
+
+int prism_run_grouped(prism_fn fn, const prism_group* groups, int ngroups, int root_p, prism_dtype dt, int degree,
+                      int max_iters, int sketch_dim, uint64_t seed, double tol, void* stream, const prism_options* opt) {
+  return run_grouped((int)fn, groups, ngroups, root_p, (int)dt, degree, max_iters, sketch_dim, seed, tol, stream, opt);
 }
 
 int prism_sketch(float* out, int n, int sketch_dim, uint64_t seed, int k, int fn, void* stream) {

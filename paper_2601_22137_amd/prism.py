@@ -23,7 +23,7 @@ INFO_DTYPE = np.dtype([("iters", np.int32), ("status", np.int32),
                        ("residual", np.float32, (MAX_ITERS + 1,)), ("alpha", np.float32, (MAX_ITERS,))])
 
 EXPORTS = ("prism_workspace_bytes", "prism_polar", "prism_polar_ex", "prism_sqrt", "prism_sqrt_ex",
-           "prism_inv_root", "prism_inv_root_ex", "prism_sign", "prism_sign_ex", "prism_inverse", "prism_inverse_ex", "prism_sqrt_newton", "prism_sqrt_newton_ex", "prism_spd_inverse",
+           "prism_inv_root", "prism_inv_root_ex", "prism_sign", "prism_sign_ex", "prism_inverse", "prism_inverse_ex", "prism_sqrt_newton", "prism_sqrt_newton_ex", "prism_spd_inverse", "prism_run_grouped",
            "prism_sketch", "prism_gauss_parts", "prism_chain_product", "prism_gemm_f32",
            "prism_gemm_f64a", "prism_gemm_bf16_nt", "prism_profile_enable", "prism_profile_collect",
            "prism_last_error")
@@ -37,6 +37,11 @@ class Options(ctypes.Structure):
     _fields_ = [("flags", ctypes.c_uint32), ("warm_iters", ctypes.c_int32), ("workspace", ctypes.c_void_p),
                 ("workspace_bytes", ctypes.c_size_t), ("info", ctypes.c_void_p),
                 ("alpha_schedule", ctypes.POINTER(ctypes.c_float)), ("schedule_len", ctypes.c_int32)]
+
+
+class Group(ctypes.Structure):
+    _fields_ = [("x", ctypes.c_void_p), ("inv_out", ctypes.c_void_p), ("info", ctypes.c_void_p),
+                ("batch", ctypes.c_int32), ("m", ctypes.c_int32), ("n", ctypes.c_int32)]
 
 
 class PrismError(RuntimeError):
@@ -68,6 +73,7 @@ def lib():
         L.prism_sqrt_newton.argtypes = [vp, vp, i, i, i, i, i, i, dbl, vp]
         L.prism_sqrt_newton_ex.argtypes = L.prism_sqrt_newton.argtypes + [ctypes.POINTER(Options)]
         L.prism_spd_inverse.argtypes = [vp, vp, i, i, vp]
+        L.prism_run_grouped.argtypes = [i, ctypes.POINTER(Group), i, i, i, i, i, i, u64, dbl, vp, ctypes.POINTER(Options)]
         L.prism_sketch.argtypes = [vp, i, i, u64, i, i, vp]
         L.prism_gauss_parts.argtypes = [ctypes.c_uint32, ctypes.c_uint32, vp, vp, vp, vp]
         L.prism_chain_product.argtypes = [vp, vp, vp, i, i, i, vp]
@@ -197,6 +203,32 @@ def sqrt_newton(a, max_iters=30, tol=1e-6, fit=True, workspace=None, alpha_sched
     _check(lib().prism_sqrt_newton_ex(a.data_ptr(), inv.data_ptr(), b, m, n, _dtype_code(a), max_iters, int(bool(fit)), tol,
                                       _stream(), ctypes.byref(o)))
     return inv, info
+
+
+def run_grouped(fn, xs, degree=5, max_iters=30, sketch_dim=8, seed=22137, tol=1e-6, root_p=0, flags=0, warm_iters=0,
+                alpha_schedule=None):
+    """One call over tensors of different shapes (each [batch, m, n], all of one dtype), in place.
+    Returns (inverse outputs or None per group, info handles per group)."""
+    groups = (Group * len(xs))()
+    infos, invs = [], []
+    two_outputs = fn in (FN_SQRT, FN_SQRT_NEWTON)
+    for g, x in zip(groups, xs):
+        b, m, n = _batched(x)
+        info = _Info(b, x.device)
+        inv = torch.empty_like(x) if two_outputs else None
+        g.x, g.inv_out, g.info = x.data_ptr(), (inv.data_ptr() if two_outputs else None), info.buf.data_ptr()
+        g.batch, g.m, g.n = b, m, n
+        infos.append(info)
+        invs.append(inv)
+    o = Options()
+    o.flags, o.warm_iters = flags, warm_iters
+    if alpha_schedule is not None and len(alpha_schedule) > 0:
+        o._sched = (ctypes.c_float * len(alpha_schedule))(*[float(a) for a in alpha_schedule])
+        o.alpha_schedule = ctypes.cast(o._sched, ctypes.POINTER(ctypes.c_float))
+        o.schedule_len = len(alpha_schedule)
+    _check(lib().prism_run_grouped(fn, groups, len(xs), root_p, _dtype_code(xs[0]), degree, max_iters, sketch_dim, seed, tol,
+                                   _stream(), ctypes.byref(o)))
+    return invs, infos
 
 
 # ---- single steps (unit tests, profiling) ----

@@ -66,18 +66,14 @@ def _sampled_rel_err(x, samples, fro, n=4096):
 
 
 def test_c2_muon_full(prism):
-    """64 bf16 matrices in four calls of 16, plain bf16 iterate, 5 fixed iterations, each call on a
-    stream of its own (the bench launch configuration)."""
-    streams = [torch.cuda.Stream() for _ in range(4)]
-    xs, handles, allbits = [], [], []
+    """64 bf16 matrices, 16 of each shape, plain bf16 iterate, 5 fixed iterations, as one grouped
+    call (the bench launch configuration)."""
+    xs, allbits = [], []
     for shape_idx in range(4):
         bits = W.c2_muon_group(shape_idx)
         allbits.append(bits)
         xs.append(_bf16_tensor(bits.copy()))
-    torch.cuda.synchronize()
-    for shape_idx in range(4):
-        with torch.cuda.stream(streams[shape_idx]):
-            handles.append(prism.polar(xs[shape_idx], 5, 5, 16, SEED, 0.0, flags=prism.FLAG_BF16_PLAIN_ITERATE))
+    _, handles = prism.run_grouped(prism.FN_POLAR, xs, 5, 5, 16, SEED, 0.0, flags=prism.FLAG_BF16_PLAIN_ITERATE)
     torch.cuda.synchronize()
     for shape_idx in range(4):
         bits, x = allbits[shape_idx], xs[shape_idx]

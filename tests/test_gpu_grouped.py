@@ -1,0 +1,91 @@
+"""The grouped call (one library call over groups of different shapes, internal fork / join
+streams): every group must come out exactly as from its own single-group call, and against the
+oracle to the usual bars; the optimizer-side helpers are thin wrappers around it."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import prism_ref as O
+from paper_2601_22137_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+SEED = W.SKETCH_SEED
+
+
+@pytest.fixture(scope="module")
+def prism():
+    from paper_2601_22137_amd import prism as P
+    P.lib()
+    return P
+
+
+def _rel(x, ref):
+    return np.linalg.norm(np.asarray(x, dtype=np.float64) - ref) / np.linalg.norm(ref)
+
+
+def _bf16(bits):
+    return torch.from_numpy(bits.view(np.int16)).cuda().view(torch.bfloat16)
+
+
+def test_grouped_polar_equals_single_calls_and_oracle(prism):
+    """Muon-shaped groups at a quarter of the size (192x192, 192x768, 768x192, 192x576), six groups
+    so that internal streams are reused, twice in a row."""
+    bits = [W.c2_muon_group(i % 4, batch=3 + i, scale=4, data_seed=1002 + 10 * (i // 4)) for i in range(6)]
+    single = []
+    for b in bits:
+        x = _bf16(b.copy())
+        prism.polar(x, 5, 5, 16, SEED, 0.0, flags=prism.FLAG_BF16_PLAIN_ITERATE)
+        single.append(x)
+    for rep in range(2):
+        xs = [_bf16(b.copy()) for b in bits]
+        _, infos = prism.run_grouped(prism.FN_POLAR, xs, 5, 5, 16, SEED, 0.0, flags=prism.FLAG_BF16_PLAIN_ITERATE)
+        torch.cuda.synchronize()
+        for g, (x, ref) in enumerate(zip(xs, single)):
+            assert torch.equal(x.view(torch.int16), ref.view(torch.int16)), g
+            rec = infos[g].read()
+            assert np.all(rec["iters"] == 5)
+    out0 = W.from_bf16_bits(xs[1][0].view(torch.int16).cpu().numpy().view(np.uint16))
+    ref, _ = O.polar(W.from_bf16_bits(bits[1][0]), 5, 5, 16, SEED, 0.0)
+    assert _rel(out0, ref) <= 2e-2
+
+
+def test_grouped_inverse_root_and_sqrt(prism):
+    A1, A2 = W.c4_shampoo_spd(n=128, batch=2), W.c4_shampoo_spd(n=200, batch=3, data_seed=77)
+    xs = [torch.from_numpy(A1.copy()).cuda(), torch.from_numpy(A2.copy()).cuda()]
+    _, infos = prism.run_grouped(prism.FN_INV_ROOT, xs, 3, 40, 16, SEED, 1e-5, root_p=4)
+    for A, x, h in zip((A1, A2), xs, infos):
+        rec = h.read()
+        for i in range(A.shape[0]):
+            ref, oinfo = O.inv_root(A[i], 4, 40, 16, SEED, 1e-5)
+            assert _rel(x[i].cpu().numpy(), ref) <= 1e-5
+            assert rec[i]["iters"] == oinfo["iters"]
+    S1, S2 = W.c5_wishart_spd(n=128, batch=2), W.c5_wishart_spd(n=192, batch=1, data_seed=5)
+    xs = [torch.from_numpy(S1.copy()).cuda(), torch.from_numpy(S2.copy()).cuda()]
+    invs, infos = prism.run_grouped(prism.FN_SQRT_NEWTON, xs, 3, 30, 1, SEED, 1e-5)
+    for S, x, inv in zip((S1, S2), xs, invs):
+        rx, ry, _ = O.sqrt_db_newton(S[0], 30, 1e-5)
+        assert _rel(x[0].cpu().numpy(), rx) <= 1e-5 and _rel(inv[0].cpu().numpy(), ry) <= 1e-5
+
+
+def test_grouped_argument_errors(prism):
+    x = torch.zeros((1, 16, 16), dtype=torch.float32, device="cuda")
+    with pytest.raises(prism.PrismError):
+        prism.run_grouped(prism.FN_POLAR, [x, torch.zeros((1, 8, 8), dtype=torch.float32, device="cuda")], 4, 3, 0, SEED, 0.0)
+
+
+def test_optimizer_helpers(prism):
+    from paper_2601_22137_amd import optim
+    rng = np.random.default_rng(3)
+    shapes = [(96, 64), (64, 96), (96, 64), (128, 128), (64, 96)]
+    grads = [torch.from_numpy(rng.standard_normal(s).astype(np.float32)).cuda() for s in shapes]
+    outs = optim.muon_orthogonalize(grads, degree=5, iters=8, sketch_dim=8)
+    for g, o in zip(grads, outs):
+        assert o.shape == g.shape
+        ref, _ = O.polar(g.cpu().numpy(), 5, 8, 8, SEED, 0.0)
+        assert _rel(o.cpu().numpy(), ref) <= 1e-5
+    stats = [torch.from_numpy(W.c4_shampoo_spd(n=n, batch=1, data_seed=90 + n)[0]).cuda() for n in (64, 128, 64)]
+    roots, iters = optim.shampoo_inverse_roots(stats, root_p=4)
+    for s, r, it in zip(stats, roots, iters):
+        ref, oinfo = O.inv_root(s.cpu().numpy(), 4, 40, 16, SEED, 1e-5)
+        assert _rel(r.cpu().numpy(), ref) <= 1e-5 and it == oinfo["iters"]
