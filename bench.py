@@ -295,6 +295,13 @@ def main():
         for rec in inf:
             algo += fa * rec["iters"]
             execd += fe * rec["iters"]
+            if getattr(wl, "split", False):
+                # the low half of the iterate is multiplied only until the fitted alpha first leaves the
+                # upper end of its interval (from that update on the library reads the high half alone)
+                al = rec["alpha"][:rec["iters"]]
+                below = np.nonzero(al < 1.4499)[0]
+                n_split = int(below[0]) if len(below) else int(rec["iters"])
+                execd -= (fe - fa) * (rec["iters"] - n_split)
             iters_all.append(int(rec["iters"]))
     tflops_algo = algo / (ms_per_step * 1e-3) / 1e12
     tflops_exec = execd / (ms_per_step * 1e-3) / 1e12

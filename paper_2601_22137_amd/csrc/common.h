@@ -13,7 +13,7 @@ struct Ctrl {
   int done;      // 0 while iterating
   int iters;     // updates performed
   int status;    // PRISM_INFO_*
-  int pad0;
+  int plain;     // bf16 polar with a split iterate: from now on the update reads the high half only
   float alpha;   // coefficient of the update being applied
   float res0;    // residual at k = 0
   float res1;    // residual at k - 1
@@ -88,6 +88,7 @@ struct Bf16Desc {
   float* rho_part;
   const Ctrl* ctrl;
   int xcd_private;                                   // set by launch_gemm_bf16: contiguous tile ranges per XCD
+  int plain_filter;                                  // 1: skip matrices whose ctrl.plain is set; 2: skip the others (0: none)
   int dbg;                                           // timing experiments only (test entry): bit0: no global loads after the prologue; bit1: XCD-private tile ranges; bit2: 4x8 tile blocks
 };
 int launch_gemm_bf16(const Bf16Desc& g, int tile, hipStream_t s);

@@ -294,6 +294,10 @@ __global__ __launch_bounds__(NT) void solve_kernel(SolveArgs a) {
     if (vh < bestv) { bestv = vh; best = hi; }
     ctl->alpha = (float)best;
     info->alpha[a.k] = (float)best;
+    // The fit has left the upper end of its interval: no eigenvalue of R is close to 1 any more,
+    // i.e. no singular value of the iterate is small.  The bf16 polar path stops carrying the low
+    // half of the iterate from here on (it exists for the small singular values only).
+    if (best < hi - 1e-6) ctl->plain = 1;
   }
 }
 

@@ -94,6 +94,7 @@ __global__ __launch_bounds__(NT, T == 128 ? 3 : 1) void gemm_bf16_kernel(Bf16Des
     tn = rem - tm * tiles_n;
   }
   if (g.ctrl && g.ctrl[b].done) return;
+  if (g.plain_filter && g.ctrl && ((g.ctrl[b].plain != 0) != (g.plain_filter == 2))) return;
   const float alpha = g.ctrl ? g.ctrl[b].alpha : 1.0f;
 
   const int t = threadIdx.x, lane = t & 63;

@@ -91,7 +91,7 @@ __global__ __launch_bounds__(NT) void prepare_kernel(PrepArgs a) {
     c.done = (finite && !zero) ? 0 : 1;
     c.iters = 0;
     c.status = !finite ? PRISM_INFO_NONFINITE : (zero ? PRISM_INFO_ZERO : PRISM_INFO_BUDGET);
-    c.pad0 = 0;
+    c.plain = 0;
     c.alpha = 0.0f; c.res0 = 0.0f; c.res1 = 0.0f; c.res2 = 0.0f;
     c.norm = norm; c.scale = scale;
     a.ctrl[b] = c;
@@ -190,7 +190,7 @@ __global__ __launch_bounds__(NT) void prepare_bf16_kernel(PrepArgs a) {
     c.done = (finite && !zero) ? 0 : 1;
     c.iters = 0;
     c.status = !finite ? PRISM_INFO_NONFINITE : (zero ? PRISM_INFO_ZERO : PRISM_INFO_BUDGET);
-    c.pad0 = 0;
+    c.plain = 0;
     c.alpha = 0.0f; c.res0 = 0.0f; c.res1 = 0.0f; c.res2 = 0.0f;
     c.norm = norm; c.scale = scale;
     a.ctrl[b] = c;

@@ -315,6 +315,7 @@ int run_polar_bf16(Run& r) {
   float* R = r.at<float>(P.o_r);
   uint16_t* Rb = r.at<uint16_t>(P.o_rb);
   uint16_t* Qb = P.d == 2 ? r.at<uint16_t>(P.o_qb) : nullptr;
+  static const int keep_split = getenv("PRISM_BF16_KEEP_SPLIT") ? atoi(getenv("PRISM_BF16_KEEP_SPLIT")) : 0;
   static const int no_dual = getenv("PRISM_BF16_NO_DUAL") ? atoi(getenv("PRISM_BF16_NO_DUAL")) : 0;
   const int ntg = Sp / Tg;
   const int nparts = sym ? ntg * (ntg + 1) / 2 : ntg * ntg;
@@ -348,7 +349,17 @@ int run_polar_bf16(Run& r) {
     a.Ct = Xg[cur ^ 1]; a.strideCt = LS; a.ldct = Lp;
     a.Xhi = Xhi[cur]; a.Xlo = Xlo[cur]; a.coef_is_alpha = P.d == 1; a.ctrl = r.ctrl;
     a.dbg = no_dual ? 8 : 0;
-    { ProfScope ps(PK_BF16_APPLY, r.s); CHECK_LAUNCH(launch_gemm_bf16(a, Ta, r.s)); }
+    if (P.split && !keep_split) {
+      // matrices whose fit has left the upper end of its interval (ctrl.plain) are updated from the
+      // high half alone: two launches, each skipping the matrices of the other kind
+      a.plain_filter = 1;
+      { ProfScope ps(PK_BF16_APPLY, r.s); CHECK_LAUNCH(launch_gemm_bf16(a, Ta, r.s)); }
+      a.A2 = nullptr; a.Xlo = nullptr; a.plain_filter = 2;
+      { ProfScope ps(PK_BF16_APPLY, r.s); CHECK_LAUNCH(launch_gemm_bf16(a, Ta, r.s)); }
+    } else {
+      ProfScope ps(PK_BF16_APPLY, r.s);
+      CHECK_LAUNCH(launch_gemm_bf16(a, Ta, r.s));
+    }
     cur ^= 1;
   }
   return PRISM_OK;
