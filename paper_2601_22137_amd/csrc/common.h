@@ -52,6 +52,8 @@ struct GemmDesc {
   int cin2_alpha_pow;   // AXPY: power of ctrl.alpha that multiplies Cin2
   int cin_one_minus_alpha;  // AXPY: Cin is weighted by (1 - ctrl.alpha) (DB Newton updates)
   int acc_neg;          // STORE, AXPY: acc enters with a minus sign
+  int sym_skew_bound;   // sym: the mirror image of a tile gets a minus sign when exactly one of its row and column
+                        // blocks lies below this index (half-swept matrices of the block Gauss-Jordan inverse); 0: none
   int skip_m0, skip_m1; // output tiles starting in rows [skip_m0, skip_m1) are left untouched (0, 0: none)
   int skip_n0, skip_n1; // likewise for columns
   float* rho_part;      // [batch][tiles] partial sums of R^2 (RESIDUAL / MNEXT)

@@ -238,6 +238,9 @@ int launch_spd_inverse(const float* M, float* N, int np, int batch, const Ctrl* 
     u.C = N; u.strideC = per_mat; u.ldc = np; u.Cin = N; u.strideCin = per_mat; u.ldcin = np;
     u.M = np; u.N = np; u.epi = EPI_AXPY; u.acc_neg = 1;
     u.skip_m0 = u.skip_n0 = k * OB; u.skip_m1 = u.skip_n1 = (k + 1) * OB;
+    // A half-swept symmetric matrix is symmetric within the swept and within the unswept blocks and
+    // antisymmetric between them, and the update keeps that: upper triangle of tiles only
+    u.sym = 1; u.sym_skew_bound = k * OB;
     rc = launch_gemm_f32(u, 128, 128, s);
     if (rc != PRISM_OK) return rc;
     GemmDesc c = g;                                      // U = -A_:,k P

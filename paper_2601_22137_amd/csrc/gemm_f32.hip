@@ -262,6 +262,7 @@ __global__ __launch_bounds__(NT) void gemm_kernel(GemmDesc g) {
       }
       if (SYM && tm != tn) {
         // the lane holds four consecutive rows of one column: one 16-byte store in the mirror image
+        if (g.sym_skew_bound > 0 && ((m0 < g.sym_skew_bound) != (n0 < g.sym_skew_bound))) outv = -outv;
         const int gi0 = m0 + wm0 + i * 16 + 4 * (lane >> 4);
         *(typename Acc<TC>::type*)((TC*)g.C + (long long)b * g.strideC + (long long)gj * g.ldc + gi0) = outv;
       }
