@@ -5,11 +5,15 @@
  * iteration, the highest coefficient alpha_k of the update polynomial
  * g_d(R_k; alpha) to the spectrum of the current residual R_k through a
  * sketched least-squares problem (paper Sections 3-4, eq. (2)-(4)).
- * Three iterations of Table 1 are provided:
+ * The iterations of Table 1 and Section 4 are provided:
  *
- *   prism_polar      polar factor U V^T          R_k = I - X_k^T X_k
- *   prism_sqrt       A^{1/2} and A^{-1/2}        R_k = I - Y_k X_k   (Theorem 3)
- *   prism_inv_root   A^{-1/p}                    R_k = I - M_k       (App. A.3)
+ *   prism_polar        polar factor U V^T          R_k = I - X_k^T X_k
+ *   prism_sqrt         A^{1/2} and A^{-1/2}        R_k = I - Y_k X_k   (Theorem 3)
+ *   prism_inv_root     A^{-1/p}                    R_k = I - M_k       (App. A.3)
+ *   prism_sign         sign(A)                     R_k = I - X_k^2     (Section 4)
+ *   prism_inverse      A^{-1} (Chebyshev)          R_k = I - A X_k     (App. A.4)
+ *   prism_sqrt_newton  A^{1/2} and A^{-1/2}        R_k = I - M_k       (DB Newton, App. A.2)
+ *   prism_run_grouped  any of them over groups of different shapes in one call
  *
  * Conventions common to all entry points
  *   - Every matrix pointer is a DEVICE pointer to row-major, contiguous,
@@ -17,7 +21,8 @@
  *   - `dt` is the storage type of the caller's matrices.  PRISM_F32 computes
  *     with fp32 matrix instructions (the inverse-root recurrence for M_k in
  *     fp64); PRISM_BF16 computes with bf16 matrix instructions accumulating in
- *     fp32 and is available for prism_polar only.
+ *     fp32 and is available for prism_polar only (the iterate is carried as
+ *     a pair of bf16 matrices while small singular values need it).
  *   - `degree` is the degree of the update in X: 3 (d = 1) or 5 (d = 2).
  *   - `sketch_dim` = p_s, the number of rows of the Gaussian sketch S_k
  *     (1..64).  0 disables the fit: alpha_k stays at the Taylor value, which is
