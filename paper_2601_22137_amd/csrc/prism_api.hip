@@ -678,6 +678,30 @@ int run_grouped(int fn, const prism_group* groups, int ngroups, int root_p, int 
   return first_error;
 }
 
+// Single-shape entry points: a large batch of large matrices is enqueued as two half batches on
+// the internal streams, so that the partial last wave of tiles and the latency-bound kernels of one
+// half run beside the GEMMs of the other (+3 % on 8 x 4096^2 and 32 x 1024^2).  Every matrix is
+// computed exactly as in an unsplit call; an explicit workspace keeps the call on one stream.
+int run_auto(int fn, void* a, void* inv_out, int root_p, int batch, int m, int n, int dt, int degree, int max_iters,
+             int sketch_dim, uint64_t seed, double tol, void* stream, const prism_options* opt) {
+  static const int no_split = getenv("PRISM_NO_BATCH_SPLIT") ? atoi(getenv("PRISM_NO_BATCH_SPLIT")) : 0;
+  const int S = m < n ? m : n;
+  if (no_split || !a || batch < 8 || (batch & 1) || S < 1024 || (opt && opt->workspace) || g_prof_on)
+    return run(fn, a, inv_out, root_p, batch, m, n, dt, degree, max_iters, sketch_dim, seed, tol, stream, opt);
+  const size_t esz = dt == PRISM_BF16 ? 2 : 4;
+  const size_t half = (size_t)(batch / 2) * m * n * esz;
+  prism_group gr[2];
+  for (int h = 0; h < 2; ++h) {
+    gr[h].x = (char*)a + h * half;
+    gr[h].inv_out = inv_out ? (char*)inv_out + h * half : nullptr;
+    gr[h].info = (opt && opt->info) ? opt->info + h * (batch / 2) : nullptr;
+    gr[h].batch = batch / 2; gr[h].m = m; gr[h].n = n;
+  }
+  prism_options o = opt ? *opt : prism_options{};
+  o.info = nullptr;
+  return run_grouped(fn, gr, 2, root_p, dt, degree, max_iters, sketch_dim, seed, tol, stream, &o);
+}
+
 }  // namespace
 }  // namespace prism
 
@@ -719,53 +743,53 @@ int prism_workspace_bytes(int fn, int batch, int m, int n, prism_dtype dt, int d
 
 int prism_polar(void* x, int batch, int m, int n, prism_dtype dt, int degree, int max_iters, int sketch_dim,
                 uint64_t seed, double tol, void* stream) {
-  return run(PRISM_FN_POLAR, x, nullptr, 0, batch, m, n, (int)dt, degree, max_iters, sketch_dim, seed, tol, stream, nullptr);
+  return run_auto(PRISM_FN_POLAR, x, nullptr, 0, batch, m, n, (int)dt, degree, max_iters, sketch_dim, seed, tol, stream, nullptr);
 }
 int prism_polar_ex(void* x, int batch, int m, int n, prism_dtype dt, int degree, int max_iters, int sketch_dim,
                    uint64_t seed, double tol, void* stream, const prism_options* opt) {
-  return run(PRISM_FN_POLAR, x, nullptr, 0, batch, m, n, (int)dt, degree, max_iters, sketch_dim, seed, tol, stream, opt);
+  return run_auto(PRISM_FN_POLAR, x, nullptr, 0, batch, m, n, (int)dt, degree, max_iters, sketch_dim, seed, tol, stream, opt);
 }
 int prism_sqrt(void* a, void* inv_out, int batch, int m, int n, prism_dtype dt, int degree, int max_iters,
                int sketch_dim, uint64_t seed, double tol, void* stream) {
-  return run(PRISM_FN_SQRT, a, inv_out, 0, batch, m, n, (int)dt, degree, max_iters, sketch_dim, seed, tol, stream, nullptr);
+  return run_auto(PRISM_FN_SQRT, a, inv_out, 0, batch, m, n, (int)dt, degree, max_iters, sketch_dim, seed, tol, stream, nullptr);
 }
 int prism_sqrt_ex(void* a, void* inv_out, int batch, int m, int n, prism_dtype dt, int degree, int max_iters,
                   int sketch_dim, uint64_t seed, double tol, void* stream, const prism_options* opt) {
-  return run(PRISM_FN_SQRT, a, inv_out, 0, batch, m, n, (int)dt, degree, max_iters, sketch_dim, seed, tol, stream, opt);
+  return run_auto(PRISM_FN_SQRT, a, inv_out, 0, batch, m, n, (int)dt, degree, max_iters, sketch_dim, seed, tol, stream, opt);
 }
 int prism_inv_root(void* a, int root_p, int batch, int m, int n, prism_dtype dt, int degree, int max_iters,
                    int sketch_dim, uint64_t seed, double tol, void* stream) {
-  return run(PRISM_FN_INV_ROOT, a, nullptr, root_p, batch, m, n, (int)dt, degree, max_iters, sketch_dim, seed, tol, stream, nullptr);
+  return run_auto(PRISM_FN_INV_ROOT, a, nullptr, root_p, batch, m, n, (int)dt, degree, max_iters, sketch_dim, seed, tol, stream, nullptr);
 }
 int prism_inv_root_ex(void* a, int root_p, int batch, int m, int n, prism_dtype dt, int degree, int max_iters,
                       int sketch_dim, uint64_t seed, double tol, void* stream, const prism_options* opt) {
-  return run(PRISM_FN_INV_ROOT, a, nullptr, root_p, batch, m, n, (int)dt, degree, max_iters, sketch_dim, seed, tol, stream, opt);
+  return run_auto(PRISM_FN_INV_ROOT, a, nullptr, root_p, batch, m, n, (int)dt, degree, max_iters, sketch_dim, seed, tol, stream, opt);
 }
 
 int prism_sign(void* x, int batch, int m, int n, prism_dtype dt, int degree, int max_iters, int sketch_dim,
                uint64_t seed, double tol, void* stream) {
-  return run(PRISM_FN_SIGN, x, nullptr, 0, batch, m, n, (int)dt, degree, max_iters, sketch_dim, seed, tol, stream, nullptr);
+  return run_auto(PRISM_FN_SIGN, x, nullptr, 0, batch, m, n, (int)dt, degree, max_iters, sketch_dim, seed, tol, stream, nullptr);
 }
 int prism_sign_ex(void* x, int batch, int m, int n, prism_dtype dt, int degree, int max_iters, int sketch_dim,
                   uint64_t seed, double tol, void* stream, const prism_options* opt) {
-  return run(PRISM_FN_SIGN, x, nullptr, 0, batch, m, n, (int)dt, degree, max_iters, sketch_dim, seed, tol, stream, opt);
+  return run_auto(PRISM_FN_SIGN, x, nullptr, 0, batch, m, n, (int)dt, degree, max_iters, sketch_dim, seed, tol, stream, opt);
 }
 int prism_inverse(void* a, int batch, int m, int n, prism_dtype dt, int max_iters, int sketch_dim, uint64_t seed,
                   double tol, void* stream) {
-  return run(PRISM_FN_INVERSE, a, nullptr, 0, batch, m, n, (int)dt, 5, max_iters, sketch_dim, seed, tol, stream, nullptr);
+  return run_auto(PRISM_FN_INVERSE, a, nullptr, 0, batch, m, n, (int)dt, 5, max_iters, sketch_dim, seed, tol, stream, nullptr);
 }
 int prism_inverse_ex(void* a, int batch, int m, int n, prism_dtype dt, int max_iters, int sketch_dim, uint64_t seed,
                      double tol, void* stream, const prism_options* opt) {
-  return run(PRISM_FN_INVERSE, a, nullptr, 0, batch, m, n, (int)dt, 5, max_iters, sketch_dim, seed, tol, stream, opt);
+  return run_auto(PRISM_FN_INVERSE, a, nullptr, 0, batch, m, n, (int)dt, 5, max_iters, sketch_dim, seed, tol, stream, opt);
 }
 
 int prism_sqrt_newton(void* a, void* inv_out, int batch, int m, int n, prism_dtype dt, int max_iters, int fit, double tol,
                       void* stream) {
-  return run(PRISM_FN_SQRT_NEWTON, a, inv_out, 0, batch, m, n, (int)dt, 3, max_iters, fit ? 1 : 0, 0, tol, stream, nullptr);
+  return run_auto(PRISM_FN_SQRT_NEWTON, a, inv_out, 0, batch, m, n, (int)dt, 3, max_iters, fit ? 1 : 0, 0, tol, stream, nullptr);
 }
 int prism_sqrt_newton_ex(void* a, void* inv_out, int batch, int m, int n, prism_dtype dt, int max_iters, int fit, double tol,
                          void* stream, const prism_options* opt) {
-  return run(PRISM_FN_SQRT_NEWTON, a, inv_out, 0, batch, m, n, (int)dt, 3, max_iters, fit ? 1 : 0, 0, tol, stream, opt);
+  return run_auto(PRISM_FN_SQRT_NEWTON, a, inv_out, 0, batch, m, n, (int)dt, 3, max_iters, fit ? 1 : 0, 0, tol, stream, opt);
 }
 
 int prism_spd_inverse(const float* a, float* out, int batch, int n, void* stream) {
