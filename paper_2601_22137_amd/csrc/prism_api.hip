@@ -246,7 +246,12 @@ GemmDesc f32_desc(const Run& r, const float* A, int lda, long long sa, const flo
   return g;
 }
 
-// Products whose exact result is symmetric are computed on the upper triangle of tiles only.
+// Upper-triangle products with a mirrored lower half.  Taken only where the symmetry does not rest
+// on iterates commuting: X^T X, the square of a matrix that was itself stored mirrored, and updates
+// whose result never re-enters the residual (X of the inverse root, X and Y of DB Newton).  In the
+// coupled square root, the sign and the Chebyshev inverse the iterates commute only up to kappa * eps;
+// mirroring there turns that defect into a perturbation the iteration amplifies (divergence from
+// kappa ~ 1e3 on), so those keep every tile.
 int f32_sym() {
   static const int off = getenv("PRISM_F32_NO_SYM") ? atoi(getenv("PRISM_F32_NO_SYM")) : 0;
   return off ? 0 : 1;
@@ -260,13 +265,14 @@ int run_polar_f32(Run& r) {
   float* X[2] = {r.at<float>(P.o_x[0]), r.at<float>(P.o_x[1])};
   float* R = r.at<float>(P.o_r);
   float* Q = P.d == 2 ? r.at<float>(P.o_q) : nullptr;
-  const int sym = f32_sym();
+  const bool polar = P.fn != PRISM_FN_SIGN;
+  const int sym = polar ? f32_sym() : 0;
   const int nparts = sym_parts(Sp / T, sym);
   int cur = 0;
   for (int k = 0; k <= r.max_iters; ++k) {
     if (k == r.max_iters && r.tol <= 0.0) break;
-    // G = X^T X; matrix sign: G = X X, symmetric by assumption on the input
-    GemmDesc g = f32_desc(r, X[cur], Sp, LS, X[cur], Sp, LS, Sp, Sp, Lp, P.fn == PRISM_FN_SIGN ? 0 : 1);
+    // G = X^T X; matrix sign: G = X X (any square input, all tiles)
+    GemmDesc g = f32_desc(r, X[cur], Sp, LS, X[cur], Sp, LS, Sp, Sp, Lp, polar ? 1 : 0);
     g.sym = sym;
     g.epi = EPI_RESIDUAL; g.C = R; g.strideC = SS; g.ldc = Sp; g.rho_part = r.rho;
     { ProfScope ps(PK_F32_RESID, r.s); CHECK_LAUNCH(launch_gemm_f32(g, T, T, r.s)); }
@@ -275,7 +281,7 @@ int run_polar_f32(Run& r) {
     if (k == r.max_iters) break;
     const float* Bop = R;
     if (P.d == 2) {
-      GemmDesc q = f32_desc(r, R, Sp, SS, R, Sp, SS, Sp, Sp, Sp, 1);           // R symmetric: R^2 = R^T R
+      GemmDesc q = f32_desc(r, R, Sp, SS, R, Sp, SS, Sp, Sp, Sp, polar ? 1 : 0);  // mirrored R: R^2 = R^T R
       q.sym = sym;
       q.epi = EPI_POLYQ; q.C = Q; q.strideC = SS; q.ldc = Sp; q.Cin = R; q.strideCin = SS; q.ldcin = Sp; q.c1 = 0.5f;
       { ProfScope ps(PK_F32_POLYQ, r.s); CHECK_LAUNCH(launch_gemm_f32(q, T, T, r.s)); }
@@ -373,8 +379,9 @@ int run_sqrt_f32(Run& r) {
   float* Y[2] = {r.at<float>(P.o_y[0]), r.at<float>(P.o_y[1])};
   float* R = r.at<float>(P.o_r);
   float* Q = P.d == 2 ? r.at<float>(P.o_q) : nullptr;
-  // X_k, Y_k, R_k and Q_k are polynomials in A: they commute and every product here is symmetric
-  const int sym = f32_sym();
+  // X_k and Y_k commute up to kappa * eps only: every product keeps all its tiles.  (Mirroring only
+  // Y X and R^2 is stable but costs the root an order of magnitude of accuracy from kappa ~ 1e4 on.)
+  const int sym = 0;
   const int nparts = sym_parts(Sp / T, sym);
   int cur = 0;
   for (int k = 0; k <= r.max_iters; ++k) {
@@ -396,11 +403,11 @@ int run_sqrt_f32(Run& r) {
     }
     GemmDesc ax = f32_desc(r, X[cur], Sp, SS, Pm, Sp, SS, Sp, Sp, Sp, 0);        // X + X Q
     ax.epi = EPI_AXPY; ax.C = X[cur ^ 1]; ax.strideC = SS; ax.ldc = Sp; ax.Cin = X[cur]; ax.strideCin = SS; ax.ldcin = Sp;
-    ax.coef_is_alpha = P.d == 1; ax.sym = sym;
+    ax.coef_is_alpha = P.d == 1;
     { ProfScope ps(PK_F32_APPLY, r.s); CHECK_LAUNCH(launch_gemm_f32(ax, T, T, r.s)); }
     GemmDesc ay = f32_desc(r, Pm, Sp, SS, Y[cur], Sp, SS, Sp, Sp, Sp, 0);        // Y + Q Y
     ay.epi = EPI_AXPY; ay.C = Y[cur ^ 1]; ay.strideC = SS; ay.ldc = Sp; ay.Cin = Y[cur]; ay.strideCin = SS; ay.ldcin = Sp;
-    ay.coef_is_alpha = P.d == 1; ay.sym = sym;
+    ay.coef_is_alpha = P.d == 1;
     { ProfScope ps(PK_F32_APPLY, r.s); CHECK_LAUNCH(launch_gemm_f32(ay, T, T, r.s)); }
     cur ^= 1;
   }
@@ -416,8 +423,7 @@ int run_inverse_f32(Run& r) {
   const float* As = r.at<float>(P.o_y[0]);
   float* R = r.at<float>(P.o_r);
   float* Q = r.at<float>(P.o_q);
-  // X_k = A_s^T q(A_s A_s^T): A_s X_k, R_k and Q_k are symmetric, X_k Q_k is not
-  const int sym = f32_sym();
+  const int sym = 0;   // A_s X_k is symmetric up to kappa * eps only: all tiles
   const int nparts = sym_parts(Sp / T, sym);
   int cur = 0;
   for (int k = 0; k <= r.max_iters; ++k) {
@@ -453,7 +459,7 @@ int run_sqrt_newton_f32(Run& r) {
   float* N = r.at<float>(P.o_q);
   const int nparts0 = (Sp / 64) * (Sp / 64);               // prepare step: one partial per 64 x 64 tile
   const int nparts = nparts0 < 512 ? nparts0 : 512;        // later: the M update
-  const int sym = f32_sym();                               // X_k, Y_k, N_k are functions of A and commute
+  const int sym = f32_sym();                               // X, Y never re-enter M: mirrored halves are safe
   int cur = 0;
   for (int k = 0; k <= r.max_iters; ++k) {
     if (k == r.max_iters && r.tol <= 0.0) break;
@@ -498,7 +504,7 @@ int run_inv_root_f32(Run& r) {
     if (k == r.max_iters) break;
     GemmDesc ax = f32_desc(r, X[cur], Sp, SS, R, Sp, SS, Sp, Sp, Sp, 0);         // X (I + alpha R)
     ax.epi = EPI_AXPY; ax.C = X[cur ^ 1]; ax.strideC = SS; ax.ldc = Sp; ax.Cin = X[cur]; ax.strideCin = SS; ax.ldcin = Sp;
-    ax.coef_is_alpha = 1; ax.sym = f32_sym();   // X_k and R_k commute; the power chain below keeps all tiles
+    ax.coef_is_alpha = 1; ax.sym = f32_sym();   // X never re-enters M; the power chain below keeps all tiles
     { ProfScope ps(PK_F32_APPLY, r.s); CHECK_LAUNCH(launch_gemm_f32(ax, T, T, r.s)); }
     // (I + alpha R)^p = I + E_p, built on the part beyond the identity so that fp32 rounding acts
     // on the small quantity only: E_1 = alpha R, squaring E <- 2E + E E, times T: E <- E + E_1 + E E_1.

@@ -143,3 +143,30 @@ def inverse_general(n=512, batch=4, data_seed=1008, cond=30.0):
         sigma = np.exp(rng.uniform(-np.log(cond), 0.0, size=n))
         out[b] = ((u * sigma[None, :]) @ v.T * (1.0 + 2.0 * b)).astype(np.float32)
     return out
+
+
+def spd_conditioned(n=384, batch=2, cond=1e4, data_seed=1009):
+    """fp32 symmetric positive definite Q diag(lambda) Q^T, lambda log-uniform in [1/cond, 1]:
+    ill-conditioned inputs for the square-root iterations (the paper's Shampoo preconditioners
+    reach such condition numbers before the ridge is added)."""
+    out = np.empty((batch, n, n), dtype=np.float32)
+    for b in range(batch):
+        rng = _rng(data_seed + b)
+        q = _orthogonal(rng, n)
+        lam = np.exp(rng.uniform(-np.log(cond), 0.0, size=n))
+        a = (q * lam[None, :]) @ q.T
+        out[b] = (0.5 * (a + a.T)).astype(np.float32)
+    return out
+
+
+def sign_nonnormal(n=256, batch=2, data_seed=1010, decades=1.5, skew=0.3):
+    """fp32 S diag(lambda) S^-1 with S = I + skew * G / sqrt(n), G Gaussian: diagonalisable with
+    real eigenvalues of both signs (|lambda| log-uniform in [10^-decades, 1]) but neither
+    symmetric nor normal, and neither is its square."""
+    out = np.empty((batch, n, n), dtype=np.float32)
+    for b in range(batch):
+        rng = _rng(data_seed + b)
+        s = np.eye(n) + skew * rng.standard_normal((n, n)) / np.sqrt(n)
+        lam = 10.0 ** rng.uniform(-decades, 0.0, size=n) * rng.choice([-1.0, 1.0], size=n)
+        out[b] = np.linalg.solve(s.T, (s * lam[None, :]).T).T.astype(np.float32)
+    return out

@@ -111,3 +111,21 @@ def test_sqrt_newton_degenerate_and_errors(prism):
     assert torch.allclose(inv[1], 0.5 * torch.eye(64, device="cuda"), atol=1e-5)
     with pytest.raises(prism.PrismError):
         prism.sqrt_newton(torch.zeros((1, 8, 12), dtype=torch.float32, device="cuda"))
+
+
+@pytest.mark.parametrize("cond", [1e3, 1e4])
+def test_sqrt_newton_ill_conditioned(prism, cond):
+    """X and Y never re-enter M, so the mirrored halves of X N and Y N only cost accuracy of the
+    order the fp32 inverse loses anyway (about cond * eps): iteration counts agree with the oracle
+    and the error bars scale with cond."""
+    A = W.spd_conditioned(n=384, batch=2, cond=cond)
+    x = torch.from_numpy(A.copy()).cuda()
+    inv, h = prism.sqrt_newton(x, 40, 1e-5)
+    info = h.read()
+    root, iroot = x.cpu().numpy(), inv.cpu().numpy()
+    for b in range(2):
+        rx, ry, oinfo = O.sqrt_db_newton(A[b], 40, 1e-5)
+        assert oinfo["status"] == O.STATUS_CONVERGED
+        assert info[b]["iters"] == oinfo["iters"] and info[b]["status"] == oinfo["status"]
+        assert _rel(root[b], rx) <= TOL_F32 * cond / 1e3 * 2
+        assert _rel(iroot[b], ry) <= TOL_F32 * cond / 1e3 * 2

@@ -143,6 +143,27 @@ def test_c5_sqrt_fp32_reduced(prism, n, degree, p_s):
         _check_info(info[i], oinfo, res_floor=3e-6)
 
 
+@pytest.mark.parametrize("degree", [3, 5])
+@pytest.mark.parametrize("cond", [1e3, 1e4, 1e5])
+def test_sqrt_fp32_ill_conditioned(prism, degree, cond):
+    """X_k and Y_k commute only up to cond * eps in floating point; an update that relies on exact
+    commutation (keeping half of a product and mirroring it) diverges from cond ~ 1e3 on.  The
+    root keeps the 1e-5 bar; the forward error of the inverse root grows with cond."""
+    A = W.spd_conditioned(n=384, batch=2, cond=cond)
+    x = torch.from_numpy(A.copy()).cuda()
+    inv, h = prism.sqrt(x, degree, 60, 32, SEED, 1e-5)
+    info = h.read()
+    root, iroot = x.cpu().numpy(), inv.cpu().numpy()
+    for i in range(2):
+        r_ref, i_ref, oinfo = O.sqrt(A[i], degree, 60, 32, SEED, 1e-5)
+        assert oinfo["status"] == O.STATUS_CONVERGED
+        # at cond = 1e5 the fp32 residual floor is close enough to tol to move the stop by one step
+        assert abs(int(info[i]["iters"]) - oinfo["iters"]) <= (1 if cond > 1e4 else 0)
+        assert info[i]["status"] == oinfo["status"]
+        assert _rel(root[i], r_ref) <= TOL_F32
+        assert _rel(iroot[i], i_ref) <= TOL_F32 * max(1.0, cond / 1e3)
+
+
 # ------------------------------------------------------------------ special cases and edges
 
 def test_no_sketch_is_classical_iteration(prism):

@@ -132,3 +132,48 @@ def test_sign_and_inverse_argument_errors(prism):
     info = prism.inverse(z, 20, 4, SEED, 1e-6).read()
     assert info[0]["status"] == prism.INFO_ZERO and info[1]["status"] == prism.INFO_CONVERGED
     assert torch.allclose(z[1], torch.eye(16, device="cuda"), atol=1e-5)
+
+
+def test_sign_of_a_nonnormal_matrix(prism):
+    """Neither the input nor its square is symmetric: every product has to keep all its tiles and
+    its operand order."""
+    A = W.sign_nonnormal()
+    x = torch.from_numpy(A.copy()).cuda()
+    info = prism.sign(x, 5, 40, 16, SEED, 1e-5).read()
+    out = x.cpu().numpy()
+    for b in range(A.shape[0]):
+        ref, oinfo = O.sign(A[b], 5, 40, 16, SEED, 1e-5)
+        assert oinfo["status"] == O.STATUS_CONVERGED
+        assert np.linalg.norm(ref - ref.T) / np.linalg.norm(ref) > 1e-2
+        assert _rel(out[b], ref) <= TOL_F32
+        _check_info(info[b], oinfo, 0.375, 1.45)
+
+
+@pytest.mark.parametrize("decades", [3.0, 4.0])
+def test_sign_ill_conditioned(prism, decades):
+    """Eigenvalues down to 10^-decades: the iterates commute only up to (1 / |lambda_min|) * eps,
+    which an update that assumed exact symmetry would amplify.  The forward error of sign itself
+    grows like 1 / |lambda_min|, so the bar scales with it; the iteration counts must still agree."""
+    A = W.sign_indefinite(n=384, batch=2, decades=decades)
+    x = torch.from_numpy(A.copy()).cuda()
+    info = prism.sign(x, 5, 60, 32, SEED, 1e-5).read()
+    out = x.cpu().numpy()
+    for b in range(2):
+        ref, oinfo = O.sign(A[b], 5, 60, 32, SEED, 1e-5)
+        assert oinfo["status"] == O.STATUS_CONVERGED
+        assert info[b]["iters"] == oinfo["iters"] and info[b]["status"] == oinfo["status"]
+        assert _rel(out[b], ref) <= TOL_F32 * 10.0 ** (decades - 2.5)
+
+
+def test_inverse_ill_conditioned_stays_at_the_rounding_floor(prism):
+    """cond = 1e3: the fp32 residual floor (about cond * 2^-24) lies above tol = 1e-5, so the call
+    runs out its budget; the iterate must sit at that floor, not drift away from it."""
+    A = W.inverse_general(n=384, batch=2, cond=1e3)
+    x = torch.from_numpy(A.copy()).cuda()
+    info = prism.inverse(x, 40, 32, SEED, 1e-5).read()
+    out = x.cpu().numpy()
+    for b in range(2):
+        ref = np.linalg.inv(A[b].astype(np.float64))
+        assert info[b]["status"] in (prism.INFO_CONVERGED, prism.INFO_BUDGET)
+        assert _rel(out[b], ref) <= 1e-4
+        assert info[b]["residual"][info[b]["iters"]] <= 2e-4
