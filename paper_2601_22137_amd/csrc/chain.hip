@@ -23,7 +23,7 @@ constexpr int KC = 64;     // k per chunk
 constexpr int ROWS = 64;   // rows of R per workgroup
 
 template <int LD>
-__global__ __launch_bounds__(NT) void chain_kernel(const float* __restrict__ R, long long strideR, int ldr,
+__global__ __launch_bounds__(NT, 2) void chain_kernel(const float* __restrict__ R, long long strideR, int ldr,
                                                    const float* __restrict__ Vin, long long strideVin,
                                                    float* __restrict__ Vout, long long strideVout, int n,
                                                    const Ctrl* __restrict__ ctrl) {
@@ -124,7 +124,7 @@ __global__ __launch_bounds__(NT) void chain_kernel(const float* __restrict__ R, 
 // area (no workgroup barrier inside the loop); the four partial sums are added through LDS in a
 // fixed order at the end.
 template <int LD>
-__global__ __launch_bounds__(NT) void chain_small_kernel(const float* __restrict__ R, long long strideR, int ldr,
+__global__ __launch_bounds__(NT, 2) void chain_small_kernel(const float* __restrict__ R, long long strideR, int ldr,
                                                          const float* __restrict__ Vin, long long strideVin,
                                                          float* __restrict__ Vout, long long strideVout, int n,
                                                          const Ctrl* __restrict__ ctrl) {

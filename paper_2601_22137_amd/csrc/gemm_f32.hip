@@ -92,7 +92,7 @@ __device__ inline TC epilogue(const GemmDesc& g, int b, int i, int j, TC acc, fl
 }
 
 template <typename TC, typename TB, int TM, int TN, int WGM, int WGN, bool A_KM, bool SYM>
-__global__ __launch_bounds__(NT) void gemm_kernel(GemmDesc g) {
+__global__ __launch_bounds__(NT, 2) void gemm_kernel(GemmDesc g) {
   constexpr int LDA = lds_ld(TM), LDB = lds_ld(TN);
   constexpr int WTM = TM / WGM, WTN = TN / WGN;  // wave tile
   constexpr int BM = WTM / 16, BN = WTN / 16;    // 16x16 blocks per wave
@@ -212,24 +212,30 @@ __global__ __launch_bounds__(NT) void gemm_kernel(GemmDesc g) {
   store_slab(0);
   __syncthreads();
   const int lr = lane & 15, lk = lane >> 4;
-  for (int kt = 0; kt < KT; ++kt) {
-    const int cur = kt & 1;
-    if (kt + 1 < KT) load_slab((kt + 1) * BK);
+  // Two nested loops, so that inside the inner one the accumulators are touched by MFMAs only and
+  // can stay in the accumulation registers; the partial sums are closed between inner loops.
+  constexpr int CHUNK = FLUSH ? 16 : (1 << 30);   // slabs per partial sum (fp32: 256 k)
+  for (int kt0 = 0; kt0 < KT; kt0 += CHUNK) {
+    const int kt1 = (FLUSH && kt0 + CHUNK < KT) ? kt0 + CHUNK : KT;
+    for (int kt = kt0; kt < kt1; ++kt) {
+      const int cur = kt & 1;
+      if (kt + 1 < KT) load_slab((kt + 1) * BK);
 #pragma unroll
-    for (int kk = 0; kk < BK / 4; ++kk) {
-      TC a[BM], bb[BN];
+      for (int kk = 0; kk < BK / 4; ++kk) {
+        TC a[BM], bb[BN];
 #pragma unroll
-      for (int i = 0; i < BM; ++i) a[i] = As[cur][kk * 4 + lk][wm0 + i * 16 + lr];
+        for (int i = 0; i < BM; ++i) a[i] = As[cur][kk * 4 + lk][wm0 + i * 16 + lr];
 #pragma unroll
-      for (int j = 0; j < BN; ++j) bb[j] = Bs[cur][kk * 4 + lk][wn0 + j * 16 + lr];
+        for (int j = 0; j < BN; ++j) bb[j] = Bs[cur][kk * 4 + lk][wn0 + j * 16 + lr];
 #pragma unroll
-      for (int i = 0; i < BM; ++i)
+        for (int i = 0; i < BM; ++i)
 #pragma unroll
-        for (int j = 0; j < BN; ++j) acc[i][j] = mfma(a[i], bb[j], acc[i][j]);
+          for (int j = 0; j < BN; ++j) acc[i][j] = mfma(a[i], bb[j], acc[i][j]);
+      }
+      if (kt + 1 < KT) store_slab(cur ^ 1);
+      __syncthreads();
     }
-    if (kt + 1 < KT) store_slab(cur ^ 1);
-    __syncthreads();
-    if (FLUSH && (kt & 15) == 15) {   // fp32: close a partial sum every 256 k
+    if (FLUSH) {
 #pragma unroll
       for (int i = 0; i < BM; ++i)
 #pragma unroll
@@ -243,7 +249,7 @@ __global__ __launch_bounds__(NT) void gemm_kernel(GemmDesc g) {
 #pragma unroll
     for (int i = 0; i < BM; ++i)
 #pragma unroll
-      for (int j = 0; j < BN; ++j) acc[i][j] += ksum[i][j];
+      for (int j = 0; j < BN; ++j) acc[i][j] = ksum[i][j];
   }
 
   TC part = 0;
