@@ -1,5 +1,5 @@
-"""Full-size parity: the five configurations at their stated sizes, in the launch configuration
-bench.py times.  The oracle is compared on sampled matrices (live for configs 2 and 4; for
+"""Full-size parity: the five configurations and the sign, inverse and DB Newton bench workloads at
+their stated sizes, in the launch configuration bench.py times.  The oracle is compared on sampled matrices (live for configs 2 and 4; for
 configs 3 and 5 through expectations stored by tests/golden/make_full_size_golden.py, which calls
 only the oracle), the remaining matrices are checked through properties that hold at any size.
 """
@@ -163,4 +163,58 @@ def test_c5_sqrt_full(prism):
         s, si = x[b].double(), inv[b].double()
         a = torch.from_numpy(A[b]).cuda().double()
         assert float(torch.linalg.norm(s @ s - a) / torch.linalg.norm(a)) <= 2e-6
+        assert float(torch.linalg.norm(s @ si - eye) / 8192 ** 0.5) <= 2e-5
+
+
+def test_sign_full(prism):
+    """bench.py --workload sign: 8 x 2048^2 symmetric indefinite; two matrices against the oracle,
+    all through S S = I."""
+    A = W.sign_indefinite(n=2048, batch=8, decades=2.0)
+    x = torch.from_numpy(A.copy()).cuda()
+    info = prism.sign(x, 5, 40, 32, SEED, 1e-5).read()
+    assert np.all(info["status"] == prism.INFO_CONVERGED)
+    for b in (0, 5):
+        ref, oinfo = O.sign(A[b], 5, 40, 32, SEED, 1e-5)
+        assert info[b]["iters"] == oinfo["iters"]
+        assert _rel(x[b].cpu().numpy(), ref) <= 1e-5
+    eye = torch.eye(2048, device="cuda", dtype=torch.float64)
+    for b in range(8):
+        s = x[b].double()
+        assert float(torch.linalg.norm(s @ s - eye) / 2048 ** 0.5) <= 5e-5
+        assert float(torch.linalg.norm(s - s.T) / torch.linalg.norm(s)) <= 1e-5
+
+
+def test_inverse_full(prism):
+    """bench.py --workload inverse: 8 x 2048^2 non-symmetric, cond 30."""
+    A = W.inverse_general(n=2048, batch=8, cond=30.0)
+    x = torch.from_numpy(A.copy()).cuda()
+    info = prism.inverse(x, 40, 32, SEED, 1e-5).read()
+    assert np.all(info["status"] == prism.INFO_CONVERGED)
+    for b in (0, 7):
+        ref, oinfo = O.inverse(A[b], 40, 32, SEED, 1e-5)
+        assert info[b]["iters"] == oinfo["iters"]
+        assert _rel(x[b].cpu().numpy(), ref) <= 1e-5
+    eye = torch.eye(2048, device="cuda", dtype=torch.float64)
+    for b in range(8):
+        a = torch.from_numpy(A[b]).cuda().double()
+        assert float(torch.linalg.norm(a @ x[b].double() - eye) / 2048 ** 0.5) <= 5e-5
+
+
+def test_sqrt_newton_full(prism):
+    """bench.py --workload sqrt-newton: PRISM DB Newton on the config-5 inputs (4 x 8192^2)."""
+    A = W.c5_wishart_spd()
+    x = torch.from_numpy(A.copy()).cuda()
+    inv, h = prism.sqrt_newton(x, 12, 1e-5)
+    info = h.read()
+    assert np.all(info["status"] == prism.INFO_CONVERGED)
+    rx, ry, oinfo = O.sqrt_db_newton(A[0], 12, 1e-5)
+    assert info[0]["iters"] == oinfo["iters"]
+    np.testing.assert_allclose(info[0]["alpha"][:oinfo["iters"]], oinfo["alpha"][:oinfo["iters"]], atol=2e-3)
+    assert _rel(x[0].cpu().numpy(), rx) <= 1e-5
+    assert _rel(inv[0].cpu().numpy(), ry) <= 1e-5
+    eye = torch.eye(8192, device="cuda", dtype=torch.float64)
+    for b in range(A.shape[0]):
+        s, si = x[b].double(), inv[b].double()
+        a = torch.from_numpy(A[b]).cuda().double()
+        assert float(torch.linalg.norm(s @ s - a) / torch.linalg.norm(a)) <= 5e-6
         assert float(torch.linalg.norm(s @ si - eye) / 8192 ** 0.5) <= 2e-5
