@@ -36,8 +36,10 @@ def parse():
     ap.add_argument("--no-grouped", dest="grouped", action="store_false",
                     help="c2: four calls on --streams streams per step instead of one prism_run_grouped call (the default, in "
                          "which the library forks to its internal streams)")
-    ap.add_argument("--graph", action="store_true",
-                    help="capture every step's calls in a HIP graph beforehand and time the replays (one stream)")
+    ap.add_argument("--graph", dest="graph", action="store_true", default=None,
+                    help="capture every step's calls in a HIP graph beforehand and time the replays (one stream); "
+                         "the default for c2 with the grouped call")
+    ap.add_argument("--no-graph", dest="graph", action="store_false")
     ap.add_argument("--only-group", type=int, default=-1, help="c2: run a single shape group (profiling aid)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
     ap.add_argument("--no-profile", action="store_true", help="skip the per-kernel event pass")
@@ -209,6 +211,8 @@ def main():
     nsub = max(1, args.sub_batches)
     if args.streams or args.sub_batches > 1 or wl.name != "c2":
         args.grouped = False
+    if args.graph is None:
+        args.graph = bool(args.grouped)
     nstreams = 1 if args.grouped else (args.streams or len(wl.host) * nsub)
     side = [torch.cuda.Stream() for _ in range(nstreams)] if nstreams > 1 else None
 

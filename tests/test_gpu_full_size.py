@@ -67,14 +67,28 @@ def _sampled_rel_err(x, samples, fro, n=4096):
 
 def test_c2_muon_full(prism):
     """64 bf16 matrices, 16 of each shape, plain bf16 iterate, 5 fixed iterations, as one grouped
-    call (the bench launch configuration)."""
+    call replayed from a HIP graph (the bench launch configuration); the eager call must give the
+    same bits."""
     xs, allbits = [], []
     for shape_idx in range(4):
         bits = W.c2_muon_group(shape_idx)
         allbits.append(bits)
         xs.append(_bf16_tensor(bits.copy()))
-    _, handles = prism.run_grouped(prism.FN_POLAR, xs, 5, 5, 16, SEED, 0.0, flags=prism.FLAG_BF16_PLAIN_ITERATE)
+    eager = [x.clone() for x in xs]
+    prism.run_grouped(prism.FN_POLAR, eager, 5, 5, 16, SEED, 0.0, flags=prism.FLAG_BF16_PLAIN_ITERATE)
     torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            _, handles = prism.run_grouped(prism.FN_POLAR, xs, 5, 5, 16, SEED, 0.0, flags=prism.FLAG_BF16_PLAIN_ITERATE)
+        for _ in range(2):
+            for x, bits in zip(xs, allbits):
+                x.copy_(_bf16_tensor(bits.copy()))
+            graph.replay()
+            side.synchronize()
+            for x, e in zip(xs, eager):
+                assert torch.equal(x.view(torch.int16), e.view(torch.int16))
     for shape_idx in range(4):
         bits, x = allbits[shape_idx], xs[shape_idx]
         info = handles[shape_idx].read()

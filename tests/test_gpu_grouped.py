@@ -50,6 +50,34 @@ def test_grouped_polar_equals_single_calls_and_oracle(prism):
     assert _rel(out0, ref) <= 2e-2
 
 
+def test_grouped_call_replays_from_a_hip_graph(prism):
+    """The fork onto the internal streams and the join back are event waits, so a grouped call
+    captures from the caller's stream like a single one: every replay, with eager work and
+    synchronisations in between, must give the bits of the eager call."""
+    bits = [W.c2_muon_group(i, batch=4, scale=4) for i in range(4)]
+    src = [_bf16(b.copy()) for b in bits]
+    eager = [t.clone() for t in src]
+    _, h = prism.run_grouped(prism.FN_POLAR, eager, 5, 5, 16, SEED, 0.0, flags=prism.FLAG_BF16_PLAIN_ITERATE)
+    torch.cuda.synchronize()
+    alpha_eager = [r.read()["alpha"].copy() for r in h]
+    xs = [t.clone() for t in src]
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        prism.run_grouped(prism.FN_POLAR, xs, 5, 5, 16, SEED, 0.0, flags=prism.FLAG_BF16_PLAIN_ITERATE)   # warm-up
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            _, handles = prism.run_grouped(prism.FN_POLAR, xs, 5, 5, 16, SEED, 0.0, flags=prism.FLAG_BF16_PLAIN_ITERATE)
+        for _ in range(3):
+            for x, s0 in zip(xs, src):
+                x.copy_(s0)                                      # eager work between the replays
+            graph.replay()
+            side.synchronize()
+            for g in range(4):
+                assert torch.equal(xs[g].view(torch.int16), eager[g].view(torch.int16)), g
+                assert np.array_equal(handles[g].read()["alpha"], alpha_eager[g])
+
+
 def test_grouped_inverse_root_and_sqrt(prism):
     A1, A2 = W.c4_shampoo_spd(n=128, batch=2), W.c4_shampoo_spd(n=200, batch=3, data_seed=77)
     xs = [torch.from_numpy(A1.copy()).cuda(), torch.from_numpy(A2.copy()).cuda()]
