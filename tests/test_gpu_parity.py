@@ -100,6 +100,27 @@ def test_c2_muon_bf16_reduced(prism, shape_idx, plain):
         assert info[i]["residual"][5] == -1.0
 
 
+@pytest.mark.parametrize("degree", [3, 5])
+@pytest.mark.parametrize("shape", [(200, 72), (72, 200), (130, 129), (300, 300), (1, 40), (257, 64)])
+def test_polar_bf16_ragged_shapes(prism, degree, shape):
+    """Sizes that are not tile multiples, wide and tall, down to a single row: the padded internal
+    layouts of the bf16 path (both tile sizes share them) must not leak into the result."""
+    m, n = shape
+    A = np.concatenate([W.c1_polar_small(m=m, n=n, data_seed=1200 + i) for i in range(2)]) if min(m, n) > 1 else \
+        np.random.Generator(np.random.PCG64(5)).standard_normal((2, m, n)).astype(np.float32)
+    bits = W.to_bf16_bits(A)
+    for flags in (0, prism.FLAG_BF16_PLAIN_ITERATE):
+        x = _bf16_tensor(bits.copy())
+        info = prism.polar(x, degree, 40, 8, SEED, 1e-2, flags=flags).read()
+        out = _bf16_to_f64(x)
+        for i in range(2):
+            ref, oinfo = O.polar(W.from_bf16_bits(bits[i]), degree, 40, 8, SEED, 1e-2)
+            assert oinfo["status"] == O.STATUS_CONVERGED
+            assert info[i]["status"] == prism.INFO_CONVERGED
+            assert abs(int(info[i]["iters"]) - oinfo["iters"]) <= 1      # bf16 residual near tol
+            assert _rel(out[i], ref) <= TOL_BF16
+
+
 # ------------------------------------------------------------------ config 3 (reduced)
 
 def test_c3_polar_bf16_reduced(prism):
