@@ -213,6 +213,11 @@ int prism_gauss_parts(uint32_t first, uint32_t count, double* radius, double* co
  * V[batch][n][ld], fp32 device arrays, n a multiple of 64, ld = 16, 32 or 64. */
 int prism_chain_product(const float* R, const float* V, float* out, int batch, int n, int ld,
                         void* stream);
+/* The same product as the bf16 polar path takes it: the off-diagonal entries of R are read from
+ * Rb, its copy in bf16 bit patterns (same shape), the diagonal from R itself:
+ * out = (Rb + diag(R - Rb)) * V.  Ld = 16 or 32 in that path; 64 is accepted too. */
+int prism_chain_product_bf16(const uint16_t* Rb, const float* R, const float* V, float* out, int batch,
+                             int n, int ld, void* stream);
 
 /* Inverse of symmetric positive definite matrices by block Gauss-Jordan elimination without
  * pivoting (the N_k = M_k^{-1} step of DB Newton, App. A.2): out[batch][n][n] = a^{-1}, fp32

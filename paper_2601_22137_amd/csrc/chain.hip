@@ -11,7 +11,15 @@
 //   four k of one instruction is free as long as both operands agree).
 //   V chunk in LDS: Vs[64][LD + 4]; with that stride the four lane groups of a fragment read
 //   (rows 4 apart) fall on disjoint bank halves.
-//   The loads of R run five chunks ahead of the MFMAs (the kernel is latency bound otherwise).
+//   The loads of R and V run five chunks ahead of the MFMAs (the kernel is latency bound otherwise).
+//
+// RB variants (bf16 polar path): R is read from its bf16 copy, half the bytes.  The diagonal of R is
+// taken from the fp32 matrix all the same: early on it is 1 - g_ii with g_ii ~ 1/n, which rounds
+// to 1 in bf16 and would erase the factor (1 - xi) of the fit objective (Section 4.2), whereas
+// rounding the off-diagonal entries perturbs the fitted coefficient by ~1e-5 only.  The kernel
+// multiplies by the bf16 matrix and adds (r_ii - bf16(r_ii)) v_i afterwards.
+#include <type_traits>
+
 #include "common.h"
 
 namespace prism {
@@ -22,59 +30,137 @@ constexpr int NT = 256;
 constexpr int KC = 64;     // k per chunk
 constexpr int ROWS = 64;   // rows of R per workgroup
 
-template <int LD>
-__global__ __launch_bounds__(NT, 2) void chain_kernel(const float* __restrict__ R, long long strideR, int ldr,
+typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
+
+// Four consecutive k of one row of R: fp32 as they are, bf16 widened in registers.
+template <bool RB> struct RFrag;
+template <> struct RFrag<false> {
+  typedef float elem;
+  f32x4 v;
+  __device__ void load(const float* p) { v = *(const f32x4*)p; }
+  __device__ float get(int e) const { return v[e]; }
+};
+template <> struct RFrag<true> {
+  typedef unsigned short elem;
+  u32x2 v;
+  __device__ void load(const unsigned short* p) { v = *(const u32x2*)p; }
+  __device__ float get(int e) const {
+    const unsigned w = v[e >> 1];
+    return __uint_as_float((e & 1) ? (w & 0xFFFF0000u) : (w << 16));
+  }
+};
+
+__device__ inline float bf16_bits_to_float(unsigned short h) { return __uint_as_float((unsigned)h << 16); }
+
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+
+// The rows of R as the large kernel fetches them, 16 bytes per lane and load: four fp32, or eight
+// bf16 widened in registers.
+template <bool RB> struct RFrag16;
+template <> struct RFrag16<false> {
+  static constexpr int K = 4;
+  f32x4 v;
+  __device__ void load(const float* p) { v = *(const f32x4*)p; }
+  __device__ float get(int e) const { return v[e]; }
+};
+template <> struct RFrag16<true> {
+  static constexpr int K = 8;
+  u32x4 v;
+  __device__ void load(const unsigned short* p) { v = *(const u32x4*)p; }
+  __device__ float get(int e) const {
+    const unsigned w = v[e >> 1];
+    return __uint_as_float((e & 1) ? (w & 0xFFFF0000u) : (w << 16));
+  }
+};
+
+template <int D, typename F>
+__device__ inline void unrolled(F&& f) {
+  if constexpr (D > 0) {
+    unrolled<D - 1>(f);
+    f(std::integral_constant<int, D - 1>{});
+  }
+}
+
+// Chunk geometry of the large kernel.  A lane fetches EK consecutive k per load (4 fp32 or 8 bf16,
+// 16 bytes either way), four loads per chunk: k = 4 EK s + EK q + e for load s, lane group q,
+// element e.  MFMA (s, e) takes one k from each lane group, so the four rows of V it reads should
+// lie 4 apart in LDS (conflict-free with the row stride LD + 4): row 16 s + 4 q + e for fp32;
+// for bf16 the chunk row k is stored at row 32 s + 16 (e >> 2) + 4 q + (e & 3).
+template <bool RB> __device__ inline int v_lds_row(int s, int q, int e) {
+  return RB ? 32 * s + 16 * (e >> 2) + 4 * q + (e & 3) : 16 * s + 4 * q + e;
+}
+
+template <int LD, bool RB>
+__global__ __launch_bounds__(NT, 2) void chain_kernel(const typename RFrag<RB>::elem* __restrict__ R, long long strideR, int ldr,
+                                                   const float* __restrict__ R32, long long strideR32, int ldr32,
                                                    const float* __restrict__ Vin, long long strideVin,
                                                    float* __restrict__ Vout, long long strideVout, int n,
                                                    const Ctrl* __restrict__ ctrl) {
   constexpr int NBLK = LD / 16;
   constexpr int VS = LD + 4;
-  __shared__ float Vs[2][KC][VS];
+  constexpr int EK = RFrag16<RB>::K;   // k per load
+  constexpr int KCH = 16 * EK;         // k per chunk: 64 (fp32) or 128 (bf16)
+  __shared__ __align__(16) float Vs[2][KCH][VS];
   const int b = blockIdx.y;
   if (ctrl && ctrl[b].done) return;
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
   const int li = lane & 15, lq = lane >> 4;
   const int row0 = blockIdx.x * ROWS + wave * 16;
-  const float* Rrow = R + (long long)b * strideR + (long long)(row0 + li) * ldr + 4 * lq;
+  const typename RFrag<RB>::elem* Rrow = R + (long long)b * strideR + (long long)(row0 + li) * ldr + EK * lq;
   const float* Vb = Vin + (long long)b * strideVin;
 
-  // V chunk loader: KC x LD floats = KC * LD / 4 float4, spread over the workgroup
-  constexpr int V_LOADS = KC * LD / 4;
+  // Loads return in order, so waiting for one drains every older one.  The chunk of V that is
+  // staged in LDS next is therefore requested DEPTH-1 chunks ahead as well, just before the rows
+  // of R of the same chunk: when the wave waits for it, the rows of the DEPTH-2 chunks behind it
+  // stay in flight (requested one chunk ahead only, that wait emptied the whole ring every chunk).
+  constexpr int DEPTH = (LD == 64 || RB) ? 4 : 6;
+  // V chunk loader: KCH x LD floats = KCH * LD / 4 float4, spread over the workgroup
+  constexpr int V_LOADS = KCH * LD / 4;
   constexpr int V_IT = (V_LOADS + NT - 1) / NT;
-  f32x4 vreg[V_IT];
-  auto load_v = [&](int k0) {
+  f32x4 vreg[DEPTH][V_IT];
+  RFrag16<RB> ra[DEPTH][4];
+  const int nchunks = n / KCH;
+  // Past the end the last chunk is fetched again (and never used): no branch around the loads, so
+  // that the compiler can count how many younger loads may stay in flight at each wait.  (With the
+  // loads under a condition it had to assume none were issued and waited for all of them.)
+  // The workgroups of one matrix all read the same V; each starts its sweep over k at a chunk of
+  // its own, so that at any moment they ask different L2 channels for it.
+  const int rot = (int)(blockIdx.x % (unsigned)nchunks);
+  auto load_chunk = [&](int slot, int c_want) {   // slot is a compile-time constant at every call site
+    int c = (c_want < nchunks ? c_want : nchunks - 1) + rot;
+    if (c >= nchunks) c -= nchunks;
 #pragma unroll
     for (int it = 0; it < V_IT; ++it) {
       const int idx = t + it * NT;
       if (V_LOADS % NT == 0 || idx < V_LOADS) {
         const int kr = idx / (LD / 4), c4 = idx % (LD / 4);
-        vreg[it] = *(const f32x4*)(Vb + (long long)(k0 + kr) * LD + c4 * 4);
+        vreg[slot][it] = *(const f32x4*)(Vb + (long long)(c * KCH + kr) * LD + c4 * 4);
       }
     }
+#pragma unroll
+    for (int s = 0; s < 4; ++s) ra[slot][s].load(Rrow + c * KCH + 4 * EK * s);
   };
-  auto store_v = [&](int buf) {
+  auto store_v = [&](int slot, int buf) {
 #pragma unroll
     for (int it = 0; it < V_IT; ++it) {
       const int idx = t + it * NT;
       if (V_LOADS % NT == 0 || idx < V_LOADS) {
         const int kr = idx / (LD / 4), c4 = idx % (LD / 4);
-        *(f32x4*)&Vs[buf][kr][c4 * 4] = vreg[it];
+        const int row = v_lds_row<RB>(kr / (4 * EK), (kr / EK) & 3, kr % EK);
+        *(f32x4*)&Vs[buf][row][c4 * 4] = vreg[slot][it];
       }
-    }
-  };
-  constexpr int DEPTH = 6;   // ring of chunks of this lane's row of R: loads run DEPTH-1 chunks ahead
-  f32x4 ra[DEPTH][4];
-  const int nchunks = n / KC;
-  auto load_r = [&](int slot, int c) {   // slot is a compile-time constant at every call site
-    if (c < nchunks) {
-#pragma unroll
-      for (int s = 0; s < 4; ++s) ra[slot][s] = *(const f32x4*)(Rrow + c * KC + 16 * s);
     }
   };
 
-  f32x4 acc[NBLK];
+  // Eight independent accumulators per wave (k taken round-robin), added up at the end: an MFMA
+  // that accumulates into the result of the one before it waits out the whole pipeline latency,
+  // and one or two chains of such MFMAs kept the matrix cores half idle.
+  constexpr int NACC = 8 / NBLK;
+  f32x4 acc[NBLK][NACC];
 #pragma unroll
-  for (int j = 0; j < NBLK; ++j) acc[j] = (f32x4){0.f, 0.f, 0.f, 0.f};
+  for (int j = 0; j < NBLK; ++j)
+#pragma unroll
+    for (int u = 0; u < NACC; ++u) acc[j][u] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
   // Workgroup barrier without the release fence of __syncthreads(): that fence waits for every
   // outstanding load and would expose the memory latency of the prefetched rows of R at every
@@ -84,38 +170,70 @@ __global__ __launch_bounds__(NT, 2) void chain_kernel(const float* __restrict__ 
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
   };
-  load_v(0);
 #pragma unroll
-  for (int d = 0; d < DEPTH - 1; ++d) load_r(d, d);
-  store_v(0);
+  for (int d = 0; d < DEPTH - 1; ++d) load_chunk(d, d);
+  store_v(0, 0);
   lds_barrier();
-  for (int c0 = 0; c0 < nchunks; c0 += DEPTH) {
+  auto step = [&](auto dtag, int c) {   // chunk c, whose rows sit in ring slot d = c % DEPTH
+    constexpr int d = decltype(dtag)::value;
+    const int cur = c & 1;
+    load_chunk((d + DEPTH - 1) % DEPTH, c + DEPTH - 1);
+    // The fragments of V are read from LDS one load step ahead of the MFMAs that use them (left
+    // to itself the compiler reads each pair right before its two MFMAs and waits every time).
+    float vf[2][EK][NBLK];
+    auto read_v = [&](int s) {
 #pragma unroll
-    for (int d = 0; d < DEPTH; ++d) {
-      const int c = c0 + d;
-      if (c < nchunks) {          // uniform
-        const int cur = c & 1;
-        // the small V chunk is requested before the rows of R further ahead, so that waiting for
-        // it (to stage it in LDS) leaves those rows in flight
-        if (c + 1 < nchunks) load_v((c + 1) * KC);
-        load_r((d + DEPTH - 1) % DEPTH, c + DEPTH - 1);
+      for (int e = 0; e < EK; ++e)
 #pragma unroll
-        for (int s = 0; s < 4; ++s)
+        for (int j = 0; j < NBLK; ++j) vf[s & 1][e][j] = Vs[cur][v_lds_row<RB>(s, lq, e)][j * 16 + li];
+    };
+    read_v(0);
 #pragma unroll
-          for (int e = 0; e < 4; ++e)
+    for (int s = 0; s < 4; ++s) {
+      __builtin_amdgcn_sched_barrier(0);
+      if (s + 1 < 4) read_v(s + 1);
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int j = 0; j < NBLK; ++j)
-              acc[j] = __builtin_amdgcn_mfma_f32_16x16x4f32(ra[d][s][e], Vs[cur][16 * s + 4 * lq + e][j * 16 + li], acc[j], 0, 0, 0);
-        if (c + 1 < nchunks) store_v(cur ^ 1);
-        lds_barrier();
-      }
+      for (int e = 0; e < EK; ++e)
+#pragma unroll
+        for (int j = 0; j < NBLK; ++j)
+          acc[j][(s * EK + e) % NACC] = __builtin_amdgcn_mfma_f32_16x16x4f32(ra[d][s].get(e), vf[s & 1][e][j], acc[j][(s * EK + e) % NACC], 0, 0, 0);
     }
+    store_v((d + 1) % DEPTH, cur ^ 1);   // chunk c + 1 (past the end: the last one again, unused)
+    lds_barrier();
+  };
+  const int nfull = nchunks / DEPTH * DEPTH;
+  for (int c0 = 0; c0 < nfull; c0 += DEPTH)
+    unrolled<DEPTH>([&](auto dt) { step(dt, c0 + decltype(dt)::value); });
+  // the last nchunks % DEPTH chunks
+  unrolled<DEPTH - 1>([&](auto dt) {
+    if (nfull + decltype(dt)::value < nchunks) step(dt, nfull + decltype(dt)::value);
+  });
+  float dfix[4] = {0.f, 0.f, 0.f, 0.f};   // exact diagonal minus the rounded one, rows of this lane
+  if constexpr (RB) {
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const int row = row0 + 4 * lq + r;
+      dfix[r] = R32[(long long)b * strideR32 + (long long)row * ldr32 + row] -
+                bf16_bits_to_float((unsigned short)R[(long long)b * strideR + (long long)row * ldr + row]);
+    }
+  }
+#pragma unroll
+  for (int j = 0; j < NBLK; ++j) {
+#pragma unroll
+    for (int w = NACC / 2; w > 0; w >>= 1)      // fixed pairwise order
+#pragma unroll
+      for (int u = 0; u < w; ++u) acc[j][u] += acc[j][u + w];
   }
 #pragma unroll
   for (int j = 0; j < NBLK; ++j)
 #pragma unroll
-    for (int r = 0; r < 4; ++r)
-      Vout[(long long)b * strideVout + (long long)(row0 + 4 * lq + r) * LD + j * 16 + li] = acc[j][r];
+    for (int r = 0; r < 4; ++r) {
+      const int row = row0 + 4 * lq + r, col = j * 16 + li;
+      float v = acc[j][0][r];
+      if constexpr (RB) v += dfix[r] * Vb[(long long)row * LD + col];
+      Vout[(long long)b * strideVout + (long long)row * LD + col] = v;
+    }
 }
 
 // Variant for small matrices (n <= 2048), where the kernel above is latency bound for lack of
@@ -123,8 +241,9 @@ __global__ __launch_bounds__(NT, 2) void chain_kernel(const float* __restrict__ 
 // (wave w takes the chunks c = w, w+4, ...), each staging its own chunks of V in a private LDS
 // area (no workgroup barrier inside the loop); the four partial sums are added through LDS in a
 // fixed order at the end.
-template <int LD>
-__global__ __launch_bounds__(NT, 2) void chain_small_kernel(const float* __restrict__ R, long long strideR, int ldr,
+template <int LD, bool RB>
+__global__ __launch_bounds__(NT, 2) void chain_small_kernel(const typename RFrag<RB>::elem* __restrict__ R, long long strideR, int ldr,
+                                                         const float* __restrict__ R32, long long strideR32, int ldr32,
                                                          const float* __restrict__ Vin, long long strideVin,
                                                          float* __restrict__ Vout, long long strideVout, int n,
                                                          const Ctrl* __restrict__ ctrl) {
@@ -138,18 +257,19 @@ __global__ __launch_bounds__(NT, 2) void chain_small_kernel(const float* __restr
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
   const int li = lane & 15, lq = lane >> 4;
   const int row0 = blockIdx.x * 16;
-  const float* Rrow = R + (long long)b * strideR + (long long)(row0 + li) * ldr + 4 * lq;
+  const typename RFrag<RB>::elem* Rrow = R + (long long)b * strideR + (long long)(row0 + li) * ldr + 4 * lq;
   const float* Vb = Vin + (long long)b * strideVin;
   const int nchunks = n / KC;
   const int mine = (nchunks - wave + 3) / 4;     // chunks of this wave
 
   constexpr int DEPTH = 3;
-  f32x4 ra[DEPTH][4], va[DEPTH][VL];
+  RFrag<RB> ra[DEPTH][4];
+  f32x4 va[DEPTH][VL];
   auto load = [&](int slot, int i) {             // i-th chunk of this wave; slot is compile time
     if (i < mine) {
       const int c = wave + 4 * i;
 #pragma unroll
-      for (int s = 0; s < 4; ++s) ra[slot][s] = *(const f32x4*)(Rrow + c * KC + 16 * s);
+      for (int s = 0; s < 4; ++s) ra[slot][s].load(Rrow + c * KC + 16 * s);
 #pragma unroll
       for (int v = 0; v < VL; ++v) {
         const int idx = lane + 64 * v;
@@ -157,9 +277,12 @@ __global__ __launch_bounds__(NT, 2) void chain_small_kernel(const float* __restr
       }
     }
   };
-  f32x4 acc[NBLK];
+  constexpr int NACC = 8 / NBLK;   // independent accumulators, as in the kernel above
+  f32x4 acc[NBLK][NACC];
 #pragma unroll
-  for (int j = 0; j < NBLK; ++j) acc[j] = (f32x4){0.f, 0.f, 0.f, 0.f};
+  for (int j = 0; j < NBLK; ++j)
+#pragma unroll
+    for (int u = 0; u < NACC; ++u) acc[j][u] = (f32x4){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
   for (int d = 0; d < DEPTH - 1; ++d) load(d, d);
   for (int i0 = 0; i0 < mine; i0 += DEPTH) {
@@ -181,24 +304,60 @@ __global__ __launch_bounds__(NT, 2) void chain_small_kernel(const float* __restr
           for (int e = 0; e < 4; ++e)
 #pragma unroll
             for (int j = 0; j < NBLK; ++j)
-              acc[j] = __builtin_amdgcn_mfma_f32_16x16x4f32(ra[d][s][e], Vs[wave][buf][16 * s + 4 * lq + e][j * 16 + li], acc[j], 0, 0, 0);
+              acc[j][(4 * s + e) % NACC] = __builtin_amdgcn_mfma_f32_16x16x4f32(ra[d][s].get(e), Vs[wave][buf][16 * s + 4 * lq + e][j * 16 + li], acc[j][(4 * s + e) % NACC], 0, 0, 0);
       }
     }
   }
 #pragma unroll
+  for (int j = 0; j < NBLK; ++j) {
+#pragma unroll
+    for (int w = NACC / 2; w > 0; w >>= 1)
+#pragma unroll
+      for (int u = 0; u < w; ++u) acc[j][u] += acc[j][u + w];
+  }
+#pragma unroll
   for (int j = 0; j < NBLK; ++j)
 #pragma unroll
-    for (int r = 0; r < 4; ++r) red[wave][j][r][lane] = acc[j][r];
+    for (int r = 0; r < 4; ++r) red[wave][j][r][lane] = acc[j][0][r];
   __syncthreads();
   if (wave == 0) {
 #pragma unroll
     for (int j = 0; j < NBLK; ++j)
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
-        const float v = (red[0][j][r][lane] + red[1][j][r][lane]) + (red[2][j][r][lane] + red[3][j][r][lane]);
-        Vout[(long long)b * strideVout + (long long)(row0 + 4 * lq + r) * LD + j * 16 + li] = v;
+        float v = (red[0][j][r][lane] + red[1][j][r][lane]) + (red[2][j][r][lane] + red[3][j][r][lane]);
+        const int row = row0 + 4 * lq + r, col = j * 16 + li;
+        if constexpr (RB) {   // exact diagonal minus the rounded one
+          const float dfix = R32[(long long)b * strideR32 + (long long)row * ldr32 + row] -
+                             bf16_bits_to_float((unsigned short)R[(long long)b * strideR + (long long)row * ldr + row]);
+          v += dfix * Vb[(long long)row * LD + col];
+        }
+        Vout[(long long)b * strideVout + (long long)row * LD + col] = v;
       }
   }
+}
+
+template <bool RB>
+int launch_chain_t(const typename RFrag<RB>::elem* R, long long strideR, int ldr, const float* R32, long long strideR32,
+                   int ldr32, const float* Vin, long long strideVin, float* Vout, long long strideVout, int n, int ld,
+                   int batch, const Ctrl* ctrl, hipStream_t s) {
+  if (n % KC || n % ROWS || ldr % 4 || batch <= 0) return PRISM_EINVAL;
+  // 64-row workgroups leave most CUs idle on small batches of small matrices: 16-row ones there
+  if (ld <= 32 && (long long)(n / ROWS) * batch < 256) {
+    const dim3 grid(n / 16, batch), block(NT);
+    if (ld == 16) hipLaunchKernelGGL((chain_small_kernel<16, RB>), grid, block, 0, s, R, strideR, ldr, R32, strideR32, ldr32, Vin, strideVin, Vout, strideVout, n, ctrl);
+    else hipLaunchKernelGGL((chain_small_kernel<32, RB>), grid, block, 0, s, R, strideR, ldr, R32, strideR32, ldr32, Vin, strideVin, Vout, strideVout, n, ctrl);
+    return hipGetLastError() == hipSuccess ? PRISM_OK : PRISM_EHIP;
+  }
+  const dim3 grid(n / ROWS, batch), block(NT);
+  if (RB && (n % 128 || ldr % 8)) return PRISM_EINVAL;   // the bf16 kernel takes K in chunks of 128, rows in 16-byte loads
+  if (ld == 16) hipLaunchKernelGGL((chain_kernel<16, RB>), grid, block, 0, s, R, strideR, ldr, R32, strideR32, ldr32, Vin, strideVin, Vout, strideVout, n, ctrl);
+  else if (ld == 32) hipLaunchKernelGGL((chain_kernel<32, RB>), grid, block, 0, s, R, strideR, ldr, R32, strideR32, ldr32, Vin, strideVin, Vout, strideVout, n, ctrl);
+  else if (ld == 64) {
+    if constexpr (!RB) hipLaunchKernelGGL((chain_kernel<64, false>), grid, block, 0, s, R, strideR, ldr, R32, strideR32, ldr32, Vin, strideVin, Vout, strideVout, n, ctrl);
+    else return PRISM_EINVAL;
+  } else return PRISM_EINVAL;
+  return hipGetLastError() == hipSuccess ? PRISM_OK : PRISM_EHIP;
 }
 
 }  // namespace
@@ -206,20 +365,19 @@ __global__ __launch_bounds__(NT, 2) void chain_small_kernel(const float* __restr
 // R: [batch][n][ldr] fp32 (n a multiple of 64), Vin/Vout: [n][ld] per matrix (strideVin may be 0)
 int launch_chain(const float* R, long long strideR, int ldr, const float* Vin, long long strideVin, float* Vout,
                  long long strideVout, int n, int ld, int batch, const Ctrl* ctrl, hipStream_t s) {
-  if (n % KC || n % ROWS || ldr % 4 || batch <= 0) return PRISM_EINVAL;
-  // 64-row workgroups leave most CUs idle on small batches of small matrices: 16-row ones there
-  if (ld <= 32 && (long long)(n / ROWS) * batch < 256) {
-    const dim3 grid(n / 16, batch), block(NT);
-    if (ld == 16) hipLaunchKernelGGL(chain_small_kernel<16>, grid, block, 0, s, R, strideR, ldr, Vin, strideVin, Vout, strideVout, n, ctrl);
-    else hipLaunchKernelGGL(chain_small_kernel<32>, grid, block, 0, s, R, strideR, ldr, Vin, strideVin, Vout, strideVout, n, ctrl);
-    return hipGetLastError() == hipSuccess ? PRISM_OK : PRISM_EHIP;
-  }
-  const dim3 grid(n / ROWS, batch), block(NT);
-  if (ld == 16) hipLaunchKernelGGL(chain_kernel<16>, grid, block, 0, s, R, strideR, ldr, Vin, strideVin, Vout, strideVout, n, ctrl);
-  else if (ld == 32) hipLaunchKernelGGL(chain_kernel<32>, grid, block, 0, s, R, strideR, ldr, Vin, strideVin, Vout, strideVout, n, ctrl);
-  else if (ld == 64) hipLaunchKernelGGL(chain_kernel<64>, grid, block, 0, s, R, strideR, ldr, Vin, strideVin, Vout, strideVout, n, ctrl);
-  else return PRISM_EINVAL;
-  return hipGetLastError() == hipSuccess ? PRISM_OK : PRISM_EHIP;
+  return launch_chain_t<false>(R, strideR, ldr, nullptr, 0, 0, Vin, strideVin, Vout, strideVout, n, ld, batch, ctrl, s);
+}
+
+// Same product with R read from its bf16 copy Rb (same shape and strides) and the diagonal from R
+int launch_chain_bf16(const unsigned short* Rb, const float* R, long long strideR, int ldr, const float* Vin,
+                      long long strideVin, float* Vout, long long strideVout, int n, int ld, int batch, const Ctrl* ctrl,
+                      hipStream_t s) {
+  if (!Rb || !R) return PRISM_EINVAL;
+  // widest sketches and sizes that are no multiple of 128: the fp32 matrix
+  const bool small = ld <= 32 && (long long)(n / ROWS) * batch < 256;
+  if (ld == 64 || ldr % 8 || (!small && n % 128))
+    return launch_chain_t<false>(R, strideR, ldr, nullptr, 0, 0, Vin, strideVin, Vout, strideVout, n, ld, batch, ctrl, s);
+  return launch_chain_t<true>(Rb, strideR, ldr, R, strideR, ldr, Vin, strideVin, Vout, strideVout, n, ld, batch, ctrl, s);
 }
 
 }  // namespace prism

@@ -105,6 +105,9 @@ void launch_gauss_parts(uint32_t first, uint32_t count, double* r, double* c, do
 // ---- chain.hip : V_out = R V_in for the sketch chain (HBM bound; R read once, straight into registers) ----
 int launch_chain(const float* R, long long strideR, int ldr, const float* Vin, long long strideVin, float* Vout,
                  long long strideVout, int n, int ld, int batch, const Ctrl* ctrl, hipStream_t s);
+int launch_chain_bf16(const unsigned short* Rb, const float* R, long long strideR, int ldr, const float* Vin,
+                      long long strideVin, float* Vout, long long strideVout, int n, int ld, int batch, const Ctrl* ctrl,
+                      hipStream_t s);
 
 // ---- fit.hip ----
 struct SolveArgs {

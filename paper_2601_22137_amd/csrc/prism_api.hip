@@ -203,15 +203,20 @@ struct Run {
   template <typename T> T* at(size_t off) const { return (T*)(ws + off); }
 
   // sketch + chain V_j = R V_{j-1} (fp32 matrix cores, skinny N = padded sketch width)
-  int chain(const float* R, int k) {
+  // Rb: bf16 copy of R (bf16 polar path): the products then read it instead of R, except the diagonal
+  int chain(const float* R, int k, const uint16_t* Rb = nullptr) {
     const int Sp = P.Sp, ld = P.ld;
     const long long vs = (long long)P.batch * Sp * ld;
     for (int j = 1; j <= P.nv; ++j) {
       const float* vin = (j == 1) ? v0 + (long long)(k - first_fit) * Sp * ld : v + (j - 2) * vs;
       const long long sin = (j == 1) ? 0 : (long long)Sp * ld;
       ProfScope ps(PK_CHAIN, s);
-      CHECK_LAUNCH(launch_chain(R, (long long)Sp * Sp, Sp, vin, sin, v + (j - 1) * vs, (long long)Sp * ld, Sp, ld,
-                                P.batch, ctrl, s));
+      if (Rb)
+        CHECK_LAUNCH(launch_chain_bf16(Rb, R, (long long)Sp * Sp, Sp, vin, sin, v + (j - 1) * vs, (long long)Sp * ld, Sp,
+                                       ld, P.batch, ctrl, s));
+      else
+        CHECK_LAUNCH(launch_chain(R, (long long)Sp * Sp, Sp, vin, sin, v + (j - 1) * vs, (long long)Sp * ld, Sp, ld,
+                                  P.batch, ctrl, s));
     }
     return PRISM_OK;
   }
@@ -323,6 +328,7 @@ int run_polar_bf16(Run& r) {
   uint16_t* Qb = P.d == 2 ? r.at<uint16_t>(P.o_qb) : nullptr;
   static const int keep_split = getenv("PRISM_BF16_KEEP_SPLIT") ? atoi(getenv("PRISM_BF16_KEEP_SPLIT")) : 0;
   static const int no_dual = getenv("PRISM_BF16_NO_DUAL") ? atoi(getenv("PRISM_BF16_NO_DUAL")) : 0;
+  static const int chain_f32 = getenv("PRISM_BF16_CHAIN_F32") ? atoi(getenv("PRISM_BF16_CHAIN_F32")) : 0;
   const int ntg = Sp / Tg;
   const int nparts = sym ? ntg * (ntg + 1) / 2 : ntg * ntg;
   int cur = 0;
@@ -335,7 +341,7 @@ int run_polar_bf16(Run& r) {
     g.C32 = R; g.strideC32 = SS; g.ldc32 = Sp; g.Cb = Rb; g.strideCb = SS; g.ldcb = Sp;
     g.rho_part = r.rho; g.ctrl = r.ctrl;
     { ProfScope ps(PK_BF16_GRAM, r.s); CHECK_LAUNCH(launch_gemm_bf16(g, Tg, r.s)); }
-    if (r.fit_needed(k)) CHECK_LAUNCH(r.chain(R, k));
+    if (r.fit_needed(k)) CHECK_LAUNCH(r.chain(R, k, chain_f32 ? nullptr : Rb));
     CHECK_LAUNCH(r.solve(k, nparts));
     if (k == r.max_iters) break;
     const uint16_t* Bop = Rb;
@@ -830,6 +836,14 @@ int prism_chain_product(const float* R, const float* V, float* out, int batch, i
   if (!R || !V || !out || batch <= 0 || n <= 0) return PRISM_EINVAL;
   return launch_chain(R, (long long)n * n, n, V, (long long)n * ld, out, (long long)n * ld, n, ld, batch, nullptr,
                       (hipStream_t)stream);
+}
+
+int prism_chain_product_bf16(const uint16_t* Rb, const float* R, const float* V, float* out, int batch, int n, int ld,
+                             void* stream) {
+  set_last_error("");
+  if (!Rb || !R || !V || !out) return PRISM_EINVAL;
+  return launch_chain_bf16(Rb, R, (long long)n * n, n, V, (long long)n * ld, out, (long long)n * ld, n, ld, batch, nullptr,
+                           (hipStream_t)stream);
 }
 
 int prism_gemm_f32(const float* A, const float* B, float* C, int batch, int M, int N, int K, int a_km, void* stream) {

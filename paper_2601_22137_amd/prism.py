@@ -24,7 +24,7 @@ INFO_DTYPE = np.dtype([("iters", np.int32), ("status", np.int32),
 
 EXPORTS = ("prism_workspace_bytes", "prism_polar", "prism_polar_ex", "prism_sqrt", "prism_sqrt_ex",
            "prism_inv_root", "prism_inv_root_ex", "prism_sign", "prism_sign_ex", "prism_inverse", "prism_inverse_ex", "prism_sqrt_newton", "prism_sqrt_newton_ex", "prism_spd_inverse", "prism_run_grouped",
-           "prism_sketch", "prism_gauss_parts", "prism_chain_product", "prism_gemm_f32",
+           "prism_sketch", "prism_gauss_parts", "prism_chain_product", "prism_chain_product_bf16", "prism_gemm_f32",
            "prism_gemm_f64a", "prism_gemm_bf16_nt", "prism_profile_enable", "prism_profile_collect",
            "prism_last_error")
 
@@ -77,6 +77,7 @@ def lib():
         L.prism_sketch.argtypes = [vp, i, i, u64, i, i, vp]
         L.prism_gauss_parts.argtypes = [ctypes.c_uint32, ctypes.c_uint32, vp, vp, vp, vp]
         L.prism_chain_product.argtypes = [vp, vp, vp, i, i, i, vp]
+        L.prism_chain_product_bf16.argtypes = [vp, vp, vp, vp, i, i, i, vp]
         L.prism_gemm_f32.argtypes = [vp, vp, vp, i, i, i, i, i, vp]
         L.prism_gemm_f64a.argtypes = [vp, vp, vp, i, i, i, i, vp]
         L.prism_gemm_bf16_nt.argtypes = [vp, vp, vp, i, i, i, i, i, vp]
@@ -258,6 +259,13 @@ def chain_product(R, V):
     batch, n, ld = V.shape
     out = torch.empty_like(V)
     _check(lib().prism_chain_product(R.data_ptr(), V.data_ptr(), out.data_ptr(), batch, n, ld, _stream()))
+    return out
+
+
+def chain_product_bf16(Rb, R, V):
+    batch, n, ld = V.shape
+    out = torch.empty_like(V)
+    _check(lib().prism_chain_product_bf16(Rb.data_ptr(), R.data_ptr(), V.data_ptr(), out.data_ptr(), batch, n, ld, _stream()))
     return out
 
 
