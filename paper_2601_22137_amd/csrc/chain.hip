@@ -13,11 +13,15 @@
 //   (rows 4 apart) fall on disjoint bank halves.
 //   The loads of R and V run five chunks ahead of the MFMAs (the kernel is latency bound otherwise).
 //
-// RB variants (bf16 polar path): R is read from its bf16 copy, half the bytes.  The diagonal of R is
+// Three kernels: chain_kernel (64-row workgroups, fp32 R), chain_small_kernel (16-row workgroups
+// for small batches of small matrices, fp32 or bf16 R) and chain_bf16_kernel (64-row workgroups,
+// bf16 R, bf16 matrix cores).
+//
+// bf16 R (bf16 polar path): R is read from its bf16 copy, half the bytes.  The diagonal of R is
 // taken from the fp32 matrix all the same: early on it is 1 - g_ii with g_ii ~ 1/n, which rounds
 // to 1 in bf16 and would erase the factor (1 - xi) of the fit objective (Section 4.2), whereas
-// rounding the off-diagonal entries perturbs the fitted coefficient by ~1e-5 only.  The kernel
-// multiplies by the bf16 matrix and adds (r_ii - bf16(r_ii)) v_i afterwards.
+// rounding the off-diagonal entries perturbs the fitted coefficient by ~1e-5 only.  The kernels
+// multiply by the bf16 matrix and add (r_ii - bf16(r_ii)) v_i afterwards.
 #include <type_traits>
 
 #include "common.h"
@@ -54,25 +58,6 @@ __device__ inline float bf16_bits_to_float(unsigned short h) { return __uint_as_
 
 typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 
-// The rows of R as the large kernel fetches them, 16 bytes per lane and load: four fp32, or eight
-// bf16 widened in registers.
-template <bool RB> struct RFrag16;
-template <> struct RFrag16<false> {
-  static constexpr int K = 4;
-  f32x4 v;
-  __device__ void load(const float* p) { v = *(const f32x4*)p; }
-  __device__ float get(int e) const { return v[e]; }
-};
-template <> struct RFrag16<true> {
-  static constexpr int K = 8;
-  u32x4 v;
-  __device__ void load(const unsigned short* p) { v = *(const u32x4*)p; }
-  __device__ float get(int e) const {
-    const unsigned w = v[e >> 1];
-    return __uint_as_float((e & 1) ? (w & 0xFFFF0000u) : (w << 16));
-  }
-};
-
 template <int D, typename F>
 __device__ inline void unrolled(F&& f) {
   if constexpr (D > 0) {
@@ -81,44 +66,34 @@ __device__ inline void unrolled(F&& f) {
   }
 }
 
-// Chunk geometry of the large kernel.  A lane fetches EK consecutive k per load (4 fp32 or 8 bf16,
-// 16 bytes either way), four loads per chunk: k = 4 EK s + EK q + e for load s, lane group q,
-// element e.  MFMA (s, e) takes one k from each lane group, so the four rows of V it reads should
-// lie 4 apart in LDS (conflict-free with the row stride LD + 4): row 16 s + 4 q + e for fp32;
-// for bf16 the chunk row k is stored at row 32 s + 16 (e >> 2) + 4 q + (e & 3).
-template <bool RB> __device__ inline int v_lds_row(int s, int q, int e) {
-  return RB ? 32 * s + 16 * (e >> 2) + 4 * q + (e & 3) : 16 * s + 4 * q + e;
-}
-
-template <int LD, bool RB>
-__global__ __launch_bounds__(NT, 2) void chain_kernel(const typename RFrag<RB>::elem* __restrict__ R, long long strideR, int ldr,
-                                                   const float* __restrict__ R32, long long strideR32, int ldr32,
+template <int LD>
+__global__ __launch_bounds__(NT, 2) void chain_kernel(const float* __restrict__ R, long long strideR, int ldr,
                                                    const float* __restrict__ Vin, long long strideVin,
                                                    float* __restrict__ Vout, long long strideVout, int n,
                                                    const Ctrl* __restrict__ ctrl) {
   constexpr int NBLK = LD / 16;
   constexpr int VS = LD + 4;
-  constexpr int EK = RFrag16<RB>::K;   // k per load
-  constexpr int KCH = 16 * EK;         // k per chunk: 64 (fp32) or 128 (bf16)
+  constexpr int EK = 4;                // k per 16-byte load
+  constexpr int KCH = 16 * EK;         // k per chunk
   __shared__ __align__(16) float Vs[2][KCH][VS];
   const int b = blockIdx.y;
   if (ctrl && ctrl[b].done) return;
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
   const int li = lane & 15, lq = lane >> 4;
   const int row0 = blockIdx.x * ROWS + wave * 16;
-  const typename RFrag<RB>::elem* Rrow = R + (long long)b * strideR + (long long)(row0 + li) * ldr + EK * lq;
+  const float* Rrow = R + (long long)b * strideR + (long long)(row0 + li) * ldr + EK * lq;
   const float* Vb = Vin + (long long)b * strideVin;
 
   // Loads return in order, so waiting for one drains every older one.  The chunk of V that is
   // staged in LDS next is therefore requested DEPTH-1 chunks ahead as well, just before the rows
   // of R of the same chunk: when the wave waits for it, the rows of the DEPTH-2 chunks behind it
   // stay in flight (requested one chunk ahead only, that wait emptied the whole ring every chunk).
-  constexpr int DEPTH = (LD == 64 || RB) ? 4 : 6;
+  constexpr int DEPTH = LD == 64 ? 4 : 6;
   // V chunk loader: KCH x LD floats = KCH * LD / 4 float4, spread over the workgroup
   constexpr int V_LOADS = KCH * LD / 4;
   constexpr int V_IT = (V_LOADS + NT - 1) / NT;
   f32x4 vreg[DEPTH][V_IT];
-  RFrag16<RB> ra[DEPTH][4];
+  f32x4 ra[DEPTH][4];
   const int nchunks = n / KCH;
   // Past the end the last chunk is fetched again (and never used): no branch around the loads, so
   // that the compiler can count how many younger loads may stay in flight at each wait.  (With the
@@ -138,7 +113,7 @@ __global__ __launch_bounds__(NT, 2) void chain_kernel(const typename RFrag<RB>::
       }
     }
 #pragma unroll
-    for (int s = 0; s < 4; ++s) ra[slot][s].load(Rrow + c * KCH + 4 * EK * s);
+    for (int s = 0; s < 4; ++s) ra[slot][s] = *(const f32x4*)(Rrow + c * KCH + 4 * EK * s);
   };
   auto store_v = [&](int slot, int buf) {
 #pragma unroll
@@ -146,8 +121,7 @@ __global__ __launch_bounds__(NT, 2) void chain_kernel(const typename RFrag<RB>::
       const int idx = t + it * NT;
       if (V_LOADS % NT == 0 || idx < V_LOADS) {
         const int kr = idx / (LD / 4), c4 = idx % (LD / 4);
-        const int row = v_lds_row<RB>(kr / (4 * EK), (kr / EK) & 3, kr % EK);
-        *(f32x4*)&Vs[buf][row][c4 * 4] = vreg[slot][it];
+        *(f32x4*)&Vs[buf][kr][c4 * 4] = vreg[slot][it];
       }
     }
   };
@@ -185,7 +159,7 @@ __global__ __launch_bounds__(NT, 2) void chain_kernel(const typename RFrag<RB>::
 #pragma unroll
       for (int e = 0; e < EK; ++e)
 #pragma unroll
-        for (int j = 0; j < NBLK; ++j) vf[s & 1][e][j] = Vs[cur][v_lds_row<RB>(s, lq, e)][j * 16 + li];
+        for (int j = 0; j < NBLK; ++j) vf[s & 1][e][j] = Vs[cur][16 * s + 4 * lq + e][j * 16 + li];
     };
     read_v(0);
 #pragma unroll
@@ -197,7 +171,7 @@ __global__ __launch_bounds__(NT, 2) void chain_kernel(const typename RFrag<RB>::
       for (int e = 0; e < EK; ++e)
 #pragma unroll
         for (int j = 0; j < NBLK; ++j)
-          acc[j][(s * EK + e) % NACC] = __builtin_amdgcn_mfma_f32_16x16x4f32(ra[d][s].get(e), vf[s & 1][e][j], acc[j][(s * EK + e) % NACC], 0, 0, 0);
+          acc[j][(s * EK + e) % NACC] = __builtin_amdgcn_mfma_f32_16x16x4f32(ra[d][s][e], vf[s & 1][e][j], acc[j][(s * EK + e) % NACC], 0, 0, 0);
     }
     store_v((d + 1) % DEPTH, cur ^ 1);   // chunk c + 1 (past the end: the last one again, unused)
     lds_barrier();
@@ -209,15 +183,6 @@ __global__ __launch_bounds__(NT, 2) void chain_kernel(const typename RFrag<RB>::
   unrolled<DEPTH - 1>([&](auto dt) {
     if (nfull + decltype(dt)::value < nchunks) step(dt, nfull + decltype(dt)::value);
   });
-  float dfix[4] = {0.f, 0.f, 0.f, 0.f};   // exact diagonal minus the rounded one, rows of this lane
-  if constexpr (RB) {
-#pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      const int row = row0 + 4 * lq + r;
-      dfix[r] = R32[(long long)b * strideR32 + (long long)row * ldr32 + row] -
-                bf16_bits_to_float((unsigned short)R[(long long)b * strideR + (long long)row * ldr + row]);
-    }
-  }
 #pragma unroll
   for (int j = 0; j < NBLK; ++j) {
 #pragma unroll
@@ -230,9 +195,151 @@ __global__ __launch_bounds__(NT, 2) void chain_kernel(const typename RFrag<RB>::
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
       const int row = row0 + 4 * lq + r, col = j * 16 + li;
-      float v = acc[j][0][r];
-      if constexpr (RB) v += dfix[r] * Vb[(long long)row * LD + col];
-      Vout[(long long)b * strideVout + (long long)row * LD + col] = v;
+      Vout[(long long)b * strideVout + (long long)row * LD + col] = acc[j][0][r];
+    }
+}
+
+// Large matrices, R from its bf16 copy, on the bf16 matrix cores (v_mfma_f32_16x16x32_bf16): with
+// fp32 MFMAs the kernel above is bound by them once R shrinks to two bytes per entry.  V keeps its
+// 24 significant bits: every fp32 entry is cut into three bf16 pieces (8 bits each, exact), staged
+// in LDS as three planes Vt[plane][column][k], and R is multiplied by each plane; the partial
+// products of two bf16 numbers are exact in fp32, so only the accumulation rounds.
+//   A operand: lane (i = l % 16, g = l / 16) holds R[row i][k0 + 32 s + 8 g .. + 7]: its 16-byte load;
+//   B operand: lane (j = l % 16, g) holds the same eight k of column j: one 16-byte LDS read.
+//   A row of Vt is 128 k = 256 bytes plus 16 of padding (68 dwords: the 16 columns of a read hit
+//   all 64 banks once).
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+
+template <int LD>
+__global__ __launch_bounds__(NT, 2) void chain_bf16_kernel(const unsigned short* __restrict__ R, long long strideR, int ldr,
+                                                        const float* __restrict__ R32, long long strideR32, int ldr32,
+                                                        const float* __restrict__ Vin, long long strideVin,
+                                                        float* __restrict__ Vout, long long strideVout, int n,
+                                                        const Ctrl* __restrict__ ctrl) {
+  constexpr int NBLK = LD / 16;
+  constexpr int KCH = 128;
+  constexpr int ROWB = 2 * KCH + 16;             // bytes per (plane, column)
+  constexpr int DEPTH = 3;
+  constexpr int V_TASKS = LD * (KCH / 8);        // (column, group of 8 k) per chunk
+  constexpr int V_IT = V_TASKS / NT;
+  static_assert(V_TASKS % NT == 0, "sketch width");
+  __shared__ __align__(16) unsigned char Vt[2][3][LD][ROWB];
+  const int b = blockIdx.y;
+  if (ctrl && ctrl[b].done) return;
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  const int li = lane & 15, lq = lane >> 4;
+  const int row0 = blockIdx.x * ROWS + wave * 16;
+  const unsigned short* Rrow = R + (long long)b * strideR + (long long)(row0 + li) * ldr + 8 * lq;
+  const float* Vb = Vin + (long long)b * strideVin;
+  const int nchunks = n / KCH;
+  const int rot = (int)(blockIdx.x % (unsigned)nchunks);   // see chain_kernel
+
+  float vreg[DEPTH][V_IT][8];
+  u32x4 ra[DEPTH][4];
+  auto load_chunk = [&](int slot, int c_want) {   // unconditional, as in chain_kernel
+    int c = (c_want < nchunks ? c_want : nchunks - 1) + rot;
+    if (c >= nchunks) c -= nchunks;
+#pragma unroll
+    for (int it = 0; it < V_IT; ++it) {
+      const int idx = t + it * NT;
+      const int col = idx % LD, kg = idx / LD;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) vreg[slot][it][e] = Vb[(long long)(c * KCH + 8 * kg + e) * LD + col];
+    }
+#pragma unroll
+    for (int s = 0; s < 4; ++s) ra[slot][s] = *(const u32x4*)(Rrow + c * KCH + 32 * s);
+  };
+  auto store_v = [&](int slot, int buf) {
+#pragma unroll
+    for (int it = 0; it < V_IT; ++it) {
+      const int idx = t + it * NT;
+      const int col = idx % LD, kg = idx / LD;
+      u32x4 hi, mid, lo;
+#pragma unroll
+      for (int w = 0; w < 4; ++w) {
+        unsigned ph[2], pm[2], pl[2];
+#pragma unroll
+        for (int x = 0; x < 2; ++x) {
+          // three truncations: each piece takes the next 8 significant bits, the last one is exact
+          const float v = vreg[slot][it][2 * w + x];
+          const unsigned h = __float_as_uint(v) & 0xFFFF0000u;
+          const float r1 = v - __uint_as_float(h);
+          const unsigned m = __float_as_uint(r1) & 0xFFFF0000u;
+          const float r2 = r1 - __uint_as_float(m);
+          ph[x] = h; pm[x] = m; pl[x] = __float_as_uint(r2);
+        }
+        hi[w] = (ph[0] >> 16) | ph[1];
+        mid[w] = (pm[0] >> 16) | pm[1];
+        lo[w] = (pl[0] >> 16) | (pl[1] & 0xFFFF0000u);
+      }
+      *(u32x4*)&Vt[buf][0][col][16 * kg] = hi;
+      *(u32x4*)&Vt[buf][1][col][16 * kg] = mid;
+      *(u32x4*)&Vt[buf][2][col][16 * kg] = lo;
+    }
+  };
+
+  f32x4 acc[NBLK][3];
+#pragma unroll
+  for (int j = 0; j < NBLK; ++j)
+#pragma unroll
+    for (int p = 0; p < 3; ++p) acc[j][p] = (f32x4){0.f, 0.f, 0.f, 0.f};
+  auto lds_barrier = [&]() {   // see chain_kernel
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+  };
+#pragma unroll
+  for (int d = 0; d < DEPTH - 1; ++d) load_chunk(d, d);
+  store_v(0, 0);
+  lds_barrier();
+  auto step = [&](auto dtag, int c) {
+    constexpr int d = decltype(dtag)::value;
+    const int cur = c & 1;
+    load_chunk((d + DEPTH - 1) % DEPTH, c + DEPTH - 1);
+    // fragments of V one step ahead of their MFMAs (see chain_kernel)
+    u32x4 fb[2][3][NBLK];
+    auto read_v = [&](int s) {
+#pragma unroll
+      for (int p = 0; p < 3; ++p)
+#pragma unroll
+        for (int j = 0; j < NBLK; ++j) fb[s & 1][p][j] = *(const u32x4*)&Vt[cur][p][j * 16 + li][64 * s + 16 * lq];
+    };
+    read_v(0);
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      __builtin_amdgcn_sched_barrier(0);
+      if (s + 1 < 4) read_v(s + 1);
+      __builtin_amdgcn_sched_barrier(0);
+      const bf16x8 a = __builtin_bit_cast(bf16x8, ra[d][s]);
+#pragma unroll
+      for (int p = 0; p < 3; ++p)
+#pragma unroll
+        for (int j = 0; j < NBLK; ++j)
+          acc[j][p] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, __builtin_bit_cast(bf16x8, fb[s & 1][p][j]), acc[j][p], 0, 0, 0);
+    }
+    store_v((d + 1) % DEPTH, cur ^ 1);
+    lds_barrier();
+  };
+  const int nfull = nchunks / DEPTH * DEPTH;
+  for (int c0 = 0; c0 < nfull; c0 += DEPTH)
+    unrolled<DEPTH>([&](auto dt) { step(dt, c0 + decltype(dt)::value); });
+  unrolled<DEPTH - 1>([&](auto dt) {
+    if (nfull + decltype(dt)::value < nchunks) step(dt, nfull + decltype(dt)::value);
+  });
+  float dfix[4];   // exact diagonal minus the rounded one, rows of this lane
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    const int row = row0 + 4 * lq + r;
+    dfix[r] = R32[(long long)b * strideR32 + (long long)row * ldr32 + row] -
+              bf16_bits_to_float(R[(long long)b * strideR + (long long)row * ldr + row]);
+  }
+#pragma unroll
+  for (int j = 0; j < NBLK; ++j)
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const int row = row0 + 4 * lq + r, col = j * 16 + li;
+      const float v = (acc[j][2][r] + acc[j][1][r]) + acc[j][0][r];   // small pieces first
+      Vout[(long long)b * strideVout + (long long)row * LD + col] = v + dfix[r] * Vb[(long long)row * LD + col];
     }
 }
 
@@ -350,14 +457,20 @@ int launch_chain_t(const typename RFrag<RB>::elem* R, long long strideR, int ldr
     return hipGetLastError() == hipSuccess ? PRISM_OK : PRISM_EHIP;
   }
   const dim3 grid(n / ROWS, batch), block(NT);
-  if (RB && (n % 128 || ldr % 8)) return PRISM_EINVAL;   // the bf16 kernel takes K in chunks of 128, rows in 16-byte loads
-  if (ld == 16) hipLaunchKernelGGL((chain_kernel<16, RB>), grid, block, 0, s, R, strideR, ldr, R32, strideR32, ldr32, Vin, strideVin, Vout, strideVout, n, ctrl);
-  else if (ld == 32) hipLaunchKernelGGL((chain_kernel<32, RB>), grid, block, 0, s, R, strideR, ldr, R32, strideR32, ldr32, Vin, strideVin, Vout, strideVout, n, ctrl);
-  else if (ld == 64) {
-    if constexpr (!RB) hipLaunchKernelGGL((chain_kernel<64, false>), grid, block, 0, s, R, strideR, ldr, R32, strideR32, ldr32, Vin, strideVin, Vout, strideVout, n, ctrl);
+  if constexpr (RB) {   // K in chunks of 128, rows in 16-byte loads
+    if (n % 128 || ldr % 8) return PRISM_EINVAL;
+    if (ld == 16) hipLaunchKernelGGL((chain_bf16_kernel<16>), grid, block, 0, s, R, strideR, ldr, R32, strideR32, ldr32, Vin, strideVin, Vout, strideVout, n, ctrl);
+    else if (ld == 32) hipLaunchKernelGGL((chain_bf16_kernel<32>), grid, block, 0, s, R, strideR, ldr, R32, strideR32, ldr32, Vin, strideVin, Vout, strideVout, n, ctrl);
     else return PRISM_EINVAL;
-  } else return PRISM_EINVAL;
-  return hipGetLastError() == hipSuccess ? PRISM_OK : PRISM_EHIP;
+    return hipGetLastError() == hipSuccess ? PRISM_OK : PRISM_EHIP;
+  }
+  else {
+    if (ld == 16) hipLaunchKernelGGL((chain_kernel<16>), grid, block, 0, s, R, strideR, ldr, Vin, strideVin, Vout, strideVout, n, ctrl);
+    else if (ld == 32) hipLaunchKernelGGL((chain_kernel<32>), grid, block, 0, s, R, strideR, ldr, Vin, strideVin, Vout, strideVout, n, ctrl);
+    else if (ld == 64) hipLaunchKernelGGL((chain_kernel<64>), grid, block, 0, s, R, strideR, ldr, Vin, strideVin, Vout, strideVout, n, ctrl);
+    else return PRISM_EINVAL;
+    return hipGetLastError() == hipSuccess ? PRISM_OK : PRISM_EHIP;
+  }
 }
 
 }  // namespace
