@@ -7,6 +7,8 @@
 // (As[k][m], Bs[k][n]) and double buffered: the global loads of slab t+1 are in flight while
 // the MFMAs of slab t run.  All operand sizes are padded to tile multiples by the caller, so
 // the main loop has no bounds checks; masks are applied in the epilogue only.
+#include <type_traits>
+
 #include "common.h"
 
 namespace prism {
@@ -137,20 +139,22 @@ __global__ __launch_bounds__(NT, 2) void gemm_kernel(GemmDesc g) {
   constexpr int BV = Vec16<TB>::N;
   constexpr int B_LOADS = TN * BK / BV;
   constexpr int B_IT = (B_LOADS + NT - 1) / NT;
-  f32x4 ra[A_IT];
-  typename Vec16<TB>::type rb[B_IT];
+  // two register sets: the loads of slab t+2 are issued while slab t is multiplied and slab t+1
+  // waits in the other set (one slab of MFMAs is shorter than the memory latency under load)
+  f32x4 ra[2][A_IT];
+  typename Vec16<TB>::type rb[2][B_IT];
 
-  auto load_slab = [&](int k0) {
+  auto load_slab = [&](int set, int k0) {   // set is a compile-time constant at every call site
 #pragma unroll
     for (int it = 0; it < A_IT; ++it) {
       const int idx = t + it * NT;
       if (A_LOADS % NT == 0 || idx < A_LOADS) {
         if (A_KM) {
           const int kr = idx / (TM / 4), c4 = idx % (TM / 4);
-          ra[it] = *(const f32x4*)(Ab + (long long)(k0 + kr) * g.lda + m0 + c4 * 4);
+          ra[set][it] = *(const f32x4*)(Ab + (long long)(k0 + kr) * g.lda + m0 + c4 * 4);
         } else {
           const int row = idx / (BK / 4), c4 = idx % (BK / 4);
-          ra[it] = *(const f32x4*)(Ab + (long long)(m0 + row) * g.lda + k0 + c4 * 4);
+          ra[set][it] = *(const f32x4*)(Ab + (long long)(m0 + row) * g.lda + k0 + c4 * 4);
         }
       }
     }
@@ -159,11 +163,11 @@ __global__ __launch_bounds__(NT, 2) void gemm_kernel(GemmDesc g) {
       const int idx = t + it * NT;
       if (B_LOADS % NT == 0 || idx < B_LOADS) {
         const int kr = idx / (TN / BV), c = idx % (TN / BV);
-        rb[it] = *(const typename Vec16<TB>::type*)(Bb + (long long)(k0 + kr) * g.ldb + n0 + c * BV);
+        rb[set][it] = *(const typename Vec16<TB>::type*)(Bb + (long long)(k0 + kr) * g.ldb + n0 + c * BV);
       }
     }
   };
-  auto store_slab = [&](int buf) {
+  auto store_slab = [&](int set, int buf) {
 #pragma unroll
     for (int it = 0; it < A_IT; ++it) {
       const int idx = t + it * NT;
@@ -171,11 +175,11 @@ __global__ __launch_bounds__(NT, 2) void gemm_kernel(GemmDesc g) {
         if (A_KM) {
           const int kr = idx / (TM / 4), c4 = idx % (TM / 4);
 #pragma unroll
-          for (int e = 0; e < 4; ++e) As[buf][kr][c4 * 4 + e] = (TC)ra[it][e];
+          for (int e = 0; e < 4; ++e) As[buf][kr][c4 * 4 + e] = (TC)ra[set][it][e];
         } else {
           const int row = idx / (BK / 4), c4 = idx % (BK / 4);
 #pragma unroll
-          for (int e = 0; e < 4; ++e) As[buf][c4 * 4 + e][row] = (TC)ra[it][e];
+          for (int e = 0; e < 4; ++e) As[buf][c4 * 4 + e][row] = (TC)ra[set][it][e];
         }
       }
     }
@@ -185,7 +189,7 @@ __global__ __launch_bounds__(NT, 2) void gemm_kernel(GemmDesc g) {
       if (B_LOADS % NT == 0 || idx < B_LOADS) {
         const int kr = idx / (TN / BV), c = idx % (TN / BV);
 #pragma unroll
-        for (int e = 0; e < BV; ++e) Bs[buf][kr][c * BV + e] = (TC)rb[it][e];
+        for (int e = 0; e < BV; ++e) Bs[buf][kr][c * BV + e] = (TC)rb[set][it][e];
       }
     }
   };
@@ -208,33 +212,50 @@ __global__ __launch_bounds__(NT, 2) void gemm_kernel(GemmDesc g) {
       for (int j = 0; j < BN; ++j) ksum[i][j] = (typename Acc<TC>::type){0, 0, 0, 0};
   }
   const int KT = g.K / BK;
-  load_slab(0);
-  store_slab(0);
-  __syncthreads();
+  // Past the end the last slab is fetched (and staged) again, unused: no branch around the loads,
+  // so that the compiler can count the younger loads that may stay in flight at each wait.
+  auto kclamp = [&](int kt) { return (kt < KT ? kt : KT - 1) * BK; };
+  // barrier for the LDS tiles only: __syncthreads() would also wait for the loads in flight
+  auto lds_barrier = [&]() {
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+  };
+  load_slab(0, 0);
+  store_slab(0, 0);
+  load_slab(1, kclamp(1));
+  lds_barrier();
   const int lr = lane & 15, lk = lane >> 4;
-  // Two nested loops, so that inside the inner one the accumulators are touched by MFMAs only and
-  // can stay in the accumulation registers; the partial sums are closed between inner loops.
-  constexpr int CHUNK = FLUSH ? 16 : (1 << 30);   // slabs per partial sum (fp32: 256 k)
+  auto slab = [&](auto ptag, int kt) {   // slab kt, P = kt & 1: LDS buffer P, next slab in register set P ^ 1
+    constexpr int P = decltype(ptag)::value;
+    load_slab(P, kclamp(kt + 2));
+    __builtin_amdgcn_sched_barrier(0);   // the loads stay ahead of the MFMAs
+#pragma unroll
+    for (int kk = 0; kk < BK / 4; ++kk) {
+      TC a[BM], bb[BN];
+#pragma unroll
+      for (int i = 0; i < BM; ++i) a[i] = As[P][kk * 4 + lk][wm0 + i * 16 + lr];
+#pragma unroll
+      for (int j = 0; j < BN; ++j) bb[j] = Bs[P][kk * 4 + lk][wn0 + j * 16 + lr];
+#pragma unroll
+      for (int i = 0; i < BM; ++i)
+#pragma unroll
+        for (int j = 0; j < BN; ++j) acc[i][j] = mfma(a[i], bb[j], acc[i][j]);
+    }
+    store_slab(P ^ 1, P ^ 1);
+    lds_barrier();
+  };
+  // Two nested loops, so that inside the inner one the accumulators are touched by MFMAs only;
+  // the partial sums are closed between inner loops.
+  constexpr int CHUNK = FLUSH ? 16 : (1 << 30);   // slabs per partial sum (fp32: 256 k); even
   for (int kt0 = 0; kt0 < KT; kt0 += CHUNK) {
     const int kt1 = (FLUSH && kt0 + CHUNK < KT) ? kt0 + CHUNK : KT;
-    for (int kt = kt0; kt < kt1; ++kt) {
-      const int cur = kt & 1;
-      if (kt + 1 < KT) load_slab((kt + 1) * BK);
-#pragma unroll
-      for (int kk = 0; kk < BK / 4; ++kk) {
-        TC a[BM], bb[BN];
-#pragma unroll
-        for (int i = 0; i < BM; ++i) a[i] = As[cur][kk * 4 + lk][wm0 + i * 16 + lr];
-#pragma unroll
-        for (int j = 0; j < BN; ++j) bb[j] = Bs[cur][kk * 4 + lk][wn0 + j * 16 + lr];
-#pragma unroll
-        for (int i = 0; i < BM; ++i)
-#pragma unroll
-          for (int j = 0; j < BN; ++j) acc[i][j] = mfma(a[i], bb[j], acc[i][j]);
-      }
-      if (kt + 1 < KT) store_slab(cur ^ 1);
-      __syncthreads();
+    int kt = kt0;
+    for (; kt + 1 < kt1; kt += 2) {
+      slab(std::integral_constant<int, 0>{}, kt);
+      slab(std::integral_constant<int, 1>{}, kt + 1);
     }
+    if (kt < kt1) slab(std::integral_constant<int, 0>{}, kt);
     if (FLUSH) {
 #pragma unroll
       for (int i = 0; i < BM; ++i)
