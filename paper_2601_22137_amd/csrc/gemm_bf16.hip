@@ -442,8 +442,25 @@ __global__ __launch_bounds__(NT, T == 128 ? 3 : 1) void gemm_bf16_kernel(Bf16Des
     const int rr = lane / LPR, cc = (lane % LPR) * 8;
     const int cq = lane >> 2, rq = lane & 3;
     const long long base = (long long)b * g.strideCb;
+    // The old iterate of row block i + 1 is requested while block i is worked on (and that of
+    // block 0 before the accumulators go to LDS): its memory latency is paid once per tile
+    // instead of once per block.
+    constexpr int ITS = 32 / RPI;
+    u32x4 xh[2][ITS], xl[2][ITS];
+    const bool has_lo = g.Xlo != nullptr;
+    auto fetch_x = [&](int i, int set) {
+#pragma unroll
+      for (int it = 0; it < ITS; ++it) {
+        const long long o = base + (long long)(m0 + wm0 + i * 32 + it * RPI + rr) * g.ldcb + n0 + wn0 + cc;
+        xh[set][it] = *(const u32x4*)(g.Xhi + o);
+        xl[set][it] = (u32x4){0u, 0u, 0u, 0u};
+        if (has_lo) xl[set][it] = *(const u32x4*)(g.Xlo + o);
+      }
+    };
+    fetch_x(0, 0);
 #pragma unroll
     for (int i = 0; i < NB; ++i) {
+      if (i + 1 < NB) fetch_x(i + 1, (i + 1) & 1);
 #pragma unroll
       for (int j = 0; j < NB; ++j)
 #pragma unroll
@@ -451,14 +468,13 @@ __global__ __launch_bounds__(NT, T == 128 ? 3 : 1) void gemm_bf16_kernel(Bf16Des
           strip[((r >> 2) * 8 + rbase + (r & 3)) * SW + j * 32 + lr] = acc[i][j][r];
       // row-wise: x' = x_hi + x_lo + coef * acc, split again, keep the high half for the transpose
 #pragma unroll
-      for (int it = 0; it < 32 / RPI; ++it) {
+      for (int it = 0; it < ITS; ++it) {
         const int row = it * RPI + rr;
         float* sp = strip + row * SW + cc;
         const f32x4 a0 = *(const f32x4*)sp, a1 = *(const f32x4*)(sp + 4);
         const long long o = base + (long long)(m0 + wm0 + i * 32 + row) * g.ldcb + n0 + wn0 + cc;
-        const u32x4 hi = *(const u32x4*)(g.Xhi + o);
-        u32x4 lo = {0u, 0u, 0u, 0u};
-        if (g.Xlo) lo = *(const u32x4*)(g.Xlo + o);
+        const u32x4 hi = xh[i & 1][it];
+        const u32x4 lo = xl[i & 1][it];
         u32x4 nh, nl;
         f32x4 k0, k1;
 #pragma unroll
