@@ -362,6 +362,21 @@ __global__ __launch_bounds__(NT, T == 128 ? 3 : 1) void gemm_bf16_kernel(Bf16Des
     const int cq = lane >> 2, rq = lane & 3;
     const bool mirror = tm != tn;
     const long long b32 = (long long)b * g.strideC32, bb = (long long)b * g.strideCb;
+    // R^2 epilogue: the entries of R of a row block are requested before its accumulators go
+    // through LDS, those of the next block while the mirror image of this one is written.
+    constexpr int ITS = 32 / RPI;
+    f32x4 rin0[EPI == BEPI_POLYQ ? ITS : 1], rin1[EPI == BEPI_POLYQ ? ITS : 1];
+    auto fetch_r = [&](int i) {
+      if constexpr (EPI == BEPI_POLYQ) {
+#pragma unroll
+        for (int it = 0; it < ITS; ++it) {
+          const long long o32 = b32 + (long long)(m0 + wm0 + i * 32 + it * RPI + rr) * g.ldc32 + n0 + wn0 + cc;
+          rin0[it] = *(const f32x4*)(g.C32 + o32);
+          rin1[it] = *(const f32x4*)(g.C32 + o32 + 4);
+        }
+      }
+    };
+    fetch_r(0);
 #pragma unroll
     for (int i = 0; i < NB; ++i) {
 #pragma unroll
@@ -370,7 +385,7 @@ __global__ __launch_bounds__(NT, T == 128 ? 3 : 1) void gemm_bf16_kernel(Bf16Des
         for (int r = 0; r < 16; ++r)
           strip[((r >> 2) * 8 + rbase + (r & 3)) * SW + j * 32 + lr] = acc[i][j][r];
 #pragma unroll
-      for (int it = 0; it < 32 / RPI; ++it) {
+      for (int it = 0; it < ITS; ++it) {
         const int row = it * RPI + rr;
         float* sp = strip + row * SW + cc;
         f32x4 v0 = *(const f32x4*)sp, v1 = *(const f32x4*)(sp + 4);
@@ -386,7 +401,7 @@ __global__ __launch_bounds__(NT, T == 128 ? 3 : 1) void gemm_bf16_kernel(Bf16Des
           *(f32x4*)(g.C32 + o32) = v0;
           *(f32x4*)(g.C32 + o32 + 4) = v1;
         } else {
-          const f32x4 r0 = *(const f32x4*)(g.C32 + o32), r1 = *(const f32x4*)(g.C32 + o32 + 4);
+          const f32x4 r0 = rin0[EPI == BEPI_POLYQ ? it : 0], r1 = rin1[EPI == BEPI_POLYQ ? it : 0];
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
             v0[e] = g.c1 * r0[e] + alpha * v0[e];
@@ -404,6 +419,7 @@ __global__ __launch_bounds__(NT, T == 128 ? 3 : 1) void gemm_bf16_kernel(Bf16Des
           *(f32x4*)(sp + 4) = v1;
         }
       }
+      if (i + 1 < NB) fetch_r(i + 1);
       if (mirror) {
         // column-wise: 8 consecutive rows of one column = 8 consecutive entries of a mirrored row
 #pragma unroll
