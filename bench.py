@@ -63,7 +63,9 @@ def make_workload(args, torch, prism, W):
         wl.dtype = "bf16"
         wl.host = [W.c2_muon_group(i) for i in range(4) if args.only_group < 0 or i == args.only_group]
         wl.flags = 0 if args.split else prism.FLAG_BF16_PLAIN_ITERATE
-        wl.call = lambda x: prism.polar(x, 5, 5, 16, wl.seed, 0.0, flags=wl.flags)
+        # single calls (profile pass, --no-grouped) carry the hint that the grouped call gives its groups,
+        # so that the same kernels are timed
+        wl.call = lambda x: prism.polar(x, 5, 5, 16, wl.seed, 0.0, flags=wl.flags | prism.FLAG_SHARED_GPU)
         wl.split = args.split
     elif name == "c3":
         b = args.batch or 8

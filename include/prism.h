@@ -96,7 +96,12 @@ enum {
    * matrix-core pass per update).  By default X_k is carried as a pair of bf16
    * matrices (high + low part, two passes per update), which is what an
    * ill-conditioned input needs to reach its own polar factor. */
-  PRISM_FLAG_BF16_PLAIN_ITERATE = 1u
+  PRISM_FLAG_BF16_PLAIN_ITERATE = 1u,
+  /* Scheduling hint, results unchanged: other work of the caller runs on the GPU beside this
+   * call (calls for other shapes on other streams).  The bf16 Gram product then takes 256 x 256
+   * tiles even when they are too few to fill the chip: they move half the bytes per flop and
+   * leave whole CUs to the other work.  prism_run_grouped sets it for its groups. */
+  PRISM_FLAG_SHARED_GPU = 2u
 };
 
 typedef struct {

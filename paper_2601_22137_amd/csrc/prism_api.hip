@@ -53,6 +53,7 @@ struct Plan {
   // byte offsets into the workspace
   size_t o_ctrl, o_info, o_sumsq, o_rho, o_v0, o_v, o_cpart;
   int ngroups;     // workgroups per matrix of the moments kernel
+  bool shared_gpu; // PRISM_FLAG_SHARED_GPU
   size_t o_x[2], o_y[2], o_r, o_q, o_t[3];        // fp32 paths (o_y doubles as M64 for inverse root)
   size_t o_xhi[2], o_xlo[2], o_xg[2], o_rb, o_qb; // bf16 polar
   size_t total;
@@ -80,6 +81,7 @@ int make_plan(Plan& P, int fn, int batch, int m, int n, int dt, int degree, int 
   P.ld = sketch_dim <= 16 ? 16 : (sketch_dim <= 32 ? 32 : 64);
   P.nv = fn == PRISM_FN_INV_ROOT ? root_p + 1 : (fn == PRISM_FN_INVERSE ? 3 : 2 * P.d + 1);
   P.split = (dt == PRISM_BF16) && !(flags & PRISM_FLAG_BF16_PLAIN_ITERATE);
+  P.shared_gpu = (flags & PRISM_FLAG_SHARED_GPU) != 0;
   if (dt == PRISM_BF16) {
     P.tile = P.S >= 512 ? 256 : 128;   // padding granularity; the tile is chosen per launch
   } else {
@@ -305,8 +307,12 @@ int run_polar_f32(Run& r) {
 // CU) but nothing overlaps their epilogue: they are taken when they still give every CU work and
 // K is long enough to amortise it.  (At K = 768 the bare product is faster with large tiles from
 // 144 tiles on, the update GEMM with its three-output epilogue is not.)
-int bf16_tile(const Plan& P, int M, int N, int K, bool symmetric) {
+int bf16_tile_forced() {
   static const int forced = getenv("PRISM_BF16_TILE") ? atoi(getenv("PRISM_BF16_TILE")) : 0;
+  return (forced == 128 || forced == 256) ? forced : 0;
+}
+int bf16_tile(const Plan& P, int M, int N, int K, bool symmetric) {
+  const int forced = bf16_tile_forced();
   if (P.tile != 256) return 128;
   if (forced == 128 || forced == 256) return forced;
   const long long per_mat = symmetric ? (long long)(M / 256) * (M / 256 + 1) / 2 : (long long)(M / 256) * (N / 256);
@@ -318,7 +324,12 @@ int run_polar_bf16(Run& r) {
   const int Sp = P.Sp, Lp = P.Lp;
   static const int no_sym = getenv("PRISM_BF16_NO_SYM") ? atoi(getenv("PRISM_BF16_NO_SYM")) : 0;
   const int sym = no_sym ? 0 : 1;
-  const int Tg = bf16_tile(P, Sp, Sp, Lp, sym != 0), Ta = bf16_tile(P, Lp, Sp, Sp, false);
+  // Gram product: with other work beside this call, large tiles also when they are few (measured on
+  // the Muon-shaped batch of four groups: 3.96 -> 3.80 ms; alone on the GPU the same choice costs
+  // 1.40 instead of 1.07 ms of Gram time per step).  R^2 and the update keep the rule.
+  int Tg = bf16_tile(P, Sp, Sp, Lp, sym != 0);
+  const int Tq = Tg, Ta = bf16_tile(P, Lp, Sp, Sp, false);
+  if (P.tile == 256 && P.shared_gpu && bf16_tile_forced() == 0) Tg = 256;
   const long long SS = (long long)Sp * Sp, LS = (long long)Lp * Sp;
   uint16_t* Xhi[2] = {r.at<uint16_t>(P.o_xhi[0]), r.at<uint16_t>(P.o_xhi[1])};
   uint16_t* Xlo[2] = {P.split ? r.at<uint16_t>(P.o_xlo[0]) : nullptr, P.split ? r.at<uint16_t>(P.o_xlo[1]) : nullptr};
@@ -351,7 +362,7 @@ int run_polar_bf16(Run& r) {
       q.M = Sp; q.N = Sp; q.K = Sp; q.batch = P.batch; q.epi = BEPI_POLYQ; q.sym = sym;
       q.C32 = R; q.strideC32 = SS; q.ldc32 = Sp; q.Cb = Qb; q.strideCb = SS; q.ldcb = Sp; q.c1 = 0.5f;
       q.ctrl = r.ctrl;
-      { ProfScope ps(PK_BF16_POLYQ, r.s); CHECK_LAUNCH(launch_gemm_bf16(q, Tg, r.s)); }
+      { ProfScope ps(PK_BF16_POLYQ, r.s); CHECK_LAUNCH(launch_gemm_bf16(q, Tq, r.s)); }
       Bop = Qb;
     }
     Bf16Desc a = {};
@@ -679,6 +690,7 @@ int run_grouped(int fn, const prism_group* groups, int ngroups, int root_p, int 
   for (int gi = 0; gi < ngroups && first_error == PRISM_OK; ++gi) {
     prism_options o = opt ? *opt : prism_options{};
     o.info = groups[gi].info;
+    o.flags |= PRISM_FLAG_SHARED_GPU;
     first_error = run(fn, groups[gi].x, groups[gi].inv_out, root_p, groups[gi].batch, groups[gi].m, groups[gi].n, dt,
                       degree, max_iters, sketch_dim, seed, tol, f->streams[gi % GROUP_STREAMS], &o);
   }

@@ -117,3 +117,22 @@ def test_optimizer_helpers(prism):
     for s, r, it in zip(stats, roots, iters):
         ref, oinfo = O.inv_root(s.cpu().numpy(), 4, 40, 16, SEED, 1e-5)
         assert _rel(r.cpu().numpy(), ref) <= 1e-5 and it == oinfo["iters"]
+
+
+def test_shared_gpu_flag_is_a_scheduling_hint(prism):
+    """PRISM_FLAG_SHARED_GPU changes tile sizes only: at a size where it does (Gram dimension 768,
+    a multiple of 256) a single call with the flag gives the bits of the grouped call, and both stay
+    within the rounding of the unflagged call."""
+    bits = [W.c2_muon_group(0, batch=2), W.c2_muon_group(3, batch=2)]
+    plain = prism.FLAG_BF16_PLAIN_ITERATE
+    xs = [_bf16(b.copy()) for b in bits]
+    prism.run_grouped(prism.FN_POLAR, xs, 5, 5, 16, SEED, 0.0, flags=plain)
+    torch.cuda.synchronize()
+    for g, b in enumerate(bits):
+        hinted = _bf16(b.copy())
+        prism.polar(hinted, 5, 5, 16, SEED, 0.0, flags=plain | prism.FLAG_SHARED_GPU)
+        assert torch.equal(hinted.view(torch.int16), xs[g].view(torch.int16))
+        unhinted = _bf16(b.copy())
+        prism.polar(unhinted, 5, 5, 16, SEED, 0.0, flags=plain)
+        d = (unhinted.float() - hinted.float()).norm() / hinted.float().norm()
+        assert float(d) <= 2e-2
