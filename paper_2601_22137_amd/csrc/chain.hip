@@ -330,7 +330,7 @@ __global__ __launch_bounds__(NT, 2) void chain_bf16_kernel(const unsigned short*
 #pragma unroll
   for (int r = 0; r < 4; ++r) {
     const int row = row0 + 4 * lq + r;
-    dfix[r] = R32[(long long)b * strideR32 + (long long)row * ldr32 + row] -
+    dfix[r] = R32[(long long)b * strideR32 + (long long)row * ldr32] -
               bf16_bits_to_float(R[(long long)b * strideR + (long long)row * ldr + row]);
   }
 #pragma unroll
@@ -435,7 +435,7 @@ __global__ __launch_bounds__(NT, 2) void chain_small_kernel(const typename RFrag
         float v = (red[0][j][r][lane] + red[1][j][r][lane]) + (red[2][j][r][lane] + red[3][j][r][lane]);
         const int row = row0 + 4 * lq + r, col = j * 16 + li;
         if constexpr (RB) {   // exact diagonal minus the rounded one
-          const float dfix = R32[(long long)b * strideR32 + (long long)row * ldr32 + row] -
+          const float dfix = R32[(long long)b * strideR32 + (long long)row * ldr32] -
                              bf16_bits_to_float((unsigned short)R[(long long)b * strideR + (long long)row * ldr + row]);
           v += dfix * Vb[(long long)row * LD + col];
         }
@@ -481,16 +481,19 @@ int launch_chain(const float* R, long long strideR, int ldr, const float* Vin, l
   return launch_chain_t<false>(R, strideR, ldr, nullptr, 0, 0, Vin, strideVin, Vout, strideVout, n, ld, batch, ctrl, s);
 }
 
-// Same product with R read from its bf16 copy Rb (same shape and strides) and the diagonal from R
-int launch_chain_bf16(const unsigned short* Rb, const float* R, long long strideR, int ldr, const float* Vin,
-                      long long strideVin, float* Vout, long long strideVout, int n, int ld, int batch, const Ctrl* ctrl,
-                      hipStream_t s) {
-  if (!Rb || !R) return PRISM_EINVAL;
-  // widest sketches and sizes that are no multiple of 128: the fp32 matrix
+// Shapes the bf16 kernels take: sketch width up to 32, rows of Rb in 16-byte loads, and K in chunks
+// of 128 unless the 16-row kernel applies.
+bool chain_bf16_supported(int n, int ld, int batch, int ldr) {
   const bool small = ld <= 32 && (long long)(n / ROWS) * batch < 256;
-  if (ld == 64 || ldr % 8 || (!small && n % 128))
-    return launch_chain_t<false>(R, strideR, ldr, nullptr, 0, 0, Vin, strideVin, Vout, strideVout, n, ld, batch, ctrl, s);
-  return launch_chain_t<true>(Rb, strideR, ldr, R, strideR, ldr, Vin, strideVin, Vout, strideVout, n, ld, batch, ctrl, s);
+  return (ld == 16 || ld == 32) && ldr % 8 == 0 && n % KC == 0 && (small || n % 128 == 0);
+}
+
+// Same product with R read from its bf16 copy Rb and the diagonal from D (see common.h)
+int launch_chain_bf16(const unsigned short* Rb, long long strideR, int ldr, const float* D, long long strideD, int ldd,
+                      const float* Vin, long long strideVin, float* Vout, long long strideVout, int n, int ld, int batch,
+                      const Ctrl* ctrl, hipStream_t s) {
+  if (!Rb || !D || !chain_bf16_supported(n, ld, batch, ldr)) return PRISM_EINVAL;
+  return launch_chain_t<true>(Rb, strideR, ldr, D, strideD, ldd, Vin, strideVin, Vout, strideVout, n, ld, batch, ctrl, s);
 }
 
 }  // namespace prism

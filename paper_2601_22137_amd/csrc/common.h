@@ -80,7 +80,9 @@ struct Bf16Desc {
   int epi;
   int sym;                                           // GRAM / POLYQ with A == B: compute the upper triangle of tiles only
   int n_true;                                        // GRAM mask
-  float* C32; long long strideC32; int ldc32;        // STORE / GRAM fp32 out; POLYQ fp32 in
+  float* C32; long long strideC32; int ldc32;        // STORE / GRAM fp32 out; POLYQ fp32 in.  Null with `diag` set:
+  float* diag; long long strideDiag;                 // symmetric GRAM writes only the bf16 copy and the fp32 diagonal, POLYQ reads the bf16 copy (Cin)
+  const uint16_t* Cin16;                             // POLYQ without C32: R in bf16 (layout of Cb)
   uint16_t* Cb; long long strideCb; int ldcb;        // GRAM: Rb out; POLYQ: Q out; APPLY: Xa_hi' out
   uint16_t* Cb2;                                     // APPLY: Xa_lo' out (null in plain mode)
   uint16_t* Ct; long long strideCt; int ldct;        // APPLY: Xg_hi' out, transposed [N][M]
@@ -105,9 +107,12 @@ void launch_gauss_parts(uint32_t first, uint32_t count, double* r, double* c, do
 // ---- chain.hip : V_out = R V_in for the sketch chain (HBM bound; R read once, straight into registers) ----
 int launch_chain(const float* R, long long strideR, int ldr, const float* Vin, long long strideVin, float* Vout,
                  long long strideVout, int n, int ld, int batch, const Ctrl* ctrl, hipStream_t s);
-int launch_chain_bf16(const unsigned short* Rb, const float* R, long long strideR, int ldr, const float* Vin,
-                      long long strideVin, float* Vout, long long strideVout, int n, int ld, int batch, const Ctrl* ctrl,
-                      hipStream_t s);
+// Rb: bf16 copy of R [batch][n][ldr]; D: its exact fp32 diagonal, entry i of matrix b at D[b * strideD + i * ldd]
+// (ldd = ld of R + 1 reads it out of the full fp32 matrix, ldd = 1 out of a compact array)
+bool chain_bf16_supported(int n, int ld, int batch, int ldr);
+int launch_chain_bf16(const unsigned short* Rb, long long strideR, int ldr, const float* D, long long strideD, int ldd,
+                      const float* Vin, long long strideVin, float* Vout, long long strideVout, int n, int ld, int batch,
+                      const Ctrl* ctrl, hipStream_t s);
 
 // ---- fit.hip ----
 struct SolveArgs {

@@ -366,13 +366,26 @@ __global__ __launch_bounds__(NT, T == 128 ? 3 : 1) void gemm_bf16_kernel(Bf16Des
     // through LDS, those of the next block while the mirror image of this one is written.
     constexpr int ITS = 32 / RPI;
     f32x4 rin0[EPI == BEPI_POLYQ ? ITS : 1], rin1[EPI == BEPI_POLYQ ? ITS : 1];
+    const bool lean = g.C32 == nullptr;   // GRAM: bf16 copy and diagonal only; POLYQ: R comes in bf16
     auto fetch_r = [&](int i) {
       if constexpr (EPI == BEPI_POLYQ) {
 #pragma unroll
         for (int it = 0; it < ITS; ++it) {
-          const long long o32 = b32 + (long long)(m0 + wm0 + i * 32 + it * RPI + rr) * g.ldc32 + n0 + wn0 + cc;
-          rin0[it] = *(const f32x4*)(g.C32 + o32);
-          rin1[it] = *(const f32x4*)(g.C32 + o32 + 4);
+          const int m = m0 + wm0 + i * 32 + it * RPI + rr, n = n0 + wn0 + cc;
+          if (lean) {
+            const u32x4 w = *(const u32x4*)(g.Cin16 + bb + (long long)m * g.ldcb + n);
+#pragma unroll
+            for (int e = 0; e < 2; ++e) {
+              rin0[it][2 * e] = __uint_as_float(w[e] << 16);
+              rin0[it][2 * e + 1] = __uint_as_float(w[e] & 0xFFFF0000u);
+              rin1[it][2 * e] = __uint_as_float(w[2 + e] << 16);
+              rin1[it][2 * e + 1] = __uint_as_float(w[2 + e] & 0xFFFF0000u);
+            }
+          } else {
+            const long long o32 = b32 + (long long)m * g.ldc32 + n;
+            rin0[it] = *(const f32x4*)(g.C32 + o32);
+            rin1[it] = *(const f32x4*)(g.C32 + o32 + 4);
+          }
         }
       }
     };
@@ -398,8 +411,12 @@ __global__ __launch_bounds__(NT, T == 128 ? 3 : 1) void gemm_bf16_kernel(Bf16Des
             v1[e] = (m < g.n_true && n + 4 + e < g.n_true) ? ((m == n + 4 + e ? 1.0f : 0.0f) - v1[e]) : 0.0f;
             part += v0[e] * v0[e] + v1[e] * v1[e];
           }
-          *(f32x4*)(g.C32 + o32) = v0;
-          *(f32x4*)(g.C32 + o32 + 4) = v1;
+          if (!lean) {
+            *(f32x4*)(g.C32 + o32) = v0;
+            *(f32x4*)(g.C32 + o32 + 4) = v1;
+          } else if (tm == tn && m >= n && m < n + 8) {   // the diagonal entry of this row lies in these 8 columns
+            g.diag[(long long)b * g.strideDiag + m] = (m - n < 4) ? v0[(m - n) & 3] : v1[(m - n) & 3];
+          }
         } else {
           const f32x4 r0 = rin0[EPI == BEPI_POLYQ ? it : 0], r1 = rin1[EPI == BEPI_POLYQ ? it : 0];
 #pragma unroll
@@ -432,7 +449,7 @@ __global__ __launch_bounds__(NT, T == 128 ? 3 : 1) void gemm_bf16_kernel(Bf16Des
             t1[e] = strip[(rq * 8 + 4 + e) * SW + col];
           }
           const int mr = n0 + wn0 + col, nr = m0 + wm0 + i * 32 + rq * 8;   // mirrored position
-          if (EPI == BEPI_GRAM) {
+          if (EPI == BEPI_GRAM && !lean) {
             *(f32x4*)(g.C32 + b32 + (long long)mr * g.ldc32 + nr) = t0;
             *(f32x4*)(g.C32 + b32 + (long long)mr * g.ldc32 + nr + 4) = t1;
           }
@@ -591,6 +608,10 @@ int launch_t(const Bf16Desc& g, hipStream_t s) {
   if (g.M % T || g.N % T || g.K % BK || g.lda % 8 || g.ldb % 8) return PRISM_EINVAL;
   if ((g.M / T) * (g.N / T) * g.batch <= 0) return PRISM_EINVAL;
   if (g.sym && (g.M != g.N || g.A != g.B || g.A2)) return PRISM_EINVAL;
+  if ((g.epi == BEPI_GRAM || g.epi == BEPI_POLYQ || g.epi == BEPI_STORE) && !g.C32) {
+    // without the fp32 matrix: symmetric GRAM with a diagonal array, symmetric POLYQ with R in bf16
+    if (!g.sym || (g.epi == BEPI_GRAM && !g.diag) || (g.epi == BEPI_POLYQ && !g.Cin16) || g.epi == BEPI_STORE) return PRISM_EINVAL;
+  }
   switch (g.epi) {
     case BEPI_STORE: return launch_te<T, BEPI_STORE, false>(g, s);
     case BEPI_GRAM: return g.sym ? launch_te<T, BEPI_GRAM, true>(g, s) : launch_te<T, BEPI_GRAM, false>(g, s);

@@ -205,8 +205,10 @@ struct Run {
   template <typename T> T* at(size_t off) const { return (T*)(ws + off); }
 
   // sketch + chain V_j = R V_{j-1} (fp32 matrix cores, skinny N = padded sketch width)
-  // Rb: bf16 copy of R (bf16 polar path): the products then read it instead of R, except the diagonal
-  int chain(const float* R, int k, const uint16_t* Rb = nullptr) {
+  // Rb: bf16 copy of R (bf16 polar path): the products then read it instead of R, except the diagonal,
+  // which comes from D (entry i of matrix b at D[b * strideD + i * ldd])
+  int chain(const float* R, int k, const uint16_t* Rb = nullptr, const float* D = nullptr, long long strideD = 0,
+            int ldd = 0) {
     const int Sp = P.Sp, ld = P.ld;
     const long long vs = (long long)P.batch * Sp * ld;
     for (int j = 1; j <= P.nv; ++j) {
@@ -214,8 +216,8 @@ struct Run {
       const long long sin = (j == 1) ? 0 : (long long)Sp * ld;
       ProfScope ps(PK_CHAIN, s);
       if (Rb)
-        CHECK_LAUNCH(launch_chain_bf16(Rb, R, (long long)Sp * Sp, Sp, vin, sin, v + (j - 1) * vs, (long long)Sp * ld, Sp,
-                                       ld, P.batch, ctrl, s));
+        CHECK_LAUNCH(launch_chain_bf16(Rb, (long long)Sp * Sp, Sp, D, strideD, ldd, vin, sin, v + (j - 1) * vs,
+                                       (long long)Sp * ld, Sp, ld, P.batch, ctrl, s));
       else
         CHECK_LAUNCH(launch_chain(R, (long long)Sp * Sp, Sp, vin, sin, v + (j - 1) * vs, (long long)Sp * ld, Sp, ld,
                                   P.batch, ctrl, s));
@@ -340,6 +342,15 @@ int run_polar_bf16(Run& r) {
   static const int keep_split = getenv("PRISM_BF16_KEEP_SPLIT") ? atoi(getenv("PRISM_BF16_KEEP_SPLIT")) : 0;
   static const int no_dual = getenv("PRISM_BF16_NO_DUAL") ? atoi(getenv("PRISM_BF16_NO_DUAL")) : 0;
   static const int chain_f32 = getenv("PRISM_BF16_CHAIN_F32") ? atoi(getenv("PRISM_BF16_CHAIN_F32")) : 0;
+  // The fit can read the bf16 copy of R (plus its exact diagonal) when the chain kernels take the
+  // shape; with symmetric tiles the fp32 matrix is then not written at all: the Gram epilogue
+  // stores the bf16 copy and the diagonal (at the head of the buffer of R), R^2 reads the copy.
+  // Only with the plain bf16 iterate: with the split one the linear term of Q = R/2 + alpha R^2 keeps
+  // the fp32 R (taking it from the bf16 copy raises the residual floor by a few 1e-4, which at
+  // tol = 1e-2 cost the reduced config-3 case one more iteration than the oracle).
+  const bool chain_b = !chain_f32 && (P.p_s == 0 || chain_bf16_supported(Sp, P.ld, P.batch, Sp));
+  const bool lean = chain_b && sym && !P.split;
+  float* Dg = R;
   const int ntg = Sp / Tg;
   const int nparts = sym ? ntg * (ntg + 1) / 2 : ntg * ntg;
   int cur = 0;
@@ -349,10 +360,15 @@ int run_polar_bf16(Run& r) {
     g.sym = sym;
     g.A = Xg[cur]; g.strideA = LS; g.lda = Lp; g.B = Xg[cur]; g.strideB = LS; g.ldb = Lp;
     g.M = Sp; g.N = Sp; g.K = Lp; g.batch = P.batch; g.epi = BEPI_GRAM; g.n_true = P.S;
-    g.C32 = R; g.strideC32 = SS; g.ldc32 = Sp; g.Cb = Rb; g.strideCb = SS; g.ldcb = Sp;
+    g.C32 = lean ? nullptr : R; g.strideC32 = SS; g.ldc32 = Sp; g.Cb = Rb; g.strideCb = SS; g.ldcb = Sp;
+    g.diag = lean ? Dg : nullptr; g.strideDiag = Sp;
     g.rho_part = r.rho; g.ctrl = r.ctrl;
     { ProfScope ps(PK_BF16_GRAM, r.s); CHECK_LAUNCH(launch_gemm_bf16(g, Tg, r.s)); }
-    if (r.fit_needed(k)) CHECK_LAUNCH(r.chain(R, k, chain_f32 ? nullptr : Rb));
+    if (r.fit_needed(k)) {
+      if (lean) CHECK_LAUNCH(r.chain(R, k, Rb, Dg, Sp, 1));
+      else if (chain_b) CHECK_LAUNCH(r.chain(R, k, Rb, R, SS, Sp + 1));
+      else CHECK_LAUNCH(r.chain(R, k));
+    }
     CHECK_LAUNCH(r.solve(k, nparts));
     if (k == r.max_iters) break;
     const uint16_t* Bop = Rb;
@@ -360,7 +376,8 @@ int run_polar_bf16(Run& r) {
       Bf16Desc q = {};
       q.A = Rb; q.strideA = SS; q.lda = Sp; q.B = Rb; q.strideB = SS; q.ldb = Sp;
       q.M = Sp; q.N = Sp; q.K = Sp; q.batch = P.batch; q.epi = BEPI_POLYQ; q.sym = sym;
-      q.C32 = R; q.strideC32 = SS; q.ldc32 = Sp; q.Cb = Qb; q.strideCb = SS; q.ldcb = Sp; q.c1 = 0.5f;
+      q.C32 = lean ? nullptr : R; q.strideC32 = SS; q.ldc32 = Sp; q.Cb = Qb; q.strideCb = SS; q.ldcb = Sp; q.c1 = 0.5f;
+      q.Cin16 = lean ? Rb : nullptr;
       q.ctrl = r.ctrl;
       { ProfScope ps(PK_BF16_POLYQ, r.s); CHECK_LAUNCH(launch_gemm_bf16(q, Tq, r.s)); }
       Bop = Qb;
@@ -854,8 +871,9 @@ int prism_chain_product_bf16(const uint16_t* Rb, const float* R, const float* V,
                              void* stream) {
   set_last_error("");
   if (!Rb || !R || !V || !out) return PRISM_EINVAL;
-  return launch_chain_bf16(Rb, R, (long long)n * n, n, V, (long long)n * ld, out, (long long)n * ld, n, ld, batch, nullptr,
-                           (hipStream_t)stream);
+  if (!chain_bf16_supported(n, ld, batch, n)) return PRISM_EUNSUPPORTED;
+  return launch_chain_bf16(Rb, (long long)n * n, n, R, (long long)n * n, n + 1, V, (long long)n * ld, out,
+                           (long long)n * ld, n, ld, batch, nullptr, (hipStream_t)stream);
 }
 
 int prism_gemm_f32(const float* A, const float* B, float* C, int batch, int M, int N, int K, int a_km, void* stream) {
