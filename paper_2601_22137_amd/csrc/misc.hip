@@ -273,6 +273,7 @@ __global__ __launch_bounds__(NT) void finalize_bf16_kernel(FinalArgs a) {
   if (i >= nvec) return;
   const int r = (int)(i / vec_per_row), col = (int)(i % vec_per_row) * 8;
   const unsigned short* srcm = a.transpose ? a.Xg[par] : a.Xa_hi[par];
+  if (srcm == (const unsigned short*)a.dst) return;   // the caller's array was that iterate buffer: already in place
   const int ld = a.transpose ? a.Lp : a.Sp;
   const u32x4 v = *(const u32x4*)(srcm + (long long)b * a.Lp * a.Sp + (long long)r * ld + col);
   *(u32x4*)((unsigned short*)a.dst + (long long)b * a.m * a.n + (long long)r * a.n + col) = v;

@@ -201,6 +201,11 @@ struct Run {
   int first_fit;                       // first update whose coefficient is fitted
   double tol;
   uint64_t seed;
+  // bf16 polar, plain iterate, no padding: the caller's array serves as the odd one of the two
+  // iterate buffers that has its orientation (the input is consumed by the prepare step before the
+  // first update writes there), so that after an odd number of updates the result is in place
+  uint16_t* out_as_xhi1 = nullptr;
+  uint16_t* out_as_xg1 = nullptr;
 
   template <typename T> T* at(size_t off) const { return (T*)(ws + off); }
 
@@ -333,9 +338,9 @@ int run_polar_bf16(Run& r) {
   const int Tq = Tg, Ta = bf16_tile(P, Lp, Sp, Sp, false);
   if (P.tile == 256 && P.shared_gpu && bf16_tile_forced() == 0) Tg = 256;
   const long long SS = (long long)Sp * Sp, LS = (long long)Lp * Sp;
-  uint16_t* Xhi[2] = {r.at<uint16_t>(P.o_xhi[0]), r.at<uint16_t>(P.o_xhi[1])};
+  uint16_t* Xhi[2] = {r.at<uint16_t>(P.o_xhi[0]), r.out_as_xhi1 ? r.out_as_xhi1 : r.at<uint16_t>(P.o_xhi[1])};
   uint16_t* Xlo[2] = {P.split ? r.at<uint16_t>(P.o_xlo[0]) : nullptr, P.split ? r.at<uint16_t>(P.o_xlo[1]) : nullptr};
-  uint16_t* Xg[2] = {r.at<uint16_t>(P.o_xg[0]), r.at<uint16_t>(P.o_xg[1])};
+  uint16_t* Xg[2] = {r.at<uint16_t>(P.o_xg[0]), r.out_as_xg1 ? r.out_as_xg1 : r.at<uint16_t>(P.o_xg[1])};
   float* R = r.at<float>(P.o_r);
   uint16_t* Rb = r.at<uint16_t>(P.o_rb);
   uint16_t* Qb = P.d == 2 ? r.at<uint16_t>(P.o_qb) : nullptr;
@@ -620,10 +625,14 @@ int run(int fn, void* a, void* inv_out, int root_p, int batch, int m, int n, int
   if (dt == PRISM_BF16) {
     pa.Xa_hi = r.at<uint16_t>(P.o_xhi[0]); pa.Xa_lo = P.split ? r.at<uint16_t>(P.o_xlo[0]) : nullptr;
     pa.Xg = r.at<uint16_t>(P.o_xg[0]);
+    static const int no_alias = getenv("PRISM_BF16_NO_OUTPUT_ALIAS") ? atoi(getenv("PRISM_BF16_NO_OUTPUT_ALIAS")) : 0;
+    if (!P.split && P.Sp == P.S && P.Lp == P.L && !no_alias) {
+      if (P.transpose) r.out_as_xg1 = (uint16_t*)a; else r.out_as_xhi1 = (uint16_t*)a;
+    }
     for (int i = 0; i < 2; ++i) {
-      fa.Xa_hi[i] = r.at<uint16_t>(P.o_xhi[i]);
+      fa.Xa_hi[i] = (i == 1 && r.out_as_xhi1) ? r.out_as_xhi1 : r.at<uint16_t>(P.o_xhi[i]);
       fa.Xa_lo[i] = P.split ? r.at<uint16_t>(P.o_xlo[i]) : nullptr;
-      fa.Xg[i] = r.at<uint16_t>(P.o_xg[i]);
+      fa.Xg[i] = (i == 1 && r.out_as_xg1) ? r.out_as_xg1 : r.at<uint16_t>(P.o_xg[i]);
     }
   } else {
     pa.X32 = r.at<float>(P.o_x[0]);

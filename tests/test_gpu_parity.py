@@ -221,6 +221,29 @@ def test_degenerate_matrices_are_reported_and_left_alone(prism):
     assert _rel(out[0], ref) <= TOL_F32
 
 
+@pytest.mark.parametrize("budget", [4, 5])
+@pytest.mark.parametrize("shape", [(256, 128), (128, 256), (768, 768)])
+def test_bf16_plain_iterate_in_place_buffers(prism, shape, budget):
+    """Unpadded shapes with the plain bf16 iterate: the caller's array doubles as one of the two
+    iterate buffers.  After an odd number of updates the result is already in place, after an even
+    number it is copied there; a zero or non-finite matrix of the batch must come back untouched."""
+    m, n = shape
+    A = np.concatenate([W.c1_polar_small(m=m, n=n, data_seed=1300 + i) for i in range(4)])
+    A[1] = 0.0
+    A[2, 1, 2] = np.inf
+    bits = W.to_bf16_bits(A)
+    x = _bf16_tensor(bits.copy())
+    info = prism.polar(x, 5, budget, 8, SEED, 0.0, flags=prism.FLAG_BF16_PLAIN_ITERATE).read()
+    out_bits = x.view(torch.int16).cpu().numpy().view(np.uint16)
+    assert list(info["status"]) == [prism.INFO_BUDGET, prism.INFO_ZERO, prism.INFO_NONFINITE, prism.INFO_BUDGET]
+    assert np.array_equal(out_bits[1], bits[1]) and np.array_equal(out_bits[2], bits[2])
+    out = _bf16_to_f64(x)
+    for i in (0, 3):
+        ref, oinfo = O.polar(W.from_bf16_bits(bits[i]), 5, budget, 8, SEED, 0.0)
+        assert info[i]["iters"] == budget
+        assert _rel(out[i], ref) <= TOL_BF16
+
+
 def test_batch_position_does_not_matter(prism):
     """All matrices of a call share S_k, so results do not depend on the position in the batch."""
     A = np.concatenate([W.c1_polar_small(data_seed=s) for s in (1, 2, 3)], axis=0)
