@@ -17,7 +17,11 @@
  *
  * Conventions common to all entry points
  *   - Every matrix pointer is a DEVICE pointer to row-major, contiguous,
- *     batch-strided data: x[batch][m][n].  The caller owns all of it.
+ *     batch-strided data: x[batch][m][n].  The caller owns all of it.  Alignment
+ *     to the element size is enough; bf16 arrays aligned to 16 bytes are copied
+ *     in and out with vector accesses, and a 256-byte aligned bf16 array whose
+ *     sides are tile multiples may be used as scratch for intermediate iterates
+ *     between the moment its input has been read and the end of the call.
  *   - `dt` is the storage type of the caller's matrices.  PRISM_F32 computes
  *     with fp32 matrix instructions (the inverse-root recurrence for M_k in
  *     fp64); PRISM_BF16 computes with bf16 matrix instructions accumulating in

@@ -4,6 +4,8 @@
 // un-scaling / copy-out (A^{1/2} = sqrt(s) X, A^{-1/2} = Y / sqrt(s)).  Matrix sign (Section 4)
 // starts like the polar factor; the Chebyshev inverse (App. A.4) keeps A_s = A / ||A||_F, starts
 // from X_0 = A_s^T and returns X / ||A||_F.
+#include <cstdint>
+
 #include "common.h"
 
 namespace prism {
@@ -334,12 +336,12 @@ void launch_sumsq(const PrepArgs& a, hipStream_t s) {
   hipLaunchKernelGGL(sumsq_kernel, dim3(a.nsum, a.batch), dim3(NT), 0, s, a);
 }
 
-static bool bf16_vector_path(int fn, int dt, int m, int n) {
-  return fn == PRISM_FN_POLAR && dt == PRISM_BF16 && m % 8 == 0 && n % 8 == 0;
+static bool bf16_vector_path(int fn, int dt, int m, int n, const void* user) {
+  return fn == PRISM_FN_POLAR && dt == PRISM_BF16 && m % 8 == 0 && n % 8 == 0 && ((uintptr_t)user & 15) == 0;
 }
 
 void launch_prepare(const PrepArgs& a, hipStream_t s) {
-  if (bf16_vector_path(a.fn, a.dt, a.m, a.n)) {
+  if (bf16_vector_path(a.fn, a.dt, a.m, a.n, a.src)) {
     // tiles over the padded caller-oriented matrix, so that the padding is written too
     const int tiles = (a.Lp / 64) * (a.Sp / 64);
     hipLaunchKernelGGL(prepare_bf16_kernel, dim3(tiles, a.batch), dim3(NT), 0, s, a);
@@ -350,7 +352,7 @@ void launch_prepare(const PrepArgs& a, hipStream_t s) {
 }
 
 void launch_finalize(const FinalArgs& a, hipStream_t s) {
-  if (bf16_vector_path(a.fn, a.dt, a.m, a.n)) {
+  if (bf16_vector_path(a.fn, a.dt, a.m, a.n, a.dst)) {
     const long long nvec = (long long)a.m * (a.n / 8);
     hipLaunchKernelGGL(finalize_bf16_kernel, dim3((unsigned)((nvec + NT - 1) / NT), a.batch), dim3(NT), 0, s, a);
     return;

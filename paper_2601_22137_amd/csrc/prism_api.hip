@@ -3,6 +3,7 @@
 // the caller's stream: the whole budget of iterations is enqueued up front and each kernel
 // skips matrices whose `done` flag the on-device solve step has set, so there is no host
 // round trip per iteration.
+#include <cstdint>
 #include <cstdlib>
 #include <map>
 #include <mutex>
@@ -626,7 +627,7 @@ int run(int fn, void* a, void* inv_out, int root_p, int batch, int m, int n, int
     pa.Xa_hi = r.at<uint16_t>(P.o_xhi[0]); pa.Xa_lo = P.split ? r.at<uint16_t>(P.o_xlo[0]) : nullptr;
     pa.Xg = r.at<uint16_t>(P.o_xg[0]);
     static const int no_alias = getenv("PRISM_BF16_NO_OUTPUT_ALIAS") ? atoi(getenv("PRISM_BF16_NO_OUTPUT_ALIAS")) : 0;
-    if (!P.split && P.Sp == P.S && P.Lp == P.L && !no_alias) {
+    if (!P.split && P.Sp == P.S && P.Lp == P.L && !no_alias && ((uintptr_t)a & 255) == 0) {   // aligned like the workspace buffers
       if (P.transpose) r.out_as_xg1 = (uint16_t*)a; else r.out_as_xhi1 = (uint16_t*)a;
     }
     for (int i = 0; i < 2; ++i) {

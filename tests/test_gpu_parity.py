@@ -308,3 +308,19 @@ def test_call_replays_from_a_hip_graph(prism):
             info = handle.read()
             assert info[0]["iters"] == info_eager[0]["iters"] and info[0]["status"] == info_eager[0]["status"]
             assert np.array_equal(info[0]["alpha"], info_eager[0]["alpha"])
+
+
+def test_bf16_polar_on_a_misaligned_array(prism):
+    """A caller's array that starts 2 bytes off a 16-byte boundary: copied in and out element by
+    element, never used as an iterate buffer; same result as the aligned call."""
+    A = W.c1_polar_small(m=256, n=128, data_seed=1400)
+    bits = W.to_bf16_bits(A)
+    aligned = _bf16_tensor(bits.copy())
+    prism.polar(aligned, 5, 5, 8, SEED, 0.0, flags=prism.FLAG_BF16_PLAIN_ITERATE)
+    store = torch.zeros(256 * 128 + 8, dtype=torch.bfloat16, device="cuda")
+    off = store[1:1 + 256 * 128].view(1, 256, 128)
+    assert off.data_ptr() % 16 == 2
+    off.copy_(_bf16_tensor(bits.copy()))
+    prism.polar(off, 5, 5, 8, SEED, 0.0, flags=prism.FLAG_BF16_PLAIN_ITERATE)
+    assert torch.equal(off.view(torch.int16), aligned.view(torch.int16))
+    assert float(store[0]) == 0.0 and float(store[-1]) == 0.0
