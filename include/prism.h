@@ -43,7 +43,9 @@
  *     Numerical outcomes are reported per matrix in prism_info.status.
  *   - Unless a workspace is passed through prism_options, the library keeps
  *     one grow-only device workspace per (device, stream); calls that share
- *     it must be ordered on that stream.
+ *     it must be ordered on that stream.  A block that a larger call outgrows
+ *     stays allocated (earlier work and captured HIP graphs still point into
+ *     it) until prism_release_workspaces().
  *   - A matrix whose info.status is PRISM_INFO_NONFINITE or PRISM_INFO_ZERO is
  *     left untouched.
  */
@@ -119,6 +121,10 @@ typedef struct {
                                 * fixed-coefficient schemes run through the same kernels this way */
   int32_t schedule_len;   /* 0 <= schedule_len <= PRISM_MAX_ITERS */
 } prism_options;
+
+/* Frees every cached workspace of the calling process (all devices and streams).  The caller guarantees that no call of the library is in flight and that
+ * no HIP graph captured from one will be launched again.  The next call allocates anew. */
+int prism_release_workspaces(void);
 
 /* Device bytes a call with these arguments needs (host-only computation). */
 int prism_workspace_bytes(int fn, int batch, int m, int n, prism_dtype dt, int degree,

@@ -147,8 +147,10 @@ int make_plan(Plan& P, int fn, int batch, int m, int n, int dt, int degree, int 
   return PRISM_OK;
 }
 
-// grow-only workspace per (device, stream)
-struct Cached { void* ptr = nullptr; size_t bytes = 0; };
+// Grow-only workspace per (device, stream).  A block that has become too small is kept until
+// prism_release_workspaces(): work enqueued earlier, and HIP graphs captured from earlier calls,
+// still hold its address.
+struct Cached { void* ptr = nullptr; size_t bytes = 0; std::vector<void*> retired; };
 std::mutex g_mu;
 std::map<std::pair<int, void*>, Cached> g_cache;
 
@@ -163,13 +165,14 @@ int get_workspace(size_t bytes, hipStream_t stream, const prism_options* opt, ch
   std::lock_guard<std::mutex> lock(g_mu);
   Cached& c = g_cache[std::make_pair(dev, (void*)stream)];
   if (c.bytes < bytes) {
-    if (c.ptr) { (void)hipFree(c.ptr); c.ptr = nullptr; c.bytes = 0; }
-    if (hipMalloc(&c.ptr, bytes) != hipSuccess) {
+    void* fresh = nullptr;
+    if (hipMalloc(&fresh, bytes) != hipSuccess) {
       (void)hipGetLastError();
       set_last_error("hipMalloc of the workspace failed");
-      c.ptr = nullptr;
       return PRISM_ENOMEM;
     }
+    if (c.ptr) c.retired.push_back(c.ptr);
+    c.ptr = fresh;
     c.bytes = bytes;
   }
   *out = (char*)c.ptr;
@@ -761,6 +764,23 @@ using namespace prism;
 extern "C" {
 
 const char* prism_last_error(void) { return g_last_error.c_str(); }
+
+int prism_release_workspaces(void) {
+  set_last_error("");
+  std::lock_guard<std::mutex> lock(g_mu);
+  int rc = PRISM_OK, current = 0;
+  const bool have_current = hipGetDevice(&current) == hipSuccess;
+  for (auto& kv : g_cache) {
+    if (hipSetDevice(kv.first.first) != hipSuccess) { rc = PRISM_EHIP; continue; }
+    for (void* p : kv.second.retired)
+      if (hipFree(p) != hipSuccess) rc = PRISM_EHIP;
+    if (kv.second.ptr && hipFree(kv.second.ptr) != hipSuccess) rc = PRISM_EHIP;
+  }
+  g_cache.clear();
+  if (have_current) (void)hipSetDevice(current);
+  if (rc != PRISM_OK) { (void)hipGetLastError(); set_last_error("hipFree of a cached workspace failed"); }
+  return rc;
+}
 
 int prism_profile_enable(int on) {
   for (auto& r : g_prof) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }

@@ -23,7 +23,7 @@ INFO_CONVERGED, INFO_BUDGET, INFO_NONFINITE, INFO_ZERO, INFO_DIVERGED = 0, 1, 2,
 INFO_DTYPE = np.dtype([("iters", np.int32), ("status", np.int32),
                        ("residual", np.float32, (MAX_ITERS + 1,)), ("alpha", np.float32, (MAX_ITERS,))])
 
-EXPORTS = ("prism_workspace_bytes", "prism_polar", "prism_polar_ex", "prism_sqrt", "prism_sqrt_ex",
+EXPORTS = ("prism_workspace_bytes", "prism_release_workspaces", "prism_polar", "prism_polar_ex", "prism_sqrt", "prism_sqrt_ex",
            "prism_inv_root", "prism_inv_root_ex", "prism_sign", "prism_sign_ex", "prism_inverse", "prism_inverse_ex", "prism_sqrt_newton", "prism_sqrt_newton_ex", "prism_spd_inverse", "prism_run_grouped",
            "prism_sketch", "prism_gauss_parts", "prism_chain_product", "prism_chain_product_bf16", "prism_gemm_f32",
            "prism_gemm_f64a", "prism_gemm_bf16_nt", "prism_profile_enable", "prism_profile_collect",
@@ -261,6 +261,12 @@ def chain_product(R, V):
     out = torch.empty_like(V)
     _check(lib().prism_chain_product(R.data_ptr(), V.data_ptr(), out.data_ptr(), batch, n, ld, _stream()))
     return out
+
+
+def release_workspaces():
+    """Free the library's cached workspaces (nothing may be in flight, no captured graph may be replayed)."""
+    torch.cuda.synchronize()
+    _check(lib().prism_release_workspaces())
 
 
 def chain_product_bf16(Rb, R, V):

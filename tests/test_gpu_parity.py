@@ -324,3 +324,34 @@ def test_bf16_polar_on_a_misaligned_array(prism):
     prism.polar(off, 5, 5, 8, SEED, 0.0, flags=prism.FLAG_BF16_PLAIN_ITERATE)
     assert torch.equal(off.view(torch.int16), aligned.view(torch.int16))
     assert float(store[0]) == 0.0 and float(store[-1]) == 0.0
+
+
+def test_cached_workspace_outlives_growth(prism):
+    """A graph captured from a call that used the cached workspace of its stream keeps working after
+    a larger call on the same stream has made that workspace grow (the outgrown block is kept until
+    release_workspaces), and the library allocates anew after a release."""
+    A = W.c1_polar_small(m=96, n=64)
+    src = torch.from_numpy(A.copy()).cuda()
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        x = src.clone()
+        prism.polar(x, 5, 20, 8, SEED, 1e-6)                    # creates the stream's workspace
+        side.synchronize()
+        eager = x.clone()
+        x.copy_(src)
+        with torch.cuda.graph(graph, stream=side):
+            prism.polar(x, 5, 20, 8, SEED, 1e-6)
+        big = torch.from_numpy(W.c1_polar_small(m=640, n=512, data_seed=7).copy()).cuda()
+        prism.polar(big, 5, 5, 8, SEED, 0.0)                    # needs more: the cached block is replaced
+        side.synchronize()
+        x.copy_(src)
+        graph.replay()
+        side.synchronize()
+        assert torch.equal(x, eager)
+    del graph
+    prism.release_workspaces()
+    y = src.clone()
+    prism.polar(y, 5, 20, 8, SEED, 1e-6)
+    torch.cuda.synchronize()
+    assert torch.equal(y, eager)
