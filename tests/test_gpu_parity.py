@@ -355,3 +355,21 @@ def test_cached_workspace_outlives_growth(prism):
     prism.polar(y, 5, 20, 8, SEED, 1e-6)
     torch.cuda.synchronize()
     assert torch.equal(y, eager)
+
+
+@pytest.mark.parametrize("batch,m,n,p_s", [(2, 256, 192, 40), (100, 200, 192, 16), (90, 192, 192, 8)])
+def test_polar_bf16_fit_falls_back_to_the_fp32_residual(prism, batch, m, n, p_s):
+    """Sketches wider than 32 columns, and large batches whose Gram size is no multiple of 128, are
+    shapes the bf16 chain kernels do not take: the fit then reads the fp32 residual matrix, which
+    the Gram epilogue keeps writing in that case."""
+    A = np.concatenate([W.c1_polar_small(m=m, n=n, data_seed=1500 + (i % 3)) for i in range(batch)])
+    bits = W.to_bf16_bits(A)
+    for flags in (0, prism.FLAG_BF16_PLAIN_ITERATE):
+        x = _bf16_tensor(bits.copy())
+        info = prism.polar(x, 5, 6, p_s, SEED, 0.0, flags=flags).read()
+        out = _bf16_to_f64(x)
+        for i in (0, 1, batch - 1):
+            ref, oinfo = O.polar(W.from_bf16_bits(bits[i]), 5, 6, p_s, SEED, 0.0)
+            assert info[i]["iters"] == 6
+            assert _rel(out[i], ref) <= TOL_BF16
+            np.testing.assert_allclose(info[i]["alpha"][:6], oinfo["alpha"], atol=3e-2)
