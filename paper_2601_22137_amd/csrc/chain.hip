@@ -444,6 +444,52 @@ __global__ __launch_bounds__(NT, 2) void chain_small_kernel(const typename RFrag
   }
 }
 
+// Matrices of order 64 (after padding): the whole chain V_1 .. V_nv in one launch, one workgroup per
+// matrix with R and the current V in LDS.  At this size a product is a few hundred FMAs per thread
+// and a call is bound by the number of launches, of which this removes nv - 1 per iteration.
+// Thread (row, group of 4 columns): 64 x LD / 4 tasks over 256 threads.
+template <int LD>
+__global__ __launch_bounds__(NT) void chain_tiny_kernel(const float* __restrict__ R, long long strideR, int ldr,
+                                                       const float* __restrict__ V0, long long strideV0,
+                                                       float* __restrict__ Vout, long long strideJ, long long strideB,
+                                                       int nv, const Ctrl* __restrict__ ctrl) {
+  constexpr int N = 64;
+  constexpr int TASKS = N * LD / 4, T_IT = TASKS / NT;
+  static_assert(TASKS % NT == 0, "sketch width");
+  __shared__ float Rs[N][N + 1];
+  __shared__ __align__(16) float Vs[2][N][LD];
+  const int b = blockIdx.x, t = threadIdx.x;
+  if (ctrl && ctrl[b].done) return;
+  for (int idx = t; idx < N * N; idx += NT) Rs[idx / N][idx % N] = R[(long long)b * strideR + (long long)(idx / N) * ldr + idx % N];
+  for (int idx = t; idx < N * LD / 4; idx += NT)
+    *(f32x4*)&Vs[0][idx / (LD / 4)][(idx % (LD / 4)) * 4] = *(const f32x4*)(V0 + (long long)b * strideV0 + (long long)idx * 4);
+  __syncthreads();
+  int cur = 0;
+  for (int j = 0; j < nv; ++j) {
+    f32x4 acc[T_IT];
+#pragma unroll
+    for (int it = 0; it < T_IT; ++it) {
+      const int task = t + it * NT, row = task / (LD / 4), c4 = (task % (LD / 4)) * 4;
+      f32x4 a = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll 8
+      for (int k = 0; k < N; ++k) {
+        const float r = Rs[row][k];
+        const f32x4 v = *(const f32x4*)&Vs[cur][k][c4];
+        a[0] = fmaf(r, v[0], a[0]); a[1] = fmaf(r, v[1], a[1]); a[2] = fmaf(r, v[2], a[2]); a[3] = fmaf(r, v[3], a[3]);
+      }
+      acc[it] = a;
+    }
+#pragma unroll
+    for (int it = 0; it < T_IT; ++it) {
+      const int task = t + it * NT, row = task / (LD / 4), c4 = (task % (LD / 4)) * 4;
+      *(f32x4*)&Vs[cur ^ 1][row][c4] = acc[it];
+      *(f32x4*)(Vout + (long long)j * strideJ + (long long)b * strideB + (long long)row * LD + c4) = acc[it];
+    }
+    __syncthreads();
+    cur ^= 1;
+  }
+}
+
 template <bool RB>
 int launch_chain_t(const typename RFrag<RB>::elem* R, long long strideR, int ldr, const float* R32, long long strideR32,
                    int ldr32, const float* Vin, long long strideVin, float* Vout, long long strideVout, int n, int ld,
@@ -479,6 +525,18 @@ int launch_chain_t(const typename RFrag<RB>::elem* R, long long strideR, int ldr
 int launch_chain(const float* R, long long strideR, int ldr, const float* Vin, long long strideVin, float* Vout,
                  long long strideVout, int n, int ld, int batch, const Ctrl* ctrl, hipStream_t s) {
   return launch_chain_t<false>(R, strideR, ldr, nullptr, 0, 0, Vin, strideVin, Vout, strideVout, n, ld, batch, ctrl, s);
+}
+
+// V_j = R V_{j-1}, j = 1 .. nv, for matrices of order 64: V0 [64][ld] per matrix (strideV0 may be 0),
+// Vout[j - 1] at Vout + (j - 1) * strideJ + b * strideB
+int launch_chain_tiny(const float* R, long long strideR, int ldr, const float* V0, long long strideV0, float* Vout,
+                      long long strideJ, long long strideB, int nv, int ld, int batch, const Ctrl* ctrl, hipStream_t s) {
+  if (batch <= 0 || nv <= 0) return PRISM_EINVAL;
+  if (ld == 16) hipLaunchKernelGGL(chain_tiny_kernel<16>, dim3(batch), dim3(NT), 0, s, R, strideR, ldr, V0, strideV0, Vout, strideJ, strideB, nv, ctrl);
+  else if (ld == 32) hipLaunchKernelGGL(chain_tiny_kernel<32>, dim3(batch), dim3(NT), 0, s, R, strideR, ldr, V0, strideV0, Vout, strideJ, strideB, nv, ctrl);
+  else if (ld == 64) hipLaunchKernelGGL(chain_tiny_kernel<64>, dim3(batch), dim3(NT), 0, s, R, strideR, ldr, V0, strideV0, Vout, strideJ, strideB, nv, ctrl);
+  else return PRISM_EINVAL;
+  return hipGetLastError() == hipSuccess ? PRISM_OK : PRISM_EHIP;
 }
 
 // Shapes the bf16 kernels take: sketch width up to 32, rows of Rb in 16-byte loads, and K in chunks

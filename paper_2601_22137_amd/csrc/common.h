@@ -109,6 +109,8 @@ int launch_chain(const float* R, long long strideR, int ldr, const float* Vin, l
                  long long strideVout, int n, int ld, int batch, const Ctrl* ctrl, hipStream_t s);
 // Rb: bf16 copy of R [batch][n][ldr]; D: its exact fp32 diagonal, entry i of matrix b at D[b * strideD + i * ldd]
 // (ldd = ld of R + 1 reads it out of the full fp32 matrix, ldd = 1 out of a compact array)
+int launch_chain_tiny(const float* R, long long strideR, int ldr, const float* V0, long long strideV0, float* Vout,
+                      long long strideJ, long long strideB, int nv, int ld, int batch, const Ctrl* ctrl, hipStream_t s);
 bool chain_bf16_supported(int n, int ld, int batch, int ldr);
 int launch_chain_bf16(const unsigned short* Rb, long long strideR, int ldr, const float* D, long long strideD, int ldd,
                       const float* Vin, long long strideVin, float* Vout, long long strideVout, int n, int ld, int batch,

@@ -220,6 +220,11 @@ struct Run {
             int ldd = 0) {
     const int Sp = P.Sp, ld = P.ld;
     const long long vs = (long long)P.batch * Sp * ld;
+    if (Sp == 64 && !Rb) {   // whole chain in one launch
+      ProfScope ps(PK_CHAIN, s);
+      return launch_chain_tiny(R, (long long)Sp * Sp, Sp, v0 + (long long)(k - first_fit) * Sp * ld, 0, v, vs,
+                               (long long)Sp * ld, P.nv, ld, P.batch, ctrl, s);
+    }
     for (int j = 1; j <= P.nv; ++j) {
       const float* vin = (j == 1) ? v0 + (long long)(k - first_fit) * Sp * ld : v + (j - 2) * vs;
       const long long sin = (j == 1) ? 0 : (long long)Sp * ld;
@@ -357,7 +362,7 @@ int run_polar_bf16(Run& r) {
   // Only with the plain bf16 iterate: with the split one the linear term of Q = R/2 + alpha R^2 keeps
   // the fp32 R (taking it from the bf16 copy raises the residual floor by a few 1e-4, which at
   // tol = 1e-2 cost the reduced config-3 case one more iteration than the oracle).
-  const bool chain_b = !chain_f32 && (P.p_s == 0 || chain_bf16_supported(Sp, P.ld, P.batch, Sp));
+  const bool chain_b = !chain_f32 && Sp > 64 && (P.p_s == 0 || chain_bf16_supported(Sp, P.ld, P.batch, Sp));   // order 64: one-launch fp32 chain
   const bool lean = chain_b && sym && !P.split;
   float* Dg = R;
   const int ntg = Sp / Tg;

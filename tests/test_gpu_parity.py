@@ -373,3 +373,24 @@ def test_polar_bf16_fit_falls_back_to_the_fp32_residual(prism, batch, m, n, p_s)
             assert info[i]["iters"] == 6
             assert _rel(out[i], ref) <= TOL_BF16
             np.testing.assert_allclose(info[i]["alpha"][:6], oinfo["alpha"], atol=3e-2)
+
+
+@pytest.mark.parametrize("p_s", [8, 20, 40])
+def test_order_64_chain_in_one_launch(prism, p_s):
+    """Matrices whose padded order is 64 take the one-launch chain kernel, for every sketch width
+    (16, 32, 64 columns) and for the inverse root's longer chain."""
+    A = np.concatenate([W.c1_polar_small(m=64, n=48, data_seed=1600 + i) for i in range(3)])
+    x = torch.from_numpy(A.copy()).cuda()
+    info = prism.polar(x, 5, 30, p_s, SEED, 1e-6).read()
+    out = x.cpu().numpy()
+    for i in range(3):
+        ref, oinfo = O.polar(A[i], 5, 30, p_s, SEED, 1e-6)
+        assert _rel(out[i], ref) <= TOL_F32
+        _check_info(info[i], oinfo, res_floor=2e-6, alpha_res_min=1e-3)
+    S = W.c4_shampoo_spd(n=56, batch=2)
+    y = torch.from_numpy(S.copy()).cuda()
+    info = prism.inv_root(y, 3, 40, p_s, SEED, 1e-5).read()
+    for i in range(2):
+        ref, oinfo = O.inv_root(S[i], 3, 40, p_s, SEED, 1e-5)
+        assert info[i]["iters"] == oinfo["iters"]
+        assert _rel(y.cpu().numpy()[i], ref) <= TOL_F32
