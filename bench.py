@@ -322,7 +322,8 @@ def main():
             threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
         except Exception:
             threads = len(os.sched_getaffinity(0))
-        per_group = {"c1": 1, "c2": 2, "c3": 1, "c4": 4, "c5": 1, "sign": 1, "inverse": 1, "sqrt-newton": 1}[wl.name]
+        # sample sized to 10-30 s of host work where one matrix takes long; config 2 is cheap enough for the whole batch
+        per_group = {"c1": 1, "c2": 16, "c3": 1, "c4": 8, "c5": 1, "sign": 2, "inverse": 2, "sqrt-newton": 1}[wl.name]
         if wl.name in ("c3", "c5") and wl.host[0].shape[1] > 2048:
             per_group = 1
         t_cpu, n_cpu, worst = 0.0, 0, 0.0
