@@ -230,7 +230,7 @@ int prism_chain_product(const float* R, const float* V, float* out, int batch, i
                         void* stream);
 /* The same product as the bf16 polar path takes it: the off-diagonal entries of R are read from
  * Rb, its copy in bf16 bit patterns (same shape), the diagonal from R itself:
- * out = (Rb + diag(R - Rb)) * V.  ld = 16 or 32, n a multiple of 64 (of 128 when (n / 64) * batch >= 256);
+ * out = (Rb + diag(R - Rb)) * V.  ld = 16 or 32, n a multiple of 64 (of 128 when (n / 64) * batch >= 128);
  * other shapes return PRISM_EUNSUPPORTED (the library then keeps to the fp32 matrix). */
 int prism_chain_product_bf16(const uint16_t* Rb, const float* R, const float* V, float* out, int batch,
                              int n, int ld, void* stream);

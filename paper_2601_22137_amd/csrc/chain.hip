@@ -22,6 +22,7 @@
 // to 1 in bf16 and would erase the factor (1 - xi) of the fit objective (Section 4.2), whereas
 // rounding the off-diagonal entries perturbs the fitted coefficient by ~1e-5 only.  The kernels
 // multiply by the bf16 matrix and add (r_ii - bf16(r_ii)) v_i afterwards.
+#include <cstdlib>
 #include <type_traits>
 
 #include "common.h"
@@ -490,13 +491,19 @@ __global__ __launch_bounds__(NT) void chain_tiny_kernel(const float* __restrict_
   }
 }
 
+// 64-row workgroups of a launch below which the 16-row kernel is taken
+constexpr int small_below(bool rb) { return rb ? 128 : 256; }
+
 template <bool RB>
 int launch_chain_t(const typename RFrag<RB>::elem* R, long long strideR, int ldr, const float* R32, long long strideR32,
                    int ldr32, const float* Vin, long long strideVin, float* Vout, long long strideVout, int n, int ld,
                    int batch, const Ctrl* ctrl, hipStream_t s) {
   if (n % KC || n % ROWS || ldr % 4 || batch <= 0) return PRISM_EINVAL;
-  // 64-row workgroups leave most CUs idle on small batches of small matrices: 16-row ones there
-  if (ld <= 32 && (long long)(n / ROWS) * batch < 256) {
+  // 64-row workgroups leave most CUs idle on small batches of small matrices: 16-row ones there.
+  // The bf16 kernels change over earlier: the 64-row one reads V once per 64 rows instead of once per
+  // 16 and, beside other kernels, leaves them more of the chip (config 2, 192 workgroups of 64 rows:
+  // 9.3 -> 7.5 us per launch and 3.55 -> 3.30 ms per step).
+  if (ld <= 32 && (long long)(n / ROWS) * batch < small_below(RB)) {
     const dim3 grid(n / 16, batch), block(NT);
     if (ld == 16) hipLaunchKernelGGL((chain_small_kernel<16, RB>), grid, block, 0, s, R, strideR, ldr, R32, strideR32, ldr32, Vin, strideVin, Vout, strideVout, n, ctrl);
     else hipLaunchKernelGGL((chain_small_kernel<32, RB>), grid, block, 0, s, R, strideR, ldr, R32, strideR32, ldr32, Vin, strideVin, Vout, strideVout, n, ctrl);
@@ -542,7 +549,7 @@ int launch_chain_tiny(const float* R, long long strideR, int ldr, const float* V
 // Shapes the bf16 kernels take: sketch width up to 32, rows of Rb in 16-byte loads, and K in chunks
 // of 128 unless the 16-row kernel applies.
 bool chain_bf16_supported(int n, int ld, int batch, int ldr) {
-  const bool small = ld <= 32 && (long long)(n / ROWS) * batch < 256;
+  const bool small = ld <= 32 && (long long)(n / ROWS) * batch < small_below(true);
   return (ld == 16 || ld == 32) && ldr % 8 == 0 && n % KC == 0 && (small || n % 128 == 0);
 }
 

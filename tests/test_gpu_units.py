@@ -34,11 +34,11 @@ def test_gemm_f32(prism, a_km, shape):
 
 
 @pytest.mark.parametrize("n,ld,batch", [(64, 16, 2), (192, 32, 2), (768, 16, 2), (1024, 32, 2), (4096, 32, 2),
-                                        (1024, 16, 16), (2048, 32, 8), (1152, 32, 15), (1088, 32, 16), (2048, 64, 2)])
+                                        (1024, 16, 16), (2048, 32, 8), (1152, 32, 15), (768, 16, 12), (1088, 32, 16), (2048, 64, 2)])
 def test_chain_product_bf16(prism, n, ld, batch):
     """Off-diagonal entries from the bf16 copy, diagonal from the fp32 matrix; R = I - small, the
     case in which a rounded diagonal would be wrong by more than the whole off-diagonal part.
-    Small batches take the 16-row kernel, (n / 64) * batch >= 256 the 64-row one (chunks of 128 k,
+    Small batches take the 16-row kernel, (n / 64) * batch >= 128 the 64-row one (chunks of 128 k,
     with and without a ragged last ring round); the widest sketch (ld = 64) and large batches of sizes
     that are no multiple of 128 are not taken (the library keeps to the fp32 matrix there)."""
     rng = np.random.default_rng(3 * n + ld)
@@ -49,7 +49,7 @@ def test_chain_product_bf16(prism, n, ld, batch):
     V = rng.standard_normal((batch, n, ld)).astype(np.float32)
     Rb = W.to_bf16_bits(R)
     rb_dev = torch.from_numpy(Rb.view(np.int16)).cuda()
-    small = ld <= 32 and (n // 64) * batch < 256
+    small = ld <= 32 and (n // 64) * batch < 128
     if ld == 64 or (not small and n % 128):
         with pytest.raises(prism.PrismError, match="UNSUPPORTED"):
             prism.chain_product_bf16(rb_dev, _dev(R), _dev(V))
