@@ -48,6 +48,14 @@
  *     it) until prism_release_workspaces().
  *   - A matrix whose info.status is PRISM_INFO_NONFINITE or PRISM_INFO_ZERO is
  *     left untouched.
+ *   - Empty input (batch, m or n equal to 0; a grouped call with no groups) is
+ *     valid: the other arguments are checked, nothing is enqueued, no pointer is
+ *     read (they may be NULL) and the call returns PRISM_OK.  Negative extents
+ *     are PRISM_EINVAL.
+ *   - Size limits: at most 2^31 - 1 entries per matrix, counted with both
+ *     sides rounded up to the next multiple of 256 (bf16 with min(m, n) >=
+ *     512), 128 or 64 (fp32 with min(m, n) <= 256), and batch <=
+ *     PRISM_MAX_BATCH matrices per call; beyond them PRISM_EUNSUPPORTED.
  */
 #ifndef PRISM_H
 #define PRISM_H
@@ -62,6 +70,7 @@ extern "C" {
 #define PRISM_MAX_ITERS 64
 #define PRISM_MAX_SKETCH 64
 #define PRISM_MAX_ROOT 8
+#define PRISM_MAX_BATCH 65535 /* matrices per call (per group of a grouped call) */
 
 typedef enum { PRISM_F32 = 0, PRISM_BF16 = 1 } prism_dtype;
 

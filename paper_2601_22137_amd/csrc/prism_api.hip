@@ -70,7 +70,8 @@ int make_plan(Plan& P, int fn, int batch, int m, int n, int dt, int degree, int 
   if (fn != PRISM_FN_POLAR && m != n) return PRISM_EINVAL;
   if (fn == PRISM_FN_INV_ROOT && (root_p < 1 || root_p > PRISM_MAX_ROOT || degree != 3)) return PRISM_EINVAL;
   if (fn != PRISM_FN_POLAR && dt == PRISM_BF16) return PRISM_EUNSUPPORTED;
-  if ((long long)m * n > (1ll << 31) - 1) return PRISM_EUNSUPPORTED;
+  if ((long long)m * n > (1ll << 31) - 1) { set_last_error("a matrix may hold at most 2^31 - 1 entries"); return PRISM_EUNSUPPORTED; }
+  if (batch > PRISM_MAX_BATCH) { set_last_error("more than PRISM_MAX_BATCH matrices in one group"); return PRISM_EUNSUPPORTED; }
   P = Plan();
   P.fn = fn; P.dt = dt; P.batch = batch; P.m = m; P.n = n;
   P.transpose = (fn == PRISM_FN_POLAR && m < n) ? 1 : 0;
@@ -90,6 +91,10 @@ int make_plan(Plan& P, int fn, int batch, int m, int n, int dt, int degree, int 
   }
   P.Sp = round_up(P.S, P.tile);
   P.Lp = round_up(P.L, P.tile);
+  if ((long long)P.Sp * P.Lp > (1ll << 31) - 1) {   // the kernels keep some offsets within a matrix in 32 bits
+    set_last_error("a matrix may hold at most 2^31 - 1 entries after its sides are rounded up to tile multiples");
+    return PRISM_EUNSUPPORTED;
+  }
   P.nsum = 64;
   const int t0 = (P.Sp / 64) * (P.Lp / 64);   // prepare-step tiles (inverse root residual of M_0)
   P.max_parts = t0;
@@ -598,14 +603,17 @@ int run_inv_root_f32(Run& r) {
 int run(int fn, void* a, void* inv_out, int root_p, int batch, int m, int n, int dt, int degree, int max_iters,
         int sketch_dim, uint64_t seed, double tol, void* stream, const prism_options* opt) {
   set_last_error("");
-  if (!a) return PRISM_EINVAL;
-  if ((fn == PRISM_FN_SQRT || fn == PRISM_FN_SQRT_NEWTON) && !inv_out) return PRISM_EINVAL;
+  const bool empty = batch == 0 || m == 0 || n == 0;   // nothing to compute; the arguments are still checked
+  if (batch < 0 || m < 0 || n < 0) return PRISM_EINVAL;
+  if (!empty && !a) return PRISM_EINVAL;
+  if (!empty && (fn == PRISM_FN_SQRT || fn == PRISM_FN_SQRT_NEWTON) && !inv_out) return PRISM_EINVAL;
   if (max_iters < 0 || max_iters > PRISM_MAX_ITERS) return PRISM_EINVAL;
   if (!(tol == tol)) return PRISM_EINVAL;
   if (opt && opt->warm_iters < 0) return PRISM_EINVAL;
   if (opt && (opt->schedule_len < 0 || opt->schedule_len > PRISM_MAX_ITERS || (opt->schedule_len > 0 && !opt->alpha_schedule)))
     return PRISM_EINVAL;
   Run r;
+  if (empty) return make_plan(r.P, fn, 1, m ? m : 1, n ? n : 1, dt, degree, sketch_dim, root_p, opt ? opt->flags : 0u);
   int rc = make_plan(r.P, fn, batch, m, n, dt, degree, sketch_dim, root_p, opt ? opt->flags : 0u);
   if (rc != PRISM_OK) return rc;
   r.s = (hipStream_t)stream;
@@ -701,7 +709,8 @@ int get_fork(Fork** out) {
 int run_grouped(int fn, const prism_group* groups, int ngroups, int root_p, int dt, int degree, int max_iters,
                 int sketch_dim, uint64_t seed, double tol, void* stream, const prism_options* opt) {
   set_last_error("");
-  if (!groups || ngroups <= 0) return PRISM_EINVAL;
+  if (ngroups == 0) return PRISM_OK;
+  if (!groups || ngroups < 0) return PRISM_EINVAL;
   if (opt && (opt->workspace || opt->info)) return PRISM_EINVAL;
   if (fn == PRISM_FN_INVERSE) degree = 5;                     // fixed polynomial
   if (fn == PRISM_FN_SQRT_NEWTON) { degree = 3; sketch_dim = sketch_dim ? 1 : 0; seed = 0; }
@@ -809,11 +818,13 @@ int prism_profile_collect(double* ms_by_kind, long long* launches_by_kind, int n
 
 int prism_workspace_bytes(int fn, int batch, int m, int n, prism_dtype dt, int degree, int sketch_dim,
                           int root_p, size_t* out_bytes) {
-  if (!out_bytes) return PRISM_EINVAL;
+  if (!out_bytes || batch < 0 || m < 0 || n < 0) return PRISM_EINVAL;
+  const bool empty = batch == 0 || m == 0 || n == 0;
   Plan P;
-  int rc = make_plan(P, fn, batch, m, n, (int)dt, degree, sketch_dim, root_p, 0u);
+  int rc = empty ? make_plan(P, fn, 1, m ? m : 1, n ? n : 1, (int)dt, degree, sketch_dim, root_p, 0u)
+                 : make_plan(P, fn, batch, m, n, (int)dt, degree, sketch_dim, root_p, 0u);
   if (rc != PRISM_OK) return rc;
-  *out_bytes = P.total;
+  *out_bytes = empty ? 0 : P.total;
   return PRISM_OK;
 }
 
@@ -869,7 +880,7 @@ int prism_sqrt_newton_ex(void* a, void* inv_out, int batch, int m, int n, prism_
 }
 
 int prism_spd_inverse(const float* a, float* out, int batch, int n, void* stream) {
-  if (!a || !out || batch <= 0 || n <= 0 || n % 64) return PRISM_EINVAL;
+  if (!a || !out || batch <= 0 || batch > PRISM_MAX_BATCH || n <= 0 || n % 64) return PRISM_EINVAL;
   char* ws = nullptr;
   const size_t bytes = (size_t)spd_inverse_scratch_floats(n, batch) * 4;
   if (bytes) {
@@ -897,7 +908,7 @@ int prism_gauss_parts(uint32_t first, uint32_t count, double* radius, double* co
 }
 
 int prism_chain_product(const float* R, const float* V, float* out, int batch, int n, int ld, void* stream) {
-  if (!R || !V || !out || batch <= 0 || n <= 0) return PRISM_EINVAL;
+  if (!R || !V || !out || batch <= 0 || batch > PRISM_MAX_BATCH || n <= 0) return PRISM_EINVAL;
   return launch_chain(R, (long long)n * n, n, V, (long long)n * ld, out, (long long)n * ld, n, ld, batch, nullptr,
                       (hipStream_t)stream);
 }
@@ -912,7 +923,7 @@ int prism_chain_product_bf16(const uint16_t* Rb, const float* R, const float* V,
 }
 
 int prism_gemm_f32(const float* A, const float* B, float* C, int batch, int M, int N, int K, int a_km, void* stream) {
-  if (!A || !B || !C || batch <= 0 || M <= 0 || N <= 0 || K <= 0) return PRISM_EINVAL;
+  if (!A || !B || !C || batch <= 0 || batch > PRISM_MAX_BATCH || M <= 0 || N <= 0 || K <= 0) return PRISM_EINVAL;
   GemmDesc g = {};
   g.A = A; g.strideA = (long long)M * K; g.lda = (a_km & 1) ? M : K;
   g.B = B; g.strideB = (long long)K * N; g.ldb = N;
@@ -923,7 +934,7 @@ int prism_gemm_f32(const float* A, const float* B, float* C, int batch, int M, i
 }
 
 int prism_gemm_f64a(const float* A, const double* B, double* C, int batch, int M, int N, int K, void* stream) {
-  if (!A || !B || !C || batch <= 0 || M <= 0 || N <= 0 || K <= 0) return PRISM_EINVAL;
+  if (!A || !B || !C || batch <= 0 || batch > PRISM_MAX_BATCH || M <= 0 || N <= 0 || K <= 0) return PRISM_EINVAL;
   GemmDesc g = {};
   g.A = A; g.strideA = (long long)M * K; g.lda = K;
   g.B = B; g.strideB = (long long)K * N; g.ldb = N;
@@ -934,7 +945,7 @@ int prism_gemm_f64a(const float* A, const double* B, double* C, int batch, int M
 
 int prism_gemm_bf16_nt(const uint16_t* A, const uint16_t* B, float* C, int batch, int M, int N, int K, int tile,
                        void* stream) {
-  if (!A || !B || !C || batch <= 0 || M <= 0 || N <= 0 || K <= 0) return PRISM_EINVAL;
+  if (!A || !B || !C || batch <= 0 || batch > PRISM_MAX_BATCH || M <= 0 || N <= 0 || K <= 0) return PRISM_EINVAL;
   Bf16Desc g = {};
   g.A = A; g.strideA = (long long)M * K; g.lda = K;
   g.B = B; g.strideB = (long long)N * K; g.ldb = K;

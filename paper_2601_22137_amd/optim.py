@@ -23,6 +23,9 @@ def muon_orthogonalize(grads, degree=5, iters=5, sketch_dim=16, seed=22137, warm
     the orthogonalisation step of a Muon-style optimizer (paper Section 6.2: a fixed small budget
     of PRISM iterations, optionally the first `warm_iters` of them at alpha = u without a fit).
     Returns new tensors in the order of `grads`."""
+    prism.lib()
+    if len(grads) == 0:
+        return []
     groups = _by_shape(grads)
     stacked = [torch.stack([grads[i] for i in idx]).contiguous() for idx in groups.values()]
     flags = prism.FLAG_BF16_PLAIN_ITERATE if (plain_bf16 and stacked[0].dtype == torch.bfloat16) else 0
@@ -38,6 +41,9 @@ def shampoo_inverse_roots(stats, root_p=4, max_iters=40, sketch_dim=16, seed=221
     """A^(-1/root_p) of a list of symmetric positive definite fp32 preconditioner statistics (any mix of
     sizes): the root step of a Shampoo-style optimizer (paper Section 6.2, coupled inverse Newton).
     Returns (roots in the order of `stats`, per-matrix iteration counts)."""
+    prism.lib()
+    if len(stats) == 0:
+        return [], []
     groups = _by_shape(stats)
     stacked = [torch.stack([stats[i] for i in idx]).contiguous() for idx in groups.values()]
     _, infos = prism.run_grouped(prism.FN_INV_ROOT, stacked, 3, max_iters, sketch_dim, seed, tol, root_p=root_p)

@@ -211,6 +211,9 @@ def run_grouped(fn, xs, degree=5, max_iters=30, sketch_dim=8, seed=22137, tol=1e
                 alpha_schedule=None):
     """One call over tensors of different shapes (each [batch, m, n], all of one dtype), in place.
     Returns (inverse outputs or None per group, info handles per group)."""
+    if len(xs) == 0:
+        _check(lib().prism_run_grouped(fn, None, 0, root_p, F32, degree, max_iters, sketch_dim, seed, tol, _stream(), None))
+        return [], []
     groups = (Group * len(xs))()
     infos, invs = [], []
     two_outputs = fn in (FN_SQRT, FN_SQRT_NEWTON)

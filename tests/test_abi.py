@@ -41,7 +41,15 @@ def test_workspace_query_and_argument_checks(lib):
     # six bf16 copies of the iterate (hi/lo/gram layout, double buffered) + R (fp32, bf16) + Q (bf16)
     assert 8 * per_matrix * (6 * 2 + 4 + 2 + 2) <= out.value <= 8 * per_matrix * 21
     assert q(P.FN_POLAR, 1, 64, 32, P.F32, 5, 8, 0) == P.OK and out.value > 0
-    assert q(P.FN_POLAR, 0, 64, 32, P.F32, 5, 8, 0) == P.EINVAL
+    assert q(P.FN_POLAR, 0, 64, 32, P.F32, 5, 8, 0) == P.OK and out.value == 0      # an empty batch needs nothing
+    assert q(P.FN_POLAR, 0, 64, 32, P.F32, 4, 8, 0) == P.EINVAL                     # ... but its arguments are checked
+    assert q(P.FN_POLAR, -1, 64, 32, P.F32, 5, 8, 0) == P.EINVAL
+    # size limits: 65535 matrices per call, 2^31 - 1 entries per matrix after rounding up to tiles
+    assert q(P.FN_POLAR, 65535, 64, 32, P.F32, 5, 8, 0) == P.OK
+    assert q(P.FN_POLAR, 65536, 64, 32, P.F32, 5, 8, 0) == P.EUNSUPPORTED
+    assert q(P.FN_POLAR, 1, 4_190_000, 500, P.F32, 5, 8, 0) == P.OK
+    assert q(P.FN_POLAR, 1, 4_194_400, 500, P.F32, 5, 8, 0) == P.EUNSUPPORTED
+    assert q(P.FN_POLAR, 1, 129, 16_000_000, P.BF16, 5, 8, 0) == P.EUNSUPPORTED      # 256 x 16,000,000 once padded
     assert q(P.FN_POLAR, 1, 64, 32, P.F32, 4, 8, 0) == P.EINVAL
     assert q(P.FN_POLAR, 1, 64, 32, P.F32, 5, 65, 0) == P.EINVAL
     assert q(P.FN_POLAR, 1, 64, 32, 7, 5, 8, 0) == P.EINVAL

@@ -276,6 +276,40 @@ def test_invalid_arguments(prism):
         prism.sqrt(x.to(torch.bfloat16), 5, 5, 8, SEED, 1e-6)
 
 
+def test_empty_inputs_are_a_no_op(prism):
+    """A batch of no matrices, matrices without rows or columns and a grouped call without groups
+    are valid and do nothing; their other arguments are still checked; negative extents are errors."""
+    from paper_2601_22137_amd import optim
+    for shape in [(0, 8, 8), (2, 0, 8), (2, 8, 0), (0, 0, 0)]:
+        x = torch.zeros(shape, device="cuda")
+        info = prism.polar(x, 5, 5, 8, SEED, 1e-6).read()
+        assert len(info) == shape[0]
+        with pytest.raises(prism.PrismError):
+            prism.polar(x, 4, 5, 8, SEED, 1e-6)
+    e = torch.zeros((0, 16, 16), device="cuda")
+    inv, info = prism.sqrt(e, 5, 5, 8, SEED, 1e-6)
+    assert inv.shape == e.shape and len(info.read()) == 0
+    assert len(prism.inv_root(e, 4, 5, 8, SEED, 1e-6).read()) == 0
+    assert len(prism.sign(e, 5, 5, 8, SEED, 1e-6).read()) == 0
+    assert len(prism.inverse(e, 5, 8, SEED, 1e-6).read()) == 0
+    assert len(prism.sqrt_newton(e, 5, 1e-6)[1].read()) == 0
+    assert prism.polar(torch.zeros((0, 8, 8), device="cuda", dtype=torch.bfloat16), 5, 5, 8, SEED, 0.0).read().size == 0
+    assert prism.workspace_bytes(prism.FN_POLAR, 0, 8, 8, prism.F32, 5, 8) == 0
+    with pytest.raises(prism.PrismError):
+        prism.workspace_bytes(prism.FN_POLAR, -1, 8, 8, prism.F32, 5, 8)
+    with pytest.raises(prism.PrismError):
+        prism.inv_root(torch.zeros((0, 8, 16), device="cuda"), 4, 5, 8, SEED, 1e-6)      # not square
+    assert prism.run_grouped(prism.FN_POLAR, []) == ([], [])
+    assert optim.muon_orthogonalize([]) == [] and optim.shampoo_inverse_roots([]) == ([], [])
+    # an empty group beside a real one: the real one is computed as if alone
+    A = W.c1_polar_small()
+    x = torch.from_numpy(A.copy()).cuda()
+    y = x.clone()
+    _, infos = prism.run_grouped(prism.FN_POLAR, [torch.zeros((0, 8, 8), device="cuda"), x], 5, 30, 8, SEED, 1e-6)
+    prism.polar(y, 5, 30, 8, SEED, 1e-6)
+    assert torch.equal(x, y) and len(infos[0].read()) == 0 and len(infos[1].read()) == 1
+
+
 def test_call_replays_from_a_hip_graph(prism):
     """A call only enqueues kernels (no allocation with a caller workspace, no memset, no host
     read), so it can be captured once and replayed: every replay must reproduce the eager result
