@@ -374,7 +374,9 @@ def main():
             per_iter = {"bf16_apply": 2.0 * L * S * S, "bf16_gram": 2.0 * L * S * S, "bf16_polyq": 2.0 * S ** 3,
                         "f32_resid": 2.0 * L * S * S, "f32_polyq": 2.0 * S ** 3,
                         "f32_apply": (4.0 if wl.name in ("c5", "sqrt-newton") else 2.0) * L * S * S,
-                        "f32_store": 4.0 * S ** 3, "f64_mnext": 2.0 * S ** 3, "spd_inverse": 2.0 * S ** 3}[dom]
+                        "f32_store": 4.0 * S ** 3, "f64_mnext": 2.0 * S ** 3, "spd_inverse": 2.0 * S ** 3,
+                        # one launch runs every iteration: Gram, R^2 and the update
+                        "f32_small_polar": 4.0 * L * S * S + 2.0 * S ** 3}[dom]
             for rec in inf:
                 nit = rec["iters"] + (1 if dom in ("bf16_gram", "f32_resid") and rec["status"] == prism.INFO_CONVERGED else 0)
                 fl += per_iter * nit

@@ -144,6 +144,20 @@ struct SolveArgs {
 void launch_moments(const SolveArgs& a, int batch, hipStream_t s);
 void launch_solve(const SolveArgs& a, int batch, hipStream_t s);
 
+// fp32 polar factor of matrices whose padded iterate is 64 x 64: every iteration (residual, sketch
+// chain, fit, update) runs inside one workgroup per matrix, the iterate never leaves the LDS and one
+// launch replaces the five launches per iteration of the general path.
+struct SmallPolarArgs {
+  SolveArgs sv;              // k, mode and sched_alpha are filled in per iteration by the kernel;
+                             // the residual sum and the moments stay in LDS (rho_part, cpart unused)
+  float* X[2];               // [batch][64][64]: input in X[0], result left in X[iterations & 1]
+  const float* V0;           // S_k^T for k = first_fit, first_fit + 1, ...: [.][64][ld]
+  int nv;                    // products in the chain (2 d + 1)
+  int p_s, first_fit, warm, sched_len;
+  float sched[PRISM_MAX_ITERS];
+};
+int launch_small_polar(const SmallPolarArgs& a, int batch, hipStream_t s);
+
 // ---- misc.hip ----
 struct PrepArgs {
   int fn; int dt; int batch; int m, n;     // caller's shape
@@ -191,7 +205,7 @@ enum ProfKind {
   PK_PREP = 0, PK_FINAL, PK_SKETCH, PK_CHAIN, PK_SOLVE,
   PK_F32_RESID, PK_F32_POLYQ, PK_F32_APPLY, PK_F32_STORE, PK_F64_MNEXT, PK_MAKE_T,
   PK_BF16_GRAM, PK_BF16_POLYQ, PK_BF16_APPLY, PK_BF16_STORE,
-  PK_SPD_INVERSE, PK_DB_MOMENTS, PK_DB_UPDATE_M,
+  PK_SPD_INVERSE, PK_DB_MOMENTS, PK_DB_UPDATE_M, PK_F32_SMALL_POLAR,
   PK_COUNT
 };
 struct ProfScope {   // records an event pair around the launches made during its lifetime

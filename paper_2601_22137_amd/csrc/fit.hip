@@ -8,13 +8,18 @@
 //   1. sums the residual partials, applies the stop rule and records the residual;
 //   2. adds up the coefficient partials;
 //   3. minimises m over [l, u]: all real roots of m' in the interval are bracketed between the
-//      roots of m'' (recursively down to the linear derivative) and found by bisection, then m
+//      roots of m'' (recursively down to the linear derivative) and found by Newton's method
+//      safeguarded by bisection, then m
 //      is compared at the end points and those roots; the smallest alpha wins ties.
 // Nothing returns to the host: alpha_k, the done flag and the report stay on the device.
+//   small_polar_kernel: for fp32 polar factors whose padded iterate is 64 x 64, the whole method
+//   (residual, chain, fit, update, for all iterations) in one workgroup per matrix.
 #include "common.h"
 
 namespace prism {
 namespace {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int NT = 256;
 constexpr int MAXC = 2 * PRISM_MAX_ROOT + 1;  // coefficients of m
@@ -126,8 +131,12 @@ __global__ __launch_bounds__(NT) void moments_kernel(SolveArgs a) {
   accumulate_for(a, b, grp, ngrp, a.cpart + ((long long)b * ngrp + grp) * MAXC);
 }
 
-__global__ __launch_bounds__(NT) void solve_kernel(SolveArgs a) {
-  const int b = blockIdx.x, t = threadIdx.x;
+// One workgroup, matrix b: stop rule and coefficient of iteration a.k.  Every return is taken by all
+// threads of the workgroup together.
+// rho_local (LDS, one double) stands in for the residual partials in global memory and c_local
+// (LDS, MAXC doubles) for the coefficient partials when the caller has them on chip.
+__device__ void solve_body(const SolveArgs& a, int b, const double* rho_local = nullptr, double* c_local = nullptr) {
+  const int t = threadIdx.x;
   Ctrl* ctl = &a.ctrl[b];
   if (ctl->done) return;
   prism_info* info = a.info + b;
@@ -139,7 +148,7 @@ __global__ __launch_bounds__(NT) void solve_kernel(SolveArgs a) {
 
   // residual: sum of the per-tile partials, every thread a strided share, then a fixed tree
   __shared__ double s_rho[4];
-  {
+  if (!rho_local) {
     double part = 0.0;
     for (int i = t; i < a.nparts; i += NT) part += (double)a.rho_part[(long long)b * a.nparts + i];
 #pragma unroll
@@ -150,7 +159,7 @@ __global__ __launch_bounds__(NT) void solve_kernel(SolveArgs a) {
   if (a.phase == 2) {
     if (t == 0) s_stop = 0;          // coefficient only: the stop test of this k has been taken
   } else if (t == 0) {
-    const double rho = (s_rho[0] + s_rho[1]) + (s_rho[2] + s_rho[3]);
+    const double rho = rho_local ? *rho_local : (s_rho[0] + s_rho[1]) + (s_rho[2] + s_rho[3]);
     const double res = sqrt(rho / (double)a.n);
     info->residual[a.k] = (float)res;
     int status = -1;
@@ -198,15 +207,21 @@ __global__ __launch_bounds__(NT) void solve_kernel(SolveArgs a) {
   }
 
   const int nc = (a.fn == PRISM_FN_INV_ROOT) ? 2 * a.p + 1 : (a.fn == PRISM_FN_INVERSE ? 3 : 5);
-  if (a.ngroups == 1 && a.fn != PRISM_FN_SQRT_NEWTON) {   // small matrices: the moments are accumulated right here
-    accumulate_for(a, b, 0, 1, a.cpart + (long long)b * MAXC);
-    __threadfence_block();
+  if (c_local) {   // moments straight into LDS
+    accumulate_for(a, b, 0, 1, c_local);
     __syncthreads();
-  }
-  if (t < MAXC) {   // coefficient s = sum of the group partials, in group order
-    double v = 0.0;
-    for (int gidx = 0; gidx < a.ngroups; ++gidx) v += a.cpart[((long long)b * a.ngroups + gidx) * MAXC + t];
-    s_c[t] = v;
+    if (t < MAXC) s_c[t] = c_local[t];
+  } else {
+    if (a.ngroups == 1 && a.fn != PRISM_FN_SQRT_NEWTON) {   // small matrices: the moments are accumulated right here
+      accumulate_for(a, b, 0, 1, a.cpart + (long long)b * MAXC);
+      __threadfence_block();
+      __syncthreads();
+    }
+    if (t < MAXC) {   // coefficient s = sum of the group partials, in group order
+      double v = 0.0;
+      for (int gidx = 0; gidx < a.ngroups; ++gidx) v += a.cpart[((long long)b * a.ngroups + gidx) * MAXC + t];
+      s_c[t] = v;
+    }
   }
   __syncthreads();
 
@@ -256,15 +271,28 @@ __global__ __launch_bounds__(NT) void solve_kernel(SolveArgs a) {
       if (fa == 0.0) { found = xa; has = 1; }
       else if (t == nr && fb == 0.0) { found = xb; has = 1; }
       else if ((fa < 0.0) != (fb < 0.0) && fb != 0.0) {
+        // Newton's method kept inside the bracket [l, h] (f(l) has the sign of fa): a step that
+        // would leave the bracket, or that shrinks too slowly, is replaced by a bisection step.
+        // The derivative of level j is level j + 1 of the chain.
         double l = xa, h = xb;
+        double x = 0.5 * (l + h), dx = h - l, dxold = dx;
+        double fx = horner(s_q[j], pdeg, x), dfx = horner(s_q[j + 1], pdeg - 1, x);
         for (int it = 0; it < 200; ++it) {
-          const double mid = 0.5 * (l + h);
-          if (mid <= l || mid >= h) break;
-          const double fm = horner(s_q[j], pdeg, mid);
-          if (fm == 0.0) { l = h = mid; break; }
-          if ((fm < 0.0) == (fa < 0.0)) l = mid; else h = mid;
+          if (fx == 0.0) break;
+          if ((fx < 0.0) == (fa < 0.0)) l = x; else h = x;
+          const bool leaves = !((((x - h) * dfx - fx) * ((x - l) * dfx - fx)) < 0.0);
+          const bool slow = fabs(2.0 * fx) > fabs(dxold * dfx);
+          dxold = dx;
+          double xn;
+          if (leaves || slow) { dx = 0.5 * (h - l); xn = l + dx; }
+          else { dx = fx / dfx; xn = x - dx; }
+          if (xn == x || !(xn > l && xn < h)) break;   // the bracket is down to neighbouring numbers
+          x = xn;
+          if (fabs(dx) <= 2.0e-16 * fabs(x)) break;
+          fx = horner(s_q[j], pdeg, x);
+          dfx = horner(s_q[j + 1], pdeg - 1, x);
         }
-        found = 0.5 * (l + h);
+        found = x;
         has = 1;
       }
     }
@@ -301,7 +329,213 @@ __global__ __launch_bounds__(NT) void solve_kernel(SolveArgs a) {
   }
 }
 
+__global__ __launch_bounds__(NT) void solve_kernel(SolveArgs a) { solve_body(a, blockIdx.x); }
+
+// ---- fp32 polar factor, padded iterate 64 x 64: all iterations in one workgroup ----
+// The products run on v_mfma_f32_16x16x4_f32 (A operand: lane l holds A[m = l % 16][k = l / 16], B
+// operand B[k = l / 16][n = l % 16], result register r of lane l is D[4 (l / 16) + r][l % 16]); each
+// of the four waves owns a 32 x 32 quadrant of a 64 x 64 result (2 x 2 blocks), or 16 rows of a chain
+// product.  LDS: X [64][SX], R [64][SR], and a third area for the two chain buffers and later Q
+// [64][SR].  R and Q are symmetric, so they are always read with k as the row index; SR = 80 and
+// the chain stride ld + 16 put the four k rows of a fragment read into different banks, SX = 68
+// does the same for the reads of X along its rows in X Q.
+constexpr int SN = 64, SX = 68, SR = 80;
+constexpr int SMALL_LDS_FLOATS = SN * SX + SN * SR + 2 * SN * SR;
+__device__ inline int small_ldv(int ld) { return ld == 16 ? 16 : ld + 16; }
+
+// acc[i][j] += sum_k A(k, m) B(k, n) over k = 0 .. 63 for the wave's quadrant; A(k, m) sits at
+// As[k * sak + m * sam], B(k, n) at Bs[k * ldb + n]
+__device__ inline void small_mma(const float* As, int sak, int sam, const float* Bs, int ldb, int wm0, int wn0,
+                                 f32x4 (&acc)[2][2]) {
+  const int lr = threadIdx.x & 15, lk = (threadIdx.x & 63) >> 4;
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j) acc[i][j] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll 4
+  for (int k0 = 0; k0 < SN; k0 += 4) {
+    float av[2], bv[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) av[i] = As[(k0 + lk) * sak + (wm0 + i * 16 + lr) * sam];
+#pragma unroll
+    for (int j = 0; j < 2; ++j) bv[j] = Bs[(k0 + lk) * ldb + wn0 + j * 16 + lr];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[i], bv[j], acc[i][j], 0, 0, 0);
+  }
+}
+
+// Vout = R Vin (R symmetric): wave w forms rows 16 w .. 16 w + 15, all LD columns; the result goes to
+// the other LDS buffer and, densely ([64][LD]), to global memory for the moments
+template <int LD>
+__device__ inline void small_chain_step(const float* Rs, const float* Vin, float* Vout, float* Vglobal) {
+  constexpr int NB = LD / 16;
+  const int ldv = LD == 16 ? 16 : LD + 16;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, lr = lane & 15, lk = lane >> 4;
+  f32x4 acc[NB];
+#pragma unroll
+  for (int j = 0; j < NB; ++j) acc[j] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+  for (int k0 = 0; k0 < SN; k0 += 4) {
+    const float av = Rs[(k0 + lk) * SR + 16 * wave + lr];
+#pragma unroll
+    for (int j = 0; j < NB; ++j)
+      acc[j] = __builtin_amdgcn_mfma_f32_16x16x4f32(av, Vin[(k0 + lk) * ldv + 16 * j + lr], acc[j], 0, 0, 0);
+  }
+#pragma unroll
+  for (int j = 0; j < NB; ++j)
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const int row = 16 * wave + 4 * lk + r, col = 16 * j + lr;
+      Vout[row * ldv + col] = acc[j][r];
+      Vglobal[row * LD + col] = acc[j][r];
+    }
+}
+
+__global__ __launch_bounds__(NT) void small_polar_kernel(SmallPolarArgs a) {
+  extern __shared__ float small_lds[];
+  float* Xs = small_lds;
+  float* Rs = Xs + SN * SX;
+  float* Ts = Rs + SN * SR;
+  __shared__ double s_part[4];
+  __shared__ double s_rho;
+  __shared__ double s_coef[MAXC];
+  const int b = blockIdx.x, t = threadIdx.x;
+  SolveArgs sv = a.sv;
+  Ctrl* ctl = &sv.ctrl[b];
+  if (ctl->done) return;   // zero or non-finite input: reported by the prepare step
+  const int lane = t & 63, wave = t >> 6, lr = lane & 15, lk = lane >> 4;
+  const int wm0 = (wave >> 1) * 32, wn0 = (wave & 1) * 32;   // this wave's quadrant of a 64 x 64 result
+  {
+    const float* Xg = a.X[0] + (long long)b * SN * SN;
+    for (int idx = t; idx < SN * SN / 4; idx += NT) {
+      const int r = idx >> 4, c = (idx & 15) * 4;
+      *(f32x4*)&Xs[r * SX + c] = *(const f32x4*)&Xg[r * SN + c];
+    }
+  }
+  __syncthreads();
+  f32x4 acc[2][2];
+  for (int k = 0; k <= sv.max_iters; ++k) {
+    if (k == sv.max_iters && sv.tol <= 0.0) break;
+    // R = I - X^T X, zero outside the leading n x n block; rho = ||R||_F^2
+    small_mma(Xs, SX, 1, Xs, SX, wm0, wn0, acc);
+    double part = 0.0;
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const int row = wm0 + i * 16 + 4 * lk + r, col = wn0 + j * 16 + lr;
+          const float rv = (row < sv.n && col < sv.n) ? ((row == col ? 1.0f : 0.0f) - acc[i][j][r]) : 0.0f;
+          Rs[row * SR + col] = rv;
+          part += (double)rv * (double)rv;
+        }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) part += __shfl_down(part, off, 64);
+    if (lane == 0) s_part[wave] = part;
+    __syncthreads();
+    if (t == 0) s_rho = (s_part[0] + s_part[1]) + (s_part[2] + s_part[3]);
+
+    // sketch chain V_j = R V_{j-1}, V_0 = S_k^T; the V_j also go to global memory for the moments
+    if (a.p_s > 0 && k >= a.first_fit && k < sv.max_iters) {
+      const int ld = sv.ld, ldv = small_ldv(ld);
+      const float* v0 = a.V0 + (long long)(k - a.first_fit) * SN * ld;
+      for (int idx = t; idx < SN * ld / 4; idx += NT) {
+        const int r = (idx * 4) / ld, c = (idx * 4) % ld;
+        *(f32x4*)&Ts[r * ldv + c] = *(const f32x4*)&v0[idx * 4];
+      }
+      __syncthreads();
+      // between the products only the LDS copies must be in place; the stores to global memory stay
+      // in flight until the full barrier below
+      auto lds_barrier = [&]() {
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+      };
+      float* vin = Ts;
+      float* vout = Ts + SN * SR;
+      for (int j = 1; j <= a.nv; ++j) {
+        float* vg = const_cast<float*>(sv.V) + (long long)(j - 1) * sv.vstride + (long long)b * sv.bstride;
+        if (ld == 16) small_chain_step<16>(Rs, vin, vout, vg);
+        else if (ld == 32) small_chain_step<32>(Rs, vin, vout, vg);
+        else small_chain_step<64>(Rs, vin, vout, vg);
+        lds_barrier();
+        float* tmp = vin; vin = vout; vout = tmp;
+      }
+    }
+    __threadfence_block();
+    __syncthreads();
+
+    sv.k = k;
+    sv.mode = k < a.sched_len ? 3 : (a.p_s == 0 ? 1 : (k < a.warm ? 2 : 0));
+    sv.sched_alpha = k < a.sched_len ? a.sched[k] : 0.0f;
+    solve_body(sv, b, &s_rho, s_coef);
+    __threadfence_block();
+    __syncthreads();
+    if (ctl->done) break;
+    const float alpha = ctl->alpha;
+
+    const float* Bm = Rs;
+    float wa = alpha;
+    if (sv.d == 2) {   // Q = R / 2 + alpha R^2
+      small_mma(Rs, SR, 1, Rs, SR, wm0, wn0, acc);
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            const int row = wm0 + i * 16 + 4 * lk + r, col = wn0 + j * 16 + lr;
+            Ts[row * SR + col] = 0.5f * Rs[row * SR + col] + alpha * acc[i][j][r];
+          }
+      __syncthreads();
+      Bm = Ts;
+      wa = 1.0f;
+    }
+    // X <- X + wa X B: every wave reads whole rows of X, so all reads end before the first store
+    small_mma(Xs, 1, SX, Bm, SR, wm0, wn0, acc);
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const int row = wm0 + i * 16 + 4 * lk + r, col = wn0 + j * 16 + lr;
+          Xs[row * SX + col] += wa * acc[i][j][r];
+        }
+    __syncthreads();
+  }
+  {
+    float* Xg = a.X[ctl->iters & 1] + (long long)b * SN * SN;
+    for (int idx = t; idx < SN * SN / 4; idx += NT) {
+      const int r = idx >> 4, c = (idx & 15) * 4;
+      *(f32x4*)&Xg[r * SN + c] = *(const f32x4*)&Xs[r * SX + c];
+    }
+  }
+}
+
 }  // namespace
+
+int launch_small_polar(const SmallPolarArgs& a, int batch, hipStream_t s) {
+  if (a.sv.rows != SN || (a.sv.ld != 16 && a.sv.ld != 32 && a.sv.ld != 64) || a.sv.ngroups != 1 || a.sv.nparts != 1 ||
+      a.nv < 1 || a.nv > 5 || batch <= 0)
+    return PRISM_EINVAL;
+  constexpr size_t lds = SMALL_LDS_FLOATS * sizeof(float);
+  static bool attr_set = false;
+  if (!attr_set) {
+    if (hipFuncSetAttribute((const void*)small_polar_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) !=
+        hipSuccess) {
+      set_last_error("hipFuncSetAttribute(MaxDynamicSharedMemorySize) failed");
+      return PRISM_EHIP;
+    }
+    attr_set = true;
+  }
+  hipLaunchKernelGGL(small_polar_kernel, dim3(batch), dim3(NT), lds, s, a);
+  return hipGetLastError() == hipSuccess ? PRISM_OK : PRISM_EHIP;
+}
 
 void launch_moments(const SolveArgs& a, int batch, hipStream_t s) {
   hipLaunchKernelGGL(moments_kernel, dim3(a.ngroups, batch), dim3(NT), 0, s, a);

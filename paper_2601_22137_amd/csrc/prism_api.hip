@@ -296,6 +296,23 @@ int run_polar_f32(Run& r) {
   const bool polar = P.fn != PRISM_FN_SIGN;
   const int sym = polar ? f32_sym() : 0;
   const int nparts = sym_parts(Sp / T, sym);
+  static const int no_small = getenv("PRISM_NO_SMALL_KERNEL") ? atoi(getenv("PRISM_NO_SMALL_KERNEL")) : 0;
+  if (polar && Sp == 64 && Lp == 64 && P.ngroups == 1 && !no_small) {
+    // the whole iteration in one workgroup per matrix, one launch for all iterations: with five
+    // launches per iteration a call on such matrices is nothing but launch latency
+    SmallPolarArgs sa = {};
+    SolveArgs& v = sa.sv;
+    v.fn = P.fn; v.d = P.d; v.p = P.p; v.n = P.S; v.rows = Sp; v.ld = P.ld;
+    v.V = r.v; v.vstride = (long long)P.batch * Sp * P.ld; v.bstride = (long long)Sp * P.ld;
+    v.rho_part = r.rho; v.nparts = 1;
+    v.ctrl = r.ctrl; v.info = r.info; v.tol = r.tol; v.max_iters = r.max_iters;
+    v.cpart = r.at<double>(P.o_cpart); v.ngroups = 1;
+    sa.X[0] = X[0]; sa.X[1] = X[1]; sa.V0 = r.v0; sa.nv = P.nv;
+    sa.p_s = P.p_s; sa.first_fit = r.first_fit; sa.warm = r.warm; sa.sched_len = r.sched_len;
+    for (int i = 0; i < r.sched_len; ++i) sa.sched[i] = r.sched[i];
+    ProfScope ps(PK_F32_SMALL_POLAR, r.s);
+    return launch_small_polar(sa, P.batch, r.s);
+  }
   int cur = 0;
   for (int k = 0; k <= r.max_iters; ++k) {
     if (k == r.max_iters && r.tol <= 0.0) break;

@@ -413,7 +413,7 @@ def test_polar_bf16_fit_falls_back_to_the_fp32_residual(prism, batch, m, n, p_s)
 def test_order_64_chain_in_one_launch(prism, p_s):
     """Matrices whose padded order is 64 take the one-launch chain kernel, for every sketch width
     (16, 32, 64 columns) and for the inverse root's longer chain."""
-    A = np.concatenate([W.c1_polar_small(m=64, n=48, data_seed=1600 + i) for i in range(3)])
+    A = np.concatenate([W.c1_polar_small(m=200, n=48, data_seed=1600 + i) for i in range(3)])
     x = torch.from_numpy(A.copy()).cuda()
     info = prism.polar(x, 5, 30, p_s, SEED, 1e-6).read()
     out = x.cpu().numpy()
@@ -428,3 +428,48 @@ def test_order_64_chain_in_one_launch(prism, p_s):
         ref, oinfo = O.inv_root(S[i], 3, 40, p_s, SEED, 1e-5)
         assert info[i]["iters"] == oinfo["iters"]
         assert _rel(y.cpu().numpy()[i], ref) <= TOL_F32
+
+
+@pytest.mark.parametrize("degree", [3, 5])
+@pytest.mark.parametrize("shape,p_s", [((64, 48), 8), ((33, 17), 20), ((32, 64), 40), ((64, 64), 16), ((1, 1), 8)])
+def test_small_polar_kernel(prism, shape, p_s, degree):
+    """fp32 polar factors whose padded iterate is 64 x 64 run all their iterations inside one
+    workgroup per matrix: every sketch width (16, 32, 64 columns), both degrees, ragged and wide
+    shapes, to tolerance and with a fixed budget."""
+    m, n = shape
+    A = np.concatenate([W.c1_polar_small(m=m, n=n, data_seed=1700 + i) for i in range(5)])
+    x = torch.from_numpy(A.copy()).cuda()
+    info = prism.polar(x, degree, 40, p_s, SEED, 1e-6).read()
+    out = x.cpu().numpy()
+    for i in range(5):
+        ref, oinfo = O.polar(A[i], degree, 40, p_s, SEED, 1e-6)
+        assert _rel(out[i], ref) <= TOL_F32
+        _check_info(info[i], oinfo, res_floor=2e-6, alpha_res_min=1e-3)
+    y = torch.from_numpy(A.copy()).cuda()
+    info = prism.polar(y, degree, 4, p_s, SEED, 0.0).read()
+    for i in range(5):
+        ref, oinfo = O.polar(A[i], degree, 4, p_s, SEED, 0.0)
+        assert info[i]["iters"] == 4 and info[i]["status"] == prism.INFO_BUDGET
+        assert _rel(y.cpu().numpy()[i], ref) <= TOL_F32
+        np.testing.assert_allclose(info[i]["alpha"][:4], oinfo["alpha"], atol=2e-3)
+
+
+def test_small_polar_kernel_options(prism):
+    """Caller's schedule, warm start and the classical iteration through the one-workgroup kernel."""
+    A = W.c1_polar_small(m=48, n=40, data_seed=1800)
+    sched = [1.2, 0.9, 0.7]
+    for kwargs, okw in [(dict(alpha_schedule=sched), dict(alpha_schedule=sched)),
+                        (dict(warm_iters=2), dict(alpha_schedule=[1.45] * 2)),
+                        (dict(alpha_schedule=sched, warm_iters=5), dict(alpha_schedule=sched + [1.45] * 2))]:
+        x = torch.from_numpy(A.copy()).cuda()
+        info = prism.polar(x, 5, 30, 8, SEED, 1e-6, **kwargs).read()
+        ref, oinfo = O.polar(A[0], 5, 30, 8, SEED, 1e-6, **okw)
+        assert _rel(x.cpu().numpy()[0], ref) <= TOL_F32
+        _check_info(info[0], oinfo, res_floor=2e-6, alpha_res_min=1e-3)
+    x = torch.from_numpy(A.copy()).cuda()
+    info = prism.polar(x, 5, 40, 0, SEED, 1e-6).read()
+    ref, oinfo = O.polar(A[0], 5, 40, 0, SEED, 1e-6)
+    assert _rel(x.cpu().numpy()[0], ref) <= TOL_F32 and info[0]["iters"] == oinfo["iters"]
+    x = torch.from_numpy(A.copy()).cuda()
+    info = prism.polar(x, 5, 0, 8, SEED, 1e-6).read()             # no update allowed: input scaled back untouched
+    assert info[0]["iters"] == 0 and info[0]["status"] == prism.INFO_BUDGET
