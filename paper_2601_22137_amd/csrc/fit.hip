@@ -335,13 +335,18 @@ __global__ __launch_bounds__(NT) void solve_kernel(SolveArgs a) { solve_body(a, 
 // The products run on v_mfma_f32_16x16x4_f32 (A operand: lane l holds A[m = l % 16][k = l / 16], B
 // operand B[k = l / 16][n = l % 16], result register r of lane l is D[4 (l / 16) + r][l % 16]); each
 // of the four waves owns a 32 x 32 quadrant of a 64 x 64 result (2 x 2 blocks), or 16 rows of a chain
-// product.  LDS: X [64][SX], R [64][SR], and a third area for the two chain buffers and later Q
-// [64][SR].  R and Q are symmetric, so they are always read with k as the row index; SR = 80 and
+// product.  LDS: X [64][SX], R [64][SR], and a third area for the two chain buffers [64][ldv] and
+// later Q [64][SR].  R and Q are symmetric, so they are always read with k as the row index; SR = 80 and
 // the chain stride ld + 16 put the four k rows of a fragment read into different banks, SX = 68
 // does the same for the reads of X along its rows in X Q.
 constexpr int SN = 64, SX = 68, SR = 80;
-constexpr int SMALL_LDS_FLOATS = SN * SX + SN * SR + 2 * SN * SR;
-__device__ inline int small_ldv(int ld) { return ld == 16 ? 16 : ld + 16; }
+__host__ __device__ inline int small_ldv(int ld) { return ld == 16 ? 16 : ld + 16; }
+// the third area holds Q [64][SR] or the two chain buffers [64][ldv], whichever is larger (58 KiB in
+// all for 16 sketch columns, so that two workgroups share a CU; 77 KiB for 64 columns)
+inline int small_lds_floats(int ld) {
+  const int chain = 2 * SN * small_ldv(ld);
+  return SN * SX + SN * SR + (chain > SN * SR ? chain : SN * SR);
+}
 
 // acc[i][j] += sum_k A(k, m) B(k, n) over k = 0 .. 63 for the wave's quadrant; A(k, m) sits at
 // As[k * sak + m * sam], B(k, n) at Bs[k * ldb + n]
@@ -455,7 +460,7 @@ __global__ __launch_bounds__(NT) void small_polar_kernel(SmallPolarArgs a) {
         asm volatile("" ::: "memory");
       };
       float* vin = Ts;
-      float* vout = Ts + SN * SR;
+      float* vout = Ts + SN * ldv;
       for (int j = 1; j <= a.nv; ++j) {
         float* vg = const_cast<float*>(sv.V) + (long long)(j - 1) * sv.vstride + (long long)b * sv.bstride;
         if (ld == 16) small_chain_step<16>(Rs, vin, vout, vg);
@@ -523,11 +528,11 @@ int launch_small_polar(const SmallPolarArgs& a, int batch, hipStream_t s) {
   if (a.sv.rows != SN || (a.sv.ld != 16 && a.sv.ld != 32 && a.sv.ld != 64) || a.sv.ngroups != 1 || a.sv.nparts != 1 ||
       a.nv < 1 || a.nv > 5 || batch <= 0)
     return PRISM_EINVAL;
-  constexpr size_t lds = SMALL_LDS_FLOATS * sizeof(float);
+  const size_t lds = (size_t)small_lds_floats(a.sv.ld) * sizeof(float);
   static bool attr_set = false;
   if (!attr_set) {
-    if (hipFuncSetAttribute((const void*)small_polar_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) !=
-        hipSuccess) {
+    if (hipFuncSetAttribute((const void*)small_polar_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                            (int)(small_lds_floats(64) * sizeof(float))) != hipSuccess) {
       set_last_error("hipFuncSetAttribute(MaxDynamicSharedMemorySize) failed");
       return PRISM_EHIP;
     }
