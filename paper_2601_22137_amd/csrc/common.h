@@ -37,6 +37,7 @@ struct GemmDesc {
   int M, N, K;          // padded sizes: multiples of the tile sizes
   int a_km;             // A stored [K][M] instead of [M][K]
   int sym;              // the exact result is symmetric: compute the upper triangle of tiles, mirror the rest
+  int tile_blocks;      // set by the launcher: tiles are taken in blocks of 8 x 8 (plain products, grids of 8 x 8 multiples)
   int batch;
   // epilogue operands
   int epi;
@@ -92,6 +93,7 @@ struct Bf16Desc {
   float* rho_part;
   const Ctrl* ctrl;
   int xcd_private;                                   // set by launch_gemm_bf16: contiguous tile ranges per XCD
+  int xcd_blocks;                                    // set by launch_gemm_bf16: 4 x 8 tile blocks per XCD
   int plain_filter;                                  // 1: skip matrices whose ctrl.plain is set; 2: skip the others (0: none)
   int dbg;                                           // timing experiments only (test entry): bit0: no global loads after the prologue; bit1: XCD-private tile ranges; bit2: 4x8 tile blocks
 };

@@ -89,6 +89,14 @@ __global__ __launch_bounds__(NT, T == 128 ? 3 : 1) void gemm_bf16_kernel(Bf16Des
     tm = 0;
     while (left >= tiles_m - tm) { left -= tiles_m - tm; ++tm; }
     tn = tm + left;
+  } else if (g.xcd_blocks && !xcd_private) {
+    // Every XCD sweeps blocks of 4 x 8 tiles of its own (its 32 CUs run one block at a time): the
+    // tiles that meet in an L2 share 4 row panels and 8 column panels, where the plain order gives an
+    // XCD two tile columns of every row, i.e. 16 row panels and 2 column panels per 32 tiles.
+    const int x = rem & 7, q = rem >> 3;
+    const int blk = (q >> 5) * 8 + x, w = q & 31, nbn = tiles_n >> 3;
+    tm = (blk / nbn) * 4 + (w >> 3);
+    tn = (blk % nbn) * 8 + (w & 7);
   } else {
     tm = rem / tiles_n;
     tn = rem - tm * tiles_n;
@@ -631,6 +639,8 @@ int launch_gemm_bf16(const Bf16Desc& g0, int tile, hipStream_t s) {
   const long long tm = g.M / tile, tn = g.N / tile;
   const long long per_mat = g.sym ? tm * (tm + 1) / 2 : tm * tn;
   g.xcd_private = per_mat <= 64 || operand_bytes <= 128.0 * 1024 * 1024;
+  static const int no_blocks = getenv("PRISM_BF16_NO_XCD_BLOCKS") ? atoi(getenv("PRISM_BF16_NO_XCD_BLOCKS")) : 0;
+  g.xcd_blocks = !no_blocks && !g.sym && per_mat % 256 == 0 && tm % 4 == 0 && tn % 8 == 0;
   if (tile == 256) return launch_t<256>(g, s);
   if (tile == 128) return launch_t<128>(g, s);
   return PRISM_EINVAL;

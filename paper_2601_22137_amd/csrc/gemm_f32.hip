@@ -9,6 +9,8 @@
 // the main loop has no bounds checks; masks are applied in the epilogue only.
 #include <type_traits>
 
+#include <cstdlib>
+
 #include "common.h"
 
 namespace prism {
@@ -118,6 +120,12 @@ __global__ __launch_bounds__(NT, 2) void gemm_kernel(GemmDesc g) {
     tm = 0;
     while (left >= tiles_m - tm) { left -= tiles_m - tm; ++tm; }
     tn = tm + left;
+  } else if (g.tile_blocks) {
+    // blocks of 8 x 8 tiles in sequence: the 64 tiles an XCD works on at a time (32 CUs, two workgroups
+    // each) share 8 row panels and 8 column panels; row by row they are one row panel and 64 column panels
+    const int blk = rem >> 6, w = rem & 63, nbn = tiles_n >> 3;
+    tm = (blk / nbn) * 8 + (w >> 3);
+    tn = (blk % nbn) * 8 + (w & 7);
   } else {
     tm = rem / tiles_n;
     tn = rem - tm * tiles_n;
@@ -322,10 +330,13 @@ int launch_cfg(const GemmDesc& g, hipStream_t s) {
     }
   }
   if (g.sym) return PRISM_EINVAL;
+  static const int no_blocks = getenv("PRISM_F32_NO_TILE_BLOCKS") ? atoi(getenv("PRISM_F32_NO_TILE_BLOCKS")) : 0;
+  GemmDesc gb = g;
+  gb.tile_blocks = !no_blocks && tm % 8 == 0 && tn % 8 == 0 && tm * tn > 64;
   if (g.a_km)
-    hipLaunchKernelGGL((gemm_kernel<TC, TB, TM, TN, WGM, WGN, true, false>), dim3(total), dim3(NT), 0, s, g);
+    hipLaunchKernelGGL((gemm_kernel<TC, TB, TM, TN, WGM, WGN, true, false>), dim3(total), dim3(NT), 0, s, gb);
   else
-    hipLaunchKernelGGL((gemm_kernel<TC, TB, TM, TN, WGM, WGN, false, false>), dim3(total), dim3(NT), 0, s, g);
+    hipLaunchKernelGGL((gemm_kernel<TC, TB, TM, TN, WGM, WGN, false, false>), dim3(total), dim3(NT), 0, s, gb);
   return hipGetLastError() == hipSuccess ? PRISM_OK : PRISM_EHIP;
 }
 

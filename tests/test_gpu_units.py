@@ -102,7 +102,10 @@ def test_gemm_f64a(prism):
     assert np.linalg.norm(C - ref) / np.linalg.norm(ref) < 1e-14
 
 
-@pytest.mark.parametrize("tile,shape", [(128, (128, 256, 192)), (256, (512, 256, 128)), (128, (384, 128, 64))])
+@pytest.mark.parametrize("tile,shape", [(128, (128, 256, 192)), (256, (512, 256, 128)), (128, (384, 128, 64)),
+                                        # operands beyond half the Infinity Cache and a multiple of 256 tiles:
+                                        # the tile order in which every XCD sweeps 4 x 8 blocks of its own
+                                        (128, (2048, 2048, 8448)), (256, (1024, 16384, 2048))])
 def test_gemm_bf16_nt(prism, tile, shape):
     M, N, K = shape
     rng = np.random.default_rng(M * 3 + N)
