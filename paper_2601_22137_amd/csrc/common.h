@@ -37,6 +37,7 @@ struct GemmDesc {
   int M, N, K;          // padded sizes: multiples of the tile sizes
   int a_km;             // A stored [K][M] instead of [M][K]
   int sym;              // the exact result is symmetric: compute the upper triangle of tiles, mirror the rest
+  int ctrl_fixed;       // ctrl[0] applies to every batch entry (the parts of a split-K product)
   int tile_blocks;      // set by the launcher: tiles are taken in blocks of 8 x 8 (plain products, grids of 8 x 8 multiples)
   int batch;
   // epilogue operands
@@ -94,6 +95,7 @@ struct Bf16Desc {
   const Ctrl* ctrl;
   int xcd_private;                                   // set by launch_gemm_bf16: contiguous tile ranges per XCD
   int xcd_blocks;                                    // set by launch_gemm_bf16: 4 x 8 tile blocks per XCD
+  int ctrl_fixed;                                    // ctrl[0] applies to every batch entry (the parts of a split-K product)
   int plain_filter;                                  // 1: skip matrices whose ctrl.plain is set; 2: skip the others (0: none)
   int dbg;                                           // timing experiments only (test entry): bit0: no global loads after the prologue; bit1: XCD-private tile ranges; bit2: 4x8 tile blocks
 };
@@ -185,6 +187,20 @@ struct FinalArgs {
   const uint16_t* Xa_hi[2]; const uint16_t* Xa_lo[2]; const uint16_t* Xg[2];
 };
 void launch_finalize(const FinalArgs& a, hipStream_t s);
+
+// Second pass of a split-K Gram product: R = I - sum_p part_p (zero outside the leading n x n block),
+// summed in part order, exactly symmetric (the lower triangle is the mirror image of the upper one).
+struct GramReduceArgs {
+  const float* part;        // [batch][parts][np][np]
+  int parts, np, n_true;
+  float* R32;               // [batch][np][np] or null
+  uint16_t* Rb;             // bf16 copy [batch][np][np] or null
+  float* diag;              // exact diagonal [batch][np] or null
+  float* rho_part;          // [batch][tiles]: tiles = (np / 64) (np / 64 + 1) / 2 partial sums of R^2
+  const Ctrl* ctrl;
+};
+int gram_reduce_parts(int np);
+void launch_gram_reduce(const GramReduceArgs& a, int batch, hipStream_t s);
 // E = alpha R, one matrix per blockIdx.y; skipped when done
 void launch_make_e(float* E, const float* R, const Ctrl* ctrl, int batch, int np, hipStream_t s);
 

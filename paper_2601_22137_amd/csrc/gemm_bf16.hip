@@ -101,9 +101,10 @@ __global__ __launch_bounds__(NT, T == 128 ? 3 : 1) void gemm_bf16_kernel(Bf16Des
     tm = rem / tiles_n;
     tn = rem - tm * tiles_n;
   }
-  if (g.ctrl && g.ctrl[b].done) return;
-  if (g.plain_filter && g.ctrl && ((g.ctrl[b].plain != 0) != (g.plain_filter == 2))) return;
-  const float alpha = g.ctrl ? g.ctrl[b].alpha : 1.0f;
+  const int cb = g.ctrl_fixed ? 0 : b;   // split-K launches: every batch entry is a part of the same matrix
+  if (g.ctrl && g.ctrl[cb].done) return;
+  if (g.plain_filter && g.ctrl && ((g.ctrl[cb].plain != 0) != (g.plain_filter == 2))) return;
+  const float alpha = g.ctrl ? g.ctrl[cb].alpha : 1.0f;
 
   const int t = threadIdx.x, lane = t & 63;
   const int wave = __builtin_amdgcn_readfirstlane(t >> 6);  // uniform: LDS destinations stay scalar

@@ -130,10 +130,11 @@ __global__ __launch_bounds__(NT, 2) void gemm_kernel(GemmDesc g) {
     tm = rem / tiles_n;
     tn = rem - tm * tiles_n;
   }
-  if (g.ctrl && g.ctrl[b].done) return;
+  const int cb = g.ctrl_fixed ? 0 : b;   // split-K launches: every batch entry is a part of the same matrix
+  if (g.ctrl && g.ctrl[cb].done) return;
   // block Gauss-Jordan: the pivot row / column block has launches of its own
   if ((tm * TM >= g.skip_m0 && tm * TM < g.skip_m1) || (tn * TN >= g.skip_n0 && tn * TN < g.skip_n1)) return;
-  const float alpha = g.ctrl ? g.ctrl[b].alpha : 1.0f;
+  const float alpha = g.ctrl ? g.ctrl[cb].alpha : 1.0f;
 
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
   const int wm0 = (wave / WGN) * WTM, wn0 = (wave % WGN) * WTN;

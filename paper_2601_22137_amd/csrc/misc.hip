@@ -325,7 +325,81 @@ __global__ __launch_bounds__(NT) void make_e_kernel(float* E, const float* R, co
   E[(long long)b * total + i] = alpha * R[(long long)b * total + i];
 }
 
+// One workgroup per 64 x 64 tile on or above the diagonal; thread t: row t / 4, 16 consecutive columns.
+__global__ __launch_bounds__(NT) void gram_reduce_kernel(GramReduceArgs a) {
+  const int b = blockIdx.y;
+  if (a.ctrl[b].done) return;
+  const int nt = a.np / 64;
+  int left = blockIdx.x, tm = 0;
+  while (left >= nt - tm) { left -= nt - tm; ++tm; }
+  const int tn = tm + left;
+  const int m0 = tm * 64, n0 = tn * 64;
+  const long long SS = (long long)a.np * a.np;
+  const int r = threadIdx.x >> 2, c0 = (threadIdx.x & 3) * 16;
+  __shared__ float tile[64][65];
+  {
+    f32x4 acc[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) acc[q] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+    const float* src = a.part + (long long)b * a.parts * SS + (long long)(m0 + r) * a.np + n0 + c0;
+    for (int p = 0; p < a.parts; ++p)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) acc[q] += *(const f32x4*)(src + (long long)p * SS + 4 * q);
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int m = m0 + r, n = n0 + c0 + 4 * q + e;
+        tile[r][c0 + 4 * q + e] = (m < a.n_true && n < a.n_true) ? ((m == n ? 1.0f : 0.0f) - acc[q][e]) : 0.0f;
+      }
+  }
+  __syncthreads();
+  const bool diag_tile = tm == tn;
+  float part = 0.0f;
+  auto emit = [&](int row0, int col0, bool transposed) {   // this thread's 16 entries of the tile at (row0, col0)
+    float v[16];
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+      const int c = c0 + e;
+      v[e] = transposed ? tile[c][r] : ((diag_tile && c < r) ? tile[c][r] : tile[r][c]);
+    }
+    const long long o = (long long)b * SS + (long long)(row0 + r) * a.np + col0 + c0;
+    if (a.R32) {
+#pragma unroll
+      for (int q = 0; q < 4; ++q) *(f32x4*)(a.R32 + o + 4 * q) = f32x4{v[4 * q], v[4 * q + 1], v[4 * q + 2], v[4 * q + 3]};
+    }
+    if (a.Rb) {
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        u32x4 pk;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) pk[e] = (unsigned)f2bf(v[8 * h + 2 * e]) | ((unsigned)f2bf(v[8 * h + 2 * e + 1]) << 16);
+        *(u32x4*)(a.Rb + o + 8 * h) = pk;
+      }
+    }
+    if (!transposed) {
+#pragma unroll
+      for (int e = 0; e < 16; ++e) part += v[e] * v[e];
+      if (a.diag && diag_tile && r >= c0 && r < c0 + 16) a.diag[(long long)b * a.np + m0 + r] = tile[r][r];
+    }
+  };
+  emit(m0, n0, false);
+  if (!diag_tile) { emit(n0, m0, true); part *= 2.0f; }
+  __shared__ float red[4];
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) part += __shfl_down(part, off, 64);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = part;
+  __syncthreads();
+  if (threadIdx.x == 0) a.rho_part[(long long)b * gridDim.x + blockIdx.x] = (red[0] + red[1]) + (red[2] + red[3]);
+}
+
 }  // namespace
+
+int gram_reduce_parts(int np) { return (np / 64) * (np / 64 + 1) / 2; }
+
+void launch_gram_reduce(const GramReduceArgs& a, int batch, hipStream_t s) {
+  hipLaunchKernelGGL(gram_reduce_kernel, dim3(gram_reduce_parts(a.np), batch), dim3(NT), 0, s, a);
+}
 
 void launch_make_e(float* E, const float* R, const Ctrl* ctrl, int batch, int np, hipStream_t s) {
   const long long total = (long long)np * np;

@@ -57,6 +57,8 @@ struct Plan {
   bool shared_gpu; // PRISM_FLAG_SHARED_GPU
   size_t o_x[2], o_y[2], o_r, o_q, o_t[3];        // fp32 paths (o_y doubles as M64 for inverse root)
   size_t o_xhi[2], o_xlo[2], o_xg[2], o_rb, o_qb; // bf16 polar
+  int ksplit;      // polar: parts of the K loop of X^T X (0 = one pass); partial products at o_gpart
+  size_t o_gpart;
   size_t total;
 };
 
@@ -147,6 +149,20 @@ int make_plan(Plan& P, int fn, int batch, int m, int n, int dt, int degree, int 
     for (int i = 0; i < 2; ++i) { P.o_x[i] = take(B * SS * 4); P.o_y[i] = take(B * SS * 8); }
     P.o_r = take(B * SS * 4);
     for (int i = 0; i < 3; ++i) P.o_t[i] = take(B * SS * 4);
+  }
+  // Polar factor of a few tall matrices: X^T X has few tiles and a long K loop, which would leave
+  // most CUs idle; the loop is then cut into parts that run as separate workgroups and a second
+  // pass adds the partial products up (in part order, so results stay run-to-run identical).
+  P.ksplit = 0; P.o_gpart = 0;
+  static const int no_split_k = getenv("PRISM_NO_SPLIT_K") ? atoi(getenv("PRISM_NO_SPLIT_K")) : 0;
+  if (fn == PRISM_FN_POLAR && !no_split_k && batch <= 8 && P.Lp >= 8192 && P.Sp > 64) {
+    const int tg = dt == PRISM_BF16 ? 128 : P.tile;
+    const long long nt = P.Sp / tg, tri = nt * (nt + 1) / 2, full = nt * nt;
+    if (tri * batch <= 48) {
+      for (int parts = 32; parts >= 2; --parts)
+        if (P.Lp % (parts * 32) == 0 && P.Lp / parts >= 1024 && full * batch * parts <= 4096) { P.ksplit = parts; break; }
+    }
+    if (P.ksplit) P.o_gpart = take(B * P.ksplit * SS * 4);
   }
   P.total = off;
   return PRISM_OK;
@@ -320,9 +336,28 @@ int run_polar_f32(Run& r) {
     GemmDesc g = f32_desc(r, X[cur], Sp, LS, X[cur], Sp, LS, Sp, Sp, Lp, polar ? 1 : 0);
     g.sym = sym;
     g.epi = EPI_RESIDUAL; g.C = R; g.strideC = SS; g.ldc = Sp; g.rho_part = r.rho;
-    { ProfScope ps(PK_F32_RESID, r.s); CHECK_LAUNCH(launch_gemm_f32(g, T, T, r.s)); }
+    if (polar && P.ksplit) {
+      ProfScope ps(PK_F32_RESID, r.s);
+      const int Kp = Lp / P.ksplit;
+      float* gpart = r.at<float>(P.o_gpart);
+      for (int b = 0; b < P.batch; ++b) {   // the parts of one matrix are the batch of a plain product
+        GemmDesc sp = f32_desc(r, X[cur] + (long long)b * LS, Sp, (long long)Kp * Sp, X[cur] + (long long)b * LS, Sp,
+                               (long long)Kp * Sp, Sp, Sp, Kp, 1);
+        sp.batch = P.ksplit; sp.epi = EPI_STORE; sp.C = gpart + (long long)b * P.ksplit * SS; sp.strideC = SS; sp.ldc = Sp;
+        sp.ctrl = r.ctrl + b; sp.ctrl_fixed = 1;
+        CHECK_LAUNCH(launch_gemm_f32(sp, T, T, r.s));
+      }
+      GramReduceArgs ra = {};
+      ra.part = gpart; ra.parts = P.ksplit; ra.np = Sp; ra.n_true = P.S;
+      ra.R32 = R; ra.rho_part = r.rho; ra.ctrl = r.ctrl;
+      launch_gram_reduce(ra, P.batch, r.s);
+      CHECK_LAUNCH(check_hip());
+    } else {
+      ProfScope ps(PK_F32_RESID, r.s);
+      CHECK_LAUNCH(launch_gemm_f32(g, T, T, r.s));
+    }
     if (r.fit_needed(k)) CHECK_LAUNCH(r.chain(R, k));
-    CHECK_LAUNCH(r.solve(k, nparts));
+    CHECK_LAUNCH(r.solve(k, (polar && P.ksplit) ? gram_reduce_parts(Sp) : nparts));
     if (k == r.max_iters) break;
     const float* Bop = R;
     if (P.d == 2) {
@@ -399,13 +434,34 @@ int run_polar_bf16(Run& r) {
     g.C32 = lean ? nullptr : R; g.strideC32 = SS; g.ldc32 = Sp; g.Cb = Rb; g.strideCb = SS; g.ldcb = Sp;
     g.diag = lean ? Dg : nullptr; g.strideDiag = Sp;
     g.rho_part = r.rho; g.ctrl = r.ctrl;
-    { ProfScope ps(PK_BF16_GRAM, r.s); CHECK_LAUNCH(launch_gemm_bf16(g, Tg, r.s)); }
+    if (P.ksplit) {
+      ProfScope ps(PK_BF16_GRAM, r.s);
+      const int Kp = Lp / P.ksplit;
+      const int T1 = (P.tile == 256 && (long long)(Sp / 256) * (Sp / 256) * P.ksplit >= 256) ? 256 : 128;
+      float* gpart = r.at<float>(P.o_gpart);
+      for (int b = 0; b < P.batch; ++b) {   // the parts of one matrix are the batch of a plain product
+        Bf16Desc sp = {};
+        sp.A = Xg[cur] + (long long)b * LS; sp.B = sp.A; sp.strideA = Kp; sp.strideB = Kp; sp.lda = Lp; sp.ldb = Lp;
+        sp.M = Sp; sp.N = Sp; sp.K = Kp; sp.batch = P.ksplit; sp.epi = BEPI_STORE;
+        sp.C32 = gpart + (long long)b * P.ksplit * SS; sp.strideC32 = SS; sp.ldc32 = Sp;
+        sp.ctrl = r.ctrl + b; sp.ctrl_fixed = 1;
+        CHECK_LAUNCH(launch_gemm_bf16(sp, T1, r.s));
+      }
+      GramReduceArgs ra = {};
+      ra.part = gpart; ra.parts = P.ksplit; ra.np = Sp; ra.n_true = P.S;
+      ra.R32 = lean ? nullptr : R; ra.Rb = Rb; ra.diag = lean ? Dg : nullptr; ra.rho_part = r.rho; ra.ctrl = r.ctrl;
+      launch_gram_reduce(ra, P.batch, r.s);
+      CHECK_LAUNCH(check_hip());
+    } else {
+      ProfScope ps(PK_BF16_GRAM, r.s);
+      CHECK_LAUNCH(launch_gemm_bf16(g, Tg, r.s));
+    }
     if (r.fit_needed(k)) {
       if (lean) CHECK_LAUNCH(r.chain(R, k, Rb, Dg, Sp, 1));
       else if (chain_b) CHECK_LAUNCH(r.chain(R, k, Rb, R, SS, Sp + 1));
       else CHECK_LAUNCH(r.chain(R, k));
     }
-    CHECK_LAUNCH(r.solve(k, nparts));
+    CHECK_LAUNCH(r.solve(k, P.ksplit ? gram_reduce_parts(Sp) : nparts));
     if (k == r.max_iters) break;
     const uint16_t* Bop = Rb;
     if (P.d == 2) {

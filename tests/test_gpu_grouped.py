@@ -50,6 +50,28 @@ def test_grouped_polar_equals_single_calls_and_oracle(prism):
     assert _rel(out0, ref) <= 2e-2
 
 
+def test_grouped_fp32_polar_with_small_and_general_groups(prism):
+    """fp32 groups to tolerance: three whose padded iterate is 64 x 64 (they run in the one-workgroup
+    kernel) beside one that takes the general path; same bits as the single calls, oracle parity."""
+    shapes = [(5, 64, 32), (3, 200, 72), (2, 40, 24), (4, 48, 64)]
+    As = [np.concatenate([W.c1_polar_small(m=m, n=n, data_seed=2100 + 10 * g + i) for i in range(b)])
+          for g, (b, m, n) in enumerate(shapes)]
+    single = []
+    for A in As:
+        x = torch.from_numpy(A.copy()).cuda()
+        prism.polar(x, 5, 30, 8, SEED, 1e-6)
+        single.append(x)
+    xs = [torch.from_numpy(A.copy()).cuda() for A in As]
+    _, infos = prism.run_grouped(prism.FN_POLAR, xs, 5, 30, 8, SEED, 1e-6)
+    torch.cuda.synchronize()
+    for g, (x, ref) in enumerate(zip(xs, single)):
+        assert torch.equal(x, ref), g
+        rec = infos[g].read()
+        want, oinfo = O.polar(As[g][0], 5, 30, 8, SEED, 1e-6)
+        assert _rel(x[0].cpu().numpy(), want) <= 1e-5
+        assert rec[0]["iters"] == oinfo["iters"] and rec[0]["status"] == prism.INFO_CONVERGED
+
+
 def test_grouped_call_replays_from_a_hip_graph(prism):
     """The fork onto the internal streams and the join back are event waits, so a grouped call
     captures from the caller's stream like a single one: every replay, with eager work and

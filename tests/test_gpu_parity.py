@@ -473,3 +473,31 @@ def test_small_polar_kernel_options(prism):
     x = torch.from_numpy(A.copy()).cuda()
     info = prism.polar(x, 5, 0, 8, SEED, 1e-6).read()             # no update allowed: input scaled back untouched
     assert info[0]["iters"] == 0 and info[0]["status"] == prism.INFO_BUDGET
+
+
+@pytest.mark.parametrize("dtype,batch,m,n,p_s", [("f32", 1, 9000, 200, 8), ("f32", 3, 130, 8200, 16), ("bf16", 1, 16384, 256, 16),
+                                                 ("bf16", 2, 320, 12288, 16), ("bf16s", 2, 8192, 384, 40)])
+def test_polar_of_a_few_tall_matrices(prism, dtype, batch, m, n, p_s):
+    """Few matrices with one long side: the K loop of X^T X is cut into parts that run side by side
+    and a second pass adds them up.  Tall and wide, fp32 and bf16 (plain and split iterate), with
+    ragged sizes, against the oracle."""
+    A = np.concatenate([W.c1_polar_small(m=m, n=n, data_seed=2300 + i) for i in range(batch)])
+    if dtype == "f32":
+        x = torch.from_numpy(A.copy()).cuda()
+        info = prism.polar(x, 5, 30, p_s, SEED, 1e-6).read()
+        out = x.cpu().numpy()
+        for i in range(batch):
+            ref, oinfo = O.polar(A[i], 5, 30, p_s, SEED, 1e-6)
+            assert _rel(out[i], ref) <= TOL_F32
+            _check_info(info[i], oinfo, res_floor=2e-6, alpha_res_min=1e-3)
+    else:
+        bits = W.to_bf16_bits(A)
+        x = _bf16_tensor(bits.copy())
+        flags = prism.FLAG_BF16_PLAIN_ITERATE if dtype == "bf16" else 0
+        info = prism.polar(x, 5, 6, p_s, SEED, 0.0, flags=flags).read()
+        out = _bf16_to_f64(x)
+        for i in range(batch):
+            ref, oinfo = O.polar(W.from_bf16_bits(bits[i]), 5, 6, p_s, SEED, 0.0)
+            assert info[i]["iters"] == 6
+            assert _rel(out[i], ref) <= TOL_BF16
+            np.testing.assert_allclose(info[i]["alpha"][:6], oinfo["alpha"], atol=3e-2)
