@@ -343,8 +343,9 @@ constexpr int SN = 64, SX = 68, SR = 80;
 __host__ __device__ inline int small_ldv(int ld) { return ld == 16 ? 16 : ld + 16; }
 // the third area holds Q [64][SR] or the two chain buffers [64][ldv], whichever is larger (58 KiB in
 // all for 16 sketch columns, so that two workgroups share a CU; 77 KiB for 64 columns)
+// (16 sketch columns: V_0 .. V_5 all stay in LDS, 6 x [64][16], and the moments are taken from there)
 inline int small_lds_floats(int ld) {
-  const int chain = 2 * SN * small_ldv(ld);
+  const int chain = ld == 16 ? 6 * SN * 16 : 2 * SN * small_ldv(ld);
   return SN * SX + SN * SR + (chain > SN * SR ? chain : SN * SR);
 }
 
@@ -394,7 +395,7 @@ __device__ inline void small_chain_step(const float* Rs, const float* Vin, float
     for (int r = 0; r < 4; ++r) {
       const int row = 16 * wave + 4 * lk + r, col = 16 * j + lr;
       Vout[row * ldv + col] = acc[j][r];
-      Vglobal[row * LD + col] = acc[j][r];
+      if (Vglobal) Vglobal[row * LD + col] = acc[j][r];
     }
 }
 
@@ -410,6 +411,7 @@ __global__ __launch_bounds__(NT) void small_polar_kernel(SmallPolarArgs a) {
   SolveArgs sv = a.sv;
   Ctrl* ctl = &sv.ctrl[b];
   if (ctl->done) return;   // zero or non-finite input: reported by the prepare step
+  if (sv.ld == 16) { sv.V = Ts + SN * 16; sv.vstride = SN * 16; sv.bstride = 0; }
   const int lane = t & 63, wave = t >> 6, lr = lane & 15, lk = lane >> 4;
   const int wm0 = (wave >> 1) * 32, wn0 = (wave & 1) * 32;   // this wave's quadrant of a 64 x 64 result
   {
@@ -459,15 +461,21 @@ __global__ __launch_bounds__(NT) void small_polar_kernel(SmallPolarArgs a) {
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
       };
-      float* vin = Ts;
-      float* vout = Ts + SN * ldv;
-      for (int j = 1; j <= a.nv; ++j) {
-        float* vg = const_cast<float*>(sv.V) + (long long)(j - 1) * sv.vstride + (long long)b * sv.bstride;
-        if (ld == 16) small_chain_step<16>(Rs, vin, vout, vg);
-        else if (ld == 32) small_chain_step<32>(Rs, vin, vout, vg);
-        else small_chain_step<64>(Rs, vin, vout, vg);
-        lds_barrier();
-        float* tmp = vin; vin = vout; vout = tmp;
+      if (ld == 16) {   // V_j at Ts + j * 1024: the moments read them from LDS
+        for (int j = 1; j <= a.nv; ++j) {
+          small_chain_step<16>(Rs, Ts + (j - 1) * SN * 16, Ts + j * SN * 16, nullptr);
+          lds_barrier();
+        }
+      } else {
+        float* vin = Ts;
+        float* vout = Ts + SN * ldv;
+        for (int j = 1; j <= a.nv; ++j) {
+          float* vg = const_cast<float*>(a.sv.V) + (long long)(j - 1) * a.sv.vstride + (long long)b * a.sv.bstride;
+          if (ld == 32) small_chain_step<32>(Rs, vin, vout, vg);
+          else small_chain_step<64>(Rs, vin, vout, vg);
+          lds_barrier();
+          float* tmp = vin; vin = vout; vout = tmp;
+        }
       }
     }
     __threadfence_block();
