@@ -217,6 +217,9 @@ void launch_db_update_m(float* M, const float* N, int np, int n_true, int batch,
                         int nparts, hipStream_t s);
 
 void set_last_error(const char* msg);
+// Raises the dynamic LDS limit of a kernel to `bytes`, once per (device, kernel); the attribute
+// belongs to the device that is current when it is set.  PRISM_OK or PRISM_EHIP.
+int allow_dynamic_lds(const void* kernel, int bytes);
 
 // ---- per-kernel timing with HIP events (off unless prism_profile_enable(1)) ----
 enum ProfKind {

@@ -537,15 +537,8 @@ int launch_small_polar(const SmallPolarArgs& a, int batch, hipStream_t s) {
       a.nv < 1 || a.nv > 5 || batch <= 0)
     return PRISM_EINVAL;
   const size_t lds = (size_t)small_lds_floats(a.sv.ld) * sizeof(float);
-  static bool attr_set = false;
-  if (!attr_set) {
-    if (hipFuncSetAttribute((const void*)small_polar_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                            (int)(small_lds_floats(64) * sizeof(float))) != hipSuccess) {
-      set_last_error("hipFuncSetAttribute(MaxDynamicSharedMemorySize) failed");
-      return PRISM_EHIP;
-    }
-    attr_set = true;
-  }
+  const int rc = allow_dynamic_lds((const void*)small_polar_kernel, (int)(small_lds_floats(64) * sizeof(float)));
+  if (rc != PRISM_OK) return rc;
   hipLaunchKernelGGL(small_polar_kernel, dim3(batch), dim3(NT), lds, s, a);
   return hipGetLastError() == hipSuccess ? PRISM_OK : PRISM_EHIP;
 }

@@ -599,15 +599,8 @@ int launch_te(const Bf16Desc& g, hipStream_t s) {
   const int total = (SYM ? tm * (tm + 1) / 2 : tm * tn) * g.batch;
   // ring of STAGES x (A slab + B slab), or of 3 x (A_hi + A_lo + B)
   const size_t lds = DUAL ? (size_t)3 * 3 * T * 64 : (size_t)stages_of(T) * 2 * T * 64;
-  static bool attr_set = false;  // per instantiation
-  if (!attr_set) {
-    if (hipFuncSetAttribute((const void*)gemm_bf16_kernel<T, EPI, SYM, DUAL>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                            (int)lds) != hipSuccess) {
-      set_last_error("hipFuncSetAttribute(MaxDynamicSharedMemorySize) failed");
-      return PRISM_EHIP;
-    }
-    attr_set = true;
-  }
+  const int rc = allow_dynamic_lds((const void*)gemm_bf16_kernel<T, EPI, SYM, DUAL>, (int)lds);
+  if (rc != PRISM_OK) return rc;
   hipLaunchKernelGGL((gemm_bf16_kernel<T, EPI, SYM, DUAL>), dim3(total), dim3(NT), lds, s, g);
   return hipGetLastError() == hipSuccess ? PRISM_OK : PRISM_EHIP;
 }

@@ -18,6 +18,23 @@ namespace prism {
 static thread_local std::string g_last_error;
 void set_last_error(const char* msg) { g_last_error = msg ? msg : ""; }
 
+int allow_dynamic_lds(const void* kernel, int bytes) {
+  static std::mutex mu;
+  static std::map<std::pair<int, const void*>, int> granted;
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) { set_last_error("hipGetDevice failed"); return PRISM_EHIP; }
+  std::lock_guard<std::mutex> lock(mu);
+  int& have = granted[std::make_pair(dev, kernel)];
+  if (have >= bytes) return PRISM_OK;
+  if (hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes) != hipSuccess) {
+    (void)hipGetLastError();
+    set_last_error("hipFuncSetAttribute(MaxDynamicSharedMemorySize) failed");
+    return PRISM_EHIP;
+  }
+  have = bytes;
+  return PRISM_OK;
+}
+
 // ---------------------------------------------------------------- event profiling
 namespace {
 struct ProfRec { int kind; hipEvent_t a, b; };
