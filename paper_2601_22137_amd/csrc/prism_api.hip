@@ -639,7 +639,7 @@ int run_inv_root_f32(Run& r) {
   float* Tm[3] = {r.at<float>(P.o_t[0]), r.at<float>(P.o_t[1]), r.at<float>(P.o_t[2])};
   const int nparts0 = (Sp / 64) * (Sp / 64);  // residual of M_0 comes from the prepare step (64 x 64 tiles)
   const int nparts = (Sp / 64) * (Sp / 64);   // later ones from the fp64 product (64 x 64 tiles)
-  int cur = 0;
+  int cur = 0, mc = 0;   // current X and M buffers
   for (int k = 0; k <= r.max_iters; ++k) {
     if (k == r.max_iters && r.tol <= 0.0) break;
     if (r.fit_needed(k)) CHECK_LAUNCH(r.chain(R, k));
@@ -649,42 +649,77 @@ int run_inv_root_f32(Run& r) {
     ax.epi = EPI_AXPY; ax.C = X[cur ^ 1]; ax.strideC = SS; ax.ldc = Sp; ax.Cin = X[cur]; ax.strideCin = SS; ax.ldcin = Sp;
     ax.coef_is_alpha = 1; ax.sym = f32_sym();   // X never re-enters M; the power chain below keeps all tiles
     { ProfScope ps(PK_F32_APPLY, r.s); CHECK_LAUNCH(launch_gemm_f32(ax, T, T, r.s)); }
-    // (I + alpha R)^p = I + E_p, built on the part beyond the identity so that fp32 rounding acts
+    // (I + alpha R)^q = I + E_q, built on the part beyond the identity so that fp32 rounding acts
     // on the small quantity only: E_1 = alpha R, squaring E <- 2E + E E, times T: E <- E + E_1 + E E_1.
     // E_1 itself is never stored: wherever it is an operand R stands in and the epilogue supplies
     // the powers of alpha.
-    const float* U = nullptr;   // null: E = E_1 = alpha R
-    int hb = 0;
-    while ((p >> (hb + 1)) != 0) ++hb;
-    for (int bit = hb - 1; bit >= 0; --bit) {
-      float* dst = (U == Tm[1]) ? Tm[2] : Tm[1];
-      const float* E = U ? U : R;
-      GemmDesc sq = f32_desc(r, E, Sp, SS, E, Sp, SS, Sp, Sp, Sp, 0);
-      sq.epi = EPI_AXPY; sq.C = dst; sq.strideC = SS; sq.ldc = Sp; sq.Cin = E; sq.strideCin = SS; sq.ldcin = Sp; sq.c_in = 2.0f;
-      if (!U) { sq.cin_alpha_pow = 1; sq.coef_is_alpha = 2; }
-      { ProfScope ps(PK_F32_STORE, r.s); CHECK_LAUNCH(launch_gemm_f32(sq, T, T, r.s)); }
-      U = dst;
-      if ((p >> bit) & 1) {
-        float* dst2 = (U == Tm[1]) ? Tm[2] : Tm[1];
-        GemmDesc mu = f32_desc(r, U, Sp, SS, R, Sp, SS, Sp, Sp, Sp, 0);          // E + alpha R + alpha E R
-        mu.epi = EPI_AXPY; mu.C = dst2; mu.strideC = SS; mu.ldc = Sp; mu.Cin = U; mu.strideCin = SS; mu.ldcin = Sp; mu.c_in = 1.0f;
-        mu.Cin2 = R; mu.cin2_alpha_pow = 1; mu.coef_is_alpha = 1;
-        { ProfScope ps(PK_F32_STORE, r.s); CHECK_LAUNCH(launch_gemm_f32(mu, T, T, r.s)); }
-        U = dst2;
+    auto square = [&](const float* E /* null: E_1 */, float* dst) -> int {
+      const float* Eop = E ? E : R;
+      GemmDesc sq = f32_desc(r, Eop, Sp, SS, Eop, Sp, SS, Sp, Sp, Sp, 0);
+      sq.epi = EPI_AXPY; sq.C = dst; sq.strideC = SS; sq.ldc = Sp; sq.Cin = Eop; sq.strideCin = SS; sq.ldcin = Sp; sq.c_in = 2.0f;
+      if (!E) { sq.cin_alpha_pow = 1; sq.coef_is_alpha = 2; }
+      ProfScope ps(PK_F32_STORE, r.s);
+      return launch_gemm_f32(sq, T, T, r.s);
+    };
+    auto times_t = [&](const float* U, float* dst) -> int {                      // U + alpha R + alpha U R
+      GemmDesc mu = f32_desc(r, U, Sp, SS, R, Sp, SS, Sp, Sp, Sp, 0);
+      mu.epi = EPI_AXPY; mu.C = dst; mu.strideC = SS; mu.ldc = Sp; mu.Cin = U; mu.strideCin = SS; mu.ldcin = Sp; mu.c_in = 1.0f;
+      mu.Cin2 = R; mu.cin2_alpha_pow = 1; mu.coef_is_alpha = 1;
+      ProfScope ps(PK_F32_STORE, r.s);
+      return launch_gemm_f32(mu, T, T, r.s);
+    };
+    auto m_times = [&](const float* E, const double* Min, double* Mout, float* Rout) -> int {   // Mout = Min + E Min in fp64
+      GemmDesc mn = {};
+      mn.A = E; mn.strideA = SS; mn.lda = Sp; mn.B = Min; mn.strideB = SS; mn.ldb = Sp;
+      mn.M = Sp; mn.N = Sp; mn.K = Sp; mn.batch = P.batch; mn.n_true = P.S; mn.ctrl = r.ctrl;
+      mn.epi = EPI_MNEXT; mn.C = Mout; mn.strideC = SS; mn.ldc = Sp;
+      mn.Cin = Min; mn.strideCin = SS; mn.ldcin = Sp;
+      mn.R32out = Rout; mn.strideR = SS; mn.ldr = Sp; mn.rho_part = r.rho;
+      ProfScope ps(PK_F64_MNEXT, r.s);
+      return launch_gemm_f64a(mn, 64, 64, r.s);
+    };
+    if (p <= 4) {
+      const float* U = nullptr;   // null: E = E_1 = alpha R
+      int hb = 0;
+      while ((p >> (hb + 1)) != 0) ++hb;
+      for (int bit = hb - 1; bit >= 0; --bit) {
+        float* dst = (U == Tm[1]) ? Tm[2] : Tm[1];
+        CHECK_LAUNCH(square(U, dst));
+        U = dst;
+        if ((p >> bit) & 1) {
+          float* dst2 = (U == Tm[1]) ? Tm[2] : Tm[1];
+          CHECK_LAUNCH(times_t(U, dst2));
+          U = dst2;
+        }
+      }
+      if (!U) {   // p = 1: E_p = alpha R.  The product below overwrites R, so it cannot read R as an operand
+        { ProfScope ps(PK_MAKE_T, r.s); launch_make_e(Tm[0], R, r.ctrl, P.batch, Sp, r.s); }
+        CHECK_LAUNCH(check_hip());
+        U = Tm[0];
+      }
+      CHECK_LAUNCH(m_times(U, M[mc], M[mc ^ 1], R));                               // M' = M + E_p M in fp64
+      mc ^= 1;
+    } else {
+      // p = 5 .. 8: (I + alpha R)^p as p / 2 factors (I + E_2), and (I + E_1) for odd p, applied to M
+      // one after the other in fp64.  Every squaring in fp32 doubles the rounding error of its operand
+      // times (1 + E), and M must stay consistent with X^p A: with one fp32 chain up to E_8 the root of
+      // a 1024 x 1024 matrix came out with a relative error of 2e-5, with two factors (I + E_4) 1.6e-5,
+      // with factors of order <= 2 6e-6 (p = 8; 4e-6, 2e-6, 1e-6 for p = 7, 6, 5).
+      float* E2 = Tm[1];
+      CHECK_LAUNCH(square(nullptr, E2));
+      int left = p / 2 + (p & 1);
+      if (p & 1) {
+        { ProfScope ps(PK_MAKE_T, r.s); launch_make_e(Tm[0], R, r.ctrl, P.batch, Sp, r.s); }
+        CHECK_LAUNCH(check_hip());
+        --left;
+        CHECK_LAUNCH(m_times(Tm[0], M[mc], M[mc ^ 1], Tm[2]));   // the residual of an intermediate product goes to a spare array
+        mc ^= 1;
+      }
+      for (; left > 0; --left) {
+        CHECK_LAUNCH(m_times(E2, M[mc], M[mc ^ 1], left == 1 ? R : Tm[2]));
+        mc ^= 1;
       }
     }
-    if (!U) {   // p = 1: E_p = alpha R.  The product below overwrites R, so it cannot read R as an operand
-      { ProfScope ps(PK_MAKE_T, r.s); launch_make_e(Tm[0], R, r.ctrl, P.batch, Sp, r.s); }
-      CHECK_LAUNCH(check_hip());
-      U = Tm[0];
-    }
-    GemmDesc mn = {};                                                             // M' = M + E_p M in fp64
-    mn.A = U; mn.strideA = SS; mn.lda = Sp; mn.B = M[cur]; mn.strideB = SS; mn.ldb = Sp;
-    mn.M = Sp; mn.N = Sp; mn.K = Sp; mn.batch = P.batch; mn.n_true = P.S; mn.ctrl = r.ctrl;
-    mn.epi = EPI_MNEXT; mn.C = M[cur ^ 1]; mn.strideC = SS; mn.ldc = Sp;
-    mn.Cin = M[cur]; mn.strideCin = SS; mn.ldcin = Sp;
-    mn.R32out = R; mn.strideR = SS; mn.ldr = Sp; mn.rho_part = r.rho;
-    { ProfScope ps(PK_F64_MNEXT, r.s); CHECK_LAUNCH(launch_gemm_f64a(mn, 64, 64, r.s)); }
     cur ^= 1;
   }
   return PRISM_OK;

@@ -136,7 +136,7 @@ def test_c3_polar_bf16_reduced(prism):
 
 # ------------------------------------------------------------------ config 4 (reduced)
 
-@pytest.mark.parametrize("n,p", [(256, 4), (200, 4), (384, 2), (130, 3), (128, 1)])
+@pytest.mark.parametrize("n,p", [(256, 4), (200, 4), (384, 2), (130, 3), (128, 1), (192, 8), (128, 6), (100, 5), (64, 7), (512, 8), (320, 7)])
 def test_c4_inv_root_fp32_reduced(prism, n, p):
     A = W.c4_shampoo_spd(n=n, batch=3)
     x = torch.from_numpy(A.copy()).cuda()
