@@ -213,6 +213,9 @@ int launch_spd_inverse(const float* M, float* N, int np, int batch, const Ctrl* 
 void launch_db_moments(const float* M, const float* N, int np, int n_true, int batch, const Ctrl* ctrl, double* cpart,
                        int ngroups, hipStream_t s);
 // M <- 2a(1-a) I + (1-a)^2 M + a^2 N (a = ctrl.alpha) on the true n x n part, partial sums of ||I - M'||_F^2
+// after launch_db_moments (same ngroups): ||M N v - v||^2 partials into slot 16 of cpart; w: [batch][np] scratch
+void launch_db_probe(const float* M, const float* N, int np, int n_true, int batch, const Ctrl* ctrl, float* w, double* cpart,
+                     int ngroups, hipStream_t s);
 void launch_db_update_m(float* M, const float* N, int np, int n_true, int batch, const Ctrl* ctrl, float* rho_part,
                         int nparts, hipStream_t s);
 

@@ -111,7 +111,40 @@ __global__ __launch_bounds__(NT) void db_moments_kernel(const float* __restrict_
     const double d = (red[0][2] + red[1][2]) + (red[2][2] + red[3][2]);
     double* out = cpart + ((long long)b * ngrp + grp) * 17;
     out[0] = a; out[1] = -4.0 * a; out[2] = 4.0 * a + 2.0 * c; out[3] = -4.0 * c; out[4] = d;
-    for (int s = 5; s < 17; ++s) out[s] = 0.0;
+    for (int s = 5; s < 16; ++s) out[s] = 0.0;   // slot 16 belongs to the check of the inverse (db_probe_kernel)
+  }
+}
+
+// Check of the inverse with one probe vector v of +-1 entries: ||M (N v) - v||^2 estimates
+// ||M N - I||_F^2 (its expectation over such v), i.e. the error of N measured against the smallest
+// entries of its spectrum, which is what the large components of X = A^(1/2) inherit.  Pass 0: w = N v.
+// Pass 1: partial sums of (M w - v)^2 into slot 16 of the coefficient partials, which the solve
+// kernel adds up.
+// grid (groups, batch); wave q of group g takes rows 4 g + q, 4 (g + groups) + q, ...
+__device__ inline float probe_entry(int c) { return ((unsigned)c * 2654435761u >> 16) & 1u ? 1.0f : -1.0f; }
+__global__ __launch_bounds__(NT) void db_probe_kernel(const float* __restrict__ A, int np, int n_true, const Ctrl* __restrict__ ctrl,
+                                                      float* __restrict__ w, double* __restrict__ cpart, int pass) {
+  const int b = blockIdx.y, grp = blockIdx.x, ngrp = gridDim.x;
+  if (ctrl[b].done) return;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const float* Ab = A + (long long)b * np * np;
+  float* wb = w + (long long)b * np;
+  double err = 0.0;
+  for (int r = 4 * grp + wave; r < n_true; r += 4 * ngrp) {
+    double dot = 0.0;
+    for (int c = lane; c < n_true; c += 64) dot += (double)Ab[(long long)r * np + c] * (double)(pass == 0 ? probe_entry(c) : wb[c]);
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) dot += __shfl_down(dot, off, 64);
+    if (lane == 0) {
+      if (pass == 0) wb[r] = (float)dot;
+      else { const double d = dot - (double)probe_entry(r); err += d * d; }
+    }
+  }
+  if (pass == 1) {
+    __shared__ double red[4];
+    if (lane == 0) red[wave] = err;
+    __syncthreads();
+    if (threadIdx.x == 0) cpart[((long long)b * ngrp + grp) * 17 + 16] = (red[0] + red[1]) + (red[2] + red[3]);
   }
 }
 
@@ -260,6 +293,12 @@ int launch_spd_inverse(const float* M, float* N, int np, int batch, const Ctrl* 
 void launch_db_moments(const float* M, const float* N, int np, int n_true, int batch, const Ctrl* ctrl, double* cpart,
                        int ngroups, hipStream_t s) {
   hipLaunchKernelGGL(db_moments_kernel, dim3(ngroups, batch), dim3(NT), 0, s, M, N, np, n_true, ctrl, cpart);
+}
+
+void launch_db_probe(const float* M, const float* N, int np, int n_true, int batch, const Ctrl* ctrl, float* w, double* cpart,
+                     int ngroups, hipStream_t s) {
+  hipLaunchKernelGGL(db_probe_kernel, dim3(ngroups, batch), dim3(NT), 0, s, N, np, n_true, ctrl, w, cpart, 0);
+  hipLaunchKernelGGL(db_probe_kernel, dim3(ngroups, batch), dim3(NT), 0, s, M, np, n_true, ctrl, w, cpart, 1);
 }
 
 void launch_db_update_m(float* M, const float* N, int np, int n_true, int batch, const Ctrl* ctrl, float* rho_part,

@@ -187,6 +187,25 @@ __device__ void solve_body(const SolveArgs& a, int b, const double* rho_local = 
   __syncthreads();
   if (s_stop || a.phase == 1) return;
 
+  if (a.fn == PRISM_FN_SQRT_NEWTON) {
+    // The fp32 inverse N_k loses about cond(M_k) * eps * sqrt(n) of its accuracy and X, Y inherit
+    // that; once it is worthless the iteration would still drive M_k to I and report convergence.
+    // Slot 16 of the partials holds ||M_k N_k v - v||^2 for a probe vector v of +-1 entries, an
+    // estimate of ||M_k N_k - I||_F^2: above 10 % relative the matrix stops as diverged, before the
+    // update that would use N_k.
+    if (t == 0) {
+      double e2 = 0.0;
+      for (int gidx = 0; gidx < a.ngroups; ++gidx) e2 += a.cpart[((long long)b * a.ngroups + gidx) * MAXC + 16];
+      if (!(e2 <= 0.01 * (double)a.n)) {
+        ctl->status = PRISM_INFO_DIVERGED; ctl->iters = a.k; ctl->done = 1;
+        info->status = PRISM_INFO_DIVERGED; info->iters = a.k;
+        s_stop = 1;
+      }
+    }
+    __syncthreads();
+    if (s_stop) return;
+  }
+
   double lo, hi;
   if (a.fn == PRISM_FN_INV_ROOT) { lo = 1.0 / a.p; hi = 2.0 / a.p; }
   else if (a.fn == PRISM_FN_INVERSE) { lo = 0.5; hi = 2.0; }

@@ -609,9 +609,10 @@ int run_sqrt_newton_f32(Run& r) {
     CHECK_LAUNCH(r.solve(k, k == 0 ? nparts0 : nparts, 1));
     if (k == r.max_iters) break;
     { ProfScope ps(PK_SPD_INVERSE, r.s); CHECK_LAUNCH(launch_spd_inverse(M, N, Sp, P.batch, r.ctrl, r.at<float>(P.o_t[0]), r.s)); }
-    if (P.p_s > 0 && k >= r.sched_len) {
+    {   // also without a fit: the probe of the inverse shares the partials with the moments
       ProfScope ps(PK_DB_MOMENTS, r.s);
       launch_db_moments(M, N, Sp, P.S, P.batch, r.ctrl, r.at<double>(P.o_cpart), P.ngroups, r.s);
+      launch_db_probe(M, N, Sp, P.S, P.batch, r.ctrl, r.v, r.at<double>(P.o_cpart), P.ngroups, r.s);
     }
     CHECK_LAUNCH(r.solve(k, 0, 2));
     GemmDesc ax = f32_desc(r, X[cur], Sp, SS, N, Sp, SS, Sp, Sp, Sp, 0);

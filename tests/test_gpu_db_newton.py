@@ -129,3 +129,20 @@ def test_sqrt_newton_ill_conditioned(prism, cond):
         assert info[b]["iters"] == oinfo["iters"] and info[b]["status"] == oinfo["status"]
         assert _rel(root[b], rx) <= TOL_F32 * cond / 1e3 * 2
         assert _rel(iroot[b], ry) <= TOL_F32 * cond / 1e3 * 2
+
+
+@pytest.mark.parametrize("fit", [True, False])
+def test_sqrt_newton_stops_when_the_fp32_inverse_is_worthless(prism, fit):
+    """cond 1e7 is beyond what an fp32 inverse can resolve (cond * eps ~ 1): the check tr(M N) = n
+    fails and the matrix stops as diverged instead of running on to a 'converged' M with garbage
+    in X and Y; a well-conditioned matrix of the same call is not affected."""
+    bad = W.spd_conditioned(n=256, batch=1, cond=1e7, data_seed=3300)
+    good = W.spd_conditioned(n=256, batch=1, cond=1e2, data_seed=3301)
+    A = np.concatenate([bad, good])
+    x = torch.from_numpy(A.copy()).cuda()
+    inv, h = prism.sqrt_newton(x, 40, 1e-5, fit=fit)
+    info = h.read()
+    assert info[0]["status"] == prism.INFO_DIVERGED and info[0]["iters"] <= 2
+    rx, ry, oinfo = O.sqrt_db_newton(A[1], 40, 1e-5, fit=fit)
+    assert info[1]["status"] == prism.INFO_CONVERGED and info[1]["iters"] == oinfo["iters"]
+    assert _rel(x.cpu().numpy()[1], rx) <= 1e-5 and _rel(inv.cpu().numpy()[1], ry) <= 1e-5
