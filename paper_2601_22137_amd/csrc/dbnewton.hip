@@ -120,9 +120,11 @@ __global__ __launch_bounds__(NT) void db_moments_kernel(const float* __restrict_
 // entries of its spectrum, which is what the large components of X = A^(1/2) inherit.  Pass 0: w = N v.
 // Pass 1: partial sums of (M w - v)^2 into slot 16 of the coefficient partials, which the solve
 // kernel adds up.
-// grid (groups, batch); wave q of group g takes rows 4 g + q, 4 (g + groups) + q, ...
+// grid (groups, batch); a wave takes 16 rows at a time (16-byte loads, 16 KiB in flight per wave).  The
+// padding needs no mask: M and N are the identity there, so padded rows reproduce v exactly.
 __device__ inline float probe_entry(int c) { return ((unsigned)c * 2654435761u >> 16) & 1u ? 1.0f : -1.0f; }
-__global__ __launch_bounds__(NT) void db_probe_kernel(const float* __restrict__ A, int np, int n_true, const Ctrl* __restrict__ ctrl,
+constexpr int PR = 16;   // rows per wave and sweep
+__global__ __launch_bounds__(NT) void db_probe_kernel(const float* __restrict__ A, int np, const Ctrl* __restrict__ ctrl,
                                                       float* __restrict__ w, double* __restrict__ cpart, int pass) {
   const int b = blockIdx.y, grp = blockIdx.x, ngrp = gridDim.x;
   if (ctrl[b].done) return;
@@ -130,14 +132,31 @@ __global__ __launch_bounds__(NT) void db_probe_kernel(const float* __restrict__ 
   const float* Ab = A + (long long)b * np * np;
   float* wb = w + (long long)b * np;
   double err = 0.0;
-  for (int r = 4 * grp + wave; r < n_true; r += 4 * ngrp) {
-    double dot = 0.0;
-    for (int c = lane; c < n_true; c += 64) dot += (double)Ab[(long long)r * np + c] * (double)(pass == 0 ? probe_entry(c) : wb[c]);
+  for (int r0 = PR * (4 * grp + wave); r0 < np; r0 += 4 * PR * ngrp) {
+    double dot[PR];
 #pragma unroll
-    for (int off = 32; off > 0; off >>= 1) dot += __shfl_down(dot, off, 64);
+    for (int k = 0; k < PR; ++k) dot[k] = 0.0;
+    for (int c = lane * 4; c < np; c += 256) {
+      float4 x;
+      if (pass == 0) x = make_float4(probe_entry(c), probe_entry(c + 1), probe_entry(c + 2), probe_entry(c + 3));
+      else x = *(const float4*)(wb + c);
+#pragma unroll
+      for (int k = 0; k < PR; ++k) {
+        const float4 a = *(const float4*)(Ab + (long long)(r0 + k) * np + c);
+        dot[k] += ((double)a.x * (double)x.x + (double)a.y * (double)x.y) + ((double)a.z * (double)x.z + (double)a.w * (double)x.w);
+      }
+    }
+#pragma unroll
+    for (int k = 0; k < PR; ++k) {
+#pragma unroll
+      for (int off = 32; off > 0; off >>= 1) dot[k] += __shfl_down(dot[k], off, 64);
+    }
     if (lane == 0) {
-      if (pass == 0) wb[r] = (float)dot;
-      else { const double d = dot - (double)probe_entry(r); err += d * d; }
+#pragma unroll
+      for (int k = 0; k < PR; ++k) {
+        if (pass == 0) wb[r0 + k] = (float)dot[k];
+        else { const double d = dot[k] - (double)probe_entry(r0 + k); err += d * d; }
+      }
     }
   }
   if (pass == 1) {
@@ -297,8 +316,9 @@ void launch_db_moments(const float* M, const float* N, int np, int n_true, int b
 
 void launch_db_probe(const float* M, const float* N, int np, int n_true, int batch, const Ctrl* ctrl, float* w, double* cpart,
                      int ngroups, hipStream_t s) {
-  hipLaunchKernelGGL(db_probe_kernel, dim3(ngroups, batch), dim3(NT), 0, s, N, np, n_true, ctrl, w, cpart, 0);
-  hipLaunchKernelGGL(db_probe_kernel, dim3(ngroups, batch), dim3(NT), 0, s, M, np, n_true, ctrl, w, cpart, 1);
+  (void)n_true;
+  hipLaunchKernelGGL(db_probe_kernel, dim3(ngroups, batch), dim3(NT), 0, s, N, np, ctrl, w, cpart, 0);
+  hipLaunchKernelGGL(db_probe_kernel, dim3(ngroups, batch), dim3(NT), 0, s, M, np, ctrl, w, cpart, 1);
 }
 
 void launch_db_update_m(float* M, const float* N, int np, int n_true, int batch, const Ctrl* ctrl, float* rho_part,
