@@ -501,3 +501,50 @@ def test_polar_of_a_few_tall_matrices(prism, dtype, batch, m, n, p_s):
             assert info[i]["iters"] == 6
             assert _rel(out[i], ref) <= TOL_BF16
             np.testing.assert_allclose(info[i]["alpha"][:6], oinfo["alpha"], atol=3e-2)
+
+
+@pytest.mark.parametrize("p_s", [1, 2, 33, 64])
+def test_sketch_width_extremes(prism, p_s):
+    """One sketch row up to the maximum of 64, through the one-workgroup kernel, the general polar
+    path, the inverse root and the coupled square root: same iterations and coefficients as the oracle."""
+    for m, n in [(64, 32), (200, 72)]:
+        A = W.c1_polar_small(m=m, n=n, data_seed=4000 + p_s)
+        x = torch.from_numpy(A.copy()).cuda()
+        info = prism.polar(x, 5, 40, p_s, SEED, 1e-6).read()
+        ref, oinfo = O.polar(A[0], 5, 40, p_s, SEED, 1e-6)
+        assert _rel(x.cpu().numpy()[0], ref) <= TOL_F32
+        _check_info(info[0], oinfo, res_floor=2e-6, alpha_res_min=1e-3)
+    S = W.c4_shampoo_spd(n=160, batch=1)
+    y = torch.from_numpy(S.copy()).cuda()
+    info = prism.inv_root(y, 4, 40, p_s, SEED, 1e-5).read()
+    ref, oinfo = O.inv_root(S[0], 4, 40, p_s, SEED, 1e-5)
+    assert _rel(y.cpu().numpy()[0], ref) <= TOL_F32
+    _check_info(info[0], oinfo, res_floor=2e-6)
+    S = W.c5_wishart_spd(n=192, batch=1)
+    y = torch.from_numpy(S.copy()).cuda()
+    inv, h = prism.sqrt(y, 5, 40, p_s, SEED, 1e-5)
+    rs, ri, oinfo = O.sqrt(S[0], 5, 40, p_s, SEED, 1e-5)
+    assert _rel(y.cpu().numpy()[0], rs) <= TOL_F32 and _rel(inv.cpu().numpy()[0], ri) <= TOL_F32
+    _check_info(h.read()[0], oinfo, res_floor=2e-6)
+
+
+def test_full_iteration_budget(prism):
+    """PRISM_MAX_ITERS = 64 updates with a fixed budget: the report arrays are filled to their last
+    entry (residual[64] stays unset: a fixed budget takes no residual after the last update)."""
+    A = W.c1_polar_small(m=256, n=128, data_seed=4100)
+    x = torch.from_numpy(A.copy()).cuda()
+    info = prism.polar(x, 3, prism.MAX_ITERS, 8, SEED, 0.0).read()[0]
+    ref, oinfo = O.polar(A[0], 3, prism.MAX_ITERS, 8, SEED, 0.0)
+    assert info["iters"] == prism.MAX_ITERS == oinfo["iters"] and info["status"] == prism.INFO_BUDGET
+    assert _rel(x.cpu().numpy()[0], ref) <= TOL_F32
+    assert np.all(info["alpha"] >= 0.5 - 1e-6) and np.all(info["alpha"] <= 1.0 + 1e-6) and info["residual"][64] == -1.0
+    bits = W.to_bf16_bits(A)
+    xb = _bf16_tensor(bits.copy())
+    info = prism.polar(xb, 3, prism.MAX_ITERS, 8, SEED, 0.0).read()[0]
+    refb, _ = O.polar(W.from_bf16_bits(bits[0]), 3, prism.MAX_ITERS, 8, SEED, 0.0)
+    assert info["iters"] == prism.MAX_ITERS and _rel(_bf16_to_f64(xb)[0], refb) <= TOL_BF16
+    B = W.c1_polar_small()
+    xs = torch.from_numpy(B.copy()).cuda()
+    info = prism.polar(xs, 5, prism.MAX_ITERS, 8, SEED, 0.0).read()[0]
+    refs, _ = O.polar(B[0], 5, prism.MAX_ITERS, 8, SEED, 0.0)
+    assert info["iters"] == prism.MAX_ITERS and _rel(xs.cpu().numpy()[0], refs) <= TOL_F32
