@@ -548,3 +548,36 @@ def test_full_iteration_budget(prism):
     info = prism.polar(xs, 5, prism.MAX_ITERS, 8, SEED, 0.0).read()[0]
     refs, _ = O.polar(B[0], 5, prism.MAX_ITERS, 8, SEED, 0.0)
     assert info["iters"] == prism.MAX_ITERS and _rel(xs.cpu().numpy()[0], refs) <= TOL_F32
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_tall_matrices_with_a_degenerate_one(prism, dtype):
+    """The split K loop beside a zero and a non-finite matrix of the same call: those two are reported
+    and left alone, the regular ones come out as when called alone."""
+    m, n = 8500, 136
+    A = np.concatenate([W.c1_polar_small(m=m, n=n, data_seed=2400 + i) for i in range(4)])
+    A[1] = 0.0
+    A[2, 7000, 5] = np.nan
+    if dtype == "f32":
+        x = torch.from_numpy(A.copy()).cuda()
+        info = prism.polar(x, 5, 30, 8, SEED, 1e-6).read()
+        assert list(info["status"]) == [prism.INFO_CONVERGED, prism.INFO_ZERO, prism.INFO_NONFINITE, prism.INFO_CONVERGED]
+        out = x.cpu().numpy()
+        assert not out[1].any() and np.array_equal(out[2], A[2], equal_nan=True)
+        for i in (0, 3):
+            alone = torch.from_numpy(A[i:i + 1].copy()).cuda()
+            prism.polar(alone, 5, 30, 8, SEED, 1e-6)
+            assert torch.equal(alone[0], x[i])
+            ref, _ = O.polar(A[i], 5, 30, 8, SEED, 1e-6)
+            assert _rel(out[i], ref) <= TOL_F32
+    else:
+        bits = W.to_bf16_bits(A)
+        x = _bf16_tensor(bits.copy())
+        info = prism.polar(x, 5, 5, 8, SEED, 0.0, flags=prism.FLAG_BF16_PLAIN_ITERATE).read()
+        assert list(info["status"]) == [prism.INFO_BUDGET, prism.INFO_ZERO, prism.INFO_NONFINITE, prism.INFO_BUDGET]
+        out_bits = x.view(torch.int16).cpu().numpy().view(np.uint16)
+        assert np.array_equal(out_bits[1], bits[1]) and np.array_equal(out_bits[2], bits[2])
+        out = _bf16_to_f64(x)
+        for i in (0, 3):
+            ref, _ = O.polar(W.from_bf16_bits(bits[i]), 5, 5, 8, SEED, 0.0)
+            assert _rel(out[i], ref) <= TOL_BF16
