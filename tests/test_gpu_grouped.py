@@ -158,3 +158,41 @@ def test_shared_gpu_flag_is_a_scheduling_hint(prism):
         prism.polar(unhinted, 5, 5, 16, SEED, 0.0, flags=plain)
         d = (unhinted.float() - hinted.float()).norm() / hinted.float().norm()
         assert float(d) <= 2e-2
+
+
+def test_calls_from_two_host_threads(prism):
+    """Two host threads, each with a stream of its own, issue calls of different shapes at the same
+    time (ctypes releases the GIL during a call): workspaces are per stream and the shared state of
+    the library is locked, so both get the bits of the same calls made one after the other."""
+    import threading
+    jobs = [(np.concatenate([W.c1_polar_small(m=200, n=72, data_seed=2500 + i) for i in range(3)]), 5),
+            (np.concatenate([W.c1_polar_small(m=64, n=32, data_seed=2600 + i) for i in range(6)]), 3)]
+    want = []
+    for A, deg in jobs:
+        x = torch.from_numpy(A.copy()).cuda()
+        prism.polar(x, deg, 30, 8, SEED, 1e-6)
+        want.append(x)
+    torch.cuda.synchronize()
+    got, errors = [None, None], []
+
+    def work(j):
+        try:
+            A, deg = jobs[j]
+            st = torch.cuda.Stream()
+            with torch.cuda.stream(st):
+                for _ in range(20):
+                    x = torch.from_numpy(A.copy()).cuda()
+                    prism.polar(x, deg, 30, 8, SEED, 1e-6)
+                st.synchronize()
+            got[j] = x
+        except Exception as e:          # noqa: BLE001 - reported by the assertion below
+            errors.append(e)
+
+    threads = [threading.Thread(target=work, args=(j,)) for j in range(2)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    assert not errors, errors
+    for j in range(2):
+        assert torch.equal(got[j], want[j]), j
