@@ -581,3 +581,22 @@ def test_tall_matrices_with_a_degenerate_one(prism, dtype):
         for i in (0, 3):
             ref, _ = O.polar(W.from_bf16_bits(bits[i]), 5, 5, 8, SEED, 0.0)
             assert _rel(out[i], ref) <= TOL_BF16
+
+
+@pytest.mark.parametrize("shape", [(64, 32), (200, 72)])
+def test_a_wild_schedule_is_reported_as_diverged(prism, shape):
+    """Caller's coefficients far outside the fit interval make the residual grow: both the
+    one-workgroup kernel and the general path stop the matrix as diverged at the oracle's iteration;
+    coefficients on the wrong side that merely stall run to the budget."""
+    m, n = shape
+    A = W.c1_polar_small(m=m, n=n)
+    x = torch.from_numpy(A.copy()).cuda()
+    info = prism.polar(x, 5, 12, 8, SEED, 1e-6, alpha_schedule=[5.0] * 12).read()[0]
+    _, oinfo = O.polar(A[0], 5, 12, 8, SEED, 1e-6, alpha_schedule=[5.0] * 12)
+    assert info["status"] == prism.INFO_DIVERGED == oinfo["status"] and info["iters"] == oinfo["iters"]
+    assert bool(torch.isfinite(x).all())
+    x = torch.from_numpy(A.copy()).cuda()
+    info = prism.polar(x, 5, 12, 8, SEED, 1e-6, alpha_schedule=[-3.0] * 12).read()[0]
+    ref, oinfo = O.polar(A[0], 5, 12, 8, SEED, 1e-6, alpha_schedule=[-3.0] * 12)
+    assert info["status"] == prism.INFO_BUDGET == oinfo["status"] and info["iters"] == 12
+    assert _rel(x.cpu().numpy()[0], ref) <= TOL_F32
