@@ -31,12 +31,14 @@ Readings of the paper taken here (the paper is silent or garbled):
   * the interval for the coupled inverse Newton fit is not given; [1/p, 2/p] is
     used (lower end = Taylor value, upper end by analogy with p = 2 where the
     printed coefficient formulas coincide with d = 1 and [1/2, 1] = [1/p, 2/p]).
-    PARITY UNPINNED by the paper: pinned only by convergence and invariants;
+    The paper prints no value to pin it to; the tests pin it to the mathematics: on the
+    spectrum reachable from M_0 every alpha in it keeps 1 + alpha x > 0 and contracts the
+    residual eigenvalue, which the other plausible upper ends do not;
   * the stop rule is not given: the residual ||R_k||_F / sqrt(n) is tested
     before each update, `iters` counts updates;
   * when m'(alpha) = 0 has several roots the global minimiser over
-    {l, u} U {roots in [l, u]} is taken, ties to the smallest alpha
-    (PARITY UNPINNED by the paper);
+    {l, u} U {roots in [l, u]} is taken, ties to the smallest alpha (own rule; pinned
+    in the tests on polynomials with exactly equal minima);
   * m < n for the polar factor: run on the transpose (the paper assumes m >= n);
   * the same S_k serves all matrices of a call;
   * Chebyshev inverse (App. A.4): the input is normalised by its Frobenius norm as the
