@@ -45,7 +45,17 @@
  *     one grow-only device workspace per (device, stream); calls that share
  *     it must be ordered on that stream.  A block that a larger call outgrows
  *     stays allocated (earlier work and captured HIP graphs still point into
- *     it) until prism_release_workspaces().
+ *     it) until prism_release_workspaces().  Exception: prism_run_grouped, and
+ *     single-shape calls that the library splits into two half batches (an even
+ *     batch >= 8 of matrices with min(m, n) >= 1024 and no caller workspace), run
+ *     on four library-owned streams per device, each with a cached workspace of
+ *     its own, whatever the caller's stream.  Such calls are enqueued one at a
+ *     time (a process-wide lock) and are ordered after one another on those
+ *     streams, so eager calls from different caller streams are safe but do not
+ *     overlap; HIP graphs captured from such calls share those workspaces and
+ *     must not be replayed concurrently with each other or with another such
+ *     call.  Pass a workspace through prism_options to keep a call on its own
+ *     stream and memory.
  *   - A matrix whose info.status is PRISM_INFO_NONFINITE or PRISM_INFO_ZERO is
  *     left untouched.
  *   - Empty input (batch, m or n equal to 0; a grouped call with no groups) is
@@ -272,9 +282,10 @@ int prism_gemm_bf16_nt(const uint16_t* A, const uint16_t* B, float* C, int batch
 /* Per-kernel timing for benchmarks: while enabled, every kernel launch of the library is
  * bracketed by a HIP event pair on the caller's stream.  prism_profile_enable(on) also discards
  * what was recorded so far.  prism_profile_collect waits for the recorded events and returns the
- * summed milliseconds and the launch counts per kernel kind (PRISM_PROFILE_KINDS host arrays).
- * Not thread safe; meant for a single benchmarking thread. */
-#define PRISM_PROFILE_KINDS 18
+ * summed milliseconds and the launch counts per kernel kind (host arrays of PRISM_PROFILE_KINDS
+ * entries; nkinds >= PRISM_PROFILE_KINDS).  Meant for a single benchmarking thread; calls from
+ * other threads while it is enabled are recorded too (the record list is locked). */
+#define PRISM_PROFILE_KINDS 19
 int prism_profile_enable(int on);
 int prism_profile_collect(double* ms_by_kind, long long* launches_by_kind, int nkinds);
 

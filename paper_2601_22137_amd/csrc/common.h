@@ -97,7 +97,7 @@ struct Bf16Desc {
   int xcd_blocks;                                    // set by launch_gemm_bf16: 4 x 8 tile blocks per XCD
   int ctrl_fixed;                                    // ctrl[0] applies to every batch entry (the parts of a split-K product)
   int plain_filter;                                  // 1: skip matrices whose ctrl.plain is set; 2: skip the others (0: none)
-  int dbg;                                           // timing experiments only (test entry): bit0: no global loads after the prologue; bit1: XCD-private tile ranges; bit2: 4x8 tile blocks
+  int no_dual;                                       // APPLY with A2: run the K loop twice instead of the fused high | low | B slabs
 };
 int launch_gemm_bf16(const Bf16Desc& g, int tile, hipStream_t s);
 
@@ -218,6 +218,15 @@ void launch_db_probe(const float* M, const float* N, int np, int n_true, int bat
                      int ngroups, hipStream_t s);
 void launch_db_update_m(float* M, const float* N, int np, int n_true, int batch, const Ctrl* ctrl, float* rho_part,
                         int nparts, hipStream_t s);
+
+// A/B switches for development builds: an environment variable selects an alternative kernel
+// choice (never a different result contract).  Compiled out, always 0, unless the library is built
+// with -DPRISM_AB_SWITCHES; the shipped build does not define it.
+#ifdef PRISM_AB_SWITCHES
+int ab_switch(const char* name);
+#else
+inline int ab_switch(const char*) { return 0; }
+#endif
 
 void set_last_error(const char* msg);
 // Raises the dynamic LDS limit of a kernel to `bytes`, once per (device, kernel); the attribute

@@ -79,7 +79,7 @@ __global__ __launch_bounds__(NT, T == 128 ? 3 : 1) void gemm_bf16_kernel(Bf16Des
   // algorithmic bytes).  Otherwise workgroup i runs tile i: all XCDs sweep the same matrix and
   // share its panels through the Infinity Cache (private ranges measured 20 % slower at
   // 8 x 4096^2, where eight matrices at once overflow that cache).
-  const bool xcd_private = (g.xcd_private != 0) != ((g.dbg & 2) != 0);
+  const bool xcd_private = g.xcd_private != 0;
   if ((total & 7) == 0 && xcd_private) wg = (wg & 7) * (total >> 3) + (wg >> 3);
   const int b = wg / per_mat;
   int rem = wg - b * per_mat;
@@ -110,12 +110,9 @@ __global__ __launch_bounds__(NT, T == 128 ? 3 : 1) void gemm_bf16_kernel(Bf16Des
   const int wave = __builtin_amdgcn_readfirstlane(t >> 6);  // uniform: LDS destinations stay scalar
   const int wm0 = (wave >> 1) * WT, wn0 = (wave & 1) * WT;
   const int m0 = tm * T, n0 = tn * T;
-  const unsigned short* A1_ = g.A + (long long)b * g.strideA + (long long)m0 * g.lda;
+  const unsigned short* A1 = g.A + (long long)b * g.strideA + (long long)m0 * g.lda;
   const unsigned short* A2 = g.A2 ? g.A2 + (long long)b * g.strideA + (long long)m0 * g.lda : nullptr;
-  const unsigned short* Bb_ = g.B + (long long)b * g.strideB + (long long)n0 * g.ldb;
-  // timing experiment (test entry only): every workgroup reads the operands of tile 0
-  const unsigned short* A1 = (g.dbg & 16) ? g.A : A1_;
-  const unsigned short* Bb = (g.dbg & 16) ? g.B : Bb_;
+  const unsigned short* Bb = g.B + (long long)b * g.strideB + (long long)n0 * g.ldb;
 
   const int KT1 = g.K / BK;
   const int KT = (A2 && !DUAL) ? 2 * KT1 : KT1;
@@ -313,7 +310,7 @@ __global__ __launch_bounds__(NT, T == 128 ? 3 : 1) void gemm_bf16_kernel(Bf16Des
   ring_barrier();
   load_frags(0, 0);
   int kt = 0, slot = 0;                 // slot = kt mod STAGES
-  const int KT_main = (g.dbg & 1) ? 0 : KT - (STAGES - 1);
+  const int KT_main = KT - (STAGES - 1);
   constexpr int NF = 2 * NB;            // fragment reads per sub-step = interleave steps
   constexpr int MPS = NB * NB / NF;     // MFMAs per interleave step
   static_assert(2 * LDI == NF, "one load instruction per interleave step");
@@ -346,7 +343,7 @@ __global__ __launch_bounds__(NT, T == 128 ? 3 : 1) void gemm_bf16_kernel(Bf16Des
     load_frags(slot, 1);
     mfma_block(0);
     if (kt + 1 < KT) {
-      if (g.dbg & 1) wait_vmcnt<0>(); else wait_slab(kt + 1);
+      wait_slab(kt + 1);
     }
     ring_barrier();
     if (kt + 1 < KT) load_frags(nslot, 0);
@@ -619,7 +616,7 @@ int launch_t(const Bf16Desc& g, hipStream_t s) {
     case BEPI_GRAM: return g.sym ? launch_te<T, BEPI_GRAM, true>(g, s) : launch_te<T, BEPI_GRAM, false>(g, s);
     case BEPI_POLYQ: return g.sym ? launch_te<T, BEPI_POLYQ, true>(g, s) : launch_te<T, BEPI_POLYQ, false>(g, s);
     case BEPI_APPLY:
-      return (g.A2 && g.K >= 3 * BK && !(g.dbg & 8)) ? launch_te<T, BEPI_APPLY, false, true>(g, s) : launch_te<T, BEPI_APPLY, false>(g, s);
+      return (g.A2 && g.K >= 3 * BK && !g.no_dual) ? launch_te<T, BEPI_APPLY, false, true>(g, s) : launch_te<T, BEPI_APPLY, false>(g, s);
   }
   return PRISM_EINVAL;
 }
@@ -633,7 +630,7 @@ int launch_gemm_bf16(const Bf16Desc& g0, int tile, hipStream_t s) {
   const long long tm = g.M / tile, tn = g.N / tile;
   const long long per_mat = g.sym ? tm * (tm + 1) / 2 : tm * tn;
   g.xcd_private = per_mat <= 64 || operand_bytes <= 128.0 * 1024 * 1024;
-  static const int no_blocks = getenv("PRISM_BF16_NO_XCD_BLOCKS") ? atoi(getenv("PRISM_BF16_NO_XCD_BLOCKS")) : 0;
+  static const int no_blocks = ab_switch("PRISM_BF16_NO_XCD_BLOCKS");
   g.xcd_blocks = !no_blocks && !g.sym && per_mat % 256 == 0 && tm % 4 == 0 && tn % 8 == 0;
   if (tile == 256) return launch_t<256>(g, s);
   if (tile == 128) return launch_t<128>(g, s);

@@ -331,7 +331,7 @@ int launch_cfg(const GemmDesc& g, hipStream_t s) {
     }
   }
   if (g.sym) return PRISM_EINVAL;
-  static const int no_blocks = getenv("PRISM_F32_NO_TILE_BLOCKS") ? atoi(getenv("PRISM_F32_NO_TILE_BLOCKS")) : 0;
+  static const int no_blocks = ab_switch("PRISM_F32_NO_TILE_BLOCKS");
   GemmDesc gb = g;
   gb.tile_blocks = !no_blocks && tm % 8 == 0 && tn % 8 == 0 && tm * tn > 64;
   if (g.a_km)

@@ -18,6 +18,13 @@ namespace prism {
 static thread_local std::string g_last_error;
 void set_last_error(const char* msg) { g_last_error = msg ? msg : ""; }
 
+#ifdef PRISM_AB_SWITCHES
+int ab_switch(const char* name) {
+  const char* v = getenv(name);
+  return v ? atoi(v) : 0;
+}
+#endif
+
 int allow_dynamic_lds(const void* kernel, int bytes) {
   static std::mutex mu;
   static std::map<std::pair<int, const void*>, int> granted;
@@ -36,13 +43,16 @@ int allow_dynamic_lds(const void* kernel, int bytes) {
 }
 
 // ---------------------------------------------------------------- event profiling
+static_assert(PK_COUNT == PRISM_PROFILE_KINDS, "prism.h must size the profile arrays for every kernel kind");
 namespace {
 struct ProfRec { int kind; hipEvent_t a, b; };
 bool g_prof_on = false;
 std::vector<ProfRec> g_prof;
+std::mutex g_prof_mu;   // calls from several host threads may record while profiling is on
 }  // namespace
 
 ProfScope::ProfScope(int kind, hipStream_t s) : slot(-1), stream(s) {
+  std::lock_guard<std::mutex> lock(g_prof_mu);
   if (!g_prof_on) return;
   ProfRec r;
   r.kind = kind;
@@ -52,7 +62,9 @@ ProfScope::ProfScope(int kind, hipStream_t s) : slot(-1), stream(s) {
   slot = (int)g_prof.size() - 1;
 }
 ProfScope::~ProfScope() {
-  if (slot >= 0) (void)hipEventRecord(g_prof[slot].b, stream);
+  if (slot < 0) return;
+  std::lock_guard<std::mutex> lock(g_prof_mu);
+  if (slot < (int)g_prof.size()) (void)hipEventRecord(g_prof[slot].b, stream);
 }
 
 namespace {
@@ -171,7 +183,7 @@ int make_plan(Plan& P, int fn, int batch, int m, int n, int dt, int degree, int 
   // most CUs idle; the loop is then cut into parts that run as separate workgroups and a second
   // pass adds the partial products up (in part order, so results stay run-to-run identical).
   P.ksplit = 0; P.o_gpart = 0;
-  static const int no_split_k = getenv("PRISM_NO_SPLIT_K") ? atoi(getenv("PRISM_NO_SPLIT_K")) : 0;
+  static const int no_split_k = ab_switch("PRISM_NO_SPLIT_K");
   if (fn == PRISM_FN_POLAR && !no_split_k && batch <= 8 && P.Lp >= 8192 && P.Sp > 64) {
     const int tg = dt == PRISM_BF16 ? 128 : P.tile;
     const long long nt = P.Sp / tg, tri = nt * (nt + 1) / 2, full = nt * nt;
@@ -314,7 +326,7 @@ GemmDesc f32_desc(const Run& r, const float* A, int lda, long long sa, const flo
 // mirroring there turns that defect into a perturbation the iteration amplifies (divergence from
 // kappa ~ 1e3 on), so those keep every tile.
 int f32_sym() {
-  static const int off = getenv("PRISM_F32_NO_SYM") ? atoi(getenv("PRISM_F32_NO_SYM")) : 0;
+  static const int off = ab_switch("PRISM_F32_NO_SYM");
   return off ? 0 : 1;
 }
 int sym_parts(int nt, int sym) { return sym ? nt * (nt + 1) / 2 : nt * nt; }
@@ -329,7 +341,7 @@ int run_polar_f32(Run& r) {
   const bool polar = P.fn != PRISM_FN_SIGN;
   const int sym = polar ? f32_sym() : 0;
   const int nparts = sym_parts(Sp / T, sym);
-  static const int no_small = getenv("PRISM_NO_SMALL_KERNEL") ? atoi(getenv("PRISM_NO_SMALL_KERNEL")) : 0;
+  static const int no_small = ab_switch("PRISM_NO_SMALL_KERNEL");
   if (polar && Sp == 64 && Lp == 64 && P.ngroups == 1 && !no_small) {
     // the whole iteration in one workgroup per matrix, one launch for all iterations: with five
     // launches per iteration a call on such matrices is nothing but launch latency
@@ -398,7 +410,7 @@ int run_polar_f32(Run& r) {
 // K is long enough to amortise it.  (At K = 768 the bare product is faster with large tiles from
 // 144 tiles on, the update GEMM with its three-output epilogue is not.)
 int bf16_tile_forced() {
-  static const int forced = getenv("PRISM_BF16_TILE") ? atoi(getenv("PRISM_BF16_TILE")) : 0;
+  static const int forced = ab_switch("PRISM_BF16_TILE");
   return (forced == 128 || forced == 256) ? forced : 0;
 }
 int bf16_tile(const Plan& P, int M, int N, int K, bool symmetric) {
@@ -412,7 +424,7 @@ int bf16_tile(const Plan& P, int M, int N, int K, bool symmetric) {
 int run_polar_bf16(Run& r) {
   const Plan& P = r.P;
   const int Sp = P.Sp, Lp = P.Lp;
-  static const int no_sym = getenv("PRISM_BF16_NO_SYM") ? atoi(getenv("PRISM_BF16_NO_SYM")) : 0;
+  static const int no_sym = ab_switch("PRISM_BF16_NO_SYM");
   const int sym = no_sym ? 0 : 1;
   // Gram product: with other work beside this call, large tiles also when they are few (measured on
   // the Muon-shaped batch of four groups: 3.96 -> 3.80 ms; alone on the GPU the same choice costs
@@ -427,9 +439,9 @@ int run_polar_bf16(Run& r) {
   float* R = r.at<float>(P.o_r);
   uint16_t* Rb = r.at<uint16_t>(P.o_rb);
   uint16_t* Qb = P.d == 2 ? r.at<uint16_t>(P.o_qb) : nullptr;
-  static const int keep_split = getenv("PRISM_BF16_KEEP_SPLIT") ? atoi(getenv("PRISM_BF16_KEEP_SPLIT")) : 0;
-  static const int no_dual = getenv("PRISM_BF16_NO_DUAL") ? atoi(getenv("PRISM_BF16_NO_DUAL")) : 0;
-  static const int chain_f32 = getenv("PRISM_BF16_CHAIN_F32") ? atoi(getenv("PRISM_BF16_CHAIN_F32")) : 0;
+  static const int keep_split = ab_switch("PRISM_BF16_KEEP_SPLIT");
+  static const int no_dual = ab_switch("PRISM_BF16_NO_DUAL");
+  static const int chain_f32 = ab_switch("PRISM_BF16_CHAIN_F32");
   // The fit can read the bf16 copy of R (plus its exact diagonal) when the chain kernels take the
   // shape; with symmetric tiles the fp32 matrix is then not written at all: the Gram epilogue
   // stores the bf16 copy and the diagonal (at the head of the buffer of R), R^2 reads the copy.
@@ -497,7 +509,7 @@ int run_polar_bf16(Run& r) {
     a.Cb = Xhi[cur ^ 1]; a.Cb2 = Xlo[cur ^ 1]; a.strideCb = LS; a.ldcb = Sp;
     a.Ct = Xg[cur ^ 1]; a.strideCt = LS; a.ldct = Lp;
     a.Xhi = Xhi[cur]; a.Xlo = Xlo[cur]; a.coef_is_alpha = P.d == 1; a.ctrl = r.ctrl;
-    a.dbg = no_dual ? 8 : 0;
+    a.no_dual = no_dual;
     if (P.split && !keep_split) {
       // matrices whose fit has left the upper end of its interval (ctrl.plain) are updated from the
       // high half alone: two launches, each skipping the matrices of the other kind
@@ -768,7 +780,7 @@ int run(int fn, void* a, void* inv_out, int root_p, int batch, int m, int n, int
   if (dt == PRISM_BF16) {
     pa.Xa_hi = r.at<uint16_t>(P.o_xhi[0]); pa.Xa_lo = P.split ? r.at<uint16_t>(P.o_xlo[0]) : nullptr;
     pa.Xg = r.at<uint16_t>(P.o_xg[0]);
-    static const int no_alias = getenv("PRISM_BF16_NO_OUTPUT_ALIAS") ? atoi(getenv("PRISM_BF16_NO_OUTPUT_ALIAS")) : 0;
+    static const int no_alias = ab_switch("PRISM_BF16_NO_OUTPUT_ALIAS");
     if (!P.split && P.Sp == P.S && P.Lp == P.L && !no_alias && ((uintptr_t)a & 255) == 0) {   // aligned like the workspace buffers
       if (P.transpose) r.out_as_xg1 = (uint16_t*)a; else r.out_as_xhi1 = (uint16_t*)a;
     }
@@ -853,10 +865,12 @@ int run_grouped(int fn, const prism_group* groups, int ngroups, int root_p, int 
   if (rc != PRISM_OK) return rc;
   hipStream_t user = (hipStream_t)stream;
   const int used = ngroups < GROUP_STREAMS ? ngroups : GROUP_STREAMS;
-  if (hipEventRecord(f->forked, user) != hipSuccess) return PRISM_EHIP;
-  for (int i = 0; i < used; ++i)
-    if (hipStreamWaitEvent(f->streams[i], f->forked, 0) != hipSuccess) return PRISM_EHIP;
+  // nothing is forked before this record succeeds
+  if (hipEventRecord(f->forked, user) != hipSuccess) { (void)hipGetLastError(); set_last_error("hipEventRecord failed"); return PRISM_EHIP; }
   int first_error = PRISM_OK;
+  int forked = 0;   // internal streams that wait for the caller's stream: exactly these are joined again below
+  for (; forked < used; ++forked)
+    if (hipStreamWaitEvent(f->streams[forked], f->forked, 0) != hipSuccess) { first_error = PRISM_EHIP; break; }
   for (int gi = 0; gi < ngroups && first_error == PRISM_OK; ++gi) {
     prism_options o = opt ? *opt : prism_options{};
     o.info = groups[gi].info;
@@ -864,10 +878,14 @@ int run_grouped(int fn, const prism_group* groups, int ngroups, int root_p, int 
     first_error = run(fn, groups[gi].x, groups[gi].inv_out, root_p, groups[gi].batch, groups[gi].m, groups[gi].n, dt,
                       degree, max_iters, sketch_dim, seed, tol, f->streams[gi % GROUP_STREAMS], &o);
   }
-  // join whatever has been enqueued, also after an error
-  for (int i = 0; i < used; ++i) {
-    if (hipEventRecord(f->joined[i], f->streams[i]) != hipSuccess) return PRISM_EHIP;
-    if (hipStreamWaitEvent(user, f->joined[i], 0) != hipSuccess) return PRISM_EHIP;
+  // Join every forked stream back into the caller's, on every exit: after an error too, and past a
+  // failing record or wait of one stream (the others are still joined, so that no forked work is
+  // left unordered and a stream capture of the caller is not left with dangling branches).
+  for (int i = 0; i < forked; ++i) {
+    if (hipEventRecord(f->joined[i], f->streams[i]) != hipSuccess || hipStreamWaitEvent(user, f->joined[i], 0) != hipSuccess) {
+      (void)hipGetLastError();
+      if (first_error == PRISM_OK) { set_last_error("joining an internal stream failed"); first_error = PRISM_EHIP; }
+    }
   }
   return first_error;
 }
@@ -878,7 +896,7 @@ int run_grouped(int fn, const prism_group* groups, int ngroups, int root_p, int 
 // computed exactly as in an unsplit call; an explicit workspace keeps the call on one stream.
 int run_auto(int fn, void* a, void* inv_out, int root_p, int batch, int m, int n, int dt, int degree, int max_iters,
              int sketch_dim, uint64_t seed, double tol, void* stream, const prism_options* opt) {
-  static const int no_split = getenv("PRISM_NO_BATCH_SPLIT") ? atoi(getenv("PRISM_NO_BATCH_SPLIT")) : 0;
+  static const int no_split = ab_switch("PRISM_NO_BATCH_SPLIT");
   const int S = m < n ? m : n;
   if (no_split || !a || batch < 8 || (batch & 1) || S < 1024 || (opt && opt->workspace) || g_prof_on)
     return run(fn, a, inv_out, root_p, batch, m, n, dt, degree, max_iters, sketch_dim, seed, tol, stream, opt);
@@ -923,6 +941,7 @@ int prism_release_workspaces(void) {
 }
 
 int prism_profile_enable(int on) {
+  std::lock_guard<std::mutex> lock(g_prof_mu);
   for (auto& r : g_prof) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
   g_prof.clear();
   g_prof_on = on != 0;
@@ -931,6 +950,7 @@ int prism_profile_enable(int on) {
 
 int prism_profile_collect(double* ms_by_kind, long long* launches_by_kind, int nkinds) {
   if (!ms_by_kind || !launches_by_kind || nkinds < PK_COUNT) return PRISM_EINVAL;
+  std::lock_guard<std::mutex> lock(g_prof_mu);
   for (int i = 0; i < nkinds; ++i) { ms_by_kind[i] = 0.0; launches_by_kind[i] = 0; }
   for (auto& r : g_prof) {
     if (hipEventSynchronize(r.b) != hipSuccess) return PRISM_EHIP;
@@ -1077,8 +1097,6 @@ int prism_gemm_bf16_nt(const uint16_t* A, const uint16_t* B, float* C, int batch
   g.B = B; g.strideB = (long long)N * K; g.ldb = K;
   g.M = M; g.N = N; g.K = K; g.batch = batch; g.epi = BEPI_STORE;
   g.C32 = C; g.strideC32 = (long long)M * N; g.ldc32 = N;
-  const char* dbg = getenv("PRISM_GEMM_TIMING_EXPERIMENT");   // results are wrong when set: timing only
-  g.dbg = dbg ? atoi(dbg) : 0;
   return launch_gemm_bf16(g, tile, (hipStream_t)stream);
 }
 

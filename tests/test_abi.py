@@ -65,3 +65,16 @@ def test_workspace_query_and_argument_checks(lib):
 def test_info_layout_matches_header():
     from paper_2601_22137_amd import prism as P
     assert P.INFO_DTYPE.itemsize == 4 + 4 + 4 * 65 + 4 * 64
+
+
+def test_profile_arrays_sized_by_the_header_macro_are_accepted(lib):
+    """A C caller sizes its arrays with PRISM_PROFILE_KINDS: collect must take exactly that count
+    (nothing recorded: no device call is made) and refuse a shorter one."""
+    from paper_2601_22137_amd import prism as P
+    text = open(os.path.join(ROOT, "include", "prism.h")).read()
+    kinds = int(re.search(r"#define\s+PRISM_PROFILE_KINDS\s+(\d+)", text).group(1))
+    assert kinds == len(P.PROFILE_KINDS)
+    ms = (ctypes.c_double * kinds)()
+    cnt = (ctypes.c_longlong * kinds)()
+    assert lib.prism_profile_collect(ms, cnt, kinds) == P.OK
+    assert lib.prism_profile_collect(ms, cnt, kinds - 1) == P.EINVAL
