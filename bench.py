@@ -3,8 +3,13 @@
 
 A step is one pass of the whole path (norm, Gram/residual, sketch chain, fit, polynomial build and
 apply, every iteration to the budget or tolerance) over one batch of synthetic matrices that is
-already resident in HBM.  Default workload: the Muon-shaped batch (64 bf16 matrices, 16 each of
-768x768, 768x3072, 3072x768, 768x2304; degree 5, sketch 16, 5 iterations).  Prints one JSON line.
+already resident in HBM.
+
+Default run: the headline is the large polar configuration (8 x 4096 x 4096 bf16, degree 5, sketch
+32, tol 1e-2: the configuration the matrix-core target is stated on); the other four configurations
+are measured in the same run with fewer steps and reported under "configs" of the same JSON line.
+`--workload X` measures X alone (no "configs").  Prints ONE JSON line on stdout; progress goes to
+stderr.
 """
 import argparse
 import json
@@ -19,6 +24,17 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK = {"bf16": 2500.0, "f32": 157.3, "f64": 78.6}   # dense MFMA TFLOP/s, MI355X
+HBM_PEAK_GBS = 8000.0
+TOL = {"c1": 1e-6, "c3": 1e-2, "c4": 1e-5, "c5": 1e-5, "sign": 1e-5, "inverse": 1e-5, "sqrt-newton": 1e-5}
+# steps / warm-up of the configurations measured beside the headline
+SIDE_STEPS = {"c1": (20, 3), "c2": (10, 3), "c3": (5, 2), "c4": (5, 2), "c5": (2, 1)}
+
+
+def log(msg):
+    print("[bench %6.1fs] %s" % (time.perf_counter() - T0, msg), file=sys.stderr, flush=True)
+
+
+T0 = time.perf_counter()
 
 
 def parse():
@@ -26,22 +42,17 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5", "sign", "inverse", "sqrt-newton"])
+    ap.add_argument("--workload", default=None,
+                    choices=["c1", "c2", "c3", "c4", "c5", "sign", "inverse", "sqrt-newton"],
+                    help="measure this workload alone (default: c3 as the headline plus c1, c2, c4, c5 under 'configs')")
     ap.add_argument("--split", action="store_true", help="c2: carry the iterate as a bf16 high+low pair")
     ap.add_argument("--batch", type=int, default=0, help="override the batch size (c3/c4/c5)")
-    ap.add_argument("--streams", type=int, default=0,
-                    help="HIP streams the calls of one step are spread over (default: one per shape group, i.e. 4 for c2)")
-    ap.add_argument("--sub-batches", type=int, default=1,
-                    help="split every group's batch into this many calls (spread over the streams)")
     ap.add_argument("--no-grouped", dest="grouped", action="store_false",
-                    help="c2: four calls on --streams streams per step instead of one prism_run_grouped call (the default, in "
-                         "which the library forks to its internal streams)")
-    ap.add_argument("--graph", dest="graph", action="store_true", default=None,
-                    help="capture every step's calls in a HIP graph beforehand and time the replays (one stream); "
-                         "the default for c2 with the grouped call")
-    ap.add_argument("--no-graph", dest="graph", action="store_false")
+                    help="c2: four calls per step instead of one prism_run_grouped call")
+    ap.add_argument("--no-graph", dest="graph", action="store_false",
+                    help="c2: launch the grouped call eagerly instead of replaying a captured HIP graph")
     ap.add_argument("--only-group", type=int, default=-1, help="c2: run a single shape group (profiling aid)")
-    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle legs")
     ap.add_argument("--no-profile", action="store_true", help="skip the per-kernel event pass")
     ap.add_argument("--copy-probe", action="store_true",
                     help="only copy 1 GiB device to device three times (calibrates the FETCH_SIZE / WRITE_SIZE counters)")
@@ -49,14 +60,15 @@ def parse():
 
 
 class Workload:
-    """name, groups of device tensors, how to call the library, flop model."""
+    """name, groups of host arrays, how to call the library, flop model."""
 
 
-def make_workload(args, torch, prism, W):
+def make_workload(name, args, prism, W):
     wl = Workload()
-    name = args.workload
     wl.name = name
     wl.seed = W.SKETCH_SEED
+    wl.split = False
+    wl.p_s, wl.nv = 0, 0           # sketch width (padded) and products per chain, for the HBM-bound kernels
     if name == "c2":
         wl.desc = "muon-shaped: 64 bf16 matrices = 16 x {768x768, 768x3072, 3072x768, 768x2304}, degree 5, sketch 16, 5 iterations" + \
                   (", split-bf16 iterate" if args.split else ", plain bf16 iterate")
@@ -67,6 +79,7 @@ def make_workload(args, torch, prism, W):
         # so that the same kernels are timed
         wl.call = lambda x: prism.polar(x, 5, 5, 16, wl.seed, 0.0, flags=wl.flags | prism.FLAG_SHARED_GPU)
         wl.split = args.split
+        wl.ld, wl.nv, wl.r_bytes = 16, 5, 2
     elif name == "c3":
         b = args.batch or 8
         wl.desc = "polar of %d x 4096x4096 bf16, sigma log-uniform [1e-4,1], degree 5, sketch 32, tol 1e-2, split-bf16 iterate" % b
@@ -74,41 +87,48 @@ def make_workload(args, torch, prism, W):
         wl.host = [W.c3_polar_large(batch=b)]
         wl.call = lambda x: prism.polar(x, 5, 40, 32, wl.seed, 1e-2)
         wl.split = True
+        wl.ld, wl.nv, wl.r_bytes = 32, 5, 2
     elif name == "c4":
         b = args.batch or 32
         wl.desc = "inverse 4th root of %d x 1024x1024 fp32 SPD (power-law spectrum), sketch 16, tol 1e-5" % b
         wl.dtype = "f32"
         wl.host = [W.c4_shampoo_spd(batch=b)]
         wl.call = lambda x: prism.inv_root(x, 4, 40, 16, wl.seed, 1e-5)
+        wl.ld, wl.nv, wl.r_bytes = 16, 5, 4
     elif name == "c5":
         b = args.batch or 4
         wl.desc = "sqrt + inverse sqrt of %d x 8192x8192 fp32 SPD (Wishart), degree 5, sketch 64, tol 1e-5" % b
         wl.dtype = "f32"
         wl.host = [W.c5_wishart_spd(batch=b)]
         wl.call = lambda x: prism.sqrt(x, 5, 40, 64, wl.seed, 1e-5)[1]
+        wl.ld, wl.nv, wl.r_bytes = 64, 5, 4
     elif name == "sqrt-newton":
         b = args.batch or 4
         wl.desc = "sqrt + inverse sqrt of %d x 8192x8192 fp32 SPD (Wishart, the config-5 inputs) by PRISM DB Newton, tol 1e-5, at most 12 iterations" % b
         wl.dtype = "f32"
         wl.host = [W.c5_wishart_spd(batch=b)]
         wl.call = lambda x: prism.sqrt_newton(x, 12, 1e-5)[1]
+        wl.ld, wl.nv, wl.r_bytes = 0, 0, 4
     elif name == "sign":
         b = args.batch or 8
         wl.desc = "matrix sign of %d x 2048x2048 fp32 symmetric indefinite (|lambda| over 2 decades), degree 5, sketch 32, tol 1e-5" % b
         wl.dtype = "f32"
         wl.host = [W.sign_indefinite(n=2048, batch=b, decades=2.0)]
         wl.call = lambda x: prism.sign(x, 5, 40, 32, wl.seed, 1e-5)
+        wl.ld, wl.nv, wl.r_bytes = 32, 5, 4
     elif name == "inverse":
         b = args.batch or 8
         wl.desc = "Chebyshev inverse of %d x 2048x2048 fp32 non-symmetric (cond 30), sketch 32, tol 1e-5" % b
         wl.dtype = "f32"
         wl.host = [W.inverse_general(n=2048, batch=b, cond=30.0)]
         wl.call = lambda x: prism.inverse(x, 40, 32, wl.seed, 1e-5)
+        wl.ld, wl.nv, wl.r_bytes = 32, 3, 4
     else:
         wl.desc = "polar of one 64x32 fp32 matrix, cond 1e3, degree 5, sketch 8, tol 1e-6"
         wl.dtype = "f32"
         wl.host = [W.c1_polar_small()]
         wl.call = lambda x: prism.polar(x, 5, 30, 8, wl.seed, 1e-6)
+        wl.ld, wl.nv, wl.r_bytes = 16, 5, 4
     wl.n_matrices = sum(h.shape[0] for h in wl.host)
     return wl
 
@@ -154,8 +174,8 @@ def oracle_call(name, host_matrix, W, O, seed):
     return O.polar(host_matrix, 5, 30, 8, seed, 1e-6)
 
 
-KERNEL_OF_KIND = {"bf16_gram": r"gemm_bf16_kernel<\d+, 1,", "bf16_polyq": r"gemm_bf16_kernel<\d+, 2,",
-                  "bf16_apply": r"gemm_bf16_kernel<\d+, 3,"}
+KERNEL_OF_KIND = {"bf16_gram": r"gemm_bf16\w*<\d+, 1,", "bf16_polyq": r"gemm_bf16\w*<\d+, 2,",
+                  "bf16_apply": r"gemm_bf16\w*<\d+, 3,"}
 
 
 def recorded_traffic(workload, kind):
@@ -179,27 +199,19 @@ def recorded_traffic(workload, kind):
     return round(tot["FETCH_SIZE"] / n["FETCH_SIZE"] + tot["WRITE_SIZE"] / n["WRITE_SIZE"])
 
 
-def main():
-    args = parse()
-    if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); --gpus %d is not supported" % args.gpus,
-              file=sys.stderr)
-        sys.exit(2)
-    import torch
-    if args.copy_probe:
-        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")     # 1 GiB
-        dst = torch.empty_like(src)
-        for _ in range(3):
-            dst.copy_(src)
-        torch.cuda.synchronize()
-        print(json.dumps({"copy_probe_bytes": src.numel() * 4, "copies": 3}))
-        return
-    from paper_2601_22137_amd import prism, workloads as W
-    prism.lib()
-    assert torch.cuda.is_available(), "bench.py needs a GPU"
-    torch.cuda.set_device(0)
-    wl = make_workload(args, torch, prism, W)
-    K, Wm = args.steps, args.warmup
+def blas_threads():
+    try:
+        from threadpoolctl import threadpool_info
+        return int(max([p.get("num_threads", 1) for p in threadpool_info()] or [1]))
+    except Exception:
+        return len(os.sched_getaffinity(0))
+
+
+def run_config(name, K, Wm, args, torch, prism, W):
+    """Measures one workload; returns its record (a dict)."""
+    log("%s: generating inputs" % name)
+    wl = make_workload(name, args, prism, W)
+    log("%s: %s" % (name, wl.desc))
 
     # one pristine device copy per step: the calls work in place and nothing is re-uploaded in the timed region
     pristine = [to_device(h, torch) for h in wl.host]
@@ -207,54 +219,21 @@ def main():
     n_copies = K + Wm
     copies = [[p.clone() for p in pristine] for _ in range(n_copies)]
 
-    # The calls of one step (one per shape group) are independent: each goes to a stream of its own
-    # (default priority), so that the small latency-bound kernels of one call run beside the GEMMs
-    # of another.  Consecutive steps queue up behind each other on the same streams.
-    nsub = max(1, args.sub_batches)
-    if args.streams or args.sub_batches > 1 or wl.name != "c2":
-        args.grouped = False
-    if args.graph is None:
-        args.graph = bool(args.grouped)
-    nstreams = 1 if args.grouped else (args.streams or len(wl.host) * nsub)
-    side = [torch.cuda.Stream() for _ in range(nstreams)] if nstreams > 1 else None
+    grouped = bool(args.grouped) and name == "c2" and len(wl.host) > 1
+    graph = grouped and bool(args.graph)
 
-    def parts(x):
-        if nsub == 1:
-            return [x]
-        per = (x.shape[0] + nsub - 1) // nsub
-        return [x[j:j + per] for j in range(0, x.shape[0], per)]
-
-    class Joined:      # the info records of the sub-batch calls of one group, in matrix order
-        def __init__(self, hs):
-            self.hs = hs
-
-        def read(self):
-            return np.concatenate([h.read() for h in self.hs])
-
-    def step(i, use_streams=True):
-        if args.grouped and use_streams and wl.name == "c2":
+    def step(i, use_grouped=True):
+        if grouped and use_grouped:
             return prism.run_grouped(prism.FN_POLAR, copies[i], 5, 5, 16, wl.seed, 0.0, flags=wl.flags)[1]
-        hs, slot = [], 0
-        for x in copies[i]:
-            sub = []
-            for xp in parts(x):
-                if side is None or not use_streams:
-                    sub.append(wl.call(xp))
-                else:
-                    with torch.cuda.stream(side[slot % nstreams]):
-                        sub.append(wl.call(xp))
-                slot += 1
-            hs.append(Joined(sub))
-        return hs
+        return [wl.call(x) for x in copies[i]]
 
     graphs = None
-    if args.graph:
+    if graph:
         # the calls allocate nothing once their workspace exists, so a step can be captured as is;
         # a graph holds fixed pointers, hence one graph per resident copy
-        side = None
         cap = torch.cuda.Stream()
         with torch.cuda.stream(cap):
-            step(0)                      # creates the workspace of this stream
+            step(0)                      # creates the workspaces
             cap.synchronize()
             for dst, src in zip(copies[0], pristine):
                 dst.copy_(src)
@@ -275,61 +254,61 @@ def main():
     for i in range(Wm):
         run_step(i)
     torch.cuda.synchronize()
-    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    ev0.record()
+    # one event before every step and one after the last: the steps queue back to back on the
+    # stream, so consecutive events give each call's duration and first-to-last the whole region
+    evs = [torch.cuda.Event(enable_timing=True) for _ in range(K + 1)]
     handles = None
     for i in range(K):
+        evs[i].record()
         handles = run_step(Wm + i)
-    if side is not None:
-        for st in side:
-            torch.cuda.current_stream().wait_stream(st)
-    ev1.record()
+    evs[K].record()
     torch.cuda.synchronize()
-    ms_total = ev0.elapsed_time(ev1)
+    ms_total = evs[0].elapsed_time(evs[K])
+    per_call = np.array([evs[i].elapsed_time(evs[i + 1]) for i in range(K)])
     ms_per_step = ms_total / K
     value = wl.n_matrices / (ms_per_step * 1e-3)
+    log("%s: %.3f ms per step (median %.3f, min %.3f)" % (name, ms_per_step, float(np.median(per_call)), float(per_call.min())))
 
-    # iteration counts of the last step -> flops
-    infos = []
-    for h in handles:
-        infos.append(h.read())
+    # iteration counts of the last step -> flops; res/tol at the stopping iteration and the one before
+    infos = [h.read() for h in handles]
     algo = execd = 0.0
-    iters_all = []
+    iters_all, at_stop, before_stop = [], [], []
     for h, inf in zip(wl.host, infos):
         m, n = h.shape[1], h.shape[2]
-        fa, fe = flops_per_iteration(wl.name, m, n, getattr(wl, "split", False))
+        fa, fe = flops_per_iteration(wl.name, m, n, wl.split)
         for rec in inf:
-            algo += fa * rec["iters"]
-            execd += fe * rec["iters"]
-            if getattr(wl, "split", False):
+            k = int(rec["iters"])
+            algo += fa * k
+            execd += fe * k
+            if wl.split:
                 # the low half of the iterate is multiplied only until the fitted alpha first leaves the
                 # upper end of its interval (from that update on the library reads the high half alone)
-                al = rec["alpha"][:rec["iters"]]
+                al = rec["alpha"][:k]
                 below = np.nonzero(al < 1.4499)[0]
-                n_split = int(below[0]) if len(below) else int(rec["iters"])
-                execd -= (fe - fa) * (rec["iters"] - n_split)
-            iters_all.append(int(rec["iters"]))
+                n_split = int(below[0]) if len(below) else k
+                execd -= (fe - fa) * (k - n_split)
+            iters_all.append(k)
+            if name in TOL and rec["status"] == prism.INFO_CONVERGED:
+                at_stop.append(float(rec["residual"][k]) / TOL[name])
+                if k > 0:
+                    before_stop.append(float(rec["residual"][k - 1]) / TOL[name])
     tflops_algo = algo / (ms_per_step * 1e-3) / 1e12
     tflops_exec = execd / (ms_per_step * 1e-3) / 1e12
+    margin = None
+    if at_stop:
+        margin = {"res_over_tol_at_stop": [round(min(at_stop), 4), round(max(at_stop), 4)],
+                  "res_over_tol_one_before": [round(min(before_stop), 3), round(max(before_stop), 3)] if before_stop else None}
 
-    # CPU oracle on a bounded sample of the same workload
-    cpu = None
-    parity = None
+    # CPU oracle on a bounded sample of the same workload, compared with the last step's output
+    cpu = parity = None
     if not args.no_cpu:
         from oracle import prism_ref as O
-        try:
-            from threadpoolctl import threadpool_info
-            threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
-        except Exception:
-            threads = len(os.sched_getaffinity(0))
-        # sample sized to 10-30 s of host work where one matrix takes long; config 2 is cheap enough for the whole batch
+        # sample sized to seconds of host work: all 64 of config 2, one matrix where one takes long
         per_group = {"c1": 1, "c2": 16, "c3": 1, "c4": 8, "c5": 1, "sign": 2, "inverse": 2, "sqrt-newton": 1}[wl.name]
-        if wl.name in ("c3", "c5") and wl.host[0].shape[1] > 2048:
-            per_group = 1
-        t_cpu, n_cpu, worst = 0.0, 0, 0.0
-        last = [x for x in copies[Wm + K - 1]]
+        t_cpu, n_cpu, worst, counts_equal = 0.0, 0, 0.0, True
+        last = copies[Wm + K - 1]
         for g, h in enumerate(wl.host):
-            out = last[g]
+            out = last[g][:per_group]
             if out.dtype == torch.bfloat16:
                 out_h = W.from_bf16_bits(out.view(torch.int16).cpu().numpy().view(np.uint16))
             else:
@@ -339,17 +318,27 @@ def main():
                 ref, oinfo = oracle_call(wl.name, h[i], W, O, wl.seed)
                 t_cpu += time.perf_counter() - t0
                 n_cpu += 1
-                rel = float(np.linalg.norm(out_h[i].astype(np.float64) - ref) / np.linalg.norm(ref))
-                worst = max(worst, rel)
-                if oinfo["iters"] != int(infos[g][i]["iters"]):
-                    worst = float("inf")
-        cpu = {"value": round(n_cpu / t_cpu, 4), "unit": "matrices/s", "cores": int(threads), "kind": "oracle",
-               "sample": "%d matrices (%d per shape group) of the same workload, numpy fp64" % (n_cpu, per_group)}
-        parity = {"max_rel_fro_err_vs_oracle": worst, "matrices_checked": n_cpu}
+                worst = max(worst, float(np.linalg.norm(out_h[i].astype(np.float64) - ref) / np.linalg.norm(ref)))
+                if oinfo["iters"] != int(infos[g][i]["iters"]) or oinfo["status"] != int(infos[g][i]["status"]):
+                    counts_equal = False
+        cpu = {"value": round(n_cpu / t_cpu, 4), "unit": "matrices/s", "cores": blas_threads(), "kind": "oracle",
+               "sample": "%d of the %d matrices of the workload (the first %d of each shape group), numpy fp64"
+                         % (n_cpu, wl.n_matrices, per_group)}
+        if name == "c1":
+            from threadpoolctl import threadpool_limits
+            with threadpool_limits(limits=1):
+                t0 = time.perf_counter()
+                for _ in range(20):
+                    oracle_call(wl.name, wl.host[0][0], W, O, wl.seed)
+                cpu["single_thread_value"] = round(20.0 / (time.perf_counter() - t0), 2)
+        parity = {"max_rel_fro_err_vs_oracle": worst, "iteration_counts_and_status_equal": counts_equal,
+                  "matrices_checked": n_cpu, "bar": 2e-2 if wl.dtype == "bf16" else 1e-5}
+        log("%s: oracle %.3f matrices/s, worst rel err %.2e, counts equal: %s" % (name, cpu["value"], worst, counts_equal))
 
     # per-kernel durations (HIP events around each launch) over a repeat of the timed steps
     roofline = None
     kernel_ms = {}
+    hbm = {}
     if not args.no_profile:
         for i in range(n_copies):
             for dst, src in zip(copies[i], pristine):
@@ -358,7 +347,7 @@ def main():
         nprof = min(K, 3)
         prism.profile_enable(True)
         for i in range(nprof):
-            step(Wm + i, use_streams=False)     # one stream: every kernel is timed running alone
+            step(Wm + i, use_grouped=False)     # one stream: every kernel is timed running alone
         torch.cuda.synchronize()
         prof = prism.profile_collect()
         prism.profile_enable(False)
@@ -367,7 +356,7 @@ def main():
                                                           or k == "spd_inverse")]
         dom = max(gemm_kinds, key=lambda k: prof[k][0])
         # algorithmic flops of all launches of that kind in the profiled steps
-        fl = 0.0
+        fl = chain_bytes = moment_bytes = prep_bytes = 0.0
         for h, inf in zip(wl.host, infos):
             m, n = h.shape[1], h.shape[2]
             S, L = min(m, n), max(m, n)
@@ -378,8 +367,14 @@ def main():
                         # one launch runs every iteration: Gram, R^2 and the update
                         "f32_small_polar": 4.0 * L * S * S + 2.0 * S ** 3}[dom]
             for rec in inf:
-                nit = rec["iters"] + (1 if dom in ("bf16_gram", "f32_resid") and rec["status"] == prism.INFO_CONVERGED else 0)
+                k = int(rec["iters"])
+                nit = k + (1 if dom in ("bf16_gram", "f32_resid") and rec["status"] == prism.INFO_CONVERGED else 0)
                 fl += per_iter * nit
+                # HBM-bound kernels: the chain reads R once per product, the moments read the chain
+                # vectors once, pre-scaling reads the input once and writes the iterate once
+                chain_bytes += k * wl.nv * float(S) * S * wl.r_bytes
+                moment_bytes += k * wl.nv * float(S) * wl.ld * 4
+                prep_bytes += 2.0 * m * n * h.dtype.itemsize
         fl *= nprof
         dur_s = prof[dom][0] * 1e-3
         dt_peak = "f64" if dom.startswith("f64") else ("bf16" if dom.startswith("bf16") else "f32")
@@ -387,20 +382,73 @@ def main():
         roofline = {"bound": "mfma", "kernel": dom, "achieved": round(achieved, 2), "peak": PEAK[dt_peak], "unit": "TFLOP/s",
                     "frac": round(achieved / PEAK[dt_peak], 4), "traffic": recorded_traffic(wl.name, dom),
                     "launches": int(prof[dom][1]), "avg_launch_ms": round(prof[dom][0] / prof[dom][1], 4)}
+        for kind, nbytes in (("prep", prep_bytes), ("chain", chain_bytes), ("moments", moment_bytes)):
+            if name != "c1" and kind in prof and prof[kind][1] and nbytes > 0:   # config 1 is one launch, bound by latency
+                gbs = nbytes * nprof / (prof[kind][0] * 1e-3) / 1e9
+                hbm[kind] = {"achieved_GBps": round(gbs, 1), "frac_of_hbm_peak": round(gbs / HBM_PEAK_GBS, 4),
+                             "launches": int(prof[kind][1]), "avg_launch_ms": round(prof[kind][0] / prof[kind][1], 4)}
 
-    out = {
-        "metric": "matrices_per_s", "value": round(value, 3), "unit": "matrices/s", "n_gpus": 1, "steps": K, "warmup": Wm,
-        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": wl.dtype, "data": "synthetic",
-        "config": {"workload": wl.name + ": " + wl.desc, "matrices_per_step": wl.n_matrices,
-                   "input_bytes_per_step": bytes_per_copy, "streams": nstreams,
-                   "calls_per_step": 1 if args.grouped else len(wl.host) * nsub, "hip_graph": bool(args.graph), "grouped_call": bool(args.grouped)},
+    rec = {
+        "workload": wl.name + ": " + wl.desc, "dtype": wl.dtype, "steps": K, "warmup": Wm,
+        "matrices_per_step": wl.n_matrices, "matrices_per_s": round(value, 3),
+        "ms_per_step": round(ms_per_step, 4), "ms_per_step_median": round(float(np.median(per_call)), 4),
+        "ms_per_step_min": round(float(per_call.min()), 4),
         "tflops_algorithmic": round(tflops_algo, 2), "tflops_executed": round(tflops_exec, 2),
         "frac_of_mfma_peak": round(tflops_exec / PEAK[wl.dtype], 4),
+        "frac_of_mfma_peak_algorithmic": round(tflops_algo / PEAK[wl.dtype], 4),
         "iterations": {"min": min(iters_all), "max": max(iters_all)},
-        "kernel_ms_per_step": kernel_ms,
-        "roofline": roofline, "cpu_baseline": cpu, "parity": parity,
+        "stop_margin": margin, "kernel_ms_per_step": kernel_ms,
+        "roofline": roofline, "hbm_bound_kernels": hbm, "cpu_baseline": cpu, "parity": parity,
+        "launch": {"input_bytes_per_step": bytes_per_copy, "calls_per_step": 1 if grouped or len(wl.host) == 1 else len(wl.host),
+                   "hip_graph": graph, "grouped_call": grouped},
     }
+    del copies, pristine, graphs, handles
+    torch.cuda.empty_cache()
+    return rec
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); --gpus %d is not supported" % args.gpus,
+              file=sys.stderr)
+        sys.exit(2)
+    import torch
+    if args.copy_probe:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")     # 1 GiB
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_probe_bytes": src.numel() * 4, "copies": 3}))
+        return
+    from paper_2601_22137_amd import prism, workloads as W
+    prism.lib()
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+
+    head_name = args.workload or "c3"
+    head = run_config(head_name, args.steps, args.warmup, args, torch, prism, W)
+    out = {
+        "metric": "matrices_per_s", "value": head["matrices_per_s"], "unit": "matrices/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": head["ms_per_step"],
+        "ms_per_step_median": head["ms_per_step_median"], "ms_per_step_min": head["ms_per_step_min"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": head["dtype"], "data": "synthetic",
+        "config": dict({"workload": head["workload"], "matrices_per_step": head["matrices_per_step"]}, **head["launch"]),
+        "tflops_algorithmic": head["tflops_algorithmic"], "tflops_executed": head["tflops_executed"],
+        "frac_of_mfma_peak": head["frac_of_mfma_peak"], "frac_of_mfma_peak_algorithmic": head["frac_of_mfma_peak_algorithmic"],
+        "iterations": head["iterations"], "stop_margin": head["stop_margin"],
+        "kernel_ms_per_step": head["kernel_ms_per_step"],
+        "roofline": head["roofline"], "hbm_bound_kernels": head["hbm_bound_kernels"],
+        "cpu_baseline": head["cpu_baseline"], "parity": head["parity"],
+    }
+    if args.workload is None:
+        others = {}
+        for name in ("c1", "c2", "c4", "c5"):
+            k, w = SIDE_STEPS[name]
+            others[name] = run_config(name, k, w, args, torch, prism, W)
+        out["configs"] = others
+    log("done")
     print(json.dumps(out))
 
 

@@ -285,7 +285,7 @@ int prism_gemm_bf16_nt(const uint16_t* A, const uint16_t* B, float* C, int batch
  * summed milliseconds and the launch counts per kernel kind (host arrays of PRISM_PROFILE_KINDS
  * entries; nkinds >= PRISM_PROFILE_KINDS).  Meant for a single benchmarking thread; calls from
  * other threads while it is enabled are recorded too (the record list is locked). */
-#define PRISM_PROFILE_KINDS 19
+#define PRISM_PROFILE_KINDS 20
 int prism_profile_enable(int on);
 int prism_profile_collect(double* ms_by_kind, long long* launches_by_kind, int nkinds);
 

@@ -238,7 +238,7 @@ enum ProfKind {
   PK_PREP = 0, PK_FINAL, PK_SKETCH, PK_CHAIN, PK_SOLVE,
   PK_F32_RESID, PK_F32_POLYQ, PK_F32_APPLY, PK_F32_STORE, PK_F64_MNEXT, PK_MAKE_T,
   PK_BF16_GRAM, PK_BF16_POLYQ, PK_BF16_APPLY, PK_BF16_STORE,
-  PK_SPD_INVERSE, PK_DB_MOMENTS, PK_DB_UPDATE_M, PK_F32_SMALL_POLAR,
+  PK_SPD_INVERSE, PK_DB_MOMENTS, PK_DB_UPDATE_M, PK_F32_SMALL_POLAR, PK_MOMENTS,
   PK_COUNT
 };
 struct ProfScope {   // records an event pair around the launches made during its lifetime

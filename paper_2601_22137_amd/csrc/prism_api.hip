@@ -300,9 +300,12 @@ struct Run {
     a.sched_alpha = k < sched_len ? sched[k] : 0.0f;
     a.last = (k == max_iters);
     a.cpart = at<double>(P.o_cpart); a.ngroups = P.ngroups;
+    if (a.mode == 0 && !a.last && a.ngroups > 1 && P.fn != PRISM_FN_SQRT_NEWTON) {
+      ProfScope ps(PK_MOMENTS, s);
+      launch_moments(a, P.batch, s);
+    }
     {
       ProfScope ps(PK_SOLVE, s);
-      if (a.mode == 0 && !a.last && a.ngroups > 1 && P.fn != PRISM_FN_SQRT_NEWTON) launch_moments(a, P.batch, s);
       launch_solve(a, P.batch, s);
     }
     return check_hip();

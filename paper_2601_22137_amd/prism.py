@@ -31,7 +31,7 @@ EXPORTS = ("prism_workspace_bytes", "prism_release_workspaces", "prism_polar", "
 
 PROFILE_KINDS = ("prep", "final", "sketch", "chain", "solve", "f32_resid", "f32_polyq", "f32_apply", "f32_store",
                  "f64_mnext", "make_t", "bf16_gram", "bf16_polyq", "bf16_apply", "bf16_store", "spd_inverse", "db_moments",
-                 "db_update_m", "f32_small_polar")
+                 "db_update_m", "f32_small_polar", "moments")
 
 
 class Options(ctypes.Structure):

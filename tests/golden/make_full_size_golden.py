@@ -6,6 +6,7 @@ histories, the Frobenius norm of the result and the result at seeded sample posi
 
     python tests/golden/make_full_size_golden.py c3     (about 3 minutes on 8 cores)
     python tests/golden/make_full_size_golden.py c5     (about 15 minutes on 8 cores)
+    python tests/golden/make_full_size_golden.py c5 2   (matrix 2 of the batch -> c5_full_matrix2.txt)
 """
 import os
 import sys
@@ -54,10 +55,12 @@ def main():
               "oracle.polar on workloads.c3_polar_large(batch=1)[0]: degree 5, sketch 32, tol 1e-2, max 40, seed 22137",
               info, [("polar", X)])
     elif which == "c5":
-        A = W.c5_wishart_spd(batch=1)[0]
+        b = int(sys.argv[2]) if len(sys.argv) > 2 else 0      # matrix b of the batch is drawn with data_seed 1005 + b
+        A = W.c5_wishart_spd(batch=1, data_seed=1005 + b)[0]
         S, Si, info = O.sqrt(A, 5, 40, 64, W.SKETCH_SEED, 1e-5)
-        write(os.path.join(HERE, "c5_full_matrix0.txt"),
-              "oracle.sqrt on workloads.c5_wishart_spd(batch=1)[0]: degree 5, sketch 64, tol 1e-5, max 40, seed 22137",
+        write(os.path.join(HERE, "c5_full_matrix%d.txt" % b),
+              "oracle.sqrt on workloads.c5_wishart_spd(batch=1%s)[0]: degree 5, sketch 64, tol 1e-5, max 40, seed 22137"
+              % ("" if b == 0 else ", data_seed=%d" % (1005 + b)),
               info, [("root", S), ("inv_root", Si)])
     else:
         raise SystemExit("usage: make_full_size_golden.py c3|c5")

@@ -1,7 +1,8 @@
 """Full-size parity: the five configurations and the sign, inverse and DB Newton bench workloads at
-their stated sizes, in the launch configuration bench.py times.  The oracle is compared on sampled matrices (live for configs 2 and 4; for
-configs 3 and 5 through expectations stored by tests/golden/make_full_size_golden.py, which calls
-only the oracle), the remaining matrices are checked through properties that hold at any size.
+their stated sizes, in the launch configuration bench.py times.  Configs 2, 3 and 4: every matrix
+against the oracle run live, element by element.  Config 5: matrix 0 live over the whole matrix,
+matrices 1-3 each against its own oracle run stored by tests/golden/make_full_size_golden.py (which
+calls only the oracle); all four also through S S = A and S S^-1 = I in fp64.
 """
 import os
 
@@ -65,10 +66,17 @@ def _sampled_rel_err(x, samples, fro, n=4096):
     return np.sqrt(total) / fro
 
 
+def _margins(name, i, rec, tol):
+    """res/tol at the stopping iteration and the one before (how far the stop decision was from flipping)."""
+    k = int(rec["iters"])
+    r = rec["residual"]
+    print("%s matrix %d: iters %d, res/tol at k-1 = %.3f, at k = %.3f" % (name, i, k, r[k - 1] / tol if k else float("nan"), r[k] / tol))
+
+
 def test_c2_muon_full(prism):
     """64 bf16 matrices, 16 of each shape, plain bf16 iterate, 5 fixed iterations, as one grouped
     call replayed from a HIP graph (the bench launch configuration); the eager call must give the
-    same bits."""
+    same bits.  Every one of the 64 matrices is compared with the oracle element by element."""
     xs, allbits = [], []
     for shape_idx in range(4):
         bits = W.c2_muon_group(shape_idx)
@@ -89,88 +97,101 @@ def test_c2_muon_full(prism):
             side.synchronize()
             for x, e in zip(xs, eager):
                 assert torch.equal(x.view(torch.int16), e.view(torch.int16))
+    worst = 0.0
     for shape_idx in range(4):
         bits, x = allbits[shape_idx], xs[shape_idx]
         info = handles[shape_idx].read()
         out = W.from_bf16_bits(x.view(torch.int16).cpu().numpy().view(np.uint16))
         assert np.all(info["iters"] == 5) and np.all(info["status"] == prism.INFO_BUDGET)
         assert np.all(np.isfinite(out))
-        for i in (0, 7, 15):
+        for i in range(bits.shape[0]):
             ref, oinfo = O.polar(W.from_bf16_bits(bits[i]), 5, 5, 16, SEED, 0.0)
-            assert _rel(out[i], ref) <= 2e-2
+            assert oinfo["iters"] == 5
+            err = _rel(out[i], ref)
+            worst = max(worst, err)
+            assert err <= 2e-2, (shape_idx, i, err)
             np.testing.assert_allclose(info[i]["alpha"][:5], oinfo["alpha"], atol=2e-2)
             np.testing.assert_allclose(info[i]["residual"][:5], oinfo["residual"][:5], rtol=2e-2, atol=5e-3)
-        # every matrix: the squared singular values of the result lie in [0, ~1.5]: the fitted
-        # polynomial never overshoots further than that
-        xf = x.float()
-        gram = xf @ xf.transpose(1, 2) if xf.shape[1] < xf.shape[2] else xf.transpose(1, 2) @ xf
-        ev = torch.linalg.eigvalsh(gram)
-        assert float(ev.max()) < 1.5 and float(ev.min()) > -1e-2
+    print("c2: worst rel. Frobenius error over 64 matrices %.2e" % worst)
 
 
 def test_c3_polar_large_full(prism):
+    """All eight 4096 x 4096 matrices against the oracle run live, element by element: equal
+    iteration counts and statuses per matrix, residual and alpha histories, output within 2e-2.
+    The stored expectations for matrix 0 (written by the oracle-only script) must agree with the
+    live oracle as well, which ties the two together."""
     gold = _read_golden("c3_full_matrix0.txt")
     bits = W.c3_polar_large()
     x = _bf16_tensor(bits)
     info = prism.polar(x, 5, 40, 32, SEED, 1e-2).read()
-    out0 = W.from_bf16_bits(x[0].view(torch.int16).cpu().numpy().view(np.uint16))
-    assert info[0]["iters"] == gold["iters"] and info[0]["status"] == gold["status"], (info[0]["residual"][:17], gold["residual"])
-    k = gold["iters"]
-    got_res, want_res = info[0]["residual"][:k + 1].astype(np.float64), np.array(gold["residual"])
-    assert np.all(np.abs(got_res - want_res) <= 3e-2 * want_res + 5e-3), (got_res, want_res)
-    for j in range(k):
-        if want_res[j] >= 0.1:
-            assert abs(info[0]["alpha"][j] - gold["alpha"][j]) <= 3e-2, (j, info[0]["alpha"][:k], gold["alpha"])
-    assert _sampled_rel_err(out0, gold["polar_samples"], gold["polar_fro"]) <= 2e-2
-    # all eight matrices: converged, orthogonal to the tolerance (plus the bf16 rounding of the output)
+    out = W.from_bf16_bits(x.view(torch.int16).cpu().numpy().view(np.uint16))
     assert np.all(info["status"] == prism.INFO_CONVERGED)
-    assert np.all((info["iters"] >= 12) & (info["iters"] <= 17))
-    xf = x.float()
-    for b in range(x.shape[0]):
-        g = xf[b].T @ xf[b]
-        res = float(torch.linalg.norm(g - torch.eye(4096, device="cuda")) / 64.0)
-        assert res <= 1.3e-2, (b, res)
+    worst = 0.0
+    for b in range(bits.shape[0]):
+        ref, oinfo = O.polar(W.from_bf16_bits(bits[b]), 5, 40, 32, SEED, 1e-2)
+        if b == 0:
+            assert oinfo["iters"] == gold["iters"] and oinfo["status"] == gold["status"]
+            np.testing.assert_allclose(oinfo["residual"], gold["residual"], rtol=1e-9)
+            assert abs(_sampled_rel_err(ref, gold["polar_samples"], gold["polar_fro"])) <= 1e-9
+        _margins("c3", b, info[b], 1e-2)
+        k = oinfo["iters"]
+        assert info[b]["iters"] == k and info[b]["status"] == oinfo["status"], (b, info[b]["residual"][:k + 2], oinfo["residual"])
+        got_res, want_res = info[b]["residual"][:k + 1].astype(np.float64), np.array(oinfo["residual"])
+        assert np.all(np.abs(got_res - want_res) <= 3e-2 * want_res + 5e-3), (b, got_res, want_res)
+        for j in range(k):
+            if want_res[j] >= 0.1:
+                assert abs(info[b]["alpha"][j] - oinfo["alpha"][j]) <= 3e-2, (b, j, info[b]["alpha"][:k], oinfo["alpha"])
+        err = _rel(out[b], ref)
+        worst = max(worst, err)
+        assert err <= 2e-2, (b, err)
+    print("c3: worst rel. Frobenius error over 8 matrices %.2e" % worst)
 
 
 def test_c4_inv_root_full(prism):
+    """All 32 matrices against the oracle run live, element by element."""
     A = W.c4_shampoo_spd()
     x = torch.from_numpy(A.copy()).cuda()
     info = prism.inv_root(x, 4, 40, 16, SEED, 1e-5).read()
     out = x.cpu().numpy()
     assert np.all(info["status"] == prism.INFO_CONVERGED)
-    for i in (0, 13, 31):
+    worst = 0.0
+    for i in range(A.shape[0]):
         ref, oinfo = O.inv_root(A[i], 4, 40, 16, SEED, 1e-5)
-        assert _rel(out[i], ref) <= 1e-5
-        assert info[i]["iters"] == oinfo["iters"]
+        if i % 8 == 0:
+            _margins("c4", i, info[i], 1e-5)
+        err = _rel(out[i], ref)
+        worst = max(worst, err)
+        assert err <= 1e-5, (i, err)
+        assert info[i]["iters"] == oinfo["iters"] and info[i]["status"] == oinfo["status"]
         np.testing.assert_allclose(info[i]["alpha"][:oinfo["iters"]], oinfo["alpha"], atol=2e-3)
-    # every matrix: (A^-1/4)^4 A = I, checked in fp64.  At condition number 1e5 the map X -> X^4 A
-    # amplifies an unstructured error of relative size e in X by roughly 2e3, so the 1e-5 bar on
-    # X corresponds to a defect of a few 1e-2; the matrices the oracle was not run on must stay
-    # at the level of those it was run on.
-    xd = x.double()
-    ad = torch.from_numpy(A).cuda().double()
-    x2 = xd @ xd
-    r = x2 @ x2 @ ad - torch.eye(1024, device="cuda", dtype=torch.float64)
-    res = torch.linalg.norm(r, dim=(1, 2)) / 32.0
-    checked = float(max(res[0], res[13], res[31]))
-    assert float(res.max()) <= 1.5 * checked and float(res.max()) <= 5e-2, res
+    print("c4: worst rel. Frobenius error over 32 matrices %.2e" % worst)
 
 
 def test_c5_sqrt_full(prism):
-    gold = _read_golden("c5_full_matrix0.txt")
+    """Matrix 0 against the oracle run live over the whole matrix (root and inverse root);
+    matrices 1-3 each against their own stored oracle run (iteration count, status, residual and
+    alpha histories, 4608 sampled entries of both outputs; tests/golden/make_full_size_golden.py)."""
     A = W.c5_wishart_spd()
     x = torch.from_numpy(A.copy()).cuda()
     inv, h = prism.sqrt(x, 5, 40, 64, SEED, 1e-5)
     info = h.read()
-    k = gold["iters"]
-    assert info[0]["iters"] == k and info[0]["status"] == gold["status"], (info[0]["residual"][:10], gold["residual"])
-    got_res, want_res = info[0]["residual"][:k + 1].astype(np.float64), np.array(gold["residual"])
-    assert np.all(np.abs(got_res - want_res) <= 2e-2 * want_res + 5e-6), (got_res, want_res)
-    np.testing.assert_allclose(info[0]["alpha"][:k], gold["alpha"], atol=2e-3)
-    root0, inv0 = x[0].cpu().numpy(), inv[0].cpu().numpy()
-    assert _sampled_rel_err(root0, gold["root_samples"], gold["root_fro"]) <= 1e-5
-    assert _sampled_rel_err(inv0, gold["inv_root_samples"], gold["inv_root_fro"]) <= 1e-5
-    assert np.all(info["status"] == prism.INFO_CONVERGED) and np.all(info["iters"] == k)
+    assert np.all(info["status"] == prism.INFO_CONVERGED)
+    for b in range(A.shape[0]):
+        gold = _read_golden("c5_full_matrix%d.txt" % b)
+        _margins("c5", b, info[b], 1e-5)
+        k = gold["iters"]
+        assert info[b]["iters"] == k and info[b]["status"] == gold["status"], (b, info[b]["residual"][:10], gold["residual"])
+        got_res, want_res = info[b]["residual"][:k + 1].astype(np.float64), np.array(gold["residual"])
+        assert np.all(np.abs(got_res - want_res) <= 2e-2 * want_res + 5e-6), (b, got_res, want_res)
+        np.testing.assert_allclose(info[b]["alpha"][:k], gold["alpha"], atol=2e-3)
+        root_b, inv_b = x[b].cpu().numpy(), inv[b].cpu().numpy()
+        assert _sampled_rel_err(root_b, gold["root_samples"], gold["root_fro"]) <= 1e-5
+        assert _sampled_rel_err(inv_b, gold["inv_root_samples"], gold["inv_root_fro"]) <= 1e-5
+    r_ref, i_ref, oinfo = O.sqrt(A[0], 5, 40, 64, SEED, 1e-5)
+    assert info[0]["iters"] == oinfo["iters"] and info[0]["status"] == oinfo["status"]
+    e_root, e_inv = _rel(x[0].cpu().numpy(), r_ref), _rel(inv[0].cpu().numpy(), i_ref)
+    print("c5 matrix 0, whole matrix against the live oracle: root %.2e, inverse root %.2e" % (e_root, e_inv))
+    assert e_root <= 1e-5 and e_inv <= 1e-5
     # every matrix: S S = A and S S^-1 = I, checked in fp64
     eye = torch.eye(8192, device="cuda", dtype=torch.float64)
     for b in range(A.shape[0]):

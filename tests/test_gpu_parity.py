@@ -55,6 +55,22 @@ def _check_info(rec, oinfo, alpha_tol=2e-3, res_rtol=2e-2, res_floor=0.0, fixed_
     assert np.all(np.abs(got - want) <= res_rtol * want + res_floor), (got, want)
 
 
+def _same_stop_or_borderline(rec, oinfo, tol, margin, what):
+    """Iteration counts must be identical.  A difference of one update is accepted only when the
+    stop decision at the disputed iteration was a borderline one on BOTH sides: with k the smaller
+    count, one side saw res_k <= tol and the other res_k > tol, and both values must lie within
+    `margin` (relative) of tol.  The margin found is printed."""
+    kg, ko = int(rec["iters"]), int(oinfo["iters"])
+    if kg == ko:
+        return
+    assert abs(kg - ko) == 1, (what, kg, ko)
+    k = min(kg, ko)
+    rg, ro = float(rec["residual"][k]), float(oinfo["residual"][k])
+    print("%s: iterations %d (GPU) vs %d (oracle); res/tol at the disputed iteration %d: GPU %.4f, oracle %.4f"
+          % (what, kg, ko, k, rg / tol, ro / tol))
+    assert abs(rg / tol - 1.0) <= margin and abs(ro / tol - 1.0) <= margin, (what, rg / tol, ro / tol)
+
+
 # ------------------------------------------------------------------ config 1
 
 def test_c1_polar_fp32_small(prism):
@@ -117,7 +133,20 @@ def test_polar_bf16_ragged_shapes(prism, degree, shape):
             ref, oinfo = O.polar(W.from_bf16_bits(bits[i]), degree, 40, 8, SEED, 1e-2)
             assert oinfo["status"] == O.STATUS_CONVERGED
             assert info[i]["status"] == prism.INFO_CONVERGED
-            assert abs(int(info[i]["iters"]) - oinfo["iters"]) <= 1      # bf16 residual near tol
+            what = "bf16 %dx%d degree %d flags %d matrix %d" % (m, n, degree, flags, i)
+            if flags == 0:
+                # default (split) iterate: identical counts; the bf16 residual carries rounding noise of
+                # a few 1e-4 absolute, so at tol = 1e-2 a stop decision within 10 % of tol may fall either way
+                _same_stop_or_borderline(info[i], oinfo, 1e-2, 0.10, what)
+            else:
+                # PRISM_FLAG_BF16_PLAIN_ITERATE rounds the iterate itself to bf16 after every update, which
+                # is a reduced-precision option and not the parity configuration for inputs of condition
+                # number 1e3 like these: the rounding slows the small singular values down, the call may need
+                # one update more than the oracle (never fewer), and the output bar still holds
+                extra = int(info[i]["iters"]) - oinfo["iters"]
+                if extra:
+                    print("%s: %d update(s) more than the oracle" % (what, extra))
+                assert 0 <= extra <= 1, (what, int(info[i]["iters"]), oinfo["iters"])
             assert _rel(out[i], ref) <= TOL_BF16
 
 
@@ -178,8 +207,12 @@ def test_sqrt_fp32_ill_conditioned(prism, degree, cond):
     for i in range(2):
         r_ref, i_ref, oinfo = O.sqrt(A[i], degree, 60, 32, SEED, 1e-5)
         assert oinfo["status"] == O.STATUS_CONVERGED
-        # at cond = 1e5 the fp32 residual floor is close enough to tol to move the stop by one step
-        assert abs(int(info[i]["iters"]) - oinfo["iters"]) <= (1 if cond > 1e4 else 0)
+        # at cond = 1e5 the fp32 residual floor (a few 1e-6) is close enough to tol = 1e-5 to move the
+        # stop by one step when the residual at the disputed iteration is within 30 % of tol
+        if cond > 1e4:
+            _same_stop_or_borderline(info[i], oinfo, 1e-5, 0.3, "sqrt cond %.0e degree %d matrix %d" % (cond, degree, i))
+        else:
+            assert int(info[i]["iters"]) == oinfo["iters"]
         assert info[i]["status"] == oinfo["status"]
         assert _rel(root[i], r_ref) <= TOL_F32
         assert _rel(iroot[i], i_ref) <= TOL_F32 * max(1.0, cond / 1e3)
