@@ -157,6 +157,28 @@ int prism_polar_ex(void* x, int batch, int m, int n, prism_dtype dt, int degree,
                    int sketch_dim, uint64_t seed, double tol, void* stream,
                    const prism_options* opt);
 
+/* prism_polar_ex for callers that cannot allocate device memory: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and the
+ * same results as prism_polar_ex on one stream, but every intermediate (iterates, R, Q, sketches,
+ * chain vectors, control blocks) lives in a static device array of PRISM_STATIC_SCRATCH_BYTES
+ * that is part of the library's code object: each GPU the library runs on holds its own copy
+ * until the process ends.  The call makes no hipMalloc / hipFree, creates no stream or event and
+ * records no hipMemsetAsync; it enqueues kernels on `stream` and returns.
+ *   - opt may be NULL; opt->workspace must be NULL (PRISM_EINVAL otherwise).  opt->info, flags,
+ *     warm_iters and the coefficient schedule work as in prism_polar_ex.
+ *   - A call whose intermediates need more than the array (prism_workspace_bytes tells; e.g. one
+ *     1024 x 1024 bf16 matrix with the split iterate needs 27 MB, sixteen 768 x 768 ones do not
+ *     fit) returns PRISM_EUNSUPPORTED before anything is enqueued, with a message in
+ *     prism_last_error().
+ *   - All calls on one GPU share that GPU's array, which keeps the contents of the last call;
+ *     every call initialises what it reads.  Two calls that overlap in time on one GPU (different
+ *     streams, or concurrent replays of graphs captured from them) race: order them.
+ *   - Timing through prism_profile_enable does not see this call. */
+#define PRISM_STATIC_SCRATCH_BYTES (32u << 20)
+int prism_polar_static(void* x, int batch, int m, int n, prism_dtype dt, int degree, int max_iters,
+                       int sketch_dim, uint64_t seed, double tol, void* stream,
+                       const prism_options* opt);
+
 /* Coupled square root (Table 1, "A^{1/2}, A^{-1/2}"; Theorem 3).  a[batch][n][n]
  * symmetric positive definite is replaced by A^{1/2}; inv_out[batch][n][n]
  * receives A^{-1/2}.  m must equal n. */

@@ -47,13 +47,14 @@ static_assert(PK_COUNT == PRISM_PROFILE_KINDS, "prism.h must size the profile ar
 namespace {
 struct ProfRec { int kind; hipEvent_t a, b; };
 bool g_prof_on = false;
+thread_local bool t_prof_off = false;   // set while an entry point that must not create HIP objects runs on this thread
 std::vector<ProfRec> g_prof;
 std::mutex g_prof_mu;   // calls from several host threads may record while profiling is on
 }  // namespace
 
 ProfScope::ProfScope(int kind, hipStream_t s) : slot(-1), stream(s) {
   std::lock_guard<std::mutex> lock(g_prof_mu);
-  if (!g_prof_on) return;
+  if (!g_prof_on || t_prof_off) return;
   ProfRec r;
   r.kind = kind;
   if (hipEventCreate(&r.a) != hipSuccess || hipEventCreate(&r.b) != hipSuccess) return;
@@ -920,6 +921,41 @@ int run_auto(int fn, void* a, void* inv_out, int root_p, int batch, int m, int n
 }  // namespace
 }  // namespace prism
 
+// Device memory of the entry point that allocates nothing: one array per GPU, part of the loaded
+// code object, alive until the process ends.  In host code this name only stands for the symbol;
+// the device address is looked up once per device and that pointer is what the kernels get.
+// (No `used` attribute: the compiler gives a static device variable that host code refers to a
+// global symbol in the code object by itself, which is what the runtime's lookup by name needs;
+// with the attribute the symbol stays local and the lookup fails.)
+static __device__ __align__(256) unsigned char scratch[PRISM_STATIC_SCRATCH_BYTES];
+
+namespace prism {
+namespace {
+std::mutex g_scratch_mu;
+std::map<int, void*> g_scratch_ptr;   // device ordinal -> address of that device's copy of `scratch`
+
+int static_scratch(void** out) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) { (void)hipGetLastError(); set_last_error("hipGetDevice failed"); return PRISM_EHIP; }
+  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  auto it = g_scratch_ptr.find(dev);
+  if (it == g_scratch_ptr.end()) {
+    void* ptr = nullptr;   // the current device is `dev`: the address returned is that of its copy
+    const hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !ptr) {
+      (void)hipGetLastError();
+      set_last_error("hipGetSymbolAddress of the static scratch array failed");
+      return PRISM_EHIP;
+    }
+    if ((uintptr_t)ptr & 255) { set_last_error("static scratch array is not 256-byte aligned"); return PRISM_EHIP; }
+    it = g_scratch_ptr.emplace(dev, ptr).first;
+  }
+  *out = it->second;
+  return PRISM_OK;
+}
+}  // namespace
+}  // namespace prism
+
 using namespace prism;
 
 extern "C" {
@@ -985,6 +1021,33 @@ int prism_polar_ex(void* x, int batch, int m, int n, prism_dtype dt, int degree,
                    uint64_t seed, double tol, void* stream, const prism_options* opt) {
   return run_auto(PRISM_FN_POLAR, x, nullptr, 0, batch, m, n, (int)dt, degree, max_iters, sketch_dim, seed, tol, stream, opt);
 }
+int prism_polar_static(void* x, int batch, int m, int n, prism_dtype dt, int degree, int max_iters, int sketch_dim,
+                       uint64_t seed, double tol, void* stream, const prism_options* opt) {
+  set_last_error("");
+  if (opt && opt->workspace) { set_last_error("prism_polar_static takes no workspace: it uses the static array"); return PRISM_EINVAL; }
+  if (batch < 0 || m < 0 || n < 0) return PRISM_EINVAL;
+  prism_options o = opt ? *opt : prism_options{};
+  if (batch > 0 && m > 0 && n > 0) {
+    Plan P;
+    const int rc = make_plan(P, PRISM_FN_POLAR, batch, m, n, (int)dt, degree, sketch_dim, 0, o.flags);
+    if (rc != PRISM_OK) return rc;
+    if (P.total > (size_t)PRISM_STATIC_SCRATCH_BYTES) {
+      set_last_error("prism_polar_static: this call needs more than PRISM_STATIC_SCRATCH_BYTES of scratch; use prism_polar_ex");
+      return PRISM_EUNSUPPORTED;
+    }
+    void* ptr = nullptr;
+    const int rs = static_scratch(&ptr);
+    if (rs != PRISM_OK) return rs;
+    o.workspace = ptr;
+    o.workspace_bytes = (size_t)PRISM_STATIC_SCRATCH_BYTES;
+  }
+  // straight to the single-stream driver: no internal streams, no cached workspace, no timing events
+  t_prof_off = true;
+  const int rc = run(PRISM_FN_POLAR, x, nullptr, 0, batch, m, n, (int)dt, degree, max_iters, sketch_dim, seed, tol, stream, &o);
+  t_prof_off = false;
+  return rc;
+}
+
 int prism_sqrt(void* a, void* inv_out, int batch, int m, int n, prism_dtype dt, int degree, int max_iters,
                int sketch_dim, uint64_t seed, double tol, void* stream) {
   return run_auto(PRISM_FN_SQRT, a, inv_out, 0, batch, m, n, (int)dt, degree, max_iters, sketch_dim, seed, tol, stream, nullptr);

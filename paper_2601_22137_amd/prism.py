@@ -23,7 +23,7 @@ INFO_CONVERGED, INFO_BUDGET, INFO_NONFINITE, INFO_ZERO, INFO_DIVERGED = 0, 1, 2,
 INFO_DTYPE = np.dtype([("iters", np.int32), ("status", np.int32),
                        ("residual", np.float32, (MAX_ITERS + 1,)), ("alpha", np.float32, (MAX_ITERS,))])
 
-EXPORTS = ("prism_workspace_bytes", "prism_release_workspaces", "prism_polar", "prism_polar_ex", "prism_sqrt", "prism_sqrt_ex",
+EXPORTS = ("prism_workspace_bytes", "prism_release_workspaces", "prism_polar", "prism_polar_ex", "prism_polar_static", "prism_sqrt", "prism_sqrt_ex",
            "prism_inv_root", "prism_inv_root_ex", "prism_sign", "prism_sign_ex", "prism_inverse", "prism_inverse_ex", "prism_sqrt_newton", "prism_sqrt_newton_ex", "prism_spd_inverse", "prism_run_grouped",
            "prism_sketch", "prism_gauss_parts", "prism_chain_product", "prism_chain_product_bf16", "prism_gemm_f32",
            "prism_gemm_f64a", "prism_gemm_bf16_nt", "prism_profile_enable", "prism_profile_collect",
@@ -63,6 +63,7 @@ def lib():
         L.prism_workspace_bytes.argtypes = [i, i, i, i, i, i, i, i, ctypes.POINTER(ctypes.c_size_t)]
         L.prism_polar.argtypes = [vp, i, i, i, i, i, i, i, u64, dbl, vp]
         L.prism_polar_ex.argtypes = L.prism_polar.argtypes + [ctypes.POINTER(Options)]
+        L.prism_polar_static.argtypes = L.prism_polar_ex.argtypes
         L.prism_sqrt.argtypes = [vp, vp, i, i, i, i, i, i, i, u64, dbl, vp]
         L.prism_sqrt_ex.argtypes = L.prism_sqrt.argtypes + [ctypes.POINTER(Options)]
         L.prism_inv_root.argtypes = [vp, i, i, i, i, i, i, i, i, u64, dbl, vp]
@@ -149,6 +150,33 @@ def polar(x, degree=5, max_iters=30, sketch_dim=8, seed=22137, tol=1e-6, flags=0
     o = _options(info, flags, warm_iters, workspace, alpha_schedule)
     _check(lib().prism_polar_ex(x.data_ptr(), b, m, n, _dtype_code(x), degree, max_iters, sketch_dim, seed, tol,
                                 _stream(), ctypes.byref(o)))
+    return info
+
+
+STATIC_SCRATCH_BYTES = 32 << 20
+
+
+def new_info(batch, device="cuda"):
+    """An info handle made ahead of time, for calls that must not allocate (polar_static)."""
+    return _Info(batch, device)
+
+
+def polar_static(x, degree=5, max_iters=30, sketch_dim=8, seed=22137, tol=1e-6, flags=0, warm_iters=0, info=None,
+                 alpha_schedule=None):
+    """polar() through the entry point that allocates nothing: the library's intermediates live in
+    its static device array (STATIC_SCRATCH_BYTES; larger calls raise PRISM_EUNSUPPORTED).  `info` is
+    a handle from new_info() made beforehand, or None; nothing is allocated here either."""
+    b, m, n = _batched(x)
+    o = Options()
+    if alpha_schedule is not None and len(alpha_schedule) > 0:
+        o._sched = (ctypes.c_float * len(alpha_schedule))(*[float(a) for a in alpha_schedule])
+        o.alpha_schedule = ctypes.cast(o._sched, ctypes.POINTER(ctypes.c_float))
+        o.schedule_len = len(alpha_schedule)
+    o.flags = flags
+    o.warm_iters = warm_iters
+    o.info = info.buf.data_ptr() if info is not None else None
+    _check(lib().prism_polar_static(x.data_ptr(), b, m, n, _dtype_code(x), degree, max_iters, sketch_dim, seed, tol,
+                                    _stream(), ctypes.byref(o)))
     return info
 
 
