@@ -140,11 +140,13 @@ def to_device(h, torch):
 
 
 def flops_per_iteration(name, m, n, split):
-    """(algorithmic, executed) GEMM flops of one iteration for one matrix (dense, no symmetry savings)."""
+    """(algorithmic, executed) GEMM flops of one iteration for one matrix.  Algorithmic: the dense
+    products the method defines.  Executed: what the matrix cores run, i.e. half of the symmetric
+    products of the polar iteration (Gram matrix and R^2: upper triangle of tiles only)."""
     S, L = min(m, n), max(m, n)
     if name in ("c1", "c2", "c3"):
         algo = 4.0 * L * S * S + 2.0 * S ** 3
-        return algo, algo + (2.0 * L * S * S if split else 0.0)
+        return algo, algo - (L * S * S + S ** 3) * (1.0 if name != "c1" else 0.0)
     if name == "c5":
         return 8.0 * n ** 3, 8.0 * n ** 3
     if name == "sqrt-newton":           # block Gauss-Jordan inverse (2 n^3) and the two updates
@@ -280,13 +282,6 @@ def run_config(name, K, Wm, args, torch, prism, W):
             k = int(rec["iters"])
             algo += fa * k
             execd += fe * k
-            if wl.split:
-                # the low half of the iterate is multiplied only until the fitted alpha first leaves the
-                # upper end of its interval (from that update on the library reads the high half alone)
-                al = rec["alpha"][:k]
-                below = np.nonzero(al < 1.4499)[0]
-                n_split = int(below[0]) if len(below) else k
-                execd -= (fe - fa) * (k - n_split)
             iters_all.append(k)
             if name in TOL and rec["status"] == prism.INFO_CONVERGED:
                 at_stop.append(float(rec["residual"][k]) / TOL[name])

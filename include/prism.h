@@ -292,8 +292,8 @@ int prism_spd_inverse(const float* a, float* out, int batch, int n, void* stream
  *                    above the diagonal are computed and the rest is their mirror image.
  *   prism_gemm_f64a: A fp32 (promoted), B and C fp64, A stored [M][K].
  *   prism_gemm_bf16_nt: A [M][K], B [N][K] bf16 bit patterns, C fp32 = A B^T.
- * M, N must be multiples of 128 (bf16: of `tile`, 128 or 256; fp32 skinny N = 16, 32, 64 also allowed)
- * and K of 64. */
+ * M, N must be multiples of 128 (bf16: of `tile`, 128 or 256, or M of 256 and N of 128 for
+ * tile = 2561, the 256 x 128 shape; fp32 skinny N = 16, 32, 64 also allowed) and K of 64. */
 int prism_gemm_f32(const float* A, const float* B, float* C, int batch, int M, int N, int K,
                    int a_km, void* stream);
 int prism_gemm_f64a(const float* A, const double* B, double* C, int batch, int M, int N, int K,

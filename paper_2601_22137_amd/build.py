@@ -17,13 +17,17 @@ PER_FILE = {"sketch.hip": ["-ffp-contract=off"]}
 
 
 def build(verbose=True):
+    """Compiles every source and links libprism.so.  PRISM_EXTRA_HIPCC_FLAGS (build-time environment
+    variable, empty by default) appends compiler flags, e.g. -DPRISM_AB_SWITCHES for a development
+    build whose kernel choices can be switched through the environment."""
     os.makedirs(BUILD_DIR, exist_ok=True)
+    extra = os.environ.get("PRISM_EXTRA_HIPCC_FLAGS", "").split()
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     objs = []
     procs = []
     for src in SOURCES:
         obj = os.path.join(BUILD_DIR, src.replace(".hip", ".o"))
-        cmd = [hipcc] + COMMON + PER_FILE.get(src, []) + ["-c", os.path.join(CSRC, src), "-o", obj]
+        cmd = [hipcc] + COMMON + extra + PER_FILE.get(src, []) + ["-c", os.path.join(CSRC, src), "-o", obj]
         if verbose:
             print(" ".join(cmd), flush=True)
         procs.append((src, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))

@@ -13,7 +13,8 @@ struct Ctrl {
   int done;      // 0 while iterating
   int iters;     // updates performed
   int status;    // PRISM_INFO_*
-  int plain;     // bf16 polar with a split iterate: from now on the update reads the high half only
+  int plain;     // bf16 polar with a split iterate: the fit has left the upper end of its interval (no small
+                 // singular value is left): the update stops adding the low half's share of the product
   float alpha;   // coefficient of the update being applied
   float res0;    // residual at k = 0
   float res1;    // residual at k - 1
@@ -71,12 +72,11 @@ enum Bf16Epi {
   BEPI_STORE = 0,   // C(fp32) = acc
   BEPI_GRAM = 1,    // R = I - acc: R32 (fp32) and Rb (bf16), rho partial
   BEPI_POLYQ = 2,   // Q(bf16) = c1 * R32 + alpha * acc
-  BEPI_APPLY = 3    // X' = Xhi + Xlo + acc -> Xa_hi', Xa_lo' ([L][S]) and Xg_hi' ([S][L])
+  BEPI_APPLY = 3    // X' = Xhi + (1 + c) Xlo + acc -> Xa_hi', Xa_lo' ([L][S]) and Xg_hi' ([S][L]); acc = Xhi B
 };
 
 struct Bf16Desc {
   const uint16_t* A; long long strideA; int lda;    // [M][K]
-  const uint16_t* A2;                                // optional second A (low part), same layout
   const uint16_t* B; long long strideB; int ldb;    // [N][K]
   int M, N, K, batch;
   int epi;
@@ -91,15 +91,25 @@ struct Bf16Desc {
   const uint16_t* Xhi; const uint16_t* Xlo;          // APPLY: current iterate (same layout as Cb)
   float c1;
   int coef_is_alpha;                                 // APPLY: multiply acc by ctrl.alpha (d = 1)
-  float* rho_part;
+  float* rho_part;                                   // GRAM: partial sums of R^2, slot b * rho_stride + part_base + (tile - tile_first)
+  int rho_stride, part_base;                         // 0, 0: one slot per tile of the launch's own tiling
+  int tile_first, tile_count;                        // tiles [first, first + count) of every matrix only (count 0: all)
   const Ctrl* ctrl;
-  int xcd_private;                                   // set by launch_gemm_bf16: contiguous tile ranges per XCD
   int xcd_blocks;                                    // set by launch_gemm_bf16: 4 x 8 tile blocks per XCD
   int ctrl_fixed;                                    // ctrl[0] applies to every batch entry (the parts of a split-K product)
-  int plain_filter;                                  // 1: skip matrices whose ctrl.plain is set; 2: skip the others (0: none)
-  int no_dual;                                       // APPLY with A2: run the K loop twice instead of the fused high | low | B slabs
 };
-int launch_gemm_bf16(const Bf16Desc& g, int tile, hipStream_t s);
+// One launch over up to BF16_MAX_GROUPS products of the same kind (epilogue, symmetry) and
+// different shapes: workgroup index -> (group, matrix, tile) through the running tile counts.
+constexpr int BF16_MAX_GROUPS = 8;
+struct Bf16Multi {
+  Bf16Desc d[BF16_MAX_GROUPS];
+  int tile_start[BF16_MAX_GROUPS + 1];               // set by the launcher
+  int ngroups;
+  int xcd_private;                                   // set by the launcher: contiguous tile ranges per XCD
+};
+// tile_m x tile_n: 256 x 256, 256 x 128 or 128 x 128; M, N of every group must be multiples of them
+int launch_gemm_bf16(const Bf16Desc& g, int tile_m, int tile_n, hipStream_t s);
+int launch_gemm_bf16_multi(const Bf16Desc* groups, int ngroups, int tile_m, int tile_n, hipStream_t s);
 
 // ---- sketch.hip ----
 // v0[k - k_first][rows_total][ld] for k = k_first .. k_first + k_count - 1

@@ -409,33 +409,40 @@ int run_polar_f32(Run& r) {
   return PRISM_OK;
 }
 
-// 256 x 256 tiles (one workgroup per CU) move half the bytes per flop of 128 x 128 ones (two per
-// CU) but nothing overlaps their epilogue: they are taken when they still give every CU work and
-// K is long enough to amortise it.  (At K = 768 the bare product is faster with large tiles from
-// 144 tiles on, the update GEMM with its three-output epilogue is not.)
+// Tile shape of a bf16 product.  Large tiles move fewer bytes per flop but need enough tiles to give
+// every CU work and a K long enough to amortise their epilogue: 128 x 128 (three workgroups per CU)
+// below that.  (At K = 768 the bare product is faster with large tiles from 144 tiles on, the update
+// GEMM with its three-output epilogue is not.)  Among the large shapes 256 x 128 runs two workgroups
+// per CU, which overlap each other's epilogue and barrier waits; 256 x 256 runs one.
+struct Tile { int m, n; };
 int bf16_tile_forced() {
-  static const int forced = ab_switch("PRISM_BF16_TILE");
-  return (forced == 128 || forced == 256) ? forced : 0;
+  static const int forced = ab_switch("PRISM_BF16_TILE");   // 128, 256, or 2561 for 256 x 128
+  return forced;
 }
-int bf16_tile(const Plan& P, int M, int N, int K, bool symmetric) {
+Tile bf16_big_tile() {
+  static const int big = ab_switch("PRISM_BF16_BIG");       // 2: 256 x 128
+  return big == 2 ? Tile{256, 128} : Tile{256, 256};
+}
+Tile bf16_tile(const Plan& P, int M, int N, int K, bool symmetric) {
   const int forced = bf16_tile_forced();
-  if (P.tile != 256) return 128;
-  if (forced == 128 || forced == 256) return forced;
+  if (P.tile != 256) return Tile{128, 128};
+  if (forced == 128) return Tile{128, 128};
+  if (forced == 256) return Tile{256, 256};
+  if (forced == 2561) return Tile{256, 128};
   const long long per_mat = symmetric ? (long long)(M / 256) * (M / 256 + 1) / 2 : (long long)(M / 256) * (N / 256);
-  return (per_mat * P.batch >= 192 && K >= 2048) ? 256 : 128;
+  return (per_mat * P.batch >= 192 && K >= 2048) ? bf16_big_tile() : Tile{128, 128};
 }
 
 int run_polar_bf16(Run& r) {
   const Plan& P = r.P;
   const int Sp = P.Sp, Lp = P.Lp;
-  static const int no_sym = ab_switch("PRISM_BF16_NO_SYM");
-  const int sym = no_sym ? 0 : 1;
+  const int sym = 1;   // X^T X and the square of the (mirrored, hence exactly symmetric) R: upper triangle of tiles
   // Gram product: with other work beside this call, large tiles also when they are few (measured on
   // the Muon-shaped batch of four groups: 3.96 -> 3.80 ms; alone on the GPU the same choice costs
   // 1.40 instead of 1.07 ms of Gram time per step).  R^2 and the update keep the rule.
-  int Tg = bf16_tile(P, Sp, Sp, Lp, sym != 0);
-  const int Tq = Tg, Ta = bf16_tile(P, Lp, Sp, Sp, false);
-  if (P.tile == 256 && P.shared_gpu && bf16_tile_forced() == 0) Tg = 256;
+  Tile Tg = bf16_tile(P, Sp, Sp, Lp, true);
+  const Tile Tq = Tg, Ta = bf16_tile(P, Lp, Sp, Sp, false);
+  if (P.tile == 256 && P.shared_gpu && bf16_tile_forced() == 0) Tg = Tile{256, 256};
   const long long SS = (long long)Sp * Sp, LS = (long long)Lp * Sp;
   uint16_t* Xhi[2] = {r.at<uint16_t>(P.o_xhi[0]), r.out_as_xhi1 ? r.out_as_xhi1 : r.at<uint16_t>(P.o_xhi[1])};
   uint16_t* Xlo[2] = {P.split ? r.at<uint16_t>(P.o_xlo[0]) : nullptr, P.split ? r.at<uint16_t>(P.o_xlo[1]) : nullptr};
@@ -443,8 +450,6 @@ int run_polar_bf16(Run& r) {
   float* R = r.at<float>(P.o_r);
   uint16_t* Rb = r.at<uint16_t>(P.o_rb);
   uint16_t* Qb = P.d == 2 ? r.at<uint16_t>(P.o_qb) : nullptr;
-  static const int keep_split = ab_switch("PRISM_BF16_KEEP_SPLIT");
-  static const int no_dual = ab_switch("PRISM_BF16_NO_DUAL");
   static const int chain_f32 = ab_switch("PRISM_BF16_CHAIN_F32");
   // The fit can read the bf16 copy of R (plus its exact diagonal) when the chain kernels take the
   // shape; with symmetric tiles the fp32 matrix is then not written at all: the Gram epilogue
@@ -455,8 +460,8 @@ int run_polar_bf16(Run& r) {
   const bool chain_b = !chain_f32 && Sp > 64 && (P.p_s == 0 || chain_bf16_supported(Sp, P.ld, P.batch, Sp));   // order 64: one-launch fp32 chain
   const bool lean = chain_b && sym && !P.split;
   float* Dg = R;
-  const int ntg = Sp / Tg;
-  const int nparts = sym ? ntg * (ntg + 1) / 2 : ntg * ntg;
+  const int ntg = Sp / Tg.m;
+  const int nparts = (Tg.m / Tg.n) * ntg * (ntg + 1) / 2;   // tiles (= residual partial sums) per matrix
   int cur = 0;
   for (int k = 0; k <= r.max_iters; ++k) {
     if (k == r.max_iters && r.tol <= 0.0) break;
@@ -470,7 +475,7 @@ int run_polar_bf16(Run& r) {
     if (P.ksplit) {
       ProfScope ps(PK_BF16_GRAM, r.s);
       const int Kp = Lp / P.ksplit;
-      const int T1 = (P.tile == 256 && (long long)(Sp / 256) * (Sp / 256) * P.ksplit >= 256) ? 256 : 128;
+      const int T1 = (P.tile == 256 && (long long)(Sp / 256) * (Sp / 256) * P.ksplit >= 256) ? 256 : 128;   // square tiles
       float* gpart = r.at<float>(P.o_gpart);
       for (int b = 0; b < P.batch; ++b) {   // the parts of one matrix are the batch of a plain product
         Bf16Desc sp = {};
@@ -478,7 +483,7 @@ int run_polar_bf16(Run& r) {
         sp.M = Sp; sp.N = Sp; sp.K = Kp; sp.batch = P.ksplit; sp.epi = BEPI_STORE;
         sp.C32 = gpart + (long long)b * P.ksplit * SS; sp.strideC32 = SS; sp.ldc32 = Sp;
         sp.ctrl = r.ctrl + b; sp.ctrl_fixed = 1;
-        CHECK_LAUNCH(launch_gemm_bf16(sp, T1, r.s));
+        CHECK_LAUNCH(launch_gemm_bf16(sp, T1, T1, r.s));
       }
       GramReduceArgs ra = {};
       ra.part = gpart; ra.parts = P.ksplit; ra.np = Sp; ra.n_true = P.S;
@@ -487,7 +492,7 @@ int run_polar_bf16(Run& r) {
       CHECK_LAUNCH(check_hip());
     } else {
       ProfScope ps(PK_BF16_GRAM, r.s);
-      CHECK_LAUNCH(launch_gemm_bf16(g, Tg, r.s));
+      CHECK_LAUNCH(launch_gemm_bf16(g, Tg.m, Tg.n, r.s));
     }
     if (r.fit_needed(k)) {
       if (lean) CHECK_LAUNCH(r.chain(R, k, Rb, Dg, Sp, 1));
@@ -504,27 +509,18 @@ int run_polar_bf16(Run& r) {
       q.C32 = lean ? nullptr : R; q.strideC32 = SS; q.ldc32 = Sp; q.Cb = Qb; q.strideCb = SS; q.ldcb = Sp; q.c1 = 0.5f;
       q.Cin16 = lean ? Rb : nullptr;
       q.ctrl = r.ctrl;
-      { ProfScope ps(PK_BF16_POLYQ, r.s); CHECK_LAUNCH(launch_gemm_bf16(q, Tq, r.s)); }
+      { ProfScope ps(PK_BF16_POLYQ, r.s); CHECK_LAUNCH(launch_gemm_bf16(q, Tq.m, Tq.n, r.s)); }
       Bop = Qb;
     }
+    // One pass: the product reads the high half of the iterate only; the epilogue adds the low
+    // half's share elementwise (see the kernel) and splits the result again.
     Bf16Desc a = {};
-    a.A = Xhi[cur]; a.A2 = Xlo[cur]; a.strideA = LS; a.lda = Sp; a.B = Bop; a.strideB = SS; a.ldb = Sp;
+    a.A = Xhi[cur]; a.strideA = LS; a.lda = Sp; a.B = Bop; a.strideB = SS; a.ldb = Sp;
     a.M = Lp; a.N = Sp; a.K = Sp; a.batch = P.batch; a.epi = BEPI_APPLY;
     a.Cb = Xhi[cur ^ 1]; a.Cb2 = Xlo[cur ^ 1]; a.strideCb = LS; a.ldcb = Sp;
     a.Ct = Xg[cur ^ 1]; a.strideCt = LS; a.ldct = Lp;
     a.Xhi = Xhi[cur]; a.Xlo = Xlo[cur]; a.coef_is_alpha = P.d == 1; a.ctrl = r.ctrl;
-    a.no_dual = no_dual;
-    if (P.split && !keep_split) {
-      // matrices whose fit has left the upper end of its interval (ctrl.plain) are updated from the
-      // high half alone: two launches, each skipping the matrices of the other kind
-      a.plain_filter = 1;
-      { ProfScope ps(PK_BF16_APPLY, r.s); CHECK_LAUNCH(launch_gemm_bf16(a, Ta, r.s)); }
-      a.A2 = nullptr; a.Xlo = nullptr; a.plain_filter = 2;
-      { ProfScope ps(PK_BF16_APPLY, r.s); CHECK_LAUNCH(launch_gemm_bf16(a, Ta, r.s)); }
-    } else {
-      ProfScope ps(PK_BF16_APPLY, r.s);
-      CHECK_LAUNCH(launch_gemm_bf16(a, Ta, r.s));
-    }
+    { ProfScope ps(PK_BF16_APPLY, r.s); CHECK_LAUNCH(launch_gemm_bf16(a, Ta.m, Ta.n, r.s)); }
     cur ^= 1;
   }
   return PRISM_OK;
@@ -1163,7 +1159,8 @@ int prism_gemm_bf16_nt(const uint16_t* A, const uint16_t* B, float* C, int batch
   g.B = B; g.strideB = (long long)N * K; g.ldb = K;
   g.M = M; g.N = N; g.K = K; g.batch = batch; g.epi = BEPI_STORE;
   g.C32 = C; g.strideC32 = (long long)M * N; g.ldc32 = N;
-  return launch_gemm_bf16(g, tile, (hipStream_t)stream);
+  if (tile == 2561) return launch_gemm_bf16(g, 256, 128, (hipStream_t)stream);
+  return launch_gemm_bf16(g, tile, tile, (hipStream_t)stream);
 }
 
 }  // extern "C"

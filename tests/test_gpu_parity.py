@@ -163,6 +163,20 @@ def test_c3_polar_bf16_reduced(prism):
         _check_info(info[i], oinfo, alpha_tol=3e-2, res_rtol=3e-2, res_floor=5e-3, alpha_res_min=0.1)
 
 
+def test_c3_polar_bf16_large_tiles(prism):
+    """8 x 2048 x 2048: the smallest batch that takes the 256 x 256 tiles of the full-size
+    configuration (288 Gram tiles, 512 update tiles in 4 x 8 blocks per XCD): every matrix
+    against the oracle."""
+    bits = W.c3_polar_large(n=2048, batch=8, data_seed=1403)
+    x = _bf16_tensor(bits.copy())
+    info = prism.polar(x, 5, 40, 32, SEED, 1e-2).read()
+    out = _bf16_to_f64(x)
+    for i in range(8):
+        ref, oinfo = O.polar(W.from_bf16_bits(bits[i]), 5, 40, 32, SEED, 1e-2)
+        assert _rel(out[i], ref) <= TOL_BF16
+        _check_info(info[i], oinfo, alpha_tol=3e-2, res_rtol=3e-2, res_floor=5e-3, alpha_res_min=0.1)
+
+
 # ------------------------------------------------------------------ config 4 (reduced)
 
 @pytest.mark.parametrize("n,p", [(256, 4), (200, 4), (384, 2), (130, 3), (128, 1), (192, 8), (128, 6), (100, 5), (64, 7), (512, 8), (320, 7)])
