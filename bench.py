@@ -224,9 +224,9 @@ def run_config(name, K, Wm, args, torch, prism, W):
     grouped = bool(args.grouped) and name == "c2" and len(wl.host) > 1
     graph = grouped and bool(args.graph)
 
-    def step(i, use_grouped=True):
-        if grouped and use_grouped:
-            return prism.run_grouped(prism.FN_POLAR, copies[i], 5, 5, 16, wl.seed, 0.0, flags=wl.flags)[1]
+    def step(i, extra_flags=0):
+        if grouped:
+            return prism.run_grouped(prism.FN_POLAR, copies[i], 5, 5, 16, wl.seed, 0.0, flags=wl.flags | extra_flags)[1]
         return [wl.call(x) for x in copies[i]]
 
     graphs = None
@@ -342,7 +342,7 @@ def run_config(name, K, Wm, args, torch, prism, W):
         nprof = min(K, 3)
         prism.profile_enable(True)
         for i in range(nprof):
-            step(Wm + i, use_grouped=False)     # one stream: every kernel is timed running alone
+            step(Wm + i, prism.FLAG_SINGLE_STREAM)     # every kernel on one stream: each is timed running alone
         torch.cuda.synchronize()
         prof = prism.profile_collect()
         prism.profile_enable(False)

@@ -126,7 +126,12 @@ enum {
    * call (calls for other shapes on other streams).  The bf16 Gram product then takes 256 x 256
    * tiles even when they are too few to fill the chip: they move half the bytes per flop and
    * leave whole CUs to the other work.  prism_run_grouped sets it for its groups. */
-  PRISM_FLAG_SHARED_GPU = 2u
+  PRISM_FLAG_SHARED_GPU = 2u,
+  /* Keep every kernel of the call on the caller's stream: no internal streams (prism_run_grouped
+   * then runs its groups, or the one launch sequence over all of them, one after the other; a
+   * single-shape call is not split into half batches).  Results unchanged.  For callers that time
+   * kernels one by one or must not have work on streams they do not own. */
+  PRISM_FLAG_SINGLE_STREAM = 4u
 };
 
 typedef struct {
@@ -238,10 +243,21 @@ int prism_sqrt_newton_ex(void* a, void* inv_out, int batch, int m, int n, prism_
  *
  * Callers: a Muon-style step orthogonalises the gradient of every weight matrix, a Shampoo-style
  * step takes the inverse root of every preconditioner; the matrices come in a few shapes, each a
- * batch.  The groups are independent, so the library enqueues them on internal streams of
- * default priority that fork from and join back into `stream` (event record / wait only: the call
- * stays asynchronous and capturable), and the latency-bound kernels of one group run beside the
- * GEMMs of another.  Every group is computed exactly as by its own single-group call. */
+ * batch.  The groups are independent.
+ *   - bf16 polar factors of up to 8 groups that share min(m, n) (the weight shapes of a layer stack
+ *     do: 768 x 768, 768 x 3072, 3072 x 768, 768 x 2304) run as ONE launch sequence over all their
+ *     matrices: R_k, Q_k, the chain vectors and the control blocks of every matrix form a single
+ *     batch, so R^2, the chain products, the moments and the solve are one launch each for the
+ *     whole call, and the Gram product and the update take all shapes in one launch each (the
+ *     kernel maps its workgroup index to group, matrix and tile).  When every group's batch is a
+ *     multiple of 4 (of 2) the sequence is issued for the quarters (halves) of every group on
+ *     internal streams, so that the latency-bound steps of one part run beside the products of
+ *     another.
+ *   - any other combination runs each group as its own call on one of four internal streams.
+ * The internal streams have default priority and fork from and join back into `stream` (event
+ * record / wait only: the call stays asynchronous and capturable once the library's workspaces
+ * exist, i.e. after one eager call with the same arguments on the same stream).  Every group is
+ * computed exactly as by its own single-group call: same kernels, same bits. */
 typedef struct {
   void* x;          /* device: [batch][m][n], replaced in place as by the single-group call */
   void* inv_out;    /* device: second output of prism_sqrt / prism_sqrt_newton, else NULL */

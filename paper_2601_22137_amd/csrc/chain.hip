@@ -497,13 +497,15 @@ constexpr int small_below(bool rb) { return rb ? 128 : 256; }
 template <bool RB>
 int launch_chain_t(const typename RFrag<RB>::elem* R, long long strideR, int ldr, const float* R32, long long strideR32,
                    int ldr32, const float* Vin, long long strideVin, float* Vout, long long strideVout, int n, int ld,
-                   int batch, const Ctrl* ctrl, hipStream_t s) {
+                   int batch, const Ctrl* ctrl, hipStream_t s, int sel_batch) {
   if (n % KC || n % ROWS || ldr % 4 || batch <= 0) return PRISM_EINVAL;
+  if (sel_batch <= 0) sel_batch = batch;   // the batch size that picks the kernel (a launch over several shape groups
+                                           // passes the size of one group, so that every group gets the kernel of its own call)
   // 64-row workgroups leave most CUs idle on small batches of small matrices: 16-row ones there.
   // The bf16 kernels change over earlier: the 64-row one reads V once per 64 rows instead of once per
   // 16 and, beside other kernels, leaves them more of the chip (config 2, 192 workgroups of 64 rows:
   // 9.3 -> 7.5 us per launch and 3.55 -> 3.30 ms per step).
-  if (ld <= 32 && (long long)(n / ROWS) * batch < small_below(RB)) {
+  if (ld <= 32 && (long long)(n / ROWS) * sel_batch < small_below(RB)) {
     const dim3 grid(n / 16, batch), block(NT);
     if (ld == 16) hipLaunchKernelGGL((chain_small_kernel<16, RB>), grid, block, 0, s, R, strideR, ldr, R32, strideR32, ldr32, Vin, strideVin, Vout, strideVout, n, ctrl);
     else hipLaunchKernelGGL((chain_small_kernel<32, RB>), grid, block, 0, s, R, strideR, ldr, R32, strideR32, ldr32, Vin, strideVin, Vout, strideVout, n, ctrl);
@@ -530,8 +532,8 @@ int launch_chain_t(const typename RFrag<RB>::elem* R, long long strideR, int ldr
 
 // R: [batch][n][ldr] fp32 (n a multiple of 64), Vin/Vout: [n][ld] per matrix (strideVin may be 0)
 int launch_chain(const float* R, long long strideR, int ldr, const float* Vin, long long strideVin, float* Vout,
-                 long long strideVout, int n, int ld, int batch, const Ctrl* ctrl, hipStream_t s) {
-  return launch_chain_t<false>(R, strideR, ldr, nullptr, 0, 0, Vin, strideVin, Vout, strideVout, n, ld, batch, ctrl, s);
+                 long long strideVout, int n, int ld, int batch, const Ctrl* ctrl, hipStream_t s, int sel_batch) {
+  return launch_chain_t<false>(R, strideR, ldr, nullptr, 0, 0, Vin, strideVin, Vout, strideVout, n, ld, batch, ctrl, s, sel_batch);
 }
 
 // V_j = R V_{j-1}, j = 1 .. nv, for matrices of order 64: V0 [64][ld] per matrix (strideV0 may be 0),
@@ -548,6 +550,10 @@ int launch_chain_tiny(const float* R, long long strideR, int ldr, const float* V
 
 // Shapes the bf16 kernels take: sketch width up to 32, rows of Rb in 16-byte loads, and K in chunks
 // of 128 unless the 16-row kernel applies.
+bool chain_takes_small_kernel(int n, int ld, int batch, bool rb) {
+  return ld <= 32 && (long long)(n / ROWS) * batch < small_below(rb);
+}
+
 bool chain_bf16_supported(int n, int ld, int batch, int ldr) {
   const bool small = ld <= 32 && (long long)(n / ROWS) * batch < small_below(true);
   return (ld == 16 || ld == 32) && ldr % 8 == 0 && n % KC == 0 && (small || n % 128 == 0);
@@ -556,9 +562,9 @@ bool chain_bf16_supported(int n, int ld, int batch, int ldr) {
 // Same product with R read from its bf16 copy Rb and the diagonal from D (see common.h)
 int launch_chain_bf16(const unsigned short* Rb, long long strideR, int ldr, const float* D, long long strideD, int ldd,
                       const float* Vin, long long strideVin, float* Vout, long long strideVout, int n, int ld, int batch,
-                      const Ctrl* ctrl, hipStream_t s) {
-  if (!Rb || !D || !chain_bf16_supported(n, ld, batch, ldr)) return PRISM_EINVAL;
-  return launch_chain_t<true>(Rb, strideR, ldr, D, strideD, ldd, Vin, strideVin, Vout, strideVout, n, ld, batch, ctrl, s);
+                      const Ctrl* ctrl, hipStream_t s, int sel_batch) {
+  if (!Rb || !D || !chain_bf16_supported(n, ld, sel_batch > 0 ? sel_batch : batch, ldr)) return PRISM_EINVAL;
+  return launch_chain_t<true>(Rb, strideR, ldr, D, strideD, ldd, Vin, strideVin, Vout, strideVout, n, ld, batch, ctrl, s, sel_batch);
 }
 
 }  // namespace prism

@@ -119,8 +119,13 @@ void launch_gauss_parts(uint32_t first, uint32_t count, double* r, double* c, do
                         hipStream_t s);
 
 // ---- chain.hip : V_out = R V_in for the sketch chain (HBM bound; R read once, straight into registers) ----
+// sel_batch: the batch size that picks the kernel variant (0: batch).  A launch over the matrices of
+// several shape groups passes the size of one group, so that each matrix gets the kernel, hence the
+// summation order and the bits, of a call on its own group.
 int launch_chain(const float* R, long long strideR, int ldr, const float* Vin, long long strideVin, float* Vout,
-                 long long strideVout, int n, int ld, int batch, const Ctrl* ctrl, hipStream_t s);
+                 long long strideVout, int n, int ld, int batch, const Ctrl* ctrl, hipStream_t s, int sel_batch = 0);
+// true: (n, ld, batch) takes the 16-row kernels (few workgroups otherwise); rb: the bf16 variants
+bool chain_takes_small_kernel(int n, int ld, int batch, bool rb);
 // Rb: bf16 copy of R [batch][n][ldr]; D: its exact fp32 diagonal, entry i of matrix b at D[b * strideD + i * ldd]
 // (ldd = ld of R + 1 reads it out of the full fp32 matrix, ldd = 1 out of a compact array)
 int launch_chain_tiny(const float* R, long long strideR, int ldr, const float* V0, long long strideV0, float* Vout,
@@ -128,7 +133,7 @@ int launch_chain_tiny(const float* R, long long strideR, int ldr, const float* V
 bool chain_bf16_supported(int n, int ld, int batch, int ldr);
 int launch_chain_bf16(const unsigned short* Rb, long long strideR, int ldr, const float* D, long long strideD, int ldd,
                       const float* Vin, long long strideVin, float* Vout, long long strideVout, int n, int ld, int batch,
-                      const Ctrl* ctrl, hipStream_t s);
+                      const Ctrl* ctrl, hipStream_t s, int sel_batch = 0);
 
 // ---- fit.hip ----
 struct SolveArgs {

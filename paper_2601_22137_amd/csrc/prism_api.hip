@@ -92,8 +92,10 @@ struct Plan {
   size_t total;
 };
 
+// shared_shapes: the plan of a launch sequence over several shape groups with the same short side;
+// the iterate buffers are then laid out per group by the caller (offsets o_x* stay 0)
 int make_plan(Plan& P, int fn, int batch, int m, int n, int dt, int degree, int sketch_dim, int root_p,
-              unsigned flags) {
+              unsigned flags, bool shared_shapes = false) {
   if (batch <= 0 || m <= 0 || n <= 0) return PRISM_EINVAL;
   if (degree != 3 && degree != 5) return PRISM_EINVAL;
   if (sketch_dim < 0 || sketch_dim > PRISM_MAX_SKETCH) return PRISM_EINVAL;
@@ -149,7 +151,7 @@ int make_plan(Plan& P, int fn, int batch, int m, int n, int dt, int degree, int 
   }
   P.o_cpart = take(B * P.ngroups * 17 * sizeof(double));
   if (dt == PRISM_BF16) {
-    for (int i = 0; i < 2; ++i) {
+    for (int i = 0; i < 2 && !shared_shapes; ++i) {
       P.o_xhi[i] = take(B * LS * 2);
       P.o_xlo[i] = P.split ? take(B * LS * 2) : 0;
       P.o_xg[i] = take(B * LS * 2);
@@ -185,7 +187,7 @@ int make_plan(Plan& P, int fn, int batch, int m, int n, int dt, int degree, int 
   // pass adds the partial products up (in part order, so results stay run-to-run identical).
   P.ksplit = 0; P.o_gpart = 0;
   static const int no_split_k = ab_switch("PRISM_NO_SPLIT_K");
-  if (fn == PRISM_FN_POLAR && !no_split_k && batch <= 8 && P.Lp >= 8192 && P.Sp > 64) {
+  if (fn == PRISM_FN_POLAR && !no_split_k && !shared_shapes && batch <= 8 && P.Lp >= 8192 && P.Sp > 64) {
     const int tg = dt == PRISM_BF16 ? 128 : P.tile;
     const long long nt = P.Sp / tg, tri = nt * (nt + 1) / 2, full = nt * nt;
     if (tri * batch <= 48) {
@@ -256,11 +258,21 @@ struct Run {
   int first_fit;                       // first update whose coefficient is fitted
   double tol;
   uint64_t seed;
-  // bf16 polar, plain iterate, no padding: the caller's array serves as the odd one of the two
-  // iterate buffers that has its orientation (the input is consumed by the prepare step before the
-  // first update writes there), so that after an odd number of updates the result is in place
-  uint16_t* out_as_xhi1 = nullptr;
-  uint16_t* out_as_xg1 = nullptr;
+  // bf16 polar: the iterate buffers, per shape group (one group for a single-shape call).  All
+  // groups share the short side, so R, Q, the chain vectors and the control blocks of all their
+  // matrices form one batch (matrices [boff, boff + batch) belong to the group); only the Gram
+  // product and the update see the long side, and take all groups in one launch each.
+  // Plain iterate, no padding: the caller's array serves as the odd one of the two iterate buffers
+  // that has its orientation (the input is consumed by the prepare step before the first update
+  // writes there), so that after an odd number of updates the result is in place.
+  struct XGroup {
+    int batch, boff, m, n, L, Lp, transpose;
+    void* x;                                   // caller's array
+    uint16_t* Xhi[2]; uint16_t* Xlo[2]; uint16_t* Xg[2];
+    bool aliased;                              // buffer 1 of the caller's orientation is the caller's array
+  };
+  std::vector<XGroup> xg;
+  int chain_sel_batch = 0;                     // batch size that picks the chain kernels (0: the whole batch)
 
   template <typename T> T* at(size_t off) const { return (T*)(ws + off); }
 
@@ -282,10 +294,10 @@ struct Run {
       ProfScope ps(PK_CHAIN, s);
       if (Rb)
         CHECK_LAUNCH(launch_chain_bf16(Rb, (long long)Sp * Sp, Sp, D, strideD, ldd, vin, sin, v + (j - 1) * vs,
-                                       (long long)Sp * ld, Sp, ld, P.batch, ctrl, s));
+                                       (long long)Sp * ld, Sp, ld, P.batch, ctrl, s, chain_sel_batch));
       else
         CHECK_LAUNCH(launch_chain(R, (long long)Sp * Sp, Sp, vin, sin, v + (j - 1) * vs, (long long)Sp * ld, Sp, ld,
-                                  P.batch, ctrl, s));
+                                  P.batch, ctrl, s, chain_sel_batch));
     }
     return PRISM_OK;
   }
@@ -435,18 +447,42 @@ Tile bf16_tile(const Plan& P, int M, int N, int K, bool symmetric) {
 
 int run_polar_bf16(Run& r) {
   const Plan& P = r.P;
-  const int Sp = P.Sp, Lp = P.Lp;
+  const int Sp = P.Sp;
   const int sym = 1;   // X^T X and the square of the (mirrored, hence exactly symmetric) R: upper triangle of tiles
-  // Gram product: with other work beside this call, large tiles also when they are few (measured on
-  // the Muon-shaped batch of four groups: 3.96 -> 3.80 ms; alone on the GPU the same choice costs
-  // 1.40 instead of 1.07 ms of Gram time per step).  R^2 and the update keep the rule.
-  Tile Tg = bf16_tile(P, Sp, Sp, Lp, true);
-  const Tile Tq = Tg, Ta = bf16_tile(P, Lp, Sp, Sp, false);
-  if (P.tile == 256 && P.shared_gpu && bf16_tile_forced() == 0) Tg = Tile{256, 256};
-  const long long SS = (long long)Sp * Sp, LS = (long long)Lp * Sp;
-  uint16_t* Xhi[2] = {r.at<uint16_t>(P.o_xhi[0]), r.out_as_xhi1 ? r.out_as_xhi1 : r.at<uint16_t>(P.o_xhi[1])};
-  uint16_t* Xlo[2] = {P.split ? r.at<uint16_t>(P.o_xlo[0]) : nullptr, P.split ? r.at<uint16_t>(P.o_xlo[1]) : nullptr};
-  uint16_t* Xg[2] = {r.at<uint16_t>(P.o_xg[0]), r.out_as_xg1 ? r.out_as_xg1 : r.at<uint16_t>(P.o_xg[1])};
+  const int ng = (int)r.xg.size();
+  if (ng < 1 || ng > BF16_MAX_GROUPS) return PRISM_EINVAL;
+  // Tile shapes.  One shape per launch: with several groups the Gram product and the update take the
+  // large tiles when the launch as a whole has enough of them.
+  long long gram256 = 0, upd256 = 0;
+  for (const Run::XGroup& x : r.xg) {
+    gram256 += (long long)(Sp / 256) * (Sp / 256 + 1) / 2 * x.batch;
+    upd256 += (long long)(x.Lp / 256) * (Sp / 256) * x.batch;
+  }
+  Tile Tg, Ta;
+  if (ng == 1) {
+    // with other work beside this call, large Gram tiles also when they are few (measured on the
+    // Muon-shaped batch of four groups on four streams: 3.96 -> 3.80 ms; alone on the GPU the same
+    // choice costs 1.40 instead of 1.07 ms of Gram time per step)
+    Tg = bf16_tile(P, Sp, Sp, r.xg[0].Lp, true);
+    Ta = bf16_tile(P, r.xg[0].Lp, Sp, Sp, false);
+    if (P.tile == 256 && P.shared_gpu && bf16_tile_forced() == 0) Tg = Tile{256, 256};
+  } else {
+    const bool pad256 = P.tile == 256;
+    static const int multi_gram = ab_switch("PRISM_BF16_MULTI_GRAM");   // 1: 128 x 128, 2: 256 x 128, 3: 256 x 256
+    static const int multi_upd = ab_switch("PRISM_BF16_MULTI_UPD");
+    auto pick = [&](int sw, bool big) {
+      if (!pad256 || sw == 1) return Tile{128, 128};
+      if (sw == 2) return Tile{256, 128};
+      if (sw == 3) return Tile{256, 256};
+      return big ? bf16_big_tile() : Tile{128, 128};
+    };
+    // measured on the Muon-shaped groups (order 768, K from 768 to 3072): 256 x 256 tiles for the Gram
+    // products and 256 x 128 for the updates beat 128 x 128 ones from 96 matrices' worth of tiles on
+    Tg = multi_gram ? pick(multi_gram, false) : ((pad256 && gram256 >= 96) ? Tile{256, 256} : Tile{128, 128});
+    Ta = multi_upd ? pick(multi_upd, false) : ((pad256 && upd256 >= 96) ? Tile{256, 128} : Tile{128, 128});
+  }
+  const Tile Tq = (ng == 1) ? Tg : bf16_tile(P, Sp, Sp, Sp, true);
+  const long long SS = (long long)Sp * Sp;
   float* R = r.at<float>(P.o_r);
   uint16_t* Rb = r.at<uint16_t>(P.o_rb);
   uint16_t* Qb = P.d == 2 ? r.at<uint16_t>(P.o_qb) : nullptr;
@@ -457,29 +493,30 @@ int run_polar_bf16(Run& r) {
   // Only with the plain bf16 iterate: with the split one the linear term of Q = R/2 + alpha R^2 keeps
   // the fp32 R (taking it from the bf16 copy raises the residual floor by a few 1e-4, which at
   // tol = 1e-2 cost the reduced config-3 case one more iteration than the oracle).
-  const bool chain_b = !chain_f32 && Sp > 64 && (P.p_s == 0 || chain_bf16_supported(Sp, P.ld, P.batch, Sp));   // order 64: one-launch fp32 chain
+  const int sel = r.chain_sel_batch ? r.chain_sel_batch : P.batch;
+  const bool chain_b = !chain_f32 && Sp > 64 && (P.p_s == 0 || chain_bf16_supported(Sp, P.ld, sel, Sp));   // order 64: one-launch fp32 chain
   const bool lean = chain_b && sym && !P.split;
   float* Dg = R;
   const int ntg = Sp / Tg.m;
   const int nparts = (Tg.m / Tg.n) * ntg * (ntg + 1) / 2;   // tiles (= residual partial sums) per matrix
+  // launch order of the groups: longest K first, so that the short tiles fill the last round
+  int order[BF16_MAX_GROUPS];
+  for (int i = 0; i < ng; ++i) order[i] = i;
+  for (int i = 1; i < ng; ++i)
+    for (int j = i; j > 0 && r.xg[order[j]].Lp > r.xg[order[j - 1]].Lp; --j) { const int t = order[j]; order[j] = order[j - 1]; order[j - 1] = t; }
   int cur = 0;
   for (int k = 0; k <= r.max_iters; ++k) {
     if (k == r.max_iters && r.tol <= 0.0) break;
-    Bf16Desc g = {};
-    g.sym = sym;
-    g.A = Xg[cur]; g.strideA = LS; g.lda = Lp; g.B = Xg[cur]; g.strideB = LS; g.ldb = Lp;
-    g.M = Sp; g.N = Sp; g.K = Lp; g.batch = P.batch; g.epi = BEPI_GRAM; g.n_true = P.S;
-    g.C32 = lean ? nullptr : R; g.strideC32 = SS; g.ldc32 = Sp; g.Cb = Rb; g.strideCb = SS; g.ldcb = Sp;
-    g.diag = lean ? Dg : nullptr; g.strideDiag = Sp;
-    g.rho_part = r.rho; g.ctrl = r.ctrl;
-    if (P.ksplit) {
+    if (P.ksplit) {   // single group of a few tall matrices
+      const Run::XGroup& x = r.xg[0];
+      const long long LS = (long long)x.Lp * Sp;
       ProfScope ps(PK_BF16_GRAM, r.s);
-      const int Kp = Lp / P.ksplit;
+      const int Kp = x.Lp / P.ksplit;
       const int T1 = (P.tile == 256 && (long long)(Sp / 256) * (Sp / 256) * P.ksplit >= 256) ? 256 : 128;   // square tiles
       float* gpart = r.at<float>(P.o_gpart);
       for (int b = 0; b < P.batch; ++b) {   // the parts of one matrix are the batch of a plain product
         Bf16Desc sp = {};
-        sp.A = Xg[cur] + (long long)b * LS; sp.B = sp.A; sp.strideA = Kp; sp.strideB = Kp; sp.lda = Lp; sp.ldb = Lp;
+        sp.A = x.Xg[cur] + (long long)b * LS; sp.B = sp.A; sp.strideA = Kp; sp.strideB = Kp; sp.lda = x.Lp; sp.ldb = x.Lp;
         sp.M = Sp; sp.N = Sp; sp.K = Kp; sp.batch = P.ksplit; sp.epi = BEPI_STORE;
         sp.C32 = gpart + (long long)b * P.ksplit * SS; sp.strideC32 = SS; sp.ldc32 = Sp;
         sp.ctrl = r.ctrl + b; sp.ctrl_fixed = 1;
@@ -491,8 +528,22 @@ int run_polar_bf16(Run& r) {
       launch_gram_reduce(ra, P.batch, r.s);
       CHECK_LAUNCH(check_hip());
     } else {
+      Bf16Desc gd[BF16_MAX_GROUPS];
+      for (int i = 0; i < ng; ++i) {
+        const Run::XGroup& x = r.xg[order[i]];
+        const long long LS = (long long)x.Lp * Sp;
+        Bf16Desc& g = gd[i];
+        g = Bf16Desc{};
+        g.sym = sym;
+        g.A = x.Xg[cur]; g.strideA = LS; g.lda = x.Lp; g.B = x.Xg[cur]; g.strideB = LS; g.ldb = x.Lp;
+        g.M = Sp; g.N = Sp; g.K = x.Lp; g.batch = x.batch; g.epi = BEPI_GRAM; g.n_true = P.S;
+        g.C32 = lean ? nullptr : R + x.boff * SS; g.strideC32 = SS; g.ldc32 = Sp;
+        g.Cb = Rb + x.boff * SS; g.strideCb = SS; g.ldcb = Sp;
+        g.diag = lean ? Dg + (long long)x.boff * Sp : nullptr; g.strideDiag = Sp;
+        g.rho_part = r.rho + (long long)x.boff * nparts; g.ctrl = r.ctrl + x.boff;
+      }
       ProfScope ps(PK_BF16_GRAM, r.s);
-      CHECK_LAUNCH(launch_gemm_bf16(g, Tg.m, Tg.n, r.s));
+      CHECK_LAUNCH(launch_gemm_bf16_multi(gd, ng, Tg.m, Tg.n, r.s));
     }
     if (r.fit_needed(k)) {
       if (lean) CHECK_LAUNCH(r.chain(R, k, Rb, Dg, Sp, 1));
@@ -502,7 +553,7 @@ int run_polar_bf16(Run& r) {
     CHECK_LAUNCH(r.solve(k, P.ksplit ? gram_reduce_parts(Sp) : nparts));
     if (k == r.max_iters) break;
     const uint16_t* Bop = Rb;
-    if (P.d == 2) {
+    if (P.d == 2) {   // one launch over the matrices of all groups: R has the same order everywhere
       Bf16Desc q = {};
       q.A = Rb; q.strideA = SS; q.lda = Sp; q.B = Rb; q.strideB = SS; q.ldb = Sp;
       q.M = Sp; q.N = Sp; q.K = Sp; q.batch = P.batch; q.epi = BEPI_POLYQ; q.sym = sym;
@@ -514,13 +565,19 @@ int run_polar_bf16(Run& r) {
     }
     // One pass: the product reads the high half of the iterate only; the epilogue adds the low
     // half's share elementwise (see the kernel) and splits the result again.
-    Bf16Desc a = {};
-    a.A = Xhi[cur]; a.strideA = LS; a.lda = Sp; a.B = Bop; a.strideB = SS; a.ldb = Sp;
-    a.M = Lp; a.N = Sp; a.K = Sp; a.batch = P.batch; a.epi = BEPI_APPLY;
-    a.Cb = Xhi[cur ^ 1]; a.Cb2 = Xlo[cur ^ 1]; a.strideCb = LS; a.ldcb = Sp;
-    a.Ct = Xg[cur ^ 1]; a.strideCt = LS; a.ldct = Lp;
-    a.Xhi = Xhi[cur]; a.Xlo = Xlo[cur]; a.coef_is_alpha = P.d == 1; a.ctrl = r.ctrl;
-    { ProfScope ps(PK_BF16_APPLY, r.s); CHECK_LAUNCH(launch_gemm_bf16(a, Ta.m, Ta.n, r.s)); }
+    Bf16Desc ad[BF16_MAX_GROUPS];
+    for (int i = 0; i < ng; ++i) {
+      const Run::XGroup& x = r.xg[order[i]];
+      const long long LS = (long long)x.Lp * Sp;
+      Bf16Desc& a = ad[i];
+      a = Bf16Desc{};
+      a.A = x.Xhi[cur]; a.strideA = LS; a.lda = Sp; a.B = Bop + x.boff * SS; a.strideB = SS; a.ldb = Sp;
+      a.M = x.Lp; a.N = Sp; a.K = Sp; a.batch = x.batch; a.epi = BEPI_APPLY;
+      a.Cb = x.Xhi[cur ^ 1]; a.Cb2 = x.Xlo[cur ^ 1]; a.strideCb = LS; a.ldcb = Sp;
+      a.Ct = x.Xg[cur ^ 1]; a.strideCt = LS; a.ldct = x.Lp;
+      a.Xhi = x.Xhi[cur]; a.Xlo = x.Xlo[cur]; a.coef_is_alpha = P.d == 1; a.ctrl = r.ctrl + x.boff;
+    }
+    { ProfScope ps(PK_BF16_APPLY, r.s); CHECK_LAUNCH(launch_gemm_bf16_multi(ad, ng, Ta.m, Ta.n, r.s)); }
     cur ^= 1;
   }
   return PRISM_OK;
@@ -738,6 +795,23 @@ int run_inv_root_f32(Run& r) {
   return PRISM_OK;
 }
 
+// bf16 polar, plain iterate, shapes that need no padding, array aligned like the workspace buffers:
+// the caller's array takes the place of buffer 1 of its own orientation
+void alias_output(const Plan& P, Run::XGroup& x) {
+  static const int no_alias = ab_switch("PRISM_BF16_NO_OUTPUT_ALIAS");
+  const int S = x.m < x.n ? x.m : x.n;
+  x.aliased = false;
+  if (P.split || P.Sp != S || x.Lp != x.L || no_alias || ((uintptr_t)x.x & 255)) return;
+  if (x.transpose) x.Xg[1] = (uint16_t*)x.x; else x.Xhi[1] = (uint16_t*)x.x;
+  x.aliased = true;
+}
+// iterate buffers of one shape group in the arguments of the pre-scaling and copy-out kernels
+void bf16_prep_final(const Plan& P, const Run::XGroup& x, PrepArgs& pa, FinalArgs& fa) {
+  pa.Xa_hi = x.Xhi[0]; pa.Xa_lo = x.Xlo[0]; pa.Xg = x.Xg[0];
+  for (int i = 0; i < 2; ++i) { fa.Xa_hi[i] = x.Xhi[i]; fa.Xa_lo[i] = x.Xlo[i]; fa.Xg[i] = x.Xg[i]; }
+  (void)P;
+}
+
 int run(int fn, void* a, void* inv_out, int root_p, int batch, int m, int n, int dt, int degree, int max_iters,
         int sketch_dim, uint64_t seed, double tol, void* stream, const prism_options* opt) {
   set_last_error("");
@@ -778,17 +852,16 @@ int run(int fn, void* a, void* inv_out, int root_p, int batch, int m, int n, int
   fa.fn = fn; fa.dt = dt; fa.batch = batch; fa.m = m; fa.n = n; fa.S = P.S; fa.L = P.L; fa.Sp = P.Sp; fa.Lp = P.Lp;
   fa.transpose = P.transpose; fa.dst = a; fa.dst2 = inv_out; fa.ctrl = r.ctrl;
   if (dt == PRISM_BF16) {
-    pa.Xa_hi = r.at<uint16_t>(P.o_xhi[0]); pa.Xa_lo = P.split ? r.at<uint16_t>(P.o_xlo[0]) : nullptr;
-    pa.Xg = r.at<uint16_t>(P.o_xg[0]);
-    static const int no_alias = ab_switch("PRISM_BF16_NO_OUTPUT_ALIAS");
-    if (!P.split && P.Sp == P.S && P.Lp == P.L && !no_alias && ((uintptr_t)a & 255) == 0) {   // aligned like the workspace buffers
-      if (P.transpose) r.out_as_xg1 = (uint16_t*)a; else r.out_as_xhi1 = (uint16_t*)a;
-    }
+    Run::XGroup x = {};
+    x.batch = batch; x.boff = 0; x.m = m; x.n = n; x.L = P.L; x.Lp = P.Lp; x.transpose = P.transpose; x.x = a;
     for (int i = 0; i < 2; ++i) {
-      fa.Xa_hi[i] = (i == 1 && r.out_as_xhi1) ? r.out_as_xhi1 : r.at<uint16_t>(P.o_xhi[i]);
-      fa.Xa_lo[i] = P.split ? r.at<uint16_t>(P.o_xlo[i]) : nullptr;
-      fa.Xg[i] = (i == 1 && r.out_as_xg1) ? r.out_as_xg1 : r.at<uint16_t>(P.o_xg[i]);
+      x.Xhi[i] = r.at<uint16_t>(P.o_xhi[i]);
+      x.Xlo[i] = P.split ? r.at<uint16_t>(P.o_xlo[i]) : nullptr;
+      x.Xg[i] = r.at<uint16_t>(P.o_xg[i]);
     }
+    alias_output(P, x);
+    r.xg.push_back(x);
+    bf16_prep_final(P, x, pa, fa);
   } else {
     pa.X32 = r.at<float>(P.o_x[0]);
     if (fn == PRISM_FN_SQRT || fn == PRISM_FN_INVERSE || fn == PRISM_FN_SQRT_NEWTON) pa.Y32 = r.at<float>(P.o_y[0]);
@@ -815,6 +888,128 @@ int run(int fn, void* a, void* inv_out, int root_p, int batch, int m, int n, int
   if (rc != PRISM_OK) return rc;
   { ProfScope ps(PK_FINAL, r.s); launch_finalize(fa, r.s); }
   return check_hip();
+}
+
+// bf16 polar factors of several shape groups that share the short side (the weight gradients of a
+// layer stack: 768 x 768, 768 x 3072, 3072 x 768, 768 x 2304): one launch sequence for all of them
+// on the caller's stream.  R, Q, the chain vectors and the control blocks of all matrices form one
+// batch, so R^2, the chain products, the moments and the solve are single launches over every
+// matrix of the call; the Gram product and the update take one descriptor per group in one launch
+// each (the kernel maps its workgroup index to group, matrix and tile).  Every matrix goes through
+// the kernels its own single-group call would pick.  Returns PRISM_EUNSUPPORTED (nothing enqueued)
+// when the groups do not fit this form; the caller then takes the per-group path.
+int run_polar_bf16_shapes(const prism_group* groups, int ngroups, int degree, int max_iters, int sketch_dim, uint64_t seed,
+                          double tol, void* stream, const prism_options* opt, int batch_scale = 1) {
+  static const int off = ab_switch("PRISM_NO_SHARED_SHAPES");
+  if (off || ngroups < 2 || ngroups > BF16_MAX_GROUPS) return PRISM_EUNSUPPORTED;
+  if (max_iters < 0 || max_iters > PRISM_MAX_ITERS || !(tol == tol)) return PRISM_EINVAL;
+  if (opt && (opt->warm_iters < 0 || opt->schedule_len < 0 || opt->schedule_len > PRISM_MAX_ITERS ||
+              (opt->schedule_len > 0 && !opt->alpha_schedule)))
+    return PRISM_EINVAL;
+  const unsigned flags = opt ? opt->flags : 0u;
+  Plan Pg[BF16_MAX_GROUPS];
+  long long btot = 0;
+  for (int g = 0; g < ngroups; ++g) {
+    if (groups[g].batch <= 0 || groups[g].m <= 0 || groups[g].n <= 0 || !groups[g].x) return PRISM_EUNSUPPORTED;   // empty or invalid: per-group path
+    const int rc = make_plan(Pg[g], PRISM_FN_POLAR, groups[g].batch, groups[g].m, groups[g].n, PRISM_BF16, degree, sketch_dim, 0, flags);
+    if (rc != PRISM_OK) return rc;
+    if (Pg[g].S != Pg[0].S || Pg[g].Sp != Pg[0].Sp || Pg[g].tile != Pg[0].tile || Pg[g].ksplit) return PRISM_EUNSUPPORTED;
+    // every group must get the chain kernels of its own call (batch_scale: the groups passed in are
+    // 1 / batch_scale of the caller's groups each)
+    const int bg = groups[g].batch * batch_scale, b0 = groups[0].batch * batch_scale;
+    if (chain_takes_small_kernel(Pg[g].Sp, Pg[g].ld, bg, true) != chain_takes_small_kernel(Pg[0].Sp, Pg[0].ld, b0, true) ||
+        chain_takes_small_kernel(Pg[g].Sp, Pg[g].ld, bg, false) != chain_takes_small_kernel(Pg[0].Sp, Pg[0].ld, b0, false) ||
+        chain_bf16_supported(Pg[g].Sp, Pg[g].ld, bg, Pg[g].Sp) != chain_bf16_supported(Pg[0].Sp, Pg[0].ld, b0, Pg[0].Sp))
+      return PRISM_EUNSUPPORTED;
+    btot += groups[g].batch;
+  }
+  if (btot > PRISM_MAX_BATCH) return PRISM_EUNSUPPORTED;
+  Run r;
+  int rc = make_plan(r.P, PRISM_FN_POLAR, (int)btot, Pg[0].S, Pg[0].S, PRISM_BF16, degree, sketch_dim, 0, flags, true);
+  if (rc != PRISM_OK) return rc;
+  Plan& P = r.P;
+  // iterate buffers per group behind the shared part
+  size_t off_bytes = P.total;
+  auto take = [&](size_t bytes) { size_t o = off_bytes; off_bytes = align256(off_bytes + bytes); return o; };
+  size_t o_xhi[BF16_MAX_GROUPS][2], o_xlo[BF16_MAX_GROUPS][2], o_xg[BF16_MAX_GROUPS][2];
+  for (int g = 0; g < ngroups; ++g) {
+    const size_t bytes = (size_t)groups[g].batch * Pg[g].Lp * Pg[g].Sp * 2;
+    for (int i = 0; i < 2; ++i) {
+      o_xhi[g][i] = take(bytes);
+      o_xlo[g][i] = P.split ? take(bytes) : 0;
+      o_xg[g][i] = take(bytes);
+    }
+  }
+  P.total = off_bytes;
+  r.s = (hipStream_t)stream;
+  rc = get_workspace(P.total, r.s, nullptr, &r.ws);
+  if (rc != PRISM_OK) return rc;
+  r.ctrl = r.at<Ctrl>(P.o_ctrl);
+  r.info = r.at<prism_info>(P.o_info);
+  r.rho = r.at<float>(P.o_rho);
+  r.v0 = r.at<float>(P.o_v0);
+  r.v = r.at<float>(P.o_v);
+  r.max_iters = max_iters; r.tol = tol; r.seed = seed; r.warm = opt ? opt->warm_iters : 0;
+  r.sched = opt ? opt->alpha_schedule : nullptr;
+  r.sched_len = opt ? opt->schedule_len : 0;
+  r.first_fit = r.warm > r.sched_len ? r.warm : r.sched_len;
+  r.chain_sel_batch = groups[0].batch * batch_scale;
+  int boff = 0;
+  for (int g = 0; g < ngroups; ++g) {
+    Run::XGroup x = {};
+    x.batch = groups[g].batch; x.boff = boff; x.m = groups[g].m; x.n = groups[g].n;
+    x.L = Pg[g].L; x.Lp = Pg[g].Lp; x.transpose = Pg[g].transpose; x.x = groups[g].x;
+    for (int i = 0; i < 2; ++i) {
+      x.Xhi[i] = r.at<uint16_t>(o_xhi[g][i]);
+      x.Xlo[i] = P.split ? r.at<uint16_t>(o_xlo[g][i]) : nullptr;
+      x.Xg[i] = r.at<uint16_t>(o_xg[g][i]);
+    }
+    alias_output(P, x);
+    r.xg.push_back(x);
+    boff += x.batch;
+  }
+  auto group_args = [&](const Run::XGroup& x, PrepArgs& pa, FinalArgs& fa) {
+    pa = PrepArgs{}; fa = FinalArgs{};
+    pa.fn = PRISM_FN_POLAR; pa.dt = PRISM_BF16; pa.batch = x.batch; pa.m = x.m; pa.n = x.n;
+    pa.S = P.S; pa.L = x.L; pa.Sp = P.Sp; pa.Lp = x.Lp; pa.transpose = x.transpose; pa.root_p = 0; pa.src = x.x;
+    pa.sumsq_part = r.at<double>(P.o_sumsq) + (long long)x.boff * P.nsum; pa.nsum = P.nsum;
+    pa.ctrl = r.ctrl + x.boff; pa.info = r.info + x.boff; pa.rho_part = r.rho; pa.tile = P.tile;
+    fa.fn = PRISM_FN_POLAR; fa.dt = PRISM_BF16; fa.batch = x.batch; fa.m = x.m; fa.n = x.n;
+    fa.S = P.S; fa.L = x.L; fa.Sp = P.Sp; fa.Lp = x.Lp; fa.transpose = x.transpose; fa.dst = x.x; fa.dst2 = nullptr;
+    fa.ctrl = r.ctrl + x.boff;
+    bf16_prep_final(P, x, pa, fa);
+  };
+  PrepArgs pa; FinalArgs fa;
+  {
+    ProfScope ps(PK_PREP, r.s);
+    for (const Run::XGroup& x : r.xg) { group_args(x, pa, fa); launch_sumsq(pa, r.s); launch_prepare(pa, r.s); }
+  }
+  if (P.p_s > 0 && max_iters > r.first_fit) {
+    ProfScope ps(PK_SKETCH, r.s);
+    launch_sketch(r.v0, P.Sp, P.S, P.ld, P.p_s, seed, r.first_fit, max_iters - r.first_fit, P.fn, r.s);
+  }
+  rc = check_hip();
+  if (rc != PRISM_OK) return rc;
+  rc = run_polar_bf16(r);
+  if (rc != PRISM_OK) return rc;
+  {
+    ProfScope ps(PK_FINAL, r.s);
+    for (const Run::XGroup& x : r.xg) { group_args(x, pa, fa); launch_finalize(fa, r.s); }
+  }
+  rc = check_hip();
+  if (rc != PRISM_OK) return rc;
+  // the reports were written into one array over all matrices: hand each group its part
+  boff = 0;
+  for (int g = 0; g < ngroups; ++g) {
+    if (groups[g].info &&
+        hipMemcpyAsync(groups[g].info, r.info + boff, (size_t)groups[g].batch * sizeof(prism_info), hipMemcpyDeviceToDevice, r.s) != hipSuccess) {
+      (void)hipGetLastError();
+      set_last_error("copying the per-matrix reports failed");
+      return PRISM_EHIP;
+    }
+    boff += groups[g].batch;
+  }
+  return PRISM_OK;
 }
 
 // Internal streams of the grouped call, per device, created on first use (default priority).
@@ -845,7 +1040,7 @@ int get_fork(Fork** out) {
 }
 
 int run_grouped(int fn, const prism_group* groups, int ngroups, int root_p, int dt, int degree, int max_iters,
-                int sketch_dim, uint64_t seed, double tol, void* stream, const prism_options* opt) {
+                int sketch_dim, uint64_t seed, double tol, void* stream, const prism_options* opt, bool from_auto_split = false) {
   set_last_error("");
   if (ngroups == 0) return PRISM_OK;
   if (!groups || ngroups < 0) return PRISM_EINVAL;
@@ -860,10 +1055,74 @@ int run_grouped(int fn, const prism_group* groups, int ngroups, int root_p, int 
     return run(fn, groups[0].x, groups[0].inv_out, root_p, groups[0].batch, groups[0].m, groups[0].n, dt, degree,
                max_iters, sketch_dim, seed, tol, stream, &o);
   }
+  int rc;
   Fork* f = nullptr;
-  int rc = get_fork(&f);
-  if (rc != PRISM_OK) return rc;
   hipStream_t user = (hipStream_t)stream;
+  const bool single_stream = opt && (opt->flags & PRISM_FLAG_SINGLE_STREAM);
+  if (fn == PRISM_FN_POLAR && dt == PRISM_BF16 && !from_auto_split) {
+    // Groups that share the short side run as one launch sequence over all their matrices.  With
+    // many matrices the sequence is issued for four quarters (or two halves) of every group on
+    // internal streams: the latency-bound steps of one part (chain, moments, solve, prologues and
+    // epilogues of short products) then run beside the products of another.  Measured on the
+    // Muon-shaped batch of 64 (replayed from a HIP graph / eager): one sequence 4.00 / 3.93 ms, two
+    // halves 3.80 / 3.82, four quarters 3.39 / 4.07, one call per group on four streams 3.40 / 4.09.
+    static const int no_halves = ab_switch("PRISM_SHARED_SHAPES_NO_HALVES");
+    static const int parts_sw = ab_switch("PRISM_SHARED_SHAPES_PARTS");
+    long long btot = 0;
+    int common = 4;   // parts every group's batch divides into: 4, else 2, else 1
+    for (int gi = 0; gi < ngroups; ++gi) {
+      btot += groups[gi].batch;
+      while (common > 1 && (groups[gi].batch <= 0 || groups[gi].batch % common)) common >>= 1;
+    }
+    const int NP = (parts_sw == 2 || parts_sw == 4) ? (common >= parts_sw ? parts_sw : common) : common;
+    const bool even = ngroups <= BF16_MAX_GROUPS && NP >= 2 && !single_stream;
+    if (!even || btot < 32 || no_halves) {
+      rc = run_polar_bf16_shapes(groups, ngroups, degree, max_iters, sketch_dim, seed, tol, stream, opt);
+      if (rc != PRISM_EUNSUPPORTED) return rc;
+    } else {
+      prism_group half[4][BF16_MAX_GROUPS];   // NP <= 4 parts
+      for (int gi = 0; gi < ngroups; ++gi) {
+        const size_t bytes = (size_t)(groups[gi].batch / NP) * groups[gi].m * groups[gi].n * 2;
+        for (int h = 0; h < NP; ++h) {
+          half[h][gi] = groups[gi];
+          half[h][gi].batch = groups[gi].batch / NP;
+          half[h][gi].x = (char*)groups[gi].x + h * bytes;
+          half[h][gi].info = groups[gi].info ? groups[gi].info + h * (groups[gi].batch / NP) : nullptr;
+        }
+      }
+      rc = get_fork(&f);
+      if (rc != PRISM_OK) return rc;
+      if (hipEventRecord(f->forked, user) != hipSuccess) { (void)hipGetLastError(); set_last_error("hipEventRecord failed"); return PRISM_EHIP; }
+      int forked = 0, first_error = PRISM_OK;
+      for (; forked < NP; ++forked)
+        if (hipStreamWaitEvent(f->streams[forked], f->forked, 0) != hipSuccess) { first_error = PRISM_EHIP; break; }
+      bool unsupported = false;
+      for (int h = 0; h < NP && first_error == PRISM_OK; ++h) {
+        first_error = run_polar_bf16_shapes(half[h], ngroups, degree, max_iters, sketch_dim, seed, tol, f->streams[h], opt, NP);
+        if (h == 0 && first_error == PRISM_EUNSUPPORTED) { unsupported = true; first_error = PRISM_OK; break; }   // nothing was enqueued
+      }
+      for (int i = 0; i < forked; ++i) {
+        if (hipEventRecord(f->joined[i], f->streams[i]) != hipSuccess || hipStreamWaitEvent(user, f->joined[i], 0) != hipSuccess) {
+          (void)hipGetLastError();
+          if (first_error == PRISM_OK) { set_last_error("joining an internal stream failed"); first_error = PRISM_EHIP; }
+        }
+      }
+      if (!unsupported) return first_error;
+    }
+    set_last_error("");
+  }
+  if (single_stream) {
+    for (int gi = 0; gi < ngroups; ++gi) {
+      prism_options o = opt ? *opt : prism_options{};
+      o.info = groups[gi].info;
+      rc = run(fn, groups[gi].x, groups[gi].inv_out, root_p, groups[gi].batch, groups[gi].m, groups[gi].n, dt, degree,
+               max_iters, sketch_dim, seed, tol, stream, &o);
+      if (rc != PRISM_OK) return rc;
+    }
+    return PRISM_OK;
+  }
+  rc = get_fork(&f);
+  if (rc != PRISM_OK) return rc;
   const int used = ngroups < GROUP_STREAMS ? ngroups : GROUP_STREAMS;
   // nothing is forked before this record succeeds
   if (hipEventRecord(f->forked, user) != hipSuccess) { (void)hipGetLastError(); set_last_error("hipEventRecord failed"); return PRISM_EHIP; }
@@ -898,7 +1157,7 @@ int run_auto(int fn, void* a, void* inv_out, int root_p, int batch, int m, int n
              int sketch_dim, uint64_t seed, double tol, void* stream, const prism_options* opt) {
   static const int no_split = ab_switch("PRISM_NO_BATCH_SPLIT");
   const int S = m < n ? m : n;
-  if (no_split || !a || batch < 8 || (batch & 1) || S < 1024 || (opt && opt->workspace) || g_prof_on)
+  if (no_split || !a || batch < 8 || (batch & 1) || S < 1024 || (opt && opt->workspace) || (opt && (opt->flags & PRISM_FLAG_SINGLE_STREAM)) || g_prof_on)
     return run(fn, a, inv_out, root_p, batch, m, n, dt, degree, max_iters, sketch_dim, seed, tol, stream, opt);
   const size_t esz = dt == PRISM_BF16 ? 2 : 4;
   const size_t half = (size_t)(batch / 2) * m * n * esz;
@@ -911,7 +1170,7 @@ int run_auto(int fn, void* a, void* inv_out, int root_p, int batch, int m, int n
   }
   prism_options o = opt ? *opt : prism_options{};
   o.info = nullptr;
-  return run_grouped(fn, gr, 2, root_p, dt, degree, max_iters, sketch_dim, seed, tol, stream, &o);
+  return run_grouped(fn, gr, 2, root_p, dt, degree, max_iters, sketch_dim, seed, tol, stream, &o, true);
 }
 
 }  // namespace

@@ -17,6 +17,7 @@ FN_POLAR, FN_SQRT, FN_INV_ROOT, FN_SIGN, FN_INVERSE, FN_SQRT_NEWTON = 1, 2, 3, 4
 MAX_ITERS = 64
 FLAG_BF16_PLAIN_ITERATE = 1
 FLAG_SHARED_GPU = 2
+FLAG_SINGLE_STREAM = 4
 OK, EINVAL, EUNSUPPORTED, ENOMEM, EHIP = 0, 1, 2, 3, 4
 INFO_CONVERGED, INFO_BUDGET, INFO_NONFINITE, INFO_ZERO, INFO_DIVERGED = 0, 1, 2, 3, 4
 

@@ -83,11 +83,12 @@ def test_c2_muon_full(prism):
         allbits.append(bits)
         xs.append(_bf16_tensor(bits.copy()))
     eager = [x.clone() for x in xs]
-    prism.run_grouped(prism.FN_POLAR, eager, 5, 5, 16, SEED, 0.0, flags=prism.FLAG_BF16_PLAIN_ITERATE)
-    torch.cuda.synchronize()
     side = torch.cuda.Stream()
     graph = torch.cuda.CUDAGraph()
     with torch.cuda.stream(side):
+        # the eager call also creates the library's workspace of this stream, so that the capture below allocates nothing
+        prism.run_grouped(prism.FN_POLAR, eager, 5, 5, 16, SEED, 0.0, flags=prism.FLAG_BF16_PLAIN_ITERATE)
+        side.synchronize()
         with torch.cuda.graph(graph, stream=side):
             _, handles = prism.run_grouped(prism.FN_POLAR, xs, 5, 5, 16, SEED, 0.0, flags=prism.FLAG_BF16_PLAIN_ITERATE)
         for _ in range(2):

@@ -37,9 +37,10 @@ def test_grouped_polar_equals_single_calls_and_oracle(prism):
         x = _bf16(b.copy())
         prism.polar(x, 5, 5, 16, SEED, 0.0, flags=prism.FLAG_BF16_PLAIN_ITERATE)
         single.append(x)
-    for rep in range(2):
+    for rep in range(3):   # the last one with every kernel on the caller's stream
         xs = [_bf16(b.copy()) for b in bits]
-        _, infos = prism.run_grouped(prism.FN_POLAR, xs, 5, 5, 16, SEED, 0.0, flags=prism.FLAG_BF16_PLAIN_ITERATE)
+        flags = prism.FLAG_BF16_PLAIN_ITERATE | (prism.FLAG_SINGLE_STREAM if rep == 2 else 0)
+        _, infos = prism.run_grouped(prism.FN_POLAR, xs, 5, 5, 16, SEED, 0.0, flags=flags)
         torch.cuda.synchronize()
         for g, (x, ref) in enumerate(zip(xs, single)):
             assert torch.equal(x.view(torch.int16), ref.view(torch.int16)), g
@@ -48,6 +49,29 @@ def test_grouped_polar_equals_single_calls_and_oracle(prism):
     out0 = W.from_bf16_bits(xs[1][0].view(torch.int16).cpu().numpy().view(np.uint16))
     ref, _ = O.polar(W.from_bf16_bits(bits[1][0]), 5, 5, 16, SEED, 0.0)
     assert _rel(out0, ref) <= 2e-2
+
+
+def test_grouped_polar_in_parts_on_internal_streams(prism):
+    """Batches that are multiples of four: the one launch sequence over all shapes is issued per
+    quarter of every group on internal streams (split iterate here, and a tolerance, so that the
+    per-matrix stop flags matter).  Same bits as the single calls, reports in the caller's arrays."""
+    bits = [W.c2_muon_group(i, batch=8, scale=4, data_seed=1500 + i) for i in range(4)]
+    single, single_info = [], []
+    for b in bits:
+        x = _bf16(b.copy())
+        single_info.append(prism.polar(x, 5, 30, 16, SEED, 2e-2).read())
+        single.append(x)
+    xs = [_bf16(b.copy()) for b in bits]
+    _, infos = prism.run_grouped(prism.FN_POLAR, xs, 5, 30, 16, SEED, 2e-2)
+    torch.cuda.synchronize()
+    for g in range(4):
+        assert torch.equal(xs[g].view(torch.int16), single[g].view(torch.int16)), g
+        rec = infos[g].read()
+        assert np.array_equal(rec["iters"], single_info[g]["iters"]) and np.array_equal(rec["alpha"], single_info[g]["alpha"])
+        assert np.array_equal(rec["status"], single_info[g]["status"])
+    out0 = W.from_bf16_bits(xs[2][5].view(torch.int16).cpu().numpy().view(np.uint16))
+    ref, oinfo = O.polar(W.from_bf16_bits(bits[2][5]), 5, 30, 16, SEED, 2e-2)
+    assert _rel(out0, ref) <= 2e-2 and infos[2].read()[5]["iters"] == oinfo["iters"]
 
 
 def test_grouped_fp32_polar_with_small_and_general_groups(prism):
