@@ -52,6 +52,8 @@ def parse():
     ap.add_argument("--no-graph", dest="graph", action="store_false",
                     help="c2: launch the grouped call eagerly instead of replaying a captured HIP graph")
     ap.add_argument("--only-group", type=int, default=-1, help="c2: run a single shape group (profiling aid)")
+    ap.add_argument("--input-cache", default=None, metavar="DIR",
+                    help="keep the generated inputs of c3 / c5 (a minute of host work each) as .npy files in DIR and reuse them")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle legs")
     ap.add_argument("--no-profile", action="store_true", help="skip the per-kernel event pass")
     ap.add_argument("--copy-probe", action="store_true",
@@ -61,6 +63,19 @@ def parse():
 
 class Workload:
     """name, groups of host arrays, how to call the library, flop model."""
+
+
+def cached(args, key, make):
+    """make() or its copy kept in --input-cache (the generators are seeded: same bits either way)."""
+    if not args.input_cache:
+        return make()
+    os.makedirs(args.input_cache, exist_ok=True)
+    path = os.path.join(args.input_cache, key + ".npy")
+    if os.path.exists(path):
+        return np.load(path)
+    arr = make()
+    np.save(path, arr)
+    return arr
 
 
 def make_workload(name, args, prism, W):
@@ -84,7 +99,7 @@ def make_workload(name, args, prism, W):
         b = args.batch or 8
         wl.desc = "polar of %d x 4096x4096 bf16, sigma log-uniform [1e-4,1], degree 5, sketch 32, tol 1e-2, split-bf16 iterate" % b
         wl.dtype = "bf16"
-        wl.host = [W.c3_polar_large(batch=b)]
+        wl.host = [cached(args, "c3_b%d" % b, lambda: W.c3_polar_large(batch=b))]
         wl.call = lambda x: prism.polar(x, 5, 40, 32, wl.seed, 1e-2)
         wl.split = True
         wl.ld, wl.nv, wl.r_bytes = 32, 5, 2
@@ -99,7 +114,7 @@ def make_workload(name, args, prism, W):
         b = args.batch or 4
         wl.desc = "sqrt + inverse sqrt of %d x 8192x8192 fp32 SPD (Wishart), degree 5, sketch 64, tol 1e-5" % b
         wl.dtype = "f32"
-        wl.host = [W.c5_wishart_spd(batch=b)]
+        wl.host = [cached(args, "c5_b%d" % b, lambda: W.c5_wishart_spd(batch=b))]
         wl.call = lambda x: prism.sqrt(x, 5, 40, 64, wl.seed, 1e-5)[1]
         wl.ld, wl.nv, wl.r_bytes = 64, 5, 4
     elif name == "sqrt-newton":

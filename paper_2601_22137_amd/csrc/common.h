@@ -83,6 +83,8 @@ struct Bf16Desc {
   int sym;                                           // GRAM / POLYQ with A == B: compute the upper triangle of tiles only
   int n_true;                                        // GRAM mask
   float* C32; long long strideC32; int ldc32;        // STORE / GRAM fp32 out; POLYQ fp32 in.  Null with `diag` set:
+  int upper32;                                       // GRAM: the fp32 matrix is written in the computed tiles only (no mirror image):
+                                                     // enough for the R^2 epilogue and for readers of the diagonal
   float* diag; long long strideDiag;                 // symmetric GRAM writes only the bf16 copy and the fp32 diagonal, POLYQ reads the bf16 copy (Cin)
   const uint16_t* Cin16;                             // POLYQ without C32: R in bf16 (layout of Cb)
   uint16_t* Cb; long long strideCb; int ldcb;        // GRAM: Rb out; POLYQ: Q out; APPLY: Xa_hi' out

@@ -230,19 +230,24 @@ __global__ __launch_bounds__(NT, wgs_per_cu(TM, TN)) void gemm_bf16_kernel(Bf16M
   for (; kt < KT_main; ++kt) {          // steady state: no conditions inside
     const int nslot = slot == STAGES - 1 ? 0 : slot + 1;
     const int lslot = slot == 0 ? STAGES - 1 : slot - 1;   // slot of slab kt-1 = slot of slab kt+STAGES-1
+    // Every step issues its MFMA first: the first one of a half waits for the fragments read during
+    // the half before (long complete), and a read placed ahead of it would add its own LDS latency
+    // to that wait (the counter only tells "all reads done").
 #pragma unroll
     for (int u = 0; u < NSTEP; ++u) {
+      if (u < NM) mfma_one(0, u);
+      __builtin_amdgcn_sched_barrier(0);
       if (u < NF) load_frag(slot, 1, u);
       if (u < NL) issue_load(kt + STAGES - 1, lslot, u);
-      if (u < NM) mfma_one(0, u);
       __builtin_amdgcn_sched_barrier(0);
     }
     wait_vmcnt<(STAGES - 2) * NL>();   // slab kt+1 has landed; the younger ones may be in flight
     ring_barrier();
 #pragma unroll
     for (int u = 0; u < NSTEP; ++u) {
-      if (u < NF) load_frag(nslot, 0, u);
       if (u < NM) mfma_one(1, u);
+      __builtin_amdgcn_sched_barrier(0);
+      if (u < NF) load_frag(nslot, 0, u);
       __builtin_amdgcn_sched_barrier(0);
     }
     slot = nslot;
@@ -360,7 +365,7 @@ __global__ __launch_bounds__(NT, wgs_per_cu(TM, TN)) void gemm_bf16_kernel(Bf16M
             t1[e] = strip[(rq * 8 + 4 + e) * SW + col];
           }
           const int mr = n0 + wn0 + col, nr = m0 + wm0 + i * 32 + rq * 8;   // mirrored position
-          if (EPI == BEPI_GRAM && !lean) {
+          if (EPI == BEPI_GRAM && !lean && !g.upper32) {
             *(f32x4*)(g.C32 + b32 + (long long)mr * g.ldc32 + nr) = t0;
             *(f32x4*)(g.C32 + b32 + (long long)mr * g.ldc32 + nr + 4) = t1;
           }

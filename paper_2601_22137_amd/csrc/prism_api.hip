@@ -538,6 +538,9 @@ int run_polar_bf16(Run& r) {
         g.A = x.Xg[cur]; g.strideA = LS; g.lda = x.Lp; g.B = x.Xg[cur]; g.strideB = LS; g.ldb = x.Lp;
         g.M = Sp; g.N = Sp; g.K = x.Lp; g.batch = x.batch; g.epi = BEPI_GRAM; g.n_true = P.S;
         g.C32 = lean ? nullptr : R + x.boff * SS; g.strideC32 = SS; g.ldc32 = Sp;
+        // with the bf16 chain only the R^2 epilogue and the chain's diagonal read the fp32 matrix: both stay
+        // inside the tiles the Gram product computes when its tile rows are whole multiples of those of R^2
+        g.upper32 = (chain_b && Tg.m % Tq.m == 0) ? 1 : 0;
         g.Cb = Rb + x.boff * SS; g.strideCb = SS; g.ldcb = Sp;
         g.diag = lean ? Dg + (long long)x.boff * Sp : nullptr; g.strideDiag = Sp;
         g.rho_part = r.rho + (long long)x.boff * nparts; g.ctrl = r.ctrl + x.boff;
