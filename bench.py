@@ -56,6 +56,12 @@ def parse():
                     help="keep the generated inputs of c3 / c5 (a minute of host work each) as .npy files in DIR and reuse them")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle legs")
     ap.add_argument("--no-profile", action="store_true", help="skip the per-kernel event pass")
+    ap.add_argument("--single-stream", action="store_true",
+                    help="keep every kernel on one stream (PRISM_FLAG_SINGLE_STREAM; no HIP graph): the launch configuration "
+                         "of the per-kernel pass, for profiler runs in which no kernel is stretched by a neighbour")
+    ap.add_argument("--gemm-probe", type=int, default=0, metavar="TILE",
+                    help="only run the bare bf16 product 8 x 4096^3 (no epilogue work beyond the fp32 store) ten times with "
+                         "tile 256, 2561 (256 x 128) or 128, and print its rate: the kernel under the profiler's counters")
     ap.add_argument("--copy-probe", action="store_true",
                     help="only copy 1 GiB device to device three times (calibrates the FETCH_SIZE / WRITE_SIZE counters)")
     return ap.parse_args()
@@ -84,6 +90,7 @@ def make_workload(name, args, prism, W):
     wl.seed = W.SKETCH_SEED
     wl.split = False
     wl.p_s, wl.nv = 0, 0           # sketch width (padded) and products per chain, for the HBM-bound kernels
+    ss = prism.FLAG_SINGLE_STREAM if args.single_stream else 0
     if name == "c2":
         wl.desc = "muon-shaped: 64 bf16 matrices = 16 x {768x768, 768x3072, 3072x768, 768x2304}, degree 5, sketch 16, 5 iterations" + \
                   (", split-bf16 iterate" if args.split else ", plain bf16 iterate")
@@ -92,7 +99,7 @@ def make_workload(name, args, prism, W):
         wl.flags = 0 if args.split else prism.FLAG_BF16_PLAIN_ITERATE
         # single calls (profile pass, --no-grouped) carry the hint that the grouped call gives its groups,
         # so that the same kernels are timed
-        wl.call = lambda x: prism.polar(x, 5, 5, 16, wl.seed, 0.0, flags=wl.flags | prism.FLAG_SHARED_GPU)
+        wl.call = lambda x: prism.polar(x, 5, 5, 16, wl.seed, 0.0, flags=wl.flags | prism.FLAG_SHARED_GPU | ss)
         wl.split = args.split
         wl.ld, wl.nv, wl.r_bytes = 16, 5, 2
     elif name == "c3":
@@ -100,7 +107,7 @@ def make_workload(name, args, prism, W):
         wl.desc = "polar of %d x 4096x4096 bf16, sigma log-uniform [1e-4,1], degree 5, sketch 32, tol 1e-2, split-bf16 iterate" % b
         wl.dtype = "bf16"
         wl.host = [cached(args, "c3_b%d" % b, lambda: W.c3_polar_large(batch=b))]
-        wl.call = lambda x: prism.polar(x, 5, 40, 32, wl.seed, 1e-2)
+        wl.call = lambda x: prism.polar(x, 5, 40, 32, wl.seed, 1e-2, flags=ss)
         wl.split = True
         wl.ld, wl.nv, wl.r_bytes = 32, 5, 2
     elif name == "c4":
@@ -108,14 +115,14 @@ def make_workload(name, args, prism, W):
         wl.desc = "inverse 4th root of %d x 1024x1024 fp32 SPD (power-law spectrum), sketch 16, tol 1e-5" % b
         wl.dtype = "f32"
         wl.host = [W.c4_shampoo_spd(batch=b)]
-        wl.call = lambda x: prism.inv_root(x, 4, 40, 16, wl.seed, 1e-5)
+        wl.call = lambda x: prism.inv_root(x, 4, 40, 16, wl.seed, 1e-5, flags=ss)
         wl.ld, wl.nv, wl.r_bytes = 16, 5, 4
     elif name == "c5":
         b = args.batch or 4
         wl.desc = "sqrt + inverse sqrt of %d x 8192x8192 fp32 SPD (Wishart), degree 5, sketch 64, tol 1e-5" % b
         wl.dtype = "f32"
         wl.host = [cached(args, "c5_b%d" % b, lambda: W.c5_wishart_spd(batch=b))]
-        wl.call = lambda x: prism.sqrt(x, 5, 40, 64, wl.seed, 1e-5)[1]
+        wl.call = lambda x: prism.sqrt(x, 5, 40, 64, wl.seed, 1e-5, flags=ss)[1]
         wl.ld, wl.nv, wl.r_bytes = 64, 5, 4
     elif name == "sqrt-newton":
         b = args.batch or 4
@@ -237,11 +244,12 @@ def run_config(name, K, Wm, args, torch, prism, W):
     copies = [[p.clone() for p in pristine] for _ in range(n_copies)]
 
     grouped = bool(args.grouped) and name == "c2" and len(wl.host) > 1
-    graph = grouped and bool(args.graph)
+    graph = grouped and bool(args.graph) and not args.single_stream
+    ss = prism.FLAG_SINGLE_STREAM if args.single_stream else 0
 
     def step(i, extra_flags=0):
         if grouped:
-            return prism.run_grouped(prism.FN_POLAR, copies[i], 5, 5, 16, wl.seed, 0.0, flags=wl.flags | extra_flags)[1]
+            return prism.run_grouped(prism.FN_POLAR, copies[i], 5, 5, 16, wl.seed, 0.0, flags=wl.flags | extra_flags | ss)[1]
         return [wl.call(x) for x in copies[i]]
 
     graphs = None
@@ -436,6 +444,22 @@ def main():
     prism.lib()
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
+    if args.gemm_probe:
+        gen = torch.Generator(device="cuda").manual_seed(1)
+        a = torch.randn(8, 4096, 4096, device="cuda", generator=gen).to(torch.bfloat16)
+        b = torch.randn(8, 4096, 4096, device="cuda", generator=gen).to(torch.bfloat16)
+        prism.gemm_bf16_nt(a, b, args.gemm_probe)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(10):
+            prism.gemm_bf16_nt(a, b, args.gemm_probe)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / 10
+        print(json.dumps({"gemm_probe": "8 x 4096^3 bf16, tile %d" % args.gemm_probe, "ms": round(ms, 4),
+                          "tflops": round(2 * 8 * 4096.0 ** 3 / ms / 1e9, 1)}))
+        return
 
     head_name = args.workload or "c3"
     head = run_config(head_name, args.steps, args.warmup, args, torch, prism, W)

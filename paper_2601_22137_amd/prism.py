@@ -182,55 +182,55 @@ def polar_static(x, degree=5, max_iters=30, sketch_dim=8, seed=22137, tol=1e-6, 
 
 
 def sqrt(a, degree=5, max_iters=30, sketch_dim=8, seed=22137, tol=1e-6, warm_iters=0, workspace=None,
-         alpha_schedule=None):
+         alpha_schedule=None, flags=0):
     """In place: a <- A^(1/2); returns (A^(-1/2), info handle)."""
     b, m, n = _batched(a)
     inv = torch.empty_like(a)
     info = _Info(b, a.device)
-    o = _options(info, 0, warm_iters, workspace, alpha_schedule)
+    o = _options(info, flags, warm_iters, workspace, alpha_schedule)
     _check(lib().prism_sqrt_ex(a.data_ptr(), inv.data_ptr(), b, m, n, _dtype_code(a), degree, max_iters, sketch_dim,
                                seed, tol, _stream(), ctypes.byref(o)))
     return inv, info
 
 
 def inv_root(a, root_p, max_iters=30, sketch_dim=8, seed=22137, tol=1e-6, warm_iters=0, workspace=None,
-             alpha_schedule=None):
+             alpha_schedule=None, flags=0):
     """In place: a <- A^(-1/root_p).  Returns an info handle."""
     b, m, n = _batched(a)
     info = _Info(b, a.device)
-    o = _options(info, 0, warm_iters, workspace, alpha_schedule)
+    o = _options(info, flags, warm_iters, workspace, alpha_schedule)
     _check(lib().prism_inv_root_ex(a.data_ptr(), root_p, b, m, n, _dtype_code(a), 3, max_iters, sketch_dim, seed,
                                    tol, _stream(), ctypes.byref(o)))
     return info
 
 
 def sign(x, degree=5, max_iters=30, sketch_dim=8, seed=22137, tol=1e-6, warm_iters=0, workspace=None,
-         alpha_schedule=None):
+         alpha_schedule=None, flags=0):
     """In place: x[batch, n, n] <- sign(x).  Returns an info handle."""
     b, m, n = _batched(x)
     info = _Info(b, x.device)
-    o = _options(info, 0, warm_iters, workspace, alpha_schedule)
+    o = _options(info, flags, warm_iters, workspace, alpha_schedule)
     _check(lib().prism_sign_ex(x.data_ptr(), b, m, n, _dtype_code(x), degree, max_iters, sketch_dim, seed, tol,
                                _stream(), ctypes.byref(o)))
     return info
 
 
-def inverse(a, max_iters=30, sketch_dim=8, seed=22137, tol=1e-6, warm_iters=0, workspace=None, alpha_schedule=None):
+def inverse(a, max_iters=30, sketch_dim=8, seed=22137, tol=1e-6, warm_iters=0, workspace=None, alpha_schedule=None, flags=0):
     """In place: a[batch, n, n] <- a^(-1) by the Chebyshev iteration.  Returns an info handle."""
     b, m, n = _batched(a)
     info = _Info(b, a.device)
-    o = _options(info, 0, warm_iters, workspace, alpha_schedule)
+    o = _options(info, flags, warm_iters, workspace, alpha_schedule)
     _check(lib().prism_inverse_ex(a.data_ptr(), b, m, n, _dtype_code(a), max_iters, sketch_dim, seed, tol,
                                   _stream(), ctypes.byref(o)))
     return info
 
 
-def sqrt_newton(a, max_iters=30, tol=1e-6, fit=True, workspace=None, alpha_schedule=None):
+def sqrt_newton(a, max_iters=30, tol=1e-6, fit=True, workspace=None, alpha_schedule=None, flags=0):
     """In place: a <- A^(1/2) by the DB Newton iteration; returns (A^(-1/2), info handle)."""
     b, m, n = _batched(a)
     inv = torch.empty_like(a)
     info = _Info(b, a.device)
-    o = _options(info, 0, 0, workspace, alpha_schedule)
+    o = _options(info, flags, 0, workspace, alpha_schedule)
     _check(lib().prism_sqrt_newton_ex(a.data_ptr(), inv.data_ptr(), b, m, n, _dtype_code(a), max_iters, int(bool(fit)), tol,
                                       _stream(), ctypes.byref(o)))
     return inv, info
