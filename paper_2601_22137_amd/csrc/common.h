@@ -76,6 +76,7 @@ enum Bf16Epi {
 };
 
 struct Bf16Desc {
+  int km;                                            // bit 0: A stored [K][M], bit 1: B stored [K][N] (lda / ldb: elements between k-rows)
   const uint16_t* A; long long strideA; int lda;    // [M][K]
   const uint16_t* B; long long strideB; int ldb;    // [N][K]
   int M, N, K, batch;

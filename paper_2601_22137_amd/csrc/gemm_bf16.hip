@@ -53,8 +53,13 @@ template <int N> __device__ inline void wait_vmcnt() {
   __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | 0x0F70);
 }
 
-template <int TM, int TN, int EPI, bool SYM>
+// KM: both operands are stored with K as the slow index ([K][M] and [K][N]: the Gram product X^T X
+// read from the [L][S] iterate itself, no transposed copy).  The slabs then sit in LDS as [k][row]
+// and the fragments are read with ds_read_b64_tr_b16, which hands every lane of a 16-lane group four
+// consecutive k of one row out of four 32-byte row segments (see below).
+template <int TM, int TN, int EPI, bool SYM, bool KMA, bool KMB>
 __global__ __launch_bounds__(NT, wgs_per_cu(TM, TN)) void gemm_bf16_kernel(Bf16Multi mg) {
+  constexpr bool KM = KMA || KMB;   // some fragment reads are transposing ones
   constexpr int STAGES = stages_of(TM, TN);
   constexpr int WTM = TM / 2, WTN = TN / 2;      // wave tile (2 x 2 waves)
   constexpr int NBM = WTM / 32, NBN = WTN / 32;  // 32x32 blocks per wave and dimension
@@ -121,8 +126,8 @@ __global__ __launch_bounds__(NT, wgs_per_cu(TM, TN)) void gemm_bf16_kernel(Bf16M
   const int wave = __builtin_amdgcn_readfirstlane(t >> 6);  // uniform: LDS destinations stay scalar
   const int wm0 = (wave >> 1) * WTM, wn0 = (wave & 1) * WTN;
   const int m0 = tm * TM, n0 = tn * TN;
-  const unsigned short* A1 = g.A + (long long)b * g.strideA + (long long)m0 * g.lda;
-  const unsigned short* Bb = g.B + (long long)b * g.strideB + (long long)n0 * g.ldb;
+  const unsigned short* A1 = g.A + (long long)b * g.strideA + (KMA ? (long long)m0 : (long long)m0 * g.lda);
+  const unsigned short* Bb = g.B + (long long)b * g.strideB + (KMB ? (long long)n0 : (long long)n0 * g.ldb);
 
   const int KT = g.K / BK;
 
@@ -130,21 +135,43 @@ __global__ __launch_bounds__(NT, wgs_per_cu(TM, TN)) void gemm_bf16_kernel(Bf16M
   // instruction moves 64 lanes x 16 bytes into 1 KiB of consecutive LDS = 16 rows of a slab.
   // Lane l fills slot l & 15 of line l >> 4 of those 16 rows and fetches the chunk that belongs
   // there (the line index within the slab is (it * 4 + wave) * 4 + (l >> 4)).
+  // KM: a slab is 32 k-rows of T consecutive entries; one wave instruction moves 64 / (T / 8) of
+  // them.  16-byte unit u of row k holds chunk u ^ (4 (k & 3)) of that row, so that the four row
+  // segments a transposing read touches (same chunks, rows 4j .. 4j + 3) fall on different banks.
   const int lq = lane >> 4, lu = (lane & 15) ^ ((wave * 4 + lq) & 15);
   unsigned aoff[LDA], boff[LDB];
+  if constexpr (KMA) {
+    constexpr int URA = TM / 8;          // 16-byte units per k-row
 #pragma unroll
-  for (int it = 0; it < LDA; ++it) aoff[it] = (unsigned)(((it * 4 + wave) * 16 + 4 * lq + (lu >> 2)) * g.lda + (lu & 3) * 8) * 2u;
+    for (int it = 0; it < LDA; ++it) {
+      const int k = (it * 4 + wave) * (64 / URA) + lane / URA, c = (lane % URA) ^ (4 * (k & 3));
+      aoff[it] = (unsigned)(k * g.lda + c * 8) * 2u;
+    }
+  } else {
 #pragma unroll
-  for (int it = 0; it < LDB; ++it) boff[it] = (unsigned)(((it * 4 + wave) * 16 + 4 * lq + (lu >> 2)) * g.ldb + (lu & 3) * 8) * 2u;
+    for (int it = 0; it < LDA; ++it) aoff[it] = (unsigned)(((it * 4 + wave) * 16 + 4 * lq + (lu >> 2)) * g.lda + (lu & 3) * 8) * 2u;
+  }
+  if constexpr (KMB) {
+    constexpr int URB = TN / 8;
+#pragma unroll
+    for (int it = 0; it < LDB; ++it) {
+      const int k = (it * 4 + wave) * (64 / URB) + lane / URB, c = (lane % URB) ^ (4 * (k & 3));
+      boff[it] = (unsigned)(k * g.ldb + c * 8) * 2u;
+    }
+  } else {
+#pragma unroll
+    for (int it = 0; it < LDB; ++it) boff[it] = (unsigned)(((it * 4 + wave) * 16 + 4 * lq + (lu >> 2)) * g.ldb + (lu & 3) * 8) * 2u;
+  }
   // load instruction u in [0, NL): first the LDA of A, then the LDB of B
   auto issue_load = [&](int kt, int slot, int u) {
-    const int kk0 = kt * BK;
+    const long long ka = KMA ? (long long)kt * BK * g.lda : (long long)kt * BK;
+    const long long kb = KMB ? (long long)kt * BK * g.ldb : (long long)kt * BK;
     if (u < LDA) {
       unsigned char* dst = smem + slot * BUF_BYTES + wave * 1024 + u * 4096;
-      __builtin_amdgcn_global_load_lds((gptr_t)((const char*)(A1 + kk0) + aoff[u]), (lptr_t)dst, 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((gptr_t)((const char*)(A1 + ka) + aoff[u]), (lptr_t)dst, 16, 0, 0);
     } else {
       unsigned char* dst = smem + slot * BUF_BYTES + OPA_BYTES + wave * 1024 + (u - LDA) * 4096;
-      __builtin_amdgcn_global_load_lds((gptr_t)((const char*)(Bb + kk0) + boff[u - LDA]), (lptr_t)dst, 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((gptr_t)((const char*)(Bb + kb) + boff[u - LDA]), (lptr_t)dst, 16, 0, 0);
     }
   };
   auto issue_loads = [&](int kt, int slot) {
@@ -172,14 +199,74 @@ __global__ __launch_bounds__(NT, wgs_per_cu(TM, TN)) void gemm_bf16_kernel(Bf16M
 #pragma unroll
     for (int par = 0; par < 2; ++par)
       koff[kk][par] = ((((lr & 3) << 2) + kk * 2 + lh) ^ ((lr >> 2) + 8 * par)) << 4;
+  // KM: lane l = (i = l % 16, mb = (l / 16) % 2, kg = l / 32) of row block f reads, for the half r of
+  // its eight k, the 8 bytes at row k = 16 kk + 8 kg + 4 r + i / 4, entries 32 f + 16 mb + 4 (i % 4) ..
+  // + 3 of the wave's rows; the instruction returns to lane l the entry 32 f + 16 mb + i of rows
+  // 16 kk + 8 kg + 4 r .. + 3: eight consecutive k of one row after two reads, the MFMA operand layout.
+  int fra[NBM], frb[NBN];
+  if constexpr (KMA) {
+    const int i = lane & 15, mb = (lane >> 4) & 1, kg = lane >> 5;
+#pragma unroll
+    for (int f = 0; f < NBM; ++f) {
+      const int c = wm0 / 8 + 4 * f + 2 * mb + ((i & 3) >> 1);
+      fra[f] = (8 * kg + (i >> 2)) * (TM / 8) * 16 + ((c ^ (4 * (i >> 2))) * 16) + 8 * (i & 1);
+    }
+  }
+  if constexpr (KMB) {
+    const int i = lane & 15, mb = (lane >> 4) & 1, kg = lane >> 5;
+#pragma unroll
+    for (int f = 0; f < NBN; ++f) {
+      const int c = wn0 / 8 + 4 * f + 2 * mb + ((i & 3) >> 1);
+      frb[f] = OPA_BYTES + (8 * kg + (i >> 2)) * (TN / 8) * 16 + ((c ^ (4 * (i >> 2))) * 16) + 8 * (i & 1);
+    }
+  }
+  // The transposing reads are issued as inline assembly: given as a builtin, the compiler cannot
+  // tell them from readers of the slabs still on their way into LDS and waits for every outstanding
+  // global load before each one, which empties the ring at every step.  The price: it does not wait
+  // for their results either, so every place that consumes fragments says so itself (frag_wait).
+  typedef unsigned u32x2v __attribute__((ext_vector_type(2)));
+  const unsigned lds0 = (unsigned)(size_t)(__attribute__((address_space(3))) unsigned char*)smem;
+  auto read_tr = [&](int byte_off) {
+    u32x2v r;
+    asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(r) : "v"(lds0 + (unsigned)byte_off));
+    return r;
+  };
+  // In a kernel with transposing reads the ordinary fragment reads are issued the same way, so that
+  // one explicit wait covers both kinds.
+  auto plain_frag = [&](const unsigned char* p) {
+    if constexpr (KM) {
+      u32x4 r;
+      asm volatile("ds_read_b128 %0, %1" : "=v"(r) : "v"((unsigned)(size_t)(__attribute__((address_space(3))) const unsigned char*)p));
+      return __builtin_bit_cast(bf16x8, r);
+    } else {
+      return *(const bf16x8*)p;
+    }
+  };
+  auto frag_wait = [&]() {   // KM: all fragment reads issued so far have landed
+    if constexpr (KM) {
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  };
   bf16x8 fa[2][NBM], fb[2][NBN];
   constexpr int NF = NBM + NBN;          // fragment reads per sub-step
   constexpr int NM = NBM * NBN;          // MFMAs per sub-step
   // fragment f in [0, NF) of sub-step kk: first the NBM row blocks of A, then the NBN of B
   auto load_frag = [&](int slot, int kk, int f) {
     const int o = slot * BUF_BYTES;
-    if (f < NBM) fa[kk][f] = *(const bf16x8*)(Afr + o + koff[kk][f & 1] + f * 2048);
-    else fb[kk][f - NBM] = *(const bf16x8*)(Bfr + o + koff[kk][(f - NBM) & 1] + (f - NBM) * 2048);
+    auto tr_frag = [&](int base, int step) {
+      const u32x2v h0 = read_tr(base), h1 = read_tr(base + step);
+      const u32x4 v = {h0[0], h0[1], h1[0], h1[1]};
+      return __builtin_bit_cast(bf16x8, v);
+    };
+    // KM operand: rows 16 kk + 4 r of the slab lie (16 kk + 4 r) * (T / 8) * 16 bytes further on
+    if (f < NBM) {
+      if constexpr (KMA) fa[kk][f] = tr_frag(o + fra[f] + kk * 16 * (TM / 8) * 16, 4 * (TM / 8) * 16);
+      else fa[kk][f] = plain_frag(Afr + o + koff[kk][f & 1] + f * 2048);
+    } else {
+      if constexpr (KMB) fb[kk][f - NBM] = tr_frag(o + frb[f - NBM] + kk * 16 * (TN / 8) * 16, 4 * (TN / 8) * 16);
+      else fb[kk][f - NBM] = plain_frag(Bfr + o + koff[kk][(f - NBM) & 1] + (f - NBM) * 2048);
+    }
   };
   auto load_frags = [&](int slot, int kk) {
 #pragma unroll
@@ -209,6 +296,7 @@ __global__ __launch_bounds__(NT, wgs_per_cu(TM, TN)) void gemm_bf16_kernel(Bf16M
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
+    if constexpr (KM) __builtin_amdgcn_sched_barrier(0);   // no MFMA may move above the wait for its fragments
   };
 
   // Main loop.  Slab kt+STAGES-1 is requested during the first half of slab kt (its ring slot was
@@ -230,6 +318,7 @@ __global__ __launch_bounds__(NT, wgs_per_cu(TM, TN)) void gemm_bf16_kernel(Bf16M
   for (; kt < KT_main; ++kt) {          // steady state: no conditions inside
     const int nslot = slot == STAGES - 1 ? 0 : slot + 1;
     const int lslot = slot == 0 ? STAGES - 1 : slot - 1;   // slot of slab kt-1 = slot of slab kt+STAGES-1
+    frag_wait();                         // fragments of the first half (read during the half before)
     // Every step issues its MFMA first: the first one of a half waits for the fragments read during
     // the half before (long complete), and a read placed ahead of it would add its own LDS latency
     // to that wait (the counter only tells "all reads done").
@@ -254,6 +343,7 @@ __global__ __launch_bounds__(NT, wgs_per_cu(TM, TN)) void gemm_bf16_kernel(Bf16M
   }
   for (; kt < KT; ++kt) {               // drain: nothing left to request
     const int nslot = slot == STAGES - 1 ? 0 : slot + 1;
+    frag_wait();
     load_frags(slot, 1);
     mfma_block(0);
     if (kt + 1 < KT) wait_slab(kt + 1);
@@ -499,7 +589,7 @@ long long tiles_per_matrix(const Bf16Desc& g) {
   return g.tile_count ? g.tile_count : all;
 }
 
-template <int TM, int TN, int EPI, bool SYM>
+template <int TM, int TN, int EPI, bool SYM, bool KMA = false, bool KMB = false>
 int launch_te(Bf16Multi& mg, hipStream_t s) {
   long long total = 0;
   for (int i = 0; i < mg.ngroups; ++i) {
@@ -509,18 +599,18 @@ int launch_te(Bf16Multi& mg, hipStream_t s) {
   }
   mg.tile_start[mg.ngroups] = (int)total;
   const size_t lds = (size_t)stages_of(TM, TN) * (TM + TN) * 64;   // ring of STAGES x (A slab + B slab)
-  const int rc = allow_dynamic_lds((const void*)gemm_bf16_kernel<TM, TN, EPI, SYM>, (int)lds);
+  const int rc = allow_dynamic_lds((const void*)gemm_bf16_kernel<TM, TN, EPI, SYM, KMA, KMB>, (int)lds);
   if (rc != PRISM_OK) return rc;
-  hipLaunchKernelGGL((gemm_bf16_kernel<TM, TN, EPI, SYM>), dim3((unsigned)total), dim3(NT), lds, s, mg);
+  hipLaunchKernelGGL((gemm_bf16_kernel<TM, TN, EPI, SYM, KMA, KMB>), dim3((unsigned)total), dim3(NT), lds, s, mg);
   return hipGetLastError() == hipSuccess ? PRISM_OK : PRISM_EHIP;
 }
 
 template <int TM, int TN>
 int launch_t(Bf16Multi& mg, hipStream_t s) {
-  const int epi = mg.d[0].epi, sym = mg.d[0].sym;
+  const int epi = mg.d[0].epi, sym = mg.d[0].sym, km = mg.d[0].km;
   for (int i = 0; i < mg.ngroups; ++i) {
     const Bf16Desc& g = mg.d[i];
-    if (g.epi != epi || g.sym != sym) return PRISM_EINVAL;
+    if (g.epi != epi || g.sym != sym || g.km != km) return PRISM_EINVAL;
     if (g.M % TM || g.N % TN || g.K % BK || g.K < BK || g.lda % 8 || g.ldb % 8) return PRISM_EINVAL;
     if ((long long)(g.M / TM) * (g.N / TN) * g.batch <= 0) return PRISM_EINVAL;
     {
@@ -537,11 +627,25 @@ int launch_t(Bf16Multi& mg, hipStream_t s) {
     if (g.epi == BEPI_GRAM && !g.C32 && !g.diag) return PRISM_EINVAL;
     if (g.epi == BEPI_POLYQ && !g.C32 && !g.Cin16) return PRISM_EINVAL;
   }
+  // operand layouts (km: bit 0 = A stored [K][M], bit 1 = B stored [K][N]) per kind of product
   switch (epi) {
-    case BEPI_STORE: return launch_te<TM, TN, BEPI_STORE, false>(mg, s);
-    case BEPI_GRAM: return launch_te<TM, TN, BEPI_GRAM, true>(mg, s);
-    case BEPI_POLYQ: return launch_te<TM, TN, BEPI_POLYQ, true>(mg, s);
-    case BEPI_APPLY: return launch_te<TM, TN, BEPI_APPLY, false>(mg, s);
+    case BEPI_STORE:
+      if (km == 3) return launch_te<TM, TN, BEPI_STORE, false, true, true>(mg, s);
+      if (km == 2) return launch_te<TM, TN, BEPI_STORE, false, false, true>(mg, s);
+      if (km == 0) return launch_te<TM, TN, BEPI_STORE, false>(mg, s);
+      return PRISM_EINVAL;
+    case BEPI_GRAM:
+      if (km == 3) return launch_te<TM, TN, BEPI_GRAM, true, true, true>(mg, s);
+      if (km == 0) return launch_te<TM, TN, BEPI_GRAM, true>(mg, s);
+      return PRISM_EINVAL;
+    case BEPI_POLYQ:
+      if (km == 3) return launch_te<TM, TN, BEPI_POLYQ, true, true, true>(mg, s);
+      if (km == 0) return launch_te<TM, TN, BEPI_POLYQ, true>(mg, s);
+      return PRISM_EINVAL;
+    case BEPI_APPLY:
+      if (km == 2) return launch_te<TM, TN, BEPI_APPLY, false, false, true>(mg, s);
+      if (km == 0) return launch_te<TM, TN, BEPI_APPLY, false>(mg, s);
+      return PRISM_EINVAL;
   }
   return PRISM_EINVAL;
 }

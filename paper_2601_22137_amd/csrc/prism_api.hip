@@ -559,6 +559,7 @@ int run_polar_bf16(Run& r) {
     if (P.d == 2) {   // one launch over the matrices of all groups: R has the same order everywhere
       Bf16Desc q = {};
       q.A = Rb; q.strideA = SS; q.lda = Sp; q.B = Rb; q.strideB = SS; q.ldb = Sp;
+      q.km = 3;   // R is symmetric bit for bit: read as [K][M], whose whole-cache-line loads are the faster ones
       q.M = Sp; q.N = Sp; q.K = Sp; q.batch = P.batch; q.epi = BEPI_POLYQ; q.sym = sym;
       q.C32 = lean ? nullptr : R; q.strideC32 = SS; q.ldc32 = Sp; q.Cb = Qb; q.strideCb = SS; q.ldcb = Sp; q.c1 = 0.5f;
       q.Cin16 = lean ? Rb : nullptr;
@@ -575,6 +576,7 @@ int run_polar_bf16(Run& r) {
       Bf16Desc& a = ad[i];
       a = Bf16Desc{};
       a.A = x.Xhi[cur]; a.strideA = LS; a.lda = Sp; a.B = Bop + x.boff * SS; a.strideB = SS; a.ldb = Sp;
+      a.km = 2;   // Q (d = 1: R) is symmetric: read as [K][N]
       a.M = x.Lp; a.N = Sp; a.K = Sp; a.batch = x.batch; a.epi = BEPI_APPLY;
       a.Cb = x.Xhi[cur ^ 1]; a.Cb2 = x.Xlo[cur ^ 1]; a.strideCb = LS; a.ldcb = Sp;
       a.Ct = x.Xg[cur ^ 1]; a.strideCt = LS; a.ldct = x.Lp;
@@ -1421,6 +1423,13 @@ int prism_gemm_bf16_nt(const uint16_t* A, const uint16_t* B, float* C, int batch
   g.B = B; g.strideB = (long long)N * K; g.ldb = K;
   g.M = M; g.N = N; g.K = K; g.batch = batch; g.epi = BEPI_STORE;
   g.C32 = C; g.strideC32 = (long long)M * N; g.ldc32 = N;
+  if (tile >= 20000) {          // B stored [K][N]
+    tile -= 20000;
+    g.km = 2; g.ldb = N;
+  } else if (tile >= 10000) {   // A stored [K][M] and B stored [K][N]
+    tile -= 10000;
+    g.km = 3; g.lda = M; g.ldb = N;
+  }
   if (tile == 2561) return launch_gemm_bf16(g, 256, 128, (hipStream_t)stream);
   return launch_gemm_bf16(g, tile, tile, (hipStream_t)stream);
 }
