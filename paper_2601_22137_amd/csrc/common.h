@@ -72,7 +72,7 @@ enum Bf16Epi {
   BEPI_STORE = 0,   // C(fp32) = acc
   BEPI_GRAM = 1,    // R = I - acc: R32 (fp32) and Rb (bf16), rho partial
   BEPI_POLYQ = 2,   // Q(bf16) = c1 * R32 + alpha * acc
-  BEPI_APPLY = 3    // X' = Xhi + (1 + c) Xlo + acc -> Xa_hi', Xa_lo' ([L][S]) and Xg_hi' ([S][L]); acc = Xhi B
+  BEPI_APPLY = 3    // X' = Xhi + (1 + c) Xlo + acc -> Xa_hi', Xa_lo' ([L][S]); acc = Xhi B
 };
 
 struct Bf16Desc {
@@ -90,7 +90,6 @@ struct Bf16Desc {
   const uint16_t* Cin16;                             // POLYQ without C32: R in bf16 (layout of Cb)
   uint16_t* Cb; long long strideCb; int ldcb;        // GRAM: Rb out; POLYQ: Q out; APPLY: Xa_hi' out
   uint16_t* Cb2;                                     // APPLY: Xa_lo' out (null in plain mode)
-  uint16_t* Ct; long long strideCt; int ldct;        // APPLY: Xg_hi' out, transposed [N][M]
   const uint16_t* Xhi; const uint16_t* Xlo;          // APPLY: current iterate (same layout as Cb)
   float c1;
   int coef_is_alpha;                                 // APPLY: multiply acc by ctrl.alpha (d = 1)
@@ -191,7 +190,7 @@ struct PrepArgs {
   Ctrl* ctrl; prism_info* info;
   // outputs (which are used depends on fn/dt)
   float* X32; float* Y32; double* M64; float* R32;   // fp32 paths (inverse: Y32 = A / ||A||_F)
-  uint16_t* Xa_hi; uint16_t* Xa_lo; uint16_t* Xg;    // bf16 polar
+  uint16_t* Xa_hi; uint16_t* Xa_lo;                  // bf16 polar: iterate [Lp][Sp], high and low halves
   float* rho_part; int tile;                // inverse root: residual of M_0
 };
 void launch_sumsq(const PrepArgs& a, hipStream_t s);
@@ -202,7 +201,7 @@ struct FinalArgs {
   void* dst; void* dst2;                    // caller's arrays (dst2 = inverse square root)
   const Ctrl* ctrl;
   const float* X32[2]; const float* Y32[2];
-  const uint16_t* Xa_hi[2]; const uint16_t* Xa_lo[2]; const uint16_t* Xg[2];
+  const uint16_t* Xa_hi[2]; const uint16_t* Xa_lo[2];
 };
 void launch_finalize(const FinalArgs& a, hipStream_t s);
 

@@ -470,16 +470,13 @@ __global__ __launch_bounds__(NT, wgs_per_cu(TM, TN)) void gemm_bf16_kernel(Bf16M
     }
     if (mirror) part *= 2.0f;
   } else if constexpr (EPI == BEPI_APPLY) {
-    // The new iterate goes out in two layouts ([L][S] for the next update, [S][L] for the next
-    // Gram product).  Each wave passes its tile through its own LDS strip of 32 rows so that
-    // every global access is a 16-byte vector on a contiguous run: row-wise for X (read) and
-    // Xa' (write), column-wise for the transposed Xg'.  The LDS ring is free here: no wave reads
-    // fragments after the last barrier of the main loop.
+    // Each wave passes its tile through its own LDS strip of 32 rows so that every global access
+    // is a 16-byte vector on a contiguous run of a row of X (read) and X' (write).  The LDS ring is
+    // free here: no wave reads fragments after the last barrier of the main loop.
     constexpr int SW = WTN + 4;                      // strip row stride in floats (16-byte aligned)
     float* strip = (float*)smem + wave * 32 * SW;
     constexpr int LPR = WTN / 8, RPI = 64 / LPR;     // lanes per row, rows per instruction
     const int rr = lane / LPR, cc = (lane % LPR) * 8;
-    const int cq = lane >> 2, rq = lane & 3;
     const long long base = (long long)b * g.strideCb;
     // The old iterate of row block i + 1 is requested while block i is worked on (and that of
     // block 0 before the accumulators go to LDS): its memory latency is paid once per tile
@@ -513,7 +510,7 @@ __global__ __launch_bounds__(NT, wgs_per_cu(TM, TN)) void gemm_bf16_kernel(Bf16M
 #pragma unroll
         for (int r = 0; r < 16; ++r)
           strip[((r >> 2) * 8 + rbase + (r & 3)) * SW + j * 32 + lr] = acc[i][j][r];
-      // row-wise: x' = x_hi + lo_gain * x_lo + coef * acc, split again, keep the high half for the transpose
+      // row-wise: x' = x_hi + lo_gain * x_lo + coef * acc, split again
 #pragma unroll
       for (int it = 0; it < ITS; ++it) {
         const int row = it * RPI + rr;
@@ -523,7 +520,6 @@ __global__ __launch_bounds__(NT, wgs_per_cu(TM, TN)) void gemm_bf16_kernel(Bf16M
         const u32x4 hi = xh[i & 1][it];
         const u32x4 lo = xl[i & 1][it];
         u32x4 nh, nl;
-        f32x4 k0, k1;
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           // two bf16 per 32-bit word: even element in the low half
@@ -532,26 +528,9 @@ __global__ __launch_bounds__(NT, wgs_per_cu(TM, TN)) void gemm_bf16_kernel(Bf16M
           const unsigned h0 = f2bf(x0), h1 = f2bf(x1);
           nh[e] = h0 | (h1 << 16);
           nl[e] = (unsigned)f2bf(x0 - bf2f((unsigned short)h0)) | ((unsigned)f2bf(x1 - bf2f((unsigned short)h1)) << 16);
-          if (e < 2) { k0[2 * e] = bf2f((unsigned short)h0); k0[2 * e + 1] = bf2f((unsigned short)h1); }
-          else { k1[2 * e - 4] = bf2f((unsigned short)h0); k1[2 * e - 3] = bf2f((unsigned short)h1); }
         }
         *(u32x4*)(g.Cb + o) = nh;
         if (g.Cb2) *(u32x4*)(g.Cb2 + o) = nl;
-        *(f32x4*)sp = k0;
-        *(f32x4*)(sp + 4) = k1;
-      }
-      // column-wise: 8 consecutive rows of one column = 16 bytes of a row of Xg'
-#pragma unroll
-      for (int it = 0; it < WTN / 16; ++it) {
-        const int col = it * 16 + cq;
-        u32x4 tv;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const unsigned h0 = f2bf(strip[(rq * 8 + 2 * e) * SW + col]);
-          const unsigned h1 = f2bf(strip[(rq * 8 + 2 * e + 1) * SW + col]);
-          tv[e] = h0 | (h1 << 16);
-        }
-        *(u32x4*)(g.Ct + (long long)b * g.strideCt + (long long)(n0 + wn0 + col) * g.ldct + m0 + wm0 + i * 32 + rq * 8) = tv;
       }
     }
   } else {

@@ -105,7 +105,6 @@ __global__ __launch_bounds__(NT) void prepare_kernel(PrepArgs a) {
     for (int i = threadIdx.x; i < PRISM_MAX_ITERS; i += NT) a.info[b].alpha[i] = 0.0f;
   }
 
-  __shared__ float tile_t[64][65];
   float rho = 0.0f;
   const long long mat = (long long)a.m * a.n;
   for (int e = threadIdx.x; e < 64 * 64; e += NT) {
@@ -135,7 +134,6 @@ __global__ __launch_bounds__(NT) void prepare_kernel(PrepArgs a) {
         const unsigned short hi = f2bf((float)v);
         a.Xa_hi[o] = hi;
         if (a.Xa_lo) a.Xa_lo[o] = f2bf((float)v - bf2f(hi));
-        tile_t[lc][lr] = bf2f(hi);
       } else {
         a.X32[o] = (float)v;
       }
@@ -152,15 +150,6 @@ __global__ __launch_bounds__(NT) void prepare_kernel(PrepArgs a) {
       rho += (float)(res * res);
     }
   }
-  if (a.fn == PRISM_FN_POLAR && a.dt == PRISM_BF16) {
-    __syncthreads();
-    // transposed copy Xg[Sp][Lp] (high part), written with the long side contiguous
-    for (int e = threadIdx.x; e < 64 * 64; e += NT) {
-      const int lc = e >> 6, lr = e & 63;
-      const int r = tr * 64 + lr, c = tc * 64 + lc;
-      a.Xg[(long long)b * a.Lp * a.Sp + (long long)c * a.Lp + r] = f2bf(tile_t[lc][lr]);
-    }
-  }
   if (a.fn == PRISM_FN_INV_ROOT || a.fn == PRISM_FN_SQRT_NEWTON) {
     __shared__ float red[4];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -174,9 +163,9 @@ __global__ __launch_bounds__(NT) void prepare_kernel(PrepArgs a) {
 }
 
 // bf16 polar, both sides multiples of 8: one workgroup per 64 x 64 tile of the CALLER's matrix.
-// The tile is read with 16-byte loads along the caller's rows, scaled, split into high and low
-// halves and written to the internal array of the same orientation directly and to the other one
-// through an LDS transpose, everything as 16-byte vectors.
+// The tile is read with 16-byte loads along the caller's rows, scaled and split into high and low
+// halves; a tall or square matrix goes straight into the internal [Lp][Sp] iterate, a wide one
+// (the iterate is its transpose) through an LDS transpose, everything as 16-byte vectors.
 __global__ __launch_bounds__(NT) void prepare_bf16_kernel(PrepArgs a) {
   const int b = blockIdx.y;
   const int tiles_c = (a.transpose ? a.Lp : a.Sp) / 64;             // tiles over the padded, caller-oriented matrix
@@ -203,10 +192,6 @@ __global__ __launch_bounds__(NT) void prepare_bf16_kernel(PrepArgs a) {
     for (int i = threadIdx.x; i <= PRISM_MAX_ITERS; i += NT) a.info[b].residual[i] = -1.0f;
     for (int i = threadIdx.x; i < PRISM_MAX_ITERS; i += NT) a.info[b].alpha[i] = 0.0f;
   }
-  // "same" = internal array with the caller's orientation, "other" = its transpose
-  //   m >= n: same = Xa [Lp][Sp] (hi, lo), other = Xg [Sp][Lp] (hi)
-  //   m <  n: same = Xg [Sp][Lp] (hi),     other = Xa [Lp][Sp] (hi, lo)
-  const int ld_same = a.transpose ? a.Lp : a.Sp, ld_other = a.transpose ? a.Sp : a.Lp;
   const long long mat_int = (long long)a.Lp * a.Sp;
   __shared__ float tile_hi[64][65], tile_lo[64][65];
   const unsigned short* src = (const unsigned short*)a.src + (long long)b * a.m * a.n;
@@ -225,19 +210,18 @@ __global__ __launch_bounds__(NT) void prepare_bf16_kernel(PrepArgs a) {
       const unsigned short l0 = f2bf(x0 - bf2f(h0)), l1 = f2bf(x1 - bf2f(h1));
       hi[e] = (unsigned)h0 | ((unsigned)h1 << 16);
       lo[e] = (unsigned)l0 | ((unsigned)l1 << 16);
-      tile_hi[lc + 2 * e][lr] = bf2f(h0); tile_hi[lc + 2 * e + 1][lr] = bf2f(h1);
-      tile_lo[lc + 2 * e][lr] = bf2f(l0); tile_lo[lc + 2 * e + 1][lr] = bf2f(l1);
-    }
-    {  // rows / columns beyond the caller's matrix but inside the padded arrays are written as zeros
-      const long long o = (long long)b * mat_int + (long long)r * ld_same + c;
       if (a.transpose) {
-        *(u32x4*)(a.Xg + o) = hi;
-      } else {
-        *(u32x4*)(a.Xa_hi + o) = hi;
-        if (a.Xa_lo) *(u32x4*)(a.Xa_lo + o) = lo;
+        tile_hi[lc + 2 * e][lr] = bf2f(h0); tile_hi[lc + 2 * e + 1][lr] = bf2f(h1);
+        tile_lo[lc + 2 * e][lr] = bf2f(l0); tile_lo[lc + 2 * e + 1][lr] = bf2f(l1);
       }
     }
+    if (!a.transpose) {  // rows / columns beyond the caller's matrix but inside the padded array are written as zeros
+      const long long o = (long long)b * mat_int + (long long)r * a.Sp + c;
+      *(u32x4*)(a.Xa_hi + o) = hi;
+      if (a.Xa_lo) *(u32x4*)(a.Xa_lo + o) = lo;
+    }
   }
+  if (!a.transpose) return;
   __syncthreads();
 #pragma unroll
   for (int it = 0; it < 2; ++it) {
@@ -250,35 +234,62 @@ __global__ __launch_bounds__(NT) void prepare_bf16_kernel(PrepArgs a) {
       hi[e] = (unsigned)f2bf(tile_hi[lc][lr + 2 * e]) | ((unsigned)f2bf(tile_hi[lc][lr + 2 * e + 1]) << 16);
       lo[e] = (unsigned)f2bf(tile_lo[lc][lr + 2 * e]) | ((unsigned)f2bf(tile_lo[lc][lr + 2 * e + 1]) << 16);
     }
-    {
-      const long long o = (long long)b * mat_int + (long long)c * ld_other + r;
-      if (a.transpose) {
-        *(u32x4*)(a.Xa_hi + o) = hi;
-        if (a.Xa_lo) *(u32x4*)(a.Xa_lo + o) = lo;
-      } else {
-        *(u32x4*)(a.Xg + o) = hi;
-      }
-    }
+    const long long o = (long long)b * mat_int + (long long)c * a.Sp + r;   // internal row = caller's column
+    *(u32x4*)(a.Xa_hi + o) = hi;
+    if (a.Xa_lo) *(u32x4*)(a.Xa_lo + o) = lo;
   }
 }
 
-// bf16 polar, both sides multiples of 8: the result is the high half of the iterate, copied with
-// 16-byte vectors from the internal array that has the caller's orientation.
+// bf16 polar, both sides multiples of 8: the result is the high half of the iterate.  One workgroup
+// per 64 x 64 tile of the caller's matrix: a tall or square one is copied with 16-byte vectors, a
+// wide one (the iterate is its transpose) goes through an LDS transpose.
 __global__ __launch_bounds__(NT) void finalize_bf16_kernel(FinalArgs a) {
   const int b = blockIdx.y;
   const Ctrl c = a.ctrl[b];
   if (c.status == PRISM_INFO_NONFINITE || c.status == PRISM_INFO_ZERO) return;
   const int par = c.iters & 1;
-  const int vec_per_row = a.n / 8;
-  const long long nvec = (long long)a.m * vec_per_row;
-  const long long i = (long long)blockIdx.x * NT + threadIdx.x;
-  if (i >= nvec) return;
-  const int r = (int)(i / vec_per_row), col = (int)(i % vec_per_row) * 8;
-  const unsigned short* srcm = a.transpose ? a.Xg[par] : a.Xa_hi[par];
-  if (srcm == (const unsigned short*)a.dst) return;   // the caller's array was that iterate buffer: already in place
-  const int ld = a.transpose ? a.Lp : a.Sp;
-  const u32x4 v = *(const u32x4*)(srcm + (long long)b * a.Lp * a.Sp + (long long)r * ld + col);
-  *(u32x4*)((unsigned short*)a.dst + (long long)b * a.m * a.n + (long long)r * a.n + col) = v;
+  const unsigned short* srcm = a.Xa_hi[par] + (long long)b * a.Lp * a.Sp;
+  unsigned short* dst = (unsigned short*)a.dst + (long long)b * a.m * a.n;
+  if (!a.transpose && a.Xa_hi[par] == (const unsigned short*)a.dst) return;   // the caller's array was that iterate buffer: in place
+  const int tiles_c = (a.n + 63) / 64;
+  const int tr = blockIdx.x / tiles_c, tc = blockIdx.x % tiles_c;
+  if (!a.transpose) {
+#pragma unroll
+    for (int it = 0; it < 2; ++it) {
+      const int v = threadIdx.x + it * NT;
+      const int r = tr * 64 + (v >> 3), col = tc * 64 + (v & 7) * 8;
+      if (r < a.m && col < a.n) *(u32x4*)(dst + (long long)r * a.n + col) = *(const u32x4*)(srcm + (long long)r * a.Sp + col);
+    }
+    return;
+  }
+  // caller's tile (rows tr, columns tc) = transpose of the internal tile (rows tc, columns tr)
+  __shared__ unsigned short tile[64][72];
+#pragma unroll
+  for (int it = 0; it < 2; ++it) {
+    const int v = threadIdx.x + it * NT;
+    const int lr = v >> 3, lc = (v & 7) * 8;                 // internal row (caller's column), 8 internal columns
+    const int ri = tc * 64 + lr, ci = tr * 64 + lc;
+    u32x4 w = {0u, 0u, 0u, 0u};
+    if (ri < a.Lp && ci < a.Sp) w = *(const u32x4*)(srcm + (long long)ri * a.Sp + ci);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      tile[lc + 2 * e][lr] = (unsigned short)(w[e] & 0xFFFFu);
+      tile[lc + 2 * e + 1][lr] = (unsigned short)(w[e] >> 16);
+    }
+  }
+  __syncthreads();
+#pragma unroll
+  for (int it = 0; it < 2; ++it) {
+    const int v = threadIdx.x + it * NT;
+    const int lr = v >> 3, lc = (v & 7) * 8;                 // caller's row within the tile, 8 caller's columns
+    const int r = tr * 64 + lr, col = tc * 64 + lc;
+    if (r < a.m && col < a.n) {
+      u32x4 w;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) w[e] = (unsigned)tile[lr][lc + 2 * e] | ((unsigned)tile[lr][lc + 2 * e + 1] << 16);
+      *(u32x4*)(dst + (long long)r * a.n + col) = w;
+    }
+  }
 }
 
 // One thread per element of the caller's array.
@@ -427,8 +438,8 @@ void launch_prepare(const PrepArgs& a, hipStream_t s) {
 
 void launch_finalize(const FinalArgs& a, hipStream_t s) {
   if (bf16_vector_path(a.fn, a.dt, a.m, a.n, a.dst)) {
-    const long long nvec = (long long)a.m * (a.n / 8);
-    hipLaunchKernelGGL(finalize_bf16_kernel, dim3((unsigned)((nvec + NT - 1) / NT), a.batch), dim3(NT), 0, s, a);
+    const int tiles = ((a.m + 63) / 64) * ((a.n + 63) / 64);
+    hipLaunchKernelGGL(finalize_bf16_kernel, dim3((unsigned)tiles, a.batch), dim3(NT), 0, s, a);
     return;
   }
   const long long mat = (long long)a.m * a.n;

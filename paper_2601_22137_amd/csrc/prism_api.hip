@@ -86,7 +86,7 @@ struct Plan {
   int ngroups;     // workgroups per matrix of the moments kernel
   bool shared_gpu; // PRISM_FLAG_SHARED_GPU
   size_t o_x[2], o_y[2], o_r, o_q, o_t[3];        // fp32 paths (o_y doubles as M64 for inverse root)
-  size_t o_xhi[2], o_xlo[2], o_xg[2], o_rb, o_qb; // bf16 polar
+  size_t o_xhi[2], o_xlo[2], o_rb, o_qb;          // bf16 polar
   int ksplit;      // polar: parts of the K loop of X^T X (0 = one pass); partial products at o_gpart
   size_t o_gpart;
   size_t total;
@@ -154,7 +154,6 @@ int make_plan(Plan& P, int fn, int batch, int m, int n, int dt, int degree, int 
     for (int i = 0; i < 2 && !shared_shapes; ++i) {
       P.o_xhi[i] = take(B * LS * 2);
       P.o_xlo[i] = P.split ? take(B * LS * 2) : 0;
-      P.o_xg[i] = take(B * LS * 2);
     }
     P.o_r = take(B * SS * 4);
     P.o_rb = take(B * SS * 2);
@@ -262,14 +261,14 @@ struct Run {
   // groups share the short side, so R, Q, the chain vectors and the control blocks of all their
   // matrices form one batch (matrices [boff, boff + batch) belong to the group); only the Gram
   // product and the update see the long side, and take all groups in one launch each.
-  // Plain iterate, no padding: the caller's array serves as the odd one of the two iterate buffers
-  // that has its orientation (the input is consumed by the prepare step before the first update
+  // Plain iterate, no padding, tall or square input: the caller's array serves as the odd one of
+  // the two iterate buffers (the input is consumed by the prepare step before the first update
   // writes there), so that after an odd number of updates the result is in place.
   struct XGroup {
     int batch, boff, m, n, L, Lp, transpose;
     void* x;                                   // caller's array
-    uint16_t* Xhi[2]; uint16_t* Xlo[2]; uint16_t* Xg[2];
-    bool aliased;                              // buffer 1 of the caller's orientation is the caller's array
+    uint16_t* Xhi[2]; uint16_t* Xlo[2];        // iterate [Lp][Sp], double buffered
+    bool aliased;                              // buffer 1 is the caller's array
   };
   std::vector<XGroup> xg;
   int chain_sel_batch = 0;                     // batch size that picks the chain kernels (0: the whole batch)
@@ -516,7 +515,9 @@ int run_polar_bf16(Run& r) {
       float* gpart = r.at<float>(P.o_gpart);
       for (int b = 0; b < P.batch; ++b) {   // the parts of one matrix are the batch of a plain product
         Bf16Desc sp = {};
-        sp.A = x.Xg[cur] + (long long)b * LS; sp.B = sp.A; sp.strideA = Kp; sp.strideB = Kp; sp.lda = x.Lp; sp.ldb = x.Lp;
+        // part p = rows [p Kp, (p + 1) Kp) of the [Lp][Sp] iterate, read as [K][M]
+        sp.A = x.Xhi[cur] + (long long)b * LS; sp.B = sp.A; sp.strideA = (long long)Kp * Sp; sp.strideB = sp.strideA;
+        sp.lda = Sp; sp.ldb = Sp; sp.km = 3;
         sp.M = Sp; sp.N = Sp; sp.K = Kp; sp.batch = P.ksplit; sp.epi = BEPI_STORE;
         sp.C32 = gpart + (long long)b * P.ksplit * SS; sp.strideC32 = SS; sp.ldc32 = Sp;
         sp.ctrl = r.ctrl + b; sp.ctrl_fixed = 1;
@@ -535,7 +536,8 @@ int run_polar_bf16(Run& r) {
         Bf16Desc& g = gd[i];
         g = Bf16Desc{};
         g.sym = sym;
-        g.A = x.Xg[cur]; g.strideA = LS; g.lda = x.Lp; g.B = x.Xg[cur]; g.strideB = LS; g.ldb = x.Lp;
+        // X^T X straight from the [Lp][Sp] iterate: both operands stored [K][M]
+        g.A = x.Xhi[cur]; g.strideA = LS; g.lda = Sp; g.B = x.Xhi[cur]; g.strideB = LS; g.ldb = Sp; g.km = 3;
         g.M = Sp; g.N = Sp; g.K = x.Lp; g.batch = x.batch; g.epi = BEPI_GRAM; g.n_true = P.S;
         g.C32 = lean ? nullptr : R + x.boff * SS; g.strideC32 = SS; g.ldc32 = Sp;
         // with the bf16 chain only the R^2 epilogue and the chain's diagonal read the fp32 matrix: both stay
@@ -579,7 +581,6 @@ int run_polar_bf16(Run& r) {
       a.km = 2;   // Q (d = 1: R) is symmetric: read as [K][N]
       a.M = x.Lp; a.N = Sp; a.K = Sp; a.batch = x.batch; a.epi = BEPI_APPLY;
       a.Cb = x.Xhi[cur ^ 1]; a.Cb2 = x.Xlo[cur ^ 1]; a.strideCb = LS; a.ldcb = Sp;
-      a.Ct = x.Xg[cur ^ 1]; a.strideCt = LS; a.ldct = x.Lp;
       a.Xhi = x.Xhi[cur]; a.Xlo = x.Xlo[cur]; a.coef_is_alpha = P.d == 1; a.ctrl = r.ctrl + x.boff;
     }
     { ProfScope ps(PK_BF16_APPLY, r.s); CHECK_LAUNCH(launch_gemm_bf16_multi(ad, ng, Ta.m, Ta.n, r.s)); }
@@ -806,14 +807,14 @@ void alias_output(const Plan& P, Run::XGroup& x) {
   static const int no_alias = ab_switch("PRISM_BF16_NO_OUTPUT_ALIAS");
   const int S = x.m < x.n ? x.m : x.n;
   x.aliased = false;
-  if (P.split || P.Sp != S || x.Lp != x.L || no_alias || ((uintptr_t)x.x & 255)) return;
-  if (x.transpose) x.Xg[1] = (uint16_t*)x.x; else x.Xhi[1] = (uint16_t*)x.x;
+  if (P.split || x.transpose || P.Sp != S || x.Lp != x.L || no_alias || ((uintptr_t)x.x & 255)) return;
+  x.Xhi[1] = (uint16_t*)x.x;
   x.aliased = true;
 }
 // iterate buffers of one shape group in the arguments of the pre-scaling and copy-out kernels
 void bf16_prep_final(const Plan& P, const Run::XGroup& x, PrepArgs& pa, FinalArgs& fa) {
-  pa.Xa_hi = x.Xhi[0]; pa.Xa_lo = x.Xlo[0]; pa.Xg = x.Xg[0];
-  for (int i = 0; i < 2; ++i) { fa.Xa_hi[i] = x.Xhi[i]; fa.Xa_lo[i] = x.Xlo[i]; fa.Xg[i] = x.Xg[i]; }
+  pa.Xa_hi = x.Xhi[0]; pa.Xa_lo = x.Xlo[0];
+  for (int i = 0; i < 2; ++i) { fa.Xa_hi[i] = x.Xhi[i]; fa.Xa_lo[i] = x.Xlo[i]; }
   (void)P;
 }
 
@@ -862,7 +863,6 @@ int run(int fn, void* a, void* inv_out, int root_p, int batch, int m, int n, int
     for (int i = 0; i < 2; ++i) {
       x.Xhi[i] = r.at<uint16_t>(P.o_xhi[i]);
       x.Xlo[i] = P.split ? r.at<uint16_t>(P.o_xlo[i]) : nullptr;
-      x.Xg[i] = r.at<uint16_t>(P.o_xg[i]);
     }
     alias_output(P, x);
     r.xg.push_back(x);
@@ -936,13 +936,12 @@ int run_polar_bf16_shapes(const prism_group* groups, int ngroups, int degree, in
   // iterate buffers per group behind the shared part
   size_t off_bytes = P.total;
   auto take = [&](size_t bytes) { size_t o = off_bytes; off_bytes = align256(off_bytes + bytes); return o; };
-  size_t o_xhi[BF16_MAX_GROUPS][2], o_xlo[BF16_MAX_GROUPS][2], o_xg[BF16_MAX_GROUPS][2];
+  size_t o_xhi[BF16_MAX_GROUPS][2], o_xlo[BF16_MAX_GROUPS][2];
   for (int g = 0; g < ngroups; ++g) {
     const size_t bytes = (size_t)groups[g].batch * Pg[g].Lp * Pg[g].Sp * 2;
     for (int i = 0; i < 2; ++i) {
       o_xhi[g][i] = take(bytes);
       o_xlo[g][i] = P.split ? take(bytes) : 0;
-      o_xg[g][i] = take(bytes);
     }
   }
   P.total = off_bytes;
@@ -967,7 +966,6 @@ int run_polar_bf16_shapes(const prism_group* groups, int ngroups, int degree, in
     for (int i = 0; i < 2; ++i) {
       x.Xhi[i] = r.at<uint16_t>(o_xhi[g][i]);
       x.Xlo[i] = P.split ? r.at<uint16_t>(o_xlo[g][i]) : nullptr;
-      x.Xg[i] = r.at<uint16_t>(o_xg[g][i]);
     }
     alias_output(P, x);
     r.xg.push_back(x);
