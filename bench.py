@@ -198,8 +198,9 @@ def oracle_call(name, host_matrix, W, O, seed):
     return O.polar(host_matrix, 5, 30, 8, seed, 1e-6)
 
 
-KERNEL_OF_KIND = {"bf16_gram": r"gemm_bf16\w*<\d+, 1,", "bf16_polyq": r"gemm_bf16\w*<\d+, 2,",
-                  "bf16_apply": r"gemm_bf16\w*<\d+, 3,"}
+# kernel name as rocprofv3 prints it: gemm_bf16_kernel<tile rows, tile columns, epilogue, ...>
+KERNEL_OF_KIND = {"bf16_gram": r"gemm_bf16\w*<\d+, \d+, 1,", "bf16_polyq": r"gemm_bf16\w*<\d+, \d+, 2,",
+                  "bf16_apply": r"gemm_bf16\w*<\d+, \d+, 3,"}
 
 
 def recorded_traffic(workload, kind):

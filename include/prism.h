@@ -293,9 +293,15 @@ int prism_chain_product(const float* R, const float* V, float* out, int batch, i
 /* The same product as the bf16 polar path takes it: the off-diagonal entries of R are read from
  * Rb, its copy in bf16 bit patterns (same shape), the diagonal from R itself:
  * out = (Rb + diag(R - Rb)) * V.  ld = 16 or 32, n a multiple of 64 (of 128 when (n / 64) * batch >= 128);
- * other shapes return PRISM_EUNSUPPORTED (the library then keeps to the fp32 matrix). */
-int prism_chain_product_bf16(const uint16_t* Rb, const float* R, const float* V, float* out, int batch,
-                             int n, int ld, void* stream);
+ * other shapes return PRISM_EUNSUPPORTED (the library then keeps to the fp32 matrix).
+ * Launches of (n / 64) * batch >= 128 workgroups read V as three bf16 planes (the exact 8 + 8 + 8 bit
+ * split of every fp32 entry, laid out [matrix][k / 128][plane][column][u ^ (column % 16)][8] with
+ * u = (k % 128) / 8, the image of the kernel's LDS stage) and write their
+ * result in that form too, for the next product of the chain: `planes` is device scratch of
+ * 2 * batch * n * ld * 3 entries; on return its first half holds the planes of V, the second half
+ * those of out.  It may be null for smaller launches, which do not use it. */
+int prism_chain_product_bf16(const uint16_t* Rb, const float* R, const float* V, float* out,
+                             uint16_t* planes, int batch, int n, int ld, void* stream);
 
 /* Inverse of symmetric positive definite matrices by block Gauss-Jordan elimination without
  * pivoting (the N_k = M_k^{-1} step of DB Newton, App. A.2): out[batch][n][n] = a^{-1}, fp32
@@ -307,9 +313,11 @@ int prism_spd_inverse(const float* a, float* out, int batch, int n, void* stream
  *                    caller asserts A B is symmetric (M = N, tile-sized); only the tiles on and
  *                    above the diagonal are computed and the rest is their mirror image.
  *   prism_gemm_f64a: A fp32 (promoted), B and C fp64, A stored [M][K].
- *   prism_gemm_bf16_nt: A [M][K], B [N][K] bf16 bit patterns, C fp32 = A B^T.
- * M, N must be multiples of 128 (bf16: of `tile`, 128 or 256, or M of 256 and N of 128 for
- * tile = 2561, the 256 x 128 shape; fp32 skinny N = 16, 32, 64 also allowed) and K of 64. */
+ *   prism_gemm_bf16_nt: A [M][K], B [N][K] bf16 bit patterns, C fp32 = A B^T.  `tile` = 128, 256
+ *                    (square tiles) or 2561 (256 x 128); + 20000: B is stored [K][N] (row length N);
+ *                    + 10000: A is stored [K][M] and B [K][N] (row lengths M and N).
+ * M, N must be multiples of 128 (bf16: of the tile's sides; fp32 skinny N = 16, 32, 64 also
+ * allowed) and K of 64. */
 int prism_gemm_f32(const float* A, const float* B, float* C, int batch, int M, int N, int K,
                    int a_km, void* stream);
 int prism_gemm_f64a(const float* A, const double* B, double* C, int batch, int M, int N, int K,

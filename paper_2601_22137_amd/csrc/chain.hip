@@ -202,81 +202,90 @@ __global__ __launch_bounds__(NT, 2) void chain_kernel(const float* __restrict__ 
 
 // Large matrices, R from its bf16 copy, on the bf16 matrix cores (v_mfma_f32_16x16x32_bf16): with
 // fp32 MFMAs the kernel above is bound by them once R shrinks to two bytes per entry.  V keeps its
-// 24 significant bits: every fp32 entry is cut into three bf16 pieces (8 bits each, exact), staged
-// in LDS as three planes Vt[plane][column][k], and R is multiplied by each plane; the partial
-// products of two bf16 numbers are exact in fp32, so only the accumulation rounds.
-//   A operand: lane (i = l % 16, g = l / 16) holds R[row i][k0 + 32 s + 8 g .. + 7]: its 16-byte load;
-//   B operand: lane (j = l % 16, g) holds the same eight k of column j: one 16-byte LDS read.
-//   A row of Vt is 128 k = 256 bytes plus 16 of padding (68 dwords: the 16 columns of a read hit
-//   all 64 banks once).
+// 24 significant bits: every fp32 entry is cut into three bf16 pieces (8 bits each, exact) and R is
+// multiplied by each piece; the partial products of two bf16 numbers are exact in fp32, so only the
+// accumulation rounds.
+//
+// The pieces are not cut here (every workgroup would cut all of V again).  Whoever produces a V (this
+// kernel for V_1 .. V_{nv-1}, split_planes_kernel for the sketches) also writes it as three bf16
+// planes, chunk by chunk of 128 k, as the image of the LDS stage the consumer wants:
+//     P[matrix][c = k / 128][plane][column][unit u ^ (column % 16)][8 k],   u = (k % 128) / 8
+// A stage is 3 * LD rows of 256 bytes; the workgroup moves it from global memory straight into LDS
+// (global_load_lds_dwordx4, 1 KiB per wave instruction, no registers, no arithmetic).
+//   A operand: lane (i = l % 16, g = l / 16) holds R[row i][128 c + 32 s + 8 g .. + 7]: its 16-byte load;
+//   B operand: lane (j = l % 16, g) reads unit 4 s + g of column 16 jb + j: with the unit index xor-ed
+//   by the column the 16 lanes of a group hit 16 different units of their (bank-aligned) rows.
+// R goes straight into registers.  Rows of R and stages of V run STAGES - 1 chunks ahead.
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef const void __attribute__((address_space(1)))* gptr_t;
+typedef void __attribute__((address_space(3)))* lptr_t;
+
+// three truncations: each piece takes the next 8 significant bits, the last one is exact
+__device__ inline void split3(float v, unsigned& h, unsigned& m, unsigned& l) {
+  h = __float_as_uint(v) & 0xFFFF0000u;
+  const float r1 = v - __uint_as_float(h);
+  m = __float_as_uint(r1) & 0xFFFF0000u;
+  const float r2 = r1 - __uint_as_float(m);
+  l = __float_as_uint(r2) & 0xFFFF0000u;
+}
+
+constexpr int PCH = 128;   // k per chunk of the plane layout
+// entry offset of (k, column) in plane 0 of its matrix; planes 1 and 2 lie LD * 128 and 2 * LD * 128 further on
+template <int LD> __device__ inline long long plane_offset(int k, int col) {
+  const int c = k / PCH, u = (k % PCH) / 8;
+  return ((long long)(c * 3) * LD + col) * PCH + ((u ^ (col & 15)) * 8) + (k & 7);
+}
+
+// s_waitcnt vmcnt(N) with the other counters left alone (gfx9 encoding)
+template <int N> __device__ inline void wait_vmcnt() {
+  __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | 0x0F70);
+}
 
 template <int LD>
-__global__ __launch_bounds__(NT, 2) void chain_bf16_kernel(const unsigned short* __restrict__ R, long long strideR, int ldr,
-                                                        const float* __restrict__ R32, long long strideR32, int ldr32,
-                                                        const float* __restrict__ Vin, long long strideVin,
-                                                        float* __restrict__ Vout, long long strideVout, int n,
-                                                        const Ctrl* __restrict__ ctrl) {
+__global__ __launch_bounds__(NT, 1) void chain_planes_kernel(const unsigned short* __restrict__ R, long long strideR, int ldr,
+                                                          const float* __restrict__ R32, long long strideR32, int ldr32,
+                                                          const float* __restrict__ Vin, long long strideVin,
+                                                          const unsigned short* __restrict__ Pin, long long stridePin,
+                                                          float* __restrict__ Vout, long long strideVout,
+                                                          unsigned short* __restrict__ Pout, long long stridePout, int n,
+                                                          const Ctrl* __restrict__ ctrl) {
   constexpr int NBLK = LD / 16;
-  constexpr int KCH = 128;
-  constexpr int ROWB = 2 * KCH + 16;             // bytes per (plane, column)
-  constexpr int DEPTH = 3;
-  constexpr int V_TASKS = LD * (KCH / 8);        // (column, group of 8 k) per chunk
-  constexpr int V_IT = V_TASKS / NT;
-  static_assert(V_TASKS % NT == 0, "sketch width");
-  __shared__ __align__(16) unsigned char Vt[2][3][LD][ROWB];
+  constexpr int STAGES = 4;
+  constexpr int STAGE_BYTES = 3 * LD * 256;
+  constexpr int VL = STAGE_BYTES / 4096;         // direct-to-LDS instructions per wave and chunk
+  constexpr int NL = 4 + VL;                     // loads per wave and chunk
+  static_assert(STAGE_BYTES % 4096 == 0, "sketch width");
+  extern __shared__ __align__(1024) unsigned char Vt[];       // [STAGES][STAGE_BYTES]
   const int b = blockIdx.y;
   if (ctrl && ctrl[b].done) return;
-  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  const int t = threadIdx.x, lane = t & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(t >> 6);   // uniform: LDS destinations stay scalar
   const int li = lane & 15, lq = lane >> 4;
   const int row0 = blockIdx.x * ROWS + wave * 16;
   const unsigned short* Rrow = R + (long long)b * strideR + (long long)(row0 + li) * ldr + 8 * lq;
-  const float* Vb = Vin + (long long)b * strideVin;
-  const int nchunks = n / KCH;
-  const int rot = (int)(blockIdx.x % (unsigned)nchunks);   // see chain_kernel
+  const char* Pb = (const char*)(Pin + (long long)b * stridePin) + wave * 1024 + lane * 16;
+  const int nchunks = n / PCH;
+  // The workgroups of one matrix all read the same V.  Those that share an L2 (workgroups are dealt
+  // round-robin to the 8 XCDs) sweep k in step, so that a chunk of V is fetched once per XCD and
+  // found there by the others before the stream of R has pushed it out; the XCDs start at chunks of
+  // their own and ask different memory channels at any moment.
+#ifdef PRISM_CHAIN_ROT_PER_WG
+  const int rot = (int)(blockIdx.x % (unsigned)nchunks);
+#else
+  const int xcd = (int)((blockIdx.x + gridDim.x * blockIdx.y) & 7u);
+  const int rot = (int)((unsigned)(xcd * nchunks) / 8u);
+#endif
 
-  float vreg[DEPTH][V_IT][8];
-  u32x4 ra[DEPTH][4];
-  auto load_chunk = [&](int slot, int c_want) {   // unconditional, as in chain_kernel
+  u32x4 ra[STAGES][4];
+  auto load_chunk = [&](int slot, int c_want) {   // unconditional (past the end the last chunk again, unused)
     int c = (c_want < nchunks ? c_want : nchunks - 1) + rot;
     if (c >= nchunks) c -= nchunks;
 #pragma unroll
-    for (int it = 0; it < V_IT; ++it) {
-      const int idx = t + it * NT;
-      const int col = idx % LD, kg = idx / LD;
+    for (int i = 0; i < VL; ++i)
+      __builtin_amdgcn_global_load_lds((gptr_t)(Pb + (long long)c * STAGE_BYTES + i * 4096),
+                                       (lptr_t)(Vt + slot * STAGE_BYTES + wave * 1024 + i * 4096), 16, 0, 0);
 #pragma unroll
-      for (int e = 0; e < 8; ++e) vreg[slot][it][e] = Vb[(long long)(c * KCH + 8 * kg + e) * LD + col];
-    }
-#pragma unroll
-    for (int s = 0; s < 4; ++s) ra[slot][s] = *(const u32x4*)(Rrow + c * KCH + 32 * s);
-  };
-  auto store_v = [&](int slot, int buf) {
-#pragma unroll
-    for (int it = 0; it < V_IT; ++it) {
-      const int idx = t + it * NT;
-      const int col = idx % LD, kg = idx / LD;
-      u32x4 hi, mid, lo;
-#pragma unroll
-      for (int w = 0; w < 4; ++w) {
-        unsigned ph[2], pm[2], pl[2];
-#pragma unroll
-        for (int x = 0; x < 2; ++x) {
-          // three truncations: each piece takes the next 8 significant bits, the last one is exact
-          const float v = vreg[slot][it][2 * w + x];
-          const unsigned h = __float_as_uint(v) & 0xFFFF0000u;
-          const float r1 = v - __uint_as_float(h);
-          const unsigned m = __float_as_uint(r1) & 0xFFFF0000u;
-          const float r2 = r1 - __uint_as_float(m);
-          ph[x] = h; pm[x] = m; pl[x] = __float_as_uint(r2);
-        }
-        hi[w] = (ph[0] >> 16) | ph[1];
-        mid[w] = (pm[0] >> 16) | pm[1];
-        lo[w] = (pl[0] >> 16) | (pl[1] & 0xFFFF0000u);
-      }
-      *(u32x4*)&Vt[buf][0][col][16 * kg] = hi;
-      *(u32x4*)&Vt[buf][1][col][16 * kg] = mid;
-      *(u32x4*)&Vt[buf][2][col][16 * kg] = lo;
-    }
+    for (int s = 0; s < 4; ++s) ra[slot][s] = *(const u32x4*)(Rrow + c * PCH + 32 * s);
   };
 
   f32x4 acc[NBLK][3];
@@ -284,26 +293,32 @@ __global__ __launch_bounds__(NT, 2) void chain_bf16_kernel(const unsigned short*
   for (int j = 0; j < NBLK; ++j)
 #pragma unroll
     for (int p = 0; p < 3; ++p) acc[j][p] = (f32x4){0.f, 0.f, 0.f, 0.f};
-  auto lds_barrier = [&]() {   // see chain_kernel
+  // Workgroup barrier without the release fence of __syncthreads() (which would wait for every
+  // outstanding load): this wave's share of the next stage has landed (vmcnt), its reads of the stage
+  // just used are complete (lgkmcnt).
+  auto stage_barrier = [&]() {
+    wait_vmcnt<NL * (STAGES - 2)>();
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
   };
 #pragma unroll
-  for (int d = 0; d < DEPTH - 1; ++d) load_chunk(d, d);
-  store_v(0, 0);
-  lds_barrier();
+  for (int d = 0; d < STAGES - 1; ++d) load_chunk(d, d);
+  stage_barrier();
+  // fragment addresses within a stage: row (plane, column 16 jb + li), unit (4 s + lq) ^ li
+  const unsigned char* fr = Vt + li * 256;
   auto step = [&](auto dtag, int c) {
     constexpr int d = decltype(dtag)::value;
-    const int cur = c & 1;
-    load_chunk((d + DEPTH - 1) % DEPTH, c + DEPTH - 1);
-    // fragments of V one step ahead of their MFMAs (see chain_kernel)
+    __builtin_amdgcn_sched_barrier(0);
+    load_chunk((d + STAGES - 1) % STAGES, c + STAGES - 1);   // the stage chunk c - 1 was read from
+    __builtin_amdgcn_sched_barrier(0);
     u32x4 fb[2][3][NBLK];
     auto read_v = [&](int s) {
 #pragma unroll
       for (int p = 0; p < 3; ++p)
 #pragma unroll
-        for (int j = 0; j < NBLK; ++j) fb[s & 1][p][j] = *(const u32x4*)&Vt[cur][p][j * 16 + li][64 * s + 16 * lq];
+        for (int j = 0; j < NBLK; ++j)
+          fb[s & 1][p][j] = *(const u32x4*)(fr + d * STAGE_BYTES + (p * LD + 16 * j) * 256 + (((4 * s + lq) ^ li) * 16));
     };
     read_v(0);
 #pragma unroll
@@ -318,30 +333,63 @@ __global__ __launch_bounds__(NT, 2) void chain_bf16_kernel(const unsigned short*
         for (int j = 0; j < NBLK; ++j)
           acc[j][p] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, __builtin_bit_cast(bf16x8, fb[s & 1][p][j]), acc[j][p], 0, 0, 0);
     }
-    store_v((d + 1) % DEPTH, cur ^ 1);
-    lds_barrier();
+    stage_barrier();
   };
-  const int nfull = nchunks / DEPTH * DEPTH;
-  for (int c0 = 0; c0 < nfull; c0 += DEPTH)
-    unrolled<DEPTH>([&](auto dt) { step(dt, c0 + decltype(dt)::value); });
-  unrolled<DEPTH - 1>([&](auto dt) {
+  const int nfull = nchunks / STAGES * STAGES;
+  for (int c0 = 0; c0 < nfull; c0 += STAGES)
+    unrolled<STAGES>([&](auto dt) { step(dt, c0 + decltype(dt)::value); });
+  unrolled<STAGES - 1>([&](auto dt) {
     if (nfull + decltype(dt)::value < nchunks) step(dt, nfull + decltype(dt)::value);
   });
-  float dfix[4];   // exact diagonal minus the rounded one, rows of this lane
+  wait_vmcnt<0>();   // the requests past the end write into this workgroup's LDS: none may outlive it
+  const float* Vb = Vin + (long long)b * strideVin;
 #pragma unroll
-  for (int r = 0; r < 4; ++r) {
-    const int row = row0 + 4 * lq + r;
-    dfix[r] = R32[(long long)b * strideR32 + (long long)row * ldr32] -
-              bf16_bits_to_float(R[(long long)b * strideR + (long long)row * ldr + row]);
-  }
-#pragma unroll
-  for (int j = 0; j < NBLK; ++j)
+  for (int j = 0; j < NBLK; ++j) {
+    const int col = j * 16 + li;
+    float o[4];
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
-      const int row = row0 + 4 * lq + r, col = j * 16 + li;
+      const int row = row0 + 4 * lq + r;
+      // exact diagonal minus the rounded one
+      const float dfix = R32[(long long)b * strideR32 + (long long)row * ldr32] -
+                         bf16_bits_to_float(R[(long long)b * strideR + (long long)row * ldr + row]);
       const float v = (acc[j][2][r] + acc[j][1][r]) + acc[j][0][r];   // small pieces first
-      Vout[(long long)b * strideVout + (long long)row * LD + col] = v + dfix[r] * Vb[(long long)row * LD + col];
+      o[r] = v + dfix * Vb[(long long)row * LD + col];
+      Vout[(long long)b * strideVout + (long long)row * LD + col] = o[r];
     }
+    if (Pout) {   // rows 4 lq .. 4 lq + 3 of the wave = four consecutive k of the next product: 8 bytes per plane
+      unsigned h[4], m[4], l[4];
+#pragma unroll
+      for (int r = 0; r < 4; ++r) split3(o[r], h[r], m[r], l[r]);
+      unsigned short* P = Pout + (long long)b * stridePout + plane_offset<LD>(row0 + 4 * lq, col);
+      *(u32x2*)P = (u32x2){(h[0] >> 16) | h[1], (h[2] >> 16) | h[3]};
+      *(u32x2*)(P + (long long)LD * PCH) = (u32x2){(m[0] >> 16) | m[1], (m[2] >> 16) | m[3]};
+      *(u32x2*)(P + 2ll * LD * PCH) = (u32x2){(l[0] >> 16) | l[1], (l[2] >> 16) | l[3]};
+    }
+  }
+}
+
+// V [count][n][LD] fp32 -> planes (the sketches of a call, once per call)
+template <int LD>
+__global__ __launch_bounds__(NT) void split_planes_kernel(const float* __restrict__ V, unsigned short* __restrict__ P, int n) {
+  const long long mat = (long long)blockIdx.y * n * LD;
+  const int task = blockIdx.x * NT + threadIdx.x;   // (unit of eight k, column)
+  const int col = task % LD, u = task / LD;
+  if (u >= n / 8) return;
+  u32x4 hi, mid, lo;
+#pragma unroll
+  for (int w = 0; w < 4; ++w) {
+    unsigned h0, m0, l0, h1, m1, l1;
+    split3(V[mat + (long long)(8 * u + 2 * w) * LD + col], h0, m0, l0);
+    split3(V[mat + (long long)(8 * u + 2 * w + 1) * LD + col], h1, m1, l1);
+    hi[w] = (h0 >> 16) | h1;
+    mid[w] = (m0 >> 16) | m1;
+    lo[w] = (l0 >> 16) | l1;
+  }
+  unsigned short* o = P + mat * 3 + plane_offset<LD>(8 * u, col);
+  *(u32x4*)o = hi;
+  *(u32x4*)(o + (long long)LD * PCH) = mid;
+  *(u32x4*)(o + 2ll * LD * PCH) = lo;
 }
 
 // Variant for small matrices (n <= 2048), where the kernel above is latency bound for lack of
@@ -512,12 +560,8 @@ int launch_chain_t(const typename RFrag<RB>::elem* R, long long strideR, int ldr
     return hipGetLastError() == hipSuccess ? PRISM_OK : PRISM_EHIP;
   }
   const dim3 grid(n / ROWS, batch), block(NT);
-  if constexpr (RB) {   // K in chunks of 128, rows in 16-byte loads
-    if (n % 128 || ldr % 8) return PRISM_EINVAL;
-    if (ld == 16) hipLaunchKernelGGL((chain_bf16_kernel<16>), grid, block, 0, s, R, strideR, ldr, R32, strideR32, ldr32, Vin, strideVin, Vout, strideVout, n, ctrl);
-    else if (ld == 32) hipLaunchKernelGGL((chain_bf16_kernel<32>), grid, block, 0, s, R, strideR, ldr, R32, strideR32, ldr32, Vin, strideVin, Vout, strideVout, n, ctrl);
-    else return PRISM_EINVAL;
-    return hipGetLastError() == hipSuccess ? PRISM_OK : PRISM_EHIP;
+  if constexpr (RB) {
+    return PRISM_EINVAL;   // large bf16 products take the plane kernel (launch_chain_planes)
   }
   else {
     if (ld == 16) hipLaunchKernelGGL((chain_kernel<16>), grid, block, 0, s, R, strideR, ldr, Vin, strideVin, Vout, strideVout, n, ctrl);
@@ -559,7 +603,33 @@ bool chain_bf16_supported(int n, int ld, int batch, int ldr) {
   return (ld == 16 || ld == 32) && ldr % 8 == 0 && n % KC == 0 && (small || n % 128 == 0);
 }
 
-// Same product with R read from its bf16 copy Rb and the diagonal from D (see common.h)
+// 64-row kernel for bf16 R: V comes as fp32 (for the diagonal term) and as planes; the result is written
+// as fp32 and, when Pout is given, as planes for the next product.  n a multiple of 128.
+int launch_chain_planes(const unsigned short* Rb, long long strideR, int ldr, const float* D, long long strideD, int ldd,
+                        const float* Vin, long long strideVin, const unsigned short* Pin, long long stridePin, float* Vout,
+                        long long strideVout, unsigned short* Pout, long long stridePout, int n, int ld, int batch,
+                        const Ctrl* ctrl, hipStream_t s) {
+  if (!Rb || !D || !Vin || !Pin || !Vout || n % PCH || ldr % 8 || batch <= 0 || (ld != 16 && ld != 32)) return PRISM_EINVAL;
+  const dim3 grid(n / ROWS, batch), block(NT);
+  const int lds = 4 * 3 * ld * 256;   // STAGES stages of three planes
+  const int rc = allow_dynamic_lds(ld == 16 ? (const void*)chain_planes_kernel<16> : (const void*)chain_planes_kernel<32>, lds);
+  if (rc != PRISM_OK) return rc;
+  if (ld == 16) hipLaunchKernelGGL((chain_planes_kernel<16>), grid, block, lds, s, Rb, strideR, ldr, D, strideD, ldd, Vin, strideVin, Pin, stridePin, Vout, strideVout, Pout, stridePout, n, ctrl);
+  else hipLaunchKernelGGL((chain_planes_kernel<32>), grid, block, lds, s, Rb, strideR, ldr, D, strideD, ldd, Vin, strideVin, Pin, stridePin, Vout, strideVout, Pout, stridePout, n, ctrl);
+  return hipGetLastError() == hipSuccess ? PRISM_OK : PRISM_EHIP;
+}
+
+// V [count][n][ld] fp32 -> bf16 planes [count][n / 128][3][ld][128]
+int launch_split_planes(const float* V, unsigned short* P, int n, int ld, int count, hipStream_t s) {
+  if (!V || !P || n % PCH || count <= 0 || (ld != 16 && ld != 32)) return PRISM_EINVAL;
+  const dim3 grid((unsigned)(((long long)n / 8 * ld + NT - 1) / NT), count), block(NT);
+  if (ld == 16) hipLaunchKernelGGL((split_planes_kernel<16>), grid, block, 0, s, V, P, n);
+  else hipLaunchKernelGGL((split_planes_kernel<32>), grid, block, 0, s, V, P, n);
+  return hipGetLastError() == hipSuccess ? PRISM_OK : PRISM_EHIP;
+}
+
+// Same product with R read from its bf16 copy Rb and the diagonal from D (see common.h): the 16-row
+// kernel only (chain_takes_small_kernel); larger launches go through launch_chain_planes
 int launch_chain_bf16(const unsigned short* Rb, long long strideR, int ldr, const float* D, long long strideD, int ldd,
                       const float* Vin, long long strideVin, float* Vout, long long strideVout, int n, int ld, int batch,
                       const Ctrl* ctrl, hipStream_t s, int sel_batch) {

@@ -93,9 +93,7 @@ struct Bf16Desc {
   const uint16_t* Xhi; const uint16_t* Xlo;          // APPLY: current iterate (same layout as Cb)
   float c1;
   int coef_is_alpha;                                 // APPLY: multiply acc by ctrl.alpha (d = 1)
-  float* rho_part;                                   // GRAM: partial sums of R^2, slot b * rho_stride + part_base + (tile - tile_first)
-  int rho_stride, part_base;                         // 0, 0: one slot per tile of the launch's own tiling
-  int tile_first, tile_count;                        // tiles [first, first + count) of every matrix only (count 0: all)
+  float* rho_part;                                   // GRAM: partial sums of R^2, one slot per computed tile: b * tiles + tile
   const Ctrl* ctrl;
   int xcd_blocks;                                    // set by launch_gemm_bf16: 4 x 8 tile blocks per XCD
   int ctrl_fixed;                                    // ctrl[0] applies to every batch entry (the parts of a split-K product)
@@ -133,6 +131,14 @@ bool chain_takes_small_kernel(int n, int ld, int batch, bool rb);
 int launch_chain_tiny(const float* R, long long strideR, int ldr, const float* V0, long long strideV0, float* Vout,
                       long long strideJ, long long strideB, int nv, int ld, int batch, const Ctrl* ctrl, hipStream_t s);
 bool chain_bf16_supported(int n, int ld, int batch, int ldr);
+// bf16 R, launches too large for the 16-row kernel: V is read as three bf16 planes (the exact 8 + 8 + 8 bit
+// split of its fp32 entries) laid out [matrix][k / 128][plane][column][unit ^ (column % 16)][8 k]; Vin (fp32) serves the
+// diagonal term; the result goes to Vout (fp32) and, if Pout is given, to planes for the next product.
+int launch_chain_planes(const unsigned short* Rb, long long strideR, int ldr, const float* D, long long strideD, int ldd,
+                        const float* Vin, long long strideVin, const unsigned short* Pin, long long stridePin, float* Vout,
+                        long long strideVout, unsigned short* Pout, long long stridePout, int n, int ld, int batch,
+                        const Ctrl* ctrl, hipStream_t s);
+int launch_split_planes(const float* V, unsigned short* P, int n, int ld, int count, hipStream_t s);
 int launch_chain_bf16(const unsigned short* Rb, long long strideR, int ldr, const float* D, long long strideD, int ldd,
                       const float* Vin, long long strideVin, float* Vout, long long strideVout, int n, int ld, int batch,
                       const Ctrl* ctrl, hipStream_t s, int sel_batch = 0);

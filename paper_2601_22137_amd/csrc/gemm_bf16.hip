@@ -2,10 +2,12 @@
 // accumulate) with the epilogues of the PRISM polar iteration fused in (Table 1, rows
 // "Newton-Schulz, U V^T": Gram/residual R = I - X^T X, Q = R/2 + alpha R^2, update X + X Q).
 //
-// Both operands are stored with K contiguous ([M][K] and [N][K]), which is the layout the
-// instruction consumes: each lane feeds 8 consecutive k of one row.  The polar iteration is
-// arranged so that every product has this form: the Gram matrix is taken from the [S][L] copy
-// of the iterate, R and Q are symmetric, and the update reads the [L][S] copy.
+// The instruction consumes operands with K contiguous (each lane feeds 8 consecutive k of one row).
+// An operand may be stored that way ([M][K] / [N][K]) or with K as the slow index ([K][M] / [K][N]);
+// the latter is read from LDS with transposing reads.  The polar iteration keeps one copy of the
+// iterate, X[L][S]: the Gram product X^T X reads it as [K][M] for both operands, the update X Q reads
+// it as [M][K]; R and Q are symmetric and are read as [K][N], which fetches whole cache lines per
+// request where the K-contiguous form fetches 64 bytes per row and slab.
 //
 // One workgroup = 4 wavefronts (2 x 2) computes a TM x TN tile for one matrix; K runs in slabs of
 // 32 moved straight from global memory into an LDS ring (no register staging; loads run
@@ -95,11 +97,9 @@ __global__ __launch_bounds__(NT, wgs_per_cu(TM, TN)) void gemm_bf16_kernel(Bf16M
   // diagonal or lie above it are computed; a tile wholly above the diagonal blocks is also written
   // mirrored.
   const int tiles_m = g.M / TM, tiles_n = g.N / TN;
-  // a launch may cover only tiles [tile_first, tile_first + tile_count) of every matrix (the rest
-  // then belongs to a launch with another tile shape)
-  const int per_mat = g.tile_count ? g.tile_count : (SYM ? RT * tiles_m * (tiles_m + 1) / 2 : tiles_m * tiles_n);
+  const int per_mat = SYM ? RT * tiles_m * (tiles_m + 1) / 2 : tiles_m * tiles_n;
   const int b = wg / per_mat;
-  const int rem = wg - b * per_mat + g.tile_first;
+  const int rem = wg - b * per_mat;
   int tm, tn;
   if (SYM) {       // row tm of the upper triangle holds tiles_n - RT * tm tiles
     int left = rem;
@@ -556,7 +556,7 @@ __global__ __launch_bounds__(NT, wgs_per_cu(TM, TN)) void gemm_bf16_kernel(Bf16M
     __syncthreads();
     if (lane == 0) red[wave] = part;
     __syncthreads();
-    if (t == 0) g.rho_part[(long long)b * g.rho_stride + g.part_base + rem - g.tile_first] = red[0] + red[1] + red[2] + red[3];
+    if (t == 0) g.rho_part[(long long)b * per_mat + rem] = red[0] + red[1] + red[2] + red[3];
   }
 }
 
@@ -564,8 +564,7 @@ __global__ __launch_bounds__(NT, wgs_per_cu(TM, TN)) void gemm_bf16_kernel(Bf16M
 template <int TM, int TN, bool SYM>
 long long tiles_per_matrix(const Bf16Desc& g) {
   const long long tm = g.M / TM, tn = g.N / TN;
-  const long long all = SYM ? (TM / TN) * tm * (tm + 1) / 2 : tm * tn;
-  return g.tile_count ? g.tile_count : all;
+  return SYM ? (TM / TN) * tm * (tm + 1) / 2 : tm * tn;
 }
 
 template <int TM, int TN, int EPI, bool SYM, bool KMA = false, bool KMB = false>
@@ -592,13 +591,6 @@ int launch_t(Bf16Multi& mg, hipStream_t s) {
     if (g.epi != epi || g.sym != sym || g.km != km) return PRISM_EINVAL;
     if (g.M % TM || g.N % TN || g.K % BK || g.K < BK || g.lda % 8 || g.ldb % 8) return PRISM_EINVAL;
     if ((long long)(g.M / TM) * (g.N / TN) * g.batch <= 0) return PRISM_EINVAL;
-    {
-      const long long tm = g.M / TM, tn = g.N / TN;
-      const long long all = g.sym ? (TM / TN) * tm * (tm + 1) / 2 : tm * tn;
-      if (g.tile_first < 0 || g.tile_count < 0 || g.tile_first + (long long)g.tile_count > all) return PRISM_EINVAL;
-      if (g.tile_count == 0 && g.tile_first != 0) return PRISM_EINVAL;
-      if (g.tile_count && g.xcd_blocks) return PRISM_EINVAL;   // the block order covers whole matrices
-    }
     if (g.sym && (g.M != g.N || g.A != g.B)) return PRISM_EINVAL;
     if ((g.epi == BEPI_GRAM || g.epi == BEPI_POLYQ) && !g.sym) return PRISM_EINVAL;   // symmetric products only
     if (g.epi == BEPI_STORE && (g.sym || !g.C32)) return PRISM_EINVAL;
@@ -646,8 +638,7 @@ int launch_gemm_bf16_multi(const Bf16Desc* groups, int ngroups, int tile_m, int 
     const long long tm = g.M / tile_m, tn = g.N / tile_n;
     const long long per_mat = g.sym ? (tile_m / tile_n) * tm * (tm + 1) / 2 : tm * tn;
     if (per_mat > 64) small = false;
-    g.xcd_blocks = !no_blocks && !g.sym && !g.tile_count && per_mat % 256 == 0 && tm % 4 == 0 && tn % 8 == 0;
-    if (g.epi == BEPI_GRAM && g.rho_stride == 0) { g.rho_stride = (int)per_mat; g.part_base = 0; }   // one launch writes all partials
+    g.xcd_blocks = !no_blocks && !g.sym && per_mat % 256 == 0 && tm % 4 == 0 && tn % 8 == 0;
   }
   mg.xcd_private = small || operand_bytes <= 128.0 * 1024 * 1024;
   if (tile_m == 256 && tile_n == 256) return launch_t<256, 256>(mg, s);

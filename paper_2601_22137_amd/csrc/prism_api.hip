@@ -83,6 +83,8 @@ struct Plan {
   int max_parts;   // residual partials per matrix
   // byte offsets into the workspace
   size_t o_ctrl, o_info, o_sumsq, o_rho, o_v0, o_v, o_cpart;
+  size_t o_vp0, o_vp;                             // bf16 polar: bf16 planes of the sketches and of V_1 .. V_{nv-1}
+  bool has_planes;
   int ngroups;     // workgroups per matrix of the moments kernel
   bool shared_gpu; // PRISM_FLAG_SHARED_GPU
   size_t o_x[2], o_y[2], o_r, o_q, o_t[3];        // fp32 paths (o_y doubles as M64 for inverse root)
@@ -150,6 +152,11 @@ int make_plan(Plan& P, int fn, int batch, int m, int n, int dt, int degree, int 
     }
   }
   P.o_cpart = take(B * P.ngroups * 17 * sizeof(double));
+  if (dt == PRISM_BF16 && P.ld <= 32 && P.p_s > 0) {   // operands of the plane chain kernel: 3 x 2 bytes per entry
+    P.o_vp0 = take((size_t)PRISM_MAX_ITERS * P.Sp * P.ld * 6);
+    P.o_vp = take((size_t)(P.nv - 1) * B * P.Sp * P.ld * 6);
+    P.has_planes = true;
+  }
   if (dt == PRISM_BF16) {
     for (int i = 0; i < 2 && !shared_shapes; ++i) {
       P.o_xhi[i] = take(B * LS * 2);
@@ -252,6 +259,8 @@ struct Run {
   float* rho;
   float* v0;
   float* v;
+  uint16_t* vp0 = nullptr;             // bf16 planes of the sketches / of V_1 .. (bf16 polar, large launches)
+  uint16_t* vp = nullptr;
   int max_iters, warm;
   const float* sched; int sched_len;   // caller's coefficients for the leading updates (host array)
   int first_fit;                       // first update whose coefficient is fitted
@@ -291,7 +300,13 @@ struct Run {
       const float* vin = (j == 1) ? v0 + (long long)(k - first_fit) * Sp * ld : v + (j - 2) * vs;
       const long long sin = (j == 1) ? 0 : (long long)Sp * ld;
       ProfScope ps(PK_CHAIN, s);
-      if (Rb)
+      if (Rb && planes()) {
+        const long long pe = (long long)Sp * ld * 3;   // plane entries per matrix
+        const uint16_t* pin = (j == 1) ? vp0 + (long long)(k - first_fit) * pe : vp + (long long)(j - 2) * P.batch * pe;
+        uint16_t* pout = j < P.nv ? vp + (long long)(j - 1) * P.batch * pe : nullptr;
+        CHECK_LAUNCH(launch_chain_planes(Rb, (long long)Sp * Sp, Sp, D, strideD, ldd, vin, sin, pin, j == 1 ? 0 : pe,
+                                         v + (j - 1) * vs, (long long)Sp * ld, pout, pe, Sp, ld, P.batch, ctrl, s));
+      } else if (Rb)
         CHECK_LAUNCH(launch_chain_bf16(Rb, (long long)Sp * Sp, Sp, D, strideD, ldd, vin, sin, v + (j - 1) * vs,
                                        (long long)Sp * ld, Sp, ld, P.batch, ctrl, s, chain_sel_batch));
       else
@@ -323,6 +338,10 @@ struct Run {
     return check_hip();
   }
   bool fit_needed(int k) const { return P.p_s > 0 && k >= first_fit && k < max_iters; }
+  // bf16 chain products too large for the 16-row kernel read V as bf16 planes
+  bool planes() const {
+    return vp0 && !chain_takes_small_kernel(P.Sp, P.ld, chain_sel_batch ? chain_sel_batch : P.batch, true);
+  }
 };
 
 GemmDesc f32_desc(const Run& r, const float* A, int lda, long long sa, const float* B, int ldb, long long sb,
@@ -843,6 +862,7 @@ int run(int fn, void* a, void* inv_out, int root_p, int batch, int m, int n, int
   r.rho = r.at<float>(P.o_rho);
   r.v0 = r.at<float>(P.o_v0);
   r.v = r.at<float>(P.o_v);
+  if (P.has_planes) { r.vp0 = r.at<uint16_t>(P.o_vp0); r.vp = r.at<uint16_t>(P.o_vp); }
   r.max_iters = max_iters; r.tol = tol; r.seed = seed; r.warm = opt ? opt->warm_iters : 0;
   r.sched = opt ? opt->alpha_schedule : nullptr;
   r.sched_len = opt ? opt->schedule_len : 0;
@@ -881,6 +901,7 @@ int run(int fn, void* a, void* inv_out, int root_p, int batch, int m, int n, int
   if (P.p_s > 0 && max_iters > r.first_fit && fn != PRISM_FN_SQRT_NEWTON) {
     ProfScope ps(PK_SKETCH, r.s);
     launch_sketch(r.v0, P.Sp, P.S, P.ld, P.p_s, seed, r.first_fit, max_iters - r.first_fit, P.fn, r.s);
+    if (r.planes()) CHECK_LAUNCH(launch_split_planes(r.v0, r.vp0, P.Sp, P.ld, max_iters - r.first_fit, r.s));
   }
   rc = check_hip();
   if (rc != PRISM_OK) return rc;
@@ -953,6 +974,7 @@ int run_polar_bf16_shapes(const prism_group* groups, int ngroups, int degree, in
   r.rho = r.at<float>(P.o_rho);
   r.v0 = r.at<float>(P.o_v0);
   r.v = r.at<float>(P.o_v);
+  if (P.has_planes) { r.vp0 = r.at<uint16_t>(P.o_vp0); r.vp = r.at<uint16_t>(P.o_vp); }
   r.max_iters = max_iters; r.tol = tol; r.seed = seed; r.warm = opt ? opt->warm_iters : 0;
   r.sched = opt ? opt->alpha_schedule : nullptr;
   r.sched_len = opt ? opt->schedule_len : 0;
@@ -990,6 +1012,7 @@ int run_polar_bf16_shapes(const prism_group* groups, int ngroups, int degree, in
   if (P.p_s > 0 && max_iters > r.first_fit) {
     ProfScope ps(PK_SKETCH, r.s);
     launch_sketch(r.v0, P.Sp, P.S, P.ld, P.p_s, seed, r.first_fit, max_iters - r.first_fit, P.fn, r.s);
+    if (r.planes()) CHECK_LAUNCH(launch_split_planes(r.v0, r.vp0, P.Sp, P.ld, max_iters - r.first_fit, r.s));
   }
   rc = check_hip();
   if (rc != PRISM_OK) return rc;
@@ -1383,13 +1406,20 @@ int prism_chain_product(const float* R, const float* V, float* out, int batch, i
                       (hipStream_t)stream);
 }
 
-int prism_chain_product_bf16(const uint16_t* Rb, const float* R, const float* V, float* out, int batch, int n, int ld,
-                             void* stream) {
+int prism_chain_product_bf16(const uint16_t* Rb, const float* R, const float* V, float* out, uint16_t* planes, int batch,
+                             int n, int ld, void* stream) {
   set_last_error("");
-  if (!Rb || !R || !V || !out) return PRISM_EINVAL;
+  if (!Rb || !R || !V || !out || batch <= 0 || batch > PRISM_MAX_BATCH || n <= 0) return PRISM_EINVAL;
   if (!chain_bf16_supported(n, ld, batch, n)) return PRISM_EUNSUPPORTED;
-  return launch_chain_bf16(Rb, (long long)n * n, n, R, (long long)n * n, n + 1, V, (long long)n * ld, out,
-                           (long long)n * ld, n, ld, batch, nullptr, (hipStream_t)stream);
+  hipStream_t s = (hipStream_t)stream;
+  if (chain_takes_small_kernel(n, ld, batch, true))
+    return launch_chain_bf16(Rb, (long long)n * n, n, R, (long long)n * n, n + 1, V, (long long)n * ld, out,
+                             (long long)n * ld, n, ld, batch, nullptr, s);
+  if (!planes) return PRISM_EINVAL;
+  const long long pe = (long long)n * ld * 3;
+  CHECK_LAUNCH(launch_split_planes(V, planes, n, ld, batch, s));
+  return launch_chain_planes(Rb, (long long)n * n, n, R, (long long)n * n, n + 1, V, (long long)n * ld, planes, pe, out,
+                             (long long)n * ld, planes + (long long)batch * pe, pe, n, ld, batch, nullptr, s);
 }
 
 int prism_gemm_f32(const float* A, const float* B, float* C, int batch, int M, int N, int K, int a_km, void* stream) {

@@ -80,7 +80,7 @@ def lib():
         L.prism_sketch.argtypes = [vp, i, i, u64, i, i, vp]
         L.prism_gauss_parts.argtypes = [ctypes.c_uint32, ctypes.c_uint32, vp, vp, vp, vp]
         L.prism_chain_product.argtypes = [vp, vp, vp, i, i, i, vp]
-        L.prism_chain_product_bf16.argtypes = [vp, vp, vp, vp, i, i, i, vp]
+        L.prism_chain_product_bf16.argtypes = [vp, vp, vp, vp, vp, i, i, i, vp]
         L.prism_gemm_f32.argtypes = [vp, vp, vp, i, i, i, i, i, vp]
         L.prism_gemm_f64a.argtypes = [vp, vp, vp, i, i, i, i, vp]
         L.prism_gemm_bf16_nt.argtypes = [vp, vp, vp, i, i, i, i, i, vp]
@@ -301,11 +301,16 @@ def release_workspaces():
     _check(lib().prism_release_workspaces())
 
 
-def chain_product_bf16(Rb, R, V):
+def chain_product_bf16(Rb, R, V, return_planes=False):
+    """out = (Rb + diag(R - Rb)) V.  With return_planes also the scratch array of the call: bf16 bit
+    patterns [2][batch][n / 128][3][ld][16 units, xor-ed with column % 16][8], the planes of V and of out (zeros where the launch is
+    small enough for the kernel that does not use them)."""
     batch, n, ld = V.shape
     out = torch.empty_like(V)
-    _check(lib().prism_chain_product_bf16(Rb.data_ptr(), R.data_ptr(), V.data_ptr(), out.data_ptr(), batch, n, ld, _stream()))
-    return out
+    planes = torch.zeros((2, batch, n * ld * 3), dtype=torch.int16, device=V.device)
+    _check(lib().prism_chain_product_bf16(Rb.data_ptr(), R.data_ptr(), V.data_ptr(), out.data_ptr(), planes.data_ptr(),
+                                          batch, n, ld, _stream()))
+    return (out, planes) if return_planes else out
 
 
 def gemm_f32(A, B, a_km=False, sym=False):
@@ -325,9 +330,17 @@ def gemm_f64a(A, B):
     return C
 
 
-def gemm_bf16_nt(A, B, tile):
-    batch, M, K = A.shape
-    N = B.shape[1]
+def gemm_bf16_nt(A, B, tile, km=0):
+    """C = A B^T.  km = 0: A [batch][M][K], B [batch][N][K]; km = 2: B is stored [batch][K][N];
+    km = 3: A is stored [batch][K][M] and B [batch][K][N]."""
+    if km not in (0, 2, 3):
+        raise ValueError("km must be 0, 2 or 3")
+    batch = A.shape[0]
+    K, M = (A.shape[1], A.shape[2]) if km == 3 else (A.shape[2], A.shape[1])
+    N = B.shape[2] if km else B.shape[1]
+    if (B.shape[1] if km else B.shape[2]) != K or B.shape[0] != batch:
+        raise ValueError("operand shapes do not match")
+    tile = tile + (10000 if km == 3 else 20000 if km == 2 else 0)
     C = torch.empty((batch, M, N), dtype=torch.float32, device=A.device)
     _check(lib().prism_gemm_bf16_nt(A.data_ptr(), B.data_ptr(), C.data_ptr(), batch, M, N, K, tile, _stream()))
     return C

@@ -39,7 +39,7 @@ def test_chain_product_bf16(prism, n, ld, batch):
     """Off-diagonal entries from the bf16 copy, diagonal from the fp32 matrix; R = I - small, the
     case in which a rounded diagonal would be wrong by more than the whole off-diagonal part.
     Small batches take the 16-row kernel, (n / 64) * batch >= 128 the 64-row one (chunks of 128 k,
-    with and without a ragged last ring round); the widest sketch (ld = 64) and large batches of sizes
+    with and without a ragged last ring round; V and the result also as bf16 planes); the widest sketch (ld = 64) and large batches of sizes
     that are no multiple of 128 are not taken (the library keeps to the fp32 matrix there)."""
     rng = np.random.default_rng(3 * n + ld)
     R = np.empty((batch, n, n), dtype=np.float32)
@@ -54,7 +54,21 @@ def test_chain_product_bf16(prism, n, ld, batch):
         with pytest.raises(prism.PrismError, match="UNSUPPORTED"):
             prism.chain_product_bf16(rb_dev, _dev(R), _dev(V))
         return
-    out = prism.chain_product_bf16(rb_dev, _dev(R), _dev(V)).cpu().numpy()
+    out, planes = prism.chain_product_bf16(rb_dev, _dev(R), _dev(V), return_planes=True)
+    out = out.cpu().numpy()
+    if not small:
+        # the launch read V as three bf16 planes and wrote its result that way too: each is the exact
+        # 8 + 8 + 8 bit split of the fp32 array, laid out [matrix][k / 128][plane][column][unit ^ (column % 16)][8 k]
+        pl = planes.cpu().numpy().view(np.uint16).reshape(2, batch, n // 128, 3, ld, 16, 8)
+        unswz = np.arange(16)[None, :] ^ (np.arange(ld)[:, None] % 16)            # [column][unit] -> stored unit
+        pl = np.take_along_axis(pl, unswz[None, None, None, None, :, :, None], axis=5).reshape(2, batch, n // 128, 3, ld, 128)
+        for which, arr in ((0, V), (1, out)):
+            parts = W.from_bf16_bits(pl[which]).astype(np.float64)              # [batch][c][plane][col][k]
+            total = parts.sum(axis=2).transpose(0, 1, 3, 2).reshape(batch, n, ld)
+            assert np.array_equal(total.astype(np.float32), arr), which
+            # pieces are truncations: each carries at most 8 significant bits of what the ones before left
+            hi = parts[:, :, 0].transpose(0, 1, 3, 2).reshape(batch, n, ld)
+            assert np.array_equal(hi.astype(np.float32).view(np.uint32), arr.view(np.uint32) & 0xFFFF0000), which
     idx = np.arange(n)
     for b in (0, batch - 1):
         exact = R[b].astype(np.float64) @ V[b].astype(np.float64)
@@ -112,6 +126,33 @@ def test_gemm_bf16_nt(prism, tile, shape):
     A = W.to_bf16_bits(rng.standard_normal((2, M, K)))
     B = W.to_bf16_bits(rng.standard_normal((2, N, K)))
     C = prism.gemm_bf16_nt(_dev(A.view(np.int16)), _dev(B.view(np.int16)), tile).cpu().numpy()
+    ref = W.from_bf16_bits(A).astype(np.float64) @ W.from_bf16_bits(B).astype(np.float64).transpose(0, 2, 1)
+    assert np.linalg.norm(C - ref) / np.linalg.norm(ref) < 1e-6
+
+
+@pytest.mark.parametrize("km", [2, 3])
+@pytest.mark.parametrize("tile,shape", [(128, (128, 256, 192)), (128, (384, 128, 64)), (2561, (512, 384, 320)),
+                                        (256, (512, 256, 128)), (2561, (2048, 2048, 4160)), (256, (1024, 4096, 2048))])
+def test_gemm_bf16_operands_stored_k_major(prism, tile, shape, km):
+    """The same product with B (km = 2) or both operands (km = 3) stored with K as the slow index,
+    which the kernel reads from LDS with transposing reads."""
+    M, N, K = shape
+    rng = np.random.default_rng(M * 3 + N + km)
+    A = W.to_bf16_bits(rng.standard_normal((2, M, K)))
+    B = W.to_bf16_bits(rng.standard_normal((2, N, K)))
+    ref = W.from_bf16_bits(A).astype(np.float64) @ W.from_bf16_bits(B).astype(np.float64).transpose(0, 2, 1)
+    As = np.ascontiguousarray(A.transpose(0, 2, 1)) if km == 3 else A
+    Bs = np.ascontiguousarray(B.transpose(0, 2, 1))
+    C = prism.gemm_bf16_nt(_dev(As.view(np.int16)), _dev(Bs.view(np.int16)), tile, km).cpu().numpy()
+    assert np.linalg.norm(C - ref) / np.linalg.norm(ref) < 1e-6
+
+
+def test_gemm_bf16_256x128_tiles(prism):
+    M, N, K = 768, 640, 448
+    rng = np.random.default_rng(5)
+    A = W.to_bf16_bits(rng.standard_normal((3, M, K)))
+    B = W.to_bf16_bits(rng.standard_normal((3, N, K)))
+    C = prism.gemm_bf16_nt(_dev(A.view(np.int16)), _dev(B.view(np.int16)), 2561).cpu().numpy()
     ref = W.from_bf16_bits(A).astype(np.float64) @ W.from_bf16_bits(B).astype(np.float64).transpose(0, 2, 1)
     assert np.linalg.norm(C - ref) / np.linalg.norm(ref) < 1e-6
 
