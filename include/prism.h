@@ -292,11 +292,11 @@ int prism_chain_product(const float* R, const float* V, float* out, int batch, i
                         void* stream);
 /* The same product as the bf16 polar path takes it: the off-diagonal entries of R are read from
  * Rb, its copy in bf16 bit patterns (same shape), the diagonal from R itself:
- * out = (Rb + diag(R - Rb)) * V.  ld = 16 or 32, n a multiple of 64 (of 128 when (n / 64) * batch >= 128);
+ * out = (Rb + diag(R - Rb)) * V.  ld = 16 or 32, n a multiple of 64 (of 256 when (n / 64) * batch >= 128);
  * other shapes return PRISM_EUNSUPPORTED (the library then keeps to the fp32 matrix).
  * Launches of (n / 64) * batch >= 128 workgroups read V as three bf16 planes (the exact 8 + 8 + 8 bit
- * split of every fp32 entry, laid out [matrix][k / 128][plane][column][u ^ (column % 16)][8] with
- * u = (k % 128) / 8, the image of the kernel's LDS stage) and write their
+ * split of every fp32 entry, laid out [matrix][k / 256][plane][column][u'][8] with u = (k % 256) / 8,
+ * u' = (u & 16) | ((u ^ column) & 15): the image of the kernel's LDS stage) and write their
  * result in that form too, for the next product of the chain: `planes` is device scratch of
  * 2 * batch * n * ld * 3 entries; on return its first half holds the planes of V, the second half
  * those of out.  It may be null for smaller launches, which do not use it. */

@@ -208,13 +208,17 @@ __global__ __launch_bounds__(NT, 2) void chain_kernel(const float* __restrict__ 
 //
 // The pieces are not cut here (every workgroup would cut all of V again).  Whoever produces a V (this
 // kernel for V_1 .. V_{nv-1}, split_planes_kernel for the sketches) also writes it as three bf16
-// planes, chunk by chunk of 128 k, as the image of the LDS stage the consumer wants:
-//     P[matrix][c = k / 128][plane][column][unit u ^ (column % 16)][8 k],   u = (k % 128) / 8
-// A stage is 3 * LD rows of 256 bytes; the workgroup moves it from global memory straight into LDS
+// planes, chunk by chunk of 256 k, as the image of the LDS stage the consumer wants:
+//     P[matrix][c = k / 256][plane][column][unit u'][8 k],   u = (k % 256) / 8,  u' = (u & 16) | ((u ^ column) & 15)
+// A stage is 3 * LD rows of 512 bytes; the workgroup moves it from global memory straight into LDS
 // (global_load_lds_dwordx4, 1 KiB per wave instruction, no registers, no arithmetic).
-//   A operand: lane (i = l % 16, g = l / 16) holds R[row i][128 c + 32 s + 8 g .. + 7]: its 16-byte load;
-//   B operand: lane (j = l % 16, g) reads unit 4 s + g of column 16 jb + j: with the unit index xor-ed
-//   by the column the 16 lanes of a group hit 16 different units of their (bank-aligned) rows.
+// A workgroup owns 64 rows of R; wave w takes the k with (k % 256) / 64 = w of every chunk, for all
+// 64 rows: its fragments of V (a quarter of the stage) serve four row blocks, so the LDS is read
+// a quarter as often as with a wave per 16 rows, and the wave fetches whole 128-byte lines of R.
+// The four partial sums are added through LDS in a fixed order at the end.
+//   A operand: lane (i = l % 16, g = l / 16) holds R[row 16 q + i][256 c + 64 w + 32 h + 8 g .. + 7], h = 0, 1
+//   B operand: lane (j = l % 16, g) reads unit u = 8 w + 4 h + g of column 16 jb + j: with the low bits of
+//   the unit index xor-ed by the column the 16 lanes of a group hit 16 different units of their rows.
 // R goes straight into registers.  Rows of R and stages of V run STAGES - 1 chunks ahead.
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef const void __attribute__((address_space(1)))* gptr_t;
@@ -229,11 +233,25 @@ __device__ inline void split3(float v, unsigned& h, unsigned& m, unsigned& l) {
   l = __float_as_uint(r2) & 0xFFFF0000u;
 }
 
-constexpr int PCH = 128;   // k per chunk of the plane layout
-// entry offset of (k, column) in plane 0 of its matrix; planes 1 and 2 lie LD * 128 and 2 * LD * 128 further on
+// eight consecutive k (values v[0..7]) of one column -> the 16-byte units of the three planes
+__device__ inline void split3x8(const float* v, u32x4& hi, u32x4& mid, u32x4& lo) {
+#pragma unroll
+  for (int w = 0; w < 4; ++w) {
+    unsigned h0, m0, l0, h1, m1, l1;
+    split3(v[2 * w], h0, m0, l0);
+    split3(v[2 * w + 1], h1, m1, l1);
+    hi[w] = (h0 >> 16) | h1;
+    mid[w] = (m0 >> 16) | m1;
+    lo[w] = (l0 >> 16) | l1;
+  }
+}
+
+constexpr int PCH = 256;   // k per chunk of the plane layout
+// entry offset of the unit that holds (k .. k + 7, column), k a multiple of 8, in plane 0 of its matrix;
+// planes 1 and 2 lie LD * 256 and 2 * LD * 256 entries further on
 template <int LD> __device__ inline long long plane_offset(int k, int col) {
   const int c = k / PCH, u = (k % PCH) / 8;
-  return ((long long)(c * 3) * LD + col) * PCH + ((u ^ (col & 15)) * 8) + (k & 7);
+  return ((long long)(c * 3) * LD + col) * PCH + (((u & 16) | ((u ^ col) & 15)) * 8);
 }
 
 // s_waitcnt vmcnt(N) with the other counters left alone (gfx9 encoding)
@@ -250,49 +268,61 @@ __global__ __launch_bounds__(NT, 1) void chain_planes_kernel(const unsigned shor
                                                           unsigned short* __restrict__ Pout, long long stridePout, int n,
                                                           const Ctrl* __restrict__ ctrl) {
   constexpr int NBLK = LD / 16;
-  constexpr int STAGES = 4;
-  constexpr int STAGE_BYTES = 3 * LD * 256;
+  constexpr int STAGES = 3;
+  constexpr int STAGE_BYTES = 3 * LD * 512;
   constexpr int VL = STAGE_BYTES / 4096;         // direct-to-LDS instructions per wave and chunk
-  constexpr int NL = 4 + VL;                     // loads per wave and chunk
+  constexpr int NL = 8 + VL;                     // loads per wave and chunk
   static_assert(STAGE_BYTES % 4096 == 0, "sketch width");
+  static_assert(4 * ROWS * (LD + 1) * 4 <= STAGES * STAGE_BYTES, "the partial sums reuse the stages");
   extern __shared__ __align__(1024) unsigned char Vt[];       // [STAGES][STAGE_BYTES]
   const int b = blockIdx.y;
   if (ctrl && ctrl[b].done) return;
   const int t = threadIdx.x, lane = t & 63;
   const int wave = __builtin_amdgcn_readfirstlane(t >> 6);   // uniform: LDS destinations stay scalar
   const int li = lane & 15, lq = lane >> 4;
-  const int row0 = blockIdx.x * ROWS + wave * 16;
-  const unsigned short* Rrow = R + (long long)b * strideR + (long long)(row0 + li) * ldr + 8 * lq;
-  const char* Pb = (const char*)(Pin + (long long)b * stridePin) + wave * 1024 + lane * 16;
+  const int row0 = blockIdx.x * ROWS;
+  const unsigned short* Rmat = R + (long long)b * strideR;
+  const unsigned short* Rk = Rmat + 64 * wave + 8 * lq;            // this lane's k within a chunk
+  const long long rrow = (long long)(row0 + li) * ldr;              // ... and its row of block q = 0
+  const char* Pmat = (const char*)(Pin + (long long)b * stridePin);
+  const int poff = wave * 1024 + lane * 16;
   const int nchunks = n / PCH;
   // The workgroups of one matrix all read the same V.  Those that share an L2 (workgroups are dealt
   // round-robin to the 8 XCDs) sweep k in step, so that a chunk of V is fetched once per XCD and
   // found there by the others before the stream of R has pushed it out; the XCDs start at chunks of
   // their own and ask different memory channels at any moment.
-#ifdef PRISM_CHAIN_ROT_PER_WG
-  const int rot = (int)(blockIdx.x % (unsigned)nchunks);
-#else
   const int xcd = (int)((blockIdx.x + gridDim.x * blockIdx.y) & 7u);
   const int rot = (int)((unsigned)(xcd * nchunks) / 8u);
-#endif
 
-  u32x4 ra[STAGES][4];
-  auto load_chunk = [&](int slot, int c_want) {   // unconditional (past the end the last chunk again, unused)
-    int c = (c_want < nchunks ? c_want : nchunks - 1) + rot;
+  u32x4 ra[STAGES][4][2];
+  // Requests are unconditional, so that the compiler can count how many younger ones may stay in
+  // flight at each wait.  Past the end the row and chunk offsets collapse to zero: the whole wave then
+  // fetches the same few bytes (and nobody reads the result).
+  auto load_chunk = [&](int slot, int c_want) {   // slot is a compile-time constant at every call site
+    const bool valid = c_want < nchunks;          // uniform
+    int c = c_want + rot;
     if (c >= nchunks) c -= nchunks;
+    const long long pbase = valid ? (long long)c * STAGE_BYTES + poff : 0;
+    const int pstep = valid ? 4096 : 0;
 #pragma unroll
     for (int i = 0; i < VL; ++i)
-      __builtin_amdgcn_global_load_lds((gptr_t)(Pb + (long long)c * STAGE_BYTES + i * 4096),
+      __builtin_amdgcn_global_load_lds((gptr_t)(Pmat + pbase + i * pstep),
                                        (lptr_t)(Vt + slot * STAGE_BYTES + wave * 1024 + i * 4096), 16, 0, 0);
+    const long long rbase = valid ? rrow + c * PCH : 0;
+    const long long qstep = valid ? 16ll * ldr : 0;
 #pragma unroll
-    for (int s = 0; s < 4; ++s) ra[slot][s] = *(const u32x4*)(Rrow + c * PCH + 32 * s);
+    for (int q = 0; q < 4; ++q)
+#pragma unroll
+      for (int h = 0; h < 2; ++h) ra[slot][q][h] = *(const u32x4*)(Rk + rbase + q * qstep + 32 * h);
   };
 
-  f32x4 acc[NBLK][3];
+  f32x4 acc[4][NBLK][3];
 #pragma unroll
-  for (int j = 0; j < NBLK; ++j)
+  for (int q = 0; q < 4; ++q)
 #pragma unroll
-    for (int p = 0; p < 3; ++p) acc[j][p] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    for (int j = 0; j < NBLK; ++j)
+#pragma unroll
+      for (int p = 0; p < 3; ++p) acc[q][j][p] = (f32x4){0.f, 0.f, 0.f, 0.f};
   // Workgroup barrier without the release fence of __syncthreads() (which would wait for every
   // outstanding load): this wave's share of the next stage has landed (vmcnt), its reads of the stage
   // just used are complete (lgkmcnt).
@@ -305,34 +335,33 @@ __global__ __launch_bounds__(NT, 1) void chain_planes_kernel(const unsigned shor
 #pragma unroll
   for (int d = 0; d < STAGES - 1; ++d) load_chunk(d, d);
   stage_barrier();
-  // fragment addresses within a stage: row (plane, column 16 jb + li), unit (4 s + lq) ^ li
-  const unsigned char* fr = Vt + li * 256;
-  auto step = [&](auto dtag, int c) {
+  // fragment addresses within a stage: row (plane, column 16 jb + li), unit 8 w + 4 h + lq with its low bits xor li
+  const unsigned char* fr = Vt + li * 512 + (wave >> 1) * 256;
+  const int fu0 = (((8 * wave + lq) ^ li) & 15) * 16, fu1 = (((8 * wave + 4 + lq) ^ li) & 15) * 16;
+  auto step = [&](auto dtag, int c) {   // chunk c, in ring slot d = c % STAGES
     constexpr int d = decltype(dtag)::value;
     __builtin_amdgcn_sched_barrier(0);
-    load_chunk((d + STAGES - 1) % STAGES, c + STAGES - 1);   // the stage chunk c - 1 was read from
+    load_chunk((d + STAGES - 1) % STAGES, c + STAGES - 1);   // into the stage chunk c - 1 was read from
     __builtin_amdgcn_sched_barrier(0);
     u32x4 fb[2][3][NBLK];
-    auto read_v = [&](int s) {
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
 #pragma unroll
       for (int p = 0; p < 3; ++p)
 #pragma unroll
         for (int j = 0; j < NBLK; ++j)
-          fb[s & 1][p][j] = *(const u32x4*)(fr + d * STAGE_BYTES + (p * LD + 16 * j) * 256 + (((4 * s + lq) ^ li) * 16));
-    };
-    read_v(0);
+          fb[h][p][j] = *(const u32x4*)(fr + d * STAGE_BYTES + (p * LD + 16 * j) * 512 + (h ? fu1 : fu0));
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int s = 0; s < 4; ++s) {
-      __builtin_amdgcn_sched_barrier(0);
-      if (s + 1 < 4) read_v(s + 1);
-      __builtin_amdgcn_sched_barrier(0);
-      const bf16x8 a = __builtin_bit_cast(bf16x8, ra[d][s]);
+    for (int h = 0; h < 2; ++h)
 #pragma unroll
       for (int p = 0; p < 3; ++p)
 #pragma unroll
         for (int j = 0; j < NBLK; ++j)
-          acc[j][p] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, __builtin_bit_cast(bf16x8, fb[s & 1][p][j]), acc[j][p], 0, 0, 0);
-    }
+#pragma unroll
+          for (int q = 0; q < 4; ++q)
+            acc[q][j][p] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ra[d][q][h]),
+                                                                   __builtin_bit_cast(bf16x8, fb[h][p][j]), acc[q][j][p], 0, 0, 0);
     stage_barrier();
   };
   const int nfull = nchunks / STAGES * STAGES;
@@ -342,29 +371,40 @@ __global__ __launch_bounds__(NT, 1) void chain_planes_kernel(const unsigned shor
     if (nfull + decltype(dt)::value < nchunks) step(dt, nfull + decltype(dt)::value);
   });
   wait_vmcnt<0>();   // the requests past the end write into this workgroup's LDS: none may outlive it
-  const float* Vb = Vin + (long long)b * strideVin;
+  __syncthreads();   // ... nor the reuse of the stages below
+  // partial sums of this wave's k (small pieces first), added up in wave order
+  float (*red)[ROWS][LD + 1] = (float (*)[ROWS][LD + 1])Vt;
 #pragma unroll
-  for (int j = 0; j < NBLK; ++j) {
-    const int col = j * 16 + li;
-    float o[4];
+  for (int q = 0; q < 4; ++q)
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      const int row = row0 + 4 * lq + r;
+    for (int j = 0; j < NBLK; ++j)
+#pragma unroll
+      for (int r = 0; r < 4; ++r)
+        red[wave][16 * q + 4 * lq + r][16 * j + li] = (acc[q][j][2][r] + acc[q][j][1][r]) + acc[q][j][0][r];
+  __syncthreads();
+  // thread = (column, eight consecutive rows): the rows are the k of the next product, so the thread
+  // owns one 16-byte unit of each plane of the result
+  const int col = t % LD, u8 = t / LD;
+  if (u8 < ROWS / 8) {
+    const float* Vb = Vin + (long long)b * strideVin;
+    float o[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const int rl = 8 * u8 + e, row = row0 + rl;
+      const float v = (red[0][rl][col] + red[1][rl][col]) + (red[2][rl][col] + red[3][rl][col]);
       // exact diagonal minus the rounded one
       const float dfix = R32[(long long)b * strideR32 + (long long)row * ldr32] -
-                         bf16_bits_to_float(R[(long long)b * strideR + (long long)row * ldr + row]);
-      const float v = (acc[j][2][r] + acc[j][1][r]) + acc[j][0][r];   // small pieces first
-      o[r] = v + dfix * Vb[(long long)row * LD + col];
-      Vout[(long long)b * strideVout + (long long)row * LD + col] = o[r];
+                         bf16_bits_to_float(Rmat[(long long)row * ldr + row]);
+      o[e] = v + dfix * Vb[(long long)row * LD + col];
+      Vout[(long long)b * strideVout + (long long)row * LD + col] = o[e];
     }
-    if (Pout) {   // rows 4 lq .. 4 lq + 3 of the wave = four consecutive k of the next product: 8 bytes per plane
-      unsigned h[4], m[4], l[4];
-#pragma unroll
-      for (int r = 0; r < 4; ++r) split3(o[r], h[r], m[r], l[r]);
-      unsigned short* P = Pout + (long long)b * stridePout + plane_offset<LD>(row0 + 4 * lq, col);
-      *(u32x2*)P = (u32x2){(h[0] >> 16) | h[1], (h[2] >> 16) | h[3]};
-      *(u32x2*)(P + (long long)LD * PCH) = (u32x2){(m[0] >> 16) | m[1], (m[2] >> 16) | m[3]};
-      *(u32x2*)(P + 2ll * LD * PCH) = (u32x2){(l[0] >> 16) | l[1], (l[2] >> 16) | l[3]};
+    if (Pout) {
+      u32x4 hi, mid, lo;
+      split3x8(o, hi, mid, lo);
+      unsigned short* P = Pout + (long long)b * stridePout + plane_offset<LD>(row0 + 8 * u8, col);
+      *(u32x4*)P = hi;
+      *(u32x4*)(P + (long long)LD * PCH) = mid;
+      *(u32x4*)(P + 2ll * LD * PCH) = lo;
     }
   }
 }
@@ -376,16 +416,11 @@ __global__ __launch_bounds__(NT) void split_planes_kernel(const float* __restric
   const int task = blockIdx.x * NT + threadIdx.x;   // (unit of eight k, column)
   const int col = task % LD, u = task / LD;
   if (u >= n / 8) return;
-  u32x4 hi, mid, lo;
+  float v[8];
 #pragma unroll
-  for (int w = 0; w < 4; ++w) {
-    unsigned h0, m0, l0, h1, m1, l1;
-    split3(V[mat + (long long)(8 * u + 2 * w) * LD + col], h0, m0, l0);
-    split3(V[mat + (long long)(8 * u + 2 * w + 1) * LD + col], h1, m1, l1);
-    hi[w] = (h0 >> 16) | h1;
-    mid[w] = (m0 >> 16) | m1;
-    lo[w] = (l0 >> 16) | l1;
-  }
+  for (int e = 0; e < 8; ++e) v[e] = V[mat + (long long)(8 * u + e) * LD + col];
+  u32x4 hi, mid, lo;
+  split3x8(v, hi, mid, lo);
   unsigned short* o = P + mat * 3 + plane_offset<LD>(8 * u, col);
   *(u32x4*)o = hi;
   *(u32x4*)(o + (long long)LD * PCH) = mid;
@@ -600,18 +635,18 @@ bool chain_takes_small_kernel(int n, int ld, int batch, bool rb) {
 
 bool chain_bf16_supported(int n, int ld, int batch, int ldr) {
   const bool small = ld <= 32 && (long long)(n / ROWS) * batch < small_below(true);
-  return (ld == 16 || ld == 32) && ldr % 8 == 0 && n % KC == 0 && (small || n % 128 == 0);
+  return (ld == 16 || ld == 32) && ldr % 8 == 0 && n % KC == 0 && (small || n % PCH == 0);
 }
 
 // 64-row kernel for bf16 R: V comes as fp32 (for the diagonal term) and as planes; the result is written
-// as fp32 and, when Pout is given, as planes for the next product.  n a multiple of 128.
+// as fp32 and, when Pout is given, as planes for the next product.  n a multiple of 256.
 int launch_chain_planes(const unsigned short* Rb, long long strideR, int ldr, const float* D, long long strideD, int ldd,
                         const float* Vin, long long strideVin, const unsigned short* Pin, long long stridePin, float* Vout,
                         long long strideVout, unsigned short* Pout, long long stridePout, int n, int ld, int batch,
                         const Ctrl* ctrl, hipStream_t s) {
   if (!Rb || !D || !Vin || !Pin || !Vout || n % PCH || ldr % 8 || batch <= 0 || (ld != 16 && ld != 32)) return PRISM_EINVAL;
   const dim3 grid(n / ROWS, batch), block(NT);
-  const int lds = 4 * 3 * ld * 256;   // STAGES stages of three planes
+  const int lds = 3 * 3 * ld * 512;   // STAGES stages of three planes, 256 k each
   const int rc = allow_dynamic_lds(ld == 16 ? (const void*)chain_planes_kernel<16> : (const void*)chain_planes_kernel<32>, lds);
   if (rc != PRISM_OK) return rc;
   if (ld == 16) hipLaunchKernelGGL((chain_planes_kernel<16>), grid, block, lds, s, Rb, strideR, ldr, D, strideD, ldd, Vin, strideVin, Pin, stridePin, Vout, strideVout, Pout, stridePout, n, ctrl);

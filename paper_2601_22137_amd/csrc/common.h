@@ -132,7 +132,7 @@ int launch_chain_tiny(const float* R, long long strideR, int ldr, const float* V
                       long long strideJ, long long strideB, int nv, int ld, int batch, const Ctrl* ctrl, hipStream_t s);
 bool chain_bf16_supported(int n, int ld, int batch, int ldr);
 // bf16 R, launches too large for the 16-row kernel: V is read as three bf16 planes (the exact 8 + 8 + 8 bit
-// split of its fp32 entries) laid out [matrix][k / 128][plane][column][unit ^ (column % 16)][8 k]; Vin (fp32) serves the
+// split of its fp32 entries) laid out [matrix][k / 256][plane][column][unit'][8 k] (chain.hip); Vin (fp32) serves the
 // diagonal term; the result goes to Vout (fp32) and, if Pout is given, to planes for the next product.
 int launch_chain_planes(const unsigned short* Rb, long long strideR, int ldr, const float* D, long long strideD, int ldd,
                         const float* Vin, long long strideVin, const unsigned short* Pin, long long stridePin, float* Vout,

@@ -340,7 +340,8 @@ struct Run {
   bool fit_needed(int k) const { return P.p_s > 0 && k >= first_fit && k < max_iters; }
   // bf16 chain products too large for the 16-row kernel read V as bf16 planes
   bool planes() const {
-    return vp0 && !chain_takes_small_kernel(P.Sp, P.ld, chain_sel_batch ? chain_sel_batch : P.batch, true);
+    const int sel = chain_sel_batch ? chain_sel_batch : P.batch;
+    return vp0 && chain_bf16_supported(P.Sp, P.ld, sel, P.Sp) && !chain_takes_small_kernel(P.Sp, P.ld, sel, true);
   }
 };
 

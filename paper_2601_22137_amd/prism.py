@@ -303,7 +303,7 @@ def release_workspaces():
 
 def chain_product_bf16(Rb, R, V, return_planes=False):
     """out = (Rb + diag(R - Rb)) V.  With return_planes also the scratch array of the call: bf16 bit
-    patterns [2][batch][n / 128][3][ld][16 units, xor-ed with column % 16][8], the planes of V and of out (zeros where the launch is
+    patterns [2][batch][n / 256][3][ld][32 units, low four bits xor-ed with the column][8], the planes of V and of out (zeros where the launch is
     small enough for the kernel that does not use them)."""
     batch, n, ld = V.shape
     out = torch.empty_like(V)

@@ -38,9 +38,9 @@ def test_gemm_f32(prism, a_km, shape):
 def test_chain_product_bf16(prism, n, ld, batch):
     """Off-diagonal entries from the bf16 copy, diagonal from the fp32 matrix; R = I - small, the
     case in which a rounded diagonal would be wrong by more than the whole off-diagonal part.
-    Small batches take the 16-row kernel, (n / 64) * batch >= 128 the 64-row one (chunks of 128 k,
+    Small batches take the 16-row kernel, (n / 64) * batch >= 128 the 64-row one (chunks of 256 k,
     with and without a ragged last ring round; V and the result also as bf16 planes); the widest sketch (ld = 64) and large batches of sizes
-    that are no multiple of 128 are not taken (the library keeps to the fp32 matrix there)."""
+    that are no multiple of 256 are not taken (the library keeps to the fp32 matrix there)."""
     rng = np.random.default_rng(3 * n + ld)
     R = np.empty((batch, n, n), dtype=np.float32)
     for b in range(batch):
@@ -50,7 +50,7 @@ def test_chain_product_bf16(prism, n, ld, batch):
     Rb = W.to_bf16_bits(R)
     rb_dev = torch.from_numpy(Rb.view(np.int16)).cuda()
     small = ld <= 32 and (n // 64) * batch < 128
-    if ld == 64 or (not small and n % 128):
+    if ld == 64 or (not small and n % 256):
         with pytest.raises(prism.PrismError, match="UNSUPPORTED"):
             prism.chain_product_bf16(rb_dev, _dev(R), _dev(V))
         return
@@ -58,10 +58,12 @@ def test_chain_product_bf16(prism, n, ld, batch):
     out = out.cpu().numpy()
     if not small:
         # the launch read V as three bf16 planes and wrote its result that way too: each is the exact
-        # 8 + 8 + 8 bit split of the fp32 array, laid out [matrix][k / 128][plane][column][unit ^ (column % 16)][8 k]
-        pl = planes.cpu().numpy().view(np.uint16).reshape(2, batch, n // 128, 3, ld, 16, 8)
-        unswz = np.arange(16)[None, :] ^ (np.arange(ld)[:, None] % 16)            # [column][unit] -> stored unit
-        pl = np.take_along_axis(pl, unswz[None, None, None, None, :, :, None], axis=5).reshape(2, batch, n // 128, 3, ld, 128)
+        # 8 + 8 + 8 bit split of the fp32 array, laid out [matrix][k / 256][plane][column][unit'][8 k] with
+        # unit' = (unit & 16) | ((unit ^ column) & 15)
+        pl = planes.cpu().numpy().view(np.uint16).reshape(2, batch, n // 256, 3, ld, 32, 8)
+        unit = np.arange(32)[None, :]
+        stored = (unit & 16) | ((unit ^ np.arange(ld)[:, None]) & 15)                # [column][unit] -> stored unit
+        pl = np.take_along_axis(pl, stored[None, None, None, None, :, :, None], axis=5).reshape(2, batch, n // 256, 3, ld, 256)
         for which, arr in ((0, V), (1, out)):
             parts = W.from_bf16_bits(pl[which]).astype(np.float64)              # [batch][c][plane][col][k]
             total = parts.sum(axis=2).transpose(0, 1, 3, 2).reshape(batch, n, ld)
