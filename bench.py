@@ -61,7 +61,8 @@ def parse():
                          "of the per-kernel pass, for profiler runs in which no kernel is stretched by a neighbour")
     ap.add_argument("--gemm-probe", type=int, default=0, metavar="TILE",
                     help="only run the bare bf16 product 8 x 4096^3 (no epilogue work beyond the fp32 store) ten times with "
-                         "tile 256, 2561 (256 x 128) or 128, and print its rate: the kernel under the profiler's counters")
+                         "tile 256, 2561 (256 x 128) or 128 (+ 10000: both operands stored [K][M] / [K][N], + 20000: the second "
+                         "only), and print its rate: the kernel under the profiler's counters")
     ap.add_argument("--copy-probe", action="store_true",
                     help="only copy 1 GiB device to device three times (calibrates the FETCH_SIZE / WRITE_SIZE counters)")
     return ap.parse_args()
@@ -449,12 +450,15 @@ def main():
         gen = torch.Generator(device="cuda").manual_seed(1)
         a = torch.randn(8, 4096, 4096, device="cuda", generator=gen).to(torch.bfloat16)
         b = torch.randn(8, 4096, 4096, device="cuda", generator=gen).to(torch.bfloat16)
-        prism.gemm_bf16_nt(a, b, args.gemm_probe)
+        # + 10000: both operands stored with K as the slow index, + 20000: the second one only
+        km = 3 if 10000 <= args.gemm_probe < 20000 else (2 if args.gemm_probe >= 20000 else 0)
+        tile = args.gemm_probe % 10000
+        prism.gemm_bf16_nt(a, b, tile, km)
         torch.cuda.synchronize()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
         for _ in range(10):
-            prism.gemm_bf16_nt(a, b, args.gemm_probe)
+            prism.gemm_bf16_nt(a, b, tile, km)
         e1.record()
         torch.cuda.synchronize()
         ms = e0.elapsed_time(e1) / 10
