@@ -211,6 +211,16 @@ struct FinalArgs {
 };
 void launch_finalize(const FinalArgs& a, hipStream_t s);
 
+// The per-matrix reports of a launch sequence over several shape groups sit in one array; each group's
+// part goes to the array its caller gave (one launch instead of a copy per group).
+struct InfoScatter {
+  const prism_info* src;
+  prism_info* dst[BF16_MAX_GROUPS];   // null: the group wants no report
+  int first[BF16_MAX_GROUPS + 1];     // group g owns matrices [first[g], first[g + 1])
+  int ngroups;
+};
+void launch_scatter_info(const InfoScatter& a, hipStream_t s);
+
 // Second pass of a split-K Gram product: R = I - sum_p part_p (zero outside the leading n x n block),
 // summed in part order, exactly symmetric (the lower triangle is the mirror image of the upper one).
 struct GramReduceArgs {

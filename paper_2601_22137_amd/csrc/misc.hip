@@ -446,4 +446,22 @@ void launch_finalize(const FinalArgs& a, hipStream_t s) {
   hipLaunchKernelGGL(finalize_kernel, dim3((unsigned)((mat + NT - 1) / NT), a.batch), dim3(NT), 0, s, a);
 }
 
+namespace {
+__global__ __launch_bounds__(256) void scatter_info_kernel(InfoScatter a) {
+  const int words = (int)(sizeof(prism_info) / 4);
+  for (int g = 0; g < a.ngroups; ++g) {
+    if (!a.dst[g]) continue;
+    const unsigned* src = (const unsigned*)(a.src + a.first[g]);
+    unsigned* dst = (unsigned*)a.dst[g];
+    const int n = (a.first[g + 1] - a.first[g]) * words;
+    for (int i = blockIdx.x * 256 + threadIdx.x; i < n; i += gridDim.x * 256) dst[i] = src[i];
+  }
+}
+}  // namespace
+
+void launch_scatter_info(const InfoScatter& a, hipStream_t s) {
+  static_assert(sizeof(prism_info) % 4 == 0, "reports are copied word by word");
+  hipLaunchKernelGGL(scatter_info_kernel, dim3(8), dim3(256), 0, s, a);
+}
+
 }  // namespace prism

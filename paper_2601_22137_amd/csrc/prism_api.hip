@@ -1026,17 +1026,18 @@ int run_polar_bf16_shapes(const prism_group* groups, int ngroups, int degree, in
   rc = check_hip();
   if (rc != PRISM_OK) return rc;
   // the reports were written into one array over all matrices: hand each group its part
+  InfoScatter sc = {};
+  sc.src = r.info; sc.ngroups = ngroups;
+  bool wanted = false;
   boff = 0;
   for (int g = 0; g < ngroups; ++g) {
-    if (groups[g].info &&
-        hipMemcpyAsync(groups[g].info, r.info + boff, (size_t)groups[g].batch * sizeof(prism_info), hipMemcpyDeviceToDevice, r.s) != hipSuccess) {
-      (void)hipGetLastError();
-      set_last_error("copying the per-matrix reports failed");
-      return PRISM_EHIP;
-    }
+    sc.dst[g] = groups[g].info; sc.first[g] = (int)boff;
+    wanted = wanted || groups[g].info;
     boff += groups[g].batch;
   }
-  return PRISM_OK;
+  sc.first[ngroups] = (int)boff;
+  if (wanted) launch_scatter_info(sc, r.s);
+  return check_hip();
 }
 
 // Internal streams of the grouped call, per device, created on first use (default priority).
