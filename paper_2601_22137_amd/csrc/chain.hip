@@ -259,8 +259,11 @@ template <int N> __device__ inline void wait_vmcnt() {
   __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | 0x0F70);
 }
 
-template <int LD>
-__global__ __launch_bounds__(NT, 1) void chain_planes_kernel(const unsigned short* __restrict__ R, long long strideR, int ldr,
+// RG row groups of 64 rows per workgroup (4 RG wavefronts): with RG = 2 a stage of V serves 128 rows, and
+// a launch fills half as many CUs at about the same speed, which leaves the others to whatever else is
+// running (the products of another part of the batch).
+template <int LD, int RG>
+__global__ __launch_bounds__(NT * RG, 1) void chain_planes_kernel(const unsigned short* __restrict__ R, long long strideR, int ldr,
                                                           const float* __restrict__ R32, long long strideR32, int ldr32,
                                                           const float* __restrict__ Vin, long long strideVin,
                                                           const unsigned short* __restrict__ Pin, long long stridePin,
@@ -270,29 +273,34 @@ __global__ __launch_bounds__(NT, 1) void chain_planes_kernel(const unsigned shor
   constexpr int NBLK = LD / 16;
   constexpr int STAGES = 3;
   constexpr int STAGE_BYTES = 3 * LD * 512;
-  constexpr int VL = STAGE_BYTES / 4096;         // direct-to-LDS instructions per wave and chunk
+  constexpr int NW = 4 * RG;                     // wavefronts
+  constexpr int VL = STAGE_BYTES / (1024 * NW);  // direct-to-LDS instructions per wave and chunk
   constexpr int NL = 8 + VL;                     // loads per wave and chunk
-  static_assert(STAGE_BYTES % 4096 == 0, "sketch width");
-  static_assert(4 * ROWS * (LD + 1) * 4 <= STAGES * STAGE_BYTES, "the partial sums reuse the stages");
+  constexpr int WROWS = ROWS * RG;               // rows per workgroup
+  static_assert(STAGE_BYTES % (1024 * NW) == 0, "sketch width");
+  static_assert(4 * WROWS * (LD + 1) * 4 <= STAGES * STAGE_BYTES, "the partial sums reuse the stages");
   extern __shared__ __align__(1024) unsigned char Vt[];       // [STAGES][STAGE_BYTES]
   const int b = blockIdx.y;
   if (ctrl && ctrl[b].done) return;
   const int t = threadIdx.x, lane = t & 63;
   const int wave = __builtin_amdgcn_readfirstlane(t >> 6);   // uniform: LDS destinations stay scalar
   const int li = lane & 15, lq = lane >> 4;
-  const int row0 = blockIdx.x * ROWS;
+  const int kq = wave & 3, rg = wave >> 2;       // quarter of the k of a chunk, row group
+  const int row0 = blockIdx.x * WROWS;           // first row of the workgroup
   const unsigned short* Rmat = R + (long long)b * strideR;
-  const unsigned short* Rk = Rmat + 64 * wave + 8 * lq;            // this lane's k within a chunk
-  const long long rrow = (long long)(row0 + li) * ldr;              // ... and its row of block q = 0
+  const unsigned short* Rk = Rmat + 64 * kq + 8 * lq;                         // this lane's k within a chunk
+  const long long rrow = (long long)(row0 + ROWS * rg + li) * ldr;             // ... and its row of block q = 0
   const char* Pmat = (const char*)(Pin + (long long)b * stridePin);
   const int poff = wave * 1024 + lane * 16;
   const int nchunks = n / PCH;
   // The workgroups of one matrix all read the same V.  Those that share an L2 (workgroups are dealt
   // round-robin to the 8 XCDs) sweep k in step, so that a chunk of V is fetched once per XCD and
   // found there by the others before the stream of R has pushed it out; the XCDs start at chunks of
-  // their own and ask different memory channels at any moment.
-  const int xcd = (int)((blockIdx.x + gridDim.x * blockIdx.y) & 7u);
-  const int rot = (int)((unsigned)(xcd * nchunks) / 8u);
+  // their own and ask different memory channels at any moment.  The starting chunk is a function of
+  // the row alone (128-row block modulo 8: the XCD of a 128-row workgroup when the row blocks of a
+  // matrix are a multiple of 8), so that the order of summation, hence the bits of a result, do not
+  // depend on the launch a matrix is part of.
+  const int rot = (int)((unsigned)(((row0 / (2 * ROWS)) & 7) * nchunks) / 8u);
 
   u32x4 ra[STAGES][4][2];
   // Requests are unconditional, so that the compiler can count how many younger ones may stay in
@@ -303,11 +311,11 @@ __global__ __launch_bounds__(NT, 1) void chain_planes_kernel(const unsigned shor
     int c = c_want + rot;
     if (c >= nchunks) c -= nchunks;
     const long long pbase = valid ? (long long)c * STAGE_BYTES + poff : 0;
-    const int pstep = valid ? 4096 : 0;
+    const int pstep = valid ? 1024 * NW : 0;
 #pragma unroll
     for (int i = 0; i < VL; ++i)
       __builtin_amdgcn_global_load_lds((gptr_t)(Pmat + pbase + i * pstep),
-                                       (lptr_t)(Vt + slot * STAGE_BYTES + wave * 1024 + i * 4096), 16, 0, 0);
+                                       (lptr_t)(Vt + slot * STAGE_BYTES + wave * 1024 + i * (1024 * NW)), 16, 0, 0);
     const long long rbase = valid ? rrow + c * PCH : 0;
     const long long qstep = valid ? 16ll * ldr : 0;
 #pragma unroll
@@ -336,24 +344,24 @@ __global__ __launch_bounds__(NT, 1) void chain_planes_kernel(const unsigned shor
   for (int d = 0; d < STAGES - 1; ++d) load_chunk(d, d);
   stage_barrier();
   // fragment addresses within a stage: row (plane, column 16 jb + li), unit 8 w + 4 h + lq with its low bits xor li
-  const unsigned char* fr = Vt + li * 512 + (wave >> 1) * 256;
-  const int fu0 = (((8 * wave + lq) ^ li) & 15) * 16, fu1 = (((8 * wave + 4 + lq) ^ li) & 15) * 16;
+  const unsigned char* fr = Vt + li * 512 + (kq >> 1) * 256;
+  const int fu0 = (((8 * kq + lq) ^ li) & 15) * 16, fu1 = (((8 * kq + 4 + lq) ^ li) & 15) * 16;
   auto step = [&](auto dtag, int c) {   // chunk c, in ring slot d = c % STAGES
     constexpr int d = decltype(dtag)::value;
     __builtin_amdgcn_sched_barrier(0);
     load_chunk((d + STAGES - 1) % STAGES, c + STAGES - 1);   // into the stage chunk c - 1 was read from
     __builtin_amdgcn_sched_barrier(0);
-    u32x4 fb[2][3][NBLK];
+    // the fragments of one half of the wave's k at a time (with two wavefronts per SIMD the other one
+    // covers the wait)
 #pragma unroll
-    for (int h = 0; h < 2; ++h)
+    for (int h = 0; h < 2; ++h) {
+      u32x4 fb[3][NBLK];
 #pragma unroll
       for (int p = 0; p < 3; ++p)
 #pragma unroll
         for (int j = 0; j < NBLK; ++j)
-          fb[h][p][j] = *(const u32x4*)(fr + d * STAGE_BYTES + (p * LD + 16 * j) * 512 + (h ? fu1 : fu0));
-    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-    for (int h = 0; h < 2; ++h)
+          fb[p][j] = *(const u32x4*)(fr + d * STAGE_BYTES + (p * LD + 16 * j) * 512 + (h ? fu1 : fu0));
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int p = 0; p < 3; ++p)
 #pragma unroll
@@ -361,7 +369,9 @@ __global__ __launch_bounds__(NT, 1) void chain_planes_kernel(const unsigned shor
 #pragma unroll
           for (int q = 0; q < 4; ++q)
             acc[q][j][p] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ra[d][q][h]),
-                                                                   __builtin_bit_cast(bf16x8, fb[h][p][j]), acc[q][j][p], 0, 0, 0);
+                                                                   __builtin_bit_cast(bf16x8, fb[p][j]), acc[q][j][p], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+    }
     stage_barrier();
   };
   const int nfull = nchunks / STAGES * STAGES;
@@ -373,19 +383,19 @@ __global__ __launch_bounds__(NT, 1) void chain_planes_kernel(const unsigned shor
   wait_vmcnt<0>();   // the requests past the end write into this workgroup's LDS: none may outlive it
   __syncthreads();   // ... nor the reuse of the stages below
   // partial sums of this wave's k (small pieces first), added up in wave order
-  float (*red)[ROWS][LD + 1] = (float (*)[ROWS][LD + 1])Vt;
+  float (*red)[WROWS][LD + 1] = (float (*)[WROWS][LD + 1])Vt;
 #pragma unroll
   for (int q = 0; q < 4; ++q)
 #pragma unroll
     for (int j = 0; j < NBLK; ++j)
 #pragma unroll
       for (int r = 0; r < 4; ++r)
-        red[wave][16 * q + 4 * lq + r][16 * j + li] = (acc[q][j][2][r] + acc[q][j][1][r]) + acc[q][j][0][r];
+        red[kq][ROWS * rg + 16 * q + 4 * lq + r][16 * j + li] = (acc[q][j][2][r] + acc[q][j][1][r]) + acc[q][j][0][r];
   __syncthreads();
   // thread = (column, eight consecutive rows): the rows are the k of the next product, so the thread
   // owns one 16-byte unit of each plane of the result
   const int col = t % LD, u8 = t / LD;
-  if (u8 < ROWS / 8) {
+  if (u8 < WROWS / 8) {
     const float* Vb = Vin + (long long)b * strideVin;
     float o[8];
 #pragma unroll
@@ -643,14 +653,20 @@ bool chain_bf16_supported(int n, int ld, int batch, int ldr) {
 int launch_chain_planes(const unsigned short* Rb, long long strideR, int ldr, const float* D, long long strideD, int ldd,
                         const float* Vin, long long strideVin, const unsigned short* Pin, long long stridePin, float* Vout,
                         long long strideVout, unsigned short* Pout, long long stridePout, int n, int ld, int batch,
-                        const Ctrl* ctrl, hipStream_t s) {
+                        const Ctrl* ctrl, hipStream_t s, int sel_batch) {
   if (!Rb || !D || !Vin || !Pin || !Vout || n % PCH || ldr % 8 || batch <= 0 || (ld != 16 && ld != 32)) return PRISM_EINVAL;
-  const dim3 grid(n / ROWS, batch), block(NT);
   const int lds = 3 * 3 * ld * 512;   // STAGES stages of three planes, 256 k each
-  const int rc = allow_dynamic_lds(ld == 16 ? (const void*)chain_planes_kernel<16> : (const void*)chain_planes_kernel<32>, lds);
+  // 128-row workgroups when they still fill at least half the chip (judged by sel_batch, see launch_chain)
+  const bool two = n % (2 * ROWS) == 0 && (long long)(n / (2 * ROWS)) * (sel_batch > 0 ? sel_batch : batch) >= 128;
+  const void* kern = two ? (ld == 16 ? (const void*)chain_planes_kernel<16, 2> : (const void*)chain_planes_kernel<32, 2>)
+                         : (ld == 16 ? (const void*)chain_planes_kernel<16, 1> : (const void*)chain_planes_kernel<32, 1>);
+  const int rc = allow_dynamic_lds(kern, lds);
   if (rc != PRISM_OK) return rc;
-  if (ld == 16) hipLaunchKernelGGL((chain_planes_kernel<16>), grid, block, lds, s, Rb, strideR, ldr, D, strideD, ldd, Vin, strideVin, Pin, stridePin, Vout, strideVout, Pout, stridePout, n, ctrl);
-  else hipLaunchKernelGGL((chain_planes_kernel<32>), grid, block, lds, s, Rb, strideR, ldr, D, strideD, ldd, Vin, strideVin, Pin, stridePin, Vout, strideVout, Pout, stridePout, n, ctrl);
+  const dim3 grid(n / (two ? 2 * ROWS : ROWS), batch), block(two ? 2 * NT : NT);
+#define PRISM_LAUNCH_PLANES(LD_, RG_) hipLaunchKernelGGL((chain_planes_kernel<LD_, RG_>), grid, block, lds, s, Rb, strideR, ldr, D, strideD, ldd, Vin, strideVin, Pin, stridePin, Vout, strideVout, Pout, stridePout, n, ctrl)
+  if (two) { if (ld == 16) PRISM_LAUNCH_PLANES(16, 2); else PRISM_LAUNCH_PLANES(32, 2); }
+  else { if (ld == 16) PRISM_LAUNCH_PLANES(16, 1); else PRISM_LAUNCH_PLANES(32, 1); }
+#undef PRISM_LAUNCH_PLANES
   return hipGetLastError() == hipSuccess ? PRISM_OK : PRISM_EHIP;
 }
 

@@ -137,7 +137,7 @@ bool chain_bf16_supported(int n, int ld, int batch, int ldr);
 int launch_chain_planes(const unsigned short* Rb, long long strideR, int ldr, const float* D, long long strideD, int ldd,
                         const float* Vin, long long strideVin, const unsigned short* Pin, long long stridePin, float* Vout,
                         long long strideVout, unsigned short* Pout, long long stridePout, int n, int ld, int batch,
-                        const Ctrl* ctrl, hipStream_t s);
+                        const Ctrl* ctrl, hipStream_t s, int sel_batch = 0);
 int launch_split_planes(const float* V, unsigned short* P, int n, int ld, int count, hipStream_t s);
 int launch_chain_bf16(const unsigned short* Rb, long long strideR, int ldr, const float* D, long long strideD, int ldd,
                       const float* Vin, long long strideVin, float* Vout, long long strideVout, int n, int ld, int batch,

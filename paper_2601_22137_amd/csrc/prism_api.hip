@@ -305,7 +305,7 @@ struct Run {
         const uint16_t* pin = (j == 1) ? vp0 + (long long)(k - first_fit) * pe : vp + (long long)(j - 2) * P.batch * pe;
         uint16_t* pout = j < P.nv ? vp + (long long)(j - 1) * P.batch * pe : nullptr;
         CHECK_LAUNCH(launch_chain_planes(Rb, (long long)Sp * Sp, Sp, D, strideD, ldd, vin, sin, pin, j == 1 ? 0 : pe,
-                                         v + (j - 1) * vs, (long long)Sp * ld, pout, pe, Sp, ld, P.batch, ctrl, s));
+                                         v + (j - 1) * vs, (long long)Sp * ld, pout, pe, Sp, ld, P.batch, ctrl, s, chain_sel_batch));
       } else if (Rb)
         CHECK_LAUNCH(launch_chain_bf16(Rb, (long long)Sp * Sp, Sp, D, strideD, ldd, vin, sin, v + (j - 1) * vs,
                                        (long long)Sp * ld, Sp, ld, P.batch, ctrl, s, chain_sel_batch));
