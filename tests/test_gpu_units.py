@@ -34,7 +34,10 @@ def test_gemm_f32(prism, a_km, shape):
 
 
 @pytest.mark.parametrize("n,ld,batch", [(64, 16, 2), (192, 32, 2), (768, 16, 2), (1024, 32, 2), (4096, 32, 2),
-                                        (1024, 16, 16), (2048, 32, 8), (1152, 32, 15), (768, 16, 12), (1088, 32, 16), (2048, 64, 2)])
+                                        (1024, 16, 16), (2048, 32, 8), (1152, 32, 15), (768, 16, 12), (1088, 32, 16), (2048, 64, 2),
+                                        # one and two chunks of 256 k (shorter than the kernel's ring), 128-row workgroups
+                                        # with a ragged number of ring rounds
+                                        (256, 16, 40), (512, 32, 20), (1280, 32, 13), (256, 32, 70)])
 def test_chain_product_bf16(prism, n, ld, batch):
     """Off-diagonal entries from the bf16 copy, diagonal from the fp32 matrix; R = I - small, the
     case in which a rounded diagonal would be wrong by more than the whole off-diagonal part.
