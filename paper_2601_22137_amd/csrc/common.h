@@ -106,6 +106,7 @@ struct Bf16Multi {
   int tile_start[BF16_MAX_GROUPS + 1];               // set by the launcher
   int ngroups;
   int xcd_private;                                   // set by the launcher: contiguous tile ranges per XCD
+  int waves8;                                        // set by the launcher: 256 x 256 tiles run with eight wavefronts
 };
 // tile_m x tile_n: 256 x 256, 256 x 128 or 128 x 128; M, N of every group must be multiples of them
 int launch_gemm_bf16(const Bf16Desc& g, int tile_m, int tile_n, hipStream_t s);

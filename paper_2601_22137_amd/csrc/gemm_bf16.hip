@@ -59,13 +59,18 @@ template <int N> __device__ inline void wait_vmcnt() {
 // read from the [L][S] iterate itself, no transposed copy).  The slabs then sit in LDS as [k][row]
 // and the fragments are read with ds_read_b64_tr_b16, which hands every lane of a 16-lane group four
 // consecutive k of one row out of four 32-byte row segments (see below).
-template <int TM, int TN, int EPI, bool SYM, bool KMA, bool KMB>
-__global__ __launch_bounds__(NT, wgs_per_cu(TM, TN)) void gemm_bf16_kernel(Bf16Multi mg) {
+// NW wavefronts per workgroup: 4 (2 x 2) or 8 (2 x 4: the 256 x 256 tile with two wavefronts per
+// SIMD, each 128 x 64, so that the matrix pipe has a second wave to issue from whenever one waits at
+// a barrier, for its fragments or for a slab).
+template <int TM, int TN, int EPI, bool SYM, bool KMA, bool KMB, int NW>
+__global__ __launch_bounds__(64 * NW, (NW == 8 ? 1 : wgs_per_cu(TM, TN))) void gemm_bf16_kernel(Bf16Multi mg) {
   constexpr bool KM = KMA || KMB;   // some fragment reads are transposing ones
   constexpr int STAGES = stages_of(TM, TN);
-  constexpr int WTM = TM / 2, WTN = TN / 2;      // wave tile (2 x 2 waves)
+  constexpr int WCOLS = NW / 2;                  // wavefronts side by side
+  constexpr int WTM = TM / 2, WTN = TN / WCOLS;  // wave tile (2 x WCOLS waves)
   constexpr int NBM = WTM / 32, NBN = WTN / 32;  // 32x32 blocks per wave and dimension
-  constexpr int LDA = TM / 64, LDB = TN / 64;    // direct-to-LDS load instructions per wave, operand and slab
+  constexpr int LDA = TM / (16 * NW), LDB = TN / (16 * NW);   // direct-to-LDS load instructions per wave, operand and slab
+  static_assert(NW == 4 || (NW == 8 && TM == 256 && TN == 256), "wavefronts per workgroup");
   constexpr int NL = LDA + LDB;                  // ... per wave and slab
   constexpr int OPA_BYTES = TM * 64;             // operand slabs in LDS: rows x 32 bf16, unpadded
   constexpr int BUF_BYTES = (TM + TN) * 64;
@@ -124,7 +129,7 @@ __global__ __launch_bounds__(NT, wgs_per_cu(TM, TN)) void gemm_bf16_kernel(Bf16M
 
   const int t = threadIdx.x, lane = t & 63;
   const int wave = __builtin_amdgcn_readfirstlane(t >> 6);  // uniform: LDS destinations stay scalar
-  const int wm0 = (wave >> 1) * WTM, wn0 = (wave & 1) * WTN;
+  const int wm0 = (wave / WCOLS) * WTM, wn0 = (wave % WCOLS) * WTN;
   const int m0 = tm * TM, n0 = tn * TN;
   const unsigned short* A1 = g.A + (long long)b * g.strideA + (KMA ? (long long)m0 : (long long)m0 * g.lda);
   const unsigned short* Bb = g.B + (long long)b * g.strideB + (KMB ? (long long)n0 : (long long)n0 * g.ldb);
@@ -134,7 +139,7 @@ __global__ __launch_bounds__(NT, wgs_per_cu(TM, TN)) void gemm_bf16_kernel(Bf16M
   // Global -> LDS without passing through registers (global_load_lds_dwordx4): one wave
   // instruction moves 64 lanes x 16 bytes into 1 KiB of consecutive LDS = 16 rows of a slab.
   // Lane l fills slot l & 15 of line l >> 4 of those 16 rows and fetches the chunk that belongs
-  // there (the line index within the slab is (it * 4 + wave) * 4 + (l >> 4)).
+  // there (the line index within the slab is (it * NW + wave) * 4 + (l >> 4)).
   // KM: a slab is 32 k-rows of T consecutive entries; one wave instruction moves 64 / (T / 8) of
   // them.  16-byte unit u of row k holds chunk u ^ (4 (k & 3)) of that row, so that the four row
   // segments a transposing read touches (same chunks, rows 4j .. 4j + 3) fall on different banks.
@@ -144,33 +149,33 @@ __global__ __launch_bounds__(NT, wgs_per_cu(TM, TN)) void gemm_bf16_kernel(Bf16M
     constexpr int URA = TM / 8;          // 16-byte units per k-row
 #pragma unroll
     for (int it = 0; it < LDA; ++it) {
-      const int k = (it * 4 + wave) * (64 / URA) + lane / URA, c = (lane % URA) ^ (4 * (k & 3));
+      const int k = (it * NW + wave) * (64 / URA) + lane / URA, c = (lane % URA) ^ (4 * (k & 3));
       aoff[it] = (unsigned)(k * g.lda + c * 8) * 2u;
     }
   } else {
 #pragma unroll
-    for (int it = 0; it < LDA; ++it) aoff[it] = (unsigned)(((it * 4 + wave) * 16 + 4 * lq + (lu >> 2)) * g.lda + (lu & 3) * 8) * 2u;
+    for (int it = 0; it < LDA; ++it) aoff[it] = (unsigned)(((it * NW + wave) * 16 + 4 * lq + (lu >> 2)) * g.lda + (lu & 3) * 8) * 2u;
   }
   if constexpr (KMB) {
     constexpr int URB = TN / 8;
 #pragma unroll
     for (int it = 0; it < LDB; ++it) {
-      const int k = (it * 4 + wave) * (64 / URB) + lane / URB, c = (lane % URB) ^ (4 * (k & 3));
+      const int k = (it * NW + wave) * (64 / URB) + lane / URB, c = (lane % URB) ^ (4 * (k & 3));
       boff[it] = (unsigned)(k * g.ldb + c * 8) * 2u;
     }
   } else {
 #pragma unroll
-    for (int it = 0; it < LDB; ++it) boff[it] = (unsigned)(((it * 4 + wave) * 16 + 4 * lq + (lu >> 2)) * g.ldb + (lu & 3) * 8) * 2u;
+    for (int it = 0; it < LDB; ++it) boff[it] = (unsigned)(((it * NW + wave) * 16 + 4 * lq + (lu >> 2)) * g.ldb + (lu & 3) * 8) * 2u;
   }
   // load instruction u in [0, NL): first the LDA of A, then the LDB of B
   auto issue_load = [&](int kt, int slot, int u) {
     const long long ka = KMA ? (long long)kt * BK * g.lda : (long long)kt * BK;
     const long long kb = KMB ? (long long)kt * BK * g.ldb : (long long)kt * BK;
     if (u < LDA) {
-      unsigned char* dst = smem + slot * BUF_BYTES + wave * 1024 + u * 4096;
+      unsigned char* dst = smem + slot * BUF_BYTES + wave * 1024 + u * (1024 * NW);
       __builtin_amdgcn_global_load_lds((gptr_t)((const char*)(A1 + ka) + aoff[u]), (lptr_t)dst, 16, 0, 0);
     } else {
-      unsigned char* dst = smem + slot * BUF_BYTES + OPA_BYTES + wave * 1024 + (u - LDA) * 4096;
+      unsigned char* dst = smem + slot * BUF_BYTES + OPA_BYTES + wave * 1024 + (u - LDA) * (1024 * NW);
       __builtin_amdgcn_global_load_lds((gptr_t)((const char*)(Bb + kb) + boff[u - LDA]), (lptr_t)dst, 16, 0, 0);
     }
   };
@@ -556,7 +561,11 @@ __global__ __launch_bounds__(NT, wgs_per_cu(TM, TN)) void gemm_bf16_kernel(Bf16M
     __syncthreads();
     if (lane == 0) red[wave] = part;
     __syncthreads();
-    if (t == 0) g.rho_part[(long long)b * per_mat + rem] = red[0] + red[1] + red[2] + red[3];
+    if (t == 0) {
+      float sum = (red[0] + red[1]) + (red[2] + red[3]);
+      if (NW == 8) sum += (red[4] + red[5]) + (red[6] + red[7]);
+      g.rho_part[(long long)b * per_mat + rem] = sum;
+    }
   }
 }
 
@@ -567,8 +576,8 @@ long long tiles_per_matrix(const Bf16Desc& g) {
   return SYM ? (TM / TN) * tm * (tm + 1) / 2 : tm * tn;
 }
 
-template <int TM, int TN, int EPI, bool SYM, bool KMA = false, bool KMB = false>
-int launch_te(Bf16Multi& mg, hipStream_t s) {
+template <int TM, int TN, int EPI, bool SYM, bool KMA, bool KMB, int NW>
+int launch_tw(Bf16Multi& mg, hipStream_t s) {
   long long total = 0;
   for (int i = 0; i < mg.ngroups; ++i) {
     mg.tile_start[i] = (int)total;
@@ -577,10 +586,19 @@ int launch_te(Bf16Multi& mg, hipStream_t s) {
   }
   mg.tile_start[mg.ngroups] = (int)total;
   const size_t lds = (size_t)stages_of(TM, TN) * (TM + TN) * 64;   // ring of STAGES x (A slab + B slab)
-  const int rc = allow_dynamic_lds((const void*)gemm_bf16_kernel<TM, TN, EPI, SYM, KMA, KMB>, (int)lds);
+  const int rc = allow_dynamic_lds((const void*)gemm_bf16_kernel<TM, TN, EPI, SYM, KMA, KMB, NW>, (int)lds);
   if (rc != PRISM_OK) return rc;
-  hipLaunchKernelGGL((gemm_bf16_kernel<TM, TN, EPI, SYM, KMA, KMB>), dim3((unsigned)total), dim3(NT), lds, s, mg);
+  hipLaunchKernelGGL((gemm_bf16_kernel<TM, TN, EPI, SYM, KMA, KMB, NW>), dim3((unsigned)total), dim3(64 * NW), lds, s, mg);
   return hipGetLastError() == hipSuccess ? PRISM_OK : PRISM_EHIP;
+}
+
+// 256 x 256 tiles run with eight wavefronts (mg.waves8), every other shape with four
+template <int TM, int TN, int EPI, bool SYM, bool KMA = false, bool KMB = false>
+int launch_te(Bf16Multi& mg, hipStream_t s) {
+  if constexpr (TM == 256 && TN == 256) {
+    if (mg.waves8) return launch_tw<TM, TN, EPI, SYM, KMA, KMB, 8>(mg, s);
+  }
+  return launch_tw<TM, TN, EPI, SYM, KMA, KMB, 4>(mg, s);
 }
 
 template <int TM, int TN>
@@ -641,6 +659,8 @@ int launch_gemm_bf16_multi(const Bf16Desc* groups, int ngroups, int tile_m, int 
     g.xcd_blocks = !no_blocks && !g.sym && per_mat % 256 == 0 && tm % 4 == 0 && tn % 8 == 0;
   }
   mg.xcd_private = small || operand_bytes <= 128.0 * 1024 * 1024;
+  static const int waves4 = ab_switch("PRISM_BF16_WAVES4");
+  mg.waves8 = !waves4;
   if (tile_m == 256 && tile_n == 256) return launch_t<256, 256>(mg, s);
   if (tile_m == 256 && tile_n == 128) return launch_t<256, 128>(mg, s);
   if (tile_m == 128 && tile_n == 128) return launch_t<128, 128>(mg, s);
