@@ -461,7 +461,8 @@ Tile bf16_tile(const Plan& P, int M, int N, int K, bool symmetric) {
   if (forced == 256) return Tile{256, 256};
   if (forced == 2561) return Tile{256, 128};
   const long long per_mat = symmetric ? (long long)(M / 256) * (M / 256 + 1) / 2 : (long long)(M / 256) * (N / 256);
-  return (per_mat * P.batch >= 192 && K >= 2048) ? bf16_big_tile() : Tile{128, 128};
+  // (32 x 1536^2, five iterations: 3.58 ms with large tiles against 4.18; 64 x 768^2: 1.88 against 1.72)
+  return (per_mat * P.batch >= 192 && K >= 1536) ? bf16_big_tile() : Tile{128, 128};
 }
 
 int run_polar_bf16(Run& r) {
