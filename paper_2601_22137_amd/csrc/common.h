@@ -211,6 +211,11 @@ struct FinalArgs {
   const uint16_t* Xa_hi[2]; const uint16_t* Xa_lo[2];
 };
 void launch_finalize(const FinalArgs& a, hipStream_t s);
+struct PrepMulti { PrepArgs d[BF16_MAX_GROUPS]; int start[BF16_MAX_GROUPS + 1]; int ngroups; };
+struct FinalMulti { FinalArgs d[BF16_MAX_GROUPS]; int start[BF16_MAX_GROUPS + 1]; int ngroups; };
+// one launch each over several shape groups (bf16 polar); false: not applicable, launch group by group
+bool launch_prep_multi(const PrepArgs* groups, int ngroups, hipStream_t s);
+bool launch_finalize_multi(const FinalArgs* groups, int ngroups, hipStream_t s);
 
 // The per-matrix reports of a launch sequence over several shape groups sit in one array; each group's
 // part goes to the array its caller gave (one launch instead of a copy per group).

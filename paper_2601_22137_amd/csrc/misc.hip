@@ -28,12 +28,13 @@ __device__ inline double load_src(const void* src, int dt, long long idx) {
 
 // sumsq_part[b][blockIdx.x] = sum of squares of a strided share of matrix b (fp64).
 // An inf or nan entry makes its partial non-finite, which the prepare step reports.
-__global__ __launch_bounds__(NT) void sumsq_kernel(PrepArgs a) {
-  const int b = blockIdx.y;
+// bx in [0, gx): the share of the matrix, b: the matrix (the launch geometry of a single group, which
+// the launches over several groups reproduce so that every matrix gets the same partial sums)
+__device__ inline void sumsq_body(const PrepArgs& a, int bx, int b, int gx) {
   const long long total = (long long)a.m * a.n;
   const long long base = (long long)b * total;
   double acc = 0.0;
-  const long long first = (long long)blockIdx.x * NT + threadIdx.x, step = (long long)gridDim.x * NT;
+  const long long first = (long long)bx * NT + threadIdx.x, step = (long long)gx * NT;
   if (a.dt == PRISM_BF16 && (total & 7) == 0) {          // 16-byte loads: 8 bf16 at a time
     const u32x4* v = (const u32x4*)((const unsigned short*)a.src + base);
     for (long long i = first; i < total / 8; i += step) {
@@ -63,7 +64,16 @@ __global__ __launch_bounds__(NT) void sumsq_kernel(PrepArgs a) {
   for (int off = 32; off > 0; off >>= 1) acc += __shfl_down(acc, off, 64);
   if (lane == 0) red[wave] = acc;
   __syncthreads();
-  if (threadIdx.x == 0) a.sumsq_part[(long long)b * a.nsum + blockIdx.x] = red[0] + red[1] + red[2] + red[3];
+  if (threadIdx.x == 0) a.sumsq_part[(long long)b * a.nsum + bx] = red[0] + red[1] + red[2] + red[3];
+}
+__global__ __launch_bounds__(NT) void sumsq_kernel(PrepArgs a) { sumsq_body(a, blockIdx.x, blockIdx.y, gridDim.x); }
+// several shape groups in one launch: workgroup -> (group, matrix, share)
+__global__ __launch_bounds__(NT) void sumsq_multi_kernel(PrepMulti m) {
+  int w = blockIdx.x, gi = 0;
+  while (gi + 1 < m.ngroups && w >= m.start[gi + 1]) ++gi;
+  w -= m.start[gi];
+  const PrepArgs& a = m.d[gi];
+  sumsq_body(a, w % a.nsum, w / a.nsum, a.nsum);
 }
 
 // One workgroup per 64 x 64 tile of the padded internal iterate [Lp][Sp].
@@ -166,17 +176,16 @@ __global__ __launch_bounds__(NT) void prepare_kernel(PrepArgs a) {
 // The tile is read with 16-byte loads along the caller's rows, scaled and split into high and low
 // halves; a tall or square matrix goes straight into the internal [Lp][Sp] iterate, a wide one
 // (the iterate is its transpose) through an LDS transpose, everything as 16-byte vectors.
-__global__ __launch_bounds__(NT) void prepare_bf16_kernel(PrepArgs a) {
-  const int b = blockIdx.y;
+__device__ inline void prepare_bf16_body(const PrepArgs& a, int bx, int b) {
   const int tiles_c = (a.transpose ? a.Lp : a.Sp) / 64;             // tiles over the padded, caller-oriented matrix
-  const int tr = blockIdx.x / tiles_c, tc = blockIdx.x % tiles_c;
+  const int tr = bx / tiles_c, tc = bx % tiles_c;
   double ss = 0.0;
   for (int i = 0; i < a.nsum; ++i) ss += a.sumsq_part[(long long)b * a.nsum + i];
   const bool finite = (ss == ss) && ss < 1.0e300;
   const bool zero = finite && ss == 0.0;
   const double norm = sqrt(ss);
   const float scale = (finite && !zero) ? (float)(1.0 / norm) : 0.0f;
-  if (blockIdx.x == 0 && threadIdx.x == 0) {
+  if (bx == 0 && threadIdx.x == 0) {
     Ctrl c;
     c.done = (finite && !zero) ? 0 : 1;
     c.iters = 0;
@@ -188,7 +197,7 @@ __global__ __launch_bounds__(NT) void prepare_bf16_kernel(PrepArgs a) {
     a.info[b].iters = 0;
     a.info[b].status = c.status;
   }
-  if (blockIdx.x == 0) {
+  if (bx == 0) {
     for (int i = threadIdx.x; i <= PRISM_MAX_ITERS; i += NT) a.info[b].residual[i] = -1.0f;
     for (int i = threadIdx.x; i < PRISM_MAX_ITERS; i += NT) a.info[b].alpha[i] = 0.0f;
   }
@@ -239,12 +248,20 @@ __global__ __launch_bounds__(NT) void prepare_bf16_kernel(PrepArgs a) {
     if (a.Xa_lo) *(u32x4*)(a.Xa_lo + o) = lo;
   }
 }
+__global__ __launch_bounds__(NT) void prepare_bf16_kernel(PrepArgs a) { prepare_bf16_body(a, blockIdx.x, blockIdx.y); }
+__global__ __launch_bounds__(NT) void prepare_bf16_multi_kernel(PrepMulti m) {
+  int w = blockIdx.x, gi = 0;
+  while (gi + 1 < m.ngroups && w >= m.start[gi + 1]) ++gi;
+  w -= m.start[gi];
+  const PrepArgs& a = m.d[gi];
+  const int tiles = (a.Lp / 64) * (a.Sp / 64);
+  prepare_bf16_body(a, w % tiles, w / tiles);
+}
 
 // bf16 polar, both sides multiples of 8: the result is the high half of the iterate.  One workgroup
 // per 64 x 64 tile of the caller's matrix: a tall or square one is copied with 16-byte vectors, a
 // wide one (the iterate is its transpose) goes through an LDS transpose.
-__global__ __launch_bounds__(NT) void finalize_bf16_kernel(FinalArgs a) {
-  const int b = blockIdx.y;
+__device__ inline void finalize_bf16_body(const FinalArgs& a, int bx, int b) {
   const Ctrl c = a.ctrl[b];
   if (c.status == PRISM_INFO_NONFINITE || c.status == PRISM_INFO_ZERO) return;
   const int par = c.iters & 1;
@@ -252,7 +269,7 @@ __global__ __launch_bounds__(NT) void finalize_bf16_kernel(FinalArgs a) {
   unsigned short* dst = (unsigned short*)a.dst + (long long)b * a.m * a.n;
   if (!a.transpose && a.Xa_hi[par] == (const unsigned short*)a.dst) return;   // the caller's array was that iterate buffer: in place
   const int tiles_c = (a.n + 63) / 64;
-  const int tr = blockIdx.x / tiles_c, tc = blockIdx.x % tiles_c;
+  const int tr = bx / tiles_c, tc = bx % tiles_c;
   if (!a.transpose) {
 #pragma unroll
     for (int it = 0; it < 2; ++it) {
@@ -290,6 +307,15 @@ __global__ __launch_bounds__(NT) void finalize_bf16_kernel(FinalArgs a) {
       *(u32x4*)(dst + (long long)r * a.n + col) = w;
     }
   }
+}
+__global__ __launch_bounds__(NT) void finalize_bf16_kernel(FinalArgs a) { finalize_bf16_body(a, blockIdx.x, blockIdx.y); }
+__global__ __launch_bounds__(NT) void finalize_bf16_multi_kernel(FinalMulti m) {
+  int w = blockIdx.x, gi = 0;
+  while (gi + 1 < m.ngroups && w >= m.start[gi + 1]) ++gi;
+  w -= m.start[gi];
+  const FinalArgs& a = m.d[gi];
+  const int tiles = ((a.m + 63) / 64) * ((a.n + 63) / 64);
+  finalize_bf16_body(a, w % tiles, w / tiles);
 }
 
 // One thread per element of the caller's array.
@@ -434,6 +460,46 @@ void launch_prepare(const PrepArgs& a, hipStream_t s) {
   }
   const int tiles = (a.Lp / 64) * (a.Sp / 64);
   hipLaunchKernelGGL(prepare_kernel, dim3(tiles, a.batch), dim3(NT), 0, s, a);
+}
+
+// The pre-scaling and copy-out steps of several shape groups in one launch each (bf16 polar, every group
+// on the 16-byte vector path); false: the caller launches them group by group.
+bool launch_prep_multi(const PrepArgs* groups, int ngroups, hipStream_t s) {
+  if (ngroups < 2 || ngroups > BF16_MAX_GROUPS) return false;
+  PrepMulti ms = {}, mp = {};
+  ms.ngroups = mp.ngroups = ngroups;
+  long long ts = 0, tp = 0;
+  for (int i = 0; i < ngroups; ++i) {
+    const PrepArgs& a = groups[i];
+    if (!bf16_vector_path(a.fn, a.dt, a.m, a.n, a.src)) return false;
+    ms.d[i] = mp.d[i] = a;
+    ms.start[i] = (int)ts; mp.start[i] = (int)tp;
+    ts += (long long)a.nsum * a.batch;
+    tp += (long long)(a.Lp / 64) * (a.Sp / 64) * a.batch;
+    if (ts > 0x7fffffff || tp > 0x7fffffff) return false;
+  }
+  ms.start[ngroups] = (int)ts; mp.start[ngroups] = (int)tp;
+  hipLaunchKernelGGL(sumsq_multi_kernel, dim3((unsigned)ts), dim3(NT), 0, s, ms);
+  hipLaunchKernelGGL(prepare_bf16_multi_kernel, dim3((unsigned)tp), dim3(NT), 0, s, mp);
+  return true;
+}
+
+bool launch_finalize_multi(const FinalArgs* groups, int ngroups, hipStream_t s) {
+  if (ngroups < 2 || ngroups > BF16_MAX_GROUPS) return false;
+  FinalMulti mf = {};
+  mf.ngroups = ngroups;
+  long long t = 0;
+  for (int i = 0; i < ngroups; ++i) {
+    const FinalArgs& a = groups[i];
+    if (!bf16_vector_path(a.fn, a.dt, a.m, a.n, a.dst)) return false;
+    mf.d[i] = a;
+    mf.start[i] = (int)t;
+    t += (long long)((a.m + 63) / 64) * ((a.n + 63) / 64) * a.batch;
+    if (t > 0x7fffffff) return false;
+  }
+  mf.start[ngroups] = (int)t;
+  hipLaunchKernelGGL(finalize_bf16_multi_kernel, dim3((unsigned)t), dim3(NT), 0, s, mf);
+  return true;
 }
 
 void launch_finalize(const FinalArgs& a, hipStream_t s) {

@@ -1010,7 +1010,11 @@ int run_polar_bf16_shapes(const prism_group* groups, int ngroups, int degree, in
   PrepArgs pa; FinalArgs fa;
   {
     ProfScope ps(PK_PREP, r.s);
-    for (const Run::XGroup& x : r.xg) { group_args(x, pa, fa); launch_sumsq(pa, r.s); launch_prepare(pa, r.s); }
+    PrepArgs pas[BF16_MAX_GROUPS];
+    int np = 0;
+    for (const Run::XGroup& x : r.xg) { group_args(x, pa, fa); pas[np++] = pa; }
+    if (!launch_prep_multi(pas, np, r.s))
+      for (int i = 0; i < np; ++i) { launch_sumsq(pas[i], r.s); launch_prepare(pas[i], r.s); }
   }
   if (P.p_s > 0 && max_iters > r.first_fit) {
     ProfScope ps(PK_SKETCH, r.s);
@@ -1023,7 +1027,11 @@ int run_polar_bf16_shapes(const prism_group* groups, int ngroups, int degree, in
   if (rc != PRISM_OK) return rc;
   {
     ProfScope ps(PK_FINAL, r.s);
-    for (const Run::XGroup& x : r.xg) { group_args(x, pa, fa); launch_finalize(fa, r.s); }
+    FinalArgs fas[BF16_MAX_GROUPS];
+    int nf = 0;
+    for (const Run::XGroup& x : r.xg) { group_args(x, pa, fa); fas[nf++] = fa; }
+    if (!launch_finalize_multi(fas, nf, r.s))
+      for (int i = 0; i < nf; ++i) launch_finalize(fas[i], r.s);
   }
   rc = check_hip();
   if (rc != PRISM_OK) return rc;
